@@ -1,0 +1,334 @@
+"""Pins for the oracle's reduced forward/backward (FFN and attention blocks): torch CPU
+autograd of independently written dense layers, finite differences, and the invariants the
+method fixes (keep-all = dense, compact = masked dense, permutation invariance)."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import ecospa_oracle as O
+from paper_2511_11641_amd import synth
+
+torch.set_default_dtype(torch.float64)
+
+
+def _t(a, grad=False):
+    t = torch.tensor(np.asarray(a, dtype=np.float64))
+    t.requires_grad_(grad)
+    return t
+
+
+# ---------------------------------------------------------------------------------------
+# FFN
+# ---------------------------------------------------------------------------------------
+def _ffn_inputs(seed=0, T=12, d=7, n=10, gated=False):
+    t = synth.ffn_layer(seed, T, d, n, gated=gated, dtype="f32")
+    # blow the weights up so the activations leave GELU's linear regime
+    for k in ("w1", "w1b", "w2"):
+        if k in t:
+            t[k] = t[k] * 30.0
+    return t
+
+
+@pytest.mark.parametrize("act", [O.ACT_GELU_ERF, O.ACT_GELU_TANH, O.ACT_SWIGLU])
+def test_ffn_keep_all_matches_torch_autograd(act):
+    gated = act == O.ACT_SWIGLU
+    t = _ffn_inputs(1, gated=gated)
+    y, sv = O.ffn_fwd(t["x"], t["w1"], t["b1"], t["w2"], t["b2"], act, t.get("w1b"))
+    g = O.ffn_bwd(t["x"], t["dy"], t["w1"], t["w2"], act, sv, t.get("w1b"))
+
+    x, w1, b1, w2, b2 = (_t(t[k], True) for k in ("x", "w1", "b1", "w2", "b2"))
+    if gated:
+        w1b = _t(t["w1b"], True)
+        a = F.silu(F.linear(x, w1, b1)) * F.linear(x, w1b)
+    else:
+        a = F.gelu(F.linear(x, w1, b1), approximate="tanh" if act == O.ACT_GELU_TANH else "none")
+    yt = F.linear(a, w2, b2)
+    (yt * _t(t["dy"])).sum().backward()
+    np.testing.assert_allclose(y, yt.detach().numpy(), rtol=1e-11, atol=1e-12)
+    for name, ten in (("dx", x), ("dw1", w1), ("db1", b1), ("dw2", w2), ("db2", b2)):
+        np.testing.assert_allclose(g[name], ten.grad.numpy(), rtol=1e-9, atol=1e-11, err_msg=name)
+    if gated:
+        np.testing.assert_allclose(g["dw1b"], w1b.grad.numpy(), rtol=1e-9, atol=1e-11)
+
+
+def _fd_check(f, params, grads, eps=1e-6, n_probe=12, seed=0):
+    """Central differences of the scalar f() w.r.t. a few entries of each named parameter."""
+    rs = np.random.Generator(np.random.Philox(key=[seed, 5]))
+    for name, arr in params.items():
+        flat = arr.reshape(-1)
+        for _ in range(min(n_probe, flat.size)):
+            i = int(rs.integers(flat.size))
+            old = flat[i]
+            flat[i] = old + eps
+            fp = f()
+            flat[i] = old - eps
+            fm = f()
+            flat[i] = old
+            num = (fp - fm) / (2 * eps)
+            ana = grads[name].reshape(-1)[i]
+            assert abs(num - ana) <= 1e-6 * max(1.0, abs(ana)), (name, i, num, ana)
+
+
+@pytest.mark.parametrize("act", [O.ACT_GELU_ERF, O.ACT_SWIGLU])
+def test_ffn_bwd_finite_differences(act):
+    gated = act == O.ACT_SWIGLU
+    t = {k: v.astype(np.float64) for k, v in _ffn_inputs(2, gated=gated).items()}
+
+    def loss():
+        y, _ = O.ffn_fwd(t["x"], t["w1"], t["b1"], t["w2"], t["b2"], act, t.get("w1b"))
+        return float((y * t["dy"]).sum())
+
+    _, sv = O.ffn_fwd(t["x"], t["w1"], t["b1"], t["w2"], t["b2"], act, t.get("w1b"))
+    g = O.ffn_bwd(t["x"], t["dy"], t["w1"], t["w2"], act, sv, t.get("w1b"))
+    params = {"dx": t["x"], "dw1": t["w1"], "db1": t["b1"], "dw2": t["w2"], "db2": t["b2"]}
+    if gated:
+        params["dw1b"] = t["w1b"]
+    _fd_check(loss, params, g)
+
+
+@pytest.mark.parametrize("gated", [False, True])
+def test_ffn_compact_equals_masked_dense_and_permutation(gated):
+    act = O.ACT_SWIGLU if gated else O.ACT_GELU_ERF
+    n, k = 10, 6
+    t = _ffn_inputs(3, n=n, gated=gated)
+    kind = O.PAIR_FFN_GATED if gated else O.PAIR_FFN
+    v = O.coupled_score(kind, t["w1"], t["w2"], 1, n, w1b=t.get("w1b"))
+    idx = O.select_topk(v.astype(np.float32), k)
+    c = {"w1": O.compact(t["w1"], idx, 0, n), "b1": O.compact(t["b1"], idx, 0, n),
+         "w2": O.compact(t["w2"], idx, 1, n)}
+    if gated:
+        c["w1b"] = O.compact(t["w1b"], idx, 0, n)
+    yc, svc = O.ffn_fwd(t["x"], c["w1"], c["b1"], c["w2"], t["b2"], act, c.get("w1b"))
+    gc = O.ffn_bwd(t["x"], t["dy"], c["w1"], c["w2"], act, svc, c.get("w1b"))
+
+    mask = np.zeros(n)
+    mask[idx[0]] = 1.0
+    w1m, b1m, w2m = t["w1"] * mask[:, None], t["b1"] * mask, t["w2"] * mask[None, :]
+    w1bm = t["w1b"] * mask[:, None] if gated else None
+    ym, svm = O.ffn_fwd(t["x"], w1m, b1m, w2m, t["b2"], act, w1bm)
+    gm = O.ffn_bwd(t["x"], t["dy"], w1m, w2m, act, svm, w1bm)
+    np.testing.assert_allclose(yc, ym, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(gc["dx"], gm["dx"], rtol=1e-12, atol=1e-13)
+    # scattered compact gradients equal the masked-dense gradients restricted to kept dims;
+    # W_1's pruned rows get exactly 0 because their partner column of W_2 is 0.
+    np.testing.assert_allclose(O.scatter(gc["dw1"], idx, 0, n), gm["dw1"], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(O.scatter(gc["dw2"], idx, 1, n), gm["dw2"] * mask[None, :], rtol=1e-12, atol=1e-13)
+    assert np.all(gm["dw1"][mask == 0] == 0)
+
+    # a consistent permutation of the inner dimension changes nothing
+    perm = np.random.Generator(np.random.Philox(key=[3, 1])).permutation(k)
+    yp, _ = O.ffn_fwd(t["x"], c["w1"][perm], c["b1"][perm], c["w2"][:, perm], t["b2"], act,
+                      c["w1b"][perm] if gated else None)
+    np.testing.assert_allclose(yp, yc, rtol=1e-12, atol=1e-13)
+
+    # keep all = dense
+    all_idx = np.arange(n, dtype=np.int32)[None]
+    ya, _ = O.ffn_fwd(t["x"], O.compact(t["w1"], all_idx, 0, n), t["b1"], O.compact(t["w2"], all_idx, 1, n),
+                      t["b2"], act, t.get("w1b"))
+    yd, _ = O.ffn_fwd(t["x"], t["w1"], t["b1"], t["w2"], t["b2"], act, t.get("w1b"))
+    np.testing.assert_array_equal(ya, yd)
+
+
+def test_gelu_first_order_bound_eq7():
+    """Eq. 7: for small pre-activations, the output change from removing pair j is close to
+    c ||X w_in,j w_out,j^T||_F with c = GELU'(0) = 1/2, and bounded by c ||X||_F ||w_in,j|| ||w_out,j||."""
+    T, d, n = 16, 8, 6
+    t = synth.ffn_layer(5, T, d, n, dtype="f32", bias=False)   # sigma = 0.02 -> |H| << 1
+    x, w1, w2 = (t[k].astype(np.float64) for k in ("x", "w1", "w2"))
+    assert abs(O._gelu_grad(np.zeros(1), O.ACT_GELU_ERF)[0] - 0.5) < 1e-15
+    assert abs(O._gelu_grad(np.zeros(1), O.ACT_GELU_TANH)[0] - 0.5) < 1e-15
+    y, _ = O.ffn_fwd(x, w1, None, w2, None, O.ACT_GELU_ERF)
+    for j in range(n):
+        keep = np.array([[i for i in range(n) if i != j]], dtype=np.int32)
+        yj, _ = O.ffn_fwd(x, O.compact(w1, keep, 0, n), None, O.compact(w2, keep, 1, n), None, O.ACT_GELU_ERF)
+        err = np.linalg.norm(y - yj)
+        first = 0.5 * np.linalg.norm(x @ np.outer(w1[j], w2[:, j]))
+        bound = 0.5 * np.linalg.norm(x) * np.linalg.norm(w1[j]) * np.linalg.norm(w2[:, j])
+        assert abs(err - first) / first < 0.2
+        assert first <= bound * (1 + 1e-12)
+
+
+# ---------------------------------------------------------------------------------------
+# attention
+# ---------------------------------------------------------------------------------------
+def _attn_inputs(seed=0, B=2, L=6, d=10, h=3, dh=4):
+    t = synth.attn_layer(seed, B, L, d, h, dh, dtype="f32")
+    for k in ("wq", "wk", "wv", "wo"):
+        t[k] = t[k] * 25.0
+    return t
+
+
+def _torch_rope(z, L, dh):
+    """Interleaved-pair rotary embedding, written with complex numbers (independent of the oracle)."""
+    p = torch.arange(dh // 2, dtype=torch.float64)
+    theta = 10000.0 ** (-2.0 * p / dh)
+    ang = torch.arange(L, dtype=torch.float64)[:, None] * theta[None, :]
+    zc = torch.view_as_complex(z.reshape(*z.shape[:-1], dh // 2, 2).contiguous())
+    rot = torch.polar(torch.ones_like(ang), ang)
+    return torch.view_as_real(zc * rot).reshape(z.shape)
+
+
+def _torch_mha(t, B, L, h, dh, causal, rope, scale):
+    x, wq, wk, wv, wo, bq, bk, bv, bo = (_t(t[k], True) for k in
+                                         ("x", "wq", "wk", "wv", "wo", "bq", "bk", "bv", "bo"))
+    d = x.shape[1]
+    xb = x.reshape(B, L, d)
+    q = F.linear(xb, wq, bq).reshape(B, L, h, dh).transpose(1, 2)
+    k = F.linear(xb, wk, bk).reshape(B, L, h, dh).transpose(1, 2)
+    v = F.linear(xb, wv, bv).reshape(B, L, h, dh).transpose(1, 2)
+    if rope:
+        q, k = _torch_rope(q, L, dh), _torch_rope(k, L, dh)
+    s = q @ k.transpose(-1, -2) * scale
+    if causal:
+        s = s.masked_fill(torch.ones(L, L, dtype=torch.bool).triu(1), float("-inf"))
+    o = torch.softmax(s, dim=-1) @ v
+    y = F.linear(o.transpose(1, 2).reshape(B * L, h * dh), wo, bo)
+    return y, dict(x=x, wq=wq, wk=wk, wv=wv, wo=wo, bq=bq, bk=bk, bv=bv, bo=bo)
+
+
+def _oracle_mha(t, B, L, h, dh, causal, angles, scale):
+    args = (O.heads_rows(t["wq"], h), O.heads_rows(t["wk"], h), O.heads_rows(t["wv"], h),
+            O.heads_cols(t["wo"], h))
+    kw = dict(bq=t["bq"].reshape(h, -1), bk=t["bk"].reshape(h, -1), bv=t["bv"].reshape(h, -1), bo=t["bo"])
+    y, sv = O.attn_fwd(t["x"], *args, B, L, scale, causal, angles=angles, **kw)
+    g = O.attn_bwd(t["x"], t["dy"], *args, B, L, scale, sv, angles=angles)
+    return y, g
+
+
+@pytest.mark.parametrize("causal,rope", [(False, False), (True, False), (True, True), (False, True)])
+def test_attn_keep_all_matches_torch_autograd(causal, rope):
+    B, L, d, h, dh = 2, 6, 10, 3, 4
+    t = _attn_inputs(7, B, L, d, h, dh)
+    scale = 1.0 / np.sqrt(dh)
+    angles = O.rope_angles(np.tile(np.arange(dh // 2), (h, 1)), L, dh) if rope else None
+    y, g = _oracle_mha(t, B, L, h, dh, causal, angles, scale)
+    yt, p = _torch_mha(t, B, L, h, dh, causal, rope, scale)
+    (yt * _t(t["dy"])).sum().backward()
+    np.testing.assert_allclose(y, yt.detach().numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(g["dx"], p["x"].grad.numpy(), rtol=1e-8, atol=1e-11)
+    np.testing.assert_allclose(g["dwq"].reshape(h * dh, d), p["wq"].grad.numpy(), rtol=1e-8, atol=1e-11)
+    np.testing.assert_allclose(g["dwk"].reshape(h * dh, d), p["wk"].grad.numpy(), rtol=1e-8, atol=1e-11)
+    np.testing.assert_allclose(g["dwv"].reshape(h * dh, d), p["wv"].grad.numpy(), rtol=1e-8, atol=1e-11)
+    np.testing.assert_allclose(g["dwo"].transpose(1, 0, 2).reshape(d, h * dh), p["wo"].grad.numpy(),
+                               rtol=1e-8, atol=1e-11)
+    np.testing.assert_allclose(g["dbq"].reshape(-1), p["bq"].grad.numpy(), rtol=1e-8, atol=1e-11)
+    np.testing.assert_allclose(g["dbk"].reshape(-1), p["bk"].grad.numpy(), rtol=1e-8, atol=1e-10)
+    np.testing.assert_allclose(g["dbv"].reshape(-1), p["bv"].grad.numpy(), rtol=1e-8, atol=1e-11)
+    np.testing.assert_allclose(g["dbo"], p["bo"].grad.numpy(), rtol=1e-8, atol=1e-11)
+
+
+def test_attn_bwd_finite_differences_compacted_rope():
+    """Finite differences on a compacted, rotary, causal block (the case autograd above does
+    not reach: kept blocks carry their original frequencies)."""
+    B, L, d, h, dh = 1, 5, 6, 2, 8
+    t = {k: v.astype(np.float64) for k, v in _attn_inputs(8, B, L, d, h, dh).items()}
+    idx_qk = np.array([[0, 3], [1, 2]], dtype=np.int32)          # kept rotary blocks per head
+    idx_vo = np.array([[0, 2, 5], [1, 6, 7]], dtype=np.int32)
+    angles = O.rope_angles(idx_qk, L, dh)
+    scale = 1.0 / np.sqrt(dh)
+    c = {"wq": O.heads_rows(O.compact(t["wq"], idx_qk, 0, dh, 2), h).copy(),
+         "wk": O.heads_rows(O.compact(t["wk"], idx_qk, 0, dh, 2), h).copy(),
+         "wv": O.heads_rows(O.compact(t["wv"], idx_vo, 0, dh), h).copy(),
+         "wo": O.heads_cols(O.compact(t["wo"], idx_vo, 1, dh), h).copy(),
+         "bq": O.compact(t["bq"], idx_qk, 0, dh, 2).reshape(h, -1).copy(),
+         "bk": O.compact(t["bk"], idx_qk, 0, dh, 2).reshape(h, -1).copy(),
+         "bv": O.compact(t["bv"], idx_vo, 0, dh).reshape(h, -1).copy(),
+         "bo": t["bo"].copy(), "x": t["x"].copy()}
+
+    def run():
+        return O.attn_fwd(c["x"], c["wq"], c["wk"], c["wv"], c["wo"], B, L, scale, True,
+                          bq=c["bq"], bk=c["bk"], bv=c["bv"], bo=c["bo"], angles=angles)
+
+    def loss():
+        return float((run()[0] * t["dy"]).sum())
+
+    _, sv = run()
+    g = O.attn_bwd(c["x"], t["dy"], c["wq"], c["wk"], c["wv"], c["wo"], B, L, scale, sv, angles=angles)
+    _fd_check(loss, {"dx": c["x"], "dwq": c["wq"], "dwk": c["wk"], "dwv": c["wv"], "dwo": c["wo"],
+                     "dbq": c["bq"], "dbk": c["bk"], "dbv": c["bv"], "dbo": c["bo"]}, g, n_probe=10)
+
+
+@pytest.mark.parametrize("rope", [False, True])
+def test_attn_compact_equals_masked_dense(rope):
+    """Zeroing the pruned rows of W_q, W_k, W_v (and biases) and columns of W_o in the dense
+    layer gives the compacted layer's output; with RoPE the dense layer rotates all blocks with
+    their own frequencies and the compacted one only the kept blocks, same frequencies."""
+    B, L, d, h, dh = 2, 7, 9, 2, 8
+    t = _attn_inputs(9, B, L, d, h, dh)
+    unit = 2 if rope else 1
+    vqk = O.coupled_score(O.PAIR_QK, t["wq"], t["wk"], h, dh, unit)
+    vvo = O.coupled_score(O.PAIR_VO, t["wv"], t["wo"], h, dh)
+    idx_qk = O.select_topk(vqk.astype(np.float32), 2 if rope else 5)
+    idx_vo = O.select_topk(vvo.astype(np.float32), 3)
+    scale = 1.0 / np.sqrt(dh)
+    ang_c = O.rope_angles(idx_qk, L, dh) if rope else None
+    ang_d = O.rope_angles(np.tile(np.arange(dh // 2), (h, 1)), L, dh) if rope else None
+
+    yc, svc = O.attn_fwd(
+        t["x"],
+        O.heads_rows(O.compact(t["wq"], idx_qk, 0, dh, unit), h),
+        O.heads_rows(O.compact(t["wk"], idx_qk, 0, dh, unit), h),
+        O.heads_rows(O.compact(t["wv"], idx_vo, 0, dh), h),
+        O.heads_cols(O.compact(t["wo"], idx_vo, 1, dh), h),
+        B, L, scale, True,
+        bq=O.compact(t["bq"], idx_qk, 0, dh, unit).reshape(h, -1),
+        bk=O.compact(t["bk"], idx_qk, 0, dh, unit).reshape(h, -1),
+        bv=O.compact(t["bv"], idx_vo, 0, dh).reshape(h, -1), bo=t["bo"], angles=ang_c)
+
+    mqk = np.zeros(h * dh)
+    mqk[O.kept_positions(idx_qk, dh, unit)] = 1
+    mvo = np.zeros(h * dh)
+    mvo[O.kept_positions(idx_vo, dh)] = 1
+    tm = dict(t)
+    tm["wq"], tm["wk"], tm["wv"] = t["wq"] * mqk[:, None], t["wk"] * mqk[:, None], t["wv"] * mvo[:, None]
+    tm["bq"], tm["bk"], tm["bv"] = t["bq"] * mqk, t["bk"] * mqk, t["bv"] * mvo
+    tm["wo"] = t["wo"] * mvo[None, :]
+    ym, gm = _oracle_mha(tm, B, L, h, dh, True, ang_d, scale)
+    np.testing.assert_allclose(yc, ym, rtol=1e-11, atol=1e-13)
+
+    gc = O.attn_bwd(
+        t["x"], t["dy"],
+        O.heads_rows(O.compact(t["wq"], idx_qk, 0, dh, unit), h),
+        O.heads_rows(O.compact(t["wk"], idx_qk, 0, dh, unit), h),
+        O.heads_rows(O.compact(t["wv"], idx_vo, 0, dh), h),
+        O.heads_cols(O.compact(t["wo"], idx_vo, 1, dh), h), B, L, scale, svc, angles=ang_c)
+    np.testing.assert_allclose(gc["dx"], gm["dx"], rtol=1e-10, atol=1e-13)
+    kq = idx_qk.shape[1] * unit
+    np.testing.assert_allclose(O.scatter(gc["dwq"].reshape(h * kq, d), idx_qk, 0, dh, unit),
+                               gm["dwq"].reshape(h * dh, d), rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(O.scatter(gc["dwv"].reshape(h * 3, d), idx_vo, 0, dh),
+                               gm["dwv"].reshape(h * dh, d), rtol=1e-10, atol=1e-13)
+
+
+def test_attn_permutation_invariance_without_rope():
+    B, L, d, h, dh = 1, 5, 6, 2, 4
+    t = _attn_inputs(10, B, L, d, h, dh)
+    scale = 0.5
+    y0, _ = _oracle_mha(t, B, L, h, dh, True, None, scale)
+    perm = np.array([2, 0, 3, 1])
+    full = np.concatenate([g * dh + perm for g in range(h)])
+    tp = dict(t)
+    for k in ("wq", "wk", "wv"):
+        tp[k] = t[k][full]
+    for k in ("bq", "bk", "bv"):
+        tp[k] = t[k][full]
+    tp["wo"] = t["wo"][:, full]
+    y1, _ = _oracle_mha(tp, B, L, h, dh, True, None, scale)
+    np.testing.assert_allclose(y1, y0, rtol=1e-12, atol=1e-14)
+
+
+def test_rope_scores_depend_on_relative_position_only():
+    """Eq. 6: P_t P_s^T is a rotation by (t - s) theta, so with identical input rows the
+    pre-softmax score S[t, s] is a function of t - s."""
+    L, d, h, dh = 6, 5, 1, 4
+    t = _attn_inputs(11, 1, L, d, h, dh)
+    x = np.tile(t["x"][:1], (L, 1))
+    ang = O.rope_angles(np.array([[0, 1]]), L, dh)
+    _, sv = O.attn_fwd(x, O.heads_rows(t["wq"], h), O.heads_rows(t["wk"], h), O.heads_rows(t["wv"], h),
+                       O.heads_cols(t["wo"], h), 1, L, 1.0, False, angles=ang)
+    s = sv["q"][(0, 0)] @ sv["k"][(0, 0)].T
+    for off in range(-L + 1, L):
+        diag = np.diagonal(s, offset=off)
+        assert np.ptp(diag) < 1e-10 * max(1.0, np.abs(diag).max())
+    assert np.ptp(s) > 1e-6     # and it does depend on the offset
