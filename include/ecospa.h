@@ -1,0 +1,193 @@
+/*
+ * ecospa.h - C ABI of the MI355X (gfx950) library for EcoSpa's coupled structured
+ * sparsification hot path: score -> select top-k -> compact -> reduced forward/backward.
+ *
+ * Notation follows the paper's Appendix A.1: a coupled pair is A in R^{m x n} with columns
+ * a_j and B in R^{n x p} with rows b_j^T, sharing the inner dimension n; A B = sum_j a_j b_j^T.
+ * Matrices are STORED in the Linear-layer layout W[out_features, in_features], row-major,
+ * y = x W^T.  Hence a_j is stored ROW j of the first member (W_q, W_v, W_in, W_gate (.) W_up)
+ * and b_j is stored COLUMN j of the second member (W_o, W_out, W_down); for the QK pair
+ * (Eq. 4: W_i^Q W_i^K^T) b_j is stored ROW j of W_k.
+ *
+ * General rules for every entry point
+ *   - Pointers are DEVICE pointers unless the comment says "host".  The caller owns every
+ *     buffer; the library never allocates or frees device memory.  Scratch memory comes from
+ *     the workspace the caller attaches with ecospa_set_workspace().
+ *   - Calls are asynchronous on the context's HIP stream and never synchronise with the host.
+ *   - Return value: ECOSPA_OK (0) or an error code > 0.  Arguments are validated on the host
+ *     before any launch; on a validation error nothing is launched and no output is written.
+ *   - Results are deterministic: no floating-point atomics, fixed reduction orders.
+ *   - dtype is the storage type of weights/activations (ECOSPA_F32 or ECOSPA_BF16); all
+ *     accumulation is fp32; scores are always fp32; indices are int32.
+ *   - Leading dimensions (ld*) are in elements.  Buffers used by the reduced forward/backward
+ *     must be 16-byte aligned with leading dimensions that are multiples of 8 elements.
+ */
+#ifndef ECOSPA_H
+#define ECOSPA_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { ECOSPA_OK = 0, ECOSPA_ERR_NULL = 1, ECOSPA_ERR_SHAPE = 2, ECOSPA_ERR_DTYPE = 3, ECOSPA_ERR_K = 4,
+       ECOSPA_ERR_INDEX = 5, ECOSPA_ERR_WORKSPACE = 6, ECOSPA_ERR_ALIGN = 7, ECOSPA_ERR_HIP = 8 };
+enum { ECOSPA_F32 = 0, ECOSPA_BF16 = 1 };
+enum { ECOSPA_PAIR_QK = 0, ECOSPA_PAIR_VO = 1, ECOSPA_PAIR_FFN = 2, ECOSPA_PAIR_FFN_GATED = 3 };
+enum { ECOSPA_BLOCK_ATTN = 0, ECOSPA_BLOCK_FFN = 1 };
+enum { ECOSPA_ACT_GELU_ERF = 0, ECOSPA_ACT_GELU_TANH = 1, ECOSPA_ACT_SWIGLU = 2 };
+
+typedef struct ecospa_ctx ecospa_ctx; /* host object */
+
+/* Create a context bound to a HIP stream (hipStream_t passed as void*; NULL = default stream)
+ * on the current device.  *out is a host object released by ecospa_destroy(). */
+int ecospa_create(ecospa_ctx** out, void* hip_stream);
+void ecospa_destroy(ecospa_ctx* ctx);
+/* Attach caller-owned device scratch memory (256-byte aligned).  Entry points that need more
+ * than `bytes` return ECOSPA_ERR_WORKSPACE.  The contents are clobbered by every call. */
+int ecospa_set_workspace(ecospa_ctx* ctx, void* dev, size_t bytes);
+/* Static, human-readable name of a status code. */
+const char* ecospa_status_string(int code);
+/* Text of the last HIP error seen by this context ("" if none); host string owned by ctx. */
+const char* ecospa_last_error(const ecospa_ctx* ctx);
+
+/* ------------------------------------------------------------------------------------------
+ * Step 1 - per-dimension coupled importance score (paper Eq. 10; selection criterion Eq. 12).
+ *
+ * One ecospa_pair describes `groups` independent coupled pairs of one layer (the h heads of
+ * Eq. 4, or 1 for the FFN pair of Eq. 7).  For unit u (= `unit` consecutive inner dimensions;
+ * unit = 2 is the rotary 2x2 block of Eq. 6, whose Frobenius norm is position independent):
+ *     r_u = sqrt(sum_{j in u} ||a_j||^2) * sqrt(sum_{j in u} ||b_j||^2),
+ *     score[g][u] = r_u / sqrt(sum_{u' in group g} r_{u'}^2)       (0 if the group is all zero).
+ * ECOSPA_PAIR_FFN_GATED scores a_j = row j of (w1 (.) w1b), the elementwise product of the
+ * gate and up matrices (footnote to Eq. 8).
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int kind;            /* ECOSPA_PAIR_*                                                      */
+  int dtype;           /* ECOSPA_F32 | ECOSPA_BF16                                           */
+  int groups;          /* independent pairs (heads); 1 for FFN                               */
+  int n;               /* inner dimensions per group before pruning (d_h or d_ff)            */
+  int unit;            /* 1, or 2 for rotary blocks; n % unit == 0                           */
+  int d1, d2;          /* length of a_j and of b_j                                           */
+  const void* w1;      /* [groups*n, d1], ld1: W_q | W_v | W_in | W_gate                     */
+  const void* w1b;     /* FFN_GATED: W_up [groups*n, d1], ld1b; otherwise NULL               */
+  const void* w2;      /* QK: W_k [groups*n, d2]; VO/FFN*: W_o | W_out | W_down [d2, groups*n] */
+  long long ld1, ld1b, ld2;
+} ecospa_pair;
+
+/* Workspace bytes ecospa_coupled_score needs for this batch (host-only query; 0 on bad input). */
+size_t ecospa_score_workspace_bytes(const ecospa_pair* pairs /*host*/, int n_pairs);
+/* scores[p] (host array of device pointers) receives float[groups_p * n_p / unit_p].
+ * All pairs of the batch are processed by shared launches (every weight is read once).
+ * Errors: NULL pointers -> ERR_NULL; groups/n/d < 1, n % unit, ld < extent -> ERR_SHAPE;
+ * unknown kind/dtype -> ERR_DTYPE; workspace too small -> ERR_WORKSPACE. */
+int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs /*host*/, int n_pairs,
+                         float* const* scores /*host*/);
+
+/* ------------------------------------------------------------------------------------------
+ * Step 2 - keep the k most important units of every group (Sec. 3.2: "rank upsilon_i ... remove
+ * those insignificant pairs"; Alg. 1's removal loop with the count fixed by the caller).
+ * scores: float[groups * n_units]; idx: int32[groups * k], ascending within a group, values in
+ * [0, n_units).  Order: larger score first, equal scores (-0 == +0) keep the lower index, NaN
+ * ranks below every number - so exactly one result is correct.  Needs no workspace.
+ * Errors: k < 1 or k > n_units -> ERR_K; groups/n_units < 1 -> ERR_SHAPE.
+ * ------------------------------------------------------------------------------------------ */
+int ecospa_select_topk(ecospa_ctx* ctx, const float* scores, int groups, int n_units, int k, int* idx);
+
+/* ------------------------------------------------------------------------------------------
+ * Step 3 - aligned gather of the kept inner dimensions into a smaller dense matrix (Def. 1:
+ * the remaining terms keep their original pairing), and its inverse.
+ *
+ * The source axis holds groups*n inner dimensions; the destination axis holds, per group,
+ * kp*unit slots of which the first k*unit receive the kept dimensions in ascending order and
+ * the rest (padding for aligned tiles, kp >= k) are written as zeros:
+ *   axis 0:  dst[g*kp*unit + i*unit + u, c] = src[g*n + idx[g*k+i]*unit + u, c],  c < other_extent
+ *   axis 1:  dst[r, g*kp*unit + i*unit + u] = src[r, g*n + idx[g*k+i]*unit + u],  r < other_extent
+ * Vectors (biases) are matrices with other_extent = 1 on axis 1.  Works for any dtype of 2 or 4
+ * bytes (weights, moments, master copies).  idx must be ascending and in range (as written by
+ * ecospa_select_topk); this is the caller's contract.
+ * ecospa_scatter is the inverse: kept slots of src (compact layout) go back to their place in
+ * dst (full layout) and every pruned row/column of dst is written as zero.
+ * Errors: ERR_NULL, ERR_SHAPE (extents < 1, n % unit, ld too small), ERR_K (k < 1, k > n/unit,
+ * kp < k), ERR_DTYPE.
+ * ------------------------------------------------------------------------------------------ */
+int ecospa_compact(ecospa_ctx* ctx, const void* src, void* dst, int dtype, int axis, int groups, int n,
+                   int unit, int k, int kp, long long other_extent, long long ld_src, long long ld_dst,
+                   const int* idx);
+int ecospa_scatter(ecospa_ctx* ctx, const void* src, void* dst, int dtype, int axis, int groups, int n,
+                   int unit, int k, int kp, long long other_extent, long long ld_src, long long ld_dst,
+                   const int* idx);
+
+/* cos/sin tables of the KEPT rotary blocks (Eq. 6; "position matrices are then adjusted to match
+ * new dimensions", footnote to Eq. 10): for head g, position t < L, kept block i < k,
+ *   angle = t * base^(-2 * idx[g*k+i] / d_h)   with d_h the ORIGINAL head width,
+ * cos_out/sin_out: float[h, L, kp] (slots i >= k get cos = 1, sin = 0).  idx == NULL keeps
+ * block i at slot i (dense layer).  Angles are evaluated in fp64. */
+int ecospa_rope_table(ecospa_ctx* ctx, const int* idx, int h, int L, int k, int kp, int d_h, double base,
+                      float* cos_out, float* sin_out);
+
+/* ------------------------------------------------------------------------------------------
+ * Steps 4-5 - reduced forward and backward contractions on the compacted matrices (Eq. 1-3,
+ * rewritten per head as Eq. 4; rotary form Eq. 6; gated FFN of the footnote to Eq. 8).
+ *
+ * Compact layouts (padding slots hold zeros, so results are exact):
+ *   ATTN: w_qkv [(2*h*kp_qk + h*kp_vo), d_model]: rows of W_q (head-major, kp_qk per head), then
+ *         W_k, then W_v (kp_vo per head); b_qkv same length or NULL; w_o [d_model, h*kp_vo]; b_o.
+ *         kp_qk, kp_vo are multiples of 16 and at most 128.
+ *   FFN:  w_1 [kp_ff, d_model] (SWIGLU: [2*kp_ff, d_model], gate rows then up rows); b_1 same
+ *         length or NULL; w_2 [d_model, kp_ff]; b_2.  kp_ff is a multiple of 16.
+ * scale is the softmax scale (1/sqrt(original d_h) keeps "compact = masked dense").
+ * rope_cos/rope_sin: float[h, L, kp_qk/2] from ecospa_rope_table, or NULL for no rotation;
+ * pairs are adjacent dimensions (2i, 2i+1).
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int block;                 /* ECOSPA_BLOCK_ATTN | ECOSPA_BLOCK_FFN */
+  int dtype;
+  int B, L, d_model;         /* tokens T = B*L, row-major [T, d_model] activations            */
+  /* ATTN */
+  int h, kp_qk, kp_vo;
+  int causal;
+  float scale;
+  const float *rope_cos, *rope_sin;
+  const void *w_qkv, *b_qkv, *w_o, *b_o;
+  long long ld_wqkv, ld_wo;
+  /* FFN */
+  int kp_ff, act;
+  const void *w_1, *b_1, *w_2, *b_2;
+  long long ld_w1, ld_w2;
+} ecospa_block_desc;
+
+/* Activations the forward pass keeps for the backward pass; caller-allocated, dense row-major.
+ *   ATTN: qkv [T, 2*h*kp_qk + h*kp_vo] (Q and K after bias and rotation, V after bias),
+ *         o [T, h*kp_vo] (per-head attention output), lse float[B*h*L] (log-sum-exp of the
+ *         scaled, masked scores per query).
+ *   FFN:  hpre [T, kp_ff] (SWIGLU: [T, 2*kp_ff], gate then up pre-activations), act [T, kp_ff]. */
+typedef struct {
+  void *qkv, *o;
+  float* lse;
+  void *hpre, *act;
+} ecospa_saved;
+
+/* Gradients in the compact layouts of the weights they belong to (same dtype); any pointer may
+ * be NULL to skip that gradient (bias gradients are skipped when NULL). */
+typedef struct {
+  void *dw_qkv, *db_qkv, *dw_o, *db_o;
+  void *dw_1, *db_1, *dw_2, *db_2;
+  long long ld_dwqkv, ld_dwo, ld_dw1, ld_dw2;
+} ecospa_grads;
+
+/* Workspace bytes forward+backward of this block need (host-only query; 0 on bad input). */
+size_t ecospa_block_workspace_bytes(const ecospa_block_desc* desc /*host*/);
+/* y[T, d_model] = block(x[T, d_model]); saved may be NULL for inference (ATTN still needs
+ * workspace for q, k, v then).  Errors: ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_ALIGN, ERR_WORKSPACE. */
+int ecospa_coupled_fwd(ecospa_ctx* ctx, const ecospa_block_desc* desc /*host*/, const void* x, void* y,
+                       const ecospa_saved* saved /*host*/);
+/* From dy[T, d_model]: dx[T, d_model] and the compact weight gradients.  x, saved as in forward. */
+int ecospa_coupled_bwd(ecospa_ctx* ctx, const ecospa_block_desc* desc /*host*/, const void* x, const void* dy,
+                       const ecospa_saved* saved /*host*/, void* dx, const ecospa_grads* grads /*host*/);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECOSPA_H */

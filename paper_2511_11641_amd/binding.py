@@ -1,0 +1,243 @@
+"""ctypes binding of ``libecospa.so`` (see ``include/ecospa.h``).
+
+Argument marshalling only: every step runs in the library's HIP kernels.  PyTorch supplies
+device memory (tensors) and the HIP stream.  There is no fallback: if the built library is
+missing, :func:`load` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libecospa.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_K, ERR_INDEX, ERR_WORKSPACE, ERR_ALIGN, ERR_HIP = range(9)
+F32, BF16 = 0, 1
+PAIR_QK, PAIR_VO, PAIR_FFN, PAIR_FFN_GATED = range(4)
+BLOCK_ATTN, BLOCK_FFN = 0, 1
+ACT_GELU_ERF, ACT_GELU_TANH, ACT_SWIGLU = range(3)
+
+EXPORTS = (
+    "ecospa_create", "ecospa_destroy", "ecospa_set_workspace", "ecospa_status_string", "ecospa_last_error",
+    "ecospa_score_workspace_bytes", "ecospa_coupled_score", "ecospa_select_topk", "ecospa_compact",
+    "ecospa_scatter", "ecospa_rope_table", "ecospa_block_workspace_bytes", "ecospa_coupled_fwd",
+    "ecospa_coupled_bwd",
+)
+
+
+class EcospaError(RuntimeError):
+    def __init__(self, code: int, where: str, detail: str = ""):
+        self.code = code
+        super().__init__(f"{where}: error {code} ({status_string(code)}) {detail}".strip())
+
+
+class Pair(C.Structure):
+    _fields_ = [("kind", C.c_int), ("dtype", C.c_int), ("groups", C.c_int), ("n", C.c_int), ("unit", C.c_int),
+                ("d1", C.c_int), ("d2", C.c_int), ("w1", C.c_void_p), ("w1b", C.c_void_p), ("w2", C.c_void_p),
+                ("ld1", C.c_longlong), ("ld1b", C.c_longlong), ("ld2", C.c_longlong)]
+
+
+class BlockDesc(C.Structure):
+    _fields_ = [("block", C.c_int), ("dtype", C.c_int), ("B", C.c_int), ("L", C.c_int), ("d_model", C.c_int),
+                ("h", C.c_int), ("kp_qk", C.c_int), ("kp_vo", C.c_int), ("causal", C.c_int), ("scale", C.c_float),
+                ("rope_cos", C.c_void_p), ("rope_sin", C.c_void_p),
+                ("w_qkv", C.c_void_p), ("b_qkv", C.c_void_p), ("w_o", C.c_void_p), ("b_o", C.c_void_p),
+                ("ld_wqkv", C.c_longlong), ("ld_wo", C.c_longlong),
+                ("kp_ff", C.c_int), ("act", C.c_int),
+                ("w_1", C.c_void_p), ("b_1", C.c_void_p), ("w_2", C.c_void_p), ("b_2", C.c_void_p),
+                ("ld_w1", C.c_longlong), ("ld_w2", C.c_longlong)]
+
+
+class Saved(C.Structure):
+    _fields_ = [("qkv", C.c_void_p), ("o", C.c_void_p), ("lse", C.c_void_p), ("hpre", C.c_void_p),
+                ("act", C.c_void_p)]
+
+
+class Grads(C.Structure):
+    _fields_ = [("dw_qkv", C.c_void_p), ("db_qkv", C.c_void_p), ("dw_o", C.c_void_p), ("db_o", C.c_void_p),
+                ("dw_1", C.c_void_p), ("db_1", C.c_void_p), ("dw_2", C.c_void_p), ("db_2", C.c_void_p),
+                ("ld_dwqkv", C.c_longlong), ("ld_dwo", C.c_longlong), ("ld_dw1", C.c_longlong),
+                ("ld_dw2", C.c_longlong)]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load the built library; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_11641_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    vp, ci, ll, sz = C.c_void_p, C.c_int, C.c_longlong, C.c_size_t
+    lib.ecospa_create.argtypes = [C.POINTER(vp), vp]
+    lib.ecospa_create.restype = ci
+    lib.ecospa_destroy.argtypes = [vp]
+    lib.ecospa_destroy.restype = None
+    lib.ecospa_set_workspace.argtypes = [vp, vp, sz]
+    lib.ecospa_set_workspace.restype = ci
+    lib.ecospa_status_string.argtypes = [ci]
+    lib.ecospa_status_string.restype = C.c_char_p
+    lib.ecospa_last_error.argtypes = [vp]
+    lib.ecospa_last_error.restype = C.c_char_p
+    lib.ecospa_score_workspace_bytes.argtypes = [C.POINTER(Pair), ci]
+    lib.ecospa_score_workspace_bytes.restype = sz
+    lib.ecospa_coupled_score.argtypes = [vp, C.POINTER(Pair), ci, C.POINTER(vp)]
+    lib.ecospa_coupled_score.restype = ci
+    lib.ecospa_select_topk.argtypes = [vp, vp, ci, ci, ci, vp]
+    lib.ecospa_select_topk.restype = ci
+    for f in (lib.ecospa_compact, lib.ecospa_scatter):
+        f.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ll, ll, ll, vp]
+        f.restype = ci
+    lib.ecospa_rope_table.argtypes = [vp, vp, ci, ci, ci, ci, ci, C.c_double, vp, vp]
+    lib.ecospa_rope_table.restype = ci
+    lib.ecospa_block_workspace_bytes.argtypes = [C.POINTER(BlockDesc)]
+    lib.ecospa_block_workspace_bytes.restype = sz
+    lib.ecospa_coupled_fwd.argtypes = [vp, C.POINTER(BlockDesc), vp, vp, C.POINTER(Saved)]
+    lib.ecospa_coupled_fwd.restype = ci
+    lib.ecospa_coupled_bwd.argtypes = [vp, C.POINTER(BlockDesc), vp, vp, C.POINTER(Saved), vp, C.POINTER(Grads)]
+    lib.ecospa_coupled_bwd.restype = ci
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load().ecospa_status_string(int(code)).decode()
+
+
+def dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return F32
+    if t == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def round_up(x: int, m: int) -> int:
+    return (x + m - 1) // m * m
+
+
+class Context:
+    """One ecospa_ctx on the current torch stream, with a torch-owned workspace that grows on demand."""
+
+    def __init__(self, device: str = "cuda:0", stream: Optional[torch.cuda.Stream] = None):
+        self.lib = load()
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        h = C.c_void_p()
+        rc = self.lib.ecospa_create(C.byref(h), C.c_void_p(self.stream.cuda_stream))
+        if rc:
+            raise EcospaError(rc, "ecospa_create")
+        self.h = h
+        self._ws: Optional[torch.Tensor] = None
+
+    def __del__(self):
+        try:
+            if getattr(self, "h", None):
+                self.lib.ecospa_destroy(self.h)
+                self.h = None
+        except Exception:
+            pass
+
+    def _check(self, rc: int, where: str):
+        if rc:
+            raise EcospaError(rc, where, self.lib.ecospa_last_error(self.h).decode())
+
+    def reserve(self, nbytes: int):
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=self.device)
+            self._check(self.lib.ecospa_set_workspace(self.h, self._ws.data_ptr(), self._ws.numel()),
+                        "ecospa_set_workspace")
+
+    # ---- step 1 ------------------------------------------------------------------------------
+    @staticmethod
+    def make_pair(kind: int, w1: torch.Tensor, w2: torch.Tensor, groups: int, n: int, unit: int = 1,
+                  w1b: Optional[torch.Tensor] = None) -> Pair:
+        d1 = w1.shape[1]
+        d2 = w2.shape[1] if kind == PAIR_QK else w2.shape[0]
+        return Pair(kind, dtype_code(w1.dtype), groups, n, unit, d1, d2, _ptr(w1), _ptr(w1b), _ptr(w2),
+                    w1.stride(0), 0 if w1b is None else w1b.stride(0), w2.stride(0))
+
+    def ecospa_coupled_score(self, pairs: Sequence[Pair]) -> list[torch.Tensor]:
+        arr = (Pair * len(pairs))(*pairs)
+        need = self.lib.ecospa_score_workspace_bytes(arr, len(pairs))
+        self.reserve(need)
+        outs = [torch.empty(p.groups * (p.n // max(p.unit, 1)), dtype=torch.float32, device=self.device)
+                for p in pairs]
+        ptrs = (C.c_void_p * len(pairs))(*[o.data_ptr() for o in outs])
+        self._check(self.lib.ecospa_coupled_score(self.h, arr, len(pairs), ptrs), "ecospa_coupled_score")
+        return [o.view(p.groups, -1) for o, p in zip(outs, pairs)]
+
+    # ---- step 2 ------------------------------------------------------------------------------
+    def ecospa_select_topk(self, scores: torch.Tensor, k: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        groups, n_units = scores.shape
+        assert scores.dtype == torch.float32 and scores.is_contiguous()
+        idx = out if out is not None else torch.empty((groups, max(k, 0)), dtype=torch.int32, device=self.device)
+        self._check(self.lib.ecospa_select_topk(self.h, scores.data_ptr(), groups, n_units, k, idx.data_ptr()),
+                    "ecospa_select_topk")
+        return idx
+
+    # ---- step 3 ------------------------------------------------------------------------------
+    def _mapped(self, fn, name, src, dst, axis, groups, n, unit, k, kp, idx):
+        if src.dim() == 1:
+            other, ld_s, ld_d = 1, src.numel(), dst.numel()
+            axis = 1
+        else:
+            other = src.shape[1] if axis == 0 else src.shape[0]
+            ld_s, ld_d = src.stride(0), dst.stride(0)
+        self._check(fn(self.h, src.data_ptr(), dst.data_ptr(), dtype_code(src.dtype), axis, groups, n, unit, k, kp,
+                       other, ld_s, ld_d, idx.data_ptr()), name)
+        return dst
+
+    def ecospa_compact(self, src: torch.Tensor, idx: torch.Tensor, axis: int, groups: int, n: int, unit: int = 1,
+                       kp: Optional[int] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        k = idx.shape[1]
+        kp = k if kp is None else kp
+        slots = groups * kp * unit
+        if out is None:
+            shape = (slots,) if src.dim() == 1 else ((slots, src.shape[1]) if axis == 0 else (src.shape[0], slots))
+            out = torch.empty(shape, dtype=src.dtype, device=src.device)
+        return self._mapped(self.lib.ecospa_compact, "ecospa_compact", src, out, axis, groups, n, unit, k, kp, idx)
+
+    def ecospa_scatter(self, src: torch.Tensor, idx: torch.Tensor, axis: int, groups: int, n: int, unit: int = 1,
+                       kp: Optional[int] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        k = idx.shape[1]
+        kp = k if kp is None else kp
+        slots = groups * n
+        if out is None:
+            shape = (slots,) if src.dim() == 1 else ((slots, src.shape[1]) if axis == 0 else (src.shape[0], slots))
+            out = torch.empty(shape, dtype=src.dtype, device=src.device)
+        return self._mapped(self.lib.ecospa_scatter, "ecospa_scatter", src, out, axis, groups, n, unit, k, kp, idx)
+
+    def ecospa_rope_table(self, idx: Optional[torch.Tensor], h: int, L: int, k: int, kp: int, d_h: int,
+                          base: float = 10000.0):
+        cos = torch.empty((h, L, kp), dtype=torch.float32, device=self.device)
+        sin = torch.empty_like(cos)
+        self._check(self.lib.ecospa_rope_table(self.h, _ptr(idx), h, L, k, kp, d_h, float(base), cos.data_ptr(),
+                                               sin.data_ptr()), "ecospa_rope_table")
+        return cos, sin
+
+    # ---- steps 4-5 ---------------------------------------------------------------------------
+    def ecospa_coupled_fwd(self, desc: BlockDesc, x: torch.Tensor, y: torch.Tensor, saved: Optional[Saved]):
+        self.reserve(self.lib.ecospa_block_workspace_bytes(C.byref(desc)))
+        self._check(self.lib.ecospa_coupled_fwd(self.h, C.byref(desc), x.data_ptr(), y.data_ptr(),
+                                                None if saved is None else C.byref(saved)), "ecospa_coupled_fwd")
+        return y
+
+    def ecospa_coupled_bwd(self, desc: BlockDesc, x: torch.Tensor, dy: torch.Tensor, saved: Saved,
+                           dx: Optional[torch.Tensor], grads: Grads):
+        self.reserve(self.lib.ecospa_block_workspace_bytes(C.byref(desc)))
+        self._check(self.lib.ecospa_coupled_bwd(self.h, C.byref(desc), x.data_ptr(), dy.data_ptr(), C.byref(saved),
+                                                _ptr(dx), C.byref(grads)), "ecospa_coupled_bwd")
+        return dx

@@ -1,0 +1,32 @@
+// Internal: per-block orchestration shared by block.hip (FFN, dispatch) and attn.hip.
+#pragma once
+#include "common.h"
+#include "gemm.h"
+
+struct BlockWs {           // pieces carved from the caller's workspace
+  // FFN
+  void* dh;                // [T, (1|2)*kp_ff]
+  void* hpre_tmp;          // inference only
+  void* act_tmp;
+  // ATTN
+  void* qkv_tmp;           // inference only
+  void* o_tmp;
+  float* lse_tmp;
+  void* dqkv;              // [T, nqkv]
+  void* d_o;               // [T, h*kp_vo]
+  float* delta;            // [B*h*L]
+  // shared
+  float* partial;          // split-K partials
+  float* colsum_partial;
+  size_t total;
+};
+
+// Lay out the workspace for a validated descriptor; base may be NULL to only measure.
+void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w);
+
+int attn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, void* y,
+                 const ecospa_saved* saved);
+int attn_backward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, const void* dy,
+                  const ecospa_saved& saved, void* dx, const ecospa_grads& g);
+
+static inline int attn_nqkv(const ecospa_block_desc& d) { return 2 * d.h * d.kp_qk + d.h * d.kp_vo; }

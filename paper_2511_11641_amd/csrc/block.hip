@@ -1,0 +1,200 @@
+// Steps 4-5: reduced forward/backward of one block on the compacted matrices.  This file holds
+// the argument validation, the workspace layout, the FFN block (Eq. 3; gated form of the footnote
+// to Eq. 8) and the dispatch of the C-ABI entry points; the attention block lives in attn.hip.
+#include "block.h"
+
+static bool is_gated(const ecospa_block_desc& d) { return d.act == ECOSPA_ACT_SWIGLU; }
+
+static int validate_block(const ecospa_block_desc* dp) {
+  if (!dp) return ECOSPA_ERR_NULL;
+  const ecospa_block_desc& d = *dp;
+  if (!dtype_ok(d.dtype)) return ECOSPA_ERR_DTYPE;
+  if (d.block != ECOSPA_BLOCK_ATTN && d.block != ECOSPA_BLOCK_FFN) return ECOSPA_ERR_DTYPE;
+  if (d.B < 1 || d.L < 1 || d.d_model < 1) return ECOSPA_ERR_SHAPE;
+  if (static_cast<long long>(d.B) * d.L > (1ll << 30)) return ECOSPA_ERR_SHAPE;
+  if (d.d_model % 8) return ECOSPA_ERR_ALIGN;
+  if (d.block == ECOSPA_BLOCK_FFN) {
+    if (d.act < ECOSPA_ACT_GELU_ERF || d.act > ECOSPA_ACT_SWIGLU) return ECOSPA_ERR_DTYPE;
+    if (d.kp_ff < 16 || d.kp_ff % 16) return ECOSPA_ERR_SHAPE;
+    if (!d.w_1 || !d.w_2) return ECOSPA_ERR_NULL;
+    if (d.ld_w1 < d.d_model || d.ld_w2 < d.kp_ff) return ECOSPA_ERR_SHAPE;
+    if (d.ld_w1 % 8 || d.ld_w2 % 8 || !aligned16(d.w_1) || !aligned16(d.w_2)) return ECOSPA_ERR_ALIGN;
+  } else {
+    if (d.h < 1 || d.kp_qk < 16 || d.kp_vo < 16 || d.kp_qk % 16 || d.kp_vo % 16 || d.kp_qk > 128 || d.kp_vo > 128)
+      return ECOSPA_ERR_SHAPE;
+    if (!d.w_qkv || !d.w_o) return ECOSPA_ERR_NULL;
+    if ((d.rope_cos == nullptr) != (d.rope_sin == nullptr)) return ECOSPA_ERR_NULL;
+    if (d.ld_wqkv < d.d_model || d.ld_wo < static_cast<long long>(d.h) * d.kp_vo) return ECOSPA_ERR_SHAPE;
+    if (d.ld_wqkv % 8 || d.ld_wo % 8 || !aligned16(d.w_qkv) || !aligned16(d.w_o)) return ECOSPA_ERR_ALIGN;
+    if (!(d.scale > 0.f)) return ECOSPA_ERR_SHAPE;
+  }
+  return ECOSPA_OK;
+}
+
+static size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
+
+void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
+  memset(&w, 0, sizeof(w));
+  WsCarver c(base ? base : reinterpret_cast<void*>(256), ~static_cast<size_t>(0) >> 1);
+  const size_t T = static_cast<size_t>(d.B) * d.L, es = dtype_size(d.dtype), dm = d.d_model;
+  size_t part = 0, csn = 0;
+  auto splitk_bytes = [&](int M, int N, int K) {
+    const int s = ecospa_gemm_splits(M, N, K);
+    return s > 1 ? static_cast<size_t>(s) * M * N * 4 : static_cast<size_t>(0);
+  };
+  if (d.block == ECOSPA_BLOCK_FFN) {
+    const size_t nh = static_cast<size_t>(is_gated(d) ? 2 : 1) * d.kp_ff;
+    w.dh = c.take(T * nh * es);
+    w.hpre_tmp = w.dh;                       // inference scratch aliases the backward scratch
+    w.act_tmp = c.take(T * d.kp_ff * es);
+    part = max_sz(splitk_bytes(d.d_model, d.kp_ff, static_cast<int>(T)), splitk_bytes(static_cast<int>(nh), d.d_model, static_cast<int>(T)));
+    csn = max_sz(nh, dm);
+  } else {
+    const size_t nqkv = attn_nqkv(d), nvo = static_cast<size_t>(d.h) * d.kp_vo;
+    w.dqkv = c.take(T * nqkv * es);
+    w.qkv_tmp = w.dqkv;
+    w.d_o = c.take(T * nvo * es);
+    w.o_tmp = w.d_o;
+    w.delta = static_cast<float*>(c.take(static_cast<size_t>(d.B) * d.h * d.L * 4));
+    w.lse_tmp = static_cast<float*>(c.take(static_cast<size_t>(d.B) * d.h * d.L * 4));
+    part = max_sz(splitk_bytes(d.d_model, static_cast<int>(nvo), static_cast<int>(T)), splitk_bytes(static_cast<int>(nqkv), d.d_model, static_cast<int>(T)));
+    csn = max_sz(nqkv, dm);
+  }
+  w.partial = static_cast<float*>(c.take(part));
+  w.colsum_partial = static_cast<float*>(c.take(static_cast<size_t>(ecospa_colsum_chunks(static_cast<int>(T))) * csn * 4));
+  w.total = c.off + 256;
+  if (!base) memset(&w, 0, offsetof(BlockWs, total));
+}
+
+extern "C" size_t ecospa_block_workspace_bytes(const ecospa_block_desc* desc) {
+  if (validate_block(desc) != ECOSPA_OK) return 0;
+  BlockWs w;
+  block_ws_layout(*desc, nullptr, w);
+  return w.total;
+}
+
+// ---------------------------------------------------------------------------------------------
+// FFN
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_kernel(const T* __restrict__ hpre, long long ldh, T* __restrict__ act,
+                                                     long long lda, long long rows, int kp) {
+  const long long e = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
+  if (e >= rows * kp) return;
+  const long long m = e / kp;
+  const int n = static_cast<int>(e % kp);
+  const float g = load_f32<T>(hpre + m * ldh + n), u = load_f32<T>(hpre + m * ldh + kp + n);
+  store_f32<T>(act + m * lda + n, g * act_sigmoid(g) * u);
+}
+
+static GemmDesc gemm_desc(int dtype, int M, int N, int K, const void* A, long long lda, int ta, const void* B,
+                          long long ldb, int tb) {
+  GemmDesc g;
+  memset(&g, 0, sizeof(g));
+  g.dtype = dtype; g.M = M; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.trans_a = ta;
+  g.B = B; g.ldb = ldb; g.trans_b = tb;
+  g.splits = 1;
+  return g;
+}
+
+static int ffn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, void* y,
+                       const ecospa_saved* saved) {
+  const int T = d.B * d.L, kp = d.kp_ff, nh = is_gated(d) ? 2 * kp : kp;
+  void* hpre = saved ? saved->hpre : w.hpre_tmp;
+  void* act = saved ? saved->act : w.act_tmp;
+  if (!hpre || !act) return ECOSPA_ERR_NULL;
+  int rc;
+  GemmDesc g = gemm_desc(d.dtype, T, nh, d.d_model, x, d.d_model, 0, d.w_1, d.ld_w1, 0);
+  g.epi.c = hpre; g.epi.ldc = nh; g.epi.bias = d.b_1;
+  if (is_gated(d)) {
+    g.epi.kind = EPI_STORE;
+    if ((rc = ecospa_gemm(ctx, g))) return rc;
+    const long long tot = static_cast<long long>(T) * kp;
+    const unsigned grid = static_cast<unsigned>((tot + 255) / 256);
+    if (d.dtype == ECOSPA_BF16)
+      hipLaunchKernelGGL((swiglu_kernel<bf16_t>), dim3(grid), dim3(256), 0, ctx->stream, static_cast<const bf16_t*>(hpre),
+                         static_cast<long long>(nh), static_cast<bf16_t*>(act), static_cast<long long>(kp),
+                         static_cast<long long>(T), kp);
+    else
+      hipLaunchKernelGGL((swiglu_kernel<float>), dim3(grid), dim3(256), 0, ctx->stream, static_cast<const float*>(hpre),
+                         static_cast<long long>(nh), static_cast<float*>(act), static_cast<long long>(kp),
+                         static_cast<long long>(T), kp);
+    ECOSPA_CHECK_LAUNCH(ctx, "swiglu_kernel");
+  } else {
+    g.epi.kind = EPI_BIAS_ACT; g.epi.act = d.act;
+    g.epi.c2 = act; g.epi.ldc2 = kp;
+    if ((rc = ecospa_gemm(ctx, g))) return rc;
+  }
+  GemmDesc g2 = gemm_desc(d.dtype, T, d.d_model, kp, act, kp, 0, d.w_2, d.ld_w2, 0);
+  g2.epi.kind = EPI_STORE; g2.epi.c = y; g2.epi.ldc = d.d_model; g2.epi.bias = d.b_2;
+  return ecospa_gemm(ctx, g2);
+}
+
+static int ffn_backward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, const void* dy,
+                        const ecospa_saved& sv, void* dx, const ecospa_grads& gr) {
+  const int T = d.B * d.L, kp = d.kp_ff, nh = is_gated(d) ? 2 * kp : kp, dm = d.d_model;
+  if (!sv.hpre || !sv.act) return ECOSPA_ERR_NULL;
+  int rc;
+  // dW_2 = dY^T A
+  if (gr.dw_2) {
+    if (gr.ld_dw2 < kp) return ECOSPA_ERR_SHAPE;
+    GemmDesc g = gemm_desc(d.dtype, dm, kp, T, dy, dm, 1, sv.act, kp, 1);
+    g.splits = ecospa_gemm_splits(dm, kp, T); g.partial = w.partial;
+    g.epi.kind = EPI_STORE; g.epi.c = gr.dw_2; g.epi.ldc = gr.ld_dw2;
+    if ((rc = ecospa_gemm(ctx, g))) return rc;
+  }
+  if (gr.db_2 && (rc = ecospa_colsum(ctx, d.dtype, dy, dm, T, dm, w.colsum_partial, gr.db_2))) return rc;
+  // dH = (dY W_2) * act'(H)
+  {
+    GemmDesc g = gemm_desc(d.dtype, T, kp, dm, dy, dm, 0, d.w_2, d.ld_w2, 1);
+    g.epi.c = w.dh; g.epi.ldc = nh; g.epi.h = sv.hpre; g.epi.ldh = nh; g.epi.act = d.act; g.epi.kp = kp;
+    g.epi.kind = is_gated(d) ? EPI_DSWIGLU : EPI_DACT;
+    if ((rc = ecospa_gemm(ctx, g))) return rc;
+  }
+  // dW_1 = dH^T X
+  if (gr.dw_1) {
+    if (gr.ld_dw1 < dm) return ECOSPA_ERR_SHAPE;
+    GemmDesc g = gemm_desc(d.dtype, nh, dm, T, w.dh, nh, 1, x, dm, 1);
+    g.splits = ecospa_gemm_splits(nh, dm, T); g.partial = w.partial;
+    g.epi.kind = EPI_STORE; g.epi.c = gr.dw_1; g.epi.ldc = gr.ld_dw1;
+    if ((rc = ecospa_gemm(ctx, g))) return rc;
+  }
+  if (gr.db_1 && (rc = ecospa_colsum(ctx, d.dtype, w.dh, nh, T, nh, w.colsum_partial, gr.db_1))) return rc;
+  // dX = dH W_1
+  if (dx) {
+    GemmDesc g = gemm_desc(d.dtype, T, dm, nh, w.dh, nh, 0, d.w_1, d.ld_w1, 1);
+    g.epi.kind = EPI_STORE; g.epi.c = dx; g.epi.ldc = dm;
+    if ((rc = ecospa_gemm(ctx, g))) return rc;
+  }
+  return ECOSPA_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+extern "C" int ecospa_coupled_fwd(ecospa_ctx* ctx, const ecospa_block_desc* desc, const void* x, void* y,
+                                  const ecospa_saved* saved) {
+  if (!ctx || !desc || !x || !y) return ECOSPA_ERR_NULL;
+  int rc = validate_block(desc);
+  if (rc) return rc;
+  if (!aligned16(x) || !aligned16(y)) return ECOSPA_ERR_ALIGN;
+  BlockWs w;
+  block_ws_layout(*desc, nullptr, w);
+  if (!ctx->ws || ctx->ws_bytes < w.total) return ECOSPA_ERR_WORKSPACE;
+  block_ws_layout(*desc, ctx->ws, w);
+  if (desc->block == ECOSPA_BLOCK_FFN) return ffn_forward(ctx, *desc, w, x, y, saved);
+  return attn_forward(ctx, *desc, w, x, y, saved);
+}
+
+extern "C" int ecospa_coupled_bwd(ecospa_ctx* ctx, const ecospa_block_desc* desc, const void* x, const void* dy,
+                                  const ecospa_saved* saved, void* dx, const ecospa_grads* grads) {
+  if (!ctx || !desc || !x || !dy || !saved || !grads) return ECOSPA_ERR_NULL;
+  int rc = validate_block(desc);
+  if (rc) return rc;
+  if (!aligned16(x) || !aligned16(dy) || (dx && !aligned16(dx))) return ECOSPA_ERR_ALIGN;
+  BlockWs w;
+  block_ws_layout(*desc, nullptr, w);
+  if (!ctx->ws || ctx->ws_bytes < w.total) return ECOSPA_ERR_WORKSPACE;
+  block_ws_layout(*desc, ctx->ws, w);
+  if (desc->block == ECOSPA_BLOCK_FFN) return ffn_backward(ctx, *desc, w, x, dy, *saved, dx, *grads);
+  return attn_backward(ctx, *desc, w, x, dy, *saved, dx, *grads);
+}

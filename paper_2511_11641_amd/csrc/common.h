@@ -1,0 +1,75 @@
+// Shared host/device helpers of the gfx950 library (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/ecospa.h"
+
+struct ecospa_ctx {
+  hipStream_t stream;
+  void* ws;
+  size_t ws_bytes;
+  char err[256];
+};
+
+typedef unsigned short bf16_t;  // raw bfloat16 bits
+
+static inline size_t dtype_size(int dtype) { return dtype == ECOSPA_BF16 ? 2 : 4; }
+static inline bool dtype_ok(int dtype) { return dtype == ECOSPA_F32 || dtype == ECOSPA_BF16; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Record a HIP failure on the context and return ERR_HIP.
+static inline int hip_fail(ecospa_ctx* ctx, hipError_t e, const char* where) {
+  if (ctx) snprintf(ctx->err, sizeof(ctx->err), "%s: %s", where, hipGetErrorString(e));
+  return ECOSPA_ERR_HIP;
+}
+#define ECOSPA_CHECK_LAUNCH(ctx, where)                         \
+  do {                                                          \
+    hipError_t e__ = hipGetLastError();                         \
+    if (e__ != hipSuccess) return hip_fail(ctx, e__, where);    \
+  } while (0)
+
+// Carve 256-byte aligned pieces out of the caller's workspace.
+struct WsCarver {
+  char* base;
+  size_t off, cap;
+  WsCarver(void* p, size_t bytes) : base(static_cast<char*>(p)), off(0), cap(bytes) {}
+  void* take(size_t bytes) {
+    size_t o = align_up(off, 256);
+    off = o + bytes;
+    return (base && off <= cap) ? base + o : nullptr;
+  }
+  bool ok() const { return base != nullptr && off <= cap; }
+};
+
+#ifdef __HIPCC__
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<bf16_t>(u >> 16);
+}
+template <typename T> __device__ __forceinline__ float load_f32(const T* p);
+template <> __device__ __forceinline__ float load_f32<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float load_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+template <typename T> __device__ __forceinline__ void store_f32(T* p, float v);
+template <> __device__ __forceinline__ void store_f32<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_f32<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// Sum over the 64 lanes of a wavefront; every lane gets the total (fixed order: deterministic).
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+#endif

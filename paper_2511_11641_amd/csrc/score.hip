@@ -1,0 +1,302 @@
+// Step 1: per-dimension coupled importance score (paper Eq. 10, criterion of Eq. 12).
+//
+// HBM-bound: every weight element of every pair in the batch is read exactly once with
+// 16-byte loads.  Three launches per batch of up to SCORE_MAX_PAIRS pairs:
+//   1. score_sumsq_kernel   - squared row norms (wave per row, shuffle reduction) and partial
+//                             squared column norms (16-lane x 16-row-slot tiles, LDS reduction)
+//   2. score_finish_kernel  - one workgroup per (pair, group): combine units, r = |a||b|,
+//                             group L2 norm, normalised scores
+// No floating-point atomics; all reduction orders are fixed.
+#include "common.h"
+
+#define SCORE_MAX_PAIRS 24
+#define SCORE_ROWS_PER_BLOCK 16   // row-norm blocks: 4 waves x 4 rows
+#define SCORE_COL_SLOTS 16        // column-norm blocks: 16 row slots x 16 lanes
+
+struct ScorePairDev {
+  const void* w1;
+  const void* w1b;
+  const void* w2;
+  long long ld1, ld1b, ld2;
+  float* a_sq;     // [rows]            squared norms of a_j
+  float* b_sq;     // [rows]            QK only: squared norms of rows of W_k
+  float* b_part;   // [n_chunks][rows]  other kinds: partial squared column norms of w2
+  float* scores;   // [groups * n / unit]
+  int rows;        // groups * n
+  int groups, n, unit;
+  int d1, d2;
+  int kind, dtype;
+  int n_chunks, rc;            // column kernel: chunks of rc rows of w2
+  int n_strips;                // column strips of 16 lanes * VEC columns
+  int blk_row1, blk_row2, blk_col, blk_end;   // first block index of each phase in launch 1
+  int fin_begin;               // first block index of this pair in launch 2
+};
+struct ScoreBatch {
+  int n_pairs;
+  ScorePairDev p[SCORE_MAX_PAIRS];
+};
+
+template <typename T> struct Vec16;
+template <> struct Vec16<float> { static constexpr int N = 4; };
+template <> struct Vec16<bf16_t> { static constexpr int N = 8; };
+
+template <typename T>
+__device__ __forceinline__ void load_vec(const T* p, float (&out)[Vec16<T>::N]);
+template <>
+__device__ __forceinline__ void load_vec<float>(const float* p, float (&out)[4]) {
+  float4 v = *reinterpret_cast<const float4*>(p);
+  out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+template <>
+__device__ __forceinline__ void load_vec<bf16_t>(const bf16_t* p, float (&out)[8]) {
+  uint4 v = *reinterpret_cast<const uint4*>(p);
+  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[2 * i] = __uint_as_float(w[i] << 16);
+    out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+
+// Squared norm of one row (optionally of the elementwise product of two rows), by one wavefront.
+template <typename T>
+__device__ __forceinline__ float row_sumsq(const T* r, const T* rb, int len, bool vec_ok, int lane) {
+  constexpr int V = Vec16<T>::N;
+  float acc = 0.f;
+  if (vec_ok) {
+    for (int c = lane * V; c < len; c += 64 * V) {
+      float a[V];
+      load_vec<T>(r + c, a);
+      if (rb) {
+        float b[V];
+        load_vec<T>(rb + c, b);
+#pragma unroll
+        for (int i = 0; i < V; ++i) { float t = a[i] * b[i]; acc += t * t; }
+      } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc += a[i] * a[i];
+      }
+    }
+  } else {
+    for (int c = lane; c < len; c += 64) {
+      float a = load_f32<T>(r + c);
+      if (rb) a *= load_f32<T>(rb + c);
+      acc += a * a;
+    }
+  }
+  return wave_sum(acc);
+}
+
+template <typename T>
+__device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
+  constexpr int V = Vec16<T>::N;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (blk < p.blk_col) {
+    // ---- row norms: phase 1 = w1 (x w1b), phase 2 = rows of w2 (QK) ----
+    const bool second = blk >= p.blk_row2;
+    const int local = blk - (second ? p.blk_row2 : p.blk_row1);
+    const T* w = static_cast<const T*>(second ? p.w2 : p.w1);
+    const T* wb = second ? nullptr : static_cast<const T*>(p.w1b);
+    const long long ld = second ? p.ld2 : p.ld1;
+    const int len = second ? p.d2 : p.d1;
+    float* out = second ? p.b_sq : p.a_sq;
+    bool vec_ok = (len % V == 0) && (ld % V == 0) && ((reinterpret_cast<uintptr_t>(w) & 15u) == 0);
+    if (wb) vec_ok = vec_ok && (p.ld1b % V == 0) && ((reinterpret_cast<uintptr_t>(wb) & 15u) == 0);
+#pragma unroll 1
+    for (int i = 0; i < SCORE_ROWS_PER_BLOCK / 4; ++i) {
+      const int row = local * SCORE_ROWS_PER_BLOCK + wave * (SCORE_ROWS_PER_BLOCK / 4) + i;
+      if (row >= p.rows) break;
+      float s = row_sumsq<T>(w + row * ld, wb ? wb + row * p.ld1b : nullptr, len, vec_ok, lane);
+      if (lane == 0) out[row] = s;
+    }
+    return;
+  }
+  // ---- partial squared column norms of w2 [d2, rows] ----
+  const int local = blk - p.blk_col;
+  const int strip = local % p.n_strips, chunk = local / p.n_strips;
+  const int slot = tid >> 4, l16 = tid & 15;
+  const T* w = static_cast<const T*>(p.w2);
+  const int col0 = strip * (16 * V) + l16 * V;
+  const int r_begin = chunk * p.rc;
+  const int r_end = min(r_begin + p.rc, p.d2);
+  const bool vec_ok = (p.ld2 % V == 0) && ((reinterpret_cast<uintptr_t>(w) & 15u) == 0);
+  float acc[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) acc[i] = 0.f;
+  if (vec_ok && col0 + V <= p.rows) {
+    for (int r = r_begin + slot; r < r_end; r += SCORE_COL_SLOTS) {
+      float a[V];
+      load_vec<T>(w + r * p.ld2 + col0, a);
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc[i] += a[i] * a[i];
+    }
+  } else {
+    for (int r = r_begin + slot; r < r_end; r += SCORE_COL_SLOTS) {
+#pragma unroll
+      for (int i = 0; i < V; ++i)
+        if (col0 + i < p.rows) {
+          float a = load_f32<T>(w + r * p.ld2 + col0 + i);
+          acc[i] += a * a;
+        }
+    }
+  }
+  // reduce the 16 row slots in a fixed order
+#pragma unroll
+  for (int i = 0; i < V; ++i) lds[slot * (16 * V) + l16 * V + i] = acc[i];
+  __syncthreads();
+  if (tid < 16 * V) {
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < SCORE_COL_SLOTS; ++k) s += lds[k * (16 * V) + tid];
+    const int col = strip * (16 * V) + tid;
+    if (col < p.rows) p.b_part[static_cast<long long>(chunk) * p.rows + col] = s;
+  }
+}
+
+__global__ __launch_bounds__(256) void score_sumsq_kernel(const ScoreBatch b) {
+  __shared__ float lds[SCORE_COL_SLOTS * 16 * 8];
+  const int blk = blockIdx.x;
+  int pi = 0;
+  while (pi + 1 < b.n_pairs && blk >= b.p[pi].blk_end) ++pi;
+  const ScorePairDev& p = b.p[pi];
+  if (p.dtype == ECOSPA_BF16) score_block<bf16_t>(p, blk, lds);
+  else score_block<float>(p, blk, lds);
+}
+
+// One workgroup per (pair, group).
+__global__ __launch_bounds__(256) void score_finish_kernel(const ScoreBatch b) {
+  __shared__ float red[4];
+  const int blk = blockIdx.x;
+  int pi = 0;
+  while (pi + 1 < b.n_pairs && blk >= b.p[pi + 1].fin_begin) ++pi;
+  const ScorePairDev& p = b.p[pi];
+  const int g = blk - p.fin_begin;
+  const int nu = p.n / p.unit;
+  const int tid = threadIdx.x;
+  float* out = p.scores + static_cast<long long>(g) * nu;
+  float sq = 0.f;
+  for (int u = tid; u < nu; u += 256) {
+    float a = 0.f, bsum = 0.f;
+    for (int j = 0; j < p.unit; ++j) {
+      const int row = g * p.n + u * p.unit + j;
+      a += p.a_sq[row];
+      if (p.kind == ECOSPA_PAIR_QK) {
+        bsum += p.b_sq[row];
+      } else {
+        float s = 0.f;
+        for (int c = 0; c < p.n_chunks; ++c) s += p.b_part[static_cast<long long>(c) * p.rows + row];
+        bsum += s;
+      }
+    }
+    const float r = sqrtf(a) * sqrtf(bsum);
+    out[u] = r;
+    sq += r * r;
+  }
+  sq = wave_sum(sq);
+  if ((tid & 63) == 0) red[tid >> 6] = sq;
+  __syncthreads();
+  const float tot = (red[0] + red[1]) + (red[2] + red[3]);
+  const float nrm = sqrtf(tot);
+  for (int u = tid; u < nu; u += 256) out[u] = nrm > 0.f ? out[u] / nrm : 0.f;
+}
+
+// ------------------------------------------------------------------------------------------
+static int validate_pair(const ecospa_pair& q) {
+  if (q.kind < ECOSPA_PAIR_QK || q.kind > ECOSPA_PAIR_FFN_GATED || !dtype_ok(q.dtype)) return ECOSPA_ERR_DTYPE;
+  if (!q.w1 || !q.w2 || (q.kind == ECOSPA_PAIR_FFN_GATED && !q.w1b)) return ECOSPA_ERR_NULL;
+  if (q.groups < 1 || q.n < 1 || q.unit < 1 || q.d1 < 1 || q.d2 < 1 || q.n % q.unit) return ECOSPA_ERR_SHAPE;
+  const long long rows = static_cast<long long>(q.groups) * q.n;
+  if (rows > (1ll << 30)) return ECOSPA_ERR_SHAPE;
+  if (q.ld1 < q.d1) return ECOSPA_ERR_SHAPE;
+  if (q.kind == ECOSPA_PAIR_FFN_GATED && q.ld1b < q.d1) return ECOSPA_ERR_SHAPE;
+  if (q.kind == ECOSPA_PAIR_QK ? q.ld2 < q.d2 : q.ld2 < rows) return ECOSPA_ERR_SHAPE;
+  return ECOSPA_OK;
+}
+
+// rows of w2 per column-kernel block: at most 16 chunks so the finishing pass stays short
+static int col_chunk_rows(int d2) {
+  int rc = (d2 + 15) / 16;
+  rc = (rc + SCORE_COL_SLOTS - 1) / SCORE_COL_SLOTS * SCORE_COL_SLOTS;
+  return rc < 16 ? 16 : rc;
+}
+
+static size_t pair_ws_bytes(const ecospa_pair& q) {
+  const size_t rows = static_cast<size_t>(q.groups) * q.n;
+  size_t b = align_up(rows * 4, 256);  // a_sq
+  if (q.kind == ECOSPA_PAIR_QK) {
+    b += align_up(rows * 4, 256);
+  } else {
+    const int rc = col_chunk_rows(q.d2);
+    const size_t chunks = (q.d2 + rc - 1) / rc;
+    b += align_up(chunks * rows * 4, 256);
+  }
+  return b;
+}
+
+extern "C" size_t ecospa_score_workspace_bytes(const ecospa_pair* pairs, int n_pairs) {
+  if (!pairs || n_pairs < 1) return 0;
+  size_t tot = 0;
+  for (int i = 0; i < n_pairs; ++i) {
+    if (validate_pair(pairs[i]) != ECOSPA_OK) return 0;
+    tot += pair_ws_bytes(pairs[i]);
+  }
+  return tot + 256;
+}
+
+extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, float* const* scores) {
+  if (!ctx || !pairs || !scores) return ECOSPA_ERR_NULL;
+  if (n_pairs < 1) return ECOSPA_ERR_SHAPE;
+  for (int i = 0; i < n_pairs; ++i) {
+    int rc = validate_pair(pairs[i]);
+    if (rc) return rc;
+    if (!scores[i]) return ECOSPA_ERR_NULL;
+  }
+  const size_t need = ecospa_score_workspace_bytes(pairs, n_pairs);
+  if (!ctx->ws || ctx->ws_bytes < need) return ECOSPA_ERR_WORKSPACE;
+  WsCarver ws(ctx->ws, ctx->ws_bytes);
+
+  for (int first = 0; first < n_pairs; first += SCORE_MAX_PAIRS) {
+    ScoreBatch b;
+    memset(&b, 0, sizeof(b));
+    b.n_pairs = (n_pairs - first < SCORE_MAX_PAIRS) ? n_pairs - first : SCORE_MAX_PAIRS;
+    int blk = 0, fin = 0;
+    for (int i = 0; i < b.n_pairs; ++i) {
+      const ecospa_pair& q = pairs[first + i];
+      ScorePairDev& p = b.p[i];
+      p.w1 = q.w1; p.w1b = (q.kind == ECOSPA_PAIR_FFN_GATED) ? q.w1b : nullptr; p.w2 = q.w2;
+      p.ld1 = q.ld1; p.ld1b = q.ld1b; p.ld2 = q.ld2;
+      p.rows = q.groups * q.n;
+      p.groups = q.groups; p.n = q.n; p.unit = q.unit;
+      p.d1 = q.d1; p.d2 = q.d2; p.kind = q.kind; p.dtype = q.dtype;
+      p.scores = scores[first + i];
+      p.a_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows) * 4));
+      const int row_blocks = (p.rows + SCORE_ROWS_PER_BLOCK - 1) / SCORE_ROWS_PER_BLOCK;
+      p.blk_row1 = blk;
+      blk += row_blocks;
+      p.blk_row2 = blk;
+      if (q.kind == ECOSPA_PAIR_QK) {
+        p.b_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows) * 4));
+        blk += row_blocks;
+        p.blk_col = blk;
+        p.n_chunks = 0; p.rc = 0; p.n_strips = 1;
+      } else {
+        p.blk_col = blk;
+        p.rc = col_chunk_rows(q.d2);
+        p.n_chunks = (q.d2 + p.rc - 1) / p.rc;
+        const int strip_w = 16 * (q.dtype == ECOSPA_BF16 ? 8 : 4);
+        p.n_strips = (p.rows + strip_w - 1) / strip_w;
+        p.b_part = static_cast<float*>(ws.take(static_cast<size_t>(p.n_chunks) * p.rows * 4));
+        blk += p.n_strips * p.n_chunks;
+      }
+      p.blk_end = blk;
+      p.fin_begin = fin;
+      fin += q.groups;
+    }
+    if (!ws.ok()) return ECOSPA_ERR_WORKSPACE;
+    hipLaunchKernelGGL(score_sumsq_kernel, dim3(blk), dim3(256), 0, ctx->stream, b);
+    ECOSPA_CHECK_LAUNCH(ctx, "score_sumsq_kernel");
+    hipLaunchKernelGGL(score_finish_kernel, dim3(fin), dim3(256), 0, ctx->stream, b);
+    ECOSPA_CHECK_LAUNCH(ctx, "score_finish_kernel");
+  }
+  return ECOSPA_OK;
+}

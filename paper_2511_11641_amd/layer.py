@@ -1,0 +1,166 @@
+"""Thin helpers that chain the C-ABI calls for one block: score -> select -> compact -> fwd/bwd.
+
+They only allocate tensors, fill descriptor structs and call :class:`binding.Context`; all
+arithmetic happens in the library.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import binding as B
+
+
+class FfnBlock:
+    """Compacted FFN pair (W_in / W_out, or W_gate (.) W_up / W_down)."""
+
+    def __init__(self, ctx: B.Context, w1, b1, w2, b2, act: int, w1b=None):
+        self.ctx, self.act = ctx, act
+        self.w1, self.b1, self.w2, self.b2, self.w1b = w1, b1, w2, b2, w1b
+        self.n, self.d = w1.shape
+        self.gated = act == B.ACT_SWIGLU
+        self.idx = None
+
+    def pair(self) -> B.Pair:
+        kind = B.PAIR_FFN_GATED if self.gated else B.PAIR_FFN
+        return B.Context.make_pair(kind, self.w1, self.w2, 1, self.n, 1, self.w1b)
+
+    def score(self) -> torch.Tensor:
+        return self.ctx.ecospa_coupled_score([self.pair()])[0]
+
+    def compact(self, idx: torch.Tensor):
+        """Gather the kept rows/columns named by idx[1, k] into the padded compact layout."""
+        c, k = self.ctx, idx.shape[1]
+        self.idx, self.k = idx, k
+        self.kp = kp = B.round_up(k, 16)
+        nh = 2 * kp if self.gated else kp
+        dt, dev = self.w1.dtype, self.w1.device
+        self.w1_c = torch.empty((nh, self.d), dtype=dt, device=dev)
+        c.ecospa_compact(self.w1, idx, 0, 1, self.n, 1, kp, out=self.w1_c[:kp])
+        if self.gated:
+            c.ecospa_compact(self.w1b, idx, 0, 1, self.n, 1, kp, out=self.w1_c[kp:])
+        self.b1_c = None
+        if self.b1 is not None:
+            self.b1_c = torch.empty((nh,), dtype=dt, device=dev)
+            c.ecospa_compact(self.b1, idx, 1, 1, self.n, 1, kp, out=self.b1_c[:kp])
+            if self.gated:
+                self.b1_c[kp:].zero_()
+        self.w2_c = c.ecospa_compact(self.w2, idx, 1, 1, self.n, 1, kp)
+        return self
+
+    def desc(self, Bsz: int, L: int) -> B.BlockDesc:
+        d = B.BlockDesc()
+        d.block, d.dtype, d.B, d.L, d.d_model = B.BLOCK_FFN, B.dtype_code(self.w1.dtype), Bsz, L, self.d
+        d.kp_ff, d.act = self.kp, self.act
+        d.w_1, d.b_1 = self.w1_c.data_ptr(), B._ptr(self.b1_c)
+        d.w_2, d.b_2 = self.w2_c.data_ptr(), B._ptr(self.b2)
+        d.ld_w1, d.ld_w2 = self.w1_c.stride(0), self.w2_c.stride(0)
+        return d
+
+    def alloc(self, Bsz: int, L: int):
+        T, dt, dev = Bsz * L, self.w1.dtype, self.w1.device
+        nh = 2 * self.kp if self.gated else self.kp
+        self.hpre = torch.empty((T, nh), dtype=dt, device=dev)
+        self.act_buf = torch.empty((T, self.kp), dtype=dt, device=dev)
+        self.saved = B.Saved(None, None, None, self.hpre.data_ptr(), self.act_buf.data_ptr())
+        self.y = torch.empty((T, self.d), dtype=dt, device=dev)
+        self.dx = torch.empty((T, self.d), dtype=dt, device=dev)
+        self.dw1_c = torch.empty_like(self.w1_c)
+        self.dw2_c = torch.empty_like(self.w2_c)
+        self.db1_c = torch.empty((nh,), dtype=dt, device=dev)
+        self.db2 = torch.empty((self.d,), dtype=dt, device=dev)
+        g = B.Grads()
+        g.dw_1, g.db_1, g.dw_2, g.db_2 = (t.data_ptr() for t in (self.dw1_c, self.db1_c, self.dw2_c, self.db2))
+        g.ld_dw1, g.ld_dw2 = self.dw1_c.stride(0), self.dw2_c.stride(0)
+        self.grads = g
+        self._desc = self.desc(Bsz, L)
+        return self
+
+    def fwd(self, x):
+        return self.ctx.ecospa_coupled_fwd(self._desc, x, self.y, self.saved)
+
+    def bwd(self, x, dy):
+        self.ctx.ecospa_coupled_bwd(self._desc, x, dy, self.saved, self.dx, self.grads)
+        return self.dx
+
+
+class AttnBlock:
+    """Compacted attention block: per-head W_q/W_k pairs and W_v/W_o pairs (Eq. 4), optional RoPE."""
+
+    def __init__(self, ctx: B.Context, wq, wk, wv, wo, bq, bk, bv, bo, h: int, d_h: int, *, rope: bool,
+                 causal: bool = True, rope_base: float = 10000.0):
+        self.ctx, self.h, self.d_h, self.rope, self.causal, self.rope_base = ctx, h, d_h, rope, causal, rope_base
+        self.wq, self.wk, self.wv, self.wo = wq, wk, wv, wo
+        self.bq, self.bk, self.bv, self.bo = bq, bk, bv, bo
+        self.d = wq.shape[1]
+        self.unit = 2 if rope else 1
+
+    def pairs(self):
+        mk = B.Context.make_pair
+        return [mk(B.PAIR_QK, self.wq, self.wk, self.h, self.d_h, self.unit),
+                mk(B.PAIR_VO, self.wv, self.wo, self.h, self.d_h, 1)]
+
+    def score(self):
+        return self.ctx.ecospa_coupled_score(self.pairs())
+
+    def compact(self, idx_qk: torch.Tensor, idx_vo: torch.Tensor):
+        c, h, dh, u = self.ctx, self.h, self.d_h, self.unit
+        self.idx_qk, self.idx_vo = idx_qk, idx_vo
+        self.k_qk_units, self.k_vo = idx_qk.shape[1], idx_vo.shape[1]
+        self.kp_qk = B.round_up(self.k_qk_units * u, 16)
+        self.kp_vo = B.round_up(self.k_vo, 16)
+        kpu = self.kp_qk // u
+        nq, nv = h * self.kp_qk, h * self.kp_vo
+        dt, dev = self.wq.dtype, self.wq.device
+        self.wqkv_c = torch.empty((2 * nq + nv, self.d), dtype=dt, device=dev)
+        c.ecospa_compact(self.wq, idx_qk, 0, h, dh, u, kpu, out=self.wqkv_c[:nq])
+        c.ecospa_compact(self.wk, idx_qk, 0, h, dh, u, kpu, out=self.wqkv_c[nq:2 * nq])
+        c.ecospa_compact(self.wv, idx_vo, 0, h, dh, 1, self.kp_vo, out=self.wqkv_c[2 * nq:])
+        self.bqkv_c = None
+        if self.bq is not None:
+            self.bqkv_c = torch.empty((2 * nq + nv,), dtype=dt, device=dev)
+            c.ecospa_compact(self.bq, idx_qk, 1, h, dh, u, kpu, out=self.bqkv_c[:nq])
+            c.ecospa_compact(self.bk, idx_qk, 1, h, dh, u, kpu, out=self.bqkv_c[nq:2 * nq])
+            c.ecospa_compact(self.bv, idx_vo, 1, h, dh, 1, self.kp_vo, out=self.bqkv_c[2 * nq:])
+        self.wo_c = c.ecospa_compact(self.wo, idx_vo, 1, h, dh, 1, self.kp_vo)
+        return self
+
+    def alloc(self, Bsz: int, L: int):
+        c, h = self.ctx, self.h
+        T, dt, dev = Bsz * L, self.wq.dtype, self.wq.device
+        nqkv, nv = self.wqkv_c.shape[0], h * self.kp_vo
+        self.cos = self.sin = None
+        if self.rope:
+            self.cos, self.sin = c.ecospa_rope_table(self.idx_qk, h, L, self.k_qk_units, self.kp_qk // 2, self.d_h,
+                                                     self.rope_base)
+        d = B.BlockDesc()
+        d.block, d.dtype, d.B, d.L, d.d_model = B.BLOCK_ATTN, B.dtype_code(dt), Bsz, L, self.d
+        d.h, d.kp_qk, d.kp_vo, d.causal = h, self.kp_qk, self.kp_vo, int(self.causal)
+        d.scale = float(self.d_h) ** -0.5
+        d.rope_cos, d.rope_sin = B._ptr(self.cos), B._ptr(self.sin)
+        d.w_qkv, d.b_qkv, d.w_o, d.b_o = self.wqkv_c.data_ptr(), B._ptr(self.bqkv_c), self.wo_c.data_ptr(), B._ptr(self.bo)
+        d.ld_wqkv, d.ld_wo = self.wqkv_c.stride(0), self.wo_c.stride(0)
+        self._desc = d
+        self.qkv = torch.empty((T, nqkv), dtype=dt, device=dev)
+        self.o = torch.empty((T, nv), dtype=dt, device=dev)
+        self.lse = torch.empty((Bsz * h * L,), dtype=torch.float32, device=dev)
+        self.saved = B.Saved(self.qkv.data_ptr(), self.o.data_ptr(), self.lse.data_ptr(), None, None)
+        self.y = torch.empty((T, self.d), dtype=dt, device=dev)
+        self.dx = torch.empty((T, self.d), dtype=dt, device=dev)
+        self.dwqkv_c = torch.empty_like(self.wqkv_c)
+        self.dbqkv_c = torch.empty((nqkv,), dtype=dt, device=dev)
+        self.dwo_c = torch.empty_like(self.wo_c)
+        self.dbo = torch.empty((self.d,), dtype=dt, device=dev)
+        g = B.Grads()
+        g.dw_qkv, g.db_qkv, g.dw_o, g.db_o = (t.data_ptr() for t in (self.dwqkv_c, self.dbqkv_c, self.dwo_c, self.dbo))
+        g.ld_dwqkv, g.ld_dwo = self.dwqkv_c.stride(0), self.dwo_c.stride(0)
+        self.grads = g
+        return self
+
+    def fwd(self, x):
+        return self.ctx.ecospa_coupled_fwd(self._desc, x, self.y, self.saved)
+
+    def bwd(self, x, dy):
+        self.ctx.ecospa_coupled_bwd(self._desc, x, dy, self.saved, self.dx, self.grads)
+        return self.dx

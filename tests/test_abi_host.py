@@ -1,0 +1,114 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and validates arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2511_11641_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return B.load()
+
+
+@pytest.fixture()
+def ctx(lib):
+    h = C.c_void_p()
+    assert lib.ecospa_create(C.byref(h), None) == B.OK
+    yield h
+    lib.ecospa_destroy(h)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    text = open(os.path.join(ROOT, "include", "ecospa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(ecospa_[a-z_]+)\s*\(", text))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    for code in range(9):
+        assert lib.ecospa_status_string(code)
+    assert b"unknown" in lib.ecospa_status_string(99)
+
+
+def test_select_validation(lib, ctx):
+    f = lib.ecospa_select_topk
+    assert f(ctx, 256, 1, 8, 0, 256) == B.ERR_K
+    assert f(ctx, 256, 1, 8, 9, 256) == B.ERR_K
+    assert f(ctx, 256, 0, 8, 1, 256) == B.ERR_SHAPE
+    assert f(ctx, None, 1, 8, 1, 256) == B.ERR_NULL
+    assert f(None, 256, 1, 8, 1, 256) == B.ERR_NULL
+
+
+def test_compact_validation(lib, ctx):
+    for f in (lib.ecospa_compact, lib.ecospa_scatter):
+        ok = dict(src=256, dst=512, dtype=B.F32, axis=0, groups=2, n=8, unit=1, k=4, kp=4, other=16, ls=16, ld=16, idx=768)
+
+        def call(**kw):
+            a = dict(ok, **kw)
+            return f(ctx, a["src"], a["dst"], a["dtype"], a["axis"], a["groups"], a["n"], a["unit"], a["k"], a["kp"],
+                     a["other"], a["ls"], a["ld"], a["idx"])
+
+        assert call(src=None) == B.ERR_NULL
+        assert call(idx=None) == B.ERR_NULL
+        assert call(dtype=7) == B.ERR_DTYPE
+        assert call(axis=2) == B.ERR_SHAPE
+        assert call(unit=3) == B.ERR_SHAPE          # n % unit
+        assert call(k=0) == B.ERR_K
+        assert call(k=9) == B.ERR_K
+        assert call(kp=3) == B.ERR_K
+        assert call(ls=8) == B.ERR_SHAPE
+        assert call(axis=1, ls=8, ld=8) == B.ERR_SHAPE   # axis 1 needs ld >= slots
+
+
+def test_score_validation(lib, ctx):
+    p = B.Pair(B.PAIR_FFN, B.F32, 1, 8, 1, 4, 4, 256, None, 512, 4, 0, 8)
+    arr = (B.Pair * 1)(p)
+    out = (C.c_void_p * 1)(1024)
+    assert lib.ecospa_score_workspace_bytes(arr, 1) > 0
+    assert lib.ecospa_coupled_score(ctx, arr, 1, out) == B.ERR_WORKSPACE   # no workspace attached
+    bad = B.Pair(B.PAIR_FFN_GATED, B.F32, 1, 8, 1, 4, 4, 256, None, 512, 4, 0, 8)
+    assert lib.ecospa_coupled_score(ctx, (B.Pair * 1)(bad), 1, out) == B.ERR_NULL   # gated needs w1b
+    bad = B.Pair(B.PAIR_FFN, B.F32, 1, 8, 3, 4, 4, 256, None, 512, 4, 0, 8)
+    assert lib.ecospa_coupled_score(ctx, (B.Pair * 1)(bad), 1, out) == B.ERR_SHAPE  # n % unit
+    bad = B.Pair(9, B.F32, 1, 8, 1, 4, 4, 256, None, 512, 4, 0, 8)
+    assert lib.ecospa_coupled_score(ctx, (B.Pair * 1)(bad), 1, out) == B.ERR_DTYPE
+    bad = B.Pair(B.PAIR_FFN, B.F32, 1, 8, 1, 4, 4, 256, None, 512, 4, 0, 7)
+    assert lib.ecospa_coupled_score(ctx, (B.Pair * 1)(bad), 1, out) == B.ERR_SHAPE  # ld2 < groups*n
+    assert lib.ecospa_score_workspace_bytes((B.Pair * 1)(bad), 1) == 0
+
+
+def test_block_validation(lib, ctx):
+    d = B.BlockDesc()
+    d.block, d.dtype, d.B, d.L, d.d_model = B.BLOCK_FFN, B.BF16, 2, 16, 64
+    d.kp_ff, d.act, d.w_1, d.w_2, d.ld_w1, d.ld_w2 = 32, B.ACT_GELU_ERF, 256, 512, 64, 32
+    need = lib.ecospa_block_workspace_bytes(C.byref(d))
+    assert need > 0
+    assert lib.ecospa_coupled_fwd(ctx, C.byref(d), 1024, 2048, None) == B.ERR_WORKSPACE
+    d2 = B.BlockDesc.from_buffer_copy(d)
+    d2.kp_ff = 30
+    assert lib.ecospa_block_workspace_bytes(C.byref(d2)) == 0
+    assert lib.ecospa_coupled_fwd(ctx, C.byref(d2), 1024, 2048, None) == B.ERR_SHAPE
+    d2 = B.BlockDesc.from_buffer_copy(d)
+    d2.act = 5
+    assert lib.ecospa_coupled_fwd(ctx, C.byref(d2), 1024, 2048, None) == B.ERR_DTYPE
+    d2 = B.BlockDesc.from_buffer_copy(d)
+    d2.w_1 = None
+    assert lib.ecospa_coupled_fwd(ctx, C.byref(d2), 1024, 2048, None) == B.ERR_NULL
+    d2 = B.BlockDesc.from_buffer_copy(d)
+    d2.ld_w1 = 60
+    assert lib.ecospa_coupled_fwd(ctx, C.byref(d2), 1024, 2048, None) == B.ERR_SHAPE
+    assert lib.ecospa_coupled_fwd(ctx, C.byref(d), 1028, 2048, None) == B.ERR_ALIGN
+    a = B.BlockDesc()
+    a.block, a.dtype, a.B, a.L, a.d_model = B.BLOCK_ATTN, B.BF16, 2, 16, 64
+    a.h, a.kp_qk, a.kp_vo, a.scale, a.w_qkv, a.w_o, a.ld_wqkv, a.ld_wo = 2, 16, 24, 0.125, 256, 512, 64, 64
+    assert lib.ecospa_coupled_fwd(ctx, C.byref(a), 1024, 2048, None) == B.ERR_SHAPE   # kp_vo % 16
+    assert lib.ecospa_set_workspace(ctx, 257, 1024) == B.ERR_ALIGN

@@ -1,0 +1,174 @@
+"""GPU parity (through the C ABI) of steps 1-3 against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ecospa_oracle as O
+from paper_2511_11641_amd import binding as B
+from paper_2511_11641_amd import synth
+from util import assert_close, dev, host, pad_cols, pad_rows
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    return B.Context("cuda:0")
+
+
+# ---- score -----------------------------------------------------------------------------------
+FFN_SHAPES = [  # (n, d, gated)
+    (1024, 256, False),   # the fp32 single-pair configuration
+    (1073, 264, False),   # ragged kept-dimension counts as in the paper's Tables 10-11
+    (4096, 1024, False),
+    (5461, 2048, True),
+    (37, 8, True),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("structure", ["scratch", "pretrained"])
+@pytest.mark.parametrize("n,d,gated", FFN_SHAPES)
+def test_score_ffn(ctx, n, d, gated, structure, dtype):
+    if n >= 4096 and (dtype == "f32" or structure == "scratch"):
+        pytest.skip("large shapes once")
+    t = synth.ffn_layer(3, 4, d, n, gated=gated, dtype=dtype, structure=structure, bias=False)
+    kind = O.PAIR_FFN_GATED if gated else O.PAIR_FFN
+    want = O.coupled_score(kind, t["w1"], t["w2"], 1, n, w1b=t.get("w1b"))
+    w1, w2, w1b = dev(t["w1"], dtype), dev(t["w2"], dtype), dev(t.get("w1b"), dtype)
+    got = ctx.ecospa_coupled_score([B.Context.make_pair(kind, w1, w2, 1, n, 1, w1b)])[0]
+    assert got.shape == (1, n)
+    assert_close(got, want, "f32", "ffn score")
+    assert abs(float(got.double().pow(2).sum().sqrt()) - 1.0) < 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("h,dh,d,unit", [(16, 64, 1024, 1), (32, 64, 2048, 2), (3, 64, 192, 1), (2, 8, 24, 2)])
+def test_score_attention_pairs_batched(ctx, h, dh, d, unit, dtype):
+    t = synth.attn_layer(4, 1, 2, d, h, dh, dtype=dtype, structure="pretrained", bias=False)
+    f = synth.ffn_layer(5, 2, d, 200, dtype=dtype, bias=False)
+    want = [O.coupled_score(O.PAIR_QK, t["wq"], t["wk"], h, dh, unit),
+            O.coupled_score(O.PAIR_VO, t["wv"], t["wo"], h, dh),
+            O.coupled_score(O.PAIR_FFN, f["w1"], f["w2"], 1, 200)]
+    g = {k: dev(v, dtype) for k, v in t.items()}
+    fw1, fw2 = dev(f["w1"], dtype), dev(f["w2"], dtype)
+    mk = B.Context.make_pair
+    got = ctx.ecospa_coupled_score([mk(B.PAIR_QK, g["wq"], g["wk"], h, dh, unit),
+                                    mk(B.PAIR_VO, g["wv"], g["wo"], h, dh, 1),
+                                    mk(B.PAIR_FFN, fw1, fw2, 1, 200, 1)])
+    for a, b, nm in zip(got, want, ("qk", "vo", "ffn")):
+        assert a.shape == b.shape
+        assert_close(a, b, "f32", nm)
+
+
+def test_score_many_pairs_spans_several_launch_batches(ctx):
+    pairs, want, keep = [], [], []
+    for i in range(30):
+        t = synth.ffn_layer(100 + i, 2, 40, 56 + i, dtype="bf16", bias=False)
+        w1, w2 = dev(t["w1"], "bf16"), dev(t["w2"], "bf16")
+        keep += [w1, w2]
+        pairs.append(B.Context.make_pair(B.PAIR_FFN, w1, w2, 1, 56 + i, 1))
+        want.append(O.coupled_score(O.PAIR_FFN, t["w1"], t["w2"], 1, 56 + i))
+    got = ctx.ecospa_coupled_score(pairs)
+    for a, b in zip(got, want):
+        assert_close(a, b, "f32", "batched score")
+
+
+def test_score_zero_group_and_strided_views(ctx):
+    n, d = 64, 48
+    big1 = torch.randn(n, d + 16, device="cuda", dtype=torch.float32)
+    big2 = torch.randn(d, n + 8, device="cuda", dtype=torch.float32)
+    w1, w2 = big1[:, :d], big2[:, :n]          # leading dimensions larger than the extents
+    w1[5].zero_()
+    got = ctx.ecospa_coupled_score([B.Context.make_pair(B.PAIR_FFN, w1, w2, 1, n, 1)])[0]
+    want = O.coupled_score(O.PAIR_FFN, host(w1), host(w2), 1, n)
+    assert_close(got, want, "f32", "strided")
+    assert float(got[0, 5]) == 0.0
+    z = torch.zeros(n, d, device="cuda", dtype=torch.float32)
+    got = ctx.ecospa_coupled_score([B.Context.make_pair(B.PAIR_FFN, z, w2.contiguous(), 1, n, 1)])[0]
+    assert torch.all(got == 0)
+
+
+# ---- select ----------------------------------------------------------------------------------
+@pytest.mark.parametrize("groups,n,k", [(1, 1024, 512), (16, 64, 32), (16, 64, 48), (16, 64, 19), (1, 4096, 2048),
+                                        (1, 4096, 1228), (1, 5461, 2730), (32, 32, 16), (3, 7, 7), (2, 300, 1),
+                                        (1, 70000, 35000)])
+def test_select_bit_exact(ctx, groups, n, k):
+    s = np.abs(synth.normal(7, 200, (groups, n))).astype(np.float32)
+    got = ctx.ecospa_select_topk(dev(s), k)
+    np.testing.assert_array_equal(got.cpu().numpy(), O.select_topk(s, k))
+
+
+def test_select_ties_signed_zero_nan_inf(ctx):
+    g = np.random.Generator(np.random.Philox(key=[9, 1]))
+    n = 777
+    s = g.integers(0, 12, size=(5, n)).astype(np.float32) / 8.0          # heavy exact ties
+    s[1, ::7] = -0.0
+    s[1, 1::7] = 0.0
+    s[2, ::5] = np.nan
+    s[2, 1::9] = -np.inf
+    s[2, 2::11] = np.inf
+    s[3] = 0.25
+    s[4] = -s[4]
+    for k in (1, 2, 100, 388, 776, 777):
+        got = ctx.ecospa_select_topk(dev(s), k).cpu().numpy()
+        np.testing.assert_array_equal(got, O.select_topk(s, k), err_msg=f"k={k}")
+
+
+def test_select_on_gpu_scores_of_tied_weights(ctx):
+    """Duplicated inner dimensions give exactly tied scores; the lower index must win."""
+    t = synth.ffn_layer(11, 2, 64, 256, dtype="bf16", structure="ties", bias=False)
+    w1, w2 = dev(t["w1"], "bf16"), dev(t["w2"], "bf16")
+    sc = ctx.ecospa_coupled_score([B.Context.make_pair(B.PAIR_FFN, w1, w2, 1, 256, 1)])[0]
+    s = sc.cpu().numpy()
+    assert np.array_equal(s[0, 0:4], s[0, 4:8])          # ties really are exact on the GPU
+    got = ctx.ecospa_select_topk(sc, 128).cpu().numpy()
+    np.testing.assert_array_equal(got, O.select_topk(s, 128))
+
+
+# ---- compact / scatter -----------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("groups,n,unit,k,kp,other", [(1, 1024, 1, 512, 512, 256), (16, 64, 1, 19, 32, 1024),
+                                                      (32, 64, 2, 16, 16, 2048), (1, 5461, 1, 2730, 2736, 520),
+                                                      (3, 10, 1, 4, 4, 7), (2, 12, 2, 3, 5, 9)])
+def test_compact_and_scatter_both_axes(ctx, groups, n, unit, k, kp, other, dtype):
+    nu = n // unit
+    sc = np.abs(synth.normal(13, 201, (groups, nu))).astype(np.float32)
+    idx_np = O.select_topk(sc, k)
+    idx = torch.from_numpy(idx_np).cuda()
+    src_np = synth.round_to(synth.normal(13, 202, (groups * n, other)), dtype)
+    src = dev(src_np, dtype)
+    # rows
+    got = ctx.ecospa_compact(src, idx, 0, groups, n, unit, kp)
+    want = pad_rows(O.compact(src_np, idx_np, 0, n, unit), groups, k * unit, kp * unit)
+    np.testing.assert_array_equal(host(got), want)
+    back = ctx.ecospa_scatter(got, idx, 0, groups, n, unit, kp)
+    np.testing.assert_array_equal(host(back), O.scatter(O.compact(src_np, idx_np, 0, n, unit), idx_np, 0, n, unit))
+    # columns
+    srcT = src.t().contiguous()
+    got = ctx.ecospa_compact(srcT, idx, 1, groups, n, unit, kp)
+    want = pad_cols(O.compact(src_np.T, idx_np, 1, n, unit), groups, k * unit, kp * unit)
+    np.testing.assert_array_equal(host(got), want)
+    back = ctx.ecospa_scatter(got, idx, 1, groups, n, unit, kp)
+    np.testing.assert_array_equal(host(back), O.scatter(O.compact(src_np.T, idx_np, 1, n, unit), idx_np, 1, n, unit))
+    # vector (bias)
+    vec = src[:, 0].contiguous()
+    got = ctx.ecospa_compact(vec, idx, 1, groups, n, unit, kp)
+    want = pad_rows(O.compact(src_np[:, 0], idx_np, 0, n, unit), groups, k * unit, kp * unit)
+    np.testing.assert_array_equal(host(got), want)
+
+
+def test_compact_keep_all_is_identity(ctx):
+    w = dev(synth.normal(14, 203, (4 * 16, 40)), "bf16")
+    idx = torch.arange(16, dtype=torch.int32).repeat(4, 1).cuda()
+    assert torch.equal(ctx.ecospa_compact(w, idx, 0, 4, 16, 1, 16), w)
+
+
+def test_rope_table(ctx):
+    h, L, dh = 3, 50, 16
+    idx_np = np.array([[0, 3, 7], [1, 2, 4], [5, 6, 7]], dtype=np.int32)
+    cos, sin = ctx.ecospa_rope_table(torch.from_numpy(idx_np).cuda(), h, L, 3, 4, dh)
+    ang = O.rope_angles(idx_np, L, dh)
+    np.testing.assert_allclose(host(cos)[:, :, :3], np.cos(ang), atol=2e-7)
+    np.testing.assert_allclose(host(sin)[:, :, :3], np.sin(ang), atol=2e-7)
+    assert torch.all(cos[:, :, 3] == 1) and torch.all(sin[:, :, 3] == 0)

@@ -9,7 +9,6 @@ import torch.nn.functional as F
 from oracle import ecospa_oracle as O
 from paper_2511_11641_amd import synth
 
-torch.set_default_dtype(torch.float64)
 
 
 def _t(a, grad=False):
