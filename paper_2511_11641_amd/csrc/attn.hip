@@ -1,10 +1,667 @@
-// Attention block (placeholder until the kernels land): reports an unsupported configuration.
+// Attention block on compacted heads (paper Eq. 1-2 rewritten per head as Eq. 4; rotary form
+// Eq. 6): projections and W_o run on the GEMM kernels, this file holds the attention core
+// (tiled over keys, never materialising the L x L matrix) and its backward pass, all on
+// v_mfma_f32_32x32x16_bf16.
+//
+// Layout trick used by all three kernels: the score tile is computed "transposed" so that the
+// softmax row index sits in the lane (column of the MFMA result) and the contraction index of
+// the NEXT matmul sits in the accumulator registers.  Eight consecutive accumulator registers
+// then are, after conversion to bf16, directly the B operand of that next matmul - the
+// probabilities never go through LDS.  The matching A operand is read from a transposed LDS
+// copy of V (or K, Q, dO) with the same register->index permutation:
+//   registers r = 8*(s%2) .. +7 of 32-row tile s/2, lane half hh  <->  rows 16*s + 8*(j/4) + 4*hh + j%4.
+// Determinism: dQ and dK/dV come from two kernels (one loops over keys, one over queries), so no
+// floating-point atomics are needed.
 #include "block.h"
 
-int attn_forward(ecospa_ctx*, const ecospa_block_desc&, const BlockWs&, const void*, void*, const ecospa_saved*) {
-  return ECOSPA_ERR_DTYPE;
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+#define LOG2E 1.4426950408889634f
+#define LN2 0.6931471805599453f
+
+struct AttnArgs {
+  const bf16_t* qkv;   // [T, nqkv]: Q | K | V column blocks, head-major inside each
+  long long ld_qkv;
+  bf16_t* o;           // [T, h*kp_vo]
+  const bf16_t* d_o;   // backward: gradient of o
+  long long ld_o;
+  float* lse;          // [B, h, L] natural-log sum-exp of the scaled, masked scores
+  float* delta;        // [B, h, L] rowsum(dO * O)
+  bf16_t* dqkv;        // backward output, same layout as qkv
+  int B, L, h, kp_qk, kp_vo, causal;
+  float scale;
+};
+
+// ---------------------------------------------------------------------------------------------
+// LDS tile addressing (element offsets); 16-byte chunks are XOR-swizzled against bank conflicts
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__device__ __forceinline__ int nat_off(int row, int chunk) {   // [rows][D], D in {32, 64}
+  constexpr int C = D / 8, RPL = D >= 64 ? 1 : 64 / D;   // chunks per row, rows per 128 bytes
+  return row * D + ((chunk ^ ((row / RPL) & (C - 1))) << 3);
 }
-int attn_backward(ecospa_ctx*, const ecospa_block_desc&, const BlockWs&, const void*, const void*, const ecospa_saved&,
-                  void*, const ecospa_grads&) {
-  return ECOSPA_ERR_DTYPE;
+__device__ __forceinline__ int tr_off(int row, int chunk) {    // [dims][64 tokens]
+  return row * 64 + ((chunk ^ ((row ^ (row >> 3)) & 7)) << 3);
+}
+template <int D>
+__device__ __forceinline__ bf16x8_t frag_nat(const bf16_t* tile, int row, int s, int hh) {
+  return *reinterpret_cast<const bf16x8_t*>(tile + nat_off<D>(row, 2 * s + hh));
+}
+// 8 tokens {16*s + 4*hh + 0..3, 16*s + 8 + 4*hh + 0..3} of one dim row of a transposed tile
+__device__ __forceinline__ bf16x8_t frag_tr(const bf16_t* tile, int row, int s, int hh) {
+  const u32x2 lo = *reinterpret_cast<const u32x2*>(tile + tr_off(row, 2 * s) + 4 * hh);
+  const u32x2 hi = *reinterpret_cast<const u32x2*>(tile + tr_off(row, 2 * s + 1) + 4 * hh);
+  const u32x4 v = {lo.x, lo.y, hi.x, hi.y};
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+// accumulator registers 8*half .. 8*half+7 as a bf16 B operand
+__device__ __forceinline__ bf16x8_t acc_to_frag(const floatx16& a, int half) {
+  floatx8 f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) f[i] = a[8 * half + i];
+  return __builtin_convertvector(f, bf16x8_t);
+}
+
+// A thread's 4-token x 8-dim piece ("sub-block") of a [64 tokens][D dims] tile lives in four
+// 16-byte registers: one load per token.  A tile has 16 * D/8 sub-blocks.
+template <int D>
+__device__ __forceinline__ void sub_load(u32x4 (&v)[4], const bf16_t* __restrict__ base, long long ld, long long row0,
+                                         int rows_valid, int kp, int sub) {
+  const int tblk = sub / (D / 8), dblk = sub % (D / 8);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = tblk * 4 + i;
+    v[i] = (r < rows_valid && dblk * 8 < kp)
+               ? *reinterpret_cast<const u32x4*>(base + (row0 + r) * ld + dblk * 8)
+               : u32x4{0u, 0u, 0u, 0u};
+  }
+}
+template <int D>
+__device__ __forceinline__ void sub_store_nat(const u32x4 (&v)[4], bf16_t* tile, int sub) {
+  const int tblk = sub / (D / 8), dblk = sub % (D / 8);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(tile + nat_off<D>(tblk * 4 + i, dblk)) = v[i];
+}
+template <int D>
+__device__ __forceinline__ void sub_store_tr(const u32x4 (&v)[4], bf16_t* tile, int sub) {
+  const int tblk = sub / (D / 8), dblk = sub % (D / 8);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    uint32_t e[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) e[i] = (j & 1) ? (v[i][j >> 1] >> 16) : (v[i][j >> 1] & 0xffffu);
+    u32x2 p;
+    p.x = e[0] | (e[1] << 16);
+    p.y = e[2] | (e[3] << 16);
+    *reinterpret_cast<u32x2*>(tile + tr_off(dblk * 8 + j, tblk >> 1) + 4 * (tblk & 1)) = p;
+  }
+}
+#define SUBS(D) (16 * ((D) / 8))
+
+// Write a [ROWS][D] natural LDS tile to global rows row0.. (only rows < rows_valid, dims < kp).
+template <int D>
+__device__ __forceinline__ void tile_to_global(const bf16_t* tile, int rows, bf16_t* __restrict__ base, long long ld,
+                                               long long row0, int rows_valid, int kp) {
+  for (int c = threadIdx.x; c < rows * (D / 8); c += 256) {
+    const int r = c / (D / 8), ch = c % (D / 8);
+    if (r < rows_valid && ch * 8 < kp)
+      *reinterpret_cast<u32x4*>(base + (row0 + r) * ld + ch * 8) = *reinterpret_cast<const u32x4*>(tile + nat_off<D>(r, ch));
+  }
+}
+// Park a transposed accumulator (column = token lane%32, rows = dims) in a natural LDS tile.
+template <int D>
+__device__ __forceinline__ void acc_to_tile(bf16_t* tile, int tok_row, int dim_tile, const floatx16& a, float mul,
+                                            int hh) {
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    typedef float floatx4 __attribute__((ext_vector_type(4)));
+    typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+    floatx4 f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[i] = a[4 * g + i] * mul;
+    const bf16x4_t b = __builtin_convertvector(f, bf16x4_t);
+    *reinterpret_cast<bf16x4_t*>(tile + nat_off<D>(tok_row, dim_tile * 4 + g) + 4 * hh) = b;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward: one workgroup per (128 queries, head, batch); 4 wavefronts x 32 queries
+// ---------------------------------------------------------------------------------------------
+template <int DQ, int DV>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(const AttnArgs a) {
+  constexpr int DMAX = DQ > DV ? DQ : DV;
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[128 * DMAX];   // Q tile, later the O staging tile
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[2][64 * DQ];
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[2][DV * 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, l32 = lane & 31;
+  const int qt = gridDim.x - 1 - blockIdx.x;   // heavy (late) causal tiles first
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int q0 = qt * 128;
+  const long long tok0 = static_cast<long long>(b) * a.L;
+  const bf16_t* Qg = a.qkv + head * a.kp_qk;
+  const bf16_t* Kg = a.qkv + a.h * a.kp_qk + head * a.kp_qk;
+  const bf16_t* Vg = a.qkv + 2 * a.h * a.kp_qk + head * a.kp_vo;
+  const int half = tid >> 7, sub = tid & 127;
+
+  // Q tile: two 64-row halves, one per half of the workgroup
+  u32x4 pre[4];   // this thread's sub-block of the tile in flight (K for half 0, V for half 1)
+  if (sub < SUBS(DQ)) {
+    sub_load<DQ>(pre, Qg, a.ld_qkv, tok0 + q0 + half * 64, a.L - q0 - half * 64, a.kp_qk, sub);
+    sub_store_nat<DQ>(pre, Qs + half * 64 * DQ, sub);
+  }
+  const int kv_end = a.causal ? min(a.L, q0 + 128) : a.L;
+  const int n_kv = (kv_end + 63) / 64;
+#define FWD_GLOAD(j)                                                                                   \
+  do {                                                                                                 \
+    if (half == 0) { if (sub < SUBS(DQ)) sub_load<DQ>(pre, Kg, a.ld_qkv, tok0 + (j) * 64, a.L - (j) * 64, a.kp_qk, sub); } \
+    else { if (sub < SUBS(DV)) sub_load<DV>(pre, Vg, a.ld_qkv, tok0 + (j) * 64, a.L - (j) * 64, a.kp_vo, sub); }           \
+  } while (0)
+#define FWD_SSTORE(buf)                                                           \
+  do {                                                                            \
+    if (half == 0) { if (sub < SUBS(DQ)) sub_store_nat<DQ>(pre, Ks[buf], sub); }  \
+    else { if (sub < SUBS(DV)) sub_store_tr<DV>(pre, Vt[buf], sub); }             \
+  } while (0)
+  FWD_GLOAD(0);
+  FWD_SSTORE(0);
+  __syncthreads();
+  bf16x8_t qf[DQ / 16];
+#pragma unroll
+  for (int s = 0; s < DQ / 16; ++s) qf[s] = frag_nat<DQ>(Qs, wave * 32 + l32, s, hh);
+
+  floatx16 oacc[DV / 32];
+#pragma unroll
+  for (int u = 0; u < DV / 32; ++u)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[u][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sc = a.scale * LOG2E;
+  const int qw0 = q0 + wave * 32, q_idx = qw0 + l32;
+
+  for (int j = 0; j < n_kv; ++j) {
+    const int cur = j & 1, kv0 = j * 64;
+    if (j + 1 < n_kv) FWD_GLOAD(j + 1);
+    const bool active = !(a.causal && kv0 > qw0 + 31);
+    if (active) {
+      floatx16 sacc[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[t][r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < DQ / 16; ++s)
+          sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DQ>(Ks[cur], t * 32 + l32, s, hh), qf[s], sacc[t], 0, 0, 0);
+      }
+      const bool need_mask = (a.causal && kv0 + 63 > qw0) || (kv0 + 64 > a.L);
+      float mx = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = sacc[t][r] * sc;
+          if (need_mask) {
+            const int key = kv0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
+            if (key >= a.L || (a.causal && key > q_idx)) v = -INFINITY;
+          }
+          sacc[t][r] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx);
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+      float psum = 0.f;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = __builtin_amdgcn_exp2f(sacc[t][r] - m_use);
+          sacc[t][r] = p;
+          psum += p;
+        }
+      l_run = l_run * alpha + psum;
+      m_run = m_new;
+#pragma unroll
+      for (int u = 0; u < DV / 32; ++u)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[u][r] *= alpha;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const bf16x8_t pf = acc_to_frag(sacc[s >> 1], s & 1);
+#pragma unroll
+        for (int u = 0; u < DV / 32; ++u)
+          oacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Vt[cur], u * 32 + l32, s, hh), pf, oacc[u], 0, 0, 0);
+      }
+    }
+    if (j + 1 < n_kv) FWD_SSTORE(cur ^ 1);
+    __syncthreads();
+  }
+#undef FWD_GLOAD
+#undef FWD_SSTORE
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  if (hh == 0 && q_idx < a.L)
+    a.lse[(static_cast<long long>(b) * a.h + head) * a.L + q_idx] = (m_run + __log2f(l_tot)) * LN2;
+  // O staging (the Q fragments live in registers, so the Q tile can be overwritten)
+#pragma unroll
+  for (int u = 0; u < DV / 32; ++u) acc_to_tile<DV>(Qs, wave * 32 + l32, u, oacc[u], inv, hh);
+  __syncthreads();
+  tile_to_global<DV>(Qs, 128, a.o + head * a.kp_vo, a.ld_o, tok0 + q0, a.L - q0, a.kp_vo);
+}
+
+// ---------------------------------------------------------------------------------------------
+// delta[b,h,t] = sum_dv dO * O
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_delta_kernel(const AttnArgs a) {
+  const long long e = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
+  const long long T = static_cast<long long>(a.B) * a.L;
+  if (e >= T * a.h) return;
+  const long long tok = e / a.h;
+  const int head = static_cast<int>(e % a.h);
+  const bf16_t* o = a.o + tok * a.ld_o + head * a.kp_vo;
+  const bf16_t* g = a.d_o + tok * a.ld_o + head * a.kp_vo;
+  float s = 0.f;
+  for (int c = 0; c < a.kp_vo; c += 8) {
+    const u32x4 x = *reinterpret_cast<const u32x4*>(o + c), y = *reinterpret_cast<const u32x4*>(g + c);
+    const uint32_t xw[4] = {x.x, x.y, x.z, x.w}, yw[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      s += __uint_as_float(xw[i] << 16) * __uint_as_float(yw[i] << 16);
+      s += __uint_as_float(xw[i] & 0xffff0000u) * __uint_as_float(yw[i] & 0xffff0000u);
+    }
+  }
+  const int bb = static_cast<int>(tok / a.L), t = static_cast<int>(tok % a.L);
+  a.delta[(static_cast<long long>(bb) * a.h + head) * a.L + t] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward, dQ: one workgroup per (128 queries, head, batch), loop over key tiles
+//   S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - delta), dQ^T += K^T dS^T
+// ---------------------------------------------------------------------------------------------
+template <int DQ, int DV>
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const AttnArgs a) {
+  constexpr int DMAX = DQ > DV ? DQ : DV;
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[128 * DMAX];   // Q tile, then dO tile, then dQ staging
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * DQ];
+  __shared__ __attribute__((aligned(16))) bf16_t Kt[DQ * 64];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[64 * DV];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, l32 = lane & 31;
+  const int qt = gridDim.x - 1 - blockIdx.x;
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int q0 = qt * 128;
+  const long long tok0 = static_cast<long long>(b) * a.L;
+  const bf16_t* Qg = a.qkv + head * a.kp_qk;
+  const bf16_t* Kg = a.qkv + a.h * a.kp_qk + head * a.kp_qk;
+  const bf16_t* Vg = a.qkv + 2 * a.h * a.kp_qk + head * a.kp_vo;
+  const bf16_t* dOg = a.d_o + head * a.kp_vo;
+  const int half = tid >> 7, sub = tid & 127;
+
+  bf16x8_t qf[DQ / 16], dof[DV / 16];
+  u32x4 pre[4];
+  {
+    if (sub < SUBS(DQ)) {
+      sub_load<DQ>(pre, Qg, a.ld_qkv, tok0 + q0 + half * 64, a.L - q0 - half * 64, a.kp_qk, sub);
+      sub_store_nat<DQ>(pre, Qs + half * 64 * DQ, sub);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < DQ / 16; ++s) qf[s] = frag_nat<DQ>(Qs, wave * 32 + l32, s, hh);
+    __syncthreads();
+    if (sub < SUBS(DV)) {
+      sub_load<DV>(pre, dOg, a.ld_o, tok0 + q0 + half * 64, a.L - q0 - half * 64, a.kp_vo, sub);
+      sub_store_nat<DV>(pre, Qs + half * 64 * DV, sub);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < DV / 16; ++s) dof[s] = frag_nat<DV>(Qs, wave * 32 + l32, s, hh);
+  }
+  const int qw0 = q0 + wave * 32, q_idx = qw0 + l32;
+  const long long stat = (static_cast<long long>(b) * a.h + head) * a.L;
+  const float lse2 = q_idx < a.L ? a.lse[stat + q_idx] * LOG2E : 0.f;
+  const float dlt = q_idx < a.L ? a.delta[stat + q_idx] : 0.f;
+  const float sc = a.scale * LOG2E;
+
+  floatx16 dq[DQ / 32];
+#pragma unroll
+  for (int u = 0; u < DQ / 32; ++u)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dq[u][r] = 0.f;
+
+  const int kv_end = a.causal ? min(a.L, q0 + 128) : a.L;
+  const int n_kv = (kv_end + 63) / 64;
+#define DQ_GLOAD(j)                                                                                    \
+  do {                                                                                                 \
+    if (half == 0) { if (sub < SUBS(DQ)) sub_load<DQ>(pre, Kg, a.ld_qkv, tok0 + (j) * 64, a.L - (j) * 64, a.kp_qk, sub); } \
+    else { if (sub < SUBS(DV)) sub_load<DV>(pre, Vg, a.ld_qkv, tok0 + (j) * 64, a.L - (j) * 64, a.kp_vo, sub); }           \
+  } while (0)
+  DQ_GLOAD(0);
+  for (int j = 0; j < n_kv; ++j) {
+    const int kv0 = j * 64;
+    __syncthreads();          // previous tile fully consumed
+    if (half == 0) { if (sub < SUBS(DQ)) { sub_store_nat<DQ>(pre, Ks, sub); sub_store_tr<DQ>(pre, Kt, sub); } }
+    else { if (sub < SUBS(DV)) sub_store_nat<DV>(pre, Vs, sub); }
+    __syncthreads();
+    if (j + 1 < n_kv) DQ_GLOAD(j + 1);
+    if (a.causal && kv0 > qw0 + 31) continue;
+    const bool need_mask = (a.causal && kv0 + 63 > qw0) || (kv0 + 64 > a.L);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      floatx16 sacc, pacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+#pragma unroll
+      for (int s = 0; s < DQ / 16; ++s)
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DQ>(Ks, t * 32 + l32, s, hh), qf[s], sacc, 0, 0, 0);
+#pragma unroll
+      for (int s = 0; s < DV / 16; ++s)
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DV>(Vs, t * 32 + l32, s, hh), dof[s], pacc, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = __builtin_amdgcn_exp2f(sacc[r] * sc - lse2);
+        if (need_mask) {
+          const int key = kv0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
+          if (key >= a.L || (a.causal && key > q_idx)) p = 0.f;
+        }
+        sacc[r] = p * (pacc[r] - dlt);
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8_t df = acc_to_frag(sacc, s2);
+#pragma unroll
+        for (int u = 0; u < DQ / 32; ++u)
+          dq[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Kt, u * 32 + l32, t * 2 + s2, hh), df, dq[u], 0, 0, 0);
+      }
+    }
+  }
+#undef DQ_GLOAD
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < DQ / 32; ++u) acc_to_tile<DQ>(Qs, wave * 32 + l32, u, dq[u], a.scale, hh);
+  __syncthreads();
+  tile_to_global<DQ>(Qs, 128, a.dqkv + head * a.kp_qk, a.ld_qkv, tok0 + q0, a.L - q0, a.kp_qk);
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward, dK and dV: one workgroup per (128 keys, head, batch), loop over query tiles
+//   S = Q K^T, dP = dO V^T, dS = P * (dP - delta), dV^T += dO^T P, dK^T += Q^T dS
+// ---------------------------------------------------------------------------------------------
+template <int DQ, int DV>
+__global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(const AttnArgs a) {
+  constexpr int DMAX = DQ > DV ? DQ : DV;
+  __shared__ __attribute__((aligned(16))) bf16_t KVs[128 * DMAX];   // K tile, V tile, then output staging
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[64 * DQ];
+  __shared__ __attribute__((aligned(16))) bf16_t Qt[DQ * 64];
+  __shared__ __attribute__((aligned(16))) bf16_t dOs[64 * DV];
+  __shared__ __attribute__((aligned(16))) bf16_t dOt[DV * 64];
+  __shared__ __attribute__((aligned(16))) float lse_s[64];
+  __shared__ __attribute__((aligned(16))) float dlt_s[64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, l32 = lane & 31;
+  const int kt = blockIdx.x;
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int k0 = kt * 128;
+  const long long tok0 = static_cast<long long>(b) * a.L;
+  const bf16_t* Qg = a.qkv + head * a.kp_qk;
+  const bf16_t* Kg = a.qkv + a.h * a.kp_qk + head * a.kp_qk;
+  const bf16_t* Vg = a.qkv + 2 * a.h * a.kp_qk + head * a.kp_vo;
+  const bf16_t* dOg = a.d_o + head * a.kp_vo;
+  const int half = tid >> 7, sub = tid & 127;
+
+  bf16x8_t kf[DQ / 16], vf[DV / 16];
+  u32x4 pre[4];
+  {
+    if (sub < SUBS(DQ)) {
+      sub_load<DQ>(pre, Kg, a.ld_qkv, tok0 + k0 + half * 64, a.L - k0 - half * 64, a.kp_qk, sub);
+      sub_store_nat<DQ>(pre, KVs + half * 64 * DQ, sub);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < DQ / 16; ++s) kf[s] = frag_nat<DQ>(KVs, wave * 32 + l32, s, hh);
+    __syncthreads();
+    if (sub < SUBS(DV)) {
+      sub_load<DV>(pre, Vg, a.ld_qkv, tok0 + k0 + half * 64, a.L - k0 - half * 64, a.kp_vo, sub);
+      sub_store_nat<DV>(pre, KVs + half * 64 * DV, sub);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < DV / 16; ++s) vf[s] = frag_nat<DV>(KVs, wave * 32 + l32, s, hh);
+  }
+  const int kw0 = k0 + wave * 32, key_idx = kw0 + l32;
+  const long long stat = (static_cast<long long>(b) * a.h + head) * a.L;
+  const float sc = a.scale * LOG2E;
+
+  floatx16 dk[DQ / 32], dv[DV / 32];
+#pragma unroll
+  for (int u = 0; u < DQ / 32; ++u)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dk[u][r] = 0.f;
+#pragma unroll
+  for (int u = 0; u < DV / 32; ++u)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dv[u][r] = 0.f;
+
+  const int n_q = (a.L + 63) / 64;
+  const int j0 = a.causal ? k0 / 64 : 0;     // first query tile that can see a key of this tile
+  float st = 0.f;
+  // query-tile prefetch: half 0 fetches Q, half 1 fetches dO; threads 0..63 also fetch lse,
+  // threads 64..127 delta, of the tile's 64 queries
+#define KV_GLOAD(j)                                                                                    \
+  do {                                                                                                 \
+    if (half == 0) { if (sub < SUBS(DQ)) sub_load<DQ>(pre, Qg, a.ld_qkv, tok0 + (j) * 64, a.L - (j) * 64, a.kp_qk, sub); } \
+    else { if (sub < SUBS(DV)) sub_load<DV>(pre, dOg, a.ld_o, tok0 + (j) * 64, a.L - (j) * 64, a.kp_vo, sub); }            \
+    if (tid < 128) {                                                                                   \
+      const int q_ = (j) * 64 + (tid & 63);                                                            \
+      st = q_ < a.L ? (tid < 64 ? a.lse[stat + q_] * LOG2E : a.delta[stat + q_]) : 0.f;                \
+    }                                                                                                  \
+  } while (0)
+  if (j0 < n_q) KV_GLOAD(j0);
+  for (int j = j0; j < n_q; ++j) {
+    const int qb0 = j * 64;
+    __syncthreads();
+    if (half == 0) { if (sub < SUBS(DQ)) { sub_store_nat<DQ>(pre, Qs, sub); sub_store_tr<DQ>(pre, Qt, sub); } }
+    else { if (sub < SUBS(DV)) { sub_store_nat<DV>(pre, dOs, sub); sub_store_tr<DV>(pre, dOt, sub); } }
+    if (tid < 64) lse_s[tid] = st;
+    else if (tid < 128) dlt_s[tid - 64] = st;
+    __syncthreads();
+    if (j + 1 < n_q) KV_GLOAD(j + 1);
+    if (a.causal && qb0 + 63 < kw0) continue;          // every query of the tile precedes this wave's keys
+    const bool need_mask = (a.causal && qb0 < kw0 + 31) || (qb0 + 64 > a.L) || (kw0 + 32 > a.L);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      floatx16 sacc, pacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+#pragma unroll
+      for (int s = 0; s < DQ / 16; ++s)
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DQ>(Qs, t * 32 + l32, s, hh), kf[s], sacc, 0, 0, 0);
+#pragma unroll
+      for (int s = 0; s < DV / 16; ++s)
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DV>(dOs, t * 32 + l32, s, hh), vf[s], pacc, 0, 0, 0);
+      floatx16 pr;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int qrow = t * 32 + g * 8 + hh * 4;
+        const float4 ls = *reinterpret_cast<const float4*>(lse_s + qrow);
+        const float4 dl = *reinterpret_cast<const float4*>(dlt_s + qrow);
+        const float lsv[4] = {ls.x, ls.y, ls.z, ls.w}, dlv[4] = {dl.x, dl.y, dl.z, dl.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int r = g * 4 + i;
+          float p = __builtin_amdgcn_exp2f(sacc[r] * sc - lsv[i]);
+          if (need_mask) {
+            const int q = qb0 + qrow + i;
+            if (q >= a.L || key_idx >= a.L || (a.causal && key_idx > q)) p = 0.f;
+          }
+          pr[r] = p;
+          sacc[r] = p * (pacc[r] - dlv[i]);
+        }
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8_t pf = acc_to_frag(pr, s2), df = acc_to_frag(sacc, s2);
+#pragma unroll
+        for (int u = 0; u < DV / 32; ++u)
+          dv[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(dOt, u * 32 + l32, t * 2 + s2, hh), pf, dv[u], 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < DQ / 32; ++u)
+          dk[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Qt, u * 32 + l32, t * 2 + s2, hh), df, dk[u], 0, 0, 0);
+      }
+    }
+  }
+#undef KV_GLOAD
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < DQ / 32; ++u) acc_to_tile<DQ>(KVs, wave * 32 + l32, u, dk[u], a.scale, hh);
+  __syncthreads();
+  tile_to_global<DQ>(KVs, 128, a.dqkv + a.h * a.kp_qk + head * a.kp_qk, a.ld_qkv, tok0 + k0, a.L - k0, a.kp_qk);
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < DV / 32; ++u) acc_to_tile<DV>(KVs, wave * 32 + l32, u, dv[u], 1.f, hh);
+  __syncthreads();
+  tile_to_global<DV>(KVs, 128, a.dqkv + 2 * a.h * a.kp_qk + head * a.kp_vo, a.ld_qkv, tok0 + k0, a.L - k0, a.kp_vo);
+}
+
+// ---------------------------------------------------------------------------------------------
+// rotary embedding, in place on the Q and K column blocks of a [T, nqkv] buffer (Eq. 6):
+// pair (2i, 2i+1) of head g at position t turns by +angle (forward) or -angle (gradients).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rope_kernel(bf16_t* __restrict__ buf, long long ld, const float* __restrict__ cs,
+                                                   const float* __restrict__ sn, int B, int L, int h, int kp_qk,
+                                                   float sign) {
+  const int cpr = 2 * h * kp_qk / 8;   // 16-byte chunks per token over the Q and K blocks
+  const long long e = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
+  if (e >= static_cast<long long>(B) * L * cpr) return;
+  const long long tok = e / cpr;
+  const int c = static_cast<int>(e % cpr);
+  const int col = c * 8;
+  const int within = col % (h * kp_qk);
+  const int head = within / kp_qk, i0 = (within % kp_qk) / 2;
+  const int t = static_cast<int>(tok % L);
+  const long long tab = (static_cast<long long>(head) * L + t) * (kp_qk / 2) + i0;
+  const float4 c4 = *reinterpret_cast<const float4*>(cs + tab);
+  const float4 s4 = *reinterpret_cast<const float4*>(sn + tab);
+  const float cv[4] = {c4.x, c4.y, c4.z, c4.w}, sv[4] = {s4.x, s4.y, s4.z, s4.w};
+  u32x4* p = reinterpret_cast<u32x4*>(buf + tok * ld + col);
+  const u32x4 v = *p;
+  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float x0 = __uint_as_float(w[i] << 16), x1 = __uint_as_float(w[i] & 0xffff0000u);
+    const float s = sign * sv[i];
+    const float y0 = x0 * cv[i] - x1 * s, y1 = x0 * s + x1 * cv[i];
+    w[i] = static_cast<uint32_t>(f32_to_bf16(y0)) | (static_cast<uint32_t>(f32_to_bf16(y1)) << 16);
+  }
+  *p = u32x4{w[0], w[1], w[2], w[3]};
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+static int pad32(int kp) { return (kp + 31) / 32 * 32; }
+
+template <int DQ, int DV>
+static void launch_core(int which, const AttnArgs& a, hipStream_t st) {
+  const dim3 grid((a.L + 127) / 128, a.h, a.B);
+  if (which == 0) hipLaunchKernelGGL((attn_fwd_kernel<DQ, DV>), grid, dim3(256), 0, st, a);
+  else if (which == 1) hipLaunchKernelGGL((attn_bwd_dq_kernel<DQ, DV>), grid, dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<DQ, DV>), grid, dim3(256), 0, st, a);
+}
+static int dispatch_core(ecospa_ctx* ctx, int which, const AttnArgs& a) {
+  const int dq = pad32(a.kp_qk), dv = pad32(a.kp_vo);
+  if (dq > 64 || dv > 64) return ECOSPA_ERR_SHAPE;   // head widths above 64 are not built
+  if (dq == 32 && dv == 32) launch_core<32, 32>(which, a, ctx->stream);
+  else if (dq == 32 && dv == 64) launch_core<32, 64>(which, a, ctx->stream);
+  else if (dq == 64 && dv == 32) launch_core<64, 32>(which, a, ctx->stream);
+  else launch_core<64, 64>(which, a, ctx->stream);
+  ECOSPA_CHECK_LAUNCH(ctx, "attention core kernel");
+  return ECOSPA_OK;
+}
+
+static int launch_rope(ecospa_ctx* ctx, const ecospa_block_desc& d, void* buf, long long ld, float sign) {
+  const long long tot = static_cast<long long>(d.B) * d.L * (2 * d.h * d.kp_qk / 8);
+  hipLaunchKernelGGL(rope_kernel, dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream,
+                     static_cast<bf16_t*>(buf), ld, d.rope_cos, d.rope_sin, d.B, d.L, d.h, d.kp_qk, sign);
+  ECOSPA_CHECK_LAUNCH(ctx, "rope_kernel");
+  return ECOSPA_OK;
+}
+
+static GemmDesc mk_gemm(int dtype, int M, int N, int K, const void* A, long long lda, int ta, const void* B,
+                        long long ldb, int tb, void* C, long long ldc, const void* bias) {
+  GemmDesc g;
+  memset(&g, 0, sizeof(g));
+  g.dtype = dtype; g.M = M; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.trans_a = ta;
+  g.B = B; g.ldb = ldb; g.trans_b = tb;
+  g.splits = 1;
+  g.epi.kind = EPI_STORE; g.epi.c = C; g.epi.ldc = ldc; g.epi.bias = bias;
+  return g;
+}
+
+int attn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, void* y,
+                 const ecospa_saved* saved) {
+  if (d.dtype != ECOSPA_BF16) return ECOSPA_ERR_DTYPE;   // the attention core is bf16 MFMA only
+  const int T = d.B * d.L, nqkv = attn_nqkv(d), nvo = d.h * d.kp_vo;
+  void* qkv = saved ? saved->qkv : w.qkv_tmp;
+  void* o = saved ? saved->o : w.o_tmp;
+  float* lse = saved ? saved->lse : w.lse_tmp;
+  if (!qkv || !o || !lse) return ECOSPA_ERR_NULL;
+  if (!aligned16(qkv) || !aligned16(o)) return ECOSPA_ERR_ALIGN;
+  int rc;
+  if ((rc = ecospa_gemm(ctx, mk_gemm(d.dtype, T, nqkv, d.d_model, x, d.d_model, 0, d.w_qkv, d.ld_wqkv, 0, qkv, nqkv, d.b_qkv))))
+    return rc;
+  if (d.rope_cos && (rc = launch_rope(ctx, d, qkv, nqkv, 1.f))) return rc;
+  AttnArgs a;
+  memset(&a, 0, sizeof(a));
+  a.qkv = static_cast<const bf16_t*>(qkv); a.ld_qkv = nqkv;
+  a.o = static_cast<bf16_t*>(o); a.ld_o = nvo; a.lse = lse;
+  a.B = d.B; a.L = d.L; a.h = d.h; a.kp_qk = d.kp_qk; a.kp_vo = d.kp_vo; a.causal = d.causal; a.scale = d.scale;
+  if ((rc = dispatch_core(ctx, 0, a))) return rc;
+  return ecospa_gemm(ctx, mk_gemm(d.dtype, T, d.d_model, nvo, o, nvo, 0, d.w_o, d.ld_wo, 0, y, d.d_model, d.b_o));
+}
+
+int attn_backward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, const void* dy,
+                  const ecospa_saved& sv, void* dx, const ecospa_grads& gr) {
+  if (d.dtype != ECOSPA_BF16) return ECOSPA_ERR_DTYPE;
+  const int T = d.B * d.L, nqkv = attn_nqkv(d), nvo = d.h * d.kp_vo, dm = d.d_model;
+  if (!sv.qkv || !sv.o || !sv.lse) return ECOSPA_ERR_NULL;
+  if (!aligned16(sv.qkv) || !aligned16(sv.o)) return ECOSPA_ERR_ALIGN;
+  int rc;
+  // dW_o = dY^T O,  db_o = colsum(dY),  dO = dY W_o
+  if (gr.dw_o) {
+    if (gr.ld_dwo < nvo) return ECOSPA_ERR_SHAPE;
+    GemmDesc g = mk_gemm(d.dtype, dm, nvo, T, dy, dm, 1, sv.o, nvo, 1, gr.dw_o, gr.ld_dwo, nullptr);
+    g.splits = ecospa_gemm_splits(dm, nvo, T); g.partial = w.partial;
+    if ((rc = ecospa_gemm(ctx, g))) return rc;
+  }
+  if (gr.db_o && (rc = ecospa_colsum(ctx, d.dtype, dy, dm, T, dm, w.colsum_partial, gr.db_o))) return rc;
+  if ((rc = ecospa_gemm(ctx, mk_gemm(d.dtype, T, nvo, dm, dy, dm, 0, d.w_o, d.ld_wo, 1, w.d_o, nvo, nullptr)))) return rc;
+
+  AttnArgs a;
+  memset(&a, 0, sizeof(a));
+  a.qkv = static_cast<const bf16_t*>(sv.qkv); a.ld_qkv = nqkv;
+  a.o = static_cast<bf16_t*>(sv.o); a.d_o = static_cast<const bf16_t*>(w.d_o); a.ld_o = nvo;
+  a.lse = sv.lse; a.delta = w.delta; a.dqkv = static_cast<bf16_t*>(w.dqkv);
+  a.B = d.B; a.L = d.L; a.h = d.h; a.kp_qk = d.kp_qk; a.kp_vo = d.kp_vo; a.causal = d.causal; a.scale = d.scale;
+  {
+    const long long tot = static_cast<long long>(T) * d.h;
+    hipLaunchKernelGGL(attn_delta_kernel, dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream, a);
+    ECOSPA_CHECK_LAUNCH(ctx, "attn_delta_kernel");
+  }
+  if ((rc = dispatch_core(ctx, 2, a))) return rc;
+  if ((rc = dispatch_core(ctx, 1, a))) return rc;
+  if (d.rope_cos && (rc = launch_rope(ctx, d, w.dqkv, nqkv, -1.f))) return rc;
+
+  // dW_qkv = dQKV^T X,  db_qkv = colsum(dQKV),  dX = dQKV W_qkv
+  if (gr.dw_qkv) {
+    if (gr.ld_dwqkv < dm) return ECOSPA_ERR_SHAPE;
+    GemmDesc g = mk_gemm(d.dtype, nqkv, dm, T, w.dqkv, nqkv, 1, x, dm, 1, gr.dw_qkv, gr.ld_dwqkv, nullptr);
+    g.splits = ecospa_gemm_splits(nqkv, dm, T); g.partial = w.partial;
+    if ((rc = ecospa_gemm(ctx, g))) return rc;
+  }
+  if (gr.db_qkv && (rc = ecospa_colsum(ctx, d.dtype, w.dqkv, nqkv, T, nqkv, w.colsum_partial, gr.db_qkv))) return rc;
+  if (dx && (rc = ecospa_gemm(ctx, mk_gemm(d.dtype, T, dm, nqkv, w.dqkv, nqkv, 0, d.w_qkv, d.ld_wqkv, 1, dx, dm, nullptr))))
+    return rc;
+  return ECOSPA_OK;
 }
