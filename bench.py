@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the coupled-sparse hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of a GPT-2-Medium-shaped layer
+(d=1024, 16 heads x 64, d_ff=4096, GELU, batch 8 x seq 1024, bf16):
+    score the QK, VO and FFN pairs (one batched call) -> select top-k at 50% keep ->
+    compact every matrix -> attention fwd -> FFN fwd -> FFN bwd -> attention bwd.
+Inputs are seeded synthetic tensors (weights N(0, 0.02^2), activations N(0, 1)) that are
+resident in HBM before the timed region.  One JSON line is printed.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+METRIC = "coupled-sparse layer fwd+bwd tokens/s & TFLOP/s vs dense, 50% sparsity, 1 GPU"
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+
+def model_flops(T, L, d, h, k_qk, k_vo, k_ff, causal=True):
+    """fwd+bwd model flops of one layer (backward = 2x forward, recomputation not counted,
+    causal attention counted at half)."""
+    proj = 2 * T * d * (2 * h * k_qk + h * k_vo) + 2 * T * d * h * k_vo
+    attn = (2 * T * L * h * (k_qk + k_vo)) * (0.5 if causal else 1.0)
+    ffn = 2 * 2 * T * d * k_ff
+    return 3.0 * (proj + attn + ffn)
+
+
+class Layer:
+    """One attention block followed by one FFN block, all through the C ABI."""
+
+    def __init__(self, ctx, cfg, seed, keep_num, keep_den):
+        import torch
+        from paper_2511_11641_amd import binding as B, synth
+        from paper_2511_11641_amd.layer import AttnBlock, FfnBlock
+        self.torch, self.B_ = torch, B
+        self.ctx, self.cfg = ctx, cfg
+        Bsz, L, d, h, dh, dff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
+        dt = cfg["dtype"]
+        a = synth.attn_layer(seed, Bsz, L, d, h, dh, dtype=dt, bias=cfg["bias"])
+        f = synth.ffn_layer(seed + 1000, 1, d, dff, gated=cfg["gated"], dtype=dt, bias=cfg["bias"])
+        self.host = {"attn": a, "ffn": f}
+        tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+        up = lambda arr: None if arr is None else torch.from_numpy(arr).to(tdt).cuda()
+        g = {k: up(v) for k, v in a.items()}
+        gf = {k: up(v) for k, v in f.items() if k not in ("x", "dy")}
+        self.x, self.dy = g["x"], g["dy"]
+        act = B.ACT_SWIGLU if cfg["gated"] else B.ACT_GELU_ERF
+        self.attn = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g.get("bq"), g.get("bk"), g.get("bv"),
+                              g.get("bo"), h, dh, rope=cfg["rope"], causal=True)
+        self.ffn = FfnBlock(ctx, gf["w1"], gf.get("b1"), gf["w2"], gf.get("b2"), act, gf.get("w1b"))
+        unit = 2 if cfg["rope"] else 1
+        self.k_qk_units = (dh // unit) * keep_num // keep_den
+        self.k_vo = dh * keep_num // keep_den
+        self.k_ff = dff * keep_num // keep_den
+        self.pairs = self.attn.pairs() + [self.ffn.pair()]
+        self.idx = [torch.empty((h, self.k_qk_units), dtype=torch.int32, device="cuda"),
+                    torch.empty((h, self.k_vo), dtype=torch.int32, device="cuda"),
+                    torch.empty((1, self.k_ff), dtype=torch.int32, device="cuda")]
+        self.prune()
+        self.attn.alloc(Bsz, L)
+        self.ffn.alloc(Bsz, L)
+
+    # steps 1-3
+    def score(self):
+        self.scores = self.ctx.ecospa_coupled_score(self.pairs)
+
+    def select(self):
+        for s, k, out in zip(self.scores, (self.k_qk_units, self.k_vo, self.k_ff), self.idx):
+            self.ctx.ecospa_select_topk(s, k, out=out)
+
+    def compact(self):
+        self.attn.compact(self.idx[0], self.idx[1])
+        self.ffn.compact(self.idx[2])
+
+    def prune(self):
+        self.score()
+        self.select()
+        self.compact()
+
+    # steps 4-5
+    def fwd(self):
+        y1 = self.attn.fwd(self.x)
+        return self.ffn.fwd(y1)
+
+    def bwd(self):
+        d1 = self.ffn.bwd(self.attn.y, self.dy)
+        return self.attn.bwd(self.x, d1)
+
+    def step(self):
+        self.prune()
+        self.fwd()
+        self.bwd()
+
+
+def timed(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def cpu_baseline(cfg, seed, keep_num, keep_den, sample_B):
+    """The fp64 oracle, as it stands, on `sample_B` batch elements of the same workload."""
+    import os
+    from oracle import ecospa_oracle as O
+    from paper_2511_11641_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    L, d, h, dh, dff = (cfg[k] for k in ("L", "d", "h", "d_h", "d_ff"))
+    a = synth.attn_layer(seed, sample_B, L, d, h, dh, dtype=cfg["dtype"], bias=cfg["bias"])
+    f = synth.ffn_layer(seed + 1000, 1, d, dff, gated=cfg["gated"], dtype=cfg["dtype"], bias=cfg["bias"])
+    dy = a["dy"]
+    t0 = time.perf_counter()
+    vq = O.coupled_score(O.PAIR_QK, a["wq"], a["wk"], h, dh)
+    vv = O.coupled_score(O.PAIR_VO, a["wv"], a["wo"], h, dh)
+    vf = O.coupled_score(O.PAIR_FFN, f["w1"], f["w2"], 1, dff)
+    iq = O.select_topk(vq.astype(np.float32), dh * keep_num // keep_den)
+    iv = O.select_topk(vv.astype(np.float32), dh * keep_num // keep_den)
+    iff = O.select_topk(vf.astype(np.float32), dff * keep_num // keep_den)
+    wq = O.heads_rows(O.compact(a["wq"], iq, 0, dh), h)
+    wk = O.heads_rows(O.compact(a["wk"], iq, 0, dh), h)
+    wv = O.heads_rows(O.compact(a["wv"], iv, 0, dh), h)
+    wo = O.heads_cols(O.compact(a["wo"], iv, 1, dh), h)
+    kw = dict(bq=O.compact(a["bq"], iq, 0, dh).reshape(h, -1), bk=O.compact(a["bk"], iq, 0, dh).reshape(h, -1),
+              bv=O.compact(a["bv"], iv, 0, dh).reshape(h, -1), bo=a["bo"])
+    w1, b1, w2 = O.compact(f["w1"], iff, 0, dff), O.compact(f["b1"], iff, 0, dff), O.compact(f["w2"], iff, 1, dff)
+    y1, sv = O.attn_fwd(a["x"], wq, wk, wv, wo, sample_B, L, dh ** -0.5, True, **kw)
+    _, sv2 = O.ffn_fwd(y1, w1, b1, w2, f["b2"], O.ACT_GELU_ERF)
+    g2 = O.ffn_bwd(y1, dy, w1, w2, O.ACT_GELU_ERF, sv2)
+    O.attn_bwd(a["x"], g2["dx"], wq, wk, wv, wo, sample_B, L, dh ** -0.5, sv)
+    dt = time.perf_counter() - t0
+    return {"value": sample_B * L / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{sample_B} of {cfg['B']} batch elements (seq {L}) of the same layer, whole path "
+                      f"score+select+compact+fwd+bwd in fp64 numpy, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the single-GPU hot path only: run it with --gpus 1 "
+              "(nothing in this library shards across GPUs).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2511_11641_amd import binding as B, synth
+    if not torch.cuda.is_available():
+        print("bench.py needs an MI355X: no GPU is visible.", file=sys.stderr)
+        sys.exit(2)
+    name = "c2_gpt2m_layer"
+    cfg = dict(synth.CONFIGS[name])
+    seed = cfg["seed"]
+    ctx = B.Context("cuda:0")
+    Bsz, L, d, h, dh, dff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
+    T = Bsz * L
+
+    sparse = Layer(ctx, cfg, seed, 1, 2)
+    ms_step = timed(torch, sparse.step, args.steps, args.warmup)
+
+    # break-down of the same step, each part timed on its own (not part of `value`)
+    parts = {nm: timed(torch, fn, args.steps, 2) for nm, fn in
+             (("score", sparse.score), ("select", sparse.select), ("compact", sparse.compact),
+              ("fwd", sparse.fwd), ("bwd", sparse.bwd))}
+    ms_fb = timed(torch, lambda: (sparse.fwd(), sparse.bwd()), args.steps, 2)
+
+    # dominant kernel: the bf16 MFMA contraction; per-launch events on the library's own stream
+    ctx.ecospa_profile_gemm(True)
+    for _ in range(args.steps):
+        sparse.step()
+    n_launch, gemm_ms, gemm_flop = ctx.ecospa_profile_gemm_read()
+    ctx.ecospa_profile_gemm(False)
+    gemm_tflops = gemm_flop / (gemm_ms * 1e-3) / 1e12
+
+    fl_sparse = model_flops(T, L, d, h, sparse.attn.kp_qk, sparse.attn.kp_vo, sparse.ffn.kp)
+    del sparse
+    torch.cuda.empty_cache()
+
+    dense = Layer(ctx, cfg, seed, 1, 1)        # same library at k = n: the dense layer
+    ms_dense_fb = timed(torch, lambda: (dense.fwd(), dense.bwd()), args.steps, args.warmup)
+    fl_dense = model_flops(T, L, d, h, dh, dh, dff)
+    del dense
+
+    w_bytes = 2 * (4 * d * d + 2 * d * dff)     # every weight of the three pairs, bf16
+    out = {
+        "metric": METRIC, "value": T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name, "layer": "GPT-2-Medium shaped: d=1024, 16 heads x 64, d_ff=4096, GELU, causal",
+                   "batch": Bsz, "seq_len": L, "keep": "1/2 per coupled pair (k_qk=32, k_vo=32, k_ff=2048)",
+                   "step": "score+select+compact+attn/ffn fwd+bwd"},
+        "fwd_bwd": {"ms": ms_fb, "tokens_per_s": T / (ms_fb * 1e-3), "model_tflops": fl_sparse / (ms_fb * 1e-3) / 1e12},
+        "dense_fwd_bwd": {"ms": ms_dense_fb, "tokens_per_s": T / (ms_dense_fb * 1e-3),
+                          "model_tflops": fl_dense / (ms_dense_fb * 1e-3) / 1e12},
+        "speedup_fwd_bwd_vs_dense": ms_dense_fb / ms_fb,
+        "speedup_whole_step_vs_dense_fwd_bwd": ms_dense_fb / ms_step,
+        "parts_ms": parts,
+        "score_gbs": w_bytes / (parts["score"] * 1e-3) / 1e9,
+        "compact_gbs": w_bytes / (parts["compact"] * 1e-3) / 1e9,   # kept bytes read + kept bytes written
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_mfma_kernel", "achieved": gemm_tflops,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gemm_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "launches": n_launch, "avg_launch_us": gemm_ms * 1e3 / max(n_launch, 1),
+                     "flop_per_launch_avg": gemm_flop / max(n_launch, 1),
+                     "measured": f"HIP events around each launch, {args.steps} steps re-run after the timed region"},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, seed, 1, 2, sample_B=8)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -52,6 +52,14 @@ const char* ecospa_status_string(int code);
 /* Text of the last HIP error seen by this context ("" if none); host string owned by ctx. */
 const char* ecospa_last_error(const ecospa_ctx* ctx);
 
+/* Measurement aid: time every launch of the bf16 MFMA contraction kernel with a pair of HIP events
+ * recorded on the context's own stream.  enable != 0 starts a new window (at most 4096 launches
+ * are kept); ecospa_profile_gemm_read waits for the recorded events and returns the number of
+ * launches, the sum of their durations in ms and the sum of their 2*M*N*K flops (host pointers).
+ * The events add a few microseconds per launch, so time throughput with profiling off. */
+int ecospa_profile_gemm(ecospa_ctx* ctx, int enable);
+int ecospa_profile_gemm_read(ecospa_ctx* ctx, int* launches, double* total_ms, double* total_flop);
+
 /* ------------------------------------------------------------------------------------------
  * Step 1 - per-dimension coupled importance score (paper Eq. 10; selection criterion Eq. 12).
  *

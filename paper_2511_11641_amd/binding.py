@@ -25,7 +25,7 @@ EXPORTS = (
     "ecospa_create", "ecospa_destroy", "ecospa_set_workspace", "ecospa_status_string", "ecospa_last_error",
     "ecospa_score_workspace_bytes", "ecospa_coupled_score", "ecospa_select_topk", "ecospa_compact",
     "ecospa_scatter", "ecospa_rope_table", "ecospa_block_workspace_bytes", "ecospa_coupled_fwd",
-    "ecospa_coupled_bwd",
+    "ecospa_coupled_bwd", "ecospa_profile_gemm", "ecospa_profile_gemm_read",
 )
 
 
@@ -103,6 +103,10 @@ def load() -> C.CDLL:
     lib.ecospa_coupled_fwd.restype = ci
     lib.ecospa_coupled_bwd.argtypes = [vp, C.POINTER(BlockDesc), vp, vp, C.POINTER(Saved), vp, C.POINTER(Grads)]
     lib.ecospa_coupled_bwd.restype = ci
+    lib.ecospa_profile_gemm.argtypes = [vp, ci]
+    lib.ecospa_profile_gemm.restype = ci
+    lib.ecospa_profile_gemm_read.argtypes = [vp, C.POINTER(ci), C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.ecospa_profile_gemm_read.restype = ci
     _lib = lib
     return lib
 
@@ -159,6 +163,15 @@ class Context:
             self._ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=self.device)
             self._check(self.lib.ecospa_set_workspace(self.h, self._ws.data_ptr(), self._ws.numel()),
                         "ecospa_set_workspace")
+
+    def ecospa_profile_gemm(self, enable: bool):
+        self._check(self.lib.ecospa_profile_gemm(self.h, int(enable)), "ecospa_profile_gemm")
+
+    def ecospa_profile_gemm_read(self):
+        n, ms, fl = C.c_int(), C.c_double(), C.c_double()
+        self._check(self.lib.ecospa_profile_gemm_read(self.h, C.byref(n), C.byref(ms), C.byref(fl)),
+                    "ecospa_profile_gemm_read")
+        return n.value, ms.value, fl.value
 
     # ---- step 1 ------------------------------------------------------------------------------
     @staticmethod

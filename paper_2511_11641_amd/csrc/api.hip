@@ -11,11 +11,55 @@ extern "C" int ecospa_create(ecospa_ctx** out, void* hip_stream) {
   c->ws = nullptr;
   c->ws_bytes = 0;
   c->err[0] = 0;
+  c->prof_on = c->prof_n = c->prof_cap = 0;
+  c->prof_ev = nullptr;
+  c->prof_flop = nullptr;
   *out = c;
   return ECOSPA_OK;
 }
 
-extern "C" void ecospa_destroy(ecospa_ctx* ctx) { delete ctx; }
+extern "C" void ecospa_destroy(ecospa_ctx* ctx) {
+  if (!ctx) return;
+  for (int i = 0; i < 2 * ctx->prof_cap; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
+  delete[] ctx->prof_ev;
+  delete[] ctx->prof_flop;
+  delete ctx;
+}
+
+extern "C" int ecospa_profile_gemm(ecospa_ctx* ctx, int enable) {
+  if (!ctx) return ECOSPA_ERR_NULL;
+  if (enable && !ctx->prof_ev) {
+    ctx->prof_ev = new (std::nothrow) hipEvent_t[2 * ECOSPA_PROF_MAX];
+    ctx->prof_flop = new (std::nothrow) double[ECOSPA_PROF_MAX];
+    if (!ctx->prof_ev || !ctx->prof_flop) return ECOSPA_ERR_NULL;
+    for (int i = 0; i < 2 * ECOSPA_PROF_MAX; ++i) {
+      hipError_t e = hipEventCreate(&ctx->prof_ev[i]);
+      if (e != hipSuccess) return hip_fail(ctx, e, "hipEventCreate");
+    }
+    ctx->prof_cap = ECOSPA_PROF_MAX;
+  }
+  ctx->prof_on = enable ? 1 : 0;
+  if (enable) ctx->prof_n = 0;
+  return ECOSPA_OK;
+}
+
+extern "C" int ecospa_profile_gemm_read(ecospa_ctx* ctx, int* launches, double* total_ms, double* total_flop) {
+  if (!ctx || !launches || !total_ms || !total_flop) return ECOSPA_ERR_NULL;
+  double ms = 0.0, fl = 0.0;
+  for (int i = 0; i < ctx->prof_n; ++i) {
+    hipError_t e = hipEventSynchronize(ctx->prof_ev[2 * i + 1]);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipEventSynchronize");
+    float t = 0.f;
+    e = hipEventElapsedTime(&t, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipEventElapsedTime");
+    ms += t;
+    fl += ctx->prof_flop[i];
+  }
+  *launches = ctx->prof_n;
+  *total_ms = ms;
+  *total_flop = fl;
+  return ECOSPA_OK;
+}
 
 extern "C" int ecospa_set_workspace(ecospa_ctx* ctx, void* dev, size_t bytes) {
   if (!ctx) return ECOSPA_ERR_NULL;

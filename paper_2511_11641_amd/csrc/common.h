@@ -7,11 +7,17 @@
 
 #include "../../include/ecospa.h"
 
+#define ECOSPA_PROF_MAX 4096   // GEMM launches that one profiling window can hold
+
 struct ecospa_ctx {
   hipStream_t stream;
   void* ws;
   size_t ws_bytes;
   char err[256];
+  // optional timing of the GEMM launches with events on `stream` (ecospa_profile_gemm)
+  int prof_on, prof_n, prof_cap;
+  hipEvent_t* prof_ev;      // 2 events per launch
+  double* prof_flop;
 };
 
 typedef unsigned short bf16_t;  // raw bfloat16 bits

@@ -370,6 +370,8 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
     int k_chunk = (d.K + splits - 1) / splits;
     k_chunk = (k_chunk + GB_K - 1) / GB_K * GB_K;
     dim3 grid(tm * tn, 1, splits);
+    const bool prof = ctx->prof_on && ctx->prof_n < ctx->prof_cap;
+    if (prof) (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n], ctx->stream);
     if (!d.trans_a && !d.trans_b)
       hipLaunchKernelGGL((gemm_bf16_mfma_kernel<false, false>), grid, dim3(256), 0, ctx->stream, d, tn, k_chunk);
     else if (!d.trans_a && d.trans_b)
@@ -378,6 +380,10 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
       hipLaunchKernelGGL((gemm_bf16_mfma_kernel<true, true>), grid, dim3(256), 0, ctx->stream, d, tn, k_chunk);
     else
       hipLaunchKernelGGL((gemm_bf16_mfma_kernel<true, false>), grid, dim3(256), 0, ctx->stream, d, tn, k_chunk);
+    if (prof) {
+      (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n + 1], ctx->stream);
+      ctx->prof_flop[ctx->prof_n++] = 2.0 * d.M * d.N * d.K;
+    }
     ECOSPA_CHECK_LAUNCH(ctx, "gemm_bf16_mfma_kernel");
   } else if (d.dtype == ECOSPA_F32) {
     const int tm = (d.M + 63) / 64, tn = (d.N + 63) / 64;

@@ -36,17 +36,16 @@ class FfnBlock:
         self.kp = kp = B.round_up(k, 16)
         nh = 2 * kp if self.gated else kp
         dt, dev = self.w1.dtype, self.w1.device
-        self.w1_c = torch.empty((nh, self.d), dtype=dt, device=dev)
+        if getattr(self, "w1_c", None) is None or self.w1_c.shape[0] != nh:     # buffers are reused across re-compactions
+            self.w1_c = torch.empty((nh, self.d), dtype=dt, device=dev)
+            self.b1_c = None if self.b1 is None else torch.zeros((nh,), dtype=dt, device=dev)
+            self.w2_c = torch.empty((self.d, kp), dtype=dt, device=dev)
         c.ecospa_compact(self.w1, idx, 0, 1, self.n, 1, kp, out=self.w1_c[:kp])
         if self.gated:
             c.ecospa_compact(self.w1b, idx, 0, 1, self.n, 1, kp, out=self.w1_c[kp:])
-        self.b1_c = None
-        if self.b1 is not None:
-            self.b1_c = torch.empty((nh,), dtype=dt, device=dev)
+        if self.b1 is not None:       # the up branch of a gated FFN has no bias: its slots stay zero
             c.ecospa_compact(self.b1, idx, 1, 1, self.n, 1, kp, out=self.b1_c[:kp])
-            if self.gated:
-                self.b1_c[kp:].zero_()
-        self.w2_c = c.ecospa_compact(self.w2, idx, 1, 1, self.n, 1, kp)
+        c.ecospa_compact(self.w2, idx, 1, 1, self.n, 1, kp, out=self.w2_c)
         return self
 
     def desc(self, Bsz: int, L: int) -> B.BlockDesc:
@@ -113,17 +112,22 @@ class AttnBlock:
         kpu = self.kp_qk // u
         nq, nv = h * self.kp_qk, h * self.kp_vo
         dt, dev = self.wq.dtype, self.wq.device
-        self.wqkv_c = torch.empty((2 * nq + nv, self.d), dtype=dt, device=dev)
+        if getattr(self, "wqkv_c", None) is None or self.wqkv_c.shape[0] != 2 * nq + nv:
+            self.wqkv_c = torch.empty((2 * nq + nv, self.d), dtype=dt, device=dev)
+            self.bqkv_c = None if self.bq is None else torch.empty((2 * nq + nv,), dtype=dt, device=dev)
+            self.wo_c = torch.empty((self.d, nv), dtype=dt, device=dev)
         c.ecospa_compact(self.wq, idx_qk, 0, h, dh, u, kpu, out=self.wqkv_c[:nq])
         c.ecospa_compact(self.wk, idx_qk, 0, h, dh, u, kpu, out=self.wqkv_c[nq:2 * nq])
         c.ecospa_compact(self.wv, idx_vo, 0, h, dh, 1, self.kp_vo, out=self.wqkv_c[2 * nq:])
-        self.bqkv_c = None
         if self.bq is not None:
-            self.bqkv_c = torch.empty((2 * nq + nv,), dtype=dt, device=dev)
             c.ecospa_compact(self.bq, idx_qk, 1, h, dh, u, kpu, out=self.bqkv_c[:nq])
             c.ecospa_compact(self.bk, idx_qk, 1, h, dh, u, kpu, out=self.bqkv_c[nq:2 * nq])
             c.ecospa_compact(self.bv, idx_vo, 1, h, dh, 1, self.kp_vo, out=self.bqkv_c[2 * nq:])
-        self.wo_c = c.ecospa_compact(self.wo, idx_vo, 1, h, dh, 1, self.kp_vo)
+        c.ecospa_compact(self.wo, idx_vo, 1, h, dh, 1, self.kp_vo, out=self.wo_c)
+        if self.rope and getattr(self, "cos", None) is not None:     # kept blocks changed: new frequencies
+            cos, sin = c.ecospa_rope_table(idx_qk, h, self._L, self.k_qk_units, self.kp_qk // 2, dh, self.rope_base)
+            self.cos.copy_(cos)
+            self.sin.copy_(sin)
         return self
 
     def alloc(self, Bsz: int, L: int):
@@ -131,6 +135,7 @@ class AttnBlock:
         T, dt, dev = Bsz * L, self.wq.dtype, self.wq.device
         nqkv, nv = self.wqkv_c.shape[0], h * self.kp_vo
         self.cos = self.sin = None
+        self._L = L
         if self.rope:
             self.cos, self.sin = c.ecospa_rope_table(self.idx_qk, h, L, self.k_qk_units, self.kp_qk // 2, self.d_h,
                                                      self.rope_base)
