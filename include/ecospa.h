@@ -195,6 +195,21 @@ int ecospa_coupled_fwd(ecospa_ctx* ctx, const ecospa_block_desc* desc /*host*/, 
 int ecospa_coupled_bwd(ecospa_ctx* ctx, const ecospa_block_desc* desc /*host*/, const void* x, const void* dy,
                        const ecospa_saved* saved /*host*/, void* dx, const ecospa_grads* grads /*host*/);
 
+/* ------------------------------------------------------------------------------------------
+ * The dense contraction kernel behind steps 4-5, exposed for tests and tuning:
+ *   C[m, n] = sum_k A(m, k) * B(n, k) (+ bias[n]),   m < M, n < N, k < K,   fp32 accumulation,
+ *   A(m, k) = A[m*lda + k] (trans_a = 0) or A[k*lda + m] (trans_a = 1); B(n, k) likewise with ldb.
+ * So x W^T is (0, 0), dY W is (0, 1) and dY^T X is (1, 1).  bias may be NULL.
+ * tile: 0 = library's choice, 1 = 128x128 workgroup tiles, 2 = 256x256 (bf16 only).
+ * splits: 0 = library's choice, otherwise the number of K splits (partials come from the
+ * workspace and are added in a fixed order).
+ * bf16 needs 16-byte aligned pointers, N % 8 == 0, leading dimensions % 8 == 0 and the
+ * contiguous extent of each operand % 8 == 0 (-> ERR_ALIGN otherwise).
+ * ------------------------------------------------------------------------------------------ */
+int ecospa_contract(ecospa_ctx* ctx, int dtype, int M, int N, int K, const void* A, long long lda, int trans_a,
+                    const void* B, long long ldb, int trans_b, void* C, long long ldc, const void* bias, int tile,
+                    int splits);
+
 #ifdef __cplusplus
 }
 #endif

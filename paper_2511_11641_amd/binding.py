@@ -25,7 +25,7 @@ EXPORTS = (
     "ecospa_create", "ecospa_destroy", "ecospa_set_workspace", "ecospa_status_string", "ecospa_last_error",
     "ecospa_score_workspace_bytes", "ecospa_coupled_score", "ecospa_select_topk", "ecospa_compact",
     "ecospa_scatter", "ecospa_rope_table", "ecospa_block_workspace_bytes", "ecospa_coupled_fwd",
-    "ecospa_coupled_bwd", "ecospa_profile_gemm", "ecospa_profile_gemm_read",
+    "ecospa_coupled_bwd", "ecospa_profile_gemm", "ecospa_profile_gemm_read", "ecospa_contract",
 )
 
 
@@ -107,6 +107,8 @@ def load() -> C.CDLL:
     lib.ecospa_profile_gemm.restype = ci
     lib.ecospa_profile_gemm_read.argtypes = [vp, C.POINTER(ci), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.ecospa_profile_gemm_read.restype = ci
+    lib.ecospa_contract.argtypes = [vp, ci, ci, ci, ci, vp, ll, ci, vp, ll, ci, vp, ll, vp, ci, ci]
+    lib.ecospa_contract.restype = ci
     _lib = lib
     return lib
 
@@ -172,6 +174,21 @@ class Context:
         self._check(self.lib.ecospa_profile_gemm_read(self.h, C.byref(n), C.byref(ms), C.byref(fl)),
                     "ecospa_profile_gemm_read")
         return n.value, ms.value, fl.value
+
+    def ecospa_contract(self, A: torch.Tensor, trans_a: bool, Bm: torch.Tensor, trans_b: bool,
+                        bias: Optional[torch.Tensor] = None, tile: int = 0, splits: int = 0,
+                        out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """C[m,n] = sum_k A(m,k) B(n,k) (+ bias[n]); a transposed operand is stored [K, M] / [K, N]."""
+        K, M = (A.shape if trans_a else A.shape[::-1])
+        K2, N = (Bm.shape if trans_b else Bm.shape[::-1])
+        assert K == K2
+        if out is None:
+            out = torch.empty((M, N), dtype=A.dtype, device=A.device)
+        self.reserve(64 * M * N * 4 if splits == 0 else splits * M * N * 4)
+        self._check(self.lib.ecospa_contract(self.h, dtype_code(A.dtype), M, N, K, A.data_ptr(), A.stride(0),
+                                             int(trans_a), Bm.data_ptr(), Bm.stride(0), int(trans_b), out.data_ptr(),
+                                             out.stride(0), _ptr(bias), tile, splits), "ecospa_contract")
+        return out
 
     # ---- step 1 ------------------------------------------------------------------------------
     @staticmethod

@@ -198,3 +198,23 @@ extern "C" int ecospa_coupled_bwd(ecospa_ctx* ctx, const ecospa_block_desc* desc
   if (desc->block == ECOSPA_BLOCK_FFN) return ffn_backward(ctx, *desc, w, x, dy, *saved, dx, *grads);
   return attn_backward(ctx, *desc, w, x, dy, *saved, dx, *grads);
 }
+
+// ---------------------------------------------------------------------------------------------
+extern "C" int ecospa_contract(ecospa_ctx* ctx, int dtype, int M, int N, int K, const void* A, long long lda,
+                               int trans_a, const void* B, long long ldb, int trans_b, void* C, long long ldc,
+                               const void* bias, int tile, int splits) {
+  if (!ctx || !A || !B || !C) return ECOSPA_ERR_NULL;
+  if (!dtype_ok(dtype)) return ECOSPA_ERR_DTYPE;
+  if (M < 1 || N < 1 || K < 1 || tile < 0 || tile > 3 || splits < 0 || splits > 64) return ECOSPA_ERR_SHAPE;
+  if (lda < (trans_a ? M : K) || ldb < (trans_b ? N : K) || ldc < N) return ECOSPA_ERR_SHAPE;
+  GemmDesc g = gemm_desc(dtype, M, N, K, A, lda, trans_a ? 1 : 0, B, ldb, trans_b ? 1 : 0);
+  g.tile = tile;
+  g.splits = splits == 0 ? ecospa_gemm_splits(M, N, K) : splits;
+  g.epi.kind = EPI_STORE; g.epi.c = C; g.epi.ldc = ldc; g.epi.bias = bias;
+  if (g.splits > 1) {
+    const size_t need = static_cast<size_t>(g.splits) * M * N * 4;
+    if (!ctx->ws || ctx->ws_bytes < need) return ECOSPA_ERR_WORKSPACE;
+    g.partial = static_cast<float*>(ctx->ws);
+  }
+  return ecospa_gemm(ctx, g);
+}

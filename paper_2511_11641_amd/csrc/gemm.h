@@ -36,6 +36,7 @@ struct GemmDesc {
   const void* B;
   long long ldb;
   int trans_b;
+  int tile;          // 0 = choose, 1 = 128x128 workgroup tiles, 2 = 256x256
   int splits;        // > 1: split K, fp32 partials in `partial`, reduced in a fixed order
   float* partial;    // [splits][M][N] when splits > 1
   GemmEpi epi;

@@ -51,11 +51,12 @@ __device__ __forceinline__ void unpack8(const uint4& u, float (&f)[8]) {
   }
 }
 __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
-  uint32_t w[4];
+  typedef float floatx8 __attribute__((ext_vector_type(8)));
+  floatx8 v;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-    w[i] = static_cast<uint32_t>(f32_to_bf16(f[2 * i])) | (static_cast<uint32_t>(f32_to_bf16(f[2 * i + 1])) << 16);
-  return make_uint4(w[0], w[1], w[2], w[3]);
+  for (int i = 0; i < 8; ++i) v[i] = f[i];
+  const bf16x8_t b = __builtin_convertvector(v, bf16x8_t);   // round to nearest even (v_cvt_pk_bf16_f32)
+  return __builtin_bit_cast(uint4, b);
 }
 __device__ __forceinline__ void epi_apply_vec8(const GemmEpi& e, int m, int n, float (&v)[8]) {
   bf16_t* c = static_cast<bf16_t*>(e.c) + static_cast<long long>(m) * e.ldc + n;
@@ -96,164 +97,200 @@ __device__ __forceinline__ void epi_apply_vec8(const GemmEpi& e, int m, int n, f
 }
 
 // ---------------------------------------------------------------------------------------------
-// bf16 MFMA kernel
+// bf16 MFMA kernel, parametrised by the workgroup tile BM x BN and the WGM x WGN grid of wavefronts
 // ---------------------------------------------------------------------------------------------
-#define GB_M 128
-#define GB_N 128
 #define GB_K 64
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 // 16-byte chunk swizzle of a 64-element (128-byte) LDS row
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
-// K-contiguous operand: thread moves 4 chunks of 8 elements (row = c / 8, k-chunk = c % 8)
+// K-contiguous operand: the tile is ROWS x 8 chunks of 8 elements; chunk c -> row c / 8, k-chunk c % 8
+template <int ROWS, int THREADS>
 __device__ __forceinline__ void gload_kc(const bf16_t* __restrict__ base, long long ld, int row0, int R, int k0,
-                                         int k_end, uint4 (&reg)[4]) {
+                                         int k_end, u32x4 (&reg)[ROWS * 8 / THREADS]) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = threadIdx.x + i * 256;
+  for (int i = 0; i < ROWS * 8 / THREADS; ++i) {
+    const int c = threadIdx.x + i * THREADS;
     const int gr = row0 + (c >> 3), gk = k0 + (c & 7) * 8;
-    reg[i] = (gr < R && gk < k_end) ? *reinterpret_cast<const uint4*>(base + static_cast<long long>(gr) * ld + gk)
-                                    : make_uint4(0, 0, 0, 0);
+    reg[i] = (gr < R && gk < k_end) ? *reinterpret_cast<const u32x4*>(base + static_cast<long long>(gr) * ld + gk)
+                                    : u32x4{0u, 0u, 0u, 0u};
   }
 }
-__device__ __forceinline__ void sstore_kc(bf16_t* lds, const uint4 (&reg)[4]) {
+template <int ROWS, int THREADS>
+__device__ __forceinline__ void sstore_kc(bf16_t* lds, const u32x4 (&reg)[ROWS * 8 / THREADS]) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = threadIdx.x + i * 256;
+  for (int i = 0; i < ROWS * 8 / THREADS; ++i) {
+    const int c = threadIdx.x + i * THREADS;
     const int row = c >> 3, kc = c & 7;
-    *reinterpret_cast<uint4*>(lds + row * GB_K + ((kc ^ swz(row)) << 3)) = reg[i];
+    *reinterpret_cast<u32x4*>(lds + row * GB_K + ((kc ^ swz(row)) << 3)) = reg[i];
   }
 }
-// K-slow operand (storage [K][R]): thread owns a 4(k) x 8(r) block, transposed in registers
+// K-slow operand (storage [K][R]): 4(k) x 8(r) blocks, transposed in registers on the way to LDS
+template <int ROWS, int THREADS>
 __device__ __forceinline__ void gload_tr(const bf16_t* __restrict__ base, long long ld, int row0, int R, int k0,
-                                         int k_end, uint4 (&reg)[4]) {
-  const int rblk = threadIdx.x & 15, kblk = threadIdx.x >> 4;
-  const int gr = row0 + rblk * 8;
+                                         int k_end, u32x4 (&reg)[ROWS * 8 / THREADS]) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int gk = k0 + kblk * 4 + i;
-    reg[i] = (gr < R && gk < k_end) ? *reinterpret_cast<const uint4*>(base + static_cast<long long>(gk) * ld + gr)
-                                    : make_uint4(0, 0, 0, 0);
+  for (int b = 0; b < 2 * ROWS / THREADS; ++b) {
+    const int sb = threadIdx.x + b * THREADS;
+    const int rblk = sb % (ROWS / 8), kblk = sb / (ROWS / 8);
+    const int gr = row0 + rblk * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int gk = k0 + kblk * 4 + i;
+      reg[b * 4 + i] = (gr < R && gk < k_end)
+                           ? *reinterpret_cast<const u32x4*>(base + static_cast<long long>(gk) * ld + gr)
+                           : u32x4{0u, 0u, 0u, 0u};
+    }
   }
 }
-__device__ __forceinline__ uint32_t half16(const uint4& v, int j) {
-  const uint32_t w = (j >> 1) == 0 ? v.x : (j >> 1) == 1 ? v.y : (j >> 1) == 2 ? v.z : v.w;
-  return (j & 1) ? (w >> 16) : (w & 0xffffu);
-}
-__device__ __forceinline__ void sstore_tr(bf16_t* lds, const uint4 (&reg)[4]) {
-  const int rblk = threadIdx.x & 15, kblk = threadIdx.x >> 4;
-  const int kc = kblk >> 1, half = kblk & 1;
+template <int ROWS, int THREADS>
+__device__ __forceinline__ void sstore_tr(bf16_t* lds, const u32x4 (&reg)[ROWS * 8 / THREADS]) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int r = rblk * 8 + j;
-    uint2 v;
-    v.x = half16(reg[0], j) | (half16(reg[1], j) << 16);
-    v.y = half16(reg[2], j) | (half16(reg[3], j) << 16);
-    *reinterpret_cast<uint2*>(lds + r * GB_K + ((kc ^ swz(r)) << 3) + half * 4) = v;
+  for (int b = 0; b < 2 * ROWS / THREADS; ++b) {
+    const int sb = threadIdx.x + b * THREADS;
+    const int rblk = sb % (ROWS / 8), kblk = sb / (ROWS / 8);
+    const int kc = kblk >> 1, half = kblk & 1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int r = rblk * 8 + j;
+      uint32_t e[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) e[i] = (j & 1) ? (reg[b * 4 + i][j >> 1] >> 16) : (reg[b * 4 + i][j >> 1] & 0xffffu);
+      u32x2 v;
+      v.x = e[0] | (e[1] << 16);
+      v.y = e[2] | (e[3] << 16);
+      *reinterpret_cast<u32x2*>(lds + r * GB_K + ((kc ^ swz(r)) << 3) + half * 4) = v;
+    }
   }
 }
 
-template <bool TA, bool TB>
-__global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][GB_M * GB_K];
+// LDS traffic of one wavefront with itself (its private staging area): order only, no s_barrier
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int BM, int BN, int WGM, int WGN, bool TA, bool TB>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
+  constexpr int THREADS = 64 * WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN, FM = WTM / 32, FN = WTN / 32;
+  constexpr int STAGE = (BM + BN) * GB_K;            // elements of one LDS buffer (A tile then B tile)
+  static_assert(WTN == 64 || WTN == 128, "epilogue handles 64 or 128 columns per wavefront");
+  static_assert(2 * STAGE * 2 >= WGM * WGN * 32 * WTN * 4, "epilogue staging must fit in the operand buffers");
+  extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
 
   // XCD-aware tile order: workgroup ids go round-robin over the 8 XCDs, so give each XCD a
   // contiguous range of tiles (neighbouring tiles share operand rows in that XCD's L2).
   int id = blockIdx.x;
   const int nb = gridDim.x;
   if ((nb & 7) == 0) id = (id & 7) * (nb >> 3) + (id >> 3);
-  const int m0 = (id / tiles_n) * GB_M, n0 = (id % tiles_n) * GB_N;
+  const int m0 = (id / tiles_n) * BM, n0 = (id % tiles_n) * BN;
   const int k_begin = blockIdx.z * k_chunk;
   const int k_end = min(d.K, k_begin + k_chunk);
   const int nk = (k_end - k_begin + GB_K - 1) / GB_K;
 
   const bf16_t* A = static_cast<const bf16_t*>(d.A);
   const bf16_t* B = static_cast<const bf16_t*>(d.B);
-  uint4 ra[4], rb[4];
-  floatx16 acc[2][2];
+  u32x4 ra[BM * 8 / THREADS], rb[BN * 8 / THREADS];
+  floatx16 acc[FM][FN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  auto gload = [&](int k0) {
-    if (TA) gload_tr(A, d.lda, m0, d.M, k0, k_end, ra); else gload_kc(A, d.lda, m0, d.M, k0, k_end, ra);
-    if (TB) gload_tr(B, d.ldb, n0, d.N, k0, k_end, rb); else gload_kc(B, d.ldb, n0, d.N, k0, k_end, rb);
-  };
-  auto sstore = [&](int buf) {
-    if (TA) sstore_tr(lds[buf][0], ra); else sstore_kc(lds[buf][0], ra);
-    if (TB) sstore_tr(lds[buf][1], rb); else sstore_kc(lds[buf][1], rb);
-  };
+#define GEMM_GLOAD(k0)                                                                   \
+  do {                                                                                   \
+    if (TA) gload_tr<BM, THREADS>(A, d.lda, m0, d.M, (k0), k_end, ra);                   \
+    else gload_kc<BM, THREADS>(A, d.lda, m0, d.M, (k0), k_end, ra);                      \
+    if (TB) gload_tr<BN, THREADS>(B, d.ldb, n0, d.N, (k0), k_end, rb);                   \
+    else gload_kc<BN, THREADS>(B, d.ldb, n0, d.N, (k0), k_end, rb);                      \
+  } while (0)
+#define GEMM_SSTORE(buf)                                                                 \
+  do {                                                                                   \
+    bf16_t* as_ = lds + (buf) * STAGE;                                                   \
+    if (TA) sstore_tr<BM, THREADS>(as_, ra); else sstore_kc<BM, THREADS>(as_, ra);       \
+    if (TB) sstore_tr<BN, THREADS>(as_ + BM * GB_K, rb);                                 \
+    else sstore_kc<BN, THREADS>(as_ + BM * GB_K, rb);                                    \
+  } while (0)
 
   if (nk > 0) {
-    gload(k_begin);
-    sstore(0);
+    GEMM_GLOAD(k_begin);
+    GEMM_SSTORE(0);
   }
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < nk) gload(k_begin + (kt + 1) * GB_K);
-    const bf16_t* As = lds[cur][0];
-    const bf16_t* Bs = lds[cur][1];
+    if (kt + 1 < nk) GEMM_GLOAD(k_begin + (kt + 1) * GB_K);
+    const bf16_t* As = lds + cur * STAGE;
+    const bf16_t* Bs = As + BM * GB_K;
 #pragma unroll
     for (int s = 0; s < GB_K / 16; ++s) {
-      bf16x8_t a[2], b[2];
+      bf16x8_t a[FM], b[FN];
       const int kc = s * 2 + (lane >> 5);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int row = wm * 64 + i * 32 + (lane & 31);
+      for (int i = 0; i < FM; ++i) {
+        const int row = wm * WTM + i * 32 + (lane & 31);
         a[i] = *reinterpret_cast<const bf16x8_t*>(As + row * GB_K + ((kc ^ swz(row)) << 3));
       }
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int row = wn * 64 + j * 32 + (lane & 31);
+      for (int j = 0; j < FN; ++j) {
+        const int row = wn * WTN + j * 32 + (lane & 31);
         b[j] = *reinterpret_cast<const bf16x8_t*>(Bs + row * GB_K + ((kc ^ swz(row)) << 3));
       }
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) sstore(cur ^ 1);
+    if (kt + 1 < nk) GEMM_SSTORE(cur ^ 1);
     __syncthreads();
   }
+#undef GEMM_GLOAD
+#undef GEMM_SSTORE
 
-  // Epilogue through LDS: each wavefront parks its 64x64 fp32 tile in its own 16 KB quarter of
-  // the (now idle) operand buffers, then every lane handles 8 consecutive columns of a row, so
-  // global traffic is 16-byte vectors.  Accumulator layout of a 32x32 MFMA tile:
+  // Epilogue through LDS: each wavefront parks 32 rows x WTN columns of fp32 at a time in its own
+  // slice of the (now idle) operand buffers, then every lane handles 8 consecutive columns of a
+  // row, so global traffic is 16-byte vectors.  Accumulator layout of a 32x32 MFMA tile:
   // column = lane % 32, row = 8*(r/4) + 4*(lane/32) + r%4.
-  float* cs = reinterpret_cast<float*>(&lds[0][0][0]) + wave * (64 * 64);
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        cs[(i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * 64 + j * 32 + (lane & 31)] = acc[i][j][r];
-  __syncthreads();
+  float* cs = reinterpret_cast<float*>(lds) + wave * (32 * WTN);
   const bool split = d.splits > 1;
   float* part = split ? d.partial + static_cast<long long>(blockIdx.z) * d.M * d.N : nullptr;
-  const int n = n0 + wn * 64 + (lane & 7) * 8;
+  constexpr int LPR = WTN / 8;          // lanes per row
+  constexpr int RPI = 64 / LPR;         // rows per pass
+  const int n = n0 + wn * WTN + (lane % LPR) * 8;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        cs[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * WTN + j * 32 + (lane & 31)] = acc[i][j][r];
+    wave_lds_sync();
 #pragma unroll 1
-  for (int it = 0; it < 8; ++it) {
-    const int row = it * 8 + (lane >> 3);
-    const int m = m0 + wm * 64 + row;
-    if (m >= d.M || n >= d.N) continue;
-    float v[8];
-    const float4 lo = *reinterpret_cast<const float4*>(cs + row * 64 + (lane & 7) * 8);
-    const float4 hi = *reinterpret_cast<const float4*>(cs + row * 64 + (lane & 7) * 8 + 4);
-    v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
-    if (split) {
-      float* p = part + static_cast<long long>(m) * d.N + n;
-      *reinterpret_cast<float4*>(p) = lo;
-      *reinterpret_cast<float4*>(p + 4) = hi;
-    } else {
-      epi_apply_vec8(d.epi, m, n, v);
+    for (int it = 0; it < 32 / RPI; ++it) {
+      const int row = it * RPI + lane / LPR;
+      const int m = m0 + wm * WTM + i * 32 + row;
+      if (m >= d.M || n >= d.N) continue;
+      float v[8];
+      const float4 lo = *reinterpret_cast<const float4*>(cs + row * WTN + (lane % LPR) * 8);
+      const float4 hi = *reinterpret_cast<const float4*>(cs + row * WTN + (lane % LPR) * 8 + 4);
+      v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+      if (split) {
+        float* p = part + static_cast<long long>(m) * d.N + n;
+        *reinterpret_cast<float4*>(p) = lo;
+        *reinterpret_cast<float4*>(p + 4) = hi;
+      } else {
+        epi_apply_vec8(d.epi, m, n, v);
+      }
     }
+    wave_lds_sync();
   }
 }
 
@@ -338,10 +375,60 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const GemmDesc 
   for (int z = 0; z < d.splits; ++z) s += d.partial[z * tot + e];
   epi_apply<T>(d.epi, static_cast<int>(e / d.N), static_cast<int>(e % d.N), s);
 }
+// bf16: 8 consecutive columns per thread (N is a multiple of 8)
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_vec8_kernel(const GemmDesc d) {
+  const long long tot = static_cast<long long>(d.M) * d.N;
+  const long long e = (static_cast<long long>(blockIdx.x) * 256 + threadIdx.x) * 8;
+  if (e >= tot) return;
+  float v[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = 0.f;
+  for (int z = 0; z < d.splits; ++z) {
+    const float4 lo = *reinterpret_cast<const float4*>(d.partial + z * tot + e);
+    const float4 hi = *reinterpret_cast<const float4*>(d.partial + z * tot + e + 4);
+    v[0] += lo.x; v[1] += lo.y; v[2] += lo.z; v[3] += lo.w; v[4] += hi.x; v[5] += hi.y; v[6] += hi.z; v[7] += hi.w;
+  }
+  epi_apply_vec8(d.epi, static_cast<int>(e / d.N), static_cast<int>(e % d.N), v);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Tile choice: 256x256 tiles (8 wavefronts, 128 KB LDS, one workgroup per CU) need about twice
+// fewer operand bytes per flop than 128x128 tiles (4 wavefronts, two workgroups per CU), but only
+// pay off when there are enough of them to occupy the 256 CUs.
+static bool gemm_prefers_big_tile(int M, int N, int splits) {
+  const long long big = static_cast<long long>((M + 255) / 256) * ((N + 255) / 256) * splits;
+  return big >= 192;
+}
+
+template <int BM, int BN, int WGM, int WGN>
+static hipError_t launch_tile(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
+  const int tm = (d.M + BM - 1) / BM, tn = (d.N + BN - 1) / BN;
+  const int splits = d.splits > 1 ? d.splits : 1;
+  const dim3 grid(tm * tn, 1, splits), block(64 * WGM * WGN);
+  const size_t lds_bytes = 2ull * (BM + BN) * GB_K * sizeof(bf16_t);
+#define LAUNCH_TT(TA, TB)                                                                                      \
+  do {                                                                                                         \
+    auto kern = gemm_bf16_mfma_kernel<BM, BN, WGM, WGN, TA, TB>;                                               \
+    static bool attr_set = false;                                                                              \
+    if (!attr_set && lds_bytes > 64 * 1024) {                                                                  \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)); \
+      if (e != hipSuccess) return e;                                                                           \
+      attr_set = true;                                                                                         \
+    }                                                                                                          \
+    hipLaunchKernelGGL(kern, grid, block, lds_bytes, ctx->stream, d, tn, k_chunk);                             \
+  } while (0)
+  if (!d.trans_a && !d.trans_b) LAUNCH_TT(false, false);
+  else if (!d.trans_a && d.trans_b) LAUNCH_TT(false, true);
+  else if (d.trans_a && d.trans_b) LAUNCH_TT(true, true);
+  else LAUNCH_TT(true, false);
+#undef LAUNCH_TT
+  return hipGetLastError();
+}
 
 // ---------------------------------------------------------------------------------------------
 int ecospa_gemm_splits(int M, int N, int K) {
-  const long long tiles = static_cast<long long>((M + GB_M - 1) / GB_M) * ((N + GB_N - 1) / GB_N);
+  const long long tiles = static_cast<long long>((M + 127) / 128) * ((N + 127) / 128);
   int s = 1;
   // fill ~2 waves of the 256 CUs while every split keeps at least 512 of K
   while (tiles * s < 512 && K / (s * 2) >= 512 && s < 32) s *= 2;
@@ -366,20 +453,15 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
       return ECOSPA_ERR_ALIGN;
     if (d.epi.kind == EPI_DSWIGLU && d.epi.kp % 8) return ECOSPA_ERR_ALIGN;
     if (d.splits > 1 && !aligned16(d.partial)) return ECOSPA_ERR_ALIGN;
-    const int tm = (d.M + GB_M - 1) / GB_M, tn = (d.N + GB_N - 1) / GB_N;
     int k_chunk = (d.K + splits - 1) / splits;
     k_chunk = (k_chunk + GB_K - 1) / GB_K * GB_K;
-    dim3 grid(tm * tn, 1, splits);
+    const bool big = d.tile == 2 || (d.tile == 0 && gemm_prefers_big_tile(d.M, d.N, splits));
     const bool prof = ctx->prof_on && ctx->prof_n < ctx->prof_cap;
     if (prof) (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n], ctx->stream);
-    if (!d.trans_a && !d.trans_b)
-      hipLaunchKernelGGL((gemm_bf16_mfma_kernel<false, false>), grid, dim3(256), 0, ctx->stream, d, tn, k_chunk);
-    else if (!d.trans_a && d.trans_b)
-      hipLaunchKernelGGL((gemm_bf16_mfma_kernel<false, true>), grid, dim3(256), 0, ctx->stream, d, tn, k_chunk);
-    else if (d.trans_a && d.trans_b)
-      hipLaunchKernelGGL((gemm_bf16_mfma_kernel<true, true>), grid, dim3(256), 0, ctx->stream, d, tn, k_chunk);
-    else
-      hipLaunchKernelGGL((gemm_bf16_mfma_kernel<true, false>), grid, dim3(256), 0, ctx->stream, d, tn, k_chunk);
+    hipError_t le = d.tile == 3 ? launch_tile<256, 256, 2, 2>(ctx, d, k_chunk)
+                    : big       ? launch_tile<256, 256, 2, 4>(ctx, d, k_chunk)
+                                : launch_tile<128, 128, 2, 2>(ctx, d, k_chunk);
+    if (le != hipSuccess) return hip_fail(ctx, le, "gemm launch");
     if (prof) {
       (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n + 1], ctx->stream);
       ctx->prof_flop[ctx->prof_n++] = 2.0 * d.M * d.N * d.K;
@@ -398,7 +480,8 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
     const long long tot = static_cast<long long>(d.M) * d.N;
     const unsigned grid = static_cast<unsigned>((tot + 255) / 256);
     if (d.dtype == ECOSPA_BF16)
-      hipLaunchKernelGGL((gemm_splitk_reduce_kernel<bf16_t>), dim3(grid), dim3(256), 0, ctx->stream, d);
+      hipLaunchKernelGGL(gemm_splitk_reduce_vec8_kernel, dim3(static_cast<unsigned>((tot / 8 + 255) / 256)), dim3(256), 0,
+                         ctx->stream, d);
     else
       hipLaunchKernelGGL((gemm_splitk_reduce_kernel<float>), dim3(grid), dim3(256), 0, ctx->stream, d);
     ECOSPA_CHECK_LAUNCH(ctx, "gemm_splitk_reduce_kernel");
@@ -407,26 +490,56 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// column sums (bias gradients): 16-lane x 16-row-slot tiles, then a fixed-order second stage
+// column sums (bias gradients): 8-lane x 32-row-slot tiles with 16-byte loads, then a fixed-order
+// second stage over the row chunks
 // ---------------------------------------------------------------------------------------------
-#define CS_ROWS 256   // rows per first-stage block
+#define CS_ROWS 512   // rows per first-stage block
 
 int ecospa_colsum_chunks(int M) { return (M + CS_ROWS - 1) / CS_ROWS; }
 
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ X, long long ldx, int M, int N,
                                                              float* __restrict__ partial) {
-  __shared__ float lds[16][64 + 1];
-  const int slot = threadIdx.x >> 6, lane = threadIdx.x & 63;   // 4 row slots x 64 columns
-  const int col = blockIdx.x * 64 + lane;
+  constexpr int V = 16 / sizeof(T);          // columns per lane
+  __shared__ float lds[32][8 * V + 1];
+  const int slot = threadIdx.x >> 3, l8 = threadIdx.x & 7;   // 32 row slots x 8 lanes
+  const int col0 = blockIdx.x * (8 * V) + l8 * V;
   const int r0 = blockIdx.y * CS_ROWS, r1 = min(M, r0 + CS_ROWS);
-  float acc = 0.f;
-  if (col < N)
-    for (int r = r0 + slot; r < r1; r += 4) acc += load_f32<T>(X + static_cast<long long>(r) * ldx + col);
-  lds[slot][lane] = acc;
+  float acc[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) acc[i] = 0.f;
+  const bool vec_ok = (ldx % V == 0) && ((reinterpret_cast<uintptr_t>(X) & 15u) == 0) && col0 + V <= N;
+  if (vec_ok) {
+    for (int r = r0 + slot; r < r1; r += 32) {
+      const uint4 u = *reinterpret_cast<const uint4*>(X + static_cast<long long>(r) * ldx + col0);
+      if (sizeof(T) == 2) {
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc[(2 * i) % V] += __uint_as_float(w[i] << 16);
+          acc[(2 * i + 1) % V] += __uint_as_float(w[i] & 0xffff0000u);
+        }
+      } else {
+        acc[0] += __uint_as_float(u.x); acc[1 % V] += __uint_as_float(u.y);
+        acc[2 % V] += __uint_as_float(u.z); acc[3 % V] += __uint_as_float(u.w);
+      }
+    }
+  } else {
+    for (int r = r0 + slot; r < r1; r += 32)
+#pragma unroll
+      for (int i = 0; i < V; ++i)
+        if (col0 + i < N) acc[i] += load_f32<T>(X + static_cast<long long>(r) * ldx + col0 + i);
+  }
+#pragma unroll
+  for (int i = 0; i < V; ++i) lds[slot][l8 * V + i] = acc[i];
   __syncthreads();
-  if (threadIdx.x < 64 && col < N)
-    partial[static_cast<long long>(blockIdx.y) * N + col] = (lds[0][lane] + lds[1][lane]) + (lds[2][lane] + lds[3][lane]);
+  if (threadIdx.x < 8 * V) {
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) s += lds[k][threadIdx.x];
+    const int col = blockIdx.x * (8 * V) + threadIdx.x;
+    if (col < N) partial[static_cast<long long>(blockIdx.y) * N + col] = s;
+  }
 }
 
 template <typename T>
@@ -442,7 +555,8 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
 int ecospa_colsum(ecospa_ctx* ctx, int dtype, const void* X, long long ldx, int M, int N, float* partial, void* out) {
   if (!X || !partial || !out) return ECOSPA_ERR_NULL;
   const int chunks = ecospa_colsum_chunks(M);
-  dim3 g1((N + 63) / 64, chunks), g2((N + 255) / 256);
+  const int strip = dtype == ECOSPA_BF16 ? 64 : 32;
+  dim3 g1((N + strip - 1) / strip, chunks), g2((N + 255) / 256);
   if (dtype == ECOSPA_BF16) {
     hipLaunchKernelGGL((colsum_partial_kernel<bf16_t>), g1, dim3(256), 0, ctx->stream, static_cast<const bf16_t*>(X), ldx,
                        M, N, partial);

@@ -1,0 +1,72 @@
+"""GPU parity of the dense contraction kernel (both workgroup tile sizes, all operand layouts,
+ragged extents, split K) against a plain fp64 matrix product."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_11641_amd import binding as B
+from paper_2511_11641_amd import synth
+from util import assert_close, dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    return B.Context("cuda:0")
+
+
+def _operands(seed, M, N, K, ta, tb, dtype):
+    a = synth.round_to(synth.normal(seed, 300, (K, M) if ta else (M, K)), dtype)
+    b = synth.round_to(synth.normal(seed, 301, (K, N) if tb else (N, K)), dtype)
+    bias = synth.round_to(synth.normal(seed, 302, (N,)), dtype)
+    am = a.T if ta else a
+    bm = b.T if tb else b
+    want = am.astype(np.float64) @ bm.astype(np.float64).T + bias.astype(np.float64)
+    return a, b, bias, want
+
+
+@pytest.mark.parametrize("tile", [1, 2])
+@pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, True), (True, False)])
+@pytest.mark.parametrize("M,N,K", [(300, 264, 136), (512, 512, 256), (1000, 520, 72), (64, 1032, 648)])
+def test_contract_bf16(ctx, M, N, K, ta, tb, tile):
+    if ta:
+        M = (M + 7) // 8 * 8
+    a, b, bias, want = _operands(41, M, N, K, ta, tb, "bf16")
+    got = ctx.ecospa_contract(dev(a, "bf16"), ta, dev(b, "bf16"), tb, dev(bias, "bf16"), tile=tile, splits=1)
+    assert_close(got, want, "bf16", f"tile {tile}")
+
+
+@pytest.mark.parametrize("tile", [1, 2])
+@pytest.mark.parametrize("splits", [2, 5])
+def test_contract_bf16_split_k(ctx, splits, tile):
+    a, b, bias, want = _operands(42, 264, 136, 1000, True, True, "bf16")
+    got = ctx.ecospa_contract(dev(a, "bf16"), True, dev(b, "bf16"), True, dev(bias, "bf16"), tile=tile, splits=splits)
+    assert_close(got, want, "bf16", "split k")
+    again = ctx.ecospa_contract(dev(a, "bf16"), True, dev(b, "bf16"), True, dev(bias, "bf16"), tile=tile, splits=splits)
+    assert torch.equal(got, again)
+
+
+@pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, True)])
+def test_contract_f32(ctx, ta, tb):
+    a, b, bias, want = _operands(43, 201, 77, 130, ta, tb, "f32")
+    got = ctx.ecospa_contract(dev(a), ta, dev(b), tb, dev(bias), splits=1)
+    assert_close(got, want, "f32", "fp32")
+    got = ctx.ecospa_contract(dev(a), ta, dev(b), tb, dev(bias), splits=3)
+    assert_close(got, want, "f32", "fp32 split")
+
+
+def test_contract_model_shapes_auto_tile(ctx):
+    """Projection and FFN shapes of the GPT-2-Medium layer at 50% keep, library's own tile choice."""
+    for (M, N, K, ta, tb) in [(2048, 1536, 1024, False, False), (2048, 1024, 2048, False, True), (1024, 2048, 2048, True, True)]:
+        a, b, bias, want = _operands(44, M, N, K, ta, tb, "bf16")
+        got = ctx.ecospa_contract(dev(a, "bf16"), ta, dev(b, "bf16"), tb, dev(bias, "bf16"))
+        assert_close(got, want, "bf16", f"{M}x{N}x{K}")
+
+
+def test_contract_alignment_errors(ctx):
+    a = torch.zeros((64, 72), dtype=torch.bfloat16, device="cuda")
+    b = torch.zeros((60, 72), dtype=torch.bfloat16, device="cuda")     # N = 60 is not a multiple of 8
+    with pytest.raises(B.EcospaError) as e:
+        ctx.ecospa_contract(a, False, b, False, splits=1)
+    assert e.value.code == B.ERR_ALIGN
