@@ -99,57 +99,98 @@ __device__ __forceinline__ void epi_apply_vec8(const GemmEpi& e, int m, int n, f
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA kernel, parametrised by the workgroup tile BM x BN and the WGM x WGN grid of wavefronts
 // ---------------------------------------------------------------------------------------------
-#define GB_K 64
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-// 16-byte chunk swizzle of a 64-element (128-byte) LDS row
-__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
+// LDS operand tiles are [rows][BK] bf16 with the 16-byte chunks of a row XOR-swizzled by the row
+// index, so that the 32 lanes that read one k-chunk of 32 consecutive rows spread over the banks.
+template <int BK>
+__device__ __forceinline__ int lds_off(int row, int chunk) {
+  constexpr int CPR = BK / 8;                       // chunks per row (8 for BK = 64, 4 for BK = 32)
+  const int f = BK == 64 ? (row ^ (row >> 3)) : ((row >> 1) ^ (row >> 3));
+  return row * BK + ((chunk ^ (f & (CPR - 1))) << 3);
+}
 
-// K-contiguous operand: the tile is ROWS x 8 chunks of 8 elements; chunk c -> row c / 8, k-chunk c % 8
-template <int ROWS, int THREADS>
+// Loads are unconditional (straight-line code that the scheduler can interleave with MFMAs): row
+// indices beyond the matrix are clamped - such rows only feed outputs that are never stored - and
+// only a K slab that crosses k_end (FULL = false) zero-fills its out-of-range chunks.
+// K-contiguous operand: the tile is ROWS x BK/8 chunks of 8 elements.
+template <int ROWS, int BK, int THREADS, bool FULL>
 __device__ __forceinline__ void gload_kc(const bf16_t* __restrict__ base, long long ld, int row0, int R, int k0,
-                                         int k_end, u32x4 (&reg)[ROWS * 8 / THREADS]) {
+                                         int k_end, u32x4 (&reg)[(ROWS * BK / 8 / THREADS < 4 ? 4 : ROWS * BK / 8 / THREADS)]) {
+  constexpr int CPR = BK / 8;
 #pragma unroll
-  for (int i = 0; i < ROWS * 8 / THREADS; ++i) {
+  for (int i = 0; i < ROWS * CPR / THREADS; ++i) {
     const int c = threadIdx.x + i * THREADS;
-    const int gr = row0 + (c >> 3), gk = k0 + (c & 7) * 8;
-    reg[i] = (gr < R && gk < k_end) ? *reinterpret_cast<const u32x4*>(base + static_cast<long long>(gr) * ld + gk)
-                                    : u32x4{0u, 0u, 0u, 0u};
-  }
-}
-template <int ROWS, int THREADS>
-__device__ __forceinline__ void sstore_kc(bf16_t* lds, const u32x4 (&reg)[ROWS * 8 / THREADS]) {
-#pragma unroll
-  for (int i = 0; i < ROWS * 8 / THREADS; ++i) {
-    const int c = threadIdx.x + i * THREADS;
-    const int row = c >> 3, kc = c & 7;
-    *reinterpret_cast<u32x4*>(lds + row * GB_K + ((kc ^ swz(row)) << 3)) = reg[i];
-  }
-}
-// K-slow operand (storage [K][R]): 4(k) x 8(r) blocks, transposed in registers on the way to LDS
-template <int ROWS, int THREADS>
-__device__ __forceinline__ void gload_tr(const bf16_t* __restrict__ base, long long ld, int row0, int R, int k0,
-                                         int k_end, u32x4 (&reg)[ROWS * 8 / THREADS]) {
-#pragma unroll
-  for (int b = 0; b < 2 * ROWS / THREADS; ++b) {
-    const int sb = threadIdx.x + b * THREADS;
-    const int rblk = sb % (ROWS / 8), kblk = sb / (ROWS / 8);
-    const int gr = row0 + rblk * 8;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int gk = k0 + kblk * 4 + i;
-      reg[b * 4 + i] = (gr < R && gk < k_end)
-                           ? *reinterpret_cast<const u32x4*>(base + static_cast<long long>(gk) * ld + gr)
-                           : u32x4{0u, 0u, 0u, 0u};
+    const int gr = min(row0 + c / CPR, R - 1), gk = k0 + (c % CPR) * 8;
+    if (FULL) {
+      reg[i] = *reinterpret_cast<const u32x4*>(base + static_cast<long long>(gr) * ld + gk);
+    } else {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(base + static_cast<long long>(gr) * ld + min(gk, k_end - 8));
+      reg[i] = gk < k_end ? v : u32x4{0u, 0u, 0u, 0u};
     }
   }
 }
-template <int ROWS, int THREADS>
-__device__ __forceinline__ void sstore_tr(bf16_t* lds, const u32x4 (&reg)[ROWS * 8 / THREADS]) {
+template <int ROWS, int BK, int THREADS>
+__device__ __forceinline__ void sstore_kc(bf16_t* lds, const u32x4 (&reg)[(ROWS * BK / 8 / THREADS < 4 ? 4 : ROWS * BK / 8 / THREADS)]) {
+  constexpr int CPR = BK / 8;
 #pragma unroll
-  for (int b = 0; b < 2 * ROWS / THREADS; ++b) {
+  for (int i = 0; i < ROWS * CPR / THREADS; ++i) {
+    const int c = threadIdx.x + i * THREADS;
+    *reinterpret_cast<u32x4*>(lds + lds_off<BK>(c / CPR, c % CPR)) = reg[i];
+  }
+}
+// K-contiguous operand, full K slab, BK = 64: global -> LDS without passing through registers.
+// One global_load_lds_dwordx4 of a wavefront fills 64 consecutive 16-byte chunks of LDS (lane i
+// writes chunk i of the 1 KB block the wave-uniform base points at) = 8 tile rows.  The swizzle is
+// applied on the global side: the lane that owns physical chunk pc of row r fetches the logical
+// k-chunk that lds_off() maps there.
+typedef __attribute__((address_space(3))) bf16_t lds_bf16_t;
+template <int ROWS, int THREADS>
+__device__ __forceinline__ void dload_kc(const bf16_t* __restrict__ base, long long ld, int row0, int R, int k0,
+                                         lds_bf16_t* tile) {
+  constexpr int PER = ROWS / 8 / (THREADS / 64);     // 8-row groups per wavefront
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane >> 3, pc = lane & 7;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int group = wave * PER + i;
+    const int row = group * 8 + r;
+    const int kc = pc ^ ((row ^ (row >> 3)) & 7);
+    const int gr = min(row0 + row, R - 1);
+    __builtin_amdgcn_global_load_lds(base + static_cast<long long>(gr) * ld + k0 + kc * 8, tile + group * 8 * 64, 16, 0, 0);
+  }
+}
+// K-slow operand (storage [K][R]): 4(k) x 8(r) blocks, transposed in registers on the way to LDS
+template <int ROWS, int BK, int THREADS, bool FULL>
+__device__ __forceinline__ void gload_tr(const bf16_t* __restrict__ base, long long ld, int row0, int R, int k0,
+                                         int k_end, u32x4 (&reg)[(ROWS * BK / 8 / THREADS < 4 ? 4 : ROWS * BK / 8 / THREADS)]) {
+  constexpr int NSUB = ROWS * BK / 32;            // 4 x 8 sub-blocks in the tile
+#pragma unroll
+  for (int b = 0; b < (NSUB + THREADS - 1) / THREADS; ++b) {
     const int sb = threadIdx.x + b * THREADS;
+    if (NSUB % THREADS != 0 && sb >= NSUB) break;
+    const int rblk = sb % (ROWS / 8), kblk = sb / (ROWS / 8);
+    const int gr = min(row0 + rblk * 8, R - 8);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int gk = k0 + kblk * 4 + i;
+      if (FULL) {
+        reg[b * 4 + i] = *reinterpret_cast<const u32x4*>(base + static_cast<long long>(gk) * ld + gr);
+      } else {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(base + static_cast<long long>(min(gk, k_end - 1)) * ld + gr);
+        reg[b * 4 + i] = gk < k_end ? v : u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+  }
+}
+template <int ROWS, int BK, int THREADS>
+__device__ __forceinline__ void sstore_tr(bf16_t* lds, const u32x4 (&reg)[(ROWS * BK / 8 / THREADS < 4 ? 4 : ROWS * BK / 8 / THREADS)]) {
+  constexpr int NSUB = ROWS * BK / 32;
+#pragma unroll
+  for (int b = 0; b < (NSUB + THREADS - 1) / THREADS; ++b) {
+    const int sb = threadIdx.x + b * THREADS;
+    if (NSUB % THREADS != 0 && sb >= NSUB) break;
     const int rblk = sb % (ROWS / 8), kblk = sb / (ROWS / 8);
     const int kc = kblk >> 1, half = kblk & 1;
 #pragma unroll
@@ -161,7 +202,7 @@ __device__ __forceinline__ void sstore_tr(bf16_t* lds, const u32x4 (&reg)[ROWS *
       u32x2 v;
       v.x = e[0] | (e[1] << 16);
       v.y = e[2] | (e[3] << 16);
-      *reinterpret_cast<u32x2*>(lds + r * GB_K + ((kc ^ swz(r)) << 3) + half * 4) = v;
+      *reinterpret_cast<u32x2*>(lds + lds_off<BK>(r, kc) + half * 4) = v;
     }
   }
 }
@@ -173,13 +214,18 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int BM, int BN, int WGM, int WGN, bool TA, bool TB>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
+// Workgroup tile BM x BN x BK, WGM x WGN wavefronts; WPE = wavefronts per SIMD the register
+// allocation is tuned for (occupancy hides the LDS and global latencies between MFMAs).
+template <int BM, int BN, int BK, int WGM, int WGN, int WPE, bool TA, bool TB>
+__global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
+void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   constexpr int THREADS = 64 * WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN, FM = WTM / 32, FN = WTN / 32;
-  constexpr int STAGE = (BM + BN) * GB_K;            // elements of one LDS buffer (A tile then B tile)
+  constexpr int STAGE = (BM + BN) * BK;            // elements of one LDS buffer (A tile then B tile)
+  constexpr int NA = BM * BK / 8 / THREADS < 4 ? 4 : BM * BK / 8 / THREADS;
+  constexpr int NB = BN * BK / 8 / THREADS < 4 ? 4 : BN * BK / 8 / THREADS;
   static_assert(WTN == 64 || WTN == 128, "epilogue handles 64 or 128 columns per wavefront");
-  static_assert(2 * STAGE * 2 >= WGM * WGN * 32 * WTN * 4, "epilogue staging must fit in the operand buffers");
+  static_assert((BM * BK / 8) % THREADS == 0 && (BN * BK / 8) % THREADS == 0, "loader shape");
   extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -192,11 +238,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_mfma_kernel(const Ge
   const int m0 = (id / tiles_n) * BM, n0 = (id % tiles_n) * BN;
   const int k_begin = blockIdx.z * k_chunk;
   const int k_end = min(d.K, k_begin + k_chunk);
-  const int nk = (k_end - k_begin + GB_K - 1) / GB_K;
+  const int nk = (k_end - k_begin + BK - 1) / BK;
 
   const bf16_t* A = static_cast<const bf16_t*>(d.A);
   const bf16_t* B = static_cast<const bf16_t*>(d.B);
-  u32x4 ra[BM * 8 / THREADS], rb[BN * 8 / THREADS];
+  u32x4 ra[NA], rb[NB];
   floatx16 acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
@@ -205,55 +251,68 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_mfma_kernel(const Ge
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-#define GEMM_GLOAD(k0)                                                                   \
-  do {                                                                                   \
-    if (TA) gload_tr<BM, THREADS>(A, d.lda, m0, d.M, (k0), k_end, ra);                   \
-    else gload_kc<BM, THREADS>(A, d.lda, m0, d.M, (k0), k_end, ra);                      \
-    if (TB) gload_tr<BN, THREADS>(B, d.ldb, n0, d.N, (k0), k_end, rb);                   \
-    else gload_kc<BN, THREADS>(B, d.ldb, n0, d.N, (k0), k_end, rb);                      \
+  // Operand staging for K slab k0 into LDS buffer `buf`.  K-contiguous operands whose slab lies
+  // fully inside [k_begin, k_end) go straight to LDS (BK = 64 only); K-slow operands and the ragged
+  // last slab travel through registers (FETCH now, STORE after the MFMAs of the current slab).
+  constexpr bool DIRECT_OK = BK == 64;
+  lds_bf16_t* lds3 = (lds_bf16_t*)lds;   // same array, LDS address space for the direct loads
+#define GEMM_FETCH(k0, buf)                                                                        \
+  do {                                                                                             \
+    const bool full_ = (k0) + BK <= k_end;                                                         \
+    if (!TA && DIRECT_OK && full_) dload_kc<BM, THREADS>(A, d.lda, m0, d.M, (k0), lds3 + (buf) * STAGE);          \
+    else if (TA) { if (full_) gload_tr<BM, BK, THREADS, true>(A, d.lda, m0, d.M, (k0), k_end, ra);                \
+                   else gload_tr<BM, BK, THREADS, false>(A, d.lda, m0, d.M, (k0), k_end, ra); }                   \
+    else { if (full_) gload_kc<BM, BK, THREADS, true>(A, d.lda, m0, d.M, (k0), k_end, ra);                        \
+           else gload_kc<BM, BK, THREADS, false>(A, d.lda, m0, d.M, (k0), k_end, ra); }                           \
+    if (!TB && DIRECT_OK && full_) dload_kc<BN, THREADS>(B, d.ldb, n0, d.N, (k0), lds3 + (buf) * STAGE + BM * BK); \
+    else if (TB) { if (full_) gload_tr<BN, BK, THREADS, true>(B, d.ldb, n0, d.N, (k0), k_end, rb);                \
+                   else gload_tr<BN, BK, THREADS, false>(B, d.ldb, n0, d.N, (k0), k_end, rb); }                   \
+    else { if (full_) gload_kc<BN, BK, THREADS, true>(B, d.ldb, n0, d.N, (k0), k_end, rb);                        \
+           else gload_kc<BN, BK, THREADS, false>(B, d.ldb, n0, d.N, (k0), k_end, rb); }                           \
   } while (0)
-#define GEMM_SSTORE(buf)                                                                 \
-  do {                                                                                   \
-    bf16_t* as_ = lds + (buf) * STAGE;                                                   \
-    if (TA) sstore_tr<BM, THREADS>(as_, ra); else sstore_kc<BM, THREADS>(as_, ra);       \
-    if (TB) sstore_tr<BN, THREADS>(as_ + BM * GB_K, rb);                                 \
-    else sstore_kc<BN, THREADS>(as_ + BM * GB_K, rb);                                    \
+#define GEMM_STORE(k0, buf)                                                                        \
+  do {                                                                                             \
+    const bool full_ = (k0) + BK <= k_end;                                                         \
+    bf16_t* as_ = lds + (buf) * STAGE;                                                             \
+    if (TA) sstore_tr<BM, BK, THREADS>(as_, ra);                                                   \
+    else if (!(DIRECT_OK && full_)) sstore_kc<BM, BK, THREADS>(as_, ra);                           \
+    if (TB) sstore_tr<BN, BK, THREADS>(as_ + BM * BK, rb);                                         \
+    else if (!(DIRECT_OK && full_)) sstore_kc<BN, BK, THREADS>(as_ + BM * BK, rb);                 \
   } while (0)
 
   if (nk > 0) {
-    GEMM_GLOAD(k_begin);
-    GEMM_SSTORE(0);
+    GEMM_FETCH(k_begin, 0);
+    GEMM_STORE(k_begin, 0);
   }
+  __builtin_amdgcn_s_waitcnt(0);     // direct-to-LDS loads are counted by vmcnt
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < nk) GEMM_GLOAD(k_begin + (kt + 1) * GB_K);
+    const int k_next = k_begin + (kt + 1) * BK;
+    if (kt + 1 < nk) GEMM_FETCH(k_next, cur ^ 1);
     const bf16_t* As = lds + cur * STAGE;
-    const bf16_t* Bs = As + BM * GB_K;
+    const bf16_t* Bs = As + BM * BK;
 #pragma unroll
-    for (int s = 0; s < GB_K / 16; ++s) {
+    for (int s = 0; s < BK / 16; ++s) {
       bf16x8_t a[FM], b[FN];
       const int kc = s * 2 + (lane >> 5);
 #pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        const int row = wm * WTM + i * 32 + (lane & 31);
-        a[i] = *reinterpret_cast<const bf16x8_t*>(As + row * GB_K + ((kc ^ swz(row)) << 3));
-      }
+      for (int i = 0; i < FM; ++i)
+        a[i] = *reinterpret_cast<const bf16x8_t*>(As + lds_off<BK>(wm * WTM + i * 32 + (lane & 31), kc));
 #pragma unroll
-      for (int j = 0; j < FN; ++j) {
-        const int row = wn * WTN + j * 32 + (lane & 31);
-        b[j] = *reinterpret_cast<const bf16x8_t*>(Bs + row * GB_K + ((kc ^ swz(row)) << 3));
-      }
+      for (int j = 0; j < FN; ++j)
+        b[j] = *reinterpret_cast<const bf16x8_t*>(Bs + lds_off<BK>(wn * WTN + j * 32 + (lane & 31), kc));
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) GEMM_SSTORE(cur ^ 1);
+    if (kt + 1 < nk) GEMM_STORE(k_next, cur ^ 1);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
   }
-#undef GEMM_GLOAD
-#undef GEMM_SSTORE
+#undef GEMM_FETCH
+#undef GEMM_STORE
 
   // Epilogue through LDS: each wavefront parks 32 rows x WTN columns of fp32 at a time in its own
   // slice of the (now idle) operand buffers, then every lane handles 8 consecutive columns of a
@@ -400,15 +459,17 @@ static bool gemm_prefers_big_tile(int M, int N, int splits) {
   return big >= 192;
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int BK, int WGM, int WGN, int WPE>
 static hipError_t launch_tile(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
   const int tm = (d.M + BM - 1) / BM, tn = (d.N + BN - 1) / BN;
   const int splits = d.splits > 1 ? d.splits : 1;
   const dim3 grid(tm * tn, 1, splits), block(64 * WGM * WGN);
-  const size_t lds_bytes = 2ull * (BM + BN) * GB_K * sizeof(bf16_t);
+  const size_t operand_bytes = 2ull * (BM + BN) * BK * sizeof(bf16_t);
+  const size_t staging_bytes = static_cast<size_t>(WGM) * WGN * 32 * (BN / WGN) * 4;   // epilogue tiles
+  const size_t lds_bytes = operand_bytes > staging_bytes ? operand_bytes : staging_bytes;
 #define LAUNCH_TT(TA, TB)                                                                                      \
   do {                                                                                                         \
-    auto kern = gemm_bf16_mfma_kernel<BM, BN, WGM, WGN, TA, TB>;                                               \
+    auto kern = gemm_bf16_mfma_kernel<BM, BN, BK, WGM, WGN, WPE, TA, TB>;                                               \
     static bool attr_set = false;                                                                              \
     if (!attr_set && lds_bytes > 64 * 1024) {                                                                  \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
@@ -454,13 +515,13 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
     if (d.epi.kind == EPI_DSWIGLU && d.epi.kp % 8) return ECOSPA_ERR_ALIGN;
     if (d.splits > 1 && !aligned16(d.partial)) return ECOSPA_ERR_ALIGN;
     int k_chunk = (d.K + splits - 1) / splits;
-    k_chunk = (k_chunk + GB_K - 1) / GB_K * GB_K;
+    k_chunk = (k_chunk + 63) / 64 * 64;
     const bool big = d.tile == 2 || (d.tile == 0 && gemm_prefers_big_tile(d.M, d.N, splits));
     const bool prof = ctx->prof_on && ctx->prof_n < ctx->prof_cap;
     if (prof) (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n], ctx->stream);
-    hipError_t le = d.tile == 3 ? launch_tile<256, 256, 2, 2>(ctx, d, k_chunk)
-                    : big       ? launch_tile<256, 256, 2, 4>(ctx, d, k_chunk)
-                                : launch_tile<128, 128, 2, 2>(ctx, d, k_chunk);
+    hipError_t le;
+    if (d.tile == 2 || (d.tile == 0 && big)) le = launch_tile<256, 256, 64, 2, 4, 2>(ctx, d, k_chunk);
+    else le = launch_tile<128, 128, 64, 2, 2, 2>(ctx, d, k_chunk);
     if (le != hipSuccess) return hip_fail(ctx, le, "gemm launch");
     if (prof) {
       (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n + 1], ctx->stream);
