@@ -71,13 +71,16 @@ __device__ __forceinline__ bf16x8_t acc_to_frag(const floatx16& a, int half) {
 template <int D>
 __device__ __forceinline__ void sub_load(u32x4 (&v)[4], const bf16_t* __restrict__ base, long long ld, long long row0,
                                          int rows_valid, int kp, int sub) {
+  // Unconditional loads from clamped (always valid) addresses, then a select: no divergent code.
+  // row0 + rows_valid - 1 is the last token of the sequence whatever the tile, so the clamp is safe
+  // even for tiles that start beyond the sequence end.
   const int tblk = sub / (D / 8), dblk = sub % (D / 8);
+  const int dc = min(dblk * 8, kp - 8);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int r = tblk * 4 + i;
-    v[i] = (r < rows_valid && dblk * 8 < kp)
-               ? *reinterpret_cast<const u32x4*>(base + (row0 + r) * ld + dblk * 8)
-               : u32x4{0u, 0u, 0u, 0u};
+    const u32x4 x = *reinterpret_cast<const u32x4*>(base + (row0 + min(r, rows_valid - 1)) * ld + dc);
+    v[i] = (r < rows_valid && dblk * 8 < kp) ? x : u32x4{0u, 0u, 0u, 0u};
   }
 }
 template <int D>
@@ -132,7 +135,7 @@ __device__ __forceinline__ void acc_to_tile(bf16_t* tile, int tok_row, int dim_t
 // forward: one workgroup per (128 queries, head, batch); 4 wavefronts x 32 queries
 // ---------------------------------------------------------------------------------------------
 template <int DQ, int DV>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
   __shared__ __attribute__((aligned(16))) bf16_t Qs[128 * DMAX];   // Q tile, later the O staging tile
   __shared__ __attribute__((aligned(16))) bf16_t Ks[2][64 * DQ];
@@ -195,39 +198,47 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const AttnArgs a) {
         for (int s = 0; s < DQ / 16; ++s)
           sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DQ>(Ks[cur], t * 32 + l32, s, hh), qf[s], sacc[t], 0, 0, 0);
       }
-      const bool need_mask = (a.causal && kv0 + 63 > qw0) || (kv0 + 64 > a.L);
-      float mx = -INFINITY;
+      // Softmax on raw scores: the scale is folded into the exponent's FMA.  Masking is a
+      // wave-uniform special case (tiles on the diagonal or at the end of the sequence) done
+      // with selects, never with divergent branches.
+      if ((a.causal && kv0 + 63 > qw0) || (kv0 + 64 > a.L)) {
+        const int lim = a.causal ? min(q_idx, a.L - 1) : a.L - 1;   // last visible key of this query
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = kv0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
+            sacc[t][r] = key > lim ? -INFINITY : sacc[t][r];
+          }
+      }
+      float mx = sacc[0][0];
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = sacc[t][r] * sc;
-          if (need_mask) {
-            const int key = kv0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
-            if (key >= a.L || (a.causal && key > q_idx)) v = -INFINITY;
-          }
-          sacc[t][r] = v;
-          mx = fmaxf(mx, v);
-        }
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);
-      const float m_use = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+      const float m_new = fmaxf(m_run, mx);                       // raw (unscaled) running maximum
+      const float msc = (m_new == -INFINITY ? 0.f : m_new) * sc;
       float psum = 0.f;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(sacc[t][r] - m_use);
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[t][r], sc, -msc));
           sacc[t][r] = p;
           psum += p;
         }
-      l_run = l_run * alpha + psum;
+      // rescale the running sums only when some query's maximum moved (wave-uniform test)
+      if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull) {
+        const float alpha = __builtin_amdgcn_exp2f(__builtin_fmaf(m_run, sc, -msc));
+        l_run *= alpha;
+#pragma unroll
+        for (int u = 0; u < DV / 32; ++u)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[u][r] *= alpha;
+      }
+      l_run += psum;
       m_run = m_new;
-#pragma unroll
-      for (int u = 0; u < DV / 32; ++u)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[u][r] *= alpha;
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         const bf16x8_t pf = acc_to_frag(sacc[s >> 1], s & 1);
@@ -244,7 +255,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const AttnArgs a) {
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   if (hh == 0 && q_idx < a.L)
-    a.lse[(static_cast<long long>(b) * a.h + head) * a.L + q_idx] = (m_run + __log2f(l_tot)) * LN2;
+    a.lse[(static_cast<long long>(b) * a.h + head) * a.L + q_idx] = (m_run * sc + __log2f(l_tot)) * LN2;
   // O staging (the Q fragments live in registers, so the Q tile can be overwritten)
 #pragma unroll
   for (int u = 0; u < DV / 32; ++u) acc_to_tile<DV>(Qs, wave * 32 + l32, u, oacc[u], inv, hh);
@@ -282,7 +293,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const AttnArgs a) {
 //   S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - delta), dQ^T += K^T dS^T
 // ---------------------------------------------------------------------------------------------
 template <int DQ, int DV>
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
   __shared__ __attribute__((aligned(16))) bf16_t Qs[128 * DMAX];   // Q tile, then dO tile, then dQ staging
   __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * DQ];
@@ -347,6 +358,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const AttnArgs a) {
     if (j + 1 < n_kv) DQ_GLOAD(j + 1);
     if (a.causal && kv0 > qw0 + 31) continue;
     const bool need_mask = (a.causal && kv0 + 63 > qw0) || (kv0 + 64 > a.L);
+    const int lim = a.causal ? min(q_idx, a.L - 1) : a.L - 1;       // last visible key of this query
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       floatx16 sacc, pacc;
@@ -358,13 +370,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const AttnArgs a) {
 #pragma unroll
       for (int s = 0; s < DV / 16; ++s)
         pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DV>(Vs, t * 32 + l32, s, hh), dof[s], pacc, 0, 0, 0);
+      if (need_mask) {        // wave-uniform; selects only
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kv0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
+          sacc[r] = key > lim ? -INFINITY : sacc[r];
+        }
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(sacc[r] * sc - lse2);
-        if (need_mask) {
-          const int key = kv0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
-          if (key >= a.L || (a.causal && key > q_idx)) p = 0.f;
-        }
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[r], sc, -lse2));
         sacc[r] = p * (pacc[r] - dlt);
       }
 #pragma unroll
@@ -389,7 +404,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const AttnArgs a) {
 //   S = Q K^T, dP = dO V^T, dS = P * (dP - delta), dV^T += dO^T P, dK^T += Q^T dS
 // ---------------------------------------------------------------------------------------------
 template <int DQ, int DV>
-__global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkdv_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
   __shared__ __attribute__((aligned(16))) bf16_t KVs[128 * DMAX];   // K tile, V tile, then output staging
   __shared__ __attribute__((aligned(16))) bf16_t Qs[64 * DQ];
@@ -480,6 +495,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(const AttnArgs a) {
       for (int s = 0; s < DV / 16; ++s)
         pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DV>(dOs, t * 32 + l32, s, hh), vf[s], pacc, 0, 0, 0);
       floatx16 pr;
+      // a query sees this lane's key if key <= q (causal) and both are inside the sequence
+      const int q_min = key_idx >= a.L ? 0x7fffffff : (a.causal ? key_idx : 0);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int qrow = t * 32 + g * 8 + hh * 4;
@@ -489,11 +506,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(const AttnArgs a) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int r = g * 4 + i;
-          float p = __builtin_amdgcn_exp2f(sacc[r] * sc - lsv[i]);
-          if (need_mask) {
+          float sv = sacc[r];
+          if (need_mask) {      // wave-uniform; selects only
             const int q = qb0 + qrow + i;
-            if (q >= a.L || key_idx >= a.L || (a.causal && key_idx > q)) p = 0.f;
+            sv = (q < q_min || q >= a.L) ? -INFINITY : sv;
           }
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv, sc, -lsv[i]));
           pr[r] = p;
           sacc[r] = p * (pacc[r] - dlv[i]);
         }
