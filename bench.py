@@ -23,6 +23,11 @@ METRIC = "coupled-sparse layer fwd+bwd tokens/s & TFLOP/s vs dense, 50% sparsity
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the MFMA contraction kernel, averaged over the 12 launches of one sparse
+# step, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/): (gemm.hip sha256 prefix, bytes).
+# Reported only while the kernel source still has that hash; otherwise null.
+GEMM_TRAFFIC = ("1b506c137d358563", 120.5e6)
+
 
 def model_flops(T, L, d, h, k_qk, k_vo, k_ff, causal=True):
     """fwd+bwd model flops of one layer (backward = 2x forward, recomputation not counted,
@@ -31,6 +36,17 @@ def model_flops(T, L, d, h, k_qk, k_vo, k_ff, causal=True):
     attn = (2 * T * L * h * (k_qk + k_vo)) * (0.5 if causal else 1.0)
     ffn = 2 * 2 * T * d * k_ff
     return 3.0 * (proj + attn + ffn)
+
+
+def gemm_traffic():
+    import hashlib
+    import os
+    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2511_11641_amd", "csrc", "gemm.hip")
+    try:
+        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    return GEMM_TRAFFIC[1] if GEMM_TRAFFIC[0] == digest else None
 
 
 class Layer:
@@ -155,6 +171,11 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-reference", action="store_true",
+                    help="first run 3 plain device copies of a 128 MiB tensor, so that hardware byte counters read "
+                         "under rocprofv3 --pmc can be scaled by what they show for a copy of known size")
+    ap.add_argument("--sparse-only", action="store_true",
+                    help="run only the timed sparse steps (for hardware-counter runs) and print a short line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU hot path only: run it with --gpus 1 "
@@ -173,8 +194,19 @@ def main():
     Bsz, L, d, h, dh, dff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
     T = Bsz * L
 
+    if args.pmc_reference:      # a plain device copy reads 128 MiB and writes 128 MiB per launch
+        ref = torch.zeros((65536, 1024), dtype=torch.bfloat16, device="cuda")
+        out_ref = torch.empty_like(ref)
+        for _ in range(3):
+            out_ref.copy_(ref)
+        torch.cuda.synchronize()
+        del ref, out_ref
+
     sparse = Layer(ctx, cfg, seed, 1, 2)
     ms_step = timed(torch, sparse.step, args.steps, args.warmup)
+    if args.sparse_only:
+        print(json.dumps({"ms_per_step": ms_step, "steps": args.steps, "warmup": args.warmup}))
+        return
 
     # break-down of the same step, each part timed on its own (not part of `value`)
     parts = {nm: timed(torch, fn, args.steps, 2) for nm, fn in
@@ -217,7 +249,7 @@ def main():
         "compact_gbs": w_bytes / (parts["compact"] * 1e-3) / 1e9,   # kept bytes read + kept bytes written
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_mfma_kernel", "achieved": gemm_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "frac": gemm_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": gemm_traffic(),
                      "launches": n_launch, "avg_launch_us": gemm_ms * 1e3 / max(n_launch, 1),
                      "flop_per_launch_avg": gemm_flop / max(n_launch, 1),
                      "measured": f"HIP events around each launch, {args.steps} steps re-run after the timed region"},
