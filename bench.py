@@ -3,8 +3,8 @@
 
 A "step" is one pass of the whole path over one batch of a GPT-2-Medium-shaped layer
 (d=1024, 16 heads x 64, d_ff=4096, GELU, batch 8 x seq 1024, bf16):
-    score the QK, VO and FFN pairs (one batched call) -> select top-k at 50% keep ->
-    compact every matrix -> attention fwd -> FFN fwd -> FFN bwd -> attention bwd.
+    score the QK, VO and FFN pairs (one batched call) -> select top-k at 50% keep (one call) ->
+    compact every matrix (one call) -> attention fwd -> FFN fwd -> FFN bwd -> attention bwd.
 Inputs are seeded synthetic tensors (weights N(0, 0.02^2), activations N(0, 1)) that are
 resident in HBM before the timed region.  One JSON line is printed.
 
@@ -88,13 +88,14 @@ class Layer:
     def score(self):
         self.scores = self.ctx.ecospa_coupled_score(self.pairs)
 
-    def select(self):
-        for s, k, out in zip(self.scores, (self.k_qk_units, self.k_vo, self.k_ff), self.idx):
-            self.ctx.ecospa_select_topk(s, k, out=out)
+    def select(self):       # one launch for the three pairs
+        mk = self.ctx.select_item
+        self.ctx.ecospa_select_topk_batch([mk(s, k, out) for s, k, out in
+                                           zip(self.scores, (self.k_qk_units, self.k_vo, self.k_ff), self.idx)])
 
-    def compact(self):
-        self.attn.compact(self.idx[0], self.idx[1])
-        self.ffn.compact(self.idx[2])
+    def compact(self):      # one launch for every matrix and bias of the layer
+        items = self.attn.compact(self.idx[0], self.idx[1], defer=True) + self.ffn.compact(self.idx[2], defer=True)
+        self.ctx.ecospa_compact_batch(items)
 
     def prune(self):
         self.score()

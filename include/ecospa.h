@@ -102,6 +102,14 @@ int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs /*host*/, int
  * Errors: k < 1 or k > n_units -> ERR_K; groups/n_units < 1 -> ERR_SHAPE.
  * ------------------------------------------------------------------------------------------ */
 int ecospa_select_topk(ecospa_ctx* ctx, const float* scores, int groups, int n_units, int k, int* idx);
+/* The same for several score arrays (all coupled pairs of a layer) in one launch; `items` is a host
+ * array.  Errors as above, checked for every item before anything is launched. */
+typedef struct {
+  const float* scores; /* float[groups * n_units] */
+  int groups, n_units, k;
+  int* idx;            /* int32[groups * k] */
+} ecospa_select_item;
+int ecospa_select_topk_batch(ecospa_ctx* ctx, const ecospa_select_item* items /*host*/, int n_items);
 
 /* ------------------------------------------------------------------------------------------
  * Step 3 - aligned gather of the kept inner dimensions into a smaller dense matrix (Def. 1:
@@ -126,6 +134,18 @@ int ecospa_compact(ecospa_ctx* ctx, const void* src, void* dst, int dtype, int a
 int ecospa_scatter(ecospa_ctx* ctx, const void* src, void* dst, int dtype, int axis, int groups, int n,
                    int unit, int k, int kp, long long other_extent, long long ld_src, long long ld_dst,
                    const int* idx);
+/* Several gathers and/or scatters (every matrix, bias and moment of a layer) in one launch; the
+ * fields have the meaning of the arguments above, scatter != 0 selects the inverse direction.
+ * `items` is a host array; all items are validated before anything is launched.  Items must not
+ * overlap each other's destinations. */
+typedef struct {
+  const void* src;
+  void* dst;
+  int dtype, axis, groups, n, unit, k, kp, scatter;
+  long long other_extent, ld_src, ld_dst;
+  const int* idx;
+} ecospa_map_item;
+int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* items /*host*/, int n_items);
 
 /* cos/sin tables of the KEPT rotary blocks (Eq. 6; "position matrices are then adjusted to match
  * new dimensions", footnote to Eq. 10): for head g, position t < L, kept block i < k,

@@ -26,6 +26,7 @@ EXPORTS = (
     "ecospa_score_workspace_bytes", "ecospa_coupled_score", "ecospa_select_topk", "ecospa_compact",
     "ecospa_scatter", "ecospa_rope_table", "ecospa_block_workspace_bytes", "ecospa_coupled_fwd",
     "ecospa_coupled_bwd", "ecospa_profile_gemm", "ecospa_profile_gemm_read", "ecospa_contract",
+    "ecospa_select_topk_batch", "ecospa_compact_batch",
 )
 
 
@@ -50,6 +51,18 @@ class BlockDesc(C.Structure):
                 ("kp_ff", C.c_int), ("act", C.c_int),
                 ("w_1", C.c_void_p), ("b_1", C.c_void_p), ("w_2", C.c_void_p), ("b_2", C.c_void_p),
                 ("ld_w1", C.c_longlong), ("ld_w2", C.c_longlong)]
+
+
+class SelectItem(C.Structure):
+    _fields_ = [("scores", C.c_void_p), ("groups", C.c_int), ("n_units", C.c_int), ("k", C.c_int),
+                ("idx", C.c_void_p)]
+
+
+class MapItem(C.Structure):
+    _fields_ = [("src", C.c_void_p), ("dst", C.c_void_p), ("dtype", C.c_int), ("axis", C.c_int), ("groups", C.c_int),
+                ("n", C.c_int), ("unit", C.c_int), ("k", C.c_int), ("kp", C.c_int), ("scatter", C.c_int),
+                ("other_extent", C.c_longlong), ("ld_src", C.c_longlong), ("ld_dst", C.c_longlong),
+                ("idx", C.c_void_p)]
 
 
 class Saved(C.Structure):
@@ -95,6 +108,10 @@ def load() -> C.CDLL:
     for f in (lib.ecospa_compact, lib.ecospa_scatter):
         f.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ll, ll, ll, vp]
         f.restype = ci
+    lib.ecospa_select_topk_batch.argtypes = [vp, C.POINTER(SelectItem), ci]
+    lib.ecospa_select_topk_batch.restype = ci
+    lib.ecospa_compact_batch.argtypes = [vp, C.POINTER(MapItem), ci]
+    lib.ecospa_compact_batch.restype = ci
     lib.ecospa_rope_table.argtypes = [vp, vp, ci, ci, ci, ci, ci, C.c_double, vp, vp]
     lib.ecospa_rope_table.restype = ci
     lib.ecospa_block_workspace_bytes.argtypes = [C.POINTER(BlockDesc)]
@@ -218,7 +235,36 @@ class Context:
                     "ecospa_select_topk")
         return idx
 
+    def ecospa_select_topk_batch(self, items: Sequence[SelectItem]):
+        """items: SelectItem structs (see :meth:`select_item`); one launch for all of them."""
+        arr = (SelectItem * len(items))(*items)
+        self._check(self.lib.ecospa_select_topk_batch(self.h, arr, len(items)), "ecospa_select_topk_batch")
+
+    @staticmethod
+    def select_item(scores: torch.Tensor, k: int, idx: torch.Tensor) -> SelectItem:
+        groups, n_units = scores.shape
+        assert scores.dtype == torch.float32 and scores.is_contiguous() and idx.dtype == torch.int32
+        return SelectItem(scores.data_ptr(), groups, n_units, k, idx.data_ptr())
+
     # ---- step 3 ------------------------------------------------------------------------------
+    @staticmethod
+    def map_item(src: torch.Tensor, dst: torch.Tensor, idx: torch.Tensor, axis: int, groups: int, n: int,
+                 unit: int = 1, kp: Optional[int] = None, scatter: bool = False) -> MapItem:
+        """Descriptor of one gather (or scatter) for :meth:`ecospa_compact_batch`."""
+        k = idx.shape[1]
+        kp = k if kp is None else kp
+        if src.dim() == 1:
+            other, ld_s, ld_d, axis = 1, src.numel(), dst.numel(), 1
+        else:
+            other = src.shape[1] if axis == 0 else src.shape[0]
+            ld_s, ld_d = src.stride(0), dst.stride(0)
+        return MapItem(src.data_ptr(), dst.data_ptr(), dtype_code(src.dtype), axis, groups, n, unit, k, kp,
+                       int(scatter), other, ld_s, ld_d, idx.data_ptr())
+
+    def ecospa_compact_batch(self, items: Sequence[MapItem]):
+        arr = (MapItem * len(items))(*items)
+        self._check(self.lib.ecospa_compact_batch(self.h, arr, len(items)), "ecospa_compact_batch")
+
     def _mapped(self, fn, name, src, dst, axis, groups, n, unit, k, kp, idx):
         if src.dim() == 1:
             other, ld_s, ld_d = 1, src.numel(), dst.numel()
@@ -251,9 +297,13 @@ class Context:
         return self._mapped(self.lib.ecospa_scatter, "ecospa_scatter", src, out, axis, groups, n, unit, k, kp, idx)
 
     def ecospa_rope_table(self, idx: Optional[torch.Tensor], h: int, L: int, k: int, kp: int, d_h: int,
-                          base: float = 10000.0):
-        cos = torch.empty((h, L, kp), dtype=torch.float32, device=self.device)
-        sin = torch.empty_like(cos)
+                          base: float = 10000.0, out=None):
+        if out is not None:
+            cos, sin = out
+            assert cos.shape == (h, L, kp) and sin.shape == (h, L, kp) and cos.dtype == torch.float32
+        else:
+            cos = torch.empty((h, L, kp), dtype=torch.float32, device=self.device)
+            sin = torch.empty_like(cos)
         self._check(self.lib.ecospa_rope_table(self.h, _ptr(idx), h, L, k, kp, d_h, float(base), cos.data_ptr(),
                                                sin.data_ptr()), "ecospa_rope_table")
         return cos, sin

@@ -131,11 +131,16 @@ __device__ __forceinline__ void acc_to_tile(bf16_t* tile, int tok_row, int dim_t
   }
 }
 
+// Wavefronts per SIMD the register allocation aims at: the narrow (32, 32) heads of a half-kept
+// layer need few registers, and more resident workgroups hide their barrier and LDS latencies.
+#define ATTN_WPE(DQ, DV, narrow) ((DQ) + (DV) <= 64 ? (narrow) : 2)
+
 // ---------------------------------------------------------------------------------------------
 // forward: one workgroup per (128 queries, head, batch); 4 wavefronts x 32 queries
 // ---------------------------------------------------------------------------------------------
 template <int DQ, int DV>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ, DV, 4), ATTN_WPE(DQ, DV, 4))))
+void attn_fwd_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
   __shared__ __attribute__((aligned(16))) bf16_t Qs[128 * DMAX];   // Q tile, later the O staging tile
   __shared__ __attribute__((aligned(16))) bf16_t Ks[2][64 * DQ];
@@ -293,7 +298,8 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const AttnArgs a) {
 //   S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - delta), dQ^T += K^T dS^T
 // ---------------------------------------------------------------------------------------------
 template <int DQ, int DV>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ, DV, 3), ATTN_WPE(DQ, DV, 3))))
+void attn_bwd_dq_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
   __shared__ __attribute__((aligned(16))) bf16_t Qs[128 * DMAX];   // Q tile, then dO tile, then dQ staging
   __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * DQ];
@@ -639,21 +645,16 @@ int attn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, 
   return ecospa_gemm(ctx, mk_gemm(d.dtype, T, d.d_model, nvo, o, nvo, 0, d.w_o, d.ld_wo, 0, y, d.d_model, d.b_o));
 }
 
-int attn_backward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, const void* dy,
-                  const ecospa_saved& sv, void* dx, const ecospa_grads& gr) {
-  if (d.dtype != ECOSPA_BF16) return ECOSPA_ERR_DTYPE;
+// dW_o and dW_qkv are split-K contractions whose partials are reduced, together with the two
+// bias-gradient column sums, by one batched launch at the end.
+static int attn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x,
+                              const void* dy, const ecospa_saved& sv, void* dx, const ecospa_grads& gr) {
   const int T = d.B * d.L, nqkv = attn_nqkv(d), nvo = d.h * d.kp_vo, dm = d.d_model;
-  if (!sv.qkv || !sv.o || !sv.lse) return ECOSPA_ERR_NULL;
-  if (!aligned16(sv.qkv) || !aligned16(sv.o)) return ECOSPA_ERR_ALIGN;
   int rc;
-  // dW_o = dY^T O,  db_o = colsum(dY),  dO = dY W_o
-  if (gr.dw_o) {
-    if (gr.ld_dwo < nvo) return ECOSPA_ERR_SHAPE;
-    GemmDesc g = mk_gemm(d.dtype, dm, nvo, T, dy, dm, 1, sv.o, nvo, 1, gr.dw_o, gr.ld_dwo, nullptr);
-    g.splits = ecospa_gemm_splits(dm, nvo, T); g.partial = w.partial;
-    if ((rc = ecospa_gemm(ctx, g))) return rc;
-  }
-  if (gr.db_o && (rc = ecospa_colsum(ctx, d.dtype, dy, dm, T, dm, w.colsum_partial, gr.db_o))) return rc;
+  // dW_o = dY^T O (partials),  dO = dY W_o
+  GemmDesc go = mk_gemm(d.dtype, dm, nvo, T, dy, dm, 1, sv.o, nvo, 1, gr.dw_o, gr.ld_dwo, nullptr);
+  go.splits = ecospa_gemm_splits(dm, nvo, T); go.partial = w.partial; go.defer_reduce = 1;
+  if (gr.dw_o && (rc = ecospa_gemm(ctx, go))) return rc;
   if ((rc = ecospa_gemm(ctx, mk_gemm(d.dtype, T, nvo, dm, dy, dm, 0, d.w_o, d.ld_wo, 1, w.d_o, nvo, nullptr)))) return rc;
 
   AttnArgs a;
@@ -671,15 +672,29 @@ int attn_backward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w,
   if ((rc = dispatch_core(ctx, 1, a))) return rc;
   if (d.rope_cos && (rc = launch_rope(ctx, d, w.dqkv, nqkv, -1.f))) return rc;
 
-  // dW_qkv = dQKV^T X,  db_qkv = colsum(dQKV),  dX = dQKV W_qkv
-  if (gr.dw_qkv) {
-    if (gr.ld_dwqkv < dm) return ECOSPA_ERR_SHAPE;
-    GemmDesc g = mk_gemm(d.dtype, nqkv, dm, T, w.dqkv, nqkv, 1, x, dm, 1, gr.dw_qkv, gr.ld_dwqkv, nullptr);
-    g.splits = ecospa_gemm_splits(nqkv, dm, T); g.partial = w.partial;
-    if ((rc = ecospa_gemm(ctx, g))) return rc;
-  }
-  if (gr.db_qkv && (rc = ecospa_colsum(ctx, d.dtype, w.dqkv, nqkv, T, nqkv, w.colsum_partial, gr.db_qkv))) return rc;
+  // dW_qkv = dQKV^T X (partials)
+  GemmDesc gq = mk_gemm(d.dtype, nqkv, dm, T, w.dqkv, nqkv, 1, x, dm, 1, gr.dw_qkv, gr.ld_dwqkv, nullptr);
+  gq.splits = ecospa_gemm_splits(nqkv, dm, T); gq.partial = w.partial2; gq.defer_reduce = 1;
+  if (gr.dw_qkv && (rc = ecospa_gemm(ctx, gq))) return rc;
+
+  // dX = dQKV W_qkv
   if (dx && (rc = ecospa_gemm(ctx, mk_gemm(d.dtype, T, dm, nqkv, w.dqkv, nqkv, 0, d.w_qkv, d.ld_wqkv, 1, dx, dm, nullptr))))
     return rc;
-  return ECOSPA_OK;
+  AuxBatch aux;
+  memset(&aux, 0, sizeof(aux));
+  if (gr.dw_o && go.splits > 1) aux.reduce[aux.n_reduce++] = go;
+  if (gr.dw_qkv && gq.splits > 1) aux.reduce[aux.n_reduce++] = gq;
+  if (gr.db_o) aux.colsum[aux.n_colsum++] = AuxColsum{dy, dm, T, dm, d.dtype, gr.db_o};
+  if (gr.db_qkv) aux.colsum[aux.n_colsum++] = AuxColsum{w.dqkv, nqkv, T, nqkv, d.dtype, gr.db_qkv};
+  return ecospa_aux_launch(ctx, aux);
+}
+
+int attn_backward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, const void* dy,
+                  const ecospa_saved& sv, void* dx, const ecospa_grads& gr) {
+  if (d.dtype != ECOSPA_BF16) return ECOSPA_ERR_DTYPE;
+  if (!sv.qkv || !sv.o || !sv.lse) return ECOSPA_ERR_NULL;
+  if (!aligned16(sv.qkv) || !aligned16(sv.o)) return ECOSPA_ERR_ALIGN;
+  if (gr.dw_o && gr.ld_dwo < static_cast<long long>(d.h) * d.kp_vo) return ECOSPA_ERR_SHAPE;
+  if (gr.dw_qkv && gr.ld_dwqkv < d.d_model) return ECOSPA_ERR_SHAPE;
+  return attn_backward_body(ctx, d, w, x, dy, sv, dx, gr);
 }

@@ -16,8 +16,8 @@ struct BlockWs {           // pieces carved from the caller's workspace
   void* d_o;               // [T, h*kp_vo]
   float* delta;            // [B*h*L]
   // shared
-  float* partial;          // split-K partials
-  float* colsum_partial;
+  float* partial;          // split-K partials of the first weight-gradient contraction of a backward pass
+  float* partial2;         // ... and of the second (both are reduced by the batched tail launch)
   size_t total;
 };
 

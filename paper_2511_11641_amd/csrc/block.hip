@@ -37,7 +37,7 @@ void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
   memset(&w, 0, sizeof(w));
   WsCarver c(base ? base : reinterpret_cast<void*>(256), ~static_cast<size_t>(0) >> 1);
   const size_t T = static_cast<size_t>(d.B) * d.L, es = dtype_size(d.dtype), dm = d.d_model;
-  size_t part = 0, csn = 0;
+  size_t part = 0, part2 = 0;
   auto splitk_bytes = [&](int M, int N, int K) {
     const int s = ecospa_gemm_splits(M, N, K);
     return s > 1 ? static_cast<size_t>(s) * M * N * 4 : static_cast<size_t>(0);
@@ -47,8 +47,8 @@ void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
     w.dh = c.take(T * nh * es);
     w.hpre_tmp = w.dh;                       // inference scratch aliases the backward scratch
     w.act_tmp = c.take(T * d.kp_ff * es);
-    part = max_sz(splitk_bytes(d.d_model, d.kp_ff, static_cast<int>(T)), splitk_bytes(static_cast<int>(nh), d.d_model, static_cast<int>(T)));
-    csn = max_sz(nh, dm);
+    part = splitk_bytes(d.d_model, d.kp_ff, static_cast<int>(T));
+    part2 = splitk_bytes(static_cast<int>(nh), d.d_model, static_cast<int>(T));
   } else {
     const size_t nqkv = attn_nqkv(d), nvo = static_cast<size_t>(d.h) * d.kp_vo;
     w.dqkv = c.take(T * nqkv * es);
@@ -57,11 +57,11 @@ void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
     w.o_tmp = w.d_o;
     w.delta = static_cast<float*>(c.take(static_cast<size_t>(d.B) * d.h * d.L * 4));
     w.lse_tmp = static_cast<float*>(c.take(static_cast<size_t>(d.B) * d.h * d.L * 4));
-    part = max_sz(splitk_bytes(d.d_model, static_cast<int>(nvo), static_cast<int>(T)), splitk_bytes(static_cast<int>(nqkv), d.d_model, static_cast<int>(T)));
-    csn = max_sz(nqkv, dm);
+    part = splitk_bytes(d.d_model, static_cast<int>(nvo), static_cast<int>(T));
+    part2 = splitk_bytes(static_cast<int>(nqkv), d.d_model, static_cast<int>(T));
   }
   w.partial = static_cast<float*>(c.take(part));
-  w.colsum_partial = static_cast<float*>(c.take(static_cast<size_t>(ecospa_colsum_chunks(static_cast<int>(T))) * csn * 4));
+  w.partial2 = static_cast<float*>(c.take(part2));
   w.total = c.off + 256;
   if (!base) memset(&w, 0, offsetof(BlockWs, total));
 }
@@ -131,20 +131,12 @@ static int ffn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockW
   return ecospa_gemm(ctx, g2);
 }
 
-static int ffn_backward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, const void* dy,
-                        const ecospa_saved& sv, void* dx, const ecospa_grads& gr) {
+// Backward pass: dH, the two split-K weight gradients (partials only), dX, and then ONE launch for
+// the reductions of the partials and the two bias-gradient column sums.
+static int ffn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, const void* dy,
+                             const ecospa_saved& sv, void* dx, const ecospa_grads& gr) {
   const int T = d.B * d.L, kp = d.kp_ff, nh = is_gated(d) ? 2 * kp : kp, dm = d.d_model;
-  if (!sv.hpre || !sv.act) return ECOSPA_ERR_NULL;
   int rc;
-  // dW_2 = dY^T A
-  if (gr.dw_2) {
-    if (gr.ld_dw2 < kp) return ECOSPA_ERR_SHAPE;
-    GemmDesc g = gemm_desc(d.dtype, dm, kp, T, dy, dm, 1, sv.act, kp, 1);
-    g.splits = ecospa_gemm_splits(dm, kp, T); g.partial = w.partial;
-    g.epi.kind = EPI_STORE; g.epi.c = gr.dw_2; g.epi.ldc = gr.ld_dw2;
-    if ((rc = ecospa_gemm(ctx, g))) return rc;
-  }
-  if (gr.db_2 && (rc = ecospa_colsum(ctx, d.dtype, dy, dm, T, dm, w.colsum_partial, gr.db_2))) return rc;
   // dH = (dY W_2) * act'(H)
   {
     GemmDesc g = gemm_desc(d.dtype, T, kp, dm, dy, dm, 0, d.w_2, d.ld_w2, 1);
@@ -152,22 +144,37 @@ static int ffn_backward(ecospa_ctx* ctx, const ecospa_block_desc& d, const Block
     g.epi.kind = is_gated(d) ? EPI_DSWIGLU : EPI_DACT;
     if ((rc = ecospa_gemm(ctx, g))) return rc;
   }
-  // dW_1 = dH^T X
-  if (gr.dw_1) {
-    if (gr.ld_dw1 < dm) return ECOSPA_ERR_SHAPE;
-    GemmDesc g = gemm_desc(d.dtype, nh, dm, T, w.dh, nh, 1, x, dm, 1);
-    g.splits = ecospa_gemm_splits(nh, dm, T); g.partial = w.partial;
-    g.epi.kind = EPI_STORE; g.epi.c = gr.dw_1; g.epi.ldc = gr.ld_dw1;
-    if ((rc = ecospa_gemm(ctx, g))) return rc;
-  }
-  if (gr.db_1 && (rc = ecospa_colsum(ctx, d.dtype, w.dh, nh, T, nh, w.colsum_partial, gr.db_1))) return rc;
+  // dW_2 = dY^T A,  dW_1 = dH^T X
+  GemmDesc g2 = gemm_desc(d.dtype, dm, kp, T, dy, dm, 1, sv.act, kp, 1);
+  g2.splits = ecospa_gemm_splits(dm, kp, T); g2.partial = w.partial; g2.defer_reduce = 1;
+  g2.epi.kind = EPI_STORE; g2.epi.c = gr.dw_2; g2.epi.ldc = gr.ld_dw2;
+  if (gr.dw_2 && (rc = ecospa_gemm(ctx, g2))) return rc;
+  GemmDesc g1 = gemm_desc(d.dtype, nh, dm, T, w.dh, nh, 1, x, dm, 1);
+  g1.splits = ecospa_gemm_splits(nh, dm, T); g1.partial = w.partial2; g1.defer_reduce = 1;
+  g1.epi.kind = EPI_STORE; g1.epi.c = gr.dw_1; g1.epi.ldc = gr.ld_dw1;
+  if (gr.dw_1 && (rc = ecospa_gemm(ctx, g1))) return rc;
+
   // dX = dH W_1
   if (dx) {
     GemmDesc g = gemm_desc(d.dtype, T, dm, nh, w.dh, nh, 0, d.w_1, d.ld_w1, 1);
     g.epi.kind = EPI_STORE; g.epi.c = dx; g.epi.ldc = dm;
     if ((rc = ecospa_gemm(ctx, g))) return rc;
   }
-  return ECOSPA_OK;
+  AuxBatch aux;
+  memset(&aux, 0, sizeof(aux));
+  if (gr.dw_2 && g2.splits > 1) aux.reduce[aux.n_reduce++] = g2;
+  if (gr.dw_1 && g1.splits > 1) aux.reduce[aux.n_reduce++] = g1;
+  if (gr.db_2) aux.colsum[aux.n_colsum++] = AuxColsum{dy, dm, T, dm, d.dtype, gr.db_2};
+  if (gr.db_1) aux.colsum[aux.n_colsum++] = AuxColsum{w.dh, nh, T, nh, d.dtype, gr.db_1};
+  return ecospa_aux_launch(ctx, aux);
+}
+
+static int ffn_backward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, const void* dy,
+                        const ecospa_saved& sv, void* dx, const ecospa_grads& gr) {
+  if (!sv.hpre || !sv.act) return ECOSPA_ERR_NULL;
+  if (gr.dw_2 && gr.ld_dw2 < d.kp_ff) return ECOSPA_ERR_SHAPE;
+  if (gr.dw_1 && gr.ld_dw1 < d.d_model) return ECOSPA_ERR_SHAPE;
+  return ffn_backward_body(ctx, d, w, x, dy, sv, dx, gr);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -205,7 +212,7 @@ extern "C" int ecospa_contract(ecospa_ctx* ctx, int dtype, int M, int N, int K, 
                                const void* bias, int tile, int splits) {
   if (!ctx || !A || !B || !C) return ECOSPA_ERR_NULL;
   if (!dtype_ok(dtype)) return ECOSPA_ERR_DTYPE;
-  if (M < 1 || N < 1 || K < 1 || tile < 0 || tile > 2 || splits < 0 || splits > 64) return ECOSPA_ERR_SHAPE;
+  if (M < 1 || N < 1 || K < 1 || tile < 0 || tile > 10 + GEMM_PIPE_CONFIGS || splits < 0 || splits > 64) return ECOSPA_ERR_SHAPE;
   if (lda < (trans_a ? M : K) || ldb < (trans_b ? N : K) || ldc < N) return ECOSPA_ERR_SHAPE;
   GemmDesc g = gemm_desc(dtype, M, N, K, A, lda, trans_a ? 1 : 0, B, ldb, trans_b ? 1 : 0);
   g.tile = tile;

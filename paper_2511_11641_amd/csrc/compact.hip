@@ -8,7 +8,9 @@
 //            search in the ascending index list), else -1 (pruned)
 // Rows (axis 0) are copied by one wavefront each with 16-byte accesses; for columns (axis 1)
 // each thread owns a fixed set of destination columns, resolves their sources once and then
-// walks down the rows, so that the stores are full 16-byte coalesced writes.
+// walks down the rows, so that the stores are full 16-byte coalesced writes.  A batch of copies
+// (all matrices, biases and tables of a layer) runs as ONE launch: launches of this size are
+// bound by their fixed cost, not by the bytes they move.
 #include "common.h"
 
 struct MapArgs {
@@ -37,114 +39,180 @@ __device__ __forceinline__ long long map_slot(const MapArgs& m, long long s) {
   return static_cast<long long>(g) * m.kp * m.unit + static_cast<long long>(lo) * m.unit + u;
 }
 
+// One mapped copy of a batch; all items of a batch share one launch (block ranges in `blk_begin`).
+#define MAP_MAX_ITEMS 16
+#define MAP_COL_ROWS 4      // rows a column-copy thread keeps in flight
+struct MapItemDev {
+  const void* src;
+  void* dst;
+  MapArgs m;
+  long long dst_slots, other, ld_src, ld_dst;
+  int esize;      // 2 or 4 bytes per element
+  int axis;
+  int vec;        // 16-byte accesses are legal
+  int gx;         // axis 1: blocks along the destination columns
+  int rpb;        // axis 1: rows per block
+  int blk_begin;  // first block of this item
+};
+struct MapBatch {
+  int n_items;
+  MapItemDev it[MAP_MAX_ITEMS];
+};
+
 // ---- axis 0: one wavefront per destination row ------------------------------------------------
-template <typename E, bool VEC>
-__global__ __launch_bounds__(256) void map_rows_kernel(const E* __restrict__ src, E* __restrict__ dst, MapArgs m,
-                                                       long long dst_rows, long long cols, long long ld_src,
-                                                       long long ld_dst) {
+template <typename E>
+__device__ __forceinline__ void map_rows_block(const MapItemDev& t, int blk) {
+  const E* __restrict__ src = static_cast<const E*>(t.src);
+  E* __restrict__ dst = static_cast<E*>(t.dst);
   const int lane = threadIdx.x & 63;
-  const long long row = static_cast<long long>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-  if (row >= dst_rows) return;
-  const long long srow = map_slot(m, row);
-  E* d = dst + row * ld_dst;
-  if (VEC) {
+  const long long row = static_cast<long long>(blk) * 4 + (threadIdx.x >> 6);
+  if (row >= t.dst_slots) return;
+  const long long srow = map_slot(t.m, row);
+  const long long cols = t.other;
+  E* d = dst + row * t.ld_dst;
+  if (t.vec) {
     constexpr int V = 16 / sizeof(E);
     const uint4 zero = make_uint4(0, 0, 0, 0);
     const long long nv = cols / V;
-    const uint4* s4 = srow >= 0 ? reinterpret_cast<const uint4*>(src + srow * ld_src) : nullptr;
+    const uint4* s4 = srow >= 0 ? reinterpret_cast<const uint4*>(src + srow * t.ld_src) : nullptr;
     uint4* d4 = reinterpret_cast<uint4*>(d);
     for (long long c = lane; c < nv; c += 64) d4[c] = s4 ? s4[c] : zero;
-    for (long long c = nv * V + lane; c < cols; c += 64) d[c] = srow >= 0 ? src[srow * ld_src + c] : E(0);
+    for (long long c = nv * V + lane; c < cols; c += 64) d[c] = srow >= 0 ? src[srow * t.ld_src + c] : E(0);
   } else {
-    for (long long c = lane; c < cols; c += 64) d[c] = srow >= 0 ? src[srow * ld_src + c] : E(0);
+    for (long long c = lane; c < cols; c += 64) d[c] = srow >= 0 ? src[srow * t.ld_src + c] : E(0);
   }
 }
 
-// ---- axis 1: thread owns V destination columns, loops over a chunk of rows ----------------------
+// ---- axis 1: a thread owns V destination columns, resolves their sources once and walks down its
+// rows MAP_COL_ROWS at a time (that many independent gathers in flight) ---------------------------
 template <typename E, bool VEC>
-__global__ __launch_bounds__(256) void map_cols_kernel(const E* __restrict__ src, E* __restrict__ dst, MapArgs m,
-                                                       long long rows, long long dst_cols, long long ld_src,
-                                                       long long ld_dst, int rows_per_block) {
+__device__ __forceinline__ void map_cols_block(const MapItemDev& t, int blk) {
   constexpr int V = VEC ? 16 / sizeof(E) : 1;
-  const long long c0 = (static_cast<long long>(blockIdx.x) * 256 + threadIdx.x) * V;
-  if (c0 >= dst_cols) return;
+  const E* __restrict__ src = static_cast<const E*>(t.src);
+  E* __restrict__ dst = static_cast<E*>(t.dst);
+  const int bx = blk % t.gx, by = blk / t.gx;
+  const long long c0 = (static_cast<long long>(bx) * 256 + threadIdx.x) * V;
+  if (c0 >= t.dst_slots) return;
   long long sc[V];
 #pragma unroll
-  for (int v = 0; v < V; ++v) sc[v] = (c0 + v < dst_cols) ? map_slot(m, c0 + v) : -1;
-  const long long r0 = static_cast<long long>(blockIdx.y) * rows_per_block;
-  const long long r1 = (r0 + rows_per_block < rows) ? r0 + rows_per_block : rows;
-  const bool full = c0 + V <= dst_cols;
-  for (long long r = r0; r < r1; ++r) {
-    const E* s = src + r * ld_src;
-    alignas(16) E vals[V];
+  for (int v = 0; v < V; ++v) sc[v] = (c0 + v < t.dst_slots) ? map_slot(t.m, c0 + v) : -1;
+  const long long r0 = static_cast<long long>(by) * t.rpb;
+  const long long r1 = (r0 + t.rpb < t.other) ? r0 + t.rpb : t.other;
+  const bool full = c0 + V <= t.dst_slots;
+  for (long long rb = r0; rb < r1; rb += MAP_COL_ROWS) {
+    alignas(16) E vals[MAP_COL_ROWS][V];
 #pragma unroll
-    for (int v = 0; v < V; ++v) vals[v] = sc[v] >= 0 ? s[sc[v]] : E(0);
-    E* d = dst + r * ld_dst + c0;
-    if (VEC && full) {
-      *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(vals);
-    } else {
+    for (int q = 0; q < MAP_COL_ROWS; ++q) {
+      const long long r = (rb + q < r1) ? rb + q : r1 - 1;
+      const E* s = src + r * t.ld_src;
 #pragma unroll
-      for (int v = 0; v < V; ++v)
-        if (c0 + v < dst_cols) d[v] = vals[v];
+      for (int v = 0; v < V; ++v) vals[q][v] = sc[v] >= 0 ? s[sc[v]] : E(0);
+    }
+#pragma unroll
+    for (int q = 0; q < MAP_COL_ROWS; ++q) {
+      if (rb + q >= r1) break;
+      E* d = dst + (rb + q) * t.ld_dst + c0;
+      if (VEC && full) {
+        *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(vals[q]);
+      } else {
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+          if (c0 + v < t.dst_slots) d[v] = vals[q][v];
+      }
     }
   }
 }
 
-template <typename E>
-static int launch_map(ecospa_ctx* ctx, const void* src, void* dst, int axis, const MapArgs& m, long long dst_slots,
-                      long long other, long long ld_src, long long ld_dst) {
-  const E* s = static_cast<const E*>(src);
-  E* d = static_cast<E*>(dst);
-  constexpr int V = 16 / sizeof(E);
-  if (axis == 0) {
-    const bool vec = aligned16(src) && aligned16(dst) && ld_src % V == 0 && ld_dst % V == 0;
-    const unsigned grid = static_cast<unsigned>((dst_slots + 3) / 4);
-    if (vec)
-      hipLaunchKernelGGL((map_rows_kernel<E, true>), dim3(grid), dim3(256), 0, ctx->stream, s, d, m, dst_slots, other,
-                         ld_src, ld_dst);
-    else
-      hipLaunchKernelGGL((map_rows_kernel<E, false>), dim3(grid), dim3(256), 0, ctx->stream, s, d, m, dst_slots, other,
-                         ld_src, ld_dst);
+__global__ __launch_bounds__(256) void map_batch_kernel(const MapBatch b) {
+  const int blk = blockIdx.x;
+  int i = 0;
+  while (i + 1 < b.n_items && blk >= b.it[i + 1].blk_begin) ++i;
+  const MapItemDev& t = b.it[i];
+  const int local = blk - t.blk_begin;
+  if (t.axis == 0) {
+    if (t.esize == 2) map_rows_block<bf16_t>(t, local);
+    else map_rows_block<float>(t, local);
+  } else if (t.esize == 2) {
+    if (t.vec) map_cols_block<bf16_t, true>(t, local);
+    else map_cols_block<bf16_t, false>(t, local);
   } else {
-    const bool vec = aligned16(dst) && ld_dst % V == 0;
-    const int vv = vec ? V : 1;
-    const unsigned gx = static_cast<unsigned>((dst_slots + 256ll * vv - 1) / (256ll * vv));
-    // enough row chunks to fill the chip, at least 8 rows each
-    int rpb = 8;
-    while (rpb < 64 && (other + rpb - 1) / rpb * gx > 4096) rpb *= 2;
-    const unsigned gy = static_cast<unsigned>((other + rpb - 1) / rpb);
-    if (vec)
-      hipLaunchKernelGGL((map_cols_kernel<E, true>), dim3(gx, gy), dim3(256), 0, ctx->stream, s, d, m, other, dst_slots,
-                         ld_src, ld_dst, rpb);
-    else
-      hipLaunchKernelGGL((map_cols_kernel<E, false>), dim3(gx, gy), dim3(256), 0, ctx->stream, s, d, m, other,
-                         dst_slots, ld_src, ld_dst, rpb);
+    if (t.vec) map_cols_block<float, true>(t, local);
+    else map_cols_block<float, false>(t, local);
   }
-  ECOSPA_CHECK_LAUNCH(ctx, "map kernel");
+}
+
+static int validate_map(const ecospa_map_item& q) {
+  if (!q.src || !q.dst || !q.idx) return ECOSPA_ERR_NULL;
+  if (!dtype_ok(q.dtype)) return ECOSPA_ERR_DTYPE;
+  if (q.axis != 0 && q.axis != 1) return ECOSPA_ERR_SHAPE;
+  if (q.groups < 1 || q.n < 1 || q.unit < 1 || q.n % q.unit || q.other_extent < 1) return ECOSPA_ERR_SHAPE;
+  if (q.k < 1 || q.k > q.n / q.unit || q.kp < q.k) return ECOSPA_ERR_K;
+  const long long full_slots = static_cast<long long>(q.groups) * q.n;
+  const long long cmp_slots = static_cast<long long>(q.groups) * q.kp * q.unit;
+  if (full_slots > (1ll << 31) - 1 || cmp_slots > (1ll << 31) - 1) return ECOSPA_ERR_SHAPE;
+  const long long src_slots = q.scatter ? cmp_slots : full_slots;
+  const long long dst_slots = q.scatter ? full_slots : cmp_slots;
+  if (q.axis == 0) {
+    if (q.ld_src < q.other_extent || q.ld_dst < q.other_extent) return ECOSPA_ERR_SHAPE;
+  } else {
+    if (q.ld_src < src_slots || q.ld_dst < dst_slots) return ECOSPA_ERR_SHAPE;
+  }
+  return ECOSPA_OK;
+}
+
+extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* items, int n_items) {
+  if (!ctx || !items) return ECOSPA_ERR_NULL;
+  if (n_items < 1) return ECOSPA_ERR_SHAPE;
+  for (int i = 0; i < n_items; ++i) {
+    const int rc = validate_map(items[i]);
+    if (rc) return rc;
+  }
+  for (int first = 0; first < n_items; first += MAP_MAX_ITEMS) {
+    MapBatch b;
+    memset(&b, 0, sizeof(b));
+    b.n_items = n_items - first < MAP_MAX_ITEMS ? n_items - first : MAP_MAX_ITEMS;
+    long long blk = 0;
+    for (int i = 0; i < b.n_items; ++i) {
+      const ecospa_map_item& q = items[first + i];
+      MapItemDev& t = b.it[i];
+      t.src = q.src; t.dst = q.dst;
+      t.m = MapArgs{q.idx, q.groups, q.n, q.unit, q.k, q.kp, q.scatter ? 1 : 0};
+      const long long full_slots = static_cast<long long>(q.groups) * q.n;
+      const long long cmp_slots = static_cast<long long>(q.groups) * q.kp * q.unit;
+      t.dst_slots = q.scatter ? full_slots : cmp_slots;
+      t.other = q.other_extent; t.ld_src = q.ld_src; t.ld_dst = q.ld_dst;
+      t.esize = static_cast<int>(dtype_size(q.dtype));
+      t.axis = q.axis;
+      const int V = 16 / t.esize;
+      t.blk_begin = static_cast<int>(blk);
+      if (q.axis == 0) {
+        t.vec = aligned16(q.src) && aligned16(q.dst) && q.ld_src % V == 0 && q.ld_dst % V == 0;
+        blk += (t.dst_slots + 3) / 4;
+      } else {
+        t.vec = aligned16(q.dst) && q.ld_dst % V == 0;
+        const int vv = t.vec ? V : 1;
+        t.gx = static_cast<int>((t.dst_slots + 256ll * vv - 1) / (256ll * vv));
+        // enough row chunks to fill the chip, at least MAP_COL_ROWS rows each
+        int rpb = MAP_COL_ROWS;
+        while (rpb < 64 && (q.other_extent + rpb - 1) / rpb * t.gx > 4096) rpb *= 2;
+        t.rpb = rpb;
+        blk += (q.other_extent + rpb - 1) / rpb * t.gx;
+      }
+      if (blk > (1ll << 30)) return ECOSPA_ERR_SHAPE;
+    }
+    hipLaunchKernelGGL(map_batch_kernel, dim3(static_cast<unsigned>(blk)), dim3(256), 0, ctx->stream, b);
+    ECOSPA_CHECK_LAUNCH(ctx, "map_batch_kernel");
+  }
   return ECOSPA_OK;
 }
 
 static int mapped_copy(ecospa_ctx* ctx, const void* src, void* dst, int dtype, int axis, int groups, int n, int unit,
                        int k, int kp, long long other, long long ld_src, long long ld_dst, const int* idx,
                        int scatter) {
-  if (!ctx || !src || !dst || !idx) return ECOSPA_ERR_NULL;
-  if (!dtype_ok(dtype)) return ECOSPA_ERR_DTYPE;
-  if (axis != 0 && axis != 1) return ECOSPA_ERR_SHAPE;
-  if (groups < 1 || n < 1 || unit < 1 || n % unit || other < 1) return ECOSPA_ERR_SHAPE;
-  if (k < 1 || k > n / unit || kp < k) return ECOSPA_ERR_K;
-  const long long full_slots = static_cast<long long>(groups) * n;
-  const long long cmp_slots = static_cast<long long>(groups) * kp * unit;
-  if (full_slots > (1ll << 31) - 1 || cmp_slots > (1ll << 31) - 1) return ECOSPA_ERR_SHAPE;
-  const long long src_slots = scatter ? cmp_slots : full_slots;
-  const long long dst_slots = scatter ? full_slots : cmp_slots;
-  if (axis == 0) {
-    if (ld_src < other || ld_dst < other) return ECOSPA_ERR_SHAPE;
-  } else {
-    if (ld_src < src_slots || ld_dst < dst_slots) return ECOSPA_ERR_SHAPE;
-  }
-  MapArgs m{idx, groups, n, unit, k, kp, scatter};
-  if (dtype == ECOSPA_BF16) return launch_map<bf16_t>(ctx, src, dst, axis, m, dst_slots, other, ld_src, ld_dst);
-  return launch_map<float>(ctx, src, dst, axis, m, dst_slots, other, ld_src, ld_dst);
+  ecospa_map_item q;
+  q.src = src; q.dst = dst; q.dtype = dtype; q.axis = axis; q.groups = groups; q.n = n; q.unit = unit; q.k = k;
+  q.kp = kp; q.other_extent = other; q.ld_src = ld_src; q.ld_dst = ld_dst; q.idx = idx; q.scatter = scatter;
+  return ecospa_compact_batch(ctx, &q, 1);
 }
 
 extern "C" int ecospa_compact(ecospa_ctx* ctx, const void* src, void* dst, int dtype, int axis, int groups, int n,

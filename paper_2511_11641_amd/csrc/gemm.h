@@ -39,18 +39,42 @@ struct GemmDesc {
   int tile;          // 0 = choose, 1 = 128x128 workgroup tiles, 2 = 256x256
   int splits;        // > 1: split K, fp32 partials in `partial`, reduced in a fixed order
   float* partial;    // [splits][M][N] when splits > 1
+  int defer_reduce;  // splits > 1: only write the partials; the caller runs ecospa_gemm_reduce later
   GemmEpi epi;
 };
 
 // Launch on ctx->stream.  bf16 runs on MFMA tiles; fp32 on a vector-ALU tile kernel.
 int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d);
+// Second half of a split-K contraction launched with defer_reduce: fixed-order sum of the partials,
+// then the epilogue.  Same descriptor as the first half.
+int ecospa_gemm_reduce(ecospa_ctx* ctx, const GemmDesc& d);
 // How many K splits a (M, N, K) problem should use to fill the chip, and the bytes of partials.
 int ecospa_gemm_splits(int M, int N, int K);
 
-// out[n] = sum_m X[m, n] for n < N (bias gradients); deterministic two-stage reduction.
-// partial: float[ecospa_colsum_chunks(M)][N].
-int ecospa_colsum_chunks(int M);
-int ecospa_colsum(ecospa_ctx* ctx, int dtype, const void* X, long long ldx, int M, int N, float* partial, void* out);
+// Software-pipelined kernel for full K slabs (gemm_pipe.hip): configurations 0 .. GEMM_PIPE_CONFIGS-1
+// differ in workgroup tile, slab depth and LDS ring length; d.tile = 10 + configuration forces one.
+#define GEMM_PIPE_CONFIGS 7
+bool gemm_pipe_ok(const GemmDesc& d, int cfg, int k_chunk);
+hipError_t gemm_pipe_launch(ecospa_ctx* ctx, const GemmDesc& d, int cfg, int k_chunk);
+int gemm_pipe_bk(int cfg);
+
+// The small jobs that follow the contractions of a backward pass, batched into ONE launch (each of
+// them alone would be bound by the fixed cost of a launch): fixed-order reductions of split-K
+// partials (a GemmDesc launched with defer_reduce) and bias gradients out[n] = sum_m X[m, n].
+// A column sum is done by one workgroup per strip of columns over all rows - no second pass.
+#define AUX_MAX_JOBS 4
+struct AuxColsum {
+  const void* X;
+  long long ldx;
+  int M, N, dtype;
+  void* out;
+};
+struct AuxBatch {
+  int n_reduce, n_colsum;
+  GemmDesc reduce[AUX_MAX_JOBS];
+  AuxColsum colsum[AUX_MAX_JOBS];
+};
+int ecospa_aux_launch(ecospa_ctx* ctx, const AuxBatch& b);
 
 // Activation helpers shared by the epilogues and the elementwise kernels.
 #ifdef __HIPCC__

@@ -5,96 +5,7 @@
 //       is the slow storage axis (dY W, dY^T X) are transposed in registers on the way to LDS.
 // fp32: 64x64x16 vector-ALU tiles (the fp32 configuration is small and launch bound).
 // Split-K writes fp32 partials that a second kernel adds in a fixed order (deterministic dW).
-#include "gemm.h"
-
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-// ---------------------------------------------------------------------------------------------
-// epilogue
-// ---------------------------------------------------------------------------------------------
-template <typename T>
-__device__ __forceinline__ void epi_apply(const GemmEpi& e, int m, int n, float acc) {
-  T* c = static_cast<T*>(e.c);
-  const long long off = static_cast<long long>(m) * e.ldc + n;
-  switch (e.kind) {
-    case EPI_STORE: {
-      if (e.bias) acc += load_f32<T>(static_cast<const T*>(e.bias) + n);
-      store_f32<T>(c + off, acc);
-    } break;
-    case EPI_BIAS_ACT: {
-      if (e.bias) acc += load_f32<T>(static_cast<const T*>(e.bias) + n);
-      store_f32<T>(c + off, acc);
-      store_f32<T>(static_cast<T*>(e.c2) + static_cast<long long>(m) * e.ldc2 + n, act_gelu(acc, e.act));
-    } break;
-    case EPI_DACT: {
-      const float h = load_f32<T>(static_cast<const T*>(e.h) + static_cast<long long>(m) * e.ldh + n);
-      store_f32<T>(c + off, acc * act_gelu_grad(h, e.act));
-    } break;
-    case EPI_DSWIGLU: {
-      const T* hp = static_cast<const T*>(e.h) + static_cast<long long>(m) * e.ldh + n;
-      const float g = load_f32<T>(hp), u = load_f32<T>(hp + e.kp);
-      const float sg = act_sigmoid(g);
-      store_f32<T>(c + off, acc * u * sg * (1.f + g * (1.f - sg)));
-      store_f32<T>(c + off + e.kp, acc * g * sg);
-    } break;
-  }
-}
-
-// 8 consecutive columns of one row, bf16 storage, 16-byte aligned (N, ld* multiples of 8)
-__device__ __forceinline__ void unpack8(const uint4& u, float (&f)[8]) {
-  const uint32_t w[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    f[2 * i] = __uint_as_float(w[i] << 16);
-    f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-  }
-}
-__device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
-  typedef float floatx8 __attribute__((ext_vector_type(8)));
-  floatx8 v;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) v[i] = f[i];
-  const bf16x8_t b = __builtin_convertvector(v, bf16x8_t);   // round to nearest even (v_cvt_pk_bf16_f32)
-  return __builtin_bit_cast(uint4, b);
-}
-__device__ __forceinline__ void epi_apply_vec8(const GemmEpi& e, int m, int n, float (&v)[8]) {
-  bf16_t* c = static_cast<bf16_t*>(e.c) + static_cast<long long>(m) * e.ldc + n;
-  if (e.kind == EPI_STORE || e.kind == EPI_BIAS_ACT) {
-    if (e.bias) {
-      float b[8];
-      unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.bias) + n), b);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] += b[i];
-    }
-    *reinterpret_cast<uint4*>(c) = pack8(v);
-    if (e.kind == EPI_BIAS_ACT) {
-      float a[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) a[i] = act_gelu(v[i], e.act);
-      *reinterpret_cast<uint4*>(static_cast<bf16_t*>(e.c2) + static_cast<long long>(m) * e.ldc2 + n) = pack8(a);
-    }
-  } else if (e.kind == EPI_DACT) {
-    float h[8];
-    unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.h) + static_cast<long long>(m) * e.ldh + n), h);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] *= act_gelu_grad(h[i], e.act);
-    *reinterpret_cast<uint4*>(c) = pack8(v);
-  } else {  // EPI_DSWIGLU
-    const bf16_t* hp = static_cast<const bf16_t*>(e.h) + static_cast<long long>(m) * e.ldh + n;
-    float g[8], u[8], dg[8], du[8];
-    unpack8(*reinterpret_cast<const uint4*>(hp), g);
-    unpack8(*reinterpret_cast<const uint4*>(hp + e.kp), u);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float sg = act_sigmoid(g[i]);
-      dg[i] = v[i] * u[i] * sg * (1.f + g[i] * (1.f - sg));
-      du[i] = v[i] * g[i] * sg;
-    }
-    *reinterpret_cast<uint4*>(c) = pack8(dg);
-    *reinterpret_cast<uint4*>(c + e.kp) = pack8(du);
-  }
-}
+#include "gemm_epi.h"
 
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA kernel, parametrised by the workgroup tile BM x BN and the WGM x WGN grid of wavefronts
@@ -459,6 +370,19 @@ static bool gemm_prefers_big_tile(int M, int N, int splits) {
   return big >= 192;
 }
 
+// Which configuration of the software-pipelined kernel (gemm_pipe.hip) suits a problem, or -1 for the
+// register-staged kernel above.  Measured on the layer shapes (M = tokens = 8192, N and K between 512
+// and 4096) with operands coming from HBM: for K-contiguous operands (x W^T) the largest workgroup
+// tile that still yields about one tile per compute unit wins; with a K-slow operand (dY W, dY^T X)
+// the register-staged kernel is still ahead.
+static int gemm_pipe_choice(const GemmDesc& d) {
+  if (d.trans_a || d.trans_b) return -1;
+  const long long tm256 = (d.M + 255) / 256, t256 = tm256 * ((d.N + 255) / 256), t256x128 = tm256 * ((d.N + 127) / 128);
+  if (t256 >= 192) return 5;      // 256x256, 8 wavefronts
+  if (t256x128 >= 192) return 2;  // 256x128, 3-deep ring
+  return 4;                       // 128x128
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, int WPE>
 static hipError_t launch_tile(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
   const int tm = (d.M + BM - 1) / BM, tn = (d.N + BN - 1) / BN;
@@ -520,7 +444,10 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
     const bool prof = ctx->prof_on && ctx->prof_n < ctx->prof_cap;
     if (prof) (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n], ctx->stream);
     hipError_t le;
-    if (d.tile == 2 || (d.tile == 0 && big)) le = launch_tile<256, 256, 64, 2, 4, 2>(ctx, d, k_chunk);
+    const int k_split = (d.K + splits - 1) / splits;
+    const int cfg = d.tile >= 10 ? d.tile - 10 : (d.tile == 0 ? gemm_pipe_choice(d) : -1);
+    if (cfg >= 0 && gemm_pipe_ok(d, cfg, k_split)) le = gemm_pipe_launch(ctx, d, cfg, k_split);
+    else if (d.tile == 2 || (d.tile != 1 && big)) le = launch_tile<256, 256, 64, 2, 4, 2>(ctx, d, k_chunk);
     else le = launch_tile<128, 128, 64, 2, 2, 2>(ctx, d, k_chunk);
     if (le != hipSuccess) return hip_fail(ctx, le, "gemm launch");
     if (prof) {
@@ -537,98 +464,183 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
   } else {
     return ECOSPA_ERR_DTYPE;
   }
-  if (splits > 1) {
-    const long long tot = static_cast<long long>(d.M) * d.N;
-    const unsigned grid = static_cast<unsigned>((tot + 255) / 256);
-    if (d.dtype == ECOSPA_BF16)
-      hipLaunchKernelGGL(gemm_splitk_reduce_vec8_kernel, dim3(static_cast<unsigned>((tot / 8 + 255) / 256)), dim3(256), 0,
-                         ctx->stream, d);
-    else
-      hipLaunchKernelGGL((gemm_splitk_reduce_kernel<float>), dim3(grid), dim3(256), 0, ctx->stream, d);
-    ECOSPA_CHECK_LAUNCH(ctx, "gemm_splitk_reduce_kernel");
-  }
+  if (splits > 1 && !d.defer_reduce) return ecospa_gemm_reduce(ctx, d);
+  return ECOSPA_OK;
+}
+
+int ecospa_gemm_reduce(ecospa_ctx* ctx, const GemmDesc& d) {
+  if (d.splits <= 1) return ECOSPA_OK;
+  if (!d.partial || !d.epi.c) return ECOSPA_ERR_NULL;
+  const long long tot = static_cast<long long>(d.M) * d.N;
+  if (d.dtype == ECOSPA_BF16)
+    hipLaunchKernelGGL(gemm_splitk_reduce_vec8_kernel, dim3(static_cast<unsigned>((tot / 8 + 255) / 256)), dim3(256), 0,
+                       ctx->stream, d);
+  else
+    hipLaunchKernelGGL((gemm_splitk_reduce_kernel<float>), dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0,
+                       ctx->stream, d);
+  ECOSPA_CHECK_LAUNCH(ctx, "gemm_splitk_reduce_kernel");
   return ECOSPA_OK;
 }
 
 // ---------------------------------------------------------------------------------------------
-// column sums (bias gradients): 8-lane x 32-row-slot tiles with 16-byte loads, then a fixed-order
-// second stage over the row chunks
+// batched tail of a backward pass: split-K reductions and bias-gradient column sums in one launch
 // ---------------------------------------------------------------------------------------------
-#define CS_ROWS 512   // rows per first-stage block
+#define AUX_THREADS 1024
 
-int ecospa_colsum_chunks(int M) { return (M + CS_ROWS - 1) / CS_ROWS; }
+struct AuxBatchDev {
+  AuxBatch b;
+  int blk_begin[2 * AUX_MAX_JOBS + 1];   // column sums first (long dependent chains), then reductions
+};
 
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ X, long long ldx, int M, int N,
-                                                             float* __restrict__ partial) {
+__device__ __forceinline__ void aux_reduce_block(const GemmDesc& d, int blk) {
+  const long long tot = static_cast<long long>(d.M) * d.N;
+  if (sizeof(T) == 2) {      // 8 consecutive columns per thread (N is a multiple of 8)
+    const long long e = (static_cast<long long>(blk) * AUX_THREADS + threadIdx.x) * 8;
+    if (e >= tot) return;
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = 0.f;
+    for (int z0 = 0; z0 < d.splits; z0 += 4) {     // four partials in flight, added in split order
+      float4 lo[4], hi[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const bool on = z0 + q < d.splits;
+        const float* p = d.partial + (on ? z0 + q : z0) * tot + e;
+        lo[q] = *reinterpret_cast<const float4*>(p);
+        hi[q] = *reinterpret_cast<const float4*>(p + 4);
+        if (!on) lo[q] = hi[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        v[0] += lo[q].x; v[1] += lo[q].y; v[2] += lo[q].z; v[3] += lo[q].w;
+        v[4] += hi[q].x; v[5] += hi[q].y; v[6] += hi[q].z; v[7] += hi[q].w;
+      }
+    }
+    epi_apply_vec8(d.epi, static_cast<int>(e / d.N), static_cast<int>(e % d.N), v);
+  } else {
+    const long long e = static_cast<long long>(blk) * AUX_THREADS + threadIdx.x;
+    if (e >= tot) return;
+    float s = 0.f;
+    for (int z = 0; z < d.splits; ++z) s += d.partial[z * tot + e];
+    epi_apply<T>(d.epi, static_cast<int>(e / d.N), static_cast<int>(e % d.N), s);
+  }
+}
+
+// One workgroup sums a strip of AUX_LANES x (16 bytes of columns) over all M rows: the row slots
+// (AUX_THREADS / AUX_LANES of them) walk down the rows with 16-byte loads, several in flight, then
+// the slots are added in a fixed order.  Narrow strips (a quarter of a 128-byte line) give enough
+// workgroups to hide the latency; the four strips of a line are mapped to workgroup ids that differ
+// by 8, 16 and 24, i.e. to the same XCD, so that the line is fetched into one L2 only.
+#define AUX_LANES 2
+template <typename T>
+__device__ __forceinline__ void aux_colsum_block(const AuxColsum& c, int blk, float* lds) {
+  static_assert(AUX_LANES == 2, "four strips of AUX_LANES x 16 bytes make one 128-byte line");
   constexpr int V = 16 / sizeof(T);          // columns per lane
-  __shared__ float lds[32][8 * V + 1];
-  const int slot = threadIdx.x >> 3, l8 = threadIdx.x & 7;   // 32 row slots x 8 lanes
-  const int col0 = blockIdx.x * (8 * V) + l8 * V;
-  const int r0 = blockIdx.y * CS_ROWS, r1 = min(M, r0 + CS_ROWS);
+  constexpr int W = AUX_LANES * V;           // strip width
+  constexpr int SLOTS = AUX_THREADS / AUX_LANES;
+  const T* __restrict__ X = static_cast<const T*>(c.X);
+  const int slot = threadIdx.x / AUX_LANES, ln = threadIdx.x % AUX_LANES;
+  {   // blk -> strip: workgroup ids are dealt round-robin to the 8 XCDs (job ranges start at multiples of 8)
+    const int xcd = blk & 7, t = blk >> 3;
+    blk = (((t >> 2) * 8 + xcd) << 2) + (t & 3);
+  }
+  if (blk * W >= c.N) return;     // padding of the range (whole workgroup)
+  const int col0 = blk * W + ln * V;
   float acc[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) acc[i] = 0.f;
-  const bool vec_ok = (ldx % V == 0) && ((reinterpret_cast<uintptr_t>(X) & 15u) == 0) && col0 + V <= N;
+  const bool vec_ok = (c.ldx % V == 0) && ((reinterpret_cast<uintptr_t>(X) & 15u) == 0) && col0 + V <= c.N;
   if (vec_ok) {
-    for (int r = r0 + slot; r < r1; r += 32) {
-      const uint4 u = *reinterpret_cast<const uint4*>(X + static_cast<long long>(r) * ldx + col0);
-      if (sizeof(T) == 2) {
-        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+    for (int r0 = slot; r0 < c.M; r0 += 8 * SLOTS) {
+      uint4 u[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          acc[(2 * i) % V] += __uint_as_float(w[i] << 16);
-          acc[(2 * i + 1) % V] += __uint_as_float(w[i] & 0xffff0000u);
+      for (int q = 0; q < 8; ++q) {
+        const int r = r0 + q * SLOTS;
+        u[q] = r < c.M ? *reinterpret_cast<const uint4*>(X + static_cast<long long>(r) * c.ldx + col0) : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        if (sizeof(T) == 2) {
+          const uint32_t w[4] = {u[q].x, u[q].y, u[q].z, u[q].w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            acc[(2 * i) % V] += __uint_as_float(w[i] << 16);
+            acc[(2 * i + 1) % V] += __uint_as_float(w[i] & 0xffff0000u);
+          }
+        } else {
+          acc[0] += __uint_as_float(u[q].x); acc[1 % V] += __uint_as_float(u[q].y);
+          acc[2 % V] += __uint_as_float(u[q].z); acc[3 % V] += __uint_as_float(u[q].w);
         }
-      } else {
-        acc[0] += __uint_as_float(u.x); acc[1 % V] += __uint_as_float(u.y);
-        acc[2 % V] += __uint_as_float(u.z); acc[3 % V] += __uint_as_float(u.w);
       }
     }
   } else {
-    for (int r = r0 + slot; r < r1; r += 32)
+    for (int r = slot; r < c.M; r += SLOTS)
 #pragma unroll
       for (int i = 0; i < V; ++i)
-        if (col0 + i < N) acc[i] += load_f32<T>(X + static_cast<long long>(r) * ldx + col0 + i);
+        if (col0 + i < c.N) acc[i] += load_f32<T>(X + static_cast<long long>(r) * c.ldx + col0 + i);
   }
 #pragma unroll
-  for (int i = 0; i < V; ++i) lds[slot][l8 * V + i] = acc[i];
+  for (int i = 0; i < V; ++i) lds[slot * (W + 1) + ln * V + i] = acc[i];
   __syncthreads();
-  if (threadIdx.x < 8 * V) {
-    float s = 0.f;
-#pragma unroll
-    for (int k = 0; k < 32; ++k) s += lds[k][threadIdx.x];
-    const int col = blockIdx.x * (8 * V) + threadIdx.x;
-    if (col < N) partial[static_cast<long long>(blockIdx.y) * N + col] = s;
+  // W columns x 64 groups of SLOTS / 64 slots, then the 64 group sums by one wavefront per column
+  constexpr int GROUPS = 64, PER = SLOTS / GROUPS;
+  float part = 0.f;
+  const int colw = threadIdx.x / GROUPS, grp = threadIdx.x % GROUPS;     // AUX_THREADS == W * 64 for bf16
+  if (colw < W) {
+    for (int k = 0; k < PER; ++k) part += lds[(grp * PER + k) * (W + 1) + colw];
+  }
+  part = wave_sum(part);     // lanes of a wavefront = the 64 groups of one column; fixed order
+  if (colw < W && grp == 0) {
+    const int col = blk * W + colw;
+    if (col < c.N) store_f32<T>(static_cast<T*>(c.out) + col, part);
   }
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ partial, int chunks, int N,
-                                                           T* __restrict__ out) {
-  const int col = blockIdx.x * 256 + threadIdx.x;
-  if (col >= N) return;
-  float s = 0.f;
-  for (int c = 0; c < chunks; ++c) s += partial[static_cast<long long>(c) * N + col];
-  store_f32<T>(out + col, s);
-}
-
-int ecospa_colsum(ecospa_ctx* ctx, int dtype, const void* X, long long ldx, int M, int N, float* partial, void* out) {
-  if (!X || !partial || !out) return ECOSPA_ERR_NULL;
-  const int chunks = ecospa_colsum_chunks(M);
-  const int strip = dtype == ECOSPA_BF16 ? 64 : 32;
-  dim3 g1((N + strip - 1) / strip, chunks), g2((N + 255) / 256);
-  if (dtype == ECOSPA_BF16) {
-    hipLaunchKernelGGL((colsum_partial_kernel<bf16_t>), g1, dim3(256), 0, ctx->stream, static_cast<const bf16_t*>(X), ldx,
-                       M, N, partial);
-    hipLaunchKernelGGL((colsum_final_kernel<bf16_t>), g2, dim3(256), 0, ctx->stream, partial, chunks, N,
-                       static_cast<bf16_t*>(out));
+__global__ __launch_bounds__(AUX_THREADS) void bwd_aux_kernel(const AuxBatchDev a) {
+  __shared__ float lds[(AUX_THREADS / AUX_LANES) * (AUX_LANES * 8 + 1)];
+  const int blk = blockIdx.x;
+  int j = 0;
+  while (blk >= a.blk_begin[j + 1]) ++j;     // blk_begin[n_jobs] = grid size
+  const int local = blk - a.blk_begin[j];
+  if (j < a.b.n_colsum) {
+    const AuxColsum& c = a.b.colsum[j];
+    if (c.dtype == ECOSPA_BF16) aux_colsum_block<bf16_t>(c, local, lds);
+    else aux_colsum_block<float>(c, local, lds);
   } else {
-    hipLaunchKernelGGL((colsum_partial_kernel<float>), g1, dim3(256), 0, ctx->stream, static_cast<const float*>(X), ldx, M,
-                       N, partial);
-    hipLaunchKernelGGL((colsum_final_kernel<float>), g2, dim3(256), 0, ctx->stream, partial, chunks, N,
-                       static_cast<float*>(out));
+    const GemmDesc& d = a.b.reduce[j - a.b.n_colsum];
+    if (d.dtype == ECOSPA_BF16) aux_reduce_block<bf16_t>(d, local);
+    else aux_reduce_block<float>(d, local);
   }
-  ECOSPA_CHECK_LAUNCH(ctx, "colsum kernels");
+}
+
+int ecospa_aux_launch(ecospa_ctx* ctx, const AuxBatch& b) {
+  if (b.n_reduce < 0 || b.n_reduce > AUX_MAX_JOBS || b.n_colsum < 0 || b.n_colsum > AUX_MAX_JOBS) return ECOSPA_ERR_SHAPE;
+  AuxBatchDev a;
+  memset(&a, 0, sizeof(a));
+  a.b = b;
+  long long blk = 0;
+  int j = 0;
+  for (int i = 0; i < b.n_colsum; ++i, ++j) {
+    const AuxColsum& c = b.colsum[i];
+    if (!c.X || !c.out) return ECOSPA_ERR_NULL;
+    if (!dtype_ok(c.dtype) || c.M < 1 || c.N < 1) return ECOSPA_ERR_SHAPE;
+    const int line = 4 * AUX_LANES * (c.dtype == ECOSPA_BF16 ? 8 : 4);   // columns of four strips
+    a.blk_begin[j] = static_cast<int>(blk);                               // a multiple of 32: starts on XCD 0
+    blk += ((c.N + line - 1) / line + 7) / 8 * 32;                        // 8 lines x 4 strips at a time
+  }
+  for (int i = 0; i < b.n_reduce; ++i, ++j) {
+    const GemmDesc& d = b.reduce[i];
+    if (d.splits <= 1 || !d.partial || !d.epi.c) return ECOSPA_ERR_NULL;
+    if (!dtype_ok(d.dtype)) return ECOSPA_ERR_DTYPE;
+    a.blk_begin[j] = static_cast<int>(blk);
+    const long long items = static_cast<long long>(d.M) * d.N / (d.dtype == ECOSPA_BF16 ? 8 : 1);
+    blk += (items + AUX_THREADS - 1) / AUX_THREADS;
+  }
+  if (j == 0) return ECOSPA_OK;
+  if (blk > (1ll << 30)) return ECOSPA_ERR_SHAPE;
+  for (int q = j; q <= 2 * AUX_MAX_JOBS; ++q) a.blk_begin[q] = static_cast<int>(blk);
+  hipLaunchKernelGGL(bwd_aux_kernel, dim3(static_cast<unsigned>(blk)), dim3(AUX_THREADS), 0, ctx->stream, a);
+  ECOSPA_CHECK_LAUNCH(ctx, "bwd_aux_kernel");
   return ECOSPA_OK;
 }

@@ -1,11 +1,11 @@
 // Step 1: per-dimension coupled importance score (paper Eq. 10, criterion of Eq. 12).
 //
 // HBM-bound: every weight element of every pair in the batch is read exactly once with
-// 16-byte loads.  Three launches per batch of up to SCORE_MAX_PAIRS pairs:
-//   1. score_sumsq_kernel   - squared row norms (wave per row, shuffle reduction) and partial
-//                             squared column norms (16-lane x 16-row-slot tiles, LDS reduction)
-//   2. score_combine_kernel - one thread per unit: add the partials, r = |a||b|
-//   3. score_normalise_kernel - one workgroup per (pair, group): group L2 norm, normalised scores
+// 16-byte loads.  Two launches per batch of up to SCORE_MAX_PAIRS pairs:
+//   1. score_sumsq_kernel  - squared row norms (wave per row, shuffle reduction) and partial
+//                            squared column norms (16-lane x 16-row-slot tiles, LDS reduction)
+//   2. score_finish_kernel - one workgroup per (pair, group): add the partials, r = |a||b|,
+//                            group L2 norm, normalised scores
 // No floating-point atomics; all reduction orders are fixed.
 #include "common.h"
 
@@ -29,8 +29,7 @@ struct ScorePairDev {
   int n_chunks, rc;            // column kernel: chunks of rc rows of w2
   int n_strips;                // column strips of 16 lanes * VEC columns
   int blk_row1, blk_row2, blk_col, blk_end;   // first block index of each phase in launch 1
-  int comb_begin;              // first block index of this pair in launch 2 (one thread per unit)
-  int fin_begin;               // first block index of this pair in launch 3 (one workgroup per group)
+  int fin_begin;               // first block index of this pair in launch 2 (one workgroup per group)
 };
 struct ScoreBatch {
   int n_pairs;
@@ -164,34 +163,13 @@ __global__ __launch_bounds__(256) void score_sumsq_kernel(const ScoreBatch b) {
   else score_block<float>(p, blk, lds);
 }
 
-// Launch 2: one thread per unit adds the column-norm partials in chunk order and writes the
-// un-normalised r = |a| |b| of the unit.
-__global__ __launch_bounds__(256) void score_combine_kernel(const ScoreBatch b) {
-  const int blk = blockIdx.x;
-  int pi = 0;
-  while (pi + 1 < b.n_pairs && blk >= b.p[pi + 1].comb_begin) ++pi;
-  const ScorePairDev& p = b.p[pi];
-  const int nu_all = p.rows / p.unit;
-  const int u = (blk - p.comb_begin) * 256 + threadIdx.x;
-  if (u >= nu_all) return;
-  float a = 0.f, bsum = 0.f;
-  for (int j = 0; j < p.unit; ++j) {
-    const int row = u * p.unit + j;
-    a += p.a_sq[row];
-    if (p.kind == ECOSPA_PAIR_QK) {
-      bsum += p.b_sq[row];
-    } else {
-      float s = 0.f;
-      for (int c = 0; c < p.n_chunks; ++c) s += p.b_part[static_cast<long long>(c) * p.rows + row];
-      bsum += s;
-    }
-  }
-  p.scores[u] = sqrtf(a) * sqrtf(bsum);
-}
-
-// Launch 3: one workgroup per (pair, group): L2 norm of r over the group (fixed order), then divide.
-__global__ __launch_bounds__(256) void score_normalise_kernel(const ScoreBatch b) {
-  __shared__ float red[4];
+// Launch 2: one workgroup per (pair, group).  Every thread finishes its units (adds the column-norm
+// partials in chunk order, r = |a| |b|), the group's L2 norm of r is reduced in a fixed order, and
+// the normalised scores are written.
+#define SCORE_FIN_THREADS 1024
+#define SCORE_MAX_CHUNKS 16       // col_chunk_rows() never makes more
+__global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_kernel(const ScoreBatch b) {
+  __shared__ float red[SCORE_FIN_THREADS / 64];
   const int blk = blockIdx.x;
   int pi = 0;
   while (pi + 1 < b.n_pairs && blk >= b.p[pi + 1].fin_begin) ++pi;
@@ -201,16 +179,37 @@ __global__ __launch_bounds__(256) void score_normalise_kernel(const ScoreBatch b
   const int tid = threadIdx.x;
   float* out = p.scores + static_cast<long long>(g) * nu;
   float sq = 0.f;
-  for (int u = tid; u < nu; u += 256) {
-    const float r = out[u];
+  for (int u = tid; u < nu; u += SCORE_FIN_THREADS) {
+    float a = 0.f, bsum = 0.f;
+    for (int j = 0; j < p.unit; ++j) {
+      const int row = (g * nu + u) * p.unit + j;
+      a += p.a_sq[row];
+      if (p.kind == ECOSPA_PAIR_QK) {
+        bsum += p.b_sq[row];
+      } else {
+        // all chunk partials of this row are fetched at once, then added in chunk order
+        float part[SCORE_MAX_CHUNKS];
+#pragma unroll
+        for (int c = 0; c < SCORE_MAX_CHUNKS; ++c)
+          part[c] = c < p.n_chunks ? p.b_part[static_cast<long long>(c) * p.rows + row] : 0.f;
+        float s = 0.f;
+#pragma unroll
+        for (int c = 0; c < SCORE_MAX_CHUNKS; ++c) s += part[c];
+        bsum += s;
+      }
+    }
+    const float r = sqrtf(a) * sqrtf(bsum);
+    out[u] = r;          // re-read below by the same thread
     sq += r * r;
   }
   sq = wave_sum(sq);
   if ((tid & 63) == 0) red[tid >> 6] = sq;
   __syncthreads();
-  const float tot = (red[0] + red[1]) + (red[2] + red[3]);
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < SCORE_FIN_THREADS / 64; ++w) tot += red[w];
   const float nrm = sqrtf(tot);
-  for (int u = tid; u < nu; u += 256) out[u] = nrm > 0.f ? out[u] / nrm : 0.f;
+  for (int u = tid; u < nu; u += SCORE_FIN_THREADS) out[u] = nrm > 0.f ? out[u] / nrm : 0.f;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -272,7 +271,7 @@ extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, i
     ScoreBatch b;
     memset(&b, 0, sizeof(b));
     b.n_pairs = (n_pairs - first < SCORE_MAX_PAIRS) ? n_pairs - first : SCORE_MAX_PAIRS;
-    int blk = 0, fin = 0, comb = 0;
+    int blk = 0, fin = 0;
     for (int i = 0; i < b.n_pairs; ++i) {
       const ecospa_pair& q = pairs[first + i];
       ScorePairDev& p = b.p[i];
@@ -302,18 +301,14 @@ extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, i
         blk += p.n_strips * p.n_chunks;
       }
       p.blk_end = blk;
-      p.comb_begin = comb;
-      comb += (p.rows / p.unit + 255) / 256;
       p.fin_begin = fin;
       fin += q.groups;
     }
     if (!ws.ok()) return ECOSPA_ERR_WORKSPACE;
     hipLaunchKernelGGL(score_sumsq_kernel, dim3(blk), dim3(256), 0, ctx->stream, b);
     ECOSPA_CHECK_LAUNCH(ctx, "score_sumsq_kernel");
-    hipLaunchKernelGGL(score_combine_kernel, dim3(comb), dim3(256), 0, ctx->stream, b);
-    ECOSPA_CHECK_LAUNCH(ctx, "score_combine_kernel");
-    hipLaunchKernelGGL(score_normalise_kernel, dim3(fin), dim3(256), 0, ctx->stream, b);
-    ECOSPA_CHECK_LAUNCH(ctx, "score_normalise_kernel");
+    hipLaunchKernelGGL(score_finish_kernel, dim3(fin), dim3(SCORE_FIN_THREADS), 0, ctx->stream, b);
+    ECOSPA_CHECK_LAUNCH(ctx, "score_finish_kernel");
   }
   return ECOSPA_OK;
 }

@@ -29,8 +29,9 @@ class FfnBlock:
     def score(self) -> torch.Tensor:
         return self.ctx.ecospa_coupled_score([self.pair()])[0]
 
-    def compact(self, idx: torch.Tensor):
-        """Gather the kept rows/columns named by idx[1, k] into the padded compact layout."""
+    def compact(self, idx: torch.Tensor, defer: bool = False):
+        """Gather the kept rows/columns named by idx[1, k] into the padded compact layout (one launch).
+        With defer=True the gather descriptors are returned instead, for a larger batch."""
         c, k = self.ctx, idx.shape[1]
         self.idx, self.k = idx, k
         self.kp = kp = B.round_up(k, 16)
@@ -40,12 +41,16 @@ class FfnBlock:
             self.w1_c = torch.empty((nh, self.d), dtype=dt, device=dev)
             self.b1_c = None if self.b1 is None else torch.zeros((nh,), dtype=dt, device=dev)
             self.w2_c = torch.empty((self.d, kp), dtype=dt, device=dev)
-        c.ecospa_compact(self.w1, idx, 0, 1, self.n, 1, kp, out=self.w1_c[:kp])
+        mk = B.Context.map_item
+        items = [mk(self.w1, self.w1_c[:kp], idx, 0, 1, self.n, 1, kp)]
         if self.gated:
-            c.ecospa_compact(self.w1b, idx, 0, 1, self.n, 1, kp, out=self.w1_c[kp:])
+            items.append(mk(self.w1b, self.w1_c[kp:], idx, 0, 1, self.n, 1, kp))
         if self.b1 is not None:       # the up branch of a gated FFN has no bias: its slots stay zero
-            c.ecospa_compact(self.b1, idx, 1, 1, self.n, 1, kp, out=self.b1_c[:kp])
-        c.ecospa_compact(self.w2, idx, 1, 1, self.n, 1, kp, out=self.w2_c)
+            items.append(mk(self.b1, self.b1_c[:kp], idx, 1, 1, self.n, 1, kp))
+        items.append(mk(self.w2, self.w2_c, idx, 1, 1, self.n, 1, kp))
+        if defer:
+            return items
+        c.ecospa_compact_batch(items)
         return self
 
     def desc(self, Bsz: int, L: int) -> B.BlockDesc:
@@ -103,7 +108,7 @@ class AttnBlock:
     def score(self):
         return self.ctx.ecospa_coupled_score(self.pairs())
 
-    def compact(self, idx_qk: torch.Tensor, idx_vo: torch.Tensor):
+    def compact(self, idx_qk: torch.Tensor, idx_vo: torch.Tensor, defer: bool = False):
         c, h, dh, u = self.ctx, self.h, self.d_h, self.unit
         self.idx_qk, self.idx_vo = idx_qk, idx_vo
         self.k_qk_units, self.k_vo = idx_qk.shape[1], idx_vo.shape[1]
@@ -116,19 +121,21 @@ class AttnBlock:
             self.wqkv_c = torch.empty((2 * nq + nv, self.d), dtype=dt, device=dev)
             self.bqkv_c = None if self.bq is None else torch.empty((2 * nq + nv,), dtype=dt, device=dev)
             self.wo_c = torch.empty((self.d, nv), dtype=dt, device=dev)
-        c.ecospa_compact(self.wq, idx_qk, 0, h, dh, u, kpu, out=self.wqkv_c[:nq])
-        c.ecospa_compact(self.wk, idx_qk, 0, h, dh, u, kpu, out=self.wqkv_c[nq:2 * nq])
-        c.ecospa_compact(self.wv, idx_vo, 0, h, dh, 1, self.kp_vo, out=self.wqkv_c[2 * nq:])
+        mk = B.Context.map_item
+        items = [mk(self.wq, self.wqkv_c[:nq], idx_qk, 0, h, dh, u, kpu),
+                 mk(self.wk, self.wqkv_c[nq:2 * nq], idx_qk, 0, h, dh, u, kpu),
+                 mk(self.wv, self.wqkv_c[2 * nq:], idx_vo, 0, h, dh, 1, self.kp_vo)]
         if self.bq is not None:
-            c.ecospa_compact(self.bq, idx_qk, 1, h, dh, u, kpu, out=self.bqkv_c[:nq])
-            c.ecospa_compact(self.bk, idx_qk, 1, h, dh, u, kpu, out=self.bqkv_c[nq:2 * nq])
-            c.ecospa_compact(self.bv, idx_vo, 1, h, dh, 1, self.kp_vo, out=self.bqkv_c[2 * nq:])
-        c.ecospa_compact(self.wo, idx_vo, 1, h, dh, 1, self.kp_vo, out=self.wo_c)
+            items += [mk(self.bq, self.bqkv_c[:nq], idx_qk, 1, h, dh, u, kpu),
+                      mk(self.bk, self.bqkv_c[nq:2 * nq], idx_qk, 1, h, dh, u, kpu),
+                      mk(self.bv, self.bqkv_c[2 * nq:], idx_vo, 1, h, dh, 1, self.kp_vo)]
+        items.append(mk(self.wo, self.wo_c, idx_vo, 1, h, dh, 1, self.kp_vo))
+        if not defer:
+            c.ecospa_compact_batch(items)
         if self.rope and getattr(self, "cos", None) is not None:     # kept blocks changed: new frequencies
-            cos, sin = c.ecospa_rope_table(idx_qk, h, self._L, self.k_qk_units, self.kp_qk // 2, dh, self.rope_base)
-            self.cos.copy_(cos)
-            self.sin.copy_(sin)
-        return self
+            c.ecospa_rope_table(idx_qk, h, self._L, self.k_qk_units, self.kp_qk // 2, dh, self.rope_base,
+                                out=(self.cos, self.sin))
+        return items if defer else self
 
     def alloc(self, Bsz: int, L: int):
         c, h = self.ctx, self.h

@@ -70,3 +70,23 @@ def test_contract_alignment_errors(ctx):
     with pytest.raises(B.EcospaError) as e:
         ctx.ecospa_contract(a, False, b, False, splits=1)
     assert e.value.code == B.ERR_ALIGN
+
+
+@pytest.mark.parametrize("cfg", range(7))
+@pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, True)])
+@pytest.mark.parametrize("M,N,K", [(520, 264, 192), (256, 512, 64), (304, 136, 512)])
+def test_contract_bf16_pipelined_tiles(ctx, M, N, K, ta, tb, cfg):
+    """Every configuration of the software-pipelined kernel (tile = 10 + cfg): ragged M and N, one slab
+    (shorter than the LDS ring), a few slabs (ring wrap-around) and many."""
+    a, b, bias, want = _operands(45, M, N, K, ta, tb, "bf16")
+    got = ctx.ecospa_contract(dev(a, "bf16"), ta, dev(b, "bf16"), tb, dev(bias, "bf16"), tile=10 + cfg, splits=1)
+    assert_close(got, want, "bf16", f"pipelined cfg {cfg}")
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 4])
+def test_contract_bf16_pipelined_split_k(ctx, cfg):
+    a, b, bias, want = _operands(46, 264, 520, 1024, True, True, "bf16")
+    got = ctx.ecospa_contract(dev(a, "bf16"), True, dev(b, "bf16"), True, dev(bias, "bf16"), tile=10 + cfg, splits=4)
+    assert_close(got, want, "bf16", "split k")
+    again = ctx.ecospa_contract(dev(a, "bf16"), True, dev(b, "bf16"), True, dev(bias, "bf16"), tile=10 + cfg, splits=4)
+    assert torch.equal(got, again)

@@ -172,3 +172,35 @@ def test_rope_table(ctx):
     np.testing.assert_allclose(host(cos)[:, :, :3], np.cos(ang), atol=2e-7)
     np.testing.assert_allclose(host(sin)[:, :, :3], np.sin(ang), atol=2e-7)
     assert torch.all(cos[:, :, 3] == 1) and torch.all(sin[:, :, 3] == 0)
+
+
+def test_select_and_compact_batches_match_single_calls(ctx):
+    """The one-launch batch entry points give bit-identical results to item-by-item calls."""
+    rng = np.random.default_rng(5)
+    shapes = [(16, 64, 32), (3, 100, 37), (1, 4096, 2048), (2, 5461, 2730), (1, 7, 7)]
+    scores = [torch.from_numpy(rng.standard_normal((g, n)).astype(np.float32)).cuda() for g, n, _ in shapes]
+    scores[1][:, 10:20] = scores[1][:, 30:40]          # exact ties
+    single = [ctx.ecospa_select_topk(s, k) for s, (_, _, k) in zip(scores, shapes)]
+    outs = [torch.empty_like(i) for i in single]
+    ctx.ecospa_select_topk_batch([ctx.select_item(s, k, o) for s, (_, _, k), o in zip(scores, shapes, outs)])
+    for a, b, s, (_, _, k) in zip(single, outs, scores, shapes):
+        assert torch.equal(a, b)
+        assert np.array_equal(b.cpu().numpy(), O.select_topk(s.cpu().numpy(), k))
+    # gathers and a scatter of different dtypes / axes in one launch
+    g, n, k = shapes[0]
+    idx = single[0]
+    w_rows = torch.randn(g * n, 72, device="cuda").to(torch.bfloat16)
+    w_cols = torch.randn(40, g * n, device="cuda")
+    bias = torch.randn(g * n, device="cuda").to(torch.bfloat16)
+    items, want = [], []
+    for src, axis, kp in ((w_rows, 0, 48), (w_cols, 1, 32), (bias, 1, 32)):
+        want.append(ctx.ecospa_compact(src, idx, axis, g, n, 1, kp))
+        dst = torch.full_like(want[-1], 7)
+        items.append((ctx.map_item(src, dst, idx, axis, g, n, 1, kp), dst))
+    full = ctx.ecospa_scatter(want[1], idx, 1, g, n, 1, 32)
+    dst = torch.full_like(full, 7)
+    items.append((ctx.map_item(want[1], dst, idx, 1, g, n, 1, 32, scatter=True), dst))
+    want.append(full)
+    ctx.ecospa_compact_batch([it for it, _ in items])
+    for (_, got), w in zip(items, want):
+        assert torch.equal(got, w)
