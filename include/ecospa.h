@@ -220,7 +220,11 @@ int ecospa_coupled_bwd(ecospa_ctx* ctx, const ecospa_block_desc* desc /*host*/, 
  *   C[m, n] = sum_k A(m, k) * B(n, k) (+ bias[n]),   m < M, n < N, k < K,   fp32 accumulation,
  *   A(m, k) = A[m*lda + k] (trans_a = 0) or A[k*lda + m] (trans_a = 1); B(n, k) likewise with ldb.
  * So x W^T is (0, 0), dY W is (0, 1) and dY^T X is (1, 1).  bias may be NULL.
- * tile: 0 = library's choice, 1 = 128x128 workgroup tiles, 2 = 256x256 (bf16 only).
+ * tile (bf16 only; for tests and tuning): 0 = library's choice; 1 / 2 = 128x128 / 256x256 workgroup
+ * tiles staged through registers, K-slow operands transposed on the way to LDS; 3 / 4 = the same with
+ * K-slow operands read by transposing LDS reads; 10..16 = configurations of the software-pipelined
+ * kernel (direct global->LDS ring; needs K and K/splits to be multiples of its slab depth, else the
+ * library falls back to its own choice).
  * splits: 0 = library's choice, otherwise the number of K splits (partials come from the
  * workspace and are added in a fixed order).
  * bf16 needs 16-byte aligned pointers, N % 8 == 0, leading dimensions % 8 == 0 and the

@@ -216,15 +216,16 @@ class Context:
         return Pair(kind, dtype_code(w1.dtype), groups, n, unit, d1, d2, _ptr(w1), _ptr(w1b), _ptr(w2),
                     w1.stride(0), 0 if w1b is None else w1b.stride(0), w2.stride(0))
 
-    def ecospa_coupled_score(self, pairs: Sequence[Pair]) -> list[torch.Tensor]:
-        arr = (Pair * len(pairs))(*pairs)
-        need = self.lib.ecospa_score_workspace_bytes(arr, len(pairs))
+    def ecospa_coupled_score(self, pairs: Sequence[Pair], out: Optional[Sequence[torch.Tensor]] = None) -> list[torch.Tensor]:
+        """Scores of a batch of pairs, one float32 tensor [groups, n/unit] per pair (written into `out` if given)."""
+        arr = pairs if isinstance(pairs, C.Array) else (Pair * len(pairs))(*pairs)
+        need = self.lib.ecospa_score_workspace_bytes(arr, len(arr))
         self.reserve(need)
-        outs = [torch.empty(p.groups * (p.n // max(p.unit, 1)), dtype=torch.float32, device=self.device)
-                for p in pairs]
-        ptrs = (C.c_void_p * len(pairs))(*[o.data_ptr() for o in outs])
-        self._check(self.lib.ecospa_coupled_score(self.h, arr, len(pairs), ptrs), "ecospa_coupled_score")
-        return [o.view(p.groups, -1) for o, p in zip(outs, pairs)]
+        if out is None:
+            out = [torch.empty((p.groups, p.n // max(p.unit, 1)), dtype=torch.float32, device=self.device) for p in arr]
+        ptrs = (C.c_void_p * len(arr))(*[o.data_ptr() for o in out])
+        self._check(self.lib.ecospa_coupled_score(self.h, arr, len(arr), ptrs), "ecospa_coupled_score")
+        return list(out)
 
     # ---- step 2 ------------------------------------------------------------------------------
     def ecospa_select_topk(self, scores: torch.Tensor, k: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
@@ -237,7 +238,7 @@ class Context:
 
     def ecospa_select_topk_batch(self, items: Sequence[SelectItem]):
         """items: SelectItem structs (see :meth:`select_item`); one launch for all of them."""
-        arr = (SelectItem * len(items))(*items)
+        arr = items if isinstance(items, C.Array) else (SelectItem * len(items))(*items)
         self._check(self.lib.ecospa_select_topk_batch(self.h, arr, len(items)), "ecospa_select_topk_batch")
 
     @staticmethod
@@ -262,7 +263,7 @@ class Context:
                        int(scatter), other, ld_s, ld_d, idx.data_ptr())
 
     def ecospa_compact_batch(self, items: Sequence[MapItem]):
-        arr = (MapItem * len(items))(*items)
+        arr = items if isinstance(items, C.Array) else (MapItem * len(items))(*items)
         self._check(self.lib.ecospa_compact_batch(self.h, arr, len(items)), "ecospa_compact_batch")
 
     def _mapped(self, fn, name, src, dst, axis, groups, n, unit, k, kp, idx):

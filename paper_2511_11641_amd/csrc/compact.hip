@@ -40,7 +40,7 @@ __device__ __forceinline__ long long map_slot(const MapArgs& m, long long s) {
 }
 
 // One mapped copy of a batch; all items of a batch share one launch (block ranges in `blk_begin`).
-#define MAP_MAX_ITEMS 16
+#define MAP_MAX_ITEMS 32
 #define MAP_COL_ROWS 4      // rows a column-copy thread keeps in flight
 struct MapItemDev {
   const void* src;
@@ -52,6 +52,7 @@ struct MapItemDev {
   int vec;        // 16-byte accesses are legal
   int gx;         // axis 1: blocks along the destination columns
   int rpb;        // axis 1: rows per block
+  int lds_path;   // axis 1 gather with aligned rows: source window staged through LDS
   int blk_begin;  // first block of this item
 };
 struct MapBatch {
@@ -123,7 +124,96 @@ __device__ __forceinline__ void map_cols_block(const MapItemDev& t, int blk) {
   }
 }
 
+// ---- axis 1 through LDS (gather and scatter): a workgroup owns MAP_LDS_GROUPS x V destination columns
+// and MAP_LDS_ROWS_TOTAL rows.  The source columns of its destination range are ascending, so they lie
+// in one window of the source row; the window is fetched with coalesced 16-byte loads into LDS, 16 rows
+// at a time, and every thread picks the V columns of its 16-byte store from there.  If the window is
+// wider than the LDS tile (kept indices far apart) the region falls back to element-wise gathers.
+#define MAP_LDS_GROUPS 32          // 16-byte column groups per workgroup
+#define MAP_LDS_ROWS 8             // rows per pass (MAP_LDS_GROUPS * MAP_LDS_ROWS = 256 threads)
+#define MAP_LDS_ROWS_TOTAL 64      // rows per workgroup
+#define MAP_LDS_CHUNKS 128         // 16-byte chunks of the source window per row
+template <typename E>
+__device__ __forceinline__ void map_cols_lds_block(const MapItemDev& t, int blk, unsigned char* lds_raw) {
+  constexpr int V = 16 / sizeof(E);
+  constexpr int CB = MAP_LDS_GROUPS * V;
+  E* tile = reinterpret_cast<E*>(lds_raw);                                   // [MAP_LDS_ROWS][MAP_LDS_CHUNKS * V]
+  int* smap = reinterpret_cast<int*>(lds_raw + MAP_LDS_ROWS * MAP_LDS_CHUNKS * 16);   // [CB]
+  int* lim = smap + CB;                                                      // [2]: min, max source column
+  const E* __restrict__ src = static_cast<const E*>(t.src);
+  E* __restrict__ dst = static_cast<E*>(t.dst);
+  const int tid = threadIdx.x;
+  const int bx = blk % t.gx, by = blk / t.gx;
+  const long long c0 = static_cast<long long>(bx) * CB;
+  const long long r_begin = static_cast<long long>(by) * MAP_LDS_ROWS_TOTAL;
+  const long long r_end = r_begin + MAP_LDS_ROWS_TOTAL < t.other ? r_begin + MAP_LDS_ROWS_TOTAL : t.other;
+  if (tid == 0) { lim[0] = 0x7fffffff; lim[1] = -1; }
+  __syncthreads();
+  if (tid < CB) {
+    const long long sc = (c0 + tid < t.dst_slots) ? map_slot(t.m, c0 + tid) : -1;
+    smap[tid] = static_cast<int>(sc);
+    if (sc >= 0) { atomicMin(&lim[0], static_cast<int>(sc)); atomicMax(&lim[1], static_cast<int>(sc)); }
+  }
+  __syncthreads();
+  const int smin = lim[0], smax = lim[1];
+  const int w0 = smin & ~(V - 1);                            // window start, 16-byte aligned
+  const int chunks = smax >= 0 ? (smax - w0) / V + 1 : 0;    // 16-byte chunks per row
+  const int grp = tid % MAP_LDS_GROUPS, rr = tid / MAP_LDS_GROUPS;   // this thread's column group and row slot
+  const long long dc = c0 + static_cast<long long>(grp) * V;  // its first destination column
+  const bool full = dc + V <= t.dst_slots;
+  if (chunks > MAP_LDS_CHUNKS) {
+    // window too wide for the tile: gather element by element
+    for (long long r = r_begin + rr; r < r_end; r += MAP_LDS_ROWS) {
+      alignas(16) E vals[V];
+#pragma unroll
+      for (int v = 0; v < V; ++v) vals[v] = smap[grp * V + v] >= 0 ? src[r * t.ld_src + smap[grp * V + v]] : E(0);
+      E* d = dst + r * t.ld_dst + dc;
+      if (full) *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(vals);
+      else
+        for (int v = 0; v < V; ++v)
+          if (dc + v < t.dst_slots) d[v] = vals[v];
+    }
+    return;
+  }
+  int off[V];   // this thread's V source columns relative to the window (-1 = padding slot)
+#pragma unroll
+  for (int v = 0; v < V; ++v) off[v] = smap[grp * V + v] >= 0 ? smap[grp * V + v] - w0 : -1;
+  // From here on every wavefront works alone on its own rows of each pass (its own part of the
+  // tile): lane = (row, 16-byte column group), for the loads as for the stores, so only
+  // wavefront-level ordering is needed between the LDS writes and reads - no workgroup barriers.
+  static_assert(MAP_LDS_GROUPS * MAP_LDS_ROWS == 256 && 64 % MAP_LDS_GROUPS == 0, "a row's groups lie in one wavefront");
+  constexpr int RPW = 64 / MAP_LDS_GROUPS;     // rows per wavefront and pass
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wrow = wave * RPW + lane / MAP_LDS_GROUPS, l16 = lane % MAP_LDS_GROUPS;
+  E* wtile = tile + wrow * MAP_LDS_CHUNKS * V;
+  for (long long rb = r_begin; rb < r_end; rb += MAP_LDS_ROWS) {
+    const long long r = rb + wrow;
+    const long long rl = r < r_end ? r : r_end - 1;
+    const E* sp = src + rl * t.ld_src + w0;
+    for (int ch = l16; ch < chunks; ch += MAP_LDS_GROUPS)
+      *reinterpret_cast<uint4*>(wtile + ch * V) = *reinterpret_cast<const uint4*>(sp + ch * V);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (r < r_end && dc < t.dst_slots) {
+      alignas(16) E vals[V];
+#pragma unroll
+      for (int v = 0; v < V; ++v) vals[v] = off[v] >= 0 ? wtile[off[v]] : E(0);
+      E* d = dst + r * t.ld_dst + dc;
+      if (full) *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(vals);
+      else
+        for (int v = 0; v < V; ++v)
+          if (dc + v < t.dst_slots) d[v] = vals[v];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
 __global__ __launch_bounds__(256) void map_batch_kernel(const MapBatch b) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[MAP_LDS_ROWS * MAP_LDS_CHUNKS * 16 + (MAP_LDS_GROUPS * 8 + 2) * 4];
+  static_assert(MAP_LDS_GROUPS * 8 <= 256, "one thread per destination column resolves the source columns");
   const int blk = blockIdx.x;
   int i = 0;
   while (i + 1 < b.n_items && blk >= b.it[i + 1].blk_begin) ++i;
@@ -132,6 +222,9 @@ __global__ __launch_bounds__(256) void map_batch_kernel(const MapBatch b) {
   if (t.axis == 0) {
     if (t.esize == 2) map_rows_block<bf16_t>(t, local);
     else map_rows_block<float>(t, local);
+  } else if (t.lds_path) {
+    if (t.esize == 2) map_cols_lds_block<bf16_t>(t, local, lds_raw);
+    else map_cols_lds_block<float>(t, local, lds_raw);
   } else if (t.esize == 2) {
     if (t.vec) map_cols_block<bf16_t, true>(t, local);
     else map_cols_block<bf16_t, false>(t, local);
@@ -190,13 +283,20 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
         blk += (t.dst_slots + 3) / 4;
       } else {
         t.vec = aligned16(q.dst) && q.ld_dst % V == 0;
-        const int vv = t.vec ? V : 1;
-        t.gx = static_cast<int>((t.dst_slots + 256ll * vv - 1) / (256ll * vv));
-        // enough row chunks to fill the chip, at least MAP_COL_ROWS rows each
-        int rpb = MAP_COL_ROWS;
-        while (rpb < 64 && (q.other_extent + rpb - 1) / rpb * t.gx > 4096) rpb *= 2;
-        t.rpb = rpb;
-        blk += (q.other_extent + rpb - 1) / rpb * t.gx;
+        // the LDS path reads whole 16-byte chunks of the source rows, up to the end of the last kept chunk
+        t.lds_path = t.vec && aligned16(q.src) && q.ld_src % V == 0 && (q.scatter ? cmp_slots : full_slots) % V == 0;
+        if (t.lds_path) {
+          t.gx = static_cast<int>((t.dst_slots + MAP_LDS_GROUPS * V - 1) / (MAP_LDS_GROUPS * V));
+          blk += (q.other_extent + MAP_LDS_ROWS_TOTAL - 1) / MAP_LDS_ROWS_TOTAL * t.gx;
+        } else {
+          const int vv = t.vec ? V : 1;
+          t.gx = static_cast<int>((t.dst_slots + 256ll * vv - 1) / (256ll * vv));
+          // enough row chunks to fill the chip, at least MAP_COL_ROWS rows each
+          int rpb = MAP_COL_ROWS;
+          while (rpb < 64 && (q.other_extent + rpb - 1) / rpb * t.gx > 4096) rpb *= 2;
+          t.rpb = rpb;
+          blk += (q.other_extent + rpb - 1) / rpb * t.gx;
+        }
       }
       if (blk > (1ll << 30)) return ECOSPA_ERR_SHAPE;
     }

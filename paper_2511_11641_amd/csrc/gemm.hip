@@ -5,7 +5,7 @@
 //       is the slow storage axis (dY W, dY^T X) are transposed in registers on the way to LDS.
 // fp32: 64x64x16 vector-ALU tiles (the fp32 configuration is small and launch bound).
 // Split-K writes fp32 partials that a second kernel adds in a fixed order (deterministic dW).
-#include "gemm_epi.h"
+#include "gemm_lds.h"
 
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA kernel, parametrised by the workgroup tile BM x BN and the WGM x WGN grid of wavefronts
@@ -56,7 +56,6 @@ __device__ __forceinline__ void sstore_kc(bf16_t* lds, const u32x4 (&reg)[(ROWS 
 // writes chunk i of the 1 KB block the wave-uniform base points at) = 8 tile rows.  The swizzle is
 // applied on the global side: the lane that owns physical chunk pc of row r fetches the logical
 // k-chunk that lds_off() maps there.
-typedef __attribute__((address_space(3))) bf16_t lds_bf16_t;
 template <int ROWS, int THREADS>
 __device__ __forceinline__ void dload_kc(const bf16_t* __restrict__ base, long long ld, int row0, int R, int k0,
                                          lds_bf16_t* tile) {
@@ -118,6 +117,21 @@ __device__ __forceinline__ void sstore_tr(bf16_t* lds, const u32x4 (&reg)[(ROWS 
   }
 }
 
+// K-slow operand kept as it lies in memory, [BK][ROWS] (fragments then come from transposing LDS
+// reads): the four 16-byte pieces of a thread's 4(k) x 8(r) block go to four k rows - no shuffling.
+template <int ROWS, int BK, int THREADS>
+__device__ __forceinline__ void sstore_ks(bf16_t* lds, const u32x4 (&reg)[(ROWS * BK / 8 / THREADS < 4 ? 4 : ROWS * BK / 8 / THREADS)]) {
+  constexpr int NSUB = ROWS * BK / 32;
+#pragma unroll
+  for (int b = 0; b < (NSUB + THREADS - 1) / THREADS; ++b) {
+    const int sb = threadIdx.x + b * THREADS;
+    if (NSUB % THREADS != 0 && sb >= NSUB) break;
+    const int rblk = sb % (ROWS / 8), kblk = sb / (ROWS / 8);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(lds + ks_off<ROWS>(kblk * 4 + i, rblk)) = reg[b * 4 + i];
+  }
+}
+
 // LDS traffic of one wavefront with itself (its private staging area): order only, no s_barrier
 __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -127,7 +141,8 @@ __device__ __forceinline__ void wave_lds_sync() {
 
 // Workgroup tile BM x BN x BK, WGM x WGN wavefronts; WPE = wavefronts per SIMD the register
 // allocation is tuned for (occupancy hides the LDS and global latencies between MFMAs).
-template <int BM, int BN, int BK, int WGM, int WGN, int WPE, bool TA, bool TB>
+// TRR: K-slow operands stay untransposed in LDS and are read with ds_read_b64_tr_b16.
+template <int BM, int BN, int BK, int WGM, int WGN, int WPE, bool TA, bool TB, bool TRR>
 __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   constexpr int THREADS = 64 * WGM * WGN;
@@ -185,9 +200,11 @@ void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   do {                                                                                             \
     const bool full_ = (k0) + BK <= k_end;                                                         \
     bf16_t* as_ = lds + (buf) * STAGE;                                                             \
-    if (TA) sstore_tr<BM, BK, THREADS>(as_, ra);                                                   \
+    if (TA && TRR) sstore_ks<BM, BK, THREADS>(as_, ra);                                            \
+    else if (TA) sstore_tr<BM, BK, THREADS>(as_, ra);                                              \
     else if (!(DIRECT_OK && full_)) sstore_kc<BM, BK, THREADS>(as_, ra);                           \
-    if (TB) sstore_tr<BN, BK, THREADS>(as_ + BM * BK, rb);                                         \
+    if (TB && TRR) sstore_ks<BN, BK, THREADS>(as_ + BM * BK, rb);                                  \
+    else if (TB) sstore_tr<BN, BK, THREADS>(as_ + BM * BK, rb);                                    \
     else if (!(DIRECT_OK && full_)) sstore_kc<BN, BK, THREADS>(as_ + BM * BK, rb);                 \
   } while (0)
 
@@ -209,10 +226,12 @@ void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
       const int kc = s * 2 + (lane >> 5);
 #pragma unroll
       for (int i = 0; i < FM; ++i)
-        a[i] = *reinterpret_cast<const bf16x8_t*>(As + lds_off<BK>(wm * WTM + i * 32 + (lane & 31), kc));
+        a[i] = (TA && TRR) ? read_frag<BM, BK, true>(As, wm * WTM + i * 32, s)
+                           : *reinterpret_cast<const bf16x8_t*>(As + lds_off<BK>(wm * WTM + i * 32 + (lane & 31), kc));
 #pragma unroll
       for (int j = 0; j < FN; ++j)
-        b[j] = *reinterpret_cast<const bf16x8_t*>(Bs + lds_off<BK>(wn * WTN + j * 32 + (lane & 31), kc));
+        b[j] = (TB && TRR) ? read_frag<BN, BK, true>(Bs, wn * WTN + j * 32, s)
+                           : *reinterpret_cast<const bf16x8_t*>(Bs + lds_off<BK>(wn * WTN + j * 32 + (lane & 31), kc));
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -383,7 +402,7 @@ static int gemm_pipe_choice(const GemmDesc& d) {
   return 4;                       // 128x128
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int WPE>
+template <int BM, int BN, int BK, int WGM, int WGN, int WPE, bool TRR>
 static hipError_t launch_tile(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
   const int tm = (d.M + BM - 1) / BM, tn = (d.N + BN - 1) / BN;
   const int splits = d.splits > 1 ? d.splits : 1;
@@ -393,7 +412,7 @@ static hipError_t launch_tile(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
   const size_t lds_bytes = operand_bytes > staging_bytes ? operand_bytes : staging_bytes;
 #define LAUNCH_TT(TA, TB)                                                                                      \
   do {                                                                                                         \
-    auto kern = gemm_bf16_mfma_kernel<BM, BN, BK, WGM, WGN, WPE, TA, TB>;                                               \
+    auto kern = gemm_bf16_mfma_kernel<BM, BN, BK, WGM, WGN, WPE, TA, TB, (TRR && (TA || TB))>;                         \
     static bool attr_set = false;                                                                              \
     if (!attr_set && lds_bytes > 64 * 1024) {                                                                  \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
@@ -447,8 +466,17 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
     const int k_split = (d.K + splits - 1) / splits;
     const int cfg = d.tile >= 10 ? d.tile - 10 : (d.tile == 0 ? gemm_pipe_choice(d) : -1);
     if (cfg >= 0 && gemm_pipe_ok(d, cfg, k_split)) le = gemm_pipe_launch(ctx, d, cfg, k_split);
-    else if (d.tile == 2 || (d.tile != 1 && big)) le = launch_tile<256, 256, 64, 2, 4, 2>(ctx, d, k_chunk);
-    else le = launch_tile<128, 128, 64, 2, 2, 2>(ctx, d, k_chunk);
+    else {
+      // register-staged kernel; tile 1/2 = 128/256 tiles with K-slow operands transposed on the way to
+      // LDS, 3/4 = the same tiles with K-slow operands read by transposing LDS reads.  Measured: the
+      // transposing reads win only when BOTH operands are K-slow (dY^T X).
+      int t = d.tile >= 1 && d.tile <= 4 ? d.tile : (big ? 2 : 1);
+      if (d.tile == 0 && d.trans_a && d.trans_b) t += 2;
+      if (t == 4) le = launch_tile<256, 256, 64, 2, 4, 2, true>(ctx, d, k_chunk);
+      else if (t == 3) le = launch_tile<128, 128, 64, 2, 2, 2, true>(ctx, d, k_chunk);
+      else if (t == 2) le = launch_tile<256, 256, 64, 2, 4, 2, false>(ctx, d, k_chunk);
+      else le = launch_tile<128, 128, 64, 2, 2, 2, false>(ctx, d, k_chunk);
+    }
     if (le != hipSuccess) return hip_fail(ctx, le, "gemm launch");
     if (prof) {
       (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n + 1], ctx->stream);

@@ -2,16 +2,19 @@
 //
 // HBM-bound: every weight element of every pair in the batch is read exactly once with
 // 16-byte loads.  Two launches per batch of up to SCORE_MAX_PAIRS pairs:
-//   1. score_sumsq_kernel  - squared row norms (wave per row, shuffle reduction) and partial
-//                            squared column norms (16-lane x 16-row-slot tiles, LDS reduction)
-//   2. score_finish_kernel - one workgroup per (pair, group): add the partials, r = |a||b|,
-//                            group L2 norm, normalised scores
+//   1. score_sumsq_kernel  - squared row norms (one wavefront per row, shuffle reduction) and
+//                            squared column norms of the [d, n] member (one workgroup per strip
+//                            of one 128-byte line = 8 lanes x 16 bytes, over all d rows, eight
+//                            loads in flight per lane)
+//   2. score_finish_kernel - one workgroup per (pair, group): r = |a||b|, group L2 norm,
+//                            normalised scores
 // No floating-point atomics; all reduction orders are fixed.
 #include "common.h"
 
 #define SCORE_MAX_PAIRS 24
 #define SCORE_ROWS_PER_BLOCK 16   // row-norm blocks: 4 waves x 4 rows
-#define SCORE_COL_SLOTS 16        // column-norm blocks: 16 row slots x 16 lanes
+#define SCORE_COL_LANES 8         // column-norm blocks: 8 lanes (128 bytes of columns) x 32 row slots
+#define SCORE_COL_SLOTS (256 / SCORE_COL_LANES)
 
 struct ScorePairDev {
   const void* w1;
@@ -19,15 +22,12 @@ struct ScorePairDev {
   const void* w2;
   long long ld1, ld1b, ld2;
   float* a_sq;     // [rows]            squared norms of a_j
-  float* b_sq;     // [rows]            QK only: squared norms of rows of W_k
-  float* b_part;   // [n_chunks][rows]  other kinds: partial squared column norms of w2
+  float* b_sq;     // [rows]            squared norms of b_j (rows of W_k, or columns of w2)
   float* scores;   // [groups * n / unit]
   int rows;        // groups * n
   int groups, n, unit;
   int d1, d2;
   int kind, dtype;
-  int n_chunks, rc;            // column kernel: chunks of rc rows of w2
-  int n_strips;                // column strips of 16 lanes * VEC columns
   int blk_row1, blk_row2, blk_col, blk_end;   // first block index of each phase in launch 1
   int fin_begin;               // first block index of this pair in launch 2 (one workgroup per group)
 };
@@ -111,50 +111,66 @@ __device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
     }
     return;
   }
-  // ---- partial squared column norms of w2 [d2, rows] ----
+  // ---- squared column norms of w2 [d2, rows]: one strip of SCORE_COL_LANES x V columns, all rows ----
   const int local = blk - p.blk_col;
-  const int strip = local % p.n_strips, chunk = local / p.n_strips;
-  const int slot = tid >> 4, l16 = tid & 15;
+  constexpr int W = SCORE_COL_LANES * V;
+  if (local * W >= p.rows) return;                 // padding of the range (whole workgroup)
+  const int slot = tid / SCORE_COL_LANES, ln = tid % SCORE_COL_LANES;
   const T* w = static_cast<const T*>(p.w2);
-  const int col0 = strip * (16 * V) + l16 * V;
-  const int r_begin = chunk * p.rc;
-  const int r_end = min(r_begin + p.rc, p.d2);
+  const int col0 = local * W + ln * V;
   const bool vec_ok = (p.ld2 % V == 0) && ((reinterpret_cast<uintptr_t>(w) & 15u) == 0);
   float acc[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) acc[i] = 0.f;
   if (vec_ok && col0 + V <= p.rows) {
-    for (int r = r_begin + slot; r < r_end; r += SCORE_COL_SLOTS) {
-      float a[V];
-      load_vec<T>(w + r * p.ld2 + col0, a);
+    for (int r0 = slot; r0 < p.d2; r0 += 8 * SCORE_COL_SLOTS) {     // 8 independent loads in flight
+      float a[8][V];
 #pragma unroll
-      for (int i = 0; i < V; ++i) acc[i] += a[i] * a[i];
+      for (int q = 0; q < 8; ++q) {
+        const int r = r0 + q * SCORE_COL_SLOTS;
+        load_vec<T>(w + static_cast<long long>(r < p.d2 ? r : r0) * p.ld2 + col0, a[q]);
+        if (r >= p.d2) {
+#pragma unroll
+          for (int i = 0; i < V; ++i) a[q][i] = 0.f;
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] += a[q][i] * a[q][i];
     }
   } else {
-    for (int r = r_begin + slot; r < r_end; r += SCORE_COL_SLOTS) {
+    for (int r = slot; r < p.d2; r += SCORE_COL_SLOTS) {
 #pragma unroll
       for (int i = 0; i < V; ++i)
         if (col0 + i < p.rows) {
-          float a = load_f32<T>(w + r * p.ld2 + col0 + i);
+          float a = load_f32<T>(w + static_cast<long long>(r) * p.ld2 + col0 + i);
           acc[i] += a * a;
         }
     }
   }
-  // reduce the 16 row slots in a fixed order
+  // reduce the row slots in a fixed order: thread (column c, part q) adds slots q, q + PARTS, ...;
+  // then the PARTS partial sums of a column are added in order
 #pragma unroll
-  for (int i = 0; i < V; ++i) lds[slot * (16 * V) + l16 * V + i] = acc[i];
+  for (int i = 0; i < V; ++i) lds[slot * (W + 1) + ln * V + i] = acc[i];
   __syncthreads();
-  if (tid < 16 * V) {
-    float s = 0.f;
-#pragma unroll
-    for (int k = 0; k < SCORE_COL_SLOTS; ++k) s += lds[k * (16 * V) + tid];
-    const int col = strip * (16 * V) + tid;
-    if (col < p.rows) p.b_part[static_cast<long long>(chunk) * p.rows + col] = s;
+  constexpr int PARTS = 256 / W;                    // threads per column
+  const int c = tid / PARTS, q = tid % PARTS;
+  float s = 0.f;
+  for (int k = q; k < SCORE_COL_SLOTS; k += PARTS) s += lds[k * (W + 1) + c];
+  __syncthreads();
+  lds[c * PARTS + q] = s;
+  __syncthreads();
+  if (tid < W) {
+    float tot = 0.f;
+    for (int k = 0; k < PARTS; ++k) tot += lds[tid * PARTS + k];
+    const int col = local * W + tid;
+    if (col < p.rows) p.b_sq[col] = tot;
   }
 }
 
 __global__ __launch_bounds__(256) void score_sumsq_kernel(const ScoreBatch b) {
-  __shared__ float lds[SCORE_COL_SLOTS * 16 * 8];
+  __shared__ float lds[SCORE_COL_SLOTS * (SCORE_COL_LANES * 8 + 1)];
   const int blk = blockIdx.x;
   int pi = 0;
   while (pi + 1 < b.n_pairs && blk >= b.p[pi].blk_end) ++pi;
@@ -163,11 +179,9 @@ __global__ __launch_bounds__(256) void score_sumsq_kernel(const ScoreBatch b) {
   else score_block<float>(p, blk, lds);
 }
 
-// Launch 2: one workgroup per (pair, group).  Every thread finishes its units (adds the column-norm
-// partials in chunk order, r = |a| |b|), the group's L2 norm of r is reduced in a fixed order, and
-// the normalised scores are written.
+// Launch 2: one workgroup per (pair, group).  Every thread finishes its units (r = |a| |b|), the
+// group's L2 norm of r is reduced in a fixed order, and the normalised scores are written.
 #define SCORE_FIN_THREADS 1024
-#define SCORE_MAX_CHUNKS 16       // col_chunk_rows() never makes more
 __global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_kernel(const ScoreBatch b) {
   __shared__ float red[SCORE_FIN_THREADS / 64];
   const int blk = blockIdx.x;
@@ -184,19 +198,7 @@ __global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_kernel(const S
     for (int j = 0; j < p.unit; ++j) {
       const int row = (g * nu + u) * p.unit + j;
       a += p.a_sq[row];
-      if (p.kind == ECOSPA_PAIR_QK) {
-        bsum += p.b_sq[row];
-      } else {
-        // all chunk partials of this row are fetched at once, then added in chunk order
-        float part[SCORE_MAX_CHUNKS];
-#pragma unroll
-        for (int c = 0; c < SCORE_MAX_CHUNKS; ++c)
-          part[c] = c < p.n_chunks ? p.b_part[static_cast<long long>(c) * p.rows + row] : 0.f;
-        float s = 0.f;
-#pragma unroll
-        for (int c = 0; c < SCORE_MAX_CHUNKS; ++c) s += part[c];
-        bsum += s;
-      }
+      bsum += p.b_sq[row];
     }
     const float r = sqrtf(a) * sqrtf(bsum);
     out[u] = r;          // re-read below by the same thread
@@ -225,24 +227,9 @@ static int validate_pair(const ecospa_pair& q) {
   return ECOSPA_OK;
 }
 
-// rows of w2 per column-kernel block: at most 16 chunks so the finishing pass stays short
-static int col_chunk_rows(int d2) {
-  int rc = (d2 + 15) / 16;
-  rc = (rc + SCORE_COL_SLOTS - 1) / SCORE_COL_SLOTS * SCORE_COL_SLOTS;
-  return rc < 16 ? 16 : rc;
-}
-
 static size_t pair_ws_bytes(const ecospa_pair& q) {
   const size_t rows = static_cast<size_t>(q.groups) * q.n;
-  size_t b = align_up(rows * 4, 256);  // a_sq
-  if (q.kind == ECOSPA_PAIR_QK) {
-    b += align_up(rows * 4, 256);
-  } else {
-    const int rc = col_chunk_rows(q.d2);
-    const size_t chunks = (q.d2 + rc - 1) / rc;
-    b += align_up(chunks * rows * 4, 256);
-  }
-  return b;
+  return 2 * align_up(rows * 4, 256);   // a_sq, b_sq
 }
 
 extern "C" size_t ecospa_score_workspace_bytes(const ecospa_pair* pairs, int n_pairs) {
@@ -286,19 +273,14 @@ extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, i
       p.blk_row1 = blk;
       blk += row_blocks;
       p.blk_row2 = blk;
+      p.b_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows) * 4));
       if (q.kind == ECOSPA_PAIR_QK) {
-        p.b_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows) * 4));
         blk += row_blocks;
         p.blk_col = blk;
-        p.n_chunks = 0; p.rc = 0; p.n_strips = 1;
       } else {
         p.blk_col = blk;
-        p.rc = col_chunk_rows(q.d2);
-        p.n_chunks = (q.d2 + p.rc - 1) / p.rc;
-        const int strip_w = 16 * (q.dtype == ECOSPA_BF16 ? 8 : 4);
-        p.n_strips = (p.rows + strip_w - 1) / strip_w;
-        p.b_part = static_cast<float*>(ws.take(static_cast<size_t>(p.n_chunks) * p.rows * 4));
-        blk += p.n_strips * p.n_chunks;
+        const int strip = SCORE_COL_LANES * (q.dtype == ECOSPA_BF16 ? 8 : 4);
+        blk += (p.rows + strip - 1) / strip;
       }
       p.blk_end = blk;
       p.fin_begin = fin;

@@ -1,5 +1,5 @@
-"""GPU parity of the dense contraction kernel (both workgroup tile sizes, all operand layouts,
-ragged extents, split K) against a plain fp64 matrix product."""
+"""GPU parity of the dense contraction kernels (every workgroup tile and LDS layout variant, all
+operand layouts, ragged extents, split K) against a plain fp64 matrix product."""
 import numpy as np
 import pytest
 import torch
@@ -26,7 +26,7 @@ def _operands(seed, M, N, K, ta, tb, dtype):
     return a, b, bias, want
 
 
-@pytest.mark.parametrize("tile", [1, 2])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
 @pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, True), (True, False)])
 @pytest.mark.parametrize("M,N,K", [(300, 264, 136), (512, 512, 256), (1000, 520, 72), (64, 1032, 648)])
 def test_contract_bf16(ctx, M, N, K, ta, tb, tile):
@@ -37,7 +37,7 @@ def test_contract_bf16(ctx, M, N, K, ta, tb, tile):
     assert_close(got, want, "bf16", f"tile {tile}")
 
 
-@pytest.mark.parametrize("tile", [1, 2])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
 @pytest.mark.parametrize("splits", [2, 5])
 def test_contract_bf16_split_k(ctx, splits, tile):
     a, b, bias, want = _operands(42, 264, 136, 1000, True, True, "bf16")

@@ -1,0 +1,96 @@
+"""Full-size parity of the whole path in the launch configuration bench.py times: one step
+(score -> select -> compact -> attention fwd -> FFN fwd -> FFN bwd -> attention bwd) of the
+GPT-2-Medium-shaped layer (batch 8 x seq 1024) and of the LLaMA-1B-shaped layer (batch 16 x seq 256,
+RoPE, SwiGLU), every output against the fp64 oracle on the same seeded inputs.
+
+Blocks are compared one at a time: the oracle FFN is fed the attention output the GPU produced and the
+oracle attention backward the FFN input gradient the GPU produced, so each comparison has identical
+inputs on both sides.  Selected indices are compared bit for bit on the GPU's own scores."""
+import numpy as np
+import pytest
+import torch
+
+import bench
+from oracle import ecospa_oracle as O
+from paper_2511_11641_amd import binding as B
+from paper_2511_11641_amd import synth
+from util import assert_close, host, pad_cols, pad_rows
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    return B.Context("cuda:0")
+
+
+@pytest.mark.parametrize("name", ["c2_gpt2m_layer", "c3_llama1b_layer"])
+def test_full_layer_step_matches_oracle(ctx, name):
+    cfg = dict(synth.CONFIGS[name])
+    Bsz, L, d, h, dh, dff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
+    unit = 2 if cfg["rope"] else 1
+    lay = bench.Layer(ctx, cfg, cfg["seed"], 1, 2)
+    lay.step()
+    torch.cuda.synchronize()
+    a, f = lay.host["attn"], lay.host["ffn"]
+    act = O.ACT_SWIGLU if cfg["gated"] else O.ACT_GELU_ERF
+
+    # steps 1-2: scores within tolerance, indices exact on the GPU's scores
+    kinds = ((O.PAIR_QK, a["wq"], a["wk"], h, dh, unit, None), (O.PAIR_VO, a["wv"], a["wo"], h, dh, 1, None),
+             (O.PAIR_FFN_GATED if cfg["gated"] else O.PAIR_FFN, f["w1"], f["w2"], 1, dff, 1, f.get("w1b")))
+    ks = (lay.k_qk_units, lay.k_vo, lay.k_ff)
+    idx = []
+    for (kind, w1, w2, g, n, u, w1b), sc, k, got_idx in zip(kinds, lay.scores, ks, lay.idx):
+        want = O.coupled_score(kind, w1, w2, g, n, u, w1b)
+        assert O.rel_fro(host(sc), want) < 1e-5
+        sel = O.select_topk(sc.cpu().numpy(), k)
+        assert np.array_equal(got_idx.cpu().numpy(), sel)
+        idx.append(sel)
+    iq, iv, iff = idx
+
+    # step 3 + attention block
+    kq, kv, kpq, kpv = lay.k_qk_units * unit, lay.k_vo, lay.attn.kp_qk, lay.attn.kp_vo
+    wq, wk = (O.heads_rows(O.compact(a[n_], iq, 0, dh, unit), h) for n_ in ("wq", "wk"))
+    wv, wo = O.heads_rows(O.compact(a["wv"], iv, 0, dh), h), O.heads_cols(O.compact(a["wo"], iv, 1, dh), h)
+    kw = {}
+    if cfg["bias"]:
+        kw = dict(bq=O.compact(a["bq"], iq, 0, dh, unit).reshape(h, -1), bk=O.compact(a["bk"], iq, 0, dh, unit).reshape(h, -1),
+                  bv=O.compact(a["bv"], iv, 0, dh).reshape(h, -1), bo=a["bo"])
+    ang = O.rope_angles(iq, L, dh) if cfg["rope"] else None
+    scale = dh ** -0.5
+    y1, sv = O.attn_fwd(a["x"], wq, wk, wv, wo, Bsz, L, scale, True, angles=ang, **kw)
+    assert_close(lay.attn.y, y1, "bf16", "attention y")
+    d1 = host(lay.ffn.dx)                     # upstream gradient of the attention block, as the GPU made it
+    ga = O.attn_bwd(a["x"], d1, wq, wk, wv, wo, Bsz, L, scale, sv, angles=ang)
+    del sv
+    assert_close(lay.attn.dx, ga["dx"], "bf16", "attention dx")
+    want_dwqkv = np.concatenate([pad_rows(ga["dwq"].reshape(h * kq, d), h, kq, kpq),
+                                 pad_rows(ga["dwk"].reshape(h * kq, d), h, kq, kpq),
+                                 pad_rows(ga["dwv"].reshape(h * kv, d), h, kv, kpv)])
+    assert_close(lay.attn.dwqkv_c, want_dwqkv, "bf16", "dW_qkv")
+    want_dwo = pad_cols(np.concatenate(list(ga["dwo"]), axis=1), h, kv, kpv)
+    assert_close(lay.attn.dwo_c, want_dwo, "bf16", "dW_o")
+    assert_close(lay.attn.dbo, ga["dbo"], "bf16", "db_o")
+    want_db = np.concatenate([pad_rows(ga["dbq"].reshape(-1, 1), h, kq, kpq), pad_rows(ga["dbk"].reshape(-1, 1), h, kq, kpq),
+                              pad_rows(ga["dbv"].reshape(-1, 1), h, kv, kpv)])[:, 0]
+    assert_close(lay.attn.dbqkv_c, want_db, "bf16", "db_qkv")
+
+    # FFN block on the attention output the GPU produced
+    x2 = host(lay.attn.y)
+    kf, kpf = lay.k_ff, lay.ffn.kp
+    w1, w2 = O.compact(f["w1"], iff, 0, dff), O.compact(f["w2"], iff, 1, dff)
+    w1b = O.compact(f["w1b"], iff, 0, dff) if cfg["gated"] else None
+    b1 = O.compact(f["b1"], iff, 0, dff) if cfg["bias"] else None
+    y2, sv2 = O.ffn_fwd(x2, w1, b1, w2, f.get("b2"), act, w1b)
+    assert_close(lay.ffn.y, y2, "bf16", "ffn y")
+    gf = O.ffn_bwd(x2, a["dy"], w1, w2, act, sv2, w1b)
+    assert_close(lay.ffn.dx, gf["dx"], "bf16", "ffn dx")
+    want_dw1 = pad_rows(gf["dw1"], 1, kf, kpf)
+    want_db1 = pad_rows(gf["db1"].reshape(-1, 1), 1, kf, kpf)[:, 0]
+    if cfg["gated"]:
+        want_dw1 = np.concatenate([want_dw1, pad_rows(gf["dw1b"], 1, kf, kpf)])
+    assert_close(lay.ffn.dw1_c, want_dw1, "bf16", "dW_1")
+    assert_close(lay.ffn.dw2_c, pad_cols(gf["dw2"], 1, kf, kpf), "bf16", "dW_2")
+    assert_close(lay.ffn.db2, gf["db2"], "bf16", "db_2")
+    if not cfg["gated"]:
+        assert_close(lay.ffn.db1_c, want_db1, "bf16", "db_1")
