@@ -71,7 +71,8 @@ __device__ __forceinline__ bf16x8_t acc_to_frag(const floatx16& a, int half) {
 template <int D>
 __device__ __forceinline__ void sub_load(u32x4 (&v)[4], const bf16_t* __restrict__ base, long long ld, long long row0,
                                          int rows_valid, int kp, int sub) {
-  // Unconditional loads from clamped (always valid) addresses, then a select: no divergent code.
+  // Unconditional loads from clamped (always valid) addresses; what lies outside the tile is zeroed
+  // by sub_mask() just before the registers go to LDS, so that nothing waits for the loads here.
   // row0 + rows_valid - 1 is the last token of the sequence whatever the tile, so the clamp is safe
   // even for tiles that start beyond the sequence end.
   const int tblk = sub / (D / 8), dblk = sub % (D / 8);
@@ -79,8 +80,19 @@ __device__ __forceinline__ void sub_load(u32x4 (&v)[4], const bf16_t* __restrict
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int r = tblk * 4 + i;
-    const u32x4 x = *reinterpret_cast<const u32x4*>(base + (row0 + min(r, rows_valid - 1)) * ld + dc);
-    v[i] = (r < rows_valid && dblk * 8 < kp) ? x : u32x4{0u, 0u, 0u, 0u};
+    v[i] = *reinterpret_cast<const u32x4*>(base + (row0 + min(r, rows_valid - 1)) * ld + dc);
+  }
+}
+// Zero the rows beyond the sequence end and the dims beyond the kept width (same arguments as the
+// sub_load() that filled v); a tile that lies fully inside skips the selects (uniform branch).
+template <int D>
+__device__ __forceinline__ void sub_mask(u32x4 (&v)[4], int rows_valid, int kp, int sub) {
+  if (rows_valid >= 64 && kp >= D) return;
+  const int tblk = sub / (D / 8), dblk = sub % (D / 8);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = tblk * 4 + i;
+    v[i] = (r < rows_valid && dblk * 8 < kp) ? v[i] : u32x4{0u, 0u, 0u, 0u};
   }
 }
 template <int D>
@@ -131,6 +143,32 @@ __device__ __forceinline__ void acc_to_tile(bf16_t* tile, int tok_row, int dim_t
   }
 }
 
+// Work item of a workgroup: (128-row tile, head, batch element) from a 1-D grid of n_tiles * h * B.
+// With a causal mask the work of a tile grows linearly with its index (query tiles) or falls with it
+// (key tiles), all workgroups of the layer's shapes are resident at once, and the hardware deals
+// workgroups round-robin to the 8 XCDs - so a mapping with the tile index fastest would hand one
+// XCD all the heavy tiles.  Here tiles are taken in zigzag order (last, first, last-1, second, ...:
+// any run of 2 or 4 neighbours carries average work), all tiles of one (head, batch element) go to
+// one XCD (its L2 then holds that head's K and V for all of them), and the starting point of the
+// zigzag moves on every 32 workgroups of an XCD, so that both neighbouring workgroups and workgroups
+// 32 apart - the likely co-residents of a compute unit - differ in weight.
+__device__ __forceinline__ void attn_work_item(const AttnArgs& a, int n_tiles, int& tile, int& head, int& b) {
+  const int id = blockIdx.x, n_bh = a.h * a.B;
+  int bh, z;
+  if ((n_bh & 7) == 0) {
+    const int x = id & 7, l = id >> 3;            // XCD, index inside the XCD's share
+    const int blk = l / n_tiles, r = l - blk * n_tiles;
+    z = (r + (blk * n_tiles) / 32) % n_tiles;
+    bh = x * (n_bh >> 3) + blk;
+  } else {
+    bh = id / n_tiles;
+    z = id - bh * n_tiles;
+  }
+  tile = (z & 1) ? (z >> 1) : n_tiles - 1 - (z >> 1);
+  head = bh % a.h;
+  b = bh / a.h;
+}
+
 // Wavefronts per SIMD the register allocation aims at: the narrow (32, 32) heads of a half-kept
 // layer need few registers, and more resident workgroups hide their barrier and LDS latencies.
 #define ATTN_WPE(DQ, DV, narrow) ((DQ) + (DV) <= 64 ? (narrow) : 2)
@@ -146,8 +184,8 @@ void attn_fwd_kernel(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[2][64 * DQ];
   __shared__ __attribute__((aligned(16))) bf16_t Vt[2][DV * 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, l32 = lane & 31;
-  const int qt = gridDim.x - 1 - blockIdx.x;   // heavy (late) causal tiles first
-  const int head = blockIdx.y, b = blockIdx.z;
+  int qt, head, b;
+  attn_work_item(a, (a.L + 127) / 128, qt, head, b);
   const int q0 = qt * 128;
   const long long tok0 = static_cast<long long>(b) * a.L;
   const bf16_t* Qg = a.qkv + head * a.kp_qk;
@@ -159,6 +197,7 @@ void attn_fwd_kernel(const AttnArgs a) {
   u32x4 pre[4];   // this thread's sub-block of the tile in flight (K for half 0, V for half 1)
   if (sub < SUBS(DQ)) {
     sub_load<DQ>(pre, Qg, a.ld_qkv, tok0 + q0 + half * 64, a.L - q0 - half * 64, a.kp_qk, sub);
+    sub_mask<DQ>(pre, a.L - q0 - half * 64, a.kp_qk, sub);
     sub_store_nat<DQ>(pre, Qs + half * 64 * DQ, sub);
   }
   const int kv_end = a.causal ? min(a.L, q0 + 128) : a.L;
@@ -168,13 +207,13 @@ void attn_fwd_kernel(const AttnArgs a) {
     if (half == 0) { if (sub < SUBS(DQ)) sub_load<DQ>(pre, Kg, a.ld_qkv, tok0 + (j) * 64, a.L - (j) * 64, a.kp_qk, sub); } \
     else { if (sub < SUBS(DV)) sub_load<DV>(pre, Vg, a.ld_qkv, tok0 + (j) * 64, a.L - (j) * 64, a.kp_vo, sub); }           \
   } while (0)
-#define FWD_SSTORE(buf)                                                           \
-  do {                                                                            \
-    if (half == 0) { if (sub < SUBS(DQ)) sub_store_nat<DQ>(pre, Ks[buf], sub); }  \
-    else { if (sub < SUBS(DV)) sub_store_tr<DV>(pre, Vt[buf], sub); }             \
+#define FWD_SSTORE(buf, j)                                                                                     \
+  do {                                                                                                         \
+    if (half == 0) { if (sub < SUBS(DQ)) { sub_mask<DQ>(pre, a.L - (j) * 64, a.kp_qk, sub); sub_store_nat<DQ>(pre, Ks[buf], sub); } } \
+    else { if (sub < SUBS(DV)) { sub_mask<DV>(pre, a.L - (j) * 64, a.kp_vo, sub); sub_store_tr<DV>(pre, Vt[buf], sub); } }             \
   } while (0)
   FWD_GLOAD(0);
-  FWD_SSTORE(0);
+  FWD_SSTORE(0, 0);
   __syncthreads();
   bf16x8_t qf[DQ / 16];
 #pragma unroll
@@ -252,7 +291,7 @@ void attn_fwd_kernel(const AttnArgs a) {
           oacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Vt[cur], u * 32 + l32, s, hh), pf, oacc[u], 0, 0, 0);
       }
     }
-    if (j + 1 < n_kv) FWD_SSTORE(cur ^ 1);
+    if (j + 1 < n_kv) FWD_SSTORE(cur ^ 1, j + 1);
     __syncthreads();
   }
 #undef FWD_GLOAD
@@ -306,8 +345,8 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) bf16_t Kt[DQ * 64];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[64 * DV];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, l32 = lane & 31;
-  const int qt = gridDim.x - 1 - blockIdx.x;
-  const int head = blockIdx.y, b = blockIdx.z;
+  int qt, head, b;
+  attn_work_item(a, (a.L + 127) / 128, qt, head, b);
   const int q0 = qt * 128;
   const long long tok0 = static_cast<long long>(b) * a.L;
   const bf16_t* Qg = a.qkv + head * a.kp_qk;
@@ -321,6 +360,7 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
   {
     if (sub < SUBS(DQ)) {
       sub_load<DQ>(pre, Qg, a.ld_qkv, tok0 + q0 + half * 64, a.L - q0 - half * 64, a.kp_qk, sub);
+      sub_mask<DQ>(pre, a.L - q0 - half * 64, a.kp_qk, sub);
       sub_store_nat<DQ>(pre, Qs + half * 64 * DQ, sub);
     }
     __syncthreads();
@@ -329,6 +369,7 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
     __syncthreads();
     if (sub < SUBS(DV)) {
       sub_load<DV>(pre, dOg, a.ld_o, tok0 + q0 + half * 64, a.L - q0 - half * 64, a.kp_vo, sub);
+      sub_mask<DV>(pre, a.L - q0 - half * 64, a.kp_vo, sub);
       sub_store_nat<DV>(pre, Qs + half * 64 * DV, sub);
     }
     __syncthreads();
@@ -358,8 +399,8 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
   for (int j = 0; j < n_kv; ++j) {
     const int kv0 = j * 64;
     __syncthreads();          // previous tile fully consumed
-    if (half == 0) { if (sub < SUBS(DQ)) { sub_store_nat<DQ>(pre, Ks, sub); sub_store_tr<DQ>(pre, Kt, sub); } }
-    else { if (sub < SUBS(DV)) sub_store_nat<DV>(pre, Vs, sub); }
+    if (half == 0) { if (sub < SUBS(DQ)) { sub_mask<DQ>(pre, a.L - kv0, a.kp_qk, sub); sub_store_nat<DQ>(pre, Ks, sub); sub_store_tr<DQ>(pre, Kt, sub); } }
+    else { if (sub < SUBS(DV)) { sub_mask<DV>(pre, a.L - kv0, a.kp_vo, sub); sub_store_nat<DV>(pre, Vs, sub); } }
     __syncthreads();
     if (j + 1 < n_kv) DQ_GLOAD(j + 1);
     if (a.causal && kv0 > qw0 + 31) continue;
@@ -420,8 +461,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   __shared__ __attribute__((aligned(16))) float lse_s[64];
   __shared__ __attribute__((aligned(16))) float dlt_s[64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, l32 = lane & 31;
-  const int kt = blockIdx.x;
-  const int head = blockIdx.y, b = blockIdx.z;
+  int kt, head, b;
+  attn_work_item(a, (a.L + 127) / 128, kt, head, b);
   const int k0 = kt * 128;
   const long long tok0 = static_cast<long long>(b) * a.L;
   const bf16_t* Qg = a.qkv + head * a.kp_qk;
@@ -435,6 +476,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   {
     if (sub < SUBS(DQ)) {
       sub_load<DQ>(pre, Kg, a.ld_qkv, tok0 + k0 + half * 64, a.L - k0 - half * 64, a.kp_qk, sub);
+      sub_mask<DQ>(pre, a.L - k0 - half * 64, a.kp_qk, sub);
       sub_store_nat<DQ>(pre, KVs + half * 64 * DQ, sub);
     }
     __syncthreads();
@@ -443,6 +485,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __syncthreads();
     if (sub < SUBS(DV)) {
       sub_load<DV>(pre, Vg, a.ld_qkv, tok0 + k0 + half * 64, a.L - k0 - half * 64, a.kp_vo, sub);
+      sub_mask<DV>(pre, a.L - k0 - half * 64, a.kp_vo, sub);
       sub_store_nat<DV>(pre, KVs + half * 64 * DV, sub);
     }
     __syncthreads();
@@ -474,16 +517,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     else { if (sub < SUBS(DV)) sub_load<DV>(pre, dOg, a.ld_o, tok0 + (j) * 64, a.L - (j) * 64, a.kp_vo, sub); }            \
     if (tid < 128) {                                                                                   \
       const int q_ = (j) * 64 + (tid & 63);                                                            \
-      st = q_ < a.L ? (tid < 64 ? a.lse[stat + q_] * LOG2E : a.delta[stat + q_]) : 0.f;                \
+      st = (tid < 64 ? a.lse : a.delta)[stat + min(q_, a.L - 1)];   /* Q and dO of rows beyond L are zero */  \
     }                                                                                                  \
   } while (0)
   if (j0 < n_q) KV_GLOAD(j0);
   for (int j = j0; j < n_q; ++j) {
     const int qb0 = j * 64;
     __syncthreads();
-    if (half == 0) { if (sub < SUBS(DQ)) { sub_store_nat<DQ>(pre, Qs, sub); sub_store_tr<DQ>(pre, Qt, sub); } }
-    else { if (sub < SUBS(DV)) { sub_store_nat<DV>(pre, dOs, sub); sub_store_tr<DV>(pre, dOt, sub); } }
-    if (tid < 64) lse_s[tid] = st;
+    if (half == 0) { if (sub < SUBS(DQ)) { sub_mask<DQ>(pre, a.L - qb0, a.kp_qk, sub); sub_store_nat<DQ>(pre, Qs, sub); sub_store_tr<DQ>(pre, Qt, sub); } }
+    else { if (sub < SUBS(DV)) { sub_mask<DV>(pre, a.L - qb0, a.kp_vo, sub); sub_store_nat<DV>(pre, dOs, sub); sub_store_tr<DV>(pre, dOt, sub); } }
+    if (tid < 64) lse_s[tid] = st * LOG2E;
     else if (tid < 128) dlt_s[tid - 64] = st;
     __syncthreads();
     if (j + 1 < n_q) KV_GLOAD(j + 1);
@@ -587,7 +630,7 @@ static int pad32(int kp) { return (kp + 31) / 32 * 32; }
 
 template <int DQ, int DV>
 static void launch_core(int which, const AttnArgs& a, hipStream_t st) {
-  const dim3 grid((a.L + 127) / 128, a.h, a.B);
+  const dim3 grid(static_cast<unsigned>((a.L + 127) / 128) * a.h * a.B);
   if (which == 0) hipLaunchKernelGGL((attn_fwd_kernel<DQ, DV>), grid, dim3(256), 0, st, a);
   else if (which == 1) hipLaunchKernelGGL((attn_bwd_dq_kernel<DQ, DV>), grid, dim3(256), 0, st, a);
   else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<DQ, DV>), grid, dim3(256), 0, st, a);

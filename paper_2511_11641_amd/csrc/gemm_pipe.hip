@@ -82,10 +82,18 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
+  // Workgroups go round-robin to the 8 XCDs, each with an L2 of its own: give every XCD a contiguous
+  // range of tile ids, and order the ids in bands of GROUP_M tile rows, column by column inside a
+  // band, so that the ~32 tiles an XCD works on at a time form a near-square block of C and share
+  // their operand rows in that L2.
   int id = blockIdx.x;
   const int nb = gridDim.x;
-  if ((nb & 7) == 0) id = (id & 7) * (nb >> 3) + (id >> 3);   // contiguous tile range per XCD
-  const int m0 = (id / tiles_n) * BM, n0 = (id % tiles_n) * BN;
+  if ((nb & 7) == 0) id = (id & 7) * (nb >> 3) + (id >> 3);
+  constexpr int GROUP_M = BM >= 256 ? 4 : 8;
+  const int tiles_m = nb / tiles_n;
+  const int band = id / (GROUP_M * tiles_n), in_band = id - band * (GROUP_M * tiles_n);
+  const int band_rows = min(GROUP_M, tiles_m - band * GROUP_M);
+  const int m0 = (band * GROUP_M + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
   const int k_begin = blockIdx.z * k_chunk;
   const int k_end = min(d.K, k_begin + k_chunk);
   const int nk = (k_end - k_begin) / BK;               // full slabs only (checked on the host)
@@ -248,7 +256,10 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   X(128, 256, 64, 3, 2, 2, 1)    \
   X(128, 128, 64, 2, 2, 2, 2)    \
   X(256, 256, 64, 2, 2, 4, 2)    \
-  X(128, 128, 32, 4, 2, 2, 2)
+  X(128, 128, 32, 4, 2, 2, 2)    \
+  X(256, 256, 32, 4, 2, 4, 2)    \
+  X(256, 256, 32, 5, 2, 4, 2)    \
+  X(256, 128, 64, 3, 4, 2, 2)
 #define PIPE_INSTANTIATE(BM, BN, BK, NS, WGM, WGN, WPE)                                                             \
   template __global__ void gemm_bf16_pipe_kernel<BM, BN, BK, NS, WGM, WGN, WPE, false, false>(const GemmDesc, int, int); \
   template __global__ void gemm_bf16_pipe_kernel<BM, BN, BK, NS, WGM, WGN, WPE, false, true>(const GemmDesc, int, int);  \
@@ -286,7 +297,7 @@ static hipError_t launch_pipe(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
 
 int gemm_pipe_bk(int cfg) {
   switch (cfg) {
-    case 1: case 6: return 32;
+    case 1: case 6: case 7: case 8: return 32;
     default: return 64;
   }
 }
@@ -308,6 +319,9 @@ hipError_t gemm_pipe_launch(ecospa_ctx* ctx, const GemmDesc& d, int cfg, int k_c
     case 4: return launch_pipe<128, 128, 64, 2, 2, 2, 2>(ctx, d, k_chunk);
     case 5: return launch_pipe<256, 256, 64, 2, 2, 4, 2>(ctx, d, k_chunk);
     case 6: return launch_pipe<128, 128, 32, 4, 2, 2, 2>(ctx, d, k_chunk);
+    case 7: return launch_pipe<256, 256, 32, 4, 2, 4, 2>(ctx, d, k_chunk);
+    case 8: return launch_pipe<256, 256, 32, 5, 2, 4, 2>(ctx, d, k_chunk);
+    case 9: return launch_pipe<256, 128, 64, 3, 4, 2, 2>(ctx, d, k_chunk);
     default: return hipErrorInvalidValue;
   }
 }

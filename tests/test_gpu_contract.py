@@ -72,7 +72,7 @@ def test_contract_alignment_errors(ctx):
     assert e.value.code == B.ERR_ALIGN
 
 
-@pytest.mark.parametrize("cfg", range(7))
+@pytest.mark.parametrize("cfg", range(10))
 @pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, True)])
 @pytest.mark.parametrize("M,N,K", [(520, 264, 192), (256, 512, 64), (304, 136, 512)])
 def test_contract_bf16_pipelined_tiles(ctx, M, N, K, ta, tb, cfg):
