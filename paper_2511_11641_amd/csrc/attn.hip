@@ -37,26 +37,99 @@ struct AttnArgs {
 };
 
 // ---------------------------------------------------------------------------------------------
-// LDS tile addressing (element offsets); 16-byte chunks are XOR-swizzled against bank conflicts
+// LDS tile addressing (element offsets).  Tiles are [rows][D] (D = 32 or 64 dims, 16-byte chunks
+// XOR-swizzled by row) and are read two ways:
+//   frag_nat: ds_read_b128, lane (l32, hh) takes chunk 2s+hh of row l32 - sixteen consecutive rows
+//             of one chunk column must fall on sixteen different 16-byte bank groups;
+//   frag_trn: ds_read_b64_tr_b16, a 16-lane group takes 4 rows x 16 dims - the four rows must fall
+//             on four different 64-byte bank groups.
+// D = 64 (128-byte rows): swizzle (row % 8) ^ bit 3 of row ^ (bit 1 of row) << 2 serves both;
+// D = 32 (64-byte rows, a transposing read covers whole rows): (row / 4) % 4.
 // ---------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) bf16_t lds_bf16_t;
+typedef short shortx4_t __attribute__((ext_vector_type(4)));
+typedef short shortx8_t __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) shortx4_t lds_shortx4_t;
+
+template <int D>
+__device__ __forceinline__ int nat_swz(int row) {
+  return D >= 64 ? ((row & 7) ^ ((row >> 3) & 1) ^ (((row >> 1) & 1) << 2)) : ((row >> 2) & 3);
+}
 template <int D>
 __device__ __forceinline__ int nat_off(int row, int chunk) {   // [rows][D], D in {32, 64}
-  constexpr int C = D / 8, RPL = D >= 64 ? 1 : 64 / D;   // chunks per row, rows per 128 bytes
-  return row * D + ((chunk ^ ((row / RPL) & (C - 1))) << 3);
-}
-__device__ __forceinline__ int tr_off(int row, int chunk) {    // [dims][64 tokens]
-  return row * 64 + ((chunk ^ ((row ^ (row >> 3)) & 7)) << 3);
+  return row * D + ((chunk ^ nat_swz<D>(row)) << 3);
 }
 template <int D>
 __device__ __forceinline__ bf16x8_t frag_nat(const bf16_t* tile, int row, int s, int hh) {
   return *reinterpret_cast<const bf16x8_t*>(tile + nat_off<D>(row, 2 * s + hh));
 }
-// 8 tokens {16*s + 4*hh + 0..3, 16*s + 8 + 4*hh + 0..3} of one dim row of a transposed tile
-__device__ __forceinline__ bf16x8_t frag_tr(const bf16_t* tile, int row, int s, int hh) {
-  const u32x2 lo = *reinterpret_cast<const u32x2*>(tile + tr_off(row, 2 * s) + 4 * hh);
-  const u32x2 hi = *reinterpret_cast<const u32x2*>(tile + tr_off(row, 2 * s + 1) + 4 * hh);
-  const u32x4 v = {lo.x, lo.y, hi.x, hi.y};
+// Operand taken transposed from a natural tile with ds_read_b64_tr_b16: lane (l32, hh) gets dim
+// dim0 + l32 of the rows {16s + 4hh + 0..3, 16s + 8 + 4hh + 0..3} - the order in which acc_to_frag()
+// lays out the contraction index.  Within a 16-lane group, lane i addresses (row i / 4, dims
+// 4 * (i % 4) ..+3) and receives dim i of the group's four rows.
+// The reads are issued through inline assembly: the compiler would hold the builtin form back until
+// every direct global->LDS load in flight has landed (it cannot tell the stream buffers apart), which
+// would undo the prefetch.  trn_issue() starts the two reads of a fragment, trn_wait() waits for all LDS
+// reads issued so far, trn_frag() then hands a fragment over (its empty asm statements keep the uses
+// behind the wait).
+struct TrnRegs { shortx4_t lo, hi; };
+template <int D>
+__device__ __forceinline__ void trn_issue(TrnRegs& r, const bf16_t* tile, int dim0, int s) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, i = lane & 15;
+  const int row = 16 * s + 4 * (g >> 1) + (i >> 2);
+  const int col = dim0 + 16 * (g & 1) + 4 * (i & 3);
+  const lds_bf16_t* t3 = (const lds_bf16_t*)tile;
+  const unsigned a0 = static_cast<unsigned>(reinterpret_cast<uintptr_t>(t3 + nat_off<D>(row, col >> 3) + (col & 7)));
+  const unsigned a1 = static_cast<unsigned>(reinterpret_cast<uintptr_t>(t3 + nat_off<D>(row + 8, col >> 3) + (col & 7)));
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r.lo) : "v"(a0) : "memory");
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r.hi) : "v"(a1) : "memory");
+}
+__device__ __forceinline__ void trn_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ bf16x8_t trn_frag(TrnRegs& r) {
+  asm volatile("" : "+v"(r.lo), "+v"(r.hi));
+  const shortx8_t v = {r.lo[0], r.lo[1], r.lo[2], r.lo[3], r.hi[0], r.hi[1], r.hi[2], r.hi[3]};
   return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// Stream of [64 rows][D] tiles of a row-major matrix into LDS with direct global->LDS loads (no
+// registers in between): each of the workgroup's 4 wavefronts moves PER kilobytes per tile; an
+// instruction fills RPI consecutive tile rows, lane by lane, so the swizzle is applied on the
+// global side (the lane that owns physical chunk pc of a row fetches the logical chunk that maps
+// there).  Rows beyond the end of the sequence repeat its last row and dims beyond the kept width
+// repeat the last kept chunk: finite stand-ins that the callers keep out of every result (masked
+// scores; a zero-padded partner operand; output columns that are never stored).
+template <int D>
+struct TileStream {
+  static constexpr int CPR = D / 8, RPI = 64 / CPR, PER = (64 / RPI) / 4;
+  const bf16_t* base;
+  long long ld;
+  int row[PER], col[PER];
+  __device__ __forceinline__ void init(const bf16_t* b, long long l, int kp) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    base = b;
+    ld = l;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int r = (wave * PER + i) * RPI + lane / CPR, pc = lane % CPR;
+      row[i] = r;
+      col[i] = min((pc ^ nat_swz<D>(r)) * 8, kp - 8);
+    }
+  }
+  // rows g0 .. g0 + 63 of the matrix, of which the first rows_valid (>= 1) exist
+  __device__ __forceinline__ void issue(bf16_t* tile, long long g0, int rows_valid) const {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const bf16_t* src = base + (g0 + min(row[i], rows_valid - 1)) * ld + col[i];
+      __builtin_amdgcn_global_load_lds(src, (lds_bf16_t*)tile + (wave * PER + i) * 512, 16, 0, 0);
+    }
+  }
+};
+// own direct loads have landed (then a barrier tells the same of everyone's)
+__device__ __forceinline__ void stream_wait() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0);   // vmcnt(0) lgkmcnt(0) expcnt(0)
+  asm volatile("" ::: "memory");
 }
 // accumulator registers 8*half .. 8*half+7 as a bf16 B operand
 __device__ __forceinline__ bf16x8_t acc_to_frag(const floatx16& a, int half) {
@@ -100,20 +173,6 @@ __device__ __forceinline__ void sub_store_nat(const u32x4 (&v)[4], bf16_t* tile,
   const int tblk = sub / (D / 8), dblk = sub % (D / 8);
 #pragma unroll
   for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(tile + nat_off<D>(tblk * 4 + i, dblk)) = v[i];
-}
-template <int D>
-__device__ __forceinline__ void sub_store_tr(const u32x4 (&v)[4], bf16_t* tile, int sub) {
-  const int tblk = sub / (D / 8), dblk = sub % (D / 8);
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    uint32_t e[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) e[i] = (j & 1) ? (v[i][j >> 1] >> 16) : (v[i][j >> 1] & 0xffffu);
-    u32x2 p;
-    p.x = e[0] | (e[1] << 16);
-    p.y = e[2] | (e[3] << 16);
-    *reinterpret_cast<u32x2*>(tile + tr_off(dblk * 8 + j, tblk >> 1) + 4 * (tblk & 1)) = p;
-  }
 }
 #define SUBS(D) (16 * ((D) / 8))
 
@@ -180,123 +239,132 @@ template <int DQ, int DV>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ, DV, 4), ATTN_WPE(DQ, DV, 4))))
 void attn_fwd_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[128 * DMAX];   // Q tile, later the O staging tile
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[2][64 * DQ];
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[2][DV * 64];
+  // One LDS object per kernel, carved by hand: with several, the compiler tags every LDS access with the
+  // object it touches and then holds each read of a stream buffer back until the direct loads into the
+  // other half of that buffer have landed.
+  __shared__ __attribute__((aligned(16))) bf16_t lds_all[128 * DMAX + 2 * 64 * DQ + 2 * 64 * DV];
+  bf16_t* const Qs = lds_all;                                      // Q tile, later the O staging tile
+  bf16_t* const Ks0 = Qs + 128 * DMAX;        // [2][64 * DQ]
+  bf16_t* const Vs0 = Ks0 + 2 * 64 * DQ;      // [2][64 * DV]
+#define Ks(buf) (Ks0 + (buf) * (64 * DQ))
+#define Vs(buf) (Vs0 + (buf) * (64 * DV))
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, l32 = lane & 31;
   int qt, head, b;
   attn_work_item(a, (a.L + 127) / 128, qt, head, b);
   const int q0 = qt * 128;
   const long long tok0 = static_cast<long long>(b) * a.L;
   const bf16_t* Qg = a.qkv + head * a.kp_qk;
-  const bf16_t* Kg = a.qkv + a.h * a.kp_qk + head * a.kp_qk;
-  const bf16_t* Vg = a.qkv + 2 * a.h * a.kp_qk + head * a.kp_vo;
   const int half = tid >> 7, sub = tid & 127;
 
-  // Q tile: two 64-row halves, one per half of the workgroup
-  u32x4 pre[4];   // this thread's sub-block of the tile in flight (K for half 0, V for half 1)
+  // key/value tiles stream straight into LDS, one tile ahead of the one being used
+  TileStream<DQ> ks;
+  TileStream<DV> vs;
+  ks.init(a.qkv + a.h * a.kp_qk + head * a.kp_qk, a.ld_qkv, a.kp_qk);
+  vs.init(a.qkv + 2 * a.h * a.kp_qk + head * a.kp_vo, a.ld_qkv, a.kp_vo);
+  ks.issue(Ks(0), tok0, a.L);
+  vs.issue(Vs(0), tok0, a.L);
+
+  // Q tile: two 64-row halves, one per half of the workgroup (rows and dims outside are zeroed)
   if (sub < SUBS(DQ)) {
+    u32x4 pre[4];
     sub_load<DQ>(pre, Qg, a.ld_qkv, tok0 + q0 + half * 64, a.L - q0 - half * 64, a.kp_qk, sub);
     sub_mask<DQ>(pre, a.L - q0 - half * 64, a.kp_qk, sub);
     sub_store_nat<DQ>(pre, Qs + half * 64 * DQ, sub);
   }
   const int kv_end = a.causal ? min(a.L, q0 + 128) : a.L;
   const int n_kv = (kv_end + 63) / 64;
-#define FWD_GLOAD(j)                                                                                   \
-  do {                                                                                                 \
-    if (half == 0) { if (sub < SUBS(DQ)) sub_load<DQ>(pre, Kg, a.ld_qkv, tok0 + (j) * 64, a.L - (j) * 64, a.kp_qk, sub); } \
-    else { if (sub < SUBS(DV)) sub_load<DV>(pre, Vg, a.ld_qkv, tok0 + (j) * 64, a.L - (j) * 64, a.kp_vo, sub); }           \
-  } while (0)
-#define FWD_SSTORE(buf, j)                                                                                     \
-  do {                                                                                                         \
-    if (half == 0) { if (sub < SUBS(DQ)) { sub_mask<DQ>(pre, a.L - (j) * 64, a.kp_qk, sub); sub_store_nat<DQ>(pre, Ks[buf], sub); } } \
-    else { if (sub < SUBS(DV)) { sub_mask<DV>(pre, a.L - (j) * 64, a.kp_vo, sub); sub_store_tr<DV>(pre, Vt[buf], sub); } }             \
-  } while (0)
-  FWD_GLOAD(0);
-  FWD_SSTORE(0, 0);
   __syncthreads();
   bf16x8_t qf[DQ / 16];
 #pragma unroll
   for (int s = 0; s < DQ / 16; ++s) qf[s] = frag_nat<DQ>(Qs, wave * 32 + l32, s, hh);
 
-  floatx16 oacc[DV / 32];
+  // oacc: O^T (dims x queries); lacc: the softmax denominators, accumulated by the matrix unit from
+  // the same rounded probabilities as the numerator (an all-ones operand in place of V^T, so every
+  // row of lacc holds the row sums)
+  floatx16 oacc[DV / 32], lacc;
 #pragma unroll
   for (int u = 0; u < DV / 32; ++u)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[u][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) lacc[r] = 0.f;
+  bf16x8_t ones;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ones[i] = static_cast<__bf16>(1.0f);
+  float m_run = -INFINITY;
   const float sc = a.scale * LOG2E;
   const int qw0 = q0 + wave * 32, q_idx = qw0 + l32;
 
   for (int j = 0; j < n_kv; ++j) {
     const int cur = j & 1, kv0 = j * 64;
-    if (j + 1 < n_kv) FWD_GLOAD(j + 1);
-    const bool active = !(a.causal && kv0 > qw0 + 31);
-    if (active) {
-      floatx16 sacc[2];
+    stream_wait();
+    __syncthreads();    // tile j is in LDS; every wavefront is done with tile j-1, whose buffer is refilled now
+    if (j + 1 < n_kv) {
+      ks.issue(Ks(cur ^ 1), tok0 + kv0 + 64, a.L - kv0 - 64);
+      vs.issue(Vs(cur ^ 1), tok0 + kv0 + 64, a.L - kv0 - 64);
+    }
+    if (a.causal && kv0 > qw0 + 31) continue;   // no query of this wavefront sees the tile
+    floatx16 sacc[2];
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < 2; ++t) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[t][r] = 0.f;
+      for (int r = 0; r < 16; ++r) sacc[t][r] = 0.f;
 #pragma unroll
-        for (int s = 0; s < DQ / 16; ++s)
-          sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DQ>(Ks[cur], t * 32 + l32, s, hh), qf[s], sacc[t], 0, 0, 0);
-      }
-      // Softmax on raw scores: the scale is folded into the exponent's FMA.  Masking is a
-      // wave-uniform special case (tiles on the diagonal or at the end of the sequence) done
-      // with selects, never with divergent branches.
-      if ((a.causal && kv0 + 63 > qw0) || (kv0 + 64 > a.L)) {
-        const int lim = a.causal ? min(q_idx, a.L - 1) : a.L - 1;   // last visible key of this query
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = kv0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
-            sacc[t][r] = key > lim ? -INFINITY : sacc[t][r];
-          }
-      }
-      float mx = sacc[0][0];
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);                       // raw (unscaled) running maximum
-      const float msc = (m_new == -INFINITY ? 0.f : m_new) * sc;
-      float psum = 0.f;
+      for (int s = 0; s < DQ / 16; ++s)
+        sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DQ>(Ks(cur), t * 32 + l32, s, hh), qf[s], sacc[t], 0, 0, 0);
+    }
+    // Softmax on raw scores: the scale is folded into the exponent's FMA.  Masking is a
+    // wave-uniform special case (tiles on the diagonal or at the end of the sequence) done
+    // with selects, never with divergent branches.
+    if ((a.causal && kv0 + 63 > qw0) || (kv0 + 64 > a.L)) {
+      const int lim = a.causal ? min(q_idx, a.L - 1) : a.L - 1;   // last visible key of this query
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[t][r], sc, -msc));
-          sacc[t][r] = p;
-          psum += p;
+          const int key = kv0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
+          sacc[t][r] = key > lim ? -INFINITY : sacc[t][r];
         }
-      // rescale the running sums only when some query's maximum moved (wave-uniform test)
-      if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull) {
-        const float alpha = __builtin_amdgcn_exp2f(__builtin_fmaf(m_run, sc, -msc));
-        l_run *= alpha;
-#pragma unroll
-        for (int u = 0; u < DV / 32; ++u)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[u][r] *= alpha;
-      }
-      l_run += psum;
-      m_run = m_new;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const bf16x8_t pf = acc_to_frag(sacc[s >> 1], s & 1);
-#pragma unroll
-        for (int u = 0; u < DV / 32; ++u)
-          oacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Vt[cur], u * 32 + l32, s, hh), pf, oacc[u], 0, 0, 0);
-      }
     }
-    if (j + 1 < n_kv) FWD_SSTORE(cur ^ 1, j + 1);
-    __syncthreads();
+    float mx = sacc[0][0];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);                       // raw (unscaled) running maximum
+    const float msc = (m_new == -INFINITY ? 0.f : m_new) * sc;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[t][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[t][r], sc, -msc));
+    // rescale the running sums only when some query's maximum moved (wave-uniform test)
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull) {
+      const float alpha = __builtin_amdgcn_exp2f(__builtin_fmaf(m_run, sc, -msc));
+#pragma unroll
+      for (int r = 0; r < 16; ++r) lacc[r] *= alpha;
+#pragma unroll
+      for (int u = 0; u < DV / 32; ++u)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[u][r] *= alpha;
+    }
+    m_run = m_new;
+    TrnRegs vr[4][DV / 32];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int u = 0; u < DV / 32; ++u) trn_issue<DV>(vr[s][u], Vs(cur), u * 32, s);
+    trn_wait();
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const bf16x8_t pf = acc_to_frag(sacc[s >> 1], s & 1);
+      lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, lacc, 0, 0, 0);
+#pragma unroll
+      for (int u = 0; u < DV / 32; ++u)
+        oacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trn_frag(vr[s][u]), pf, oacc[u], 0, 0, 0);
+    }
   }
-#undef FWD_GLOAD
-#undef FWD_SSTORE
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = lacc[0];
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   if (hh == 0 && q_idx < a.L)
     a.lse[(static_cast<long long>(b) * a.h + head) * a.L + q_idx] = (m_run * sc + __log2f(l_tot)) * LN2;
@@ -305,6 +373,8 @@ void attn_fwd_kernel(const AttnArgs a) {
   for (int u = 0; u < DV / 32; ++u) acc_to_tile<DV>(Qs, wave * 32 + l32, u, oacc[u], inv, hh);
   __syncthreads();
   tile_to_global<DV>(Qs, 128, a.o + head * a.kp_vo, a.ld_o, tok0 + q0, a.L - q0, a.kp_vo);
+#undef Ks
+#undef Vs
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -340,24 +410,32 @@ template <int DQ, int DV>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ, DV, 3), ATTN_WPE(DQ, DV, 3))))
 void attn_bwd_dq_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[128 * DMAX];   // Q tile, then dO tile, then dQ staging
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * DQ];
-  __shared__ __attribute__((aligned(16))) bf16_t Kt[DQ * 64];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[64 * DV];
+  __shared__ __attribute__((aligned(16))) bf16_t lds_all[128 * DMAX + 2 * 64 * DQ + 2 * 64 * DV];   // one object: see attn_fwd_kernel
+  bf16_t* const Qs = lds_all;                                      // Q tile, then dO tile, then dQ staging
+  bf16_t* const Ks0 = Qs + 128 * DMAX;        // [2][64 * DQ]
+  bf16_t* const Vs0 = Ks0 + 2 * 64 * DQ;      // [2][64 * DV]
+#define Ks(buf) (Ks0 + (buf) * (64 * DQ))
+#define Vs(buf) (Vs0 + (buf) * (64 * DV))
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, l32 = lane & 31;
   int qt, head, b;
   attn_work_item(a, (a.L + 127) / 128, qt, head, b);
   const int q0 = qt * 128;
   const long long tok0 = static_cast<long long>(b) * a.L;
   const bf16_t* Qg = a.qkv + head * a.kp_qk;
-  const bf16_t* Kg = a.qkv + a.h * a.kp_qk + head * a.kp_qk;
-  const bf16_t* Vg = a.qkv + 2 * a.h * a.kp_qk + head * a.kp_vo;
   const bf16_t* dOg = a.d_o + head * a.kp_vo;
   const int half = tid >> 7, sub = tid & 127;
 
+  // key/value tiles stream straight into LDS, one tile ahead of the one being used
+  TileStream<DQ> ks;
+  TileStream<DV> vs;
+  ks.init(a.qkv + a.h * a.kp_qk + head * a.kp_qk, a.ld_qkv, a.kp_qk);
+  vs.init(a.qkv + 2 * a.h * a.kp_qk + head * a.kp_vo, a.ld_qkv, a.kp_vo);
+  ks.issue(Ks(0), tok0, a.L);
+  vs.issue(Vs(0), tok0, a.L);
+
   bf16x8_t qf[DQ / 16], dof[DV / 16];
-  u32x4 pre[4];
   {
+    u32x4 pre[4];
     if (sub < SUBS(DQ)) {
       sub_load<DQ>(pre, Qg, a.ld_qkv, tok0 + q0 + half * 64, a.L - q0 - half * 64, a.kp_qk, sub);
       sub_mask<DQ>(pre, a.L - q0 - half * 64, a.kp_qk, sub);
@@ -390,19 +468,14 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
 
   const int kv_end = a.causal ? min(a.L, q0 + 128) : a.L;
   const int n_kv = (kv_end + 63) / 64;
-#define DQ_GLOAD(j)                                                                                    \
-  do {                                                                                                 \
-    if (half == 0) { if (sub < SUBS(DQ)) sub_load<DQ>(pre, Kg, a.ld_qkv, tok0 + (j) * 64, a.L - (j) * 64, a.kp_qk, sub); } \
-    else { if (sub < SUBS(DV)) sub_load<DV>(pre, Vg, a.ld_qkv, tok0 + (j) * 64, a.L - (j) * 64, a.kp_vo, sub); }           \
-  } while (0)
-  DQ_GLOAD(0);
   for (int j = 0; j < n_kv; ++j) {
-    const int kv0 = j * 64;
-    __syncthreads();          // previous tile fully consumed
-    if (half == 0) { if (sub < SUBS(DQ)) { sub_mask<DQ>(pre, a.L - kv0, a.kp_qk, sub); sub_store_nat<DQ>(pre, Ks, sub); sub_store_tr<DQ>(pre, Kt, sub); } }
-    else { if (sub < SUBS(DV)) { sub_mask<DV>(pre, a.L - kv0, a.kp_vo, sub); sub_store_nat<DV>(pre, Vs, sub); } }
-    __syncthreads();
-    if (j + 1 < n_kv) DQ_GLOAD(j + 1);
+    const int cur = j & 1, kv0 = j * 64;
+    stream_wait();
+    __syncthreads();    // tile j is in LDS; every wavefront is done with tile j-1, whose buffer is refilled now
+    if (j + 1 < n_kv) {
+      ks.issue(Ks(cur ^ 1), tok0 + kv0 + 64, a.L - kv0 - 64);
+      vs.issue(Vs(cur ^ 1), tok0 + kv0 + 64, a.L - kv0 - 64);
+    }
     if (a.causal && kv0 > qw0 + 31) continue;
     const bool need_mask = (a.causal && kv0 + 63 > qw0) || (kv0 + 64 > a.L);
     const int lim = a.causal ? min(q_idx, a.L - 1) : a.L - 1;       // last visible key of this query
@@ -413,10 +486,10 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
       for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
 #pragma unroll
       for (int s = 0; s < DQ / 16; ++s)
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DQ>(Ks, t * 32 + l32, s, hh), qf[s], sacc, 0, 0, 0);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DQ>(Ks(cur), t * 32 + l32, s, hh), qf[s], sacc, 0, 0, 0);
 #pragma unroll
       for (int s = 0; s < DV / 16; ++s)
-        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DV>(Vs, t * 32 + l32, s, hh), dof[s], pacc, 0, 0, 0);
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DV>(Vs(cur), t * 32 + l32, s, hh), dof[s], pacc, 0, 0, 0);
       if (need_mask) {        // wave-uniform; selects only
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -429,21 +502,28 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
         const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[r], sc, -lse2));
         sacc[r] = p * (pacc[r] - dlt);
       }
+      TrnRegs kr[2][DQ / 32];
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int u = 0; u < DQ / 32; ++u) trn_issue<DQ>(kr[s2][u], Ks(cur), u * 32, t * 2 + s2);
+      trn_wait();
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
         const bf16x8_t df = acc_to_frag(sacc, s2);
 #pragma unroll
         for (int u = 0; u < DQ / 32; ++u)
-          dq[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Kt, u * 32 + l32, t * 2 + s2, hh), df, dq[u], 0, 0, 0);
+          dq[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trn_frag(kr[s2][u]), df, dq[u], 0, 0, 0);
       }
     }
   }
-#undef DQ_GLOAD
   __syncthreads();
 #pragma unroll
   for (int u = 0; u < DQ / 32; ++u) acc_to_tile<DQ>(Qs, wave * 32 + l32, u, dq[u], a.scale, hh);
   __syncthreads();
   tile_to_global<DQ>(Qs, 128, a.dqkv + head * a.kp_qk, a.ld_qkv, tok0 + q0, a.L - q0, a.kp_qk);
+#undef Ks
+#undef Vs
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -453,13 +533,15 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
 template <int DQ, int DV>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkdv_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
-  __shared__ __attribute__((aligned(16))) bf16_t KVs[128 * DMAX];   // K tile, V tile, then output staging
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[64 * DQ];
-  __shared__ __attribute__((aligned(16))) bf16_t Qt[DQ * 64];
-  __shared__ __attribute__((aligned(16))) bf16_t dOs[64 * DV];
-  __shared__ __attribute__((aligned(16))) bf16_t dOt[DV * 64];
-  __shared__ __attribute__((aligned(16))) float lse_s[64];
-  __shared__ __attribute__((aligned(16))) float dlt_s[64];
+  __shared__ __attribute__((aligned(16))) bf16_t lds_all[128 * DMAX + 2 * 64 * DQ + 2 * 64 * DV + 512];   // one object: see attn_fwd_kernel
+  bf16_t* const KVs = lds_all;                                     // K tile, V tile, then output staging
+  bf16_t* const Qs0 = KVs + 128 * DMAX;       // [2][64 * DQ]
+  bf16_t* const dOs0 = Qs0 + 2 * 64 * DQ;     // [2][64 * DV]
+  float* const stats = reinterpret_cast<float*>(dOs0 + 2 * 64 * DV);   // [2][64] log-sum-exp, [2][64] delta
+#define Qs(buf) (Qs0 + (buf) * (64 * DQ))
+#define dOs(buf) (dOs0 + (buf) * (64 * DV))
+#define lse_s(buf) (stats + (buf) * 64)
+#define dlt_s(buf) (stats + 128 + (buf) * 64)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, l32 = lane & 31;
   int kt, head, b;
   attn_work_item(a, (a.L + 127) / 128, kt, head, b);
@@ -508,28 +590,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   const int n_q = (a.L + 63) / 64;
   const int j0 = a.causal ? k0 / 64 : 0;     // first query tile that can see a key of this tile
+  // Query tiles (Q and dO) stream straight into LDS, one tile ahead; the tile's 64 log-sum-exp and
+  // delta values travel through a register of threads 0..127 and are parked in LDS one iteration later.
+  TileStream<DQ> qs;
+  TileStream<DV> ds;
+  qs.init(Qg, a.ld_qkv, a.kp_qk);
+  ds.init(dOg, a.ld_o, a.kp_vo);
   float st = 0.f;
-  // query-tile prefetch: half 0 fetches Q, half 1 fetches dO; threads 0..63 also fetch lse,
-  // threads 64..127 delta, of the tile's 64 queries
-#define KV_GLOAD(j)                                                                                    \
+#define KV_ISSUE(j, buf)                                                                               \
   do {                                                                                                 \
-    if (half == 0) { if (sub < SUBS(DQ)) sub_load<DQ>(pre, Qg, a.ld_qkv, tok0 + (j) * 64, a.L - (j) * 64, a.kp_qk, sub); } \
-    else { if (sub < SUBS(DV)) sub_load<DV>(pre, dOg, a.ld_o, tok0 + (j) * 64, a.L - (j) * 64, a.kp_vo, sub); }            \
-    if (tid < 128) {                                                                                   \
-      const int q_ = (j) * 64 + (tid & 63);                                                            \
-      st = (tid < 64 ? a.lse : a.delta)[stat + min(q_, a.L - 1)];   /* Q and dO of rows beyond L are zero */  \
-    }                                                                                                  \
+    qs.issue(Qs(buf), tok0 + (j) * 64, a.L - (j) * 64);                                                \
+    ds.issue(dOs(buf), tok0 + (j) * 64, a.L - (j) * 64);                                               \
+    if (tid < 128) st = (tid < 64 ? a.lse : a.delta)[stat + min((j) * 64 + (tid & 63), a.L - 1)];      \
   } while (0)
-  if (j0 < n_q) KV_GLOAD(j0);
+  if (j0 < n_q) KV_ISSUE(j0, 0);
   for (int j = j0; j < n_q; ++j) {
-    const int qb0 = j * 64;
-    __syncthreads();
-    if (half == 0) { if (sub < SUBS(DQ)) { sub_mask<DQ>(pre, a.L - qb0, a.kp_qk, sub); sub_store_nat<DQ>(pre, Qs, sub); sub_store_tr<DQ>(pre, Qt, sub); } }
-    else { if (sub < SUBS(DV)) { sub_mask<DV>(pre, a.L - qb0, a.kp_vo, sub); sub_store_nat<DV>(pre, dOs, sub); sub_store_tr<DV>(pre, dOt, sub); } }
-    if (tid < 64) lse_s[tid] = st * LOG2E;
-    else if (tid < 128) dlt_s[tid - 64] = st;
-    __syncthreads();
-    if (j + 1 < n_q) KV_GLOAD(j + 1);
+    const int qb0 = j * 64, cur = (j - j0) & 1;
+    if (tid < 64) lse_s(cur)[tid] = st * LOG2E;
+    else if (tid < 128) dlt_s(cur)[tid - 64] = st;
+    stream_wait();
+    __syncthreads();    // tile j is in LDS; every wavefront is done with tile j-1, whose buffers are refilled now
+    if (j + 1 < n_q) KV_ISSUE(j + 1, cur ^ 1);
     if (a.causal && qb0 + 63 < kw0) continue;          // every query of the tile precedes this wave's keys
     const bool need_mask = (a.causal && qb0 < kw0 + 31) || (qb0 + 64 > a.L) || (kw0 + 32 > a.L);
 #pragma unroll
@@ -539,18 +620,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
 #pragma unroll
       for (int s = 0; s < DQ / 16; ++s)
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DQ>(Qs, t * 32 + l32, s, hh), kf[s], sacc, 0, 0, 0);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DQ>(Qs(cur), t * 32 + l32, s, hh), kf[s], sacc, 0, 0, 0);
 #pragma unroll
       for (int s = 0; s < DV / 16; ++s)
-        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DV>(dOs, t * 32 + l32, s, hh), vf[s], pacc, 0, 0, 0);
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DV>(dOs(cur), t * 32 + l32, s, hh), vf[s], pacc, 0, 0, 0);
       floatx16 pr;
       // a query sees this lane's key if key <= q (causal) and both are inside the sequence
       const int q_min = key_idx >= a.L ? 0x7fffffff : (a.causal ? key_idx : 0);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int qrow = t * 32 + g * 8 + hh * 4;
-        const float4 ls = *reinterpret_cast<const float4*>(lse_s + qrow);
-        const float4 dl = *reinterpret_cast<const float4*>(dlt_s + qrow);
+        const float4 ls = *reinterpret_cast<const float4*>(lse_s(cur) + qrow);
+        const float4 dl = *reinterpret_cast<const float4*>(dlt_s(cur) + qrow);
         const float lsv[4] = {ls.x, ls.y, ls.z, ls.w}, dlv[4] = {dl.x, dl.y, dl.z, dl.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -565,19 +646,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           sacc[r] = p * (pacc[r] - dlv[i]);
         }
       }
+      TrnRegs dor[2][DV / 32], qr[2][DQ / 32];
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+#pragma unroll
+        for (int u = 0; u < DV / 32; ++u) trn_issue<DV>(dor[s2][u], dOs(cur), u * 32, t * 2 + s2);
+#pragma unroll
+        for (int u = 0; u < DQ / 32; ++u) trn_issue<DQ>(qr[s2][u], Qs(cur), u * 32, t * 2 + s2);
+      }
+      trn_wait();
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
         const bf16x8_t pf = acc_to_frag(pr, s2), df = acc_to_frag(sacc, s2);
 #pragma unroll
         for (int u = 0; u < DV / 32; ++u)
-          dv[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(dOt, u * 32 + l32, t * 2 + s2, hh), pf, dv[u], 0, 0, 0);
+          dv[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trn_frag(dor[s2][u]), pf, dv[u], 0, 0, 0);
 #pragma unroll
         for (int u = 0; u < DQ / 32; ++u)
-          dk[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Qt, u * 32 + l32, t * 2 + s2, hh), df, dk[u], 0, 0, 0);
+          dk[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trn_frag(qr[s2][u]), df, dk[u], 0, 0, 0);
       }
     }
   }
-#undef KV_GLOAD
+#undef KV_ISSUE
+#undef Qs
+#undef dOs
+#undef lse_s
+#undef dlt_s
   __syncthreads();
 #pragma unroll
   for (int u = 0; u < DQ / 32; ++u) acc_to_tile<DQ>(KVs, wave * 32 + l32, u, dk[u], a.scale, hh);
