@@ -22,6 +22,7 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 #define LOG2E 1.4426950408889634f
 #define LN2 0.6931471805599453f
+#define RESCALE_LOG2 8.0f   // forward softmax: growth of a row maximum (in binades) that triggers a rescale
 
 struct AttnArgs {
   const bf16_t* qkv;   // [T, nqkv]: Q | K | V column blocks, head-major inside each
@@ -103,6 +104,7 @@ struct TileStream {
   static constexpr int CPR = D / 8, RPI = 64 / CPR, PER = (64 / RPI) / 4;
   const bf16_t* base;
   long long ld;
+  const bf16_t* p0[PER];   // this lane's source in a tile that starts at row 0
   int row[PER], col[PER];
   __device__ __forceinline__ void init(const bf16_t* b, long long l, int kp) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -113,15 +115,23 @@ struct TileStream {
       const int r = (wave * PER + i) * RPI + lane / CPR, pc = lane % CPR;
       row[i] = r;
       col[i] = min((pc ^ nat_swz<D>(r)) * 8, kp - 8);
+      p0[i] = b + r * l + col[i];
     }
   }
   // rows g0 .. g0 + 63 of the matrix, of which the first rows_valid (>= 1) exist
   __device__ __forceinline__ void issue(bf16_t* tile, long long g0, int rows_valid) const {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (rows_valid >= 64) {      // uniform: one scalar product, one add per load
+      const long long adv = g0 * ld;
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const bf16_t* src = base + (g0 + min(row[i], rows_valid - 1)) * ld + col[i];
-      __builtin_amdgcn_global_load_lds(src, (lds_bf16_t*)tile + (wave * PER + i) * 512, 16, 0, 0);
+      for (int i = 0; i < PER; ++i)
+        __builtin_amdgcn_global_load_lds(p0[i] + adv, (lds_bf16_t*)tile + (wave * PER + i) * 512, 16, 0, 0);
+    } else {
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const bf16_t* src = base + (g0 + min(row[i], rows_valid - 1)) * ld + col[i];
+        __builtin_amdgcn_global_load_lds(src, (lds_bf16_t*)tile + (wave * PER + i) * 512, 16, 0, 0);
+      }
     }
   }
 };
@@ -332,23 +342,27 @@ void attn_fwd_kernel(const AttnArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);                       // raw (unscaled) running maximum
-    const float msc = (m_new == -INFINITY ? 0.f : m_new) * sc;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[t][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[t][r], sc, -msc));
-    // rescale the running sums only when some query's maximum moved (wave-uniform test)
-    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull) {
-      const float alpha = __builtin_amdgcn_exp2f(__builtin_fmaf(m_run, sc, -msc));
+    // Running reference maximum (raw, unscaled).  It only has to keep the exponentials in range, so it
+    // moves - and the accumulators are rescaled - only when some query's maximum has grown by more than
+    // RESCALE_LOG2 binades since the reference was set (wave-uniform test); until then probabilities
+    // up to 2^RESCALE_LOG2 are accumulated against the old reference.
+    const float m_new = fmaxf(m_run, mx);
+    if (__builtin_amdgcn_ballot_w64((m_new - m_run) * sc > RESCALE_LOG2 || (m_new > m_run && m_run == -INFINITY)) != 0ull) {
+      const float msc_new = (m_new == -INFINITY ? 0.f : m_new) * sc;
+      const float alpha = __builtin_amdgcn_exp2f(__builtin_fmaf(m_run, sc, -msc_new));
 #pragma unroll
       for (int r = 0; r < 16; ++r) lacc[r] *= alpha;
 #pragma unroll
       for (int u = 0; u < DV / 32; ++u)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[u][r] *= alpha;
+      m_run = m_new;
     }
-    m_run = m_new;
+    const float msc = (m_run == -INFINITY ? 0.f : m_run) * sc;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[t][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[t][r], sc, -msc));
     TrnRegs vr[4][DV / 32];
 #pragma unroll
     for (int s = 0; s < 4; ++s)
@@ -407,7 +421,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const AttnArgs a) {
 //   S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - delta), dQ^T += K^T dS^T
 // ---------------------------------------------------------------------------------------------
 template <int DQ, int DV>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ, DV, 3), ATTN_WPE(DQ, DV, 3))))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ, DV, 4), ATTN_WPE(DQ, DV, 4))))
 void attn_bwd_dq_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
   __shared__ __attribute__((aligned(16))) bf16_t lds_all[128 * DMAX + 2 * 64 * DQ + 2 * 64 * DV];   // one object: see attn_fwd_kernel
@@ -531,7 +545,7 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
 //   S = Q K^T, dP = dO V^T, dS = P * (dP - delta), dV^T += dO^T P, dK^T += Q^T dS
 // ---------------------------------------------------------------------------------------------
 template <int DQ, int DV>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkdv_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ, DV, 3), ATTN_WPE(DQ, DV, 3)))) void attn_bwd_dkdv_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
   __shared__ __attribute__((aligned(16))) bf16_t lds_all[128 * DMAX + 2 * 64 * DQ + 2 * 64 * DV + 512];   // one object: see attn_fwd_kernel
   bf16_t* const KVs = lds_all;                                     // K tile, V tile, then output staging
@@ -721,6 +735,18 @@ __global__ __launch_bounds__(256) void rope_kernel(bf16_t* __restrict__ buf, lon
 // host side
 // ---------------------------------------------------------------------------------------------
 static int pad32(int kp) { return (kp + 31) / 32 * 32; }
+
+// The head-width combinations that are built, instantiated explicitly (left to implicit instantiation
+// from the launch code, the host side of this compiler can drop some of the kernel stubs).
+#define ATTN_INSTANTIATE(DQ, DV)                                              \
+  template __global__ void attn_fwd_kernel<DQ, DV>(const AttnArgs);           \
+  template __global__ void attn_bwd_dq_kernel<DQ, DV>(const AttnArgs);        \
+  template __global__ void attn_bwd_dkdv_kernel<DQ, DV>(const AttnArgs);
+ATTN_INSTANTIATE(32, 32)
+ATTN_INSTANTIATE(32, 64)
+ATTN_INSTANTIATE(64, 32)
+ATTN_INSTANTIATE(64, 64)
+#undef ATTN_INSTANTIATE
 
 template <int DQ, int DV>
 static void launch_core(int which, const AttnArgs& a, hipStream_t st) {
