@@ -68,10 +68,24 @@ template <> __device__ __forceinline__ void store_f32<float>(float* p, float v) 
 template <> __device__ __forceinline__ void store_f32<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 
 // Sum over the 64 lanes of a wavefront; every lane gets the total (fixed order: deterministic).
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+// Inside each row of 16 lanes the partners come through DPP lane permutations (swap neighbours, swap
+// pairs, mirror halves of 8, mirror the row: after each step the lanes of the growing group agree), so
+// nothing goes through LDS; the four row sums are then read out and added in order.
+#define ECOSPA_DPP_ADD(v, ctrl) ((v) + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, (v)), (ctrl), 0xF, 0xF, true)))
+__device__ __forceinline__ float row16_sum(float v) {
+  v = ECOSPA_DPP_ADD(v, 0xB1);    // quad_perm [1,0,3,2]
+  v = ECOSPA_DPP_ADD(v, 0x4E);    // quad_perm [2,3,0,1]
+  v = ECOSPA_DPP_ADD(v, 0x141);   // row_half_mirror
+  v = ECOSPA_DPP_ADD(v, 0x140);   // row_mirror
   return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  v = row16_sum(v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
+  return (r0 + r1) + (r2 + r3);
 }
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll

@@ -1,17 +1,18 @@
 // Step 1: per-dimension coupled importance score (paper Eq. 10, criterion of Eq. 12).
 //
 // HBM-bound: every weight element of every pair in the batch is read exactly once with
-// 16-byte loads.  Two launches per batch of up to SCORE_MAX_PAIRS pairs:
-//   1. score_sumsq_kernel  - squared row norms (one wavefront per row, shuffle reduction) and
-//                            squared column norms of the [d, n] member (one workgroup per strip
-//                            of one 128-byte line = 8 lanes x 16 bytes, over all d rows, eight
-//                            loads in flight per lane)
-//   2. score_finish_kernel - one workgroup per (pair, group): r = |a||b|, group L2 norm,
-//                            normalised scores
+// 16-byte loads.
+//   1. score_sumsq_kernel  - one launch per SCORE_MAX_PAIRS pairs: squared row norms (a wavefront
+//                            takes four rows at a time, all their loads in flight, then lane-
+//                            permutation sums) and squared column norms of the [d, n] member (one
+//                            workgroup per strip of one 128-byte line = 8 lanes x 16 bytes, over
+//                            all d rows, eight loads in flight per lane)
+//   2. score_finish_kernel - one launch per SCORE_FIN_MAX_PAIRS pairs, one workgroup per (pair,
+//                            group): r = |a||b|, group L2 norm, normalised scores
 // No floating-point atomics; all reduction orders are fixed.
 #include "common.h"
 
-#define SCORE_MAX_PAIRS 24
+#define SCORE_MAX_PAIRS 36         // descriptors travel as kernel arguments (under 4 KB)
 #define SCORE_ROWS_PER_BLOCK 16   // row-norm blocks: 4 waves x 4 rows
 #define SCORE_COL_LANES 8         // column-norm blocks: 8 lanes (128 bytes of columns) x 32 row slots
 #define SCORE_COL_SLOTS (256 / SCORE_COL_LANES)
@@ -23,13 +24,11 @@ struct ScorePairDev {
   long long ld1, ld1b, ld2;
   float* a_sq;     // [rows]            squared norms of a_j
   float* b_sq;     // [rows]            squared norms of b_j (rows of W_k, or columns of w2)
-  float* scores;   // [groups * n / unit]
   int rows;        // groups * n
   int groups, n, unit;
   int d1, d2;
   int kind, dtype;
   int blk_row1, blk_row2, blk_col, blk_end;   // first block index of each phase in launch 1
-  int fin_begin;               // first block index of this pair in launch 2 (one workgroup per group)
 };
 struct ScoreBatch {
   int n_pairs;
@@ -58,33 +57,47 @@ __device__ __forceinline__ void load_vec<bf16_t>(const bf16_t* p, float (&out)[8
   }
 }
 
-// Squared norm of one row (optionally of the elementwise product of two rows), by one wavefront.
-template <typename T>
-__device__ __forceinline__ float row_sumsq(const T* r, const T* rb, int len, bool vec_ok, int lane) {
+// Squared norms of NR consecutive rows (optionally of the elementwise products with the rows of a
+// second matrix) by one wavefront: the loads of all NR rows are in flight together, the cross-lane
+// sums come last.  Rows >= rows_valid are skipped (their slot returns 0).
+template <typename T, int NR>
+__device__ __forceinline__ void rows_sumsq(const T* r, const T* rb, long long ld, long long ldb, int len, int rows_valid,
+                                           bool vec_ok, int lane, float (&out)[NR]) {
   constexpr int V = Vec16<T>::N;
-  float acc = 0.f;
+  float acc[NR];
+#pragma unroll
+  for (int j = 0; j < NR; ++j) acc[j] = 0.f;
   if (vec_ok) {
+#pragma unroll 2
     for (int c = lane * V; c < len; c += 64 * V) {
-      float a[V];
-      load_vec<T>(r + c, a);
-      if (rb) {
-        float b[V];
-        load_vec<T>(rb + c, b);
+      float a[NR][V], b[NR][V];
 #pragma unroll
-        for (int i = 0; i < V; ++i) { float t = a[i] * b[i]; acc += t * t; }
-      } else {
+      for (int j = 0; j < NR; ++j) {
+        const int jj = j < rows_valid ? j : 0;       // clamped: always a valid row
+        load_vec<T>(r + jj * ld + c, a[j]);
+        if (rb) load_vec<T>(rb + jj * ldb + c, b[j]);
+      }
 #pragma unroll
-        for (int i = 0; i < V; ++i) acc += a[i] * a[i];
+      for (int j = 0; j < NR; ++j) {
+        if (rb) {
+#pragma unroll
+          for (int i = 0; i < V; ++i) { const float t = a[j][i] * b[j][i]; acc[j] += t * t; }
+        } else {
+#pragma unroll
+          for (int i = 0; i < V; ++i) acc[j] += a[j][i] * a[j][i];
+        }
       }
     }
   } else {
-    for (int c = lane; c < len; c += 64) {
-      float a = load_f32<T>(r + c);
-      if (rb) a *= load_f32<T>(rb + c);
-      acc += a * a;
-    }
+    for (int j = 0; j < NR && j < rows_valid; ++j)
+      for (int c = lane; c < len; c += 64) {
+        float a = load_f32<T>(r + j * ld + c);
+        if (rb) a *= load_f32<T>(rb + j * ldb + c);
+        acc[j] += a * a;
+      }
   }
-  return wave_sum(acc);
+#pragma unroll
+  for (int j = 0; j < NR; ++j) out[j] = j < rows_valid ? wave_sum(acc[j]) : 0.f;
 }
 
 template <typename T>
@@ -102,12 +115,16 @@ __device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
     float* out = second ? p.b_sq : p.a_sq;
     bool vec_ok = (len % V == 0) && (ld % V == 0) && ((reinterpret_cast<uintptr_t>(w) & 15u) == 0);
     if (wb) vec_ok = vec_ok && (p.ld1b % V == 0) && ((reinterpret_cast<uintptr_t>(wb) & 15u) == 0);
-#pragma unroll 1
-    for (int i = 0; i < SCORE_ROWS_PER_BLOCK / 4; ++i) {
-      const int row = local * SCORE_ROWS_PER_BLOCK + wave * (SCORE_ROWS_PER_BLOCK / 4) + i;
-      if (row >= p.rows) break;
-      float s = row_sumsq<T>(w + row * ld, wb ? wb + row * p.ld1b : nullptr, len, vec_ok, lane);
-      if (lane == 0) out[row] = s;
+    constexpr int NR = SCORE_ROWS_PER_BLOCK / 4;
+    const int row0 = local * SCORE_ROWS_PER_BLOCK + wave * NR;
+    if (row0 < p.rows) {
+      float sums[NR];
+      rows_sumsq<T, NR>(w + row0 * ld, wb ? wb + row0 * p.ld1b : nullptr, ld, p.ld1b, len, p.rows - row0, vec_ok, lane, sums);
+      if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < NR; ++j)
+          if (row0 + j < p.rows) out[row0 + j] = sums[j];
+      }
     }
     return;
   }
@@ -172,22 +189,42 @@ __device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
 __global__ __launch_bounds__(256) void score_sumsq_kernel(const ScoreBatch b) {
   __shared__ float lds[SCORE_COL_SLOTS * (SCORE_COL_LANES * 8 + 1)];
   const int blk = blockIdx.x;
-  int pi = 0;
-  while (pi + 1 < b.n_pairs && blk >= b.p[pi].blk_end) ++pi;
-  const ScorePairDev& p = b.p[pi];
+  int lo = 0, hi = b.n_pairs - 1;          // last pair whose first block is <= blk
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (b.p[mid].blk_row1 <= blk) lo = mid; else hi = mid - 1;
+  }
+  const ScorePairDev& p = b.p[lo];
   if (p.dtype == ECOSPA_BF16) score_block<bf16_t>(p, blk, lds);
   else score_block<float>(p, blk, lds);
 }
 
-// Launch 2: one workgroup per (pair, group).  Every thread finishes its units (r = |a| |b|), the
-// group's L2 norm of r is reduced in a fixed order, and the normalised scores are written.
+// Finishing launch: one workgroup per (pair, group).  Every thread finishes its units (r = |a| |b|),
+// the group's L2 norm of r is reduced in a fixed order, and the normalised scores are written.  It
+// needs little per pair, so one launch serves up to SCORE_FIN_MAX_PAIRS pairs (several batches of the
+// first launch).
 #define SCORE_FIN_THREADS 1024
-__global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_kernel(const ScoreBatch b) {
+#define SCORE_FIN_MAX_PAIRS 96
+struct ScoreFinPair {
+  const float* a_sq;
+  const float* b_sq;
+  float* scores;
+  int n, unit;
+  int fin_begin, pad;
+};
+struct ScoreFinBatch {
+  int n_pairs;
+  ScoreFinPair p[SCORE_FIN_MAX_PAIRS];
+};
+__global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_kernel(const ScoreFinBatch b) {
   __shared__ float red[SCORE_FIN_THREADS / 64];
   const int blk = blockIdx.x;
-  int pi = 0;
-  while (pi + 1 < b.n_pairs && blk >= b.p[pi + 1].fin_begin) ++pi;
-  const ScorePairDev& p = b.p[pi];
+  int lo = 0, hi = b.n_pairs - 1;          // last pair whose first workgroup is <= blk
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (b.p[mid].fin_begin <= blk) lo = mid; else hi = mid - 1;
+  }
+  const ScoreFinPair& p = b.p[lo];
   const int g = blk - p.fin_begin;
   const int nu = p.n / p.unit;
   const int tid = threadIdx.x;
@@ -254,11 +291,14 @@ extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, i
   if (!ctx->ws || ctx->ws_bytes < need) return ECOSPA_ERR_WORKSPACE;
   WsCarver ws(ctx->ws, ctx->ws_bytes);
 
+  ScoreFinBatch fb;
+  fb.n_pairs = 0;
+  int fin = 0;
   for (int first = 0; first < n_pairs; first += SCORE_MAX_PAIRS) {
     ScoreBatch b;
     memset(&b, 0, sizeof(b));
     b.n_pairs = (n_pairs - first < SCORE_MAX_PAIRS) ? n_pairs - first : SCORE_MAX_PAIRS;
-    int blk = 0, fin = 0;
+    int blk = 0;
     for (int i = 0; i < b.n_pairs; ++i) {
       const ecospa_pair& q = pairs[first + i];
       ScorePairDev& p = b.p[i];
@@ -267,7 +307,6 @@ extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, i
       p.rows = q.groups * q.n;
       p.groups = q.groups; p.n = q.n; p.unit = q.unit;
       p.d1 = q.d1; p.d2 = q.d2; p.kind = q.kind; p.dtype = q.dtype;
-      p.scores = scores[first + i];
       p.a_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows) * 4));
       const int row_blocks = (p.rows + SCORE_ROWS_PER_BLOCK - 1) / SCORE_ROWS_PER_BLOCK;
       p.blk_row1 = blk;
@@ -283,13 +322,26 @@ extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, i
         blk += (p.rows + strip - 1) / strip;
       }
       p.blk_end = blk;
-      p.fin_begin = fin;
-      fin += q.groups;
     }
     if (!ws.ok()) return ECOSPA_ERR_WORKSPACE;
     hipLaunchKernelGGL(score_sumsq_kernel, dim3(blk), dim3(256), 0, ctx->stream, b);
     ECOSPA_CHECK_LAUNCH(ctx, "score_sumsq_kernel");
-    hipLaunchKernelGGL(score_finish_kernel, dim3(fin), dim3(SCORE_FIN_THREADS), 0, ctx->stream, b);
+    // queue the finishing work of this batch; launch it when the queue is full or the batches are done
+    for (int i = 0; i < b.n_pairs; ++i) {
+      if (fb.n_pairs == SCORE_FIN_MAX_PAIRS) {
+        hipLaunchKernelGGL(score_finish_kernel, dim3(fin), dim3(SCORE_FIN_THREADS), 0, ctx->stream, fb);
+        ECOSPA_CHECK_LAUNCH(ctx, "score_finish_kernel");
+        fb.n_pairs = 0;
+        fin = 0;
+      }
+      ScoreFinPair& f = fb.p[fb.n_pairs++];
+      f.a_sq = b.p[i].a_sq; f.b_sq = b.p[i].b_sq; f.scores = scores[first + i];
+      f.n = b.p[i].n; f.unit = b.p[i].unit; f.fin_begin = fin; f.pad = 0;
+      fin += b.p[i].groups;
+    }
+  }
+  if (fb.n_pairs > 0) {
+    hipLaunchKernelGGL(score_finish_kernel, dim3(fin), dim3(SCORE_FIN_THREADS), 0, ctx->stream, fb);
     ECOSPA_CHECK_LAUNCH(ctx, "score_finish_kernel");
   }
   return ECOSPA_OK;
