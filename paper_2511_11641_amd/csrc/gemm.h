@@ -58,6 +58,11 @@ bool gemm_pipe_ok(const GemmDesc& d, int cfg, int k_chunk);
 hipError_t gemm_pipe_launch(ecospa_ctx* ctx, const GemmDesc& d, int cfg, int k_chunk);
 int gemm_pipe_bk(int cfg);
 
+// Register-staged kernel with a two-slab prefetch (gemm_rs.hip): 256x256x64 tiles, four wavefronts;
+// A K-contiguous, B either way; d.tile = 20 forces it.
+bool gemm_rs_ok(const GemmDesc& d, int k_chunk);
+hipError_t gemm_rs_launch(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk);
+
 // The small jobs that follow the contractions of a backward pass, batched into ONE launch (each of
 // them alone would be bound by the fixed cost of a launch): fixed-order reductions of split-K
 // partials (a GemmDesc launched with defer_reduce) and bias gradients out[n] = sum_m X[m, n].

@@ -391,15 +391,23 @@ static bool gemm_prefers_big_tile(int M, int N, int splits) {
 
 // Which configuration of the software-pipelined kernel (gemm_pipe.hip) suits a problem, or -1 for the
 // register-staged kernel above.  Measured on the layer shapes (M = tokens = 8192, N and K between 512
-// and 4096) with operands coming from HBM: for K-contiguous operands (x W^T) the largest workgroup
-// tile that still yields about one tile per compute unit wins; with a K-slow operand (dY W, dY^T X)
-// the register-staged kernel is still ahead.
+// and 4096) inside the layer step: for K-contiguous operands (x W^T) the largest workgroup tile that
+// still yields about one tile per compute unit wins; with a K-slow B operand (dY W) that holds only
+// for the 256x256 configuration (its two wavefronts per SIMD cover the transposing reads); dY^T X
+// stays on the register-staged kernel.
 static int gemm_pipe_choice(const GemmDesc& d) {
-  if (d.trans_a || d.trans_b) return -1;
+  if (d.trans_a) return -1;
   const long long tm256 = (d.M + 255) / 256, t256 = tm256 * ((d.N + 255) / 256), t256x128 = tm256 * ((d.N + 127) / 128);
   if (t256 >= 192) return 5;      // 256x256, 8 wavefronts
+  if (d.trans_b) return -1;
   if (t256x128 >= 192) return 2;  // 256x128, 3-deep ring
   return 4;                       // 128x128
+}
+// Long contractions with a K-slow B operand (K of several thousand, at least a tile per compute unit)
+// run fastest on the two-slab register prefetch of gemm_rs.hip.
+static bool gemm_prefers_rs(const GemmDesc& d) {
+  const long long t256 = static_cast<long long>((d.M + 255) / 256) * ((d.N + 255) / 256);
+  return !d.trans_a && d.trans_b && d.splits <= 1 && d.K >= 4096 && t256 >= 192;
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int WPE, bool TRR>
@@ -464,8 +472,9 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
     if (prof) (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n], ctx->stream);
     hipError_t le;
     const int k_split = (d.K + splits - 1) / splits;
-    const int cfg = d.tile >= 10 ? d.tile - 10 : (d.tile == 0 ? gemm_pipe_choice(d) : -1);
-    if (cfg >= 0 && gemm_pipe_ok(d, cfg, k_split)) le = gemm_pipe_launch(ctx, d, cfg, k_split);
+    const int cfg = d.tile >= 10 && d.tile < 20 ? d.tile - 10 : (d.tile == 0 ? gemm_pipe_choice(d) : -1);
+    if ((d.tile == 20 || (d.tile == 0 && gemm_prefers_rs(d))) && gemm_rs_ok(d, k_split)) le = gemm_rs_launch(ctx, d, k_split);
+    else if (cfg >= 0 && gemm_pipe_ok(d, cfg, k_split)) le = gemm_pipe_launch(ctx, d, cfg, k_split);
     else {
       // register-staged kernel; tile 1/2 = 128/256 tiles with K-slow operands transposed on the way to
       // LDS, 3/4 = the same tiles with K-slow operands read by transposing LDS reads.  Measured: the

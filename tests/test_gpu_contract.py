@@ -90,3 +90,19 @@ def test_contract_bf16_pipelined_split_k(ctx, cfg):
     assert_close(got, want, "bf16", "split k")
     again = ctx.ecospa_contract(dev(a, "bf16"), True, dev(b, "bf16"), True, dev(bias, "bf16"), tile=10 + cfg, splits=4)
     assert torch.equal(got, again)
+
+
+@pytest.mark.parametrize("tb", [False, True])
+@pytest.mark.parametrize("M,N,K", [(520, 264, 192), (256, 512, 64), (304, 136, 512), (1000, 520, 128)])
+def test_contract_bf16_register_staged_prefetch(ctx, M, N, K, tb):
+    """The two-slab register-prefetch kernel (tile = 20): ragged M and N, one slab, two, three (odd count:
+    the unrolled slab pair plus a tail) and many, B K-contiguous or K-slow."""
+    a, b, bias, want = _operands(47, M, N, K, False, tb, "bf16")
+    got = ctx.ecospa_contract(dev(a, "bf16"), False, dev(b, "bf16"), tb, dev(bias, "bf16"), tile=20, splits=1)
+    assert_close(got, want, "bf16", "register-staged prefetch")
+
+
+def test_contract_bf16_register_staged_prefetch_split_k(ctx):
+    a, b, bias, want = _operands(48, 264, 520, 1024, False, True, "bf16")
+    got = ctx.ecospa_contract(dev(a, "bf16"), False, dev(b, "bf16"), True, dev(bias, "bf16"), tile=20, splits=4)
+    assert_close(got, want, "bf16", "split k")
