@@ -29,12 +29,12 @@ HBM_PEAK_GBS = 8000.0
 GEMM_TRAFFIC = ("1b506c137d358563", 120.5e6)
 
 
-def model_flops(T, L, d, h, k_qk, k_vo, k_ff, causal=True):
+def model_flops(T, L, d, h, k_qk, k_vo, k_ff, causal=True, gated=False):
     """fwd+bwd model flops of one layer (backward = 2x forward, recomputation not counted,
-    causal attention counted at half)."""
+    causal attention counted at half; a gated FFN has three matrices)."""
     proj = 2 * T * d * (2 * h * k_qk + h * k_vo) + 2 * T * d * h * k_vo
     attn = (2 * T * L * h * (k_qk + k_vo)) * (0.5 if causal else 1.0)
-    ffn = 2 * 2 * T * d * k_ff
+    ffn = (3 if gated else 2) * 2 * T * d * k_ff
     return 3.0 * (proj + attn + ffn)
 
 
@@ -128,6 +128,90 @@ def timed(torch, fn, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def timed_gpu(torch, fn, steps, warmup):
+    """Device-side time per call (events on the current stream): for calls whose host cost would
+    otherwise dominate."""
+    for _ in range(warmup):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps):
+    """Steps 1-3 on a stack of n_layers layers of the same shape (the re-scoring pass of a whole model):
+    one batched score call, one select call, one compaction call; descriptors are built once, so
+    the device-side times are not hidden behind the host."""
+    import ctypes as C
+    import torch
+    from paper_2511_11641_amd import binding as B
+    from paper_2511_11641_amd.layer import AttnBlock, FfnBlock
+    d, h, dh, dff = (cfg[k] for k in ("d", "h", "d_h", "d_ff"))
+    g = lambda *s: (torch.randn(*s, device="cuda") * 0.02).to(torch.bfloat16)
+    layers = []
+    for _ in range(n_layers):
+        a = AttnBlock(ctx, g(h * dh, d), g(h * dh, d), g(h * dh, d), g(d, h * dh), g(h * dh), g(h * dh), g(h * dh), g(d),
+                      h, dh, rope=False)
+        f = FfnBlock(ctx, g(dff, d), g(dff), g(d, dff), g(d), B.ACT_GELU_ERF)
+        layers.append((a, f))
+    pairs = [p for a, f in layers for p in a.pairs() + [f.pair()]]
+    pair_arr = (B.Pair * len(pairs))(*pairs)
+    scores = ctx.ecospa_coupled_score(pair_arr)
+    ks = (dh * keep_num // keep_den, dh * keep_num // keep_den, dff * keep_num // keep_den)
+    idx = [torch.empty((s.shape[0], ks[i % 3]), dtype=torch.int32, device="cuda") for i, s in enumerate(scores)]
+    sel = [ctx.select_item(s, ks[i % 3], o) for i, (s, o) in enumerate(zip(scores, idx))]
+    sel_arr = (B.SelectItem * len(sel))(*sel)
+    ctx.ecospa_select_topk_batch(sel_arr)
+    items = []
+    for li, (a, f) in enumerate(layers):
+        items += a.compact(idx[3 * li], idx[3 * li + 1], defer=True) + f.compact(idx[3 * li + 2], defer=True)
+    item_arr = (B.MapItem * len(items))(*items)
+    t_score = timed_gpu(torch, lambda: ctx.ecospa_coupled_score(pair_arr, out=scores), steps, 3)
+    t_select = timed_gpu(torch, lambda: ctx.ecospa_select_topk_batch(sel_arr), steps, 3)
+    t_compact = timed_gpu(torch, lambda: ctx.ecospa_compact_batch(item_arr), steps, 3)
+    w_bytes = n_layers * 2 * (4 * d * d + 2 * d * dff)
+    keep = keep_num / keep_den
+    cols = n_layers * 2 * (d * d + d * dff)                 # the members gathered by column: W_o, W_2
+    traffic = 2 * keep * (w_bytes - cols) + (1 + keep) * cols
+    return {"layers": n_layers, "weights_MB": w_bytes / 1e6,
+            "score": {"us": t_score * 1e3, "gbs": w_bytes / t_score / 1e6, "frac_of_hbm_peak": w_bytes / t_score / 1e6 / HBM_PEAK_GBS},
+            "select": {"us": t_select * 1e3},
+            "compact": {"us": t_compact * 1e3, "kept_gbs": 2 * keep * w_bytes / t_compact / 1e6,
+                        "traffic_gbs": traffic / t_compact / 1e6,
+                        "frac_of_hbm_peak": traffic / t_compact / 1e6 / HBM_PEAK_GBS,
+                        "note": "kept bytes read + written; traffic adds the whole 128-byte lines a column gather has to fetch"},
+            "timing": "device-side events, descriptors prebuilt"}
+
+
+def second_workload(ctx, name, steps, warmup):
+    """The LLaMA-1B-shaped layer (RoPE, SwiGLU, no biases) through the same path: whole step at 50 % keep,
+    fwd+bwd alone, and the dense layer (same library at k = n)."""
+    import torch
+    from paper_2511_11641_amd import synth
+    cfg = dict(synth.CONFIGS[name])
+    Bsz, L, d, h, dh, dff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
+    T = Bsz * L
+    sp = Layer(ctx, cfg, cfg["seed"], 1, 2)
+    ms_step = timed(torch, sp.step, steps, warmup)
+    ms_fb = timed(torch, lambda: (sp.fwd(), sp.bwd()), steps, 2)
+    fl_sp = model_flops(T, L, d, h, sp.attn.kp_qk, sp.attn.kp_vo, sp.ffn.kp, gated=cfg["gated"])
+    del sp
+    torch.cuda.empty_cache()
+    de = Layer(ctx, cfg, cfg["seed"], 1, 1)
+    ms_de = timed(torch, lambda: (de.fwd(), de.bwd()), steps, warmup)
+    fl_de = model_flops(T, L, d, h, dh, dh, dff, gated=cfg["gated"])
+    del de
+    torch.cuda.empty_cache()
+    return {"workload": name, "batch": Bsz, "seq_len": L, "ms_per_step": ms_step, "tokens_per_s": T / (ms_step * 1e-3),
+            "fwd_bwd": {"ms": ms_fb, "tokens_per_s": T / (ms_fb * 1e-3), "model_tflops": fl_sp / (ms_fb * 1e-3) / 1e12},
+            "dense_fwd_bwd": {"ms": ms_de, "tokens_per_s": T / (ms_de * 1e-3), "model_tflops": fl_de / (ms_de * 1e-3) / 1e12},
+            "speedup_fwd_bwd_vs_dense": ms_de / ms_fb}
+
+
 def cpu_baseline(cfg, seed, keep_num, keep_den, sample_B):
     """The fp64 oracle, as it stands, on `sample_B` batch elements of the same workload."""
     import os
@@ -172,6 +256,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the 24-layer pruning pass and the LLaMA-1B-shaped layer reported beside the main workload")
     ap.add_argument("--pmc-reference", action="store_true",
                     help="first run 3 plain device copies of a 128 MiB tensor, so that hardware byte counters read "
                          "under rocprofv3 --pmc can be scaled by what they show for a copy of known size")
@@ -255,6 +341,9 @@ def main():
                      "flop_per_launch_avg": gemm_flop / max(n_launch, 1),
                      "measured": f"HIP events around each launch, {args.steps} steps re-run after the timed region"},
     }
+    if not args.no_extras:
+        out["prune_24_layers"] = prune_stack(ctx, cfg, 24, 1, 2, 20)
+        out["also"] = second_workload(ctx, "c3_llama1b_layer", args.steps, args.warmup)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, seed, 1, 2, sample_B=8)
     print(json.dumps(out))
