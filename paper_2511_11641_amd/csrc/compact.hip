@@ -40,7 +40,7 @@ __device__ __forceinline__ long long map_slot(const MapArgs& m, long long s) {
 }
 
 // One mapped copy of a batch; all items of a batch share one launch (block ranges in `blk_begin`).
-#define MAP_MAX_ITEMS 32
+#define MAP_MAX_ITEMS 128    // descriptors travel as kernel arguments (about 14 KB)
 #define MAP_COL_ROWS 4      // rows a column-copy thread keeps in flight
 struct MapItemDev {
   const void* src;
@@ -215,8 +215,11 @@ __global__ __launch_bounds__(256) void map_batch_kernel(const MapBatch b) {
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[MAP_LDS_ROWS * MAP_LDS_CHUNKS * 16 + (MAP_LDS_GROUPS * 8 + 2) * 4];
   static_assert(MAP_LDS_GROUPS * 8 <= 256, "one thread per destination column resolves the source columns");
   const int blk = blockIdx.x;
-  int i = 0;
-  while (i + 1 < b.n_items && blk >= b.it[i + 1].blk_begin) ++i;
+  int i = 0, hi = b.n_items - 1;          // last item whose first block is <= blk
+  while (i < hi) {
+    const int mid = (i + hi + 1) >> 1;
+    if (b.it[mid].blk_begin <= blk) i = mid; else hi = mid - 1;
+  }
   const MapItemDev& t = b.it[i];
   const int local = blk - t.blk_begin;
   if (t.axis == 0) {

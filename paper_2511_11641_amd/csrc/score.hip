@@ -12,7 +12,7 @@
 // No floating-point atomics; all reduction orders are fixed.
 #include "common.h"
 
-#define SCORE_MAX_PAIRS 36         // descriptors travel as kernel arguments (under 4 KB)
+#define SCORE_MAX_PAIRS 96         // descriptors travel as kernel arguments (about 10 KB)
 #define SCORE_ROWS_PER_BLOCK 16   // row-norm blocks: 4 waves x 4 rows
 #define SCORE_COL_LANES 8         // column-norm blocks: 8 lanes (128 bytes of columns) x 32 row slots
 #define SCORE_COL_SLOTS (256 / SCORE_COL_LANES)

@@ -10,7 +10,7 @@
 #include "common.h"
 
 #define SELECT_THREADS 1024
-#define SELECT_MAX_ITEMS 16
+#define SELECT_MAX_ITEMS 96    // descriptors travel as kernel arguments
 
 struct SelectItemDev {
   const float* scores;
@@ -59,8 +59,11 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
   __shared__ uint32_t s_prefix;
   __shared__ int s_krem;
   const int tid = threadIdx.x;
-  int item = 0;
-  while (item + 1 < b.n_items && static_cast<int>(blockIdx.x) >= b.it[item + 1].blk_begin) ++item;
+  int item = 0, hi = b.n_items - 1;       // last item whose first block is <= blockIdx.x
+  while (item < hi) {
+    const int mid = (item + hi + 1) >> 1;
+    if (b.it[mid].blk_begin <= static_cast<int>(blockIdx.x)) item = mid; else hi = mid - 1;
+  }
   const SelectItemDev& t = b.it[item];
   const int n = t.n, k = t.k, g = blockIdx.x - t.blk_begin;
   const float* s = t.scores + static_cast<long long>(g) * n;
