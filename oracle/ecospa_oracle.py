@@ -99,6 +99,81 @@ def select_topk(scores, k: int) -> np.ndarray:
 # --------------------------------------------------------------------------------------
 # Step 3: aligned gather into smaller dense matrices, and its inverse (Def. 1; Alg. 1)
 # --------------------------------------------------------------------------------------
+# --------------------------------------------------------------------------------------
+# Pair-level importance (Eq. 8) and the cumulative-threshold removal rule (Alg. 1)
+# --------------------------------------------------------------------------------------
+def pair_fisher(kind: int, g1, g2, groups: int, n: int, n_samples: float, g1b=None) -> np.ndarray:
+    """I_hat[g] of Eq. 8 for each of the ``groups`` coupled pairs of one layer.
+
+    ``g1``, ``g2`` (and ``g1b``) are the loss gradients of the pair's matrices in the storage
+    layout of the weights themselves.  For pair g the two members are the group's rows of
+    ``g1`` and its rows (QK) or columns (otherwise) of ``g2``; each member contributes the
+    mean of its squared entries, the two means are averaged (the factor 1/2 and 1/|W_k| of
+    Eq. 8), and the result is divided by the number of samples |D|.  For the gated FFN the
+    first member is the pair (W_gate, W_up) - the paper defines W_1 from both (footnote to
+    Eq. 8) - so its mean runs over the entries of both gradient matrices.
+    """
+    g1, g2, g1b = _f64(g1), _f64(g2), _f64(g1b)
+    out = np.zeros(groups)
+    for g in range(groups):
+        rows = slice(g * n, (g + 1) * n)
+        first = g1[rows]
+        if kind == PAIR_FFN_GATED:
+            first = np.concatenate([first, g1b[rows]])
+        second = g2[rows] if kind == PAIR_QK else g2[:, rows]
+        out[g] = 0.5 * ((first ** 2).sum() / first.size + (second ** 2).sum() / second.size) / n_samples
+    return out
+
+
+def theta_mass(scores) -> np.ndarray:
+    """Integer mass of each score used by the threshold rule: floor(min(max(s, 0), 1) * 2^32), NaN -> 0.
+
+    The rule compares sums of scores with a threshold; summing integers makes that comparison
+    independent of the order of summation, so that exactly one result is correct.
+    """
+    s = np.asarray(scores, dtype=np.float32).astype(np.float64)
+    s = np.where(np.isnan(s), 0.0, s)
+    return np.floor(np.clip(s, 0.0, 1.0) * 4294967296.0).astype(np.uint64)
+
+
+def select_theta(scores, theta: float):
+    """Alg. 1's removal loop for each row of ``scores[groups, n_units]``: the unit with the smallest score
+    is removed while the units that remain still hold at least the fraction ``theta`` of the group's
+    total score (the scores of a group are compared as fractions of their sum, which leaves the ranking
+    of Eq. 10 untouched); at least one unit is always kept.
+
+    Order of removal: ascending score under the ordering of select_topk (NaN first, -0 = +0), and among
+    equal scores the higher index first, so that ties keep the lower index.  Masses are the integers of
+    theta_mass(); the kept-mass bound is ceil(theta * total) evaluated in fp64.
+    Returns (idx, k): idx[g] holds the k[g] kept indices in ascending order, padded with -1.
+    """
+    sc = np.asarray(scores, dtype=np.float32)
+    if sc.ndim == 1:
+        sc = sc[None, :]
+    groups, n = sc.shape
+    idx = np.full((groups, n), -1, dtype=np.int32)
+    ks = np.zeros(groups, dtype=np.int32)
+    theta = float(np.float32(theta))
+    for g in range(groups):
+        row = sc[g]
+        q = [int(v) for v in theta_mass(row)]
+        total = sum(q)
+        bound = int(np.ceil(np.float64(theta) * np.float64(total)))
+        key = np.where(np.isnan(row), -np.inf, row.astype(np.float64))
+        key = np.where(key == 0.0, 0.0, key)
+        order = sorted(range(n), key=lambda i: (key[i], -i))      # removal order
+        kept_mass, removed = total, set()
+        for i in order:
+            if len(removed) == n - 1 or kept_mass - q[i] < bound:
+                break
+            kept_mass -= q[i]
+            removed.add(i)
+        kept = [i for i in range(n) if i not in removed]
+        ks[g] = len(kept)
+        idx[g, :len(kept)] = kept
+    return idx, ks
+
+
 def kept_positions(idx, n: int, unit: int = 1) -> np.ndarray:
     """Flat positions, over all groups, of the kept inner dimensions (ascending per group)."""
     idx = np.asarray(idx, dtype=np.int64)
