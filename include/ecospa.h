@@ -112,6 +112,29 @@ typedef struct {
 int ecospa_select_topk_batch(ecospa_ctx* ctx, const ecospa_select_item* items /*host*/, int n_items);
 
 /* ------------------------------------------------------------------------------------------
+ * Pair-level importance and the cumulative-threshold rule (the two remaining pieces of Alg. 1).
+ *
+ * ecospa_pair_fisher - Eq. 8: the importance of a whole coupled pair from the loss gradients of its
+ * two members, I = 1/2 * sum_{k=1,2} (1 / |W_k|) (1 / |D|) sum_ij (dL/dW_k)_ij^2.  `grads` describes
+ * the gradient matrices exactly as an ecospa_pair describes the weights (w1 = dL/dW_1 ..., same
+ * layouts, `unit` ignored); fisher[p] (host array of device pointers) receives float[groups_p], one
+ * value per head / FFN pair.  For ECOSPA_PAIR_FFN_GATED the first member is (W_gate, W_up) together,
+ * |W_1| counting both.  n_samples = |D| > 0.  Workspace and errors as ecospa_coupled_score.
+ *
+ * ecospa_select_theta - Alg. 1's inner loop for each of `groups` score rows: the unit with the smallest
+ * score is removed while the remaining units still hold at least the fraction theta (0 <= theta <= 1)
+ * of the row's total score; at least one unit stays.  Scores enter as integer masses
+ * floor(clip(s, 0, 1) * 2^32) (NaN -> 0) and the bound is ceil(theta * total) in fp64, so all sums are
+ * exact and exactly one result is correct.  Order of removal: ascending in the ordering of
+ * ecospa_select_topk, higher index first among equal scores.  k_out: int32[groups] kept counts;
+ * idx: int32[groups * n_units], row g holds its k_out[g] kept indices ascending, then -1.
+ * Errors: ERR_NULL; groups/n_units < 1 -> ERR_SHAPE; theta outside [0, 1] (or NaN) -> ERR_K.
+ * ------------------------------------------------------------------------------------------ */
+int ecospa_pair_fisher(ecospa_ctx* ctx, const ecospa_pair* grads /*host*/, int n_pairs, float n_samples,
+                       float* const* fisher /*host*/);
+int ecospa_select_theta(ecospa_ctx* ctx, const float* scores, int groups, int n_units, float theta, int* idx, int* k_out);
+
+/* ------------------------------------------------------------------------------------------
  * Step 3 - aligned gather of the kept inner dimensions into a smaller dense matrix (Def. 1:
  * the remaining terms keep their original pairing), and its inverse.
  *

@@ -26,7 +26,7 @@ EXPORTS = (
     "ecospa_score_workspace_bytes", "ecospa_coupled_score", "ecospa_select_topk", "ecospa_compact",
     "ecospa_scatter", "ecospa_rope_table", "ecospa_block_workspace_bytes", "ecospa_coupled_fwd",
     "ecospa_coupled_bwd", "ecospa_profile_gemm", "ecospa_profile_gemm_read", "ecospa_contract",
-    "ecospa_select_topk_batch", "ecospa_compact_batch",
+    "ecospa_select_topk_batch", "ecospa_compact_batch", "ecospa_pair_fisher", "ecospa_select_theta",
 )
 
 
@@ -105,6 +105,10 @@ def load() -> C.CDLL:
     lib.ecospa_coupled_score.restype = ci
     lib.ecospa_select_topk.argtypes = [vp, vp, ci, ci, ci, vp]
     lib.ecospa_select_topk.restype = ci
+    lib.ecospa_pair_fisher.argtypes = [vp, C.POINTER(Pair), ci, C.c_float, C.POINTER(vp)]
+    lib.ecospa_pair_fisher.restype = ci
+    lib.ecospa_select_theta.argtypes = [vp, vp, ci, ci, C.c_float, vp, vp]
+    lib.ecospa_select_theta.restype = ci
     for f in (lib.ecospa_compact, lib.ecospa_scatter):
         f.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ll, ll, ll, vp]
         f.restype = ci
@@ -226,6 +230,27 @@ class Context:
         ptrs = (C.c_void_p * len(arr))(*[o.data_ptr() for o in out])
         self._check(self.lib.ecospa_coupled_score(self.h, arr, len(arr), ptrs), "ecospa_coupled_score")
         return list(out)
+
+    def ecospa_pair_fisher(self, grads: Sequence[Pair], n_samples: float) -> list[torch.Tensor]:
+        """Eq. 8 importance of each coupled pair from its gradient matrices (described like the weights): one
+        float32 tensor [groups] per pair."""
+        arr = grads if isinstance(grads, C.Array) else (Pair * len(grads))(*grads)
+        self.reserve(self.lib.ecospa_score_workspace_bytes(arr, len(arr)))
+        out = [torch.empty((p.groups,), dtype=torch.float32, device=self.device) for p in arr]
+        ptrs = (C.c_void_p * len(arr))(*[o.data_ptr() for o in out])
+        self._check(self.lib.ecospa_pair_fisher(self.h, arr, len(arr), float(n_samples), ptrs), "ecospa_pair_fisher")
+        return out
+
+    def ecospa_select_theta(self, scores: torch.Tensor, theta: float):
+        """Alg. 1's cumulative-threshold rule per row of scores[groups, n_units]: (idx[groups, n_units] int32 padded
+        with -1, k[groups] int32)."""
+        assert scores.dtype == torch.float32 and scores.dim() == 2 and scores.is_contiguous()
+        groups, n = scores.shape
+        idx = torch.empty((groups, n), dtype=torch.int32, device=scores.device)
+        k = torch.empty((groups,), dtype=torch.int32, device=scores.device)
+        self._check(self.lib.ecospa_select_theta(self.h, scores.data_ptr(), groups, n, float(theta), idx.data_ptr(),
+                                                 k.data_ptr()), "ecospa_select_theta")
+        return idx, k
 
     # ---- step 2 ------------------------------------------------------------------------------
     def ecospa_select_topk(self, scores: torch.Tensor, k: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -28,6 +28,7 @@ struct ScorePairDev {
   int groups, n, unit;
   int d1, d2;
   int kind, dtype;
+  int fisher;      // 1: squared gradient sums for Eq. 8 (w1 and w1b are added, not multiplied)
   int blk_row1, blk_row2, blk_col, blk_end;   // first block index of each phase in launch 1
 };
 struct ScoreBatch {
@@ -62,7 +63,7 @@ __device__ __forceinline__ void load_vec<bf16_t>(const bf16_t* p, float (&out)[8
 // sums come last.  Rows >= rows_valid are skipped (their slot returns 0).
 template <typename T, int NR>
 __device__ __forceinline__ void rows_sumsq(const T* r, const T* rb, long long ld, long long ldb, int len, int rows_valid,
-                                           bool vec_ok, int lane, float (&out)[NR]) {
+                                           bool vec_ok, bool add_rb, int lane, float (&out)[NR]) {
   constexpr int V = Vec16<T>::N;
   float acc[NR];
 #pragma unroll
@@ -79,7 +80,10 @@ __device__ __forceinline__ void rows_sumsq(const T* r, const T* rb, long long ld
       }
 #pragma unroll
       for (int j = 0; j < NR; ++j) {
-        if (rb) {
+        if (rb && add_rb) {
+#pragma unroll
+          for (int i = 0; i < V; ++i) acc[j] += a[j][i] * a[j][i] + b[j][i] * b[j][i];
+        } else if (rb) {
 #pragma unroll
           for (int i = 0; i < V; ++i) { const float t = a[j][i] * b[j][i]; acc[j] += t * t; }
         } else {
@@ -92,8 +96,13 @@ __device__ __forceinline__ void rows_sumsq(const T* r, const T* rb, long long ld
     for (int j = 0; j < NR && j < rows_valid; ++j)
       for (int c = lane; c < len; c += 64) {
         float a = load_f32<T>(r + j * ld + c);
-        if (rb) a *= load_f32<T>(rb + j * ldb + c);
-        acc[j] += a * a;
+        if (rb && add_rb) {
+          const float b = load_f32<T>(rb + j * ldb + c);
+          acc[j] += a * a + b * b;
+        } else {
+          if (rb) a *= load_f32<T>(rb + j * ldb + c);
+          acc[j] += a * a;
+        }
       }
   }
 #pragma unroll
@@ -119,7 +128,7 @@ __device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
     const int row0 = local * SCORE_ROWS_PER_BLOCK + wave * NR;
     if (row0 < p.rows) {
       float sums[NR];
-      rows_sumsq<T, NR>(w + row0 * ld, wb ? wb + row0 * p.ld1b : nullptr, ld, p.ld1b, len, p.rows - row0, vec_ok, lane, sums);
+      rows_sumsq<T, NR>(w + row0 * ld, wb ? wb + row0 * p.ld1b : nullptr, ld, p.ld1b, len, p.rows - row0, vec_ok, p.fisher != 0, lane, sums);
       if (lane == 0) {
 #pragma unroll
         for (int j = 0; j < NR; ++j)
@@ -210,7 +219,9 @@ struct ScoreFinPair {
   const float* b_sq;
   float* scores;
   int n, unit;
-  int fin_begin, pad;
+  int fin_begin;
+  int fisher;          // 1: Eq. 8 instead of Eq. 10: scores[g] = w1 * sum(a_sq of group g) + w2 * sum(b_sq of group g)
+  float w1, w2;        //    with w_k = 1 / (2 |W_k| |D|)
 };
 struct ScoreFinBatch {
   int n_pairs;
@@ -228,6 +239,19 @@ __global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_kernel(const S
   const int g = blk - p.fin_begin;
   const int nu = p.n / p.unit;
   const int tid = threadIdx.x;
+  if (p.fisher) {
+    float part = 0.f;
+    for (int j = tid; j < p.n; j += SCORE_FIN_THREADS) part += p.w1 * p.a_sq[g * p.n + j] + p.w2 * p.b_sq[g * p.n + j];
+    part = wave_sum(part);
+    if ((tid & 63) == 0) red[tid >> 6] = part;
+    __syncthreads();
+    if (tid == 0) {
+      float tot = 0.f;
+      for (int w = 0; w < SCORE_FIN_THREADS / 64; ++w) tot += red[w];
+      p.scores[g] = tot;
+    }
+    return;
+  }
   float* out = p.scores + static_cast<long long>(g) * nu;
   float sq = 0.f;
   for (int u = tid; u < nu; u += SCORE_FIN_THREADS) {
@@ -279,7 +303,9 @@ extern "C" size_t ecospa_score_workspace_bytes(const ecospa_pair* pairs, int n_p
   return tot + 256;
 }
 
-extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, float* const* scores) {
+// Shared driver of Eq. 10 (fisher = 0: `pairs` are weights) and Eq. 8 (fisher = 1: `pairs` are gradients).
+static int score_run(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, float* const* scores, int fisher,
+                     float n_samples) {
   if (!ctx || !pairs || !scores) return ECOSPA_ERR_NULL;
   if (n_pairs < 1) return ECOSPA_ERR_SHAPE;
   for (int i = 0; i < n_pairs; ++i) {
@@ -306,7 +332,7 @@ extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, i
       p.ld1 = q.ld1; p.ld1b = q.ld1b; p.ld2 = q.ld2;
       p.rows = q.groups * q.n;
       p.groups = q.groups; p.n = q.n; p.unit = q.unit;
-      p.d1 = q.d1; p.d2 = q.d2; p.kind = q.kind; p.dtype = q.dtype;
+      p.d1 = q.d1; p.d2 = q.d2; p.kind = q.kind; p.dtype = q.dtype; p.fisher = fisher;
       p.a_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows) * 4));
       const int row_blocks = (p.rows + SCORE_ROWS_PER_BLOCK - 1) / SCORE_ROWS_PER_BLOCK;
       p.blk_row1 = blk;
@@ -336,7 +362,10 @@ extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, i
       }
       ScoreFinPair& f = fb.p[fb.n_pairs++];
       f.a_sq = b.p[i].a_sq; f.b_sq = b.p[i].b_sq; f.scores = scores[first + i];
-      f.n = b.p[i].n; f.unit = b.p[i].unit; f.fin_begin = fin; f.pad = 0;
+      f.n = b.p[i].n; f.unit = b.p[i].unit; f.fin_begin = fin; f.fisher = fisher;
+      const double members = b.p[i].kind == ECOSPA_PAIR_FFN_GATED ? 2.0 : 1.0;   // W_gate and W_up form the first member
+      f.w1 = fisher ? static_cast<float>(0.5 / (members * b.p[i].n * static_cast<double>(b.p[i].d1) * n_samples)) : 0.f;
+      f.w2 = fisher ? static_cast<float>(0.5 / (b.p[i].n * static_cast<double>(b.p[i].d2) * n_samples)) : 0.f;
       fin += b.p[i].groups;
     }
   }
@@ -345,4 +374,14 @@ extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, i
     ECOSPA_CHECK_LAUNCH(ctx, "score_finish_kernel");
   }
   return ECOSPA_OK;
+}
+
+extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, float* const* scores) {
+  return score_run(ctx, pairs, n_pairs, scores, 0, 1.f);
+}
+
+extern "C" int ecospa_pair_fisher(ecospa_ctx* ctx, const ecospa_pair* grads, int n_pairs, float n_samples,
+                                  float* const* fisher) {
+  if (!(n_samples > 0.f)) return ECOSPA_ERR_SHAPE;
+  return score_run(ctx, grads, n_pairs, fisher, 1, n_samples);
 }

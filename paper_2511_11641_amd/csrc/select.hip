@@ -17,6 +17,8 @@ struct SelectItemDev {
   int* idx;
   int n, k;
   int blk_begin;   // first workgroup (= group) of this item
+  const int* k_dev;  // optional: per-group kept counts in device memory (then k is unused, the rows of idx
+  int ld_idx;        //           are ld_idx apart and the slots behind the kept indices are set to -1)
 };
 struct SelectBatch {
   int n_items;
@@ -65,9 +67,10 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
     if (b.it[mid].blk_begin <= static_cast<int>(blockIdx.x)) item = mid; else hi = mid - 1;
   }
   const SelectItemDev& t = b.it[item];
-  const int n = t.n, k = t.k, g = blockIdx.x - t.blk_begin;
+  const int n = t.n, g = blockIdx.x - t.blk_begin;
+  const int k = t.k_dev ? t.k_dev[g] : t.k;
   const float* s = t.scores + static_cast<long long>(g) * n;
-  int* out = t.idx + static_cast<long long>(g) * k;
+  int* out = t.idx + static_cast<long long>(g) * (t.k_dev ? t.ld_idx : k);
 
   uint32_t prefix = 0u;   // high bits of the k-th largest key found so far
   int krem = k;           // rank (1-based) of the wanted key among keys matching the prefix
@@ -119,6 +122,101 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
     if (key == T && eq_left > 0) { take = true; --eq_left; }
     if (take && pos < k) out[pos++] = i;
   }
+  if (t.k_dev)
+    for (int i = k + tid; i < t.ld_idx; i += SELECT_THREADS) out[i] = -1;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Cumulative-threshold rule (Alg. 1's inner loop): how many units of a group stay when the smallest
+// scores are removed for as long as the rest still holds the fraction theta of the group's total.
+// Scores become integer masses (floor(clip(s, 0, 1) * 2^32), NaN -> 0), so every sum is exact and the
+// count does not depend on the order of summation.  The removable mass R = total - ceil(theta * total)
+// is spent in ascending key order: a 4-pass, 8-bit radix descent over (count, mass) histograms finds the
+// first key that cannot be removed entirely; of the units with exactly that key (equal masses) as many go
+// as R still covers.  The kept set is then the top-k of the same ordering, written by select_topk_kernel.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned long long theta_mass(float x) {
+  if (!(x > 0.f)) return 0ull;                       // negative, zero, NaN
+  const double v = fmin(static_cast<double>(x), 1.0) * 4294967296.0;
+  return static_cast<unsigned long long>(v);         // exact: a float times 2^32, truncated
+}
+struct ThetaItemDev {
+  const float* scores;
+  int* k_out;
+  int n;
+  float theta;
+};
+__global__ __launch_bounds__(SELECT_THREADS) void select_theta_count_kernel(const ThetaItemDev t) {
+  __shared__ unsigned long long hsum[256];
+  __shared__ int hcnt[256];
+  __shared__ unsigned long long s_total, s_rem;
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_below, s_digit;
+  const int tid = threadIdx.x, g = blockIdx.x, n = t.n;
+  const float* s = t.scores + static_cast<long long>(g) * n;
+  if (tid == 0) s_total = 0ull;
+  __syncthreads();
+  unsigned long long mine = 0ull;
+  for (int i = tid; i < n; i += SELECT_THREADS) mine += theta_mass(s[i]);
+  if (mine) atomicAdd(&s_total, mine);
+  __syncthreads();
+  const unsigned long long total = s_total;
+  const double bound_d = ceil(static_cast<double>(t.theta) * static_cast<double>(total));
+  const unsigned long long bound = bound_d <= 0.0 ? 0ull : static_cast<unsigned long long>(bound_d);
+  unsigned long long rem = bound >= total ? 0ull : total - bound;   // mass that may be removed
+  uint32_t prefix = 0u;
+  int below = 0;             // units removed so far (keys below the range being refined)
+  int digit = 0;
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+    if (tid < 256) { hsum[tid] = 0ull; hcnt[tid] = 0; }
+    __syncthreads();
+    for (int i = tid; i < n; i += SELECT_THREADS) {
+      const float x = s[i];
+      const uint32_t key = score_key(x);
+      if ((key & hi_mask) == prefix) {
+        const int d = (key >> shift) & 255u;
+        atomicAdd(&hcnt[d], 1);
+        const unsigned long long q = theta_mass(x);
+        if (q) atomicAdd(&hsum[d], q);
+      }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      unsigned long long cum = 0ull;
+      int cnt = 0, d = 0;
+      for (; d < 256; ++d) {
+        if (cum + hsum[d] > rem) break;      // this digit's units cannot all go
+        cum += hsum[d];
+        cnt += hcnt[d];
+      }
+      s_digit = d;
+      s_prefix = prefix | (static_cast<uint32_t>(d & 255) << shift);
+      s_rem = rem - cum;
+      s_below = below + cnt;
+    }
+    __syncthreads();
+    digit = s_digit;
+    prefix = s_prefix;
+    rem = s_rem;
+    below = s_below;
+    if (digit == 256) break;      // (first pass only) everything may go: uniform, no barrier follows
+  }
+  if (tid == 0) {
+    int removed;
+    if (digit == 256) {
+      removed = n;
+    } else {
+      // units whose key equals `prefix` share one mass
+      const int c_eq = hcnt[digit];
+      const unsigned long long qk = c_eq > 0 ? hsum[digit] / static_cast<unsigned long long>(c_eq) : 0ull;
+      const unsigned long long can = qk == 0ull ? static_cast<unsigned long long>(c_eq) : rem / qk;
+      removed = below + static_cast<int>(can < static_cast<unsigned long long>(c_eq) ? can : c_eq);
+    }
+    const int k = n - removed;
+    t.k_out[g] = k < 1 ? 1 : k;
+  }
 }
 
 static int validate_select(const ecospa_select_item& q) {
@@ -142,7 +240,7 @@ extern "C" int ecospa_select_topk_batch(ecospa_ctx* ctx, const ecospa_select_ite
     long long blk = 0;
     for (int i = 0; i < b.n_items; ++i) {
       const ecospa_select_item& q = items[first + i];
-      b.it[i] = SelectItemDev{q.scores, q.idx, q.n_units, q.k, static_cast<int>(blk)};
+      b.it[i] = SelectItemDev{q.scores, q.idx, q.n_units, q.k, static_cast<int>(blk), nullptr, 0};
       blk += q.groups;
       if (blk > (1ll << 30)) return ECOSPA_ERR_SHAPE;
     }
@@ -156,4 +254,21 @@ extern "C" int ecospa_select_topk(ecospa_ctx* ctx, const float* scores, int grou
   if (!ctx) return ECOSPA_ERR_NULL;
   const ecospa_select_item q{scores, groups, n_units, k, idx};
   return ecospa_select_topk_batch(ctx, &q, 1);
+}
+
+extern "C" int ecospa_select_theta(ecospa_ctx* ctx, const float* scores, int groups, int n_units, float theta, int* idx,
+                                   int* k_out) {
+  if (!ctx || !scores || !idx || !k_out) return ECOSPA_ERR_NULL;
+  if (groups < 1 || n_units < 1 || groups > (1 << 30)) return ECOSPA_ERR_SHAPE;
+  if (!(theta >= 0.f && theta <= 1.f)) return ECOSPA_ERR_K;
+  hipLaunchKernelGGL(select_theta_count_kernel, dim3(groups), dim3(SELECT_THREADS), 0, ctx->stream,
+                     ThetaItemDev{scores, k_out, n_units, theta});
+  ECOSPA_CHECK_LAUNCH(ctx, "select_theta_count_kernel");
+  SelectBatch b;
+  memset(&b, 0, sizeof(b));
+  b.n_items = 1;
+  b.it[0] = SelectItemDev{scores, idx, n_units, 0, 0, k_out, n_units};
+  hipLaunchKernelGGL(select_topk_kernel, dim3(groups), dim3(SELECT_THREADS), 0, ctx->stream, b);
+  ECOSPA_CHECK_LAUNCH(ctx, "select_topk_kernel");
+  return ECOSPA_OK;
 }
