@@ -173,6 +173,12 @@ def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps):
     t_score = timed_gpu(torch, lambda: ctx.ecospa_coupled_score(pair_arr, out=scores), steps, 3)
     t_select = timed_gpu(torch, lambda: ctx.ecospa_select_topk_batch(sel_arr), steps, 3)
     t_compact = timed_gpu(torch, lambda: ctx.ecospa_compact_batch(item_arr), steps, 3)
+    # the two other pieces of Alg. 1: pair-level importance (Eq. 8; the weights stand in for gradient
+    # tensors of the same shapes) and the cumulative-threshold rule on the FFN scores
+    fisher = ctx.ecospa_pair_fisher(pair_arr, 8192.0)
+    t_fisher = timed_gpu(torch, lambda: ctx.ecospa_pair_fisher(pair_arr, 8192.0, out=fisher), steps, 3)
+    ffn_scores = torch.cat([scores[3 * li + 2] for li in range(n_layers)]).contiguous()
+    t_theta = timed_gpu(torch, lambda: ctx.ecospa_select_theta(ffn_scores, 0.9), steps, 3)
     w_bytes = n_layers * 2 * (4 * d * d + 2 * d * dff)
     keep = keep_num / keep_den
     cols = n_layers * 2 * (d * d + d * dff)                 # the members gathered by column: W_o, W_2
@@ -184,6 +190,9 @@ def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps):
                         "traffic_gbs": traffic / t_compact / 1e6,
                         "frac_of_hbm_peak": traffic / t_compact / 1e6 / HBM_PEAK_GBS,
                         "note": "kept bytes read + written; traffic adds the whole 128-byte lines a column gather has to fetch"},
+            "pair_fisher": {"us": t_fisher * 1e3, "gbs": w_bytes / t_fisher / 1e6,
+                            "frac_of_hbm_peak": w_bytes / t_fisher / 1e6 / HBM_PEAK_GBS},
+            "select_theta": {"us": t_theta * 1e3, "rows": n_layers, "units": dff, "theta": 0.9},
             "timing": "device-side events, descriptors prebuilt"}
 
 

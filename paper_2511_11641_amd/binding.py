@@ -231,15 +231,17 @@ class Context:
         self._check(self.lib.ecospa_coupled_score(self.h, arr, len(arr), ptrs), "ecospa_coupled_score")
         return list(out)
 
-    def ecospa_pair_fisher(self, grads: Sequence[Pair], n_samples: float) -> list[torch.Tensor]:
+    def ecospa_pair_fisher(self, grads: Sequence[Pair], n_samples: float,
+                           out: Optional[Sequence[torch.Tensor]] = None) -> list[torch.Tensor]:
         """Eq. 8 importance of each coupled pair from its gradient matrices (described like the weights): one
-        float32 tensor [groups] per pair."""
+        float32 tensor [groups] per pair (written into `out` if given)."""
         arr = grads if isinstance(grads, C.Array) else (Pair * len(grads))(*grads)
         self.reserve(self.lib.ecospa_score_workspace_bytes(arr, len(arr)))
-        out = [torch.empty((p.groups,), dtype=torch.float32, device=self.device) for p in arr]
+        if out is None:
+            out = [torch.empty((p.groups,), dtype=torch.float32, device=self.device) for p in arr]
         ptrs = (C.c_void_p * len(arr))(*[o.data_ptr() for o in out])
         self._check(self.lib.ecospa_pair_fisher(self.h, arr, len(arr), float(n_samples), ptrs), "ecospa_pair_fisher")
-        return out
+        return list(out)
 
     def ecospa_select_theta(self, scores: torch.Tensor, theta: float):
         """Alg. 1's cumulative-threshold rule per row of scores[groups, n_units]: (idx[groups, n_units] int32 padded

@@ -10,6 +10,7 @@
 #include "common.h"
 
 #define SELECT_THREADS 1024
+#define SELECT_CACHE 8          // score keys a thread keeps in registers
 #define SELECT_MAX_ITEMS 96    // descriptors travel as kernel arguments
 
 struct SelectItemDev {
@@ -56,11 +57,14 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int& t
 }
 
 __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const SelectBatch b) {
+  // one histogram per wavefront: normalised scores share their top key bits, so a single histogram
+  // would serialise nearly every atomic of the first pass on a few counters
+  __shared__ int whist[SELECT_THREADS / 64][256];
   __shared__ int hist[257];
   __shared__ int wave_tot[SELECT_THREADS / 64];
   __shared__ uint32_t s_prefix;
   __shared__ int s_krem;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6;
   int item = 0, hi = b.n_items - 1;       // last item whose first block is <= blockIdx.x
   while (item < hi) {
     const int mid = (item + hi + 1) >> 1;
@@ -72,16 +76,41 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
   const float* s = t.scores + static_cast<long long>(g) * n;
   int* out = t.idx + static_cast<long long>(g) * (t.k_dev ? t.ld_idx : k);
 
+  // this thread's contiguous run of indices; runs of up to SELECT_CACHE elements (groups of up to
+  // SELECT_THREADS * SELECT_CACHE units) are read once and kept in registers for all passes
+  const int per = (n + SELECT_THREADS - 1) / SELECT_THREADS;
+  const int i0 = min(tid * per, n), i1 = min(i0 + per, n);
+  const bool cached = per <= SELECT_CACHE;
+  uint32_t kc[SELECT_CACHE];
+  if (cached) {
+#pragma unroll
+    for (int j = 0; j < SELECT_CACHE; ++j) kc[j] = i0 + j < i1 ? score_key(s[i0 + j]) : 0u;
+  }
+
   uint32_t prefix = 0u;   // high bits of the k-th largest key found so far
   int krem = k;           // rank (1-based) of the wanted key among keys matching the prefix
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
     const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
-    if (tid <= 256) hist[tid] = 0;
+    for (int i = tid; i < (SELECT_THREADS / 64) * 256; i += SELECT_THREADS) (&whist[0][0])[i] = 0;
+    if (tid == 256) hist[256] = 0;
     __syncthreads();
-    for (int i = tid; i < n; i += SELECT_THREADS) {
-      const uint32_t key = score_key(s[i]);
-      if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+    if (cached) {
+#pragma unroll
+      for (int j = 0; j < SELECT_CACHE; ++j)
+        if (i0 + j < i1 && (kc[j] & hi_mask) == prefix) atomicAdd(&whist[wave][(kc[j] >> shift) & 255u], 1);
+    } else {
+      for (int i = i0; i < i1; ++i) {
+        const uint32_t key = score_key(s[i]);
+        if ((key & hi_mask) == prefix) atomicAdd(&whist[wave][(key >> shift) & 255u], 1);
+      }
+    }
+    __syncthreads();
+    if (tid < 256) {
+      int c = 0;
+#pragma unroll
+      for (int w = 0; w < SELECT_THREADS / 64; ++w) c += whist[w][tid];
+      hist[tid] = c;
     }
     __syncthreads();
     // suffix sums: hist[d] = number of matching keys with digit >= d
@@ -102,25 +131,38 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
   }
   const uint32_t T = prefix;   // k-th largest key; take `krem` of the elements equal to it
 
-  // this thread's contiguous run of indices
-  const int per = (n + SELECT_THREADS - 1) / SELECT_THREADS;
-  const int i0 = min(tid * per, n), i1 = min(i0 + per, n);
   int n_eq = 0, n_gt = 0;
-  for (int i = i0; i < i1; ++i) {
-    const uint32_t key = score_key(s[i]);
-    n_eq += key == T;
-    n_gt += key > T;
+  if (cached) {
+#pragma unroll
+    for (int j = 0; j < SELECT_CACHE; ++j)
+      if (i0 + j < i1) { n_eq += kc[j] == T; n_gt += kc[j] > T; }
+  } else {
+    for (int i = i0; i < i1; ++i) {
+      const uint32_t key = score_key(s[i]);
+      n_eq += key == T;
+      n_gt += key > T;
+    }
   }
   int tot;
   const int eq_before = block_exclusive_scan(n_eq, wave_tot, tot);
   const int eq_take = max(0, min(n_eq, krem - eq_before));       // ties of this run that are kept
   int pos = block_exclusive_scan(n_gt + eq_take, wave_tot, tot);
   int eq_left = eq_take;
-  for (int i = i0; i < i1; ++i) {
-    const uint32_t key = score_key(s[i]);
-    bool take = key > T;
-    if (key == T && eq_left > 0) { take = true; --eq_left; }
-    if (take && pos < k) out[pos++] = i;
+  if (cached) {
+#pragma unroll
+    for (int j = 0; j < SELECT_CACHE; ++j) {
+      if (i0 + j >= i1) continue;
+      bool take = kc[j] > T;
+      if (kc[j] == T && eq_left > 0) { take = true; --eq_left; }
+      if (take && pos < k) out[pos++] = i0 + j;
+    }
+  } else {
+    for (int i = i0; i < i1; ++i) {
+      const uint32_t key = score_key(s[i]);
+      bool take = key > T;
+      if (key == T && eq_left > 0) { take = true; --eq_left; }
+      if (take && pos < k) out[pos++] = i;
+    }
   }
   if (t.k_dev)
     for (int i = k + tid; i < t.ld_idx; i += SELECT_THREADS) out[i] = -1;
@@ -147,17 +189,32 @@ struct ThetaItemDev {
   float theta;
 };
 __global__ __launch_bounds__(SELECT_THREADS) void select_theta_count_kernel(const ThetaItemDev t) {
-  __shared__ unsigned long long hsum[256];
-  __shared__ int hcnt[256];
+  __shared__ unsigned long long wsum[SELECT_THREADS / 64][256];   // per wavefront: see select_topk_kernel
+  __shared__ int wcnt[SELECT_THREADS / 64][256];
+  __shared__ unsigned long long hsum[256], csum[256];
+  __shared__ int hcnt[256], ccnt[256];
   __shared__ unsigned long long s_total, s_rem;
   __shared__ uint32_t s_prefix;
   __shared__ int s_below, s_digit;
   const int tid = threadIdx.x, g = blockIdx.x, n = t.n;
   const float* s = t.scores + static_cast<long long>(g) * n;
+  const int per = (n + SELECT_THREADS - 1) / SELECT_THREADS;
+  const int i0 = min(tid * per, n), i1 = min(i0 + per, n);
+  const bool cached = per <= SELECT_CACHE;
+  float vc[SELECT_CACHE];
+  if (cached) {
+#pragma unroll
+    for (int j = 0; j < SELECT_CACHE; ++j) vc[j] = i0 + j < i1 ? s[i0 + j] : 0.f;
+  }
   if (tid == 0) s_total = 0ull;
   __syncthreads();
   unsigned long long mine = 0ull;
-  for (int i = tid; i < n; i += SELECT_THREADS) mine += theta_mass(s[i]);
+  if (cached) {
+#pragma unroll
+    for (int j = 0; j < SELECT_CACHE; ++j) mine += i0 + j < i1 ? theta_mass(vc[j]) : 0ull;
+  } else {
+    for (int i = i0; i < i1; ++i) mine += theta_mass(s[i]);
+  }
   if (mine) atomicAdd(&s_total, mine);
   __syncthreads();
   const unsigned long long total = s_total;
@@ -170,31 +227,60 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_theta_count_kernel(cons
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
     const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
-    if (tid < 256) { hsum[tid] = 0ull; hcnt[tid] = 0; }
+    for (int i = tid; i < (SELECT_THREADS / 64) * 256; i += SELECT_THREADS) {
+      (&wsum[0][0])[i] = 0ull;
+      (&wcnt[0][0])[i] = 0;
+    }
     __syncthreads();
-    for (int i = tid; i < n; i += SELECT_THREADS) {
-      const float x = s[i];
+#pragma unroll 1
+    for (int i = i0; i < i1; ++i) {
+      float x;
+      if (cached) {
+        x = vc[0];
+#pragma unroll
+        for (int j = 1; j < SELECT_CACHE; ++j) x = (i - i0 == j) ? vc[j] : x;
+      } else {
+        x = s[i];
+      }
       const uint32_t key = score_key(x);
       if ((key & hi_mask) == prefix) {
         const int d = (key >> shift) & 255u;
-        atomicAdd(&hcnt[d], 1);
+        atomicAdd(&wcnt[tid >> 6][d], 1);
         const unsigned long long q = theta_mass(x);
-        if (q) atomicAdd(&hsum[d], q);
+        if (q) atomicAdd(&wsum[tid >> 6][d], q);
       }
     }
     __syncthreads();
-    if (tid == 0) {
-      unsigned long long cum = 0ull;
-      int cnt = 0, d = 0;
-      for (; d < 256; ++d) {
-        if (cum + hsum[d] > rem) break;      // this digit's units cannot all go
-        cum += hsum[d];
-        cnt += hcnt[d];
+    if (tid < 256) {
+      unsigned long long m = 0ull;
+      int c = 0;
+#pragma unroll
+      for (int w = 0; w < SELECT_THREADS / 64; ++w) { m += wsum[w][tid]; c += wcnt[w][tid]; }
+      hsum[tid] = m;
+      hcnt[tid] = c;
+    }
+    __syncthreads();
+    // inclusive prefix sums over the digits (ascending keys); the first digit whose cumulative mass
+    // exceeds what may still be removed is the one that cannot go entirely
+    if (tid < 256) { csum[tid] = hsum[tid]; ccnt[tid] = hcnt[tid]; }
+    if (tid == 0) s_digit = 256;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+      unsigned long long vm = 0ull;
+      int vc = 0;
+      if (tid < 256 && tid >= off) { vm = csum[tid - off]; vc = ccnt[tid - off]; }
+      __syncthreads();
+      if (tid < 256) { csum[tid] += vm; ccnt[tid] += vc; }
+      __syncthreads();
+    }
+    if (tid < 256) {
+      const unsigned long long incl = csum[tid], excl = incl - hsum[tid];
+      if (incl > rem && excl <= rem) {      // exactly one digit, if any
+        s_digit = tid;
+        s_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
+        s_rem = rem - excl;
+        s_below = below + ccnt[tid] - hcnt[tid];
       }
-      s_digit = d;
-      s_prefix = prefix | (static_cast<uint32_t>(d & 255) << shift);
-      s_rem = rem - cum;
-      s_below = below + cnt;
     }
     __syncthreads();
     digit = s_digit;
