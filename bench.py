@@ -24,9 +24,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the MFMA contraction kernel, averaged over the 12 launches of one sparse
-# step, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/): (gemm.hip sha256 prefix, bytes).
+# step, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/): (sha256 prefix of csrc/gemm*, bytes).
 # Reported only while the kernel source still has that hash; otherwise null.
-GEMM_TRAFFIC = ("1b506c137d358563", 120.5e6)
+GEMM_TRAFFIC = ("ad51f1d358172232", 120.5e6)
 
 
 def model_flops(T, L, d, h, k_qk, k_vo, k_ff, causal=True, gated=False):
@@ -39,11 +39,14 @@ def model_flops(T, L, d, h, k_qk, k_vo, k_ff, causal=True, gated=False):
 
 
 def gemm_traffic():
+    """HBM bytes per contraction launch from the committed counter profile, or None once the kernel sources
+    (csrc/gemm*) differ from the ones the counters were taken with."""
+    import glob
     import hashlib
     import os
-    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2511_11641_amd", "csrc", "gemm.hip")
+    pat = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2511_11641_amd", "csrc", "gemm*")
     try:
-        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+        digest = hashlib.sha256(b"".join(open(p, "rb").read() for p in sorted(glob.glob(pat)))).hexdigest()[:16]
     except OSError:
         return None
     return GEMM_TRAFFIC[1] if GEMM_TRAFFIC[0] == digest else None
@@ -343,7 +346,7 @@ def main():
         "parts_ms": parts,
         "score_gbs": w_bytes / (parts["score"] * 1e-3) / 1e9,
         "compact_gbs": w_bytes / (parts["compact"] * 1e-3) / 1e9,   # kept bytes read + kept bytes written
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_mfma_kernel", "achieved": gemm_tflops,
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_{pipe,mfma,rs}_kernel", "achieved": gemm_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": gemm_traffic(),
                      "launches": n_launch, "avg_launch_us": gemm_ms * 1e3 / max(n_launch, 1),
