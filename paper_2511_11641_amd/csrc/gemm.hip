@@ -158,11 +158,10 @@ void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
 
   // XCD-aware tile order: workgroup ids go round-robin over the 8 XCDs, so give each XCD a
   // contiguous range of tiles (neighbouring tiles share operand rows in that XCD's L2).
-  int id = blockIdx.x;
-  const int nb = gridDim.x;
-  if ((nb & 7) == 0) id = (id & 7) * (nb >> 3) + (id >> 3);
+  int id, zsplit;
+  gemm_work_item(d.splits > 1 ? d.splits : 1, id, zsplit);
   const int m0 = (id / tiles_n) * BM, n0 = (id % tiles_n) * BN;
-  const int k_begin = blockIdx.z * k_chunk;
+  const int k_begin = zsplit * k_chunk;
   const int k_end = min(d.K, k_begin + k_chunk);
   const int nk = (k_end - k_begin + BK - 1) / BK;
 
@@ -250,7 +249,7 @@ void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   // column = lane % 32, row = 8*(r/4) + 4*(lane/32) + r%4.
   float* cs = reinterpret_cast<float*>(lds) + wave * (32 * WTN);
   const bool split = d.splits > 1;
-  float* part = split ? d.partial + static_cast<long long>(blockIdx.z) * d.M * d.N : nullptr;
+  float* part = split ? d.partial + static_cast<long long>(zsplit) * d.M * d.N : nullptr;
   constexpr int LPR = WTN / 8;          // lanes per row
   constexpr int RPI = 64 / LPR;         // rows per pass
   const int n = n0 + wn * WTN + (lane % LPR) * 8;
@@ -414,7 +413,7 @@ template <int BM, int BN, int BK, int WGM, int WGN, int WPE, bool TRR>
 static hipError_t launch_tile(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
   const int tm = (d.M + BM - 1) / BM, tn = (d.N + BN - 1) / BN;
   const int splits = d.splits > 1 ? d.splits : 1;
-  const dim3 grid(tm * tn, 1, splits), block(64 * WGM * WGN);
+  const dim3 grid(tm * tn * splits), block(64 * WGM * WGN);
   const size_t operand_bytes = 2ull * (BM + BN) * BK * sizeof(bf16_t);
   const size_t staging_bytes = static_cast<size_t>(WGM) * WGN * 32 * (BN / WGN) * 4;   // epilogue tiles
   const size_t lds_bytes = operand_bytes > staging_bytes ? operand_bytes : staging_bytes;

@@ -54,3 +54,30 @@ __device__ __forceinline__ bf16x8_t read_frag(const bf16_t* tile, int row0, int 
   }
 }
 
+// Work item of a workgroup on a 1-D grid of tiles * splits: which output tile and which K split.
+// Workgroups are dealt round-robin to the 8 XCDs, each with an L2 of its own.  Every XCD gets a contiguous
+// range of tile ids, and with split K the splits are spread over the XCDs first (8 / splits XCDs per split,
+// or splits / 8 splits per XCD): the tiles of one split read one K range of both operands, so an XCD's L2
+// then holds that range once instead of every XCD fetching all of K for its share of the tiles.
+__device__ __forceinline__ void gemm_work_item(int splits, int& tile, int& z) {
+  const int id = blockIdx.x, nb = gridDim.x, tiles = nb / splits;
+  if (nb & 7) {                                   // no even deal: plain order
+    z = id / tiles;
+    tile = id - z * tiles;
+    return;
+  }
+  const int xcd = id & 7, j = id >> 3;            // j: index inside the XCD's share of nb / 8 workgroups
+  if (splits <= 8 && (8 % splits) == 0 && tiles % (8 / splits) == 0) {
+    const int p = 8 / splits;                     // XCDs per split
+    z = xcd / p;
+    tile = (xcd % p) * (tiles / p) + j;
+  } else if ((splits & 7) == 0) {
+    const int q = splits >> 3;                    // splits per XCD
+    z = xcd * q + j / tiles;
+    tile = j % tiles;
+  } else {
+    const int lin = xcd * (nb >> 3) + j;          // contiguous range per XCD over (split, tile)
+    z = lin / tiles;
+    tile = lin - z * tiles;
+  }
+}

@@ -86,15 +86,15 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   // range of tile ids, and order the ids in bands of GROUP_M tile rows, column by column inside a
   // band, so that the ~32 tiles an XCD works on at a time form a near-square block of C and share
   // their operand rows in that L2.
-  int id = blockIdx.x;
-  const int nb = gridDim.x;
-  if ((nb & 7) == 0) id = (id & 7) * (nb >> 3) + (id >> 3);
+  int id, zsplit;
+  const int nsplit = d.splits > 1 ? d.splits : 1;
+  gemm_work_item(nsplit, id, zsplit);
   constexpr int GROUP_M = BM >= 256 ? 4 : 8;
-  const int tiles_m = nb / tiles_n;
+  const int tiles_m = static_cast<int>(gridDim.x) / nsplit / tiles_n;
   const int band = id / (GROUP_M * tiles_n), in_band = id - band * (GROUP_M * tiles_n);
   const int band_rows = min(GROUP_M, tiles_m - band * GROUP_M);
   const int m0 = (band * GROUP_M + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
-  const int k_begin = blockIdx.z * k_chunk;
+  const int k_begin = zsplit * k_chunk;
   const int k_end = min(d.K, k_begin + k_chunk);
   const int nk = (k_end - k_begin) / BK;               // full slabs only (checked on the host)
 
@@ -210,7 +210,7 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   // row = 8 * (r / 4) + 4 * (lane / 32) + r % 4.
   float* cs = reinterpret_cast<float*>(lds) + wave * (32 * WTN);
   const bool split = d.splits > 1;
-  float* part = split ? d.partial + static_cast<long long>(blockIdx.z) * d.M * d.N : nullptr;
+  float* part = split ? d.partial + static_cast<long long>(zsplit) * d.M * d.N : nullptr;
   constexpr int LPR = WTN / 8;          // lanes per row
   constexpr int RPI = 64 / LPR;         // rows per pass
   const int n = n0 + wn * WTN + (lane % LPR) * 8;
@@ -272,7 +272,7 @@ template <int BM, int BN, int BK, int NS, int WGM, int WGN, int WPE>
 static hipError_t launch_pipe(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
   const int tm = (d.M + BM - 1) / BM, tn = (d.N + BN - 1) / BN;
   const int splits = d.splits > 1 ? d.splits : 1;
-  const dim3 grid(tm * tn, 1, splits), block(64 * WGM * WGN);
+  const dim3 grid(tm * tn * splits), block(64 * WGM * WGN);
   const size_t operand_bytes = static_cast<size_t>(NS) * (BM + BN) * BK * sizeof(bf16_t);
   const size_t staging_bytes = static_cast<size_t>(WGM) * WGN * 32 * (BN / WGN) * 4;
   const size_t lds_bytes = operand_bytes > staging_bytes ? operand_bytes : staging_bytes;

@@ -85,15 +85,15 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   const int wm = wave / WGN, wn = wave % WGN;
 
   // tile order: a contiguous id range per XCD, bands of four tile rows walked column by column
-  int id = blockIdx.x;
-  const int nb = gridDim.x;
-  if ((nb & 7) == 0) id = (id & 7) * (nb >> 3) + (id >> 3);
+  int id, zsplit;
+  const int nsplit = d.splits > 1 ? d.splits : 1;
+  gemm_work_item(nsplit, id, zsplit);
   constexpr int GROUP_M = 4;
-  const int tiles_m = nb / tiles_n;
+  const int tiles_m = static_cast<int>(gridDim.x) / nsplit / tiles_n;
   const int band = id / (GROUP_M * tiles_n), in_band = id - band * (GROUP_M * tiles_n);
   const int band_rows = min(GROUP_M, tiles_m - band * GROUP_M);
   const int m0 = (band * GROUP_M + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
-  const int k_begin = blockIdx.z * k_chunk;
+  const int k_begin = zsplit * k_chunk;
   const int k_end = min(d.K, k_begin + k_chunk);
   const int nk = (k_end - k_begin) / BK;               // full slabs only (checked on the host)
 
@@ -190,7 +190,7 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   // row = 8 * (r / 4) + 4 * (lane / 32) + r % 4.
   float* cs = reinterpret_cast<float*>(lds) + wave * (32 * WTN);
   const bool split = d.splits > 1;
-  float* part = split ? d.partial + static_cast<long long>(blockIdx.z) * d.M * d.N : nullptr;
+  float* part = split ? d.partial + static_cast<long long>(zsplit) * d.M * d.N : nullptr;
   constexpr int LPR = WTN / 8;          // lanes per row
   constexpr int RPI = 64 / LPR;         // rows per pass
   const int n = n0 + wn * WTN + (lane % LPR) * 8;
@@ -241,7 +241,7 @@ bool gemm_rs_ok(const GemmDesc& d, int k_chunk) {
 hipError_t gemm_rs_launch(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
   const int tm = (d.M + 255) / 256, tn = (d.N + 255) / 256;
   const int splits = d.splits > 1 ? d.splits : 1;
-  const dim3 grid(tm * tn, 1, splits), block(256);
+  const dim3 grid(tm * tn * splits), block(256);
   const int lds_bytes = 2 * (256 + 256) * 64 * static_cast<int>(sizeof(bf16_t));   // also covers the epilogue staging
 #define RS_LAUNCH(TB)                                                                                          \
   do {                                                                                                         \
