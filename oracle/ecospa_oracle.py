@@ -174,6 +174,59 @@ def select_theta(scores, theta: float):
     return idx, ks
 
 
+def select_pairs(fisher, n_select: int) -> np.ndarray:
+    """Alg. 1's choice among the coupled pairs: the n_select pairs whose importance (Eq. 8) is smallest,
+    as ascending int32 indices.  Smaller value first, NaN before every number, ``-0 == +0``, equal
+    values go to the lower index."""
+    f = [float(v) for v in np.asarray(fisher).reshape(-1)]
+    assert 0 <= n_select <= len(f)
+    left = list(range(len(f)))
+    chosen = []
+    for _ in range(n_select):                      # repeatedly take the least important pair still left
+        best = left[0]
+        for i in left[1:]:
+            if f[best] != f[best]:                 # a NaN already leads; an earlier index keeps it
+                break
+            if f[i] != f[i] or f[i] < f[best]:
+                best = i
+        left.remove(best)
+        chosen.append(best)
+    return np.array(sorted(chosen), dtype=np.int32)
+
+
+def compact_ragged(src, idx, ks, axis: int, n: int, kp: int, unit: int = 1) -> np.ndarray:
+    """Aligned gather with a kept count of its own for every group (what the removal loop of Alg. 1
+    leaves): group g keeps the units idx[g, :ks[g]]; every group is padded with zeros to kp units, so
+    the result is one dense matrix."""
+    src = np.asarray(src)
+    idx = np.asarray(idx)
+    groups = idx.shape[0]
+    vec = src.ndim == 1
+    m = src.reshape(1, -1) if vec else (src.T if axis == 0 else src)       # inner axis last
+    out = np.zeros((m.shape[0], groups * kp * unit), dtype=src.dtype)
+    for g in range(groups):
+        assert 0 <= ks[g] <= kp
+        for i in range(int(ks[g])):
+            for u in range(unit):
+                out[:, (g * kp + i) * unit + u] = m[:, g * n + int(idx[g, i]) * unit + u]
+    return out.reshape(-1) if vec else (out.T if axis == 0 else out)
+
+
+def scatter_ragged(cmp, idx, ks, axis: int, n: int, kp: int, unit: int = 1) -> np.ndarray:
+    """Inverse of :func:`compact_ragged`: kept units back in place, zeros everywhere else."""
+    cmp = np.asarray(cmp)
+    idx = np.asarray(idx)
+    groups = idx.shape[0]
+    vec = cmp.ndim == 1
+    m = cmp.reshape(1, -1) if vec else (cmp.T if axis == 0 else cmp)
+    out = np.zeros((m.shape[0], groups * n), dtype=cmp.dtype)
+    for g in range(groups):
+        for i in range(int(ks[g])):
+            for u in range(unit):
+                out[:, g * n + int(idx[g, i]) * unit + u] = m[:, (g * kp + i) * unit + u]
+    return out.reshape(-1) if vec else (out.T if axis == 0 else out)
+
+
 def kept_positions(idx, n: int, unit: int = 1) -> np.ndarray:
     """Flat positions, over all groups, of the kept inner dimensions (ascending per group)."""
     idx = np.asarray(idx, dtype=np.int64)
