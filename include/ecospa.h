@@ -133,6 +133,14 @@ int ecospa_select_topk_batch(ecospa_ctx* ctx, const ecospa_select_item* items /*
 int ecospa_pair_fisher(ecospa_ctx* ctx, const ecospa_pair* grads /*host*/, int n_pairs, float n_samples,
                        float* const* fisher /*host*/);
 int ecospa_select_theta(ecospa_ctx* ctx, const float* scores, int groups, int n_units, float theta, int* idx, int* k_out);
+/* ecospa_select_pairs - Alg. 1's choice among the coupled pairs of the model: of the n_pairs importance
+ * values `fisher` (device float[n_pairs], as written by ecospa_pair_fisher into one array) the n_select
+ * smallest are chosen (n_select = the top-K ratio times n_pairs, rounded by the caller); `chosen`
+ * receives their indices, ascending (device int32[n_select]).  The order is that of ecospa_select_topk
+ * reversed: smaller value first, NaN before every number, -0 == +0, equal values go to the lower index
+ * - exactly one result is correct.  Errors: ERR_NULL; n_pairs < 1 -> ERR_SHAPE; n_select outside
+ * [1, n_pairs] -> ERR_K. */
+int ecospa_select_pairs(ecospa_ctx* ctx, const float* fisher, int n_pairs, int n_select, int* chosen);
 
 /* ------------------------------------------------------------------------------------------
  * Step 3 - aligned gather of the kept inner dimensions into a smaller dense matrix (Def. 1:
@@ -161,12 +169,23 @@ int ecospa_scatter(ecospa_ctx* ctx, const void* src, void* dst, int dtype, int a
  * fields have the meaning of the arguments above, scatter != 0 selects the inverse direction.
  * `items` is a host array; all items are validated before anything is launched.  Items must not
  * overlap each other's destinations. */
+/* Ragged kept counts (what the cumulative-threshold rule of Alg. 1 leaves: every head, every pair its
+ * own k): k_group != NULL names a device int32[groups] array (k_out of ecospa_select_theta), ld_idx the
+ * distance between the index lists of consecutive groups (idx: int32[groups * ld_idx], as written by
+ * ecospa_select_theta with ld_idx = n_units).  Group g then keeps its first min(k_group[g], kp, ld_idx)
+ * listed units and the remaining slots up to kp are zeros (scatter: its other rows/columns are
+ * zeros), so all groups share the padded width kp and the compact matrices stay dense; `k` is not
+ * used.  The counts live on the device and cannot be checked on the host: choosing kp >= max_g
+ * k_group[g] is the caller's contract (units beyond kp would be dropped).  k_group == NULL: every
+ * group keeps k units, ld_idx = 0 means k.  Errors for ragged items: kp < 1 or ld_idx < 1 -> ERR_K. */
 typedef struct {
   const void* src;
   void* dst;
   int dtype, axis, groups, n, unit, k, kp, scatter;
   long long other_extent, ld_src, ld_dst;
   const int* idx;
+  const int* k_group; /* device int32[groups] or NULL */
+  int ld_idx;
 } ecospa_map_item;
 int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* items /*host*/, int n_items);
 
@@ -177,6 +196,10 @@ int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* items /*host*/,
  * block i at slot i (dense layer).  Angles are evaluated in fp64. */
 int ecospa_rope_table(ecospa_ctx* ctx, const int* idx, int h, int L, int k, int kp, int d_h, double base,
                       float* cos_out, float* sin_out);
+/* The same with ragged kept counts: head g keeps its first min(k_group[g], kp, ld_idx) listed blocks
+ * (idx: device int32[h * ld_idx], k_group: device int32[h]), the slots behind them get cos = 1, sin = 0. */
+int ecospa_rope_table_ragged(ecospa_ctx* ctx, const int* idx, int ld_idx, const int* k_group, int h, int L, int kp,
+                             int d_h, double base, float* cos_out, float* sin_out);
 
 /* ------------------------------------------------------------------------------------------
  * Steps 4-5 - reduced forward and backward contractions on the compacted matrices (Eq. 1-3,

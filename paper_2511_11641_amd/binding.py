@@ -27,6 +27,7 @@ EXPORTS = (
     "ecospa_scatter", "ecospa_rope_table", "ecospa_block_workspace_bytes", "ecospa_coupled_fwd",
     "ecospa_coupled_bwd", "ecospa_profile_gemm", "ecospa_profile_gemm_read", "ecospa_contract",
     "ecospa_select_topk_batch", "ecospa_compact_batch", "ecospa_pair_fisher", "ecospa_select_theta",
+    "ecospa_select_pairs", "ecospa_rope_table_ragged",
 )
 
 
@@ -62,7 +63,7 @@ class MapItem(C.Structure):
     _fields_ = [("src", C.c_void_p), ("dst", C.c_void_p), ("dtype", C.c_int), ("axis", C.c_int), ("groups", C.c_int),
                 ("n", C.c_int), ("unit", C.c_int), ("k", C.c_int), ("kp", C.c_int), ("scatter", C.c_int),
                 ("other_extent", C.c_longlong), ("ld_src", C.c_longlong), ("ld_dst", C.c_longlong),
-                ("idx", C.c_void_p)]
+                ("idx", C.c_void_p), ("k_group", C.c_void_p), ("ld_idx", C.c_int)]
 
 
 class Saved(C.Structure):
@@ -109,6 +110,8 @@ def load() -> C.CDLL:
     lib.ecospa_pair_fisher.restype = ci
     lib.ecospa_select_theta.argtypes = [vp, vp, ci, ci, C.c_float, vp, vp]
     lib.ecospa_select_theta.restype = ci
+    lib.ecospa_select_pairs.argtypes = [vp, vp, ci, ci, vp]
+    lib.ecospa_select_pairs.restype = ci
     for f in (lib.ecospa_compact, lib.ecospa_scatter):
         f.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ll, ll, ll, vp]
         f.restype = ci
@@ -118,6 +121,8 @@ def load() -> C.CDLL:
     lib.ecospa_compact_batch.restype = ci
     lib.ecospa_rope_table.argtypes = [vp, vp, ci, ci, ci, ci, ci, C.c_double, vp, vp]
     lib.ecospa_rope_table.restype = ci
+    lib.ecospa_rope_table_ragged.argtypes = [vp, vp, ci, vp, ci, ci, ci, ci, C.c_double, vp, vp]
+    lib.ecospa_rope_table_ragged.restype = ci
     lib.ecospa_block_workspace_bytes.argtypes = [C.POINTER(BlockDesc)]
     lib.ecospa_block_workspace_bytes.restype = sz
     lib.ecospa_coupled_fwd.argtypes = [vp, C.POINTER(BlockDesc), vp, vp, C.POINTER(Saved)]
@@ -254,6 +259,15 @@ class Context:
                                                  k.data_ptr()), "ecospa_select_theta")
         return idx, k
 
+    def ecospa_select_pairs(self, fisher: torch.Tensor, n_select: int) -> torch.Tensor:
+        """Alg. 1's choice among the pairs: ascending indices (int32[n_select]) of the n_select smallest
+        importance values of fisher[n_pairs]."""
+        assert fisher.dtype == torch.float32 and fisher.dim() == 1 and fisher.is_contiguous()
+        chosen = torch.empty((max(n_select, 1),), dtype=torch.int32, device=fisher.device)
+        self._check(self.lib.ecospa_select_pairs(self.h, fisher.data_ptr(), fisher.numel(), n_select,
+                                                 chosen.data_ptr()), "ecospa_select_pairs")
+        return chosen[:n_select]
+
     # ---- step 2 ------------------------------------------------------------------------------
     def ecospa_select_topk(self, scores: torch.Tensor, k: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
         groups, n_units = scores.shape
@@ -277,9 +291,14 @@ class Context:
     # ---- step 3 ------------------------------------------------------------------------------
     @staticmethod
     def map_item(src: torch.Tensor, dst: torch.Tensor, idx: torch.Tensor, axis: int, groups: int, n: int,
-                 unit: int = 1, kp: Optional[int] = None, scatter: bool = False) -> MapItem:
-        """Descriptor of one gather (or scatter) for :meth:`ecospa_compact_batch`."""
-        k = idx.shape[1]
+                 unit: int = 1, kp: Optional[int] = None, scatter: bool = False,
+                 k_group: Optional[torch.Tensor] = None) -> MapItem:
+        """Descriptor of one gather (or scatter) for :meth:`ecospa_compact_batch`.  With k_group (int32[groups]
+        on the device) group g keeps its first k_group[g] entries of idx[g, :] and kp must be given."""
+        if k_group is not None:
+            assert kp is not None and k_group.dtype == torch.int32 and k_group.numel() == groups
+            assert idx.dtype == torch.int32 and idx.dim() == 2 and idx.is_contiguous() and idx.shape[0] == groups
+        k = idx.shape[1] if k_group is None else 0
         kp = k if kp is None else kp
         if src.dim() == 1:
             other, ld_s, ld_d, axis = 1, src.numel(), dst.numel(), 1
@@ -287,7 +306,19 @@ class Context:
             other = src.shape[1] if axis == 0 else src.shape[0]
             ld_s, ld_d = src.stride(0), dst.stride(0)
         return MapItem(src.data_ptr(), dst.data_ptr(), dtype_code(src.dtype), axis, groups, n, unit, k, kp,
-                       int(scatter), other, ld_s, ld_d, idx.data_ptr())
+                       int(scatter), other, ld_s, ld_d, idx.data_ptr(), _ptr(k_group),
+                       idx.shape[1] if k_group is not None else 0)
+
+    def ecospa_compact_ragged(self, src: torch.Tensor, idx: torch.Tensor, k_group: torch.Tensor, axis: int, groups: int,
+                              n: int, kp: int, unit: int = 1, scatter: bool = False,
+                              out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Gather (or scatter) with ragged kept counts, all groups padded to kp slots."""
+        slots = groups * n if scatter else groups * kp * unit
+        if out is None:
+            shape = (slots,) if src.dim() == 1 else ((slots, src.shape[1]) if axis == 0 else (src.shape[0], slots))
+            out = torch.empty(shape, dtype=src.dtype, device=src.device)
+        self.ecospa_compact_batch([self.map_item(src, out, idx, axis, groups, n, unit, kp, scatter, k_group)])
+        return out
 
     def ecospa_compact_batch(self, items: Sequence[MapItem]):
         arr = items if isinstance(items, C.Array) else (MapItem * len(items))(*items)
@@ -334,6 +365,21 @@ class Context:
             sin = torch.empty_like(cos)
         self._check(self.lib.ecospa_rope_table(self.h, _ptr(idx), h, L, k, kp, d_h, float(base), cos.data_ptr(),
                                                sin.data_ptr()), "ecospa_rope_table")
+        return cos, sin
+
+    def ecospa_rope_table_ragged(self, idx: torch.Tensor, k_group: torch.Tensor, L: int, kp: int, d_h: int,
+                                 base: float = 10000.0, out=None):
+        h = idx.shape[0]
+        assert idx.dtype == torch.int32 and idx.is_contiguous() and k_group.dtype == torch.int32 and k_group.numel() == h
+        if out is not None:
+            cos, sin = out
+            assert cos.shape == (h, L, kp) and sin.shape == (h, L, kp) and cos.dtype == torch.float32
+        else:
+            cos = torch.empty((h, L, kp), dtype=torch.float32, device=self.device)
+            sin = torch.empty_like(cos)
+        self._check(self.lib.ecospa_rope_table_ragged(self.h, idx.data_ptr(), idx.shape[1], k_group.data_ptr(), h, L, kp,
+                                                      d_h, float(base), cos.data_ptr(), sin.data_ptr()),
+                    "ecospa_rope_table_ragged")
         return cos, sin
 
     # ---- steps 4-5 ---------------------------------------------------------------------------

@@ -17,25 +17,36 @@ struct MapArgs {
   const int* idx;
   int groups, n, unit, k, kp;
   int scatter;
+  const int* k_group;   // ragged kept counts (one per group, device memory) or null: every group keeps k
+  int ld_idx;           // distance between the index lists of consecutive groups
 };
+
+// Kept count of group g: the ragged count is clamped to what the destination and the index list hold.
+__device__ __forceinline__ int map_kept(const MapArgs& m, int g) {
+  if (!m.k_group) return m.k;
+  const int kg = m.k_group[g], cap = m.kp < m.ld_idx ? m.kp : m.ld_idx;
+  return kg < 0 ? 0 : (kg < cap ? kg : cap);
+}
 
 __device__ __forceinline__ long long map_slot(const MapArgs& m, long long s) {
   if (!m.scatter) {
     const int per = m.kp * m.unit;
     const int g = static_cast<int>(s / per), rem = static_cast<int>(s % per);
     const int i = rem / m.unit, u = rem % m.unit;
-    if (i >= m.k) return -1;
-    return static_cast<long long>(g) * m.n + static_cast<long long>(m.idx[g * m.k + i]) * m.unit + u;
+    if (i >= map_kept(m, g)) return -1;
+    return static_cast<long long>(g) * m.n +
+           static_cast<long long>(m.idx[static_cast<long long>(g) * m.ld_idx + i]) * m.unit + u;
   }
   const int g = static_cast<int>(s / m.n), rem = static_cast<int>(s % m.n);
   const int q = rem / m.unit, u = rem % m.unit;
-  const int* list = m.idx + static_cast<long long>(g) * m.k;
-  int lo = 0, hi = m.k;   // first position with list[pos] >= q
+  const int* list = m.idx + static_cast<long long>(g) * m.ld_idx;
+  const int kg = map_kept(m, g);
+  int lo = 0, hi = kg;   // first position with list[pos] >= q
   while (lo < hi) {
     const int mid = (lo + hi) >> 1;
     if (list[mid] < q) lo = mid + 1; else hi = mid;
   }
-  if (lo >= m.k || list[lo] != q) return -1;
+  if (lo >= kg || list[lo] != q) return -1;
   return static_cast<long long>(g) * m.kp * m.unit + static_cast<long long>(lo) * m.unit + u;
 }
 
@@ -242,7 +253,11 @@ static int validate_map(const ecospa_map_item& q) {
   if (!dtype_ok(q.dtype)) return ECOSPA_ERR_DTYPE;
   if (q.axis != 0 && q.axis != 1) return ECOSPA_ERR_SHAPE;
   if (q.groups < 1 || q.n < 1 || q.unit < 1 || q.n % q.unit || q.other_extent < 1) return ECOSPA_ERR_SHAPE;
-  if (q.k < 1 || q.k > q.n / q.unit || q.kp < q.k) return ECOSPA_ERR_K;
+  if (q.k_group) {      // ragged: the counts live on the device, only the capacities can be checked here
+    if (q.kp < 1 || q.ld_idx < 1) return ECOSPA_ERR_K;
+  } else if (q.k < 1 || q.k > q.n / q.unit || q.kp < q.k || (q.ld_idx != 0 && q.ld_idx < q.k)) {
+    return ECOSPA_ERR_K;
+  }
   const long long full_slots = static_cast<long long>(q.groups) * q.n;
   const long long cmp_slots = static_cast<long long>(q.groups) * q.kp * q.unit;
   if (full_slots > (1ll << 31) - 1 || cmp_slots > (1ll << 31) - 1) return ECOSPA_ERR_SHAPE;
@@ -272,7 +287,7 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
       const ecospa_map_item& q = items[first + i];
       MapItemDev& t = b.it[i];
       t.src = q.src; t.dst = q.dst;
-      t.m = MapArgs{q.idx, q.groups, q.n, q.unit, q.k, q.kp, q.scatter ? 1 : 0};
+      t.m = MapArgs{q.idx, q.groups, q.n, q.unit, q.k, q.kp, q.scatter ? 1 : 0, q.k_group, q.ld_idx ? q.ld_idx : q.k};
       const long long full_slots = static_cast<long long>(q.groups) * q.n;
       const long long cmp_slots = static_cast<long long>(q.groups) * q.kp * q.unit;
       t.dst_slots = q.scatter ? full_slots : cmp_slots;
@@ -315,6 +330,7 @@ static int mapped_copy(ecospa_ctx* ctx, const void* src, void* dst, int dtype, i
   ecospa_map_item q;
   q.src = src; q.dst = dst; q.dtype = dtype; q.axis = axis; q.groups = groups; q.n = n; q.unit = unit; q.k = k;
   q.kp = kp; q.other_extent = other; q.ld_src = ld_src; q.ld_dst = ld_dst; q.idx = idx; q.scatter = scatter;
+  q.k_group = nullptr; q.ld_idx = 0;
   return ecospa_compact_batch(ctx, &q, 1);
 }
 
@@ -332,7 +348,8 @@ extern "C" int ecospa_scatter(ecospa_ctx* ctx, const void* src, void* dst, int d
 
 // ---- cos/sin tables of the kept rotary blocks (Eq. 6) -------------------------------------------
 __global__ void rope_table_kernel(const int* __restrict__ idx, int h, int L, int k, int kp, int d_h, double base,
-                                  float* __restrict__ cos_out, float* __restrict__ sin_out) {
+                                  float* __restrict__ cos_out, float* __restrict__ sin_out,
+                                  const int* __restrict__ k_group, int ld_idx) {
   const long long tot = static_cast<long long>(h) * L * kp;
   const long long e = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
   if (e >= tot) return;
@@ -340,8 +357,13 @@ __global__ void rope_table_kernel(const int* __restrict__ idx, int h, int L, int
   const int t = static_cast<int>((e / kp) % L);
   const int g = static_cast<int>(e / (static_cast<long long>(kp) * L));
   float c = 1.f, s = 0.f;
-  if (i < k) {
-    const int p = idx ? idx[g * k + i] : i;
+  int kg = k;
+  if (k_group) {
+    const int cap = kp < ld_idx ? kp : ld_idx;
+    kg = k_group[g] < 0 ? 0 : (k_group[g] < cap ? k_group[g] : cap);
+  }
+  if (i < kg) {
+    const int p = idx ? idx[static_cast<long long>(g) * ld_idx + i] : i;
     const double theta = exp(-2.0 * static_cast<double>(p) / static_cast<double>(d_h) * log(base));
     const double ang = static_cast<double>(t) * theta;
     c = static_cast<float>(cos(ang));
@@ -358,7 +380,19 @@ extern "C" int ecospa_rope_table(ecospa_ctx* ctx, const int* idx, int h, int L, 
   if (k < 1 || kp < k || k > d_h / 2) return ECOSPA_ERR_K;
   const long long tot = static_cast<long long>(h) * L * kp;
   hipLaunchKernelGGL(rope_table_kernel, dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream, idx,
-                     h, L, k, kp, d_h, base, cos_out, sin_out);
+                     h, L, k, kp, d_h, base, cos_out, sin_out, nullptr, k);
+  ECOSPA_CHECK_LAUNCH(ctx, "rope_table_kernel");
+  return ECOSPA_OK;
+}
+
+extern "C" int ecospa_rope_table_ragged(ecospa_ctx* ctx, const int* idx, int ld_idx, const int* k_group, int h, int L,
+                                        int kp, int d_h, double base, float* cos_out, float* sin_out) {
+  if (!ctx || !idx || !k_group || !cos_out || !sin_out) return ECOSPA_ERR_NULL;
+  if (h < 1 || L < 1 || d_h < 2 || !(base > 1.0)) return ECOSPA_ERR_SHAPE;
+  if (kp < 1 || ld_idx < 1) return ECOSPA_ERR_K;
+  const long long tot = static_cast<long long>(h) * L * kp;
+  hipLaunchKernelGGL(rope_table_kernel, dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream, idx,
+                     h, L, 0, kp, d_h, base, cos_out, sin_out, k_group, ld_idx);
   ECOSPA_CHECK_LAUNCH(ctx, "rope_table_kernel");
   return ECOSPA_OK;
 }

@@ -20,6 +20,7 @@ struct SelectItemDev {
   int blk_begin;   // first workgroup (= group) of this item
   const int* k_dev;  // optional: per-group kept counts in device memory (then k is unused, the rows of idx
   int ld_idx;        //           are ld_idx apart and the slots behind the kept indices are set to -1)
+  int smallest;      // take the k smallest scores instead (the order of the keys reversed, ties still to the lower index)
 };
 struct SelectBatch {
   int n_items;
@@ -56,6 +57,7 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int& t
   return before + inc - v;
 }
 
+#define ITEM_KEY(x) (score_key(x) ^ flip)
 __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const SelectBatch b) {
   // one histogram per wavefront: normalised scores share their top key bits, so a single histogram
   // would serialise nearly every atomic of the first pass on a few counters
@@ -72,6 +74,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
   }
   const SelectItemDev& t = b.it[item];
   const int n = t.n, g = blockIdx.x - t.blk_begin;
+  const uint32_t flip = t.smallest ? 0xffffffffu : 0u;
   const int k = t.k_dev ? t.k_dev[g] : t.k;
   const float* s = t.scores + static_cast<long long>(g) * n;
   int* out = t.idx + static_cast<long long>(g) * (t.k_dev ? t.ld_idx : k);
@@ -84,7 +87,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
   uint32_t kc[SELECT_CACHE];
   if (cached) {
 #pragma unroll
-    for (int j = 0; j < SELECT_CACHE; ++j) kc[j] = i0 + j < i1 ? score_key(s[i0 + j]) : 0u;
+    for (int j = 0; j < SELECT_CACHE; ++j) kc[j] = i0 + j < i1 ? ITEM_KEY(s[i0 + j]) : 0u;
   }
 
   uint32_t prefix = 0u;   // high bits of the k-th largest key found so far
@@ -101,7 +104,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
         if (i0 + j < i1 && (kc[j] & hi_mask) == prefix) atomicAdd(&whist[wave][(kc[j] >> shift) & 255u], 1);
     } else {
       for (int i = i0; i < i1; ++i) {
-        const uint32_t key = score_key(s[i]);
+        const uint32_t key = ITEM_KEY(s[i]);
         if ((key & hi_mask) == prefix) atomicAdd(&whist[wave][(key >> shift) & 255u], 1);
       }
     }
@@ -138,7 +141,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
       if (i0 + j < i1) { n_eq += kc[j] == T; n_gt += kc[j] > T; }
   } else {
     for (int i = i0; i < i1; ++i) {
-      const uint32_t key = score_key(s[i]);
+      const uint32_t key = ITEM_KEY(s[i]);
       n_eq += key == T;
       n_gt += key > T;
     }
@@ -158,7 +161,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
     }
   } else {
     for (int i = i0; i < i1; ++i) {
-      const uint32_t key = score_key(s[i]);
+      const uint32_t key = ITEM_KEY(s[i]);
       bool take = key > T;
       if (key == T && eq_left > 0) { take = true; --eq_left; }
       if (take && pos < k) out[pos++] = i;
@@ -167,6 +170,9 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
   if (t.k_dev)
     for (int i = k + tid; i < t.ld_idx; i += SELECT_THREADS) out[i] = -1;
 }
+
+// ---------------------------------------------------------------------------------------------
+#undef ITEM_KEY
 
 // ---------------------------------------------------------------------------------------------
 // Cumulative-threshold rule (Alg. 1's inner loop): how many units of a group stay when the smallest
@@ -326,7 +332,7 @@ extern "C" int ecospa_select_topk_batch(ecospa_ctx* ctx, const ecospa_select_ite
     long long blk = 0;
     for (int i = 0; i < b.n_items; ++i) {
       const ecospa_select_item& q = items[first + i];
-      b.it[i] = SelectItemDev{q.scores, q.idx, q.n_units, q.k, static_cast<int>(blk), nullptr, 0};
+      b.it[i] = SelectItemDev{q.scores, q.idx, q.n_units, q.k, static_cast<int>(blk), nullptr, 0, 0};
       blk += q.groups;
       if (blk > (1ll << 30)) return ECOSPA_ERR_SHAPE;
     }
@@ -353,8 +359,22 @@ extern "C" int ecospa_select_theta(ecospa_ctx* ctx, const float* scores, int gro
   SelectBatch b;
   memset(&b, 0, sizeof(b));
   b.n_items = 1;
-  b.it[0] = SelectItemDev{scores, idx, n_units, 0, 0, k_out, n_units};
+  b.it[0] = SelectItemDev{scores, idx, n_units, 0, 0, k_out, n_units, 0};
   hipLaunchKernelGGL(select_topk_kernel, dim3(groups), dim3(SELECT_THREADS), 0, ctx->stream, b);
+  ECOSPA_CHECK_LAUNCH(ctx, "select_topk_kernel");
+  return ECOSPA_OK;
+}
+
+// Alg. 1's choice among the coupled pairs: the n_select pairs with the smallest importance (Eq. 8).
+extern "C" int ecospa_select_pairs(ecospa_ctx* ctx, const float* fisher, int n_pairs, int n_select, int* chosen) {
+  if (!ctx || !fisher || !chosen) return ECOSPA_ERR_NULL;
+  if (n_pairs < 1) return ECOSPA_ERR_SHAPE;
+  if (n_select < 1 || n_select > n_pairs) return ECOSPA_ERR_K;
+  SelectBatch b;
+  memset(&b, 0, sizeof(b));
+  b.n_items = 1;
+  b.it[0] = SelectItemDev{fisher, chosen, n_pairs, n_select, 0, nullptr, 0, 1};
+  hipLaunchKernelGGL(select_topk_kernel, dim3(1), dim3(SELECT_THREADS), 0, ctx->stream, b);
   ECOSPA_CHECK_LAUNCH(ctx, "select_topk_kernel");
   return ECOSPA_OK;
 }

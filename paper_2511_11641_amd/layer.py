@@ -29,10 +29,13 @@ class FfnBlock:
     def score(self) -> torch.Tensor:
         return self.ctx.ecospa_coupled_score([self.pair()])[0]
 
-    def compact(self, idx: torch.Tensor, defer: bool = False):
+    def compact(self, idx: torch.Tensor, defer: bool = False, k_group: Optional[torch.Tensor] = None):
         """Gather the kept rows/columns named by idx[1, k] into the padded compact layout (one launch).
-        With defer=True the gather descriptors are returned instead, for a larger batch."""
-        c, k = self.ctx, idx.shape[1]
+        With defer=True the gather descriptors are returned instead, for a larger batch.  With k_group
+        (int32[1] on the device, the kept count of the cumulative-threshold rule) only the first k_group[0]
+        entries of idx[1, n] count (read back once here to size the compact matrices)."""
+        c = self.ctx
+        k = idx.shape[1] if k_group is None else int(k_group.item())
         self.idx, self.k = idx, k
         self.kp = kp = B.round_up(k, 16)
         nh = 2 * kp if self.gated else kp
@@ -41,13 +44,16 @@ class FfnBlock:
             self.w1_c = torch.empty((nh, self.d), dtype=dt, device=dev)
             self.b1_c = None if self.b1 is None else torch.zeros((nh,), dtype=dt, device=dev)
             self.w2_c = torch.empty((self.d, kp), dtype=dt, device=dev)
-        mk = B.Context.map_item
-        items = [mk(self.w1, self.w1_c[:kp], idx, 0, 1, self.n, 1, kp)]
+
+        def mk(src, dst, axis):
+            return B.Context.map_item(src, dst, idx, axis, 1, self.n, 1, kp, k_group=k_group)
+
+        items = [mk(self.w1, self.w1_c[:kp], 0)]
         if self.gated:
-            items.append(mk(self.w1b, self.w1_c[kp:], idx, 0, 1, self.n, 1, kp))
+            items.append(mk(self.w1b, self.w1_c[kp:], 0))
         if self.b1 is not None:       # the up branch of a gated FFN has no bias: its slots stay zero
-            items.append(mk(self.b1, self.b1_c[:kp], idx, 1, 1, self.n, 1, kp))
-        items.append(mk(self.w2, self.w2_c, idx, 1, 1, self.n, 1, kp))
+            items.append(mk(self.b1, self.b1_c[:kp], 1))
+        items.append(mk(self.w2, self.w2_c, 1))
         if defer:
             return items
         c.ecospa_compact_batch(items)
@@ -108,10 +114,16 @@ class AttnBlock:
     def score(self):
         return self.ctx.ecospa_coupled_score(self.pairs())
 
-    def compact(self, idx_qk: torch.Tensor, idx_vo: torch.Tensor, defer: bool = False):
+    def compact(self, idx_qk: torch.Tensor, idx_vo: torch.Tensor, defer: bool = False,
+                k_qk_group: Optional[torch.Tensor] = None, k_vo_group: Optional[torch.Tensor] = None):
+        """Gather the kept dimensions.  With k_qk_group / k_vo_group (int32[h] on the device, the kept counts of the
+        cumulative-threshold rule) every head keeps a count of its own: idx_* are then [h, n_units] lists whose first
+        k_*_group[g] entries count, and all heads are padded with zeros to the largest count (read back once here)."""
         c, h, dh, u = self.ctx, self.h, self.d_h, self.unit
         self.idx_qk, self.idx_vo = idx_qk, idx_vo
-        self.k_qk_units, self.k_vo = idx_qk.shape[1], idx_vo.shape[1]
+        self.k_qk_group, self.k_vo_group = k_qk_group, k_vo_group
+        self.k_qk_units = idx_qk.shape[1] if k_qk_group is None else int(k_qk_group.max().item())
+        self.k_vo = idx_vo.shape[1] if k_vo_group is None else int(k_vo_group.max().item())
         self.kp_qk = B.round_up(self.k_qk_units * u, 16)
         self.kp_vo = B.round_up(self.k_vo, 16)
         kpu = self.kp_qk // u
@@ -121,21 +133,30 @@ class AttnBlock:
             self.wqkv_c = torch.empty((2 * nq + nv, self.d), dtype=dt, device=dev)
             self.bqkv_c = None if self.bq is None else torch.empty((2 * nq + nv,), dtype=dt, device=dev)
             self.wo_c = torch.empty((self.d, nv), dtype=dt, device=dev)
-        mk = B.Context.map_item
-        items = [mk(self.wq, self.wqkv_c[:nq], idx_qk, 0, h, dh, u, kpu),
-                 mk(self.wk, self.wqkv_c[nq:2 * nq], idx_qk, 0, h, dh, u, kpu),
-                 mk(self.wv, self.wqkv_c[2 * nq:], idx_vo, 0, h, dh, 1, self.kp_vo)]
+
+        def mq(src, dst, axis):
+            return B.Context.map_item(src, dst, idx_qk, axis, h, dh, u, kpu, k_group=k_qk_group)
+
+        def mv(src, dst, axis):
+            return B.Context.map_item(src, dst, idx_vo, axis, h, dh, 1, self.kp_vo, k_group=k_vo_group)
+
+        items = [mq(self.wq, self.wqkv_c[:nq], 0), mq(self.wk, self.wqkv_c[nq:2 * nq], 0), mv(self.wv, self.wqkv_c[2 * nq:], 0)]
         if self.bq is not None:
-            items += [mk(self.bq, self.bqkv_c[:nq], idx_qk, 1, h, dh, u, kpu),
-                      mk(self.bk, self.bqkv_c[nq:2 * nq], idx_qk, 1, h, dh, u, kpu),
-                      mk(self.bv, self.bqkv_c[2 * nq:], idx_vo, 1, h, dh, 1, self.kp_vo)]
-        items.append(mk(self.wo, self.wo_c, idx_vo, 1, h, dh, 1, self.kp_vo))
+            items += [mq(self.bq, self.bqkv_c[:nq], 1), mq(self.bk, self.bqkv_c[nq:2 * nq], 1),
+                      mv(self.bv, self.bqkv_c[2 * nq:], 1)]
+        items.append(mv(self.wo, self.wo_c, 1))
         if not defer:
             c.ecospa_compact_batch(items)
         if self.rope and getattr(self, "cos", None) is not None:     # kept blocks changed: new frequencies
-            c.ecospa_rope_table(idx_qk, h, self._L, self.k_qk_units, self.kp_qk // 2, dh, self.rope_base,
-                                out=(self.cos, self.sin))
+            self._rope_table(self._L, out=(self.cos, self.sin))
         return items if defer else self
+
+    def _rope_table(self, L: int, out=None):
+        if self.k_qk_group is not None:
+            return self.ctx.ecospa_rope_table_ragged(self.idx_qk, self.k_qk_group, L, self.kp_qk // 2, self.d_h,
+                                                     self.rope_base, out=out)
+        return self.ctx.ecospa_rope_table(self.idx_qk, self.h, L, self.k_qk_units, self.kp_qk // 2, self.d_h,
+                                          self.rope_base, out=out)
 
     def alloc(self, Bsz: int, L: int):
         c, h = self.ctx, self.h
@@ -144,8 +165,7 @@ class AttnBlock:
         self.cos = self.sin = None
         self._L = L
         if self.rope:
-            self.cos, self.sin = c.ecospa_rope_table(self.idx_qk, h, L, self.k_qk_units, self.kp_qk // 2, self.d_h,
-                                                     self.rope_base)
+            self.cos, self.sin = self._rope_table(L)
         d = B.BlockDesc()
         d.block, d.dtype, d.B, d.L, d.d_model = B.BLOCK_ATTN, B.dtype_code(dt), Bsz, L, self.d
         d.h, d.kp_qk, d.kp_vo, d.causal = h, self.kp_qk, self.kp_vo, int(self.causal)

@@ -1,0 +1,192 @@
+"""GPU parity (through the C ABI) of Alg. 1's choice among pairs and of the path with a kept count per
+head: gather/scatter with ragged counts bit for bit against the oracle, and one pruning step of an attention
+block and an FFN block driven by the cumulative-threshold rule (score -> theta rule -> ragged gather ->
+forward/backward) against the oracle computing every head at its own width."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ecospa_oracle as O
+from paper_2511_11641_amd import binding as B
+from paper_2511_11641_amd import synth
+from paper_2511_11641_amd.layer import AttnBlock, FfnBlock
+from util import assert_close, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    return B.Context("cuda:0")
+
+
+# ---- choice among pairs ----------------------------------------------------------------------
+@pytest.mark.parametrize("n_pairs", [1, 3, 49, 777, 9000])
+def test_select_pairs_matches_oracle(ctx, n_pairs):
+    rng = np.random.default_rng(n_pairs)
+    f = (rng.random(n_pairs) ** 4).astype(np.float32) * np.float32(1e-3)
+    if n_pairs > 40:
+        f[rng.integers(0, n_pairs, n_pairs // 5)] = f[7]          # ties
+        f[11] = np.nan
+        f[13], f[5] = -0.0, 0.0
+    g = torch.from_numpy(f).cuda()
+    for m in sorted({1, max(1, n_pairs // 10), max(1, n_pairs // 2), n_pairs}):
+        got = ctx.ecospa_select_pairs(g, m).cpu().numpy()
+        assert np.array_equal(got, O.select_pairs(f, m)), f"n_pairs {n_pairs}, n_select {m}"
+
+
+def test_select_pairs_errors(ctx):
+    g = torch.zeros(8, device="cuda")
+    for m in (0, 9):
+        with pytest.raises(B.EcospaError) as e:
+            ctx.ecospa_select_pairs(g, m)
+        assert e.value.code == B.ERR_K
+
+
+# ---- ragged gather / scatter ---------------------------------------------------------------------
+def _ragged_idx(seed, groups, nu):
+    rng = np.random.default_rng(seed)
+    ks = rng.integers(0, nu + 1, groups).astype(np.int32)
+    ks[0], ks[-1] = nu, ks[-1] if groups > 1 else nu
+    idx = -np.ones((groups, nu), dtype=np.int32)
+    for g in range(groups):
+        idx[g, :ks[g]] = np.sort(rng.choice(nu, ks[g], replace=False))
+    return idx, ks
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("axis", [0, 1])
+@pytest.mark.parametrize("groups,n,unit,other,pad", [(16, 64, 1, 1024, 0), (32, 64, 2, 520, 0), (1, 1000, 1, 333, 8), (5, 12, 2, 7, 3),
+                                                    (3, 40, 1, 4100, 0)])
+def test_ragged_gather_and_scatter(ctx, dtype, axis, groups, n, unit, other, pad):
+    nu = n // unit
+    idx, ks = _ragged_idx(groups * 31 + n, groups, nu)
+    kp = nu + pad
+    w = synth.round_to(synth.normal(40, 1, (groups * n, other) if axis == 0 else (other, groups * n)), dtype)
+    gi, gk = torch.from_numpy(idx).cuda(), torch.from_numpy(ks).cuda()
+    c = ctx.ecospa_compact_ragged(dev(w, dtype), gi, gk, axis, groups, n, kp, unit)
+    want = O.compact_ragged(w, idx, ks, axis, n, kp, unit)
+    assert np.array_equal(host(c), want.astype(np.float64)), "ragged gather"
+    back = ctx.ecospa_compact_ragged(c, gi, gk, axis, groups, n, kp, unit, scatter=True)
+    assert np.array_equal(host(back), O.scatter_ragged(want, idx, ks, axis, n, kp, unit).astype(np.float64)), "ragged scatter"
+    # a destination narrower than a group's count keeps that group's first kp units (documented clamp)
+    kq = max(1, nu // 2)
+    c2 = ctx.ecospa_compact_ragged(dev(w, dtype), gi, gk, axis, groups, n, kq, unit)
+    assert np.array_equal(host(c2), O.compact_ragged(w, idx, np.minimum(ks, kq), axis, n, kq, unit).astype(np.float64))
+
+
+def test_ragged_vector_and_rope_table(ctx):
+    groups, n, L = 6, 32, 50
+    idx, ks = _ragged_idx(3, groups, n // 2)
+    gi, gk = torch.from_numpy(idx).cuda(), torch.from_numpy(ks).cuda()
+    b = synth.normal(41, 1, (groups * n,)).astype(np.float32)
+    c = ctx.ecospa_compact_ragged(torch.from_numpy(b).cuda(), gi, gk, 1, groups, n, n // 2, 2)
+    assert np.array_equal(c.cpu().numpy(), O.compact_ragged(b, idx, ks, 1, n, n // 2, 2))
+    cos, sin = ctx.ecospa_rope_table_ragged(gi, gk, L, n // 2, n)
+    for g in range(groups):
+        ang = O.rope_angles(idx[g:g + 1, :ks[g]], L, n)[0]
+        np.testing.assert_allclose(cos[g, :, :ks[g]].cpu().numpy(), np.cos(ang), atol=2e-6)
+        np.testing.assert_allclose(sin[g, :, :ks[g]].cpu().numpy(), np.sin(ang), atol=2e-6)
+        assert torch.all(cos[g, :, ks[g]:] == 1) and torch.all(sin[g, :, ks[g]:] == 0)
+
+
+def test_ragged_item_errors(ctx):
+    w = torch.zeros((64, 16), device="cuda")
+    idx = torch.zeros((2, 32), dtype=torch.int32, device="cuda")
+    kg = torch.ones((2,), dtype=torch.int32, device="cuda")
+    with pytest.raises(B.EcospaError) as e:
+        ctx.ecospa_compact_ragged(w, idx, kg, 0, 2, 32, 0, out=torch.zeros((64, 16), device="cuda"))
+    assert e.value.code == B.ERR_K
+
+
+# ---- one pruning step with the cumulative-threshold rule, then forward/backward at ragged widths ------------------
+@pytest.mark.parametrize("rope,theta", [(False, 0.9), (True, 0.8), (False, 0.6)])
+def test_attention_block_with_a_kept_count_per_head(ctx, rope, theta):
+    Bsz, L, d, h, dh, dtype = 2, 200, 256, 8, 64, "bf16"
+    t = synth.attn_layer(50, Bsz, L, d, h, dh, dtype=dtype, structure="pretrained", bias=not rope)
+    unit = 2 if rope else 1
+    g = {nm: dev(a, dtype) for nm, a in t.items()}
+    blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g.get("bq"), g.get("bk"), g.get("bv"), g.get("bo"),
+                    h, dh, rope=rope, causal=True)
+    s_qk, s_vo = blk.score()
+    iq_d, kq_d = ctx.ecospa_select_theta(s_qk, theta)
+    iv_d, kv_d = ctx.ecospa_select_theta(s_vo, theta)
+    # the rule on the GPU's own scores, bit for bit
+    iq, kq = O.select_theta(s_qk.cpu().numpy(), theta)
+    iv, kv = O.select_theta(s_vo.cpu().numpy(), theta)
+    assert np.array_equal(kq_d.cpu().numpy(), kq) and np.array_equal(iq_d.cpu().numpy(), iq)
+    assert np.array_equal(kv_d.cpu().numpy(), kv) and np.array_equal(iv_d.cpu().numpy(), iv)
+    assert kq.min() < kq.max() and kv.min() < kv.max(), "the case must be ragged"
+    blk.compact(iq_d, iv_d, k_qk_group=kq_d, k_vo_group=kv_d).alloc(Bsz, L)
+    assert blk.kp_qk >= kq.max() * unit and blk.kp_vo >= kv.max()
+    y = blk.fwd(g["x"])
+    dx = blk.bwd(g["x"], g["dy"])
+    torch.cuda.synchronize()
+
+    # oracle: every head at its own width, one head at a time (Eq. 4 is a sum over heads)
+    scale = dh ** -0.5
+    kpq, kpv, nq = blk.kp_qk, blk.kp_vo, h * blk.kp_qk
+    yo = np.zeros((Bsz * L, d))
+    dxo = np.zeros((Bsz * L, d))
+    want_dw = np.zeros((2 * nq + h * kpv, d))
+    want_dwo = np.zeros((d, h * kpv))
+    for i in range(h):
+        rq, rv = iq[i:i + 1, :kq[i]], iv[i:i + 1, :kv[i]]
+        sl = slice(i * dh, (i + 1) * dh)
+        wq, wk = (O.compact(t[nm][sl], rq, 0, dh, unit)[None] for nm in ("wq", "wk"))
+        wv, wo = O.compact(t["wv"][sl], rv, 0, dh)[None], O.compact(t["wo"][:, sl], rv, 1, dh)[None]
+        kw = {}
+        if not rope:
+            kw = dict(bq=O.compact(t["bq"][sl], rq, 0, dh, unit)[None], bk=O.compact(t["bk"][sl], rq, 0, dh, unit)[None],
+                      bv=O.compact(t["bv"][sl], rv, 0, dh)[None])
+        ang = O.rope_angles(rq, L, dh) if rope else None
+        yi, sv = O.attn_fwd(t["x"], wq, wk, wv, wo, Bsz, L, scale, True, angles=ang, **kw)
+        gi = O.attn_bwd(t["x"], t["dy"], wq, wk, wv, wo, Bsz, L, scale, sv, angles=ang)
+        yo += yi
+        dxo += gi["dx"]
+        want_dw[i * kpq:i * kpq + kq[i] * unit] = gi["dwq"][0]
+        want_dw[nq + i * kpq:nq + i * kpq + kq[i] * unit] = gi["dwk"][0]
+        want_dw[2 * nq + i * kpv:2 * nq + i * kpv + kv[i]] = gi["dwv"][0]
+        want_dwo[:, i * kpv:i * kpv + kv[i]] = gi["dwo"][0]
+    if not rope:
+        yo += t["bo"]
+    assert_close(y, yo, dtype, "y")
+    assert_close(dx, dxo, dtype, "dx")
+    assert_close(blk.dwqkv_c, want_dw, dtype, "dW_qkv")
+    assert_close(blk.dwo_c, want_dwo, dtype, "dW_o")
+    # padding slots never train: their gradients are exactly zero
+    dw = host(blk.dwqkv_c)
+    for i in range(h):
+        assert not dw[i * kpq + kq[i] * unit:(i + 1) * kpq].any() and not dw[2 * nq + i * kpv + kv[i]:2 * nq + (i + 1) * kpv].any()
+    # gradients back in the full layout: pruned rows zero, kept rows in place
+    full = ctx.ecospa_compact_ragged(blk.dwqkv_c[:nq], iq_d, kq_d, 0, h, dh, kpq // unit, unit, scatter=True)
+    assert np.array_equal(host(full), O.scatter_ragged(dw[:nq], iq, kq, 0, dh, kpq // unit, unit))
+
+
+@pytest.mark.parametrize("gated", [False, True])
+def test_ffn_block_with_the_threshold_rule(ctx, gated):
+    T, d, n, dtype, theta = 300, 256, 1500, "bf16", 0.85
+    t = synth.ffn_layer(51, T, d, n, gated=gated, dtype=dtype, structure="pretrained", bias=not gated)
+    g = {nm: dev(a, dtype) for nm, a in t.items()}
+    act = B.ACT_SWIGLU if gated else B.ACT_GELU_ERF
+    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), act, g.get("w1b"))
+    s = blk.score()
+    idx_d, k_d = ctx.ecospa_select_theta(s, theta)
+    idx, k = O.select_theta(s.cpu().numpy(), theta)
+    assert np.array_equal(k_d.cpu().numpy(), k) and np.array_equal(idx_d.cpu().numpy(), idx)
+    assert 1 < k[0] < n
+    blk.compact(idx_d, k_group=k_d).alloc(1, T)
+    y = blk.fwd(g["x"])
+    dx = blk.bwd(g["x"], g["dy"])
+    torch.cuda.synchronize()
+    sel = idx[:, :k[0]]
+    w1, w2 = O.compact(t["w1"], sel, 0, n), O.compact(t["w2"], sel, 1, n)
+    w1b = O.compact(t["w1b"], sel, 0, n) if gated else None
+    b1 = O.compact(t["b1"], sel, 0, n) if not gated else None
+    oact = O.ACT_SWIGLU if gated else O.ACT_GELU_ERF
+    yo, sv = O.ffn_fwd(t["x"], w1, b1, w2, t.get("b2"), oact, w1b)
+    go = O.ffn_bwd(t["x"], t["dy"], w1, w2, oact, sv, w1b)
+    assert_close(y, yo, dtype, "y")
+    assert_close(dx, go["dx"], dtype, "dx")
+    assert_close(blk.dw2_c[:, :k[0]], go["dw2"], dtype, "dW_2")
+    assert not host(blk.dw2_c[:, k[0]:]).any()
