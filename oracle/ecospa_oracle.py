@@ -20,7 +20,7 @@ Conventions
 Every function states the passage of the paper it follows.  Parity status: every function
 here is pinned by tests that do not go through this file's own formulas (library SVD,
 autograd of independently written dense layers, finite differences, brute force over
-subsets, Proposition 1 and the printed values of Table 7).
+subsets, Proposition 1, the printed values of Table 7, and a library optimizer for the update).
 """
 from __future__ import annotations
 
@@ -433,6 +433,28 @@ def attn_bwd(x, dy, wq, wk, wv, wo, B: int, L: int, scale: float, saved, angles=
             g["dbv"][i] += dv.sum(axis=0)
             g["dx"][sl] += dq @ wq[i] + dk @ wk[i] + dv @ wv[i]
     return g
+
+
+# --------------------------------------------------------------------------------------
+# Parameter update on the compact tensors (Alg. 1 "Update W"; AdamW is the optimizer of the GPT-2 and
+# DeiT runs of Sec. 4.1, and Alg. 1 removes the moments of removed rows/columns with them)
+# --------------------------------------------------------------------------------------
+def adamw_step(w, g, m, v, t: int, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+               weight_decay: float = 0.01):
+    """One AdamW update (Adam with decoupled weight decay, Loshchilov & Hutter) of step number t >= 1.
+
+    m' = beta1 m + (1 - beta1) g,  v' = beta2 v + (1 - beta2) g^2,
+    w' = w - lr * ( (m' / (1 - beta1^t)) / (sqrt(v' / (1 - beta2^t)) + eps) + weight_decay * w ).
+    Returns (w', m', v') in fp64.  Elementwise, so it acts on compact tensors exactly as on the kept
+    entries of full ones.
+    """
+    w, g, m, v = map(_f64, (w, g, m, v))
+    m1 = beta1 * m + (1.0 - beta1) * g
+    v1 = beta2 * v + (1.0 - beta2) * g * g
+    mhat = m1 / (1.0 - beta1 ** t)
+    vhat = v1 / (1.0 - beta2 ** t)
+    w1 = w - lr * (mhat / (np.sqrt(vhat) + eps) + weight_decay * w)
+    return w1, m1, v1
 
 
 # --------------------------------------------------------------------------------------
