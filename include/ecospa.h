@@ -189,6 +189,39 @@ typedef struct {
 } ecospa_map_item;
 int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* items /*host*/, int n_items);
 
+/* ------------------------------------------------------------------------------------------
+ * Parameter update on the compact tensors (Alg. 1: "Update W", and the optimizer moments of a removed
+ * row/column are removed with it - after ecospa_compact of the parameters, their master copies and both
+ * moments with the same idx, all of them live in the compact layout).  AdamW, the optimizer of the
+ * paper's GPT-2 and DeiT runs (Sec. 4.1), for step number `step` >= 1, elementwise:
+ *   m <- beta1 m + (1 - beta1) g,   v <- beta2 v + (1 - beta2) g^2,
+ *   w <- w - lr * ( (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps) + weight_decay * w )
+ * in fp32 arithmetic, each result rounded once (to nearest even) to the type it is stored in.
+ * Per tensor: w (device, n elements, updated in place; fp32 master weights or bf16 parameters), g
+ * (gradient, read only), m and v (moments, updated in place, both of type s_dtype), and optionally
+ * w_lp: a bf16 copy of the updated fp32 w, the working weights the contractions read (NULL: none; only
+ * with w_dtype = ECOSPA_F32).  Tensors are contiguous and must not overlap; padding slots (w = g = m =
+ * v = 0) stay exactly zero.  `items` and `hp` are host memory; all items are validated before anything
+ * is launched, all tensors are updated by one launch (per 192 items).  Needs no workspace.
+ * Errors: ERR_NULL; ERR_DTYPE (a type that is neither fp32 nor bf16; w_lp with bf16 w); ERR_SHAPE
+ * (n < 1, n_items < 1, step < 1, beta outside [0, 1), negative lr / eps / weight_decay or NaN).
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  void* w;
+  void* w_lp;      /* bf16[n] or NULL */
+  const void* g;
+  void* m;
+  void* v;
+  long long n;
+  int w_dtype, g_dtype, s_dtype;
+} ecospa_adamw_item;
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay;
+  int step;
+} ecospa_adamw_hyper;
+int ecospa_adamw(ecospa_ctx* ctx, const ecospa_adamw_item* items /*host*/, int n_items,
+                 const ecospa_adamw_hyper* hp /*host*/);
+
 /* cos/sin tables of the KEPT rotary blocks (Eq. 6; "position matrices are then adjusted to match
  * new dimensions", footnote to Eq. 10): for head g, position t < L, kept block i < k,
  *   angle = t * base^(-2 * idx[g*k+i] / d_h)   with d_h the ORIGINAL head width,

@@ -27,7 +27,7 @@ EXPORTS = (
     "ecospa_scatter", "ecospa_rope_table", "ecospa_block_workspace_bytes", "ecospa_coupled_fwd",
     "ecospa_coupled_bwd", "ecospa_profile_gemm", "ecospa_profile_gemm_read", "ecospa_contract",
     "ecospa_select_topk_batch", "ecospa_compact_batch", "ecospa_pair_fisher", "ecospa_select_theta",
-    "ecospa_select_pairs", "ecospa_rope_table_ragged",
+    "ecospa_select_pairs", "ecospa_rope_table_ragged", "ecospa_adamw",
 )
 
 
@@ -64,6 +64,16 @@ class MapItem(C.Structure):
                 ("n", C.c_int), ("unit", C.c_int), ("k", C.c_int), ("kp", C.c_int), ("scatter", C.c_int),
                 ("other_extent", C.c_longlong), ("ld_src", C.c_longlong), ("ld_dst", C.c_longlong),
                 ("idx", C.c_void_p), ("k_group", C.c_void_p), ("ld_idx", C.c_int)]
+
+
+class AdamwItem(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("w_lp", C.c_void_p), ("g", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
+                ("n", C.c_longlong), ("w_dtype", C.c_int), ("g_dtype", C.c_int), ("s_dtype", C.c_int)]
+
+
+class AdamwHyper(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("step", C.c_int)]
 
 
 class Saved(C.Structure):
@@ -123,6 +133,8 @@ def load() -> C.CDLL:
     lib.ecospa_rope_table.restype = ci
     lib.ecospa_rope_table_ragged.argtypes = [vp, vp, ci, vp, ci, ci, ci, ci, C.c_double, vp, vp]
     lib.ecospa_rope_table_ragged.restype = ci
+    lib.ecospa_adamw.argtypes = [vp, C.POINTER(AdamwItem), ci, C.POINTER(AdamwHyper)]
+    lib.ecospa_adamw.restype = ci
     lib.ecospa_block_workspace_bytes.argtypes = [C.POINTER(BlockDesc)]
     lib.ecospa_block_workspace_bytes.restype = sz
     lib.ecospa_coupled_fwd.argtypes = [vp, C.POINTER(BlockDesc), vp, vp, C.POINTER(Saved)]
@@ -381,6 +393,24 @@ class Context:
                                                       d_h, float(base), cos.data_ptr(), sin.data_ptr()),
                     "ecospa_rope_table_ragged")
         return cos, sin
+
+    # ---- parameter update ----------------------------------------------------------------------
+    @staticmethod
+    def adamw_item(w: torch.Tensor, g: torch.Tensor, m: torch.Tensor, v: torch.Tensor,
+                   w_lp: Optional[torch.Tensor] = None) -> AdamwItem:
+        """Descriptor of one tensor for :meth:`ecospa_adamw` (all contiguous, same element count)."""
+        n = w.numel()
+        assert all(t.is_contiguous() and t.numel() == n for t in (w, g, m, v)) and m.dtype == v.dtype
+        assert w_lp is None or (w_lp.is_contiguous() and w_lp.numel() == n and w_lp.dtype == torch.bfloat16)
+        return AdamwItem(w.data_ptr(), _ptr(w_lp), g.data_ptr(), m.data_ptr(), v.data_ptr(), n, dtype_code(w.dtype),
+                         dtype_code(g.dtype), dtype_code(m.dtype))
+
+    def ecospa_adamw(self, items: Sequence[AdamwItem], step: int, lr: float, beta1: float = 0.9, beta2: float = 0.999,
+                     eps: float = 1e-8, weight_decay: float = 0.01):
+        """One fused AdamW step over all tensors in `items` (one launch)."""
+        arr = items if isinstance(items, C.Array) else (AdamwItem * len(items))(*items)
+        hp = AdamwHyper(lr, beta1, beta2, eps, weight_decay, step)
+        self._check(self.lib.ecospa_adamw(self.h, arr, len(arr), C.byref(hp)), "ecospa_adamw")
 
     # ---- steps 4-5 ---------------------------------------------------------------------------
     def ecospa_coupled_fwd(self, desc: BlockDesc, x: torch.Tensor, y: torch.Tensor, saved: Optional[Saved]):
