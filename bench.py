@@ -182,6 +182,19 @@ def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps):
     t_fisher = timed_gpu(torch, lambda: ctx.ecospa_pair_fisher(pair_arr, 8192.0, out=fisher), steps, 3)
     ffn_scores = torch.cat([scores[3 * li + 2] for li in range(n_layers)]).contiguous()
     t_theta = timed_gpu(torch, lambda: ctx.ecospa_select_theta(ffn_scores, 0.9), steps, 3)
+    # Alg. 1's update on the compact tensors of the whole stack: fp32 master weights and moments, bf16 gradients,
+    # bf16 working copies written back - one launch for all tensors
+    opt_items, opt_keep, n_par = [], [], 0
+    for a, f in layers:
+        for w_c in (a.wqkv_c, a.wo_c, f.w1_c, f.w2_c):
+            st = [w_c.float(), torch.zeros(w_c.shape, device="cuda"), torch.zeros(w_c.shape, device="cuda"),
+                  (torch.randn(w_c.shape, device="cuda") * 1e-3).to(torch.bfloat16)]
+            opt_keep.append(st)
+            opt_items.append(ctx.adamw_item(st[0], st[3], st[1], st[2], w_c))
+            n_par += w_c.numel()
+    opt_arr = (B.AdamwItem * len(opt_items))(*opt_items)
+    t_adamw = timed_gpu(torch, lambda: ctx.ecospa_adamw(opt_arr, 10, 1e-3), steps, 3)
+    adamw_bytes = n_par * (2 + 3 * 4 + 3 * 4 + 2)
     w_bytes = n_layers * 2 * (4 * d * d + 2 * d * dff)
     keep = keep_num / keep_den
     cols = n_layers * 2 * (d * d + d * dff)                 # the members gathered by column: W_o, W_2
@@ -196,6 +209,9 @@ def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps):
             "pair_fisher": {"us": t_fisher * 1e3, "gbs": w_bytes / t_fisher / 1e6,
                             "frac_of_hbm_peak": w_bytes / t_fisher / 1e6 / HBM_PEAK_GBS},
             "select_theta": {"us": t_theta * 1e3, "rows": n_layers, "units": dff, "theta": 0.9},
+            "adamw": {"us": t_adamw * 1e3, "params_M": n_par / 1e6, "bytes_per_param": 28, "gbs": adamw_bytes / t_adamw / 1e6,
+                      "frac_of_hbm_peak": adamw_bytes / t_adamw / 1e6 / HBM_PEAK_GBS,
+                      "note": "compact tensors of the stack: bf16 gradient, fp32 master + both moments read and written, bf16 working copy written"},
             "timing": "device-side events, descriptors prebuilt"}
 
 

@@ -11,7 +11,7 @@
 #define ADAMW_MAX_ITEMS 192       // descriptors travel as kernel arguments
 #define ADAMW_THREADS 256
 #define ADAMW_VEC 8               // elements per thread and pass
-#define ADAMW_PASSES 4            // passes per workgroup: ADAMW_THREADS * ADAMW_VEC * ADAMW_PASSES elements
+#define ADAMW_PASSES 2            // passes per workgroup: ADAMW_THREADS * ADAMW_VEC * ADAMW_PASSES elements
 #define ADAMW_CHUNK (ADAMW_THREADS * ADAMW_VEC * ADAMW_PASSES)
 
 struct AdamwItemDev {
@@ -28,8 +28,10 @@ struct AdamwItemDev {
 struct AdamwBatch {
   int n_items;
   float lr, beta1, beta2, omb1, omb2, eps, wd, inv_bc1, inv_bc2;
+  int first_blk[ADAMW_MAX_ITEMS];   // blk_begin of every item, side by side: the search for a block's item stays in a few cache lines
   AdamwItemDev it[ADAMW_MAX_ITEMS];
 };
+static_assert(sizeof(AdamwBatch) <= 16384, "kernel arguments of one launch");
 
 template <typename T> __device__ __forceinline__ void load8(const T* p, float (&x)[ADAMW_VEC]);
 template <> __device__ __forceinline__ void load8<float>(const float* p, float (&x)[ADAMW_VEC]) {
@@ -74,7 +76,7 @@ __device__ __forceinline__ void adamw_slice(const AdamwBatch& b, const AdamwItem
   bf16_t* __restrict__ lp = t.w_lp;
   const long long e1 = e0 + ADAMW_CHUNK < t.n ? e0 + ADAMW_CHUNK : t.n;
   if (t.vec && e1 - e0 == ADAMW_CHUNK) {
-    // all loads of the slice first (4 passes x 4 streams in flight per thread), then the arithmetic and the stores
+    // all loads of the slice first (2 passes x 4 streams in flight per thread), then the arithmetic and the stores
     float xg[ADAMW_PASSES][ADAMW_VEC], xw[ADAMW_PASSES][ADAMW_VEC], xm[ADAMW_PASSES][ADAMW_VEC], xv[ADAMW_PASSES][ADAMW_VEC];
 #pragma unroll
     for (int p = 0; p < ADAMW_PASSES; ++p) {
@@ -111,7 +113,7 @@ __global__ __launch_bounds__(ADAMW_THREADS) void adamw_kernel(const AdamwBatch b
   int i = 0, hi = b.n_items - 1;          // last item whose first block is <= blk
   while (i < hi) {
     const int mid = (i + hi + 1) >> 1;
-    if (b.it[mid].blk_begin <= blk) i = mid; else hi = mid - 1;
+    if (b.first_blk[mid] <= blk) i = mid; else hi = mid - 1;
   }
   const AdamwItemDev& t = b.it[i];
   const long long e0 = static_cast<long long>(blk - t.blk_begin) * ADAMW_CHUNK;
@@ -164,6 +166,7 @@ extern "C" int ecospa_adamw(ecospa_ctx* ctx, const ecospa_adamw_item* items, int
       t.w_bf16 = q.w_dtype == ECOSPA_BF16; t.g_bf16 = q.g_dtype == ECOSPA_BF16; t.s_bf16 = q.s_dtype == ECOSPA_BF16;
       t.vec = aligned16(q.w) && aligned16(q.g) && aligned16(q.m) && aligned16(q.v) && (!q.w_lp || aligned16(q.w_lp));
       t.blk_begin = static_cast<int>(blk);
+      b.first_blk[i] = t.blk_begin;
       blk += (q.n + ADAMW_CHUNK - 1) / ADAMW_CHUNK;
       if (blk > (1ll << 30)) return ECOSPA_ERR_SHAPE;
     }

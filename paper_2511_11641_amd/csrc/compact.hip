@@ -51,7 +51,7 @@ __device__ __forceinline__ long long map_slot(const MapArgs& m, long long s) {
 }
 
 // One mapped copy of a batch; all items of a batch share one launch (block ranges in `blk_begin`).
-#define MAP_MAX_ITEMS 128    // descriptors travel as kernel arguments (about 14 KB)
+#define MAP_MAX_ITEMS 120    // descriptors travel as kernel arguments (about 15.5 KB)
 #define MAP_COL_ROWS 4      // rows a column-copy thread keeps in flight
 struct MapItemDev {
   const void* src;
@@ -68,8 +68,10 @@ struct MapItemDev {
 };
 struct MapBatch {
   int n_items;
+  int first_blk[MAP_MAX_ITEMS];   // blk_begin of every item, side by side: the search for a block's item stays in a few cache lines
   MapItemDev it[MAP_MAX_ITEMS];
 };
+static_assert(sizeof(MapBatch) <= 16384, "kernel arguments of one launch");
 
 // ---- axis 0: one wavefront per destination row ------------------------------------------------
 template <typename E>
@@ -229,7 +231,7 @@ __global__ __launch_bounds__(256) void map_batch_kernel(const MapBatch b) {
   int i = 0, hi = b.n_items - 1;          // last item whose first block is <= blk
   while (i < hi) {
     const int mid = (i + hi + 1) >> 1;
-    if (b.it[mid].blk_begin <= blk) i = mid; else hi = mid - 1;
+    if (b.first_blk[mid] <= blk) i = mid; else hi = mid - 1;
   }
   const MapItemDev& t = b.it[i];
   const int local = blk - t.blk_begin;
@@ -296,6 +298,7 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
       t.axis = q.axis;
       const int V = 16 / t.esize;
       t.blk_begin = static_cast<int>(blk);
+      b.first_blk[i] = t.blk_begin;
       if (q.axis == 0) {
         t.vec = aligned16(q.src) && aligned16(q.dst) && q.ld_src % V == 0 && q.ld_dst % V == 0;
         blk += (t.dst_slots + 3) / 4;

@@ -1,21 +1,22 @@
 // Step 1: per-dimension coupled importance score (paper Eq. 10, criterion of Eq. 12).
 //
 // HBM-bound: every weight element of every pair in the batch is read exactly once with
-// 16-byte loads.
-//   1. score_sumsq_kernel  - one launch per SCORE_MAX_PAIRS pairs: squared row norms (a wavefront
-//                            takes four rows at a time, all their loads in flight, then lane-
-//                            permutation sums) and squared column norms of the [d, n] member (one
-//                            workgroup per strip of one 128-byte line = 8 lanes x 16 bytes, over
-//                            all d rows, eight loads in flight per lane)
-//   2. score_finish_kernel - one launch per SCORE_FIN_MAX_PAIRS pairs, one workgroup per (pair,
-//                            group): r = |a||b|, group L2 norm, normalised scores
+// 16-byte loads, by one launch per SCORE_MAX_PAIRS pairs:
+//   * squared row norms: a wavefront takes four rows at a time, all their loads in flight, then
+//     lane-permutation sums;
+//   * squared column norms of the [d, n] member: a workgroup takes a strip of one 128-byte line
+//     (8 lanes x 16 bytes) over a range of rows, eight loads in flight per lane, and writes one
+//     partial sum per column and row range;
+// and a short finishing launch (score_finish_kernel) that adds the partial sums in order and writes the
+// scores: r = |a||b|, group L2 norm, normalised scores (or the weighted sums of Eq. 8).
 // No floating-point atomics; all reduction orders are fixed.
 #include "common.h"
 
-#define SCORE_MAX_PAIRS 96         // descriptors travel as kernel arguments (about 10 KB)
+#define SCORE_MAX_PAIRS 96         // descriptors travel as kernel arguments (about 15 KB)
+#ifndef SCORE_ROWS_PER_BLOCK
 #define SCORE_ROWS_PER_BLOCK 16   // row-norm blocks: 4 waves x 4 rows
-#define SCORE_COL_LANES 8         // column-norm blocks: 8 lanes (128 bytes of columns) x 32 row slots
-#define SCORE_COL_SLOTS (256 / SCORE_COL_LANES)
+#endif
+#define SCORE_COL_LDS (256 * 8 + 32)   // floats: slots x (strip width + 1) for every split of 256 threads into lanes x slots
 
 struct ScorePairDev {
   const void* w1;
@@ -29,12 +30,21 @@ struct ScorePairDev {
   int d1, d2;
   int kind, dtype;
   int fisher;      // 1: squared gradient sums for Eq. 8 (w1 and w1b are added, not multiplied)
-  int blk_row1, blk_row2, blk_col, blk_end;   // first block index of each phase in launch 1
+  int col_lanes;   // column norms: lanes (16 bytes each) side by side on a row; 256 / col_lanes row slots per workgroup
+  int col_strips;  //               strips of col_lanes * 16 bytes that cover the columns
+  int col_parts;   //               row ranges; part q writes its partial sums to b_sq + q * rows
+  int blk_row1, blk_row2, blk_col, blk_end;   // first block index of each phase of this pair
+  // finishing launch
+  int fin_blocks;       // workgroups of this pair in the finishing launch
+  float* scores;       // Eq. 10: [groups, n / unit]; Eq. 8: [groups]
+  float fw1, fw2;      // Eq. 8: weights 1 / (2 |W_k| |D|) of the two members' squared sums
 };
 struct ScoreBatch {
   int n_pairs;
+  int first_blk[SCORE_MAX_PAIRS];   // blk_row1 of every pair, side by side: the search for a block's pair stays in a few cache lines
   ScorePairDev p[SCORE_MAX_PAIRS];
 };
+static_assert(sizeof(ScoreBatch) <= 16384, "kernel arguments of one launch");
 
 template <typename T> struct Vec16;
 template <> struct Vec16<float> { static constexpr int N = 4; };
@@ -109,6 +119,87 @@ __device__ __forceinline__ void rows_sumsq(const T* r, const T* rb, long long ld
   for (int j = 0; j < NR; ++j) out[j] = j < rows_valid ? wave_sum(acc[j]) : 0.f;
 }
 
+// ---- finishing step of a pair --------------------------------------------------------------------
+// r of unit u of group g: |a| |b| over the unit's UR rows (Eq. 10), or the weighted squared sums (Eq. 8).
+// The partial column sums of a row are added in order of their row ranges.  No load sits behind a branch
+// or in a loop of unknown length (an index out of range is clamped and its value dropped), so that the
+// loads of all units a thread holds can be in flight together.
+#define SCORE_MAX_PARTS 4
+template <int UR>
+__device__ __forceinline__ float pair_unit_value(const ScorePairDev& p, int g, int u, int unit_rows) {
+  float a = 0.f, b = 0.f;
+  if (UR > 0) {
+#pragma unroll
+    for (int j = 0; j < UR; ++j) {
+      const int row = g * p.n + u * UR + j;
+      a += p.a_sq[row];
+#pragma unroll
+      for (int q = 0; q < SCORE_MAX_PARTS; ++q) {
+        const float v = p.b_sq[static_cast<long long>(q < p.col_parts ? q : 0) * p.rows + row];
+        b += q < p.col_parts ? v : 0.f;
+      }
+    }
+  } else {
+    for (int j = 0; j < unit_rows; ++j) {
+      const int row = g * p.n + u * unit_rows + j;
+      a += p.a_sq[row];
+      for (int q = 0; q < p.col_parts; ++q) b += p.b_sq[static_cast<long long>(q) * p.rows + row];
+    }
+  }
+  return p.fisher ? p.fw1 * a + p.fw2 * b : sqrtf(a) * sqrtf(b);
+}
+
+// Finishing launch: scores of the groups of every pair from the finished squared sums.  A pair with
+// SCORE_FIN_WAVES groups or more (attention heads) gives every wavefront a group of its own and needs no
+// workgroup barriers; otherwise (the FFN pair) a whole workgroup works on one group.  A thread keeps up to
+// SCORE_FIN_KEEP units in registers: their loads are all in flight together, and nothing is re-read.
+#define SCORE_FIN_THREADS 1024
+#define SCORE_FIN_WAVES (SCORE_FIN_THREADS / 64)
+#define SCORE_FIN_KEEP 8
+// One group by `stride` threads of which this is number `t`; `total(x)` adds x over those threads in a fixed order.
+template <int UR, int KEEP, typename Total>
+__device__ __forceinline__ void score_finish_group_k(const ScorePairDev& p, int g, int t, int stride, Total total) {
+  const int nu = p.fisher ? p.n : p.n / p.unit;      // Eq. 8 sums over single rows
+  const int unit_rows = p.fisher ? 1 : p.unit;
+  float* out = p.scores + static_cast<long long>(g) * nu;
+  float acc = 0.f;
+  if (nu <= KEEP * stride) {
+    float r[KEEP];
+#pragma unroll
+    for (int k = 0; k < KEEP; ++k) {
+      const int u = t + k * stride;
+      const float v = pair_unit_value<UR>(p, g, u < nu ? u : nu - 1, unit_rows);
+      r[k] = u < nu ? v : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < KEEP; ++k) acc += p.fisher ? r[k] : r[k] * r[k];
+    acc = total(acc);
+    if (p.fisher) {
+      if (t == 0) p.scores[g] = acc;
+      return;
+    }
+    const float nrm = sqrtf(acc);
+#pragma unroll
+    for (int k = 0; k < KEEP; ++k) {
+      const int u = t + k * stride;
+      if (u < nu) out[u] = nrm > 0.f ? r[k] / nrm : 0.f;
+    }
+    return;
+  }
+  for (int u = t; u < nu; u += stride) {
+    const float r = pair_unit_value<UR>(p, g, u, unit_rows);
+    if (p.fisher) acc += r;
+    else { acc += r * r; out[u] = r; }
+  }
+  acc = total(acc);
+  if (p.fisher) {
+    if (t == 0) p.scores[g] = acc;
+    return;
+  }
+  const float nrm = sqrtf(acc);
+  for (int u = t; u < nu; u += stride) out[u] = nrm > 0.f ? out[u] / nrm : 0.f;   // re-read by the thread that wrote it
+}
+
 template <typename T>
 __device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
   constexpr int V = Vec16<T>::N;
@@ -137,25 +228,27 @@ __device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
     }
     return;
   }
-  // ---- squared column norms of w2 [d2, rows]: one strip of SCORE_COL_LANES x V columns, all rows ----
+  // ---- squared column norms of w2 [d2, rows]: one strip of col_lanes x V columns, one range of rows ----
   const int local = blk - p.blk_col;
-  constexpr int W = SCORE_COL_LANES * V;
-  if (local * W >= p.rows) return;                 // padding of the range (whole workgroup)
-  const int slot = tid / SCORE_COL_LANES, ln = tid % SCORE_COL_LANES;
+  const int L = p.col_lanes, S = 256 / L, W = L * V;
+  const int strip = local % p.col_strips, part = local / p.col_strips;   // neighbours in the grid: neighbours on the rows
+  const int slot = tid / L, ln = tid % L;
   const T* w = static_cast<const T*>(p.w2);
-  const int col0 = local * W + ln * V;
+  const int col0 = strip * W + ln * V;
+  const int per = (p.d2 + p.col_parts - 1) / p.col_parts;
+  const int r_begin = part * per, r_end = min(p.d2, r_begin + per);
   const bool vec_ok = (p.ld2 % V == 0) && ((reinterpret_cast<uintptr_t>(w) & 15u) == 0);
   float acc[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) acc[i] = 0.f;
   if (vec_ok && col0 + V <= p.rows) {
-    for (int r0 = slot; r0 < p.d2; r0 += 8 * SCORE_COL_SLOTS) {     // 8 independent loads in flight
+    for (int r0 = r_begin + slot; r0 < r_end; r0 += 8 * S) {     // 8 independent loads in flight
       float a[8][V];
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
-        const int r = r0 + q * SCORE_COL_SLOTS;
-        load_vec<T>(w + static_cast<long long>(r < p.d2 ? r : r0) * p.ld2 + col0, a[q]);
-        if (r >= p.d2) {
+        const int r = r0 + q * S;
+        load_vec<T>(w + static_cast<long long>(r < r_end ? r : r0) * p.ld2 + col0, a[q]);
+        if (r >= r_end) {
 #pragma unroll
           for (int i = 0; i < V; ++i) a[q][i] = 0.f;
         }
@@ -166,7 +259,7 @@ __device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
         for (int i = 0; i < V; ++i) acc[i] += a[q][i] * a[q][i];
     }
   } else {
-    for (int r = slot; r < p.d2; r += SCORE_COL_SLOTS) {
+    for (int r = r_begin + slot; r < r_end; r += S) {
 #pragma unroll
       for (int i = 0; i < V; ++i)
         if (col0 + i < p.rows) {
@@ -175,104 +268,70 @@ __device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
         }
     }
   }
-  // reduce the row slots in a fixed order: thread (column c, part q) adds slots q, q + PARTS, ...;
-  // then the PARTS partial sums of a column are added in order
+  // the row slots of a column are added in slot order by one thread
 #pragma unroll
   for (int i = 0; i < V; ++i) lds[slot * (W + 1) + ln * V + i] = acc[i];
   __syncthreads();
-  constexpr int PARTS = 256 / W;                    // threads per column
-  const int c = tid / PARTS, q = tid % PARTS;
-  float s = 0.f;
-  for (int k = q; k < SCORE_COL_SLOTS; k += PARTS) s += lds[k * (W + 1) + c];
-  __syncthreads();
-  lds[c * PARTS + q] = s;
-  __syncthreads();
-  if (tid < W) {
+  float* out = p.b_sq + static_cast<long long>(part) * p.rows;
+  for (int c = tid; c < W; c += 256) {
     float tot = 0.f;
-    for (int k = 0; k < PARTS; ++k) tot += lds[tid * PARTS + k];
-    const int col = local * W + tid;
-    if (col < p.rows) p.b_sq[col] = tot;
+    for (int k = 0; k < S; ++k) tot += lds[k * (W + 1) + c];
+    const int col = strip * W + c;
+    if (col < p.rows) out[col] = tot;
   }
 }
 
 __global__ __launch_bounds__(256) void score_sumsq_kernel(const ScoreBatch b) {
-  __shared__ float lds[SCORE_COL_SLOTS * (SCORE_COL_LANES * 8 + 1)];
+  __shared__ float lds[SCORE_COL_LDS];
   const int blk = blockIdx.x;
   int lo = 0, hi = b.n_pairs - 1;          // last pair whose first block is <= blk
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
-    if (b.p[mid].blk_row1 <= blk) lo = mid; else hi = mid - 1;
+    if (b.first_blk[mid] <= blk) lo = mid; else hi = mid - 1;
   }
   const ScorePairDev& p = b.p[lo];
   if (p.dtype == ECOSPA_BF16) score_block<bf16_t>(p, blk, lds);
   else score_block<float>(p, blk, lds);
 }
 
-// Finishing launch: one workgroup per (pair, group).  Every thread finishes its units (r = |a| |b|),
-// the group's L2 norm of r is reduced in a fixed order, and the normalised scores are written.  It
-// needs little per pair, so one launch serves up to SCORE_FIN_MAX_PAIRS pairs (several batches of the
-// first launch).
-#define SCORE_FIN_THREADS 1024
-#define SCORE_FIN_MAX_PAIRS 96
-struct ScoreFinPair {
-  const float* a_sq;
-  const float* b_sq;
-  float* scores;
-  int n, unit;
-  int fin_begin;
-  int fisher;          // 1: Eq. 8 instead of Eq. 10: scores[g] = w1 * sum(a_sq of group g) + w2 * sum(b_sq of group g)
-  float w1, w2;        //    with w_k = 1 / (2 |W_k| |D|)
-};
-struct ScoreFinBatch {
-  int n_pairs;
-  ScoreFinPair p[SCORE_FIN_MAX_PAIRS];
-};
-__global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_kernel(const ScoreFinBatch b) {
-  __shared__ float red[SCORE_FIN_THREADS / 64];
-  const int blk = blockIdx.x;
-  int lo = 0, hi = b.n_pairs - 1;          // last pair whose first workgroup is <= blk
-  while (lo < hi) {
-    const int mid = (lo + hi + 1) >> 1;
-    if (b.p[mid].fin_begin <= blk) lo = mid; else hi = mid - 1;
-  }
-  const ScoreFinPair& p = b.p[lo];
-  const int g = blk - p.fin_begin;
-  const int nu = p.n / p.unit;
-  const int tid = threadIdx.x;
-  if (p.fisher) {
-    float part = 0.f;
-    for (int j = tid; j < p.n; j += SCORE_FIN_THREADS) part += p.w1 * p.a_sq[g * p.n + j] + p.w2 * p.b_sq[g * p.n + j];
-    part = wave_sum(part);
-    if ((tid & 63) == 0) red[tid >> 6] = part;
-    __syncthreads();
-    if (tid == 0) {
-      float tot = 0.f;
-      for (int w = 0; w < SCORE_FIN_THREADS / 64; ++w) tot += red[w];
-      p.scores[g] = tot;
-    }
+// The number of units a thread holds follows the size of the group, so that small groups issue no idle loads.
+template <int UR, typename Total>
+__device__ __forceinline__ void score_finish_group(const ScorePairDev& p, int g, int t, int stride, Total total) {
+  const int nu = p.fisher ? p.n : p.n / p.unit;
+  if (nu <= stride) score_finish_group_k<UR, 1>(p, g, t, stride, total);
+  else if (nu <= 4 * stride) score_finish_group_k<UR, 4>(p, g, t, stride, total);
+  else score_finish_group_k<UR, SCORE_FIN_KEEP>(p, g, t, stride, total);
+}
+
+__global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_kernel(const ScoreBatch b) {
+  __shared__ float red[SCORE_FIN_WAVES];
+  // grid: (workgroups of the pair that needs most, pairs) - the pair is named directly, a search through the
+  // descriptors would cost a chain of dependent loads that is longer than the work itself
+  const ScorePairDev& p = b.p[blockIdx.y];
+  const int local = blockIdx.x, tid = threadIdx.x;
+  if (local >= p.fin_blocks) return;
+  const int ur = p.fisher ? 1 : p.unit;              // rows per unit: 1, 2 (rotary blocks), or anything (slow form)
+  if (p.groups >= SCORE_FIN_WAVES) {
+    const int g = local * SCORE_FIN_WAVES + (tid >> 6);
+    if (g >= p.groups) return;
+    auto total = [](float v) { return wave_sum(v); };
+    if (ur == 1) score_finish_group<1>(p, g, tid & 63, 64, total);
+    else if (ur == 2) score_finish_group<2>(p, g, tid & 63, 64, total);
+    else score_finish_group<0>(p, g, tid & 63, 64, total);
     return;
   }
-  float* out = p.scores + static_cast<long long>(g) * nu;
-  float sq = 0.f;
-  for (int u = tid; u < nu; u += SCORE_FIN_THREADS) {
-    float a = 0.f, bsum = 0.f;
-    for (int j = 0; j < p.unit; ++j) {
-      const int row = (g * nu + u) * p.unit + j;
-      a += p.a_sq[row];
-      bsum += p.b_sq[row];
-    }
-    const float r = sqrtf(a) * sqrtf(bsum);
-    out[u] = r;          // re-read below by the same thread
-    sq += r * r;
-  }
-  sq = wave_sum(sq);
-  if ((tid & 63) == 0) red[tid >> 6] = sq;
-  __syncthreads();
-  float tot = 0.f;
+  auto total = [&](float v) {
+    v = wave_sum(v);
+    if ((tid & 63) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    float tot = 0.f;
 #pragma unroll
-  for (int w = 0; w < SCORE_FIN_THREADS / 64; ++w) tot += red[w];
-  const float nrm = sqrtf(tot);
-  for (int u = tid; u < nu; u += SCORE_FIN_THREADS) out[u] = nrm > 0.f ? out[u] / nrm : 0.f;
+    for (int w = 0; w < SCORE_FIN_WAVES; ++w) tot += red[w];
+    return tot;
+  };
+  if (ur == 1) score_finish_group<1>(p, local, tid, SCORE_FIN_THREADS, total);
+  else if (ur == 2) score_finish_group<2>(p, local, tid, SCORE_FIN_THREADS, total);
+  else score_finish_group<0>(p, local, tid, SCORE_FIN_THREADS, total);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -288,9 +347,31 @@ static int validate_pair(const ecospa_pair& q) {
   return ECOSPA_OK;
 }
 
+// Shape of the column-norm phase of a pair: lanes side by side on a row (strip width), strips, and row ranges.
+struct ColShape { int lanes, strips, parts; };
+static ColShape col_shape(const ecospa_pair& q) {
+  const int V = q.dtype == ECOSPA_BF16 ? 8 : 4;
+  const long long rows = static_cast<long long>(q.groups) * q.n;
+  ColShape c;
+#ifdef SCORE_FORCE_LANES
+  c.lanes = SCORE_FORCE_LANES;
+#else
+  c.lanes = 8;
+#endif
+  while (c.lanes > 8 && static_cast<long long>(c.lanes / 2) * V >= rows) c.lanes /= 2;
+  c.strips = static_cast<int>((rows + c.lanes * V - 1) / (c.lanes * V));
+#ifndef SCORE_FORCE_ROWS
+#define SCORE_FORCE_ROWS 256
+#endif
+  c.parts = (q.d2 + SCORE_FORCE_ROWS - 1) / SCORE_FORCE_ROWS;
+  if (c.parts > SCORE_MAX_PARTS) c.parts = SCORE_MAX_PARTS;
+  return c;
+}
+
 static size_t pair_ws_bytes(const ecospa_pair& q) {
   const size_t rows = static_cast<size_t>(q.groups) * q.n;
-  return 2 * align_up(rows * 4, 256);   // a_sq, b_sq
+  const size_t parts = q.kind == ECOSPA_PAIR_QK ? 1 : col_shape(q).parts;
+  return align_up(rows * 4, 256) + align_up(parts * rows * 4, 256);   // a_sq, b_sq (partial sums)
 }
 
 extern "C" size_t ecospa_score_workspace_bytes(const ecospa_pair* pairs, int n_pairs) {
@@ -317,14 +398,11 @@ static int score_run(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, flo
   if (!ctx->ws || ctx->ws_bytes < need) return ECOSPA_ERR_WORKSPACE;
   WsCarver ws(ctx->ws, ctx->ws_bytes);
 
-  ScoreFinBatch fb;
-  fb.n_pairs = 0;
-  int fin = 0;
   for (int first = 0; first < n_pairs; first += SCORE_MAX_PAIRS) {
     ScoreBatch b;
     memset(&b, 0, sizeof(b));
     b.n_pairs = (n_pairs - first < SCORE_MAX_PAIRS) ? n_pairs - first : SCORE_MAX_PAIRS;
-    int blk = 0;
+    int blk = 0, fin = 0;
     for (int i = 0; i < b.n_pairs; ++i) {
       const ecospa_pair& q = pairs[first + i];
       ScorePairDev& p = b.p[i];
@@ -336,41 +414,33 @@ static int score_run(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, flo
       p.a_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows) * 4));
       const int row_blocks = (p.rows + SCORE_ROWS_PER_BLOCK - 1) / SCORE_ROWS_PER_BLOCK;
       p.blk_row1 = blk;
+      b.first_blk[i] = blk;
       blk += row_blocks;
       p.blk_row2 = blk;
-      p.b_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows) * 4));
+      p.col_lanes = 8; p.col_strips = 1; p.col_parts = 1;
       if (q.kind == ECOSPA_PAIR_QK) {
+        p.b_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows) * 4));
         blk += row_blocks;
         p.blk_col = blk;
       } else {
+        const ColShape c = col_shape(q);
+        p.col_lanes = c.lanes; p.col_strips = c.strips; p.col_parts = c.parts;
+        p.b_sq = static_cast<float*>(ws.take(static_cast<size_t>(c.parts) * p.rows * 4));
         p.blk_col = blk;
-        const int strip = SCORE_COL_LANES * (q.dtype == ECOSPA_BF16 ? 8 : 4);
-        blk += (p.rows + strip - 1) / strip;
+        blk += c.strips * c.parts;
       }
       p.blk_end = blk;
+      p.fin_blocks = q.groups >= SCORE_FIN_WAVES ? (q.groups + SCORE_FIN_WAVES - 1) / SCORE_FIN_WAVES : q.groups;
+      if (p.fin_blocks > fin) fin = p.fin_blocks;
+      p.scores = scores[first + i];
+      const double members = q.kind == ECOSPA_PAIR_FFN_GATED ? 2.0 : 1.0;   // W_gate and W_up form the first member
+      p.fw1 = fisher ? static_cast<float>(0.5 / (members * q.n * static_cast<double>(q.d1) * n_samples)) : 0.f;
+      p.fw2 = fisher ? static_cast<float>(0.5 / (q.n * static_cast<double>(q.d2) * n_samples)) : 0.f;
     }
     if (!ws.ok()) return ECOSPA_ERR_WORKSPACE;
     hipLaunchKernelGGL(score_sumsq_kernel, dim3(blk), dim3(256), 0, ctx->stream, b);
     ECOSPA_CHECK_LAUNCH(ctx, "score_sumsq_kernel");
-    // queue the finishing work of this batch; launch it when the queue is full or the batches are done
-    for (int i = 0; i < b.n_pairs; ++i) {
-      if (fb.n_pairs == SCORE_FIN_MAX_PAIRS) {
-        hipLaunchKernelGGL(score_finish_kernel, dim3(fin), dim3(SCORE_FIN_THREADS), 0, ctx->stream, fb);
-        ECOSPA_CHECK_LAUNCH(ctx, "score_finish_kernel");
-        fb.n_pairs = 0;
-        fin = 0;
-      }
-      ScoreFinPair& f = fb.p[fb.n_pairs++];
-      f.a_sq = b.p[i].a_sq; f.b_sq = b.p[i].b_sq; f.scores = scores[first + i];
-      f.n = b.p[i].n; f.unit = b.p[i].unit; f.fin_begin = fin; f.fisher = fisher;
-      const double members = b.p[i].kind == ECOSPA_PAIR_FFN_GATED ? 2.0 : 1.0;   // W_gate and W_up form the first member
-      f.w1 = fisher ? static_cast<float>(0.5 / (members * b.p[i].n * static_cast<double>(b.p[i].d1) * n_samples)) : 0.f;
-      f.w2 = fisher ? static_cast<float>(0.5 / (b.p[i].n * static_cast<double>(b.p[i].d2) * n_samples)) : 0.f;
-      fin += b.p[i].groups;
-    }
-  }
-  if (fb.n_pairs > 0) {
-    hipLaunchKernelGGL(score_finish_kernel, dim3(fin), dim3(SCORE_FIN_THREADS), 0, ctx->stream, fb);
+    hipLaunchKernelGGL(score_finish_kernel, dim3(fin, b.n_pairs), dim3(SCORE_FIN_THREADS), 0, ctx->stream, b);
     ECOSPA_CHECK_LAUNCH(ctx, "score_finish_kernel");
   }
   return ECOSPA_OK;

@@ -24,6 +24,7 @@ struct SelectItemDev {
 };
 struct SelectBatch {
   int n_items;
+  int first_blk[SELECT_MAX_ITEMS];   // blk_begin of every item, side by side: the search for a group's item stays in a few cache lines
   SelectItemDev it[SELECT_MAX_ITEMS];
 };
 
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
   int item = 0, hi = b.n_items - 1;       // last item whose first block is <= blockIdx.x
   while (item < hi) {
     const int mid = (item + hi + 1) >> 1;
-    if (b.it[mid].blk_begin <= static_cast<int>(blockIdx.x)) item = mid; else hi = mid - 1;
+    if (b.first_blk[mid] <= static_cast<int>(blockIdx.x)) item = mid; else hi = mid - 1;
   }
   const SelectItemDev& t = b.it[item];
   const int n = t.n, g = blockIdx.x - t.blk_begin;
@@ -333,6 +334,7 @@ extern "C" int ecospa_select_topk_batch(ecospa_ctx* ctx, const ecospa_select_ite
     for (int i = 0; i < b.n_items; ++i) {
       const ecospa_select_item& q = items[first + i];
       b.it[i] = SelectItemDev{q.scores, q.idx, q.n_units, q.k, static_cast<int>(blk), nullptr, 0, 0};
+      b.first_blk[i] = static_cast<int>(blk);
       blk += q.groups;
       if (blk > (1ll << 30)) return ECOSPA_ERR_SHAPE;
     }
