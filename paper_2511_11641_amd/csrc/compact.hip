@@ -6,12 +6,14 @@
 //   gather : s = g*kp*unit + i*unit + u  ->  g*n + idx[g,i]*unit + u   (i < k), else -1 (padding)
 //   scatter: s = g*n + q*unit + u        ->  g*kp*unit + i*unit + u    where idx[g,i] == q (binary
 //            search in the ascending index list), else -1 (pruned)
-// Rows (axis 0) are copied by one wavefront each with 16-byte accesses; for columns (axis 1)
+// Rows (axis 0) are copied four at a time by a wavefront with 16-byte accesses; for columns (axis 1)
 // each thread owns a fixed set of destination columns, resolves their sources once and then
 // walks down the rows, so that the stores are full 16-byte coalesced writes.  A batch of copies
 // (all matrices, biases and tables of a layer) runs as ONE launch: launches of this size are
 // bound by their fixed cost, not by the bytes they move.
 #include "common.h"
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // 16 bytes held in registers
 
 struct MapArgs {
   const int* idx;
@@ -73,27 +75,51 @@ struct MapBatch {
 };
 static_assert(sizeof(MapBatch) <= 16384, "kernel arguments of one launch");
 
-// ---- axis 0: one wavefront per destination row ------------------------------------------------
+// ---- axis 0: a wavefront copies MAP_ROW_PER_WAVE destination rows at a time, the loads of all of them in flight
+#define MAP_ROW_PER_WAVE 4
+#define MAP_ROWS_PER_BLOCK (4 * MAP_ROW_PER_WAVE)
 template <typename E>
 __device__ __forceinline__ void map_rows_block(const MapItemDev& t, int blk) {
   const E* __restrict__ src = static_cast<const E*>(t.src);
   E* __restrict__ dst = static_cast<E*>(t.dst);
   const int lane = threadIdx.x & 63;
-  const long long row = static_cast<long long>(blk) * 4 + (threadIdx.x >> 6);
-  if (row >= t.dst_slots) return;
-  const long long srow = map_slot(t.m, row);
+  const long long row0 = static_cast<long long>(blk) * MAP_ROWS_PER_BLOCK + (threadIdx.x >> 6) * MAP_ROW_PER_WAVE;
+  if (row0 >= t.dst_slots) return;
   const long long cols = t.other;
-  E* d = dst + row * t.ld_dst;
+  long long srow[MAP_ROW_PER_WAVE];   // source row, -1: zeros (padding / pruned), -2: no such destination row
+#pragma unroll
+  for (int j = 0; j < MAP_ROW_PER_WAVE; ++j) srow[j] = row0 + j < t.dst_slots ? map_slot(t.m, row0 + j) : -2;
   if (t.vec) {
     constexpr int V = 16 / sizeof(E);
-    const uint4 zero = make_uint4(0, 0, 0, 0);
+    const u32x4_t zero = {0u, 0u, 0u, 0u};
     const long long nv = cols / V;
-    const uint4* s4 = srow >= 0 ? reinterpret_cast<const uint4*>(src + srow * t.ld_src) : nullptr;
-    uint4* d4 = reinterpret_cast<uint4*>(d);
-    for (long long c = lane; c < nv; c += 64) d4[c] = s4 ? s4[c] : zero;
-    for (long long c = nv * V + lane; c < cols; c += 64) d[c] = srow >= 0 ? src[srow * t.ld_src + c] : E(0);
+    for (long long c0 = 0; c0 < nv; c0 += 128) {         // two 16-byte pieces per lane and row
+      u32x4_t x[MAP_ROW_PER_WAVE][2];
+#pragma unroll
+      for (int j = 0; j < MAP_ROW_PER_WAVE; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const long long c = c0 + lane + 64 * i;          // out of range: a valid piece is loaded and dropped
+          const u32x4_t v = reinterpret_cast<const u32x4_t*>(src + (srow[j] >= 0 ? srow[j] : 0) * t.ld_src)[c < nv ? c : nv - 1];
+          x[j][i] = srow[j] >= 0 ? v : zero;
+        }
+#pragma unroll
+      for (int j = 0; j < MAP_ROW_PER_WAVE; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const long long c = c0 + lane + 64 * i;
+          if (srow[j] > -2 && c < nv) reinterpret_cast<u32x4_t*>(dst + (row0 + j) * t.ld_dst)[c] = x[j][i];
+        }
+    }
+    for (int j = 0; j < MAP_ROW_PER_WAVE; ++j)
+      if (srow[j] > -2)
+        for (long long c = nv * V + lane; c < cols; c += 64)
+          dst[(row0 + j) * t.ld_dst + c] = srow[j] >= 0 ? src[srow[j] * t.ld_src + c] : E(0);
   } else {
-    for (long long c = lane; c < cols; c += 64) d[c] = srow >= 0 ? src[srow * t.ld_src + c] : E(0);
+    for (int j = 0; j < MAP_ROW_PER_WAVE; ++j)
+      if (srow[j] > -2)
+        for (long long c = lane; c < cols; c += 64)
+          dst[(row0 + j) * t.ld_dst + c] = srow[j] >= 0 ? src[srow[j] * t.ld_src + c] : E(0);
   }
 }
 
@@ -143,7 +169,7 @@ __device__ __forceinline__ void map_cols_block(const MapItemDev& t, int blk) {
 // at a time, and every thread picks the V columns of its 16-byte store from there.  If the window is
 // wider than the LDS tile (kept indices far apart) the region falls back to element-wise gathers.
 #define MAP_LDS_GROUPS 32          // 16-byte column groups per workgroup
-#define MAP_LDS_ROWS 8             // rows per pass (MAP_LDS_GROUPS * MAP_LDS_ROWS = 256 threads)
+#define MAP_LDS_ROWS (256 / MAP_LDS_GROUPS)   // rows per pass (MAP_LDS_GROUPS * MAP_LDS_ROWS = 256 threads)
 #define MAP_LDS_ROWS_TOTAL 64      // rows per workgroup
 #define MAP_LDS_CHUNKS 128         // 16-byte chunks of the source window per row
 template <typename E>
@@ -162,9 +188,9 @@ __device__ __forceinline__ void map_cols_lds_block(const MapItemDev& t, int blk,
   const long long r_end = r_begin + MAP_LDS_ROWS_TOTAL < t.other ? r_begin + MAP_LDS_ROWS_TOTAL : t.other;
   if (tid == 0) { lim[0] = 0x7fffffff; lim[1] = -1; }
   __syncthreads();
-  if (tid < CB) {
-    const long long sc = (c0 + tid < t.dst_slots) ? map_slot(t.m, c0 + tid) : -1;
-    smap[tid] = static_cast<int>(sc);
+  for (int c = tid; c < CB; c += 256) {
+    const long long sc = (c0 + c < t.dst_slots) ? map_slot(t.m, c0 + c) : -1;
+    smap[c] = static_cast<int>(sc);
     if (sc >= 0) { atomicMin(&lim[0], static_cast<int>(sc)); atomicMax(&lim[1], static_cast<int>(sc)); }
   }
   __syncthreads();
@@ -174,8 +200,8 @@ __device__ __forceinline__ void map_cols_lds_block(const MapItemDev& t, int blk,
   const int grp = tid % MAP_LDS_GROUPS, rr = tid / MAP_LDS_GROUPS;   // this thread's column group and row slot
   const long long dc = c0 + static_cast<long long>(grp) * V;  // its first destination column
   const bool full = dc + V <= t.dst_slots;
-  if (chunks > MAP_LDS_CHUNKS) {
-    // window too wide for the tile: gather element by element
+  if (chunks > MAP_LDS_CHUNKS || chunks == 0) {
+    // window too wide for the tile (or no source column at all: padding only): element by element
     for (long long r = r_begin + rr; r < r_end; r += MAP_LDS_ROWS) {
       alignas(16) E vals[V];
 #pragma unroll
@@ -199,34 +225,55 @@ __device__ __forceinline__ void map_cols_lds_block(const MapItemDev& t, int blk,
   const int lane = tid & 63, wave = tid >> 6;
   const int wrow = wave * RPW + lane / MAP_LDS_GROUPS, l16 = lane % MAP_LDS_GROUPS;
   E* wtile = tile + wrow * MAP_LDS_CHUNKS * V;
-  for (long long rb = r_begin; rb < r_end; rb += MAP_LDS_ROWS) {
-    const long long r = rb + wrow;
-    const long long rl = r < r_end ? r : r_end - 1;
-    const E* sp = src + rl * t.ld_src + w0;
-    for (int ch = l16; ch < chunks; ch += MAP_LDS_GROUPS)
-      *reinterpret_cast<uint4*>(wtile + ch * V) = *reinterpret_cast<const uint4*>(sp + ch * V);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    if (r < r_end && dc < t.dst_slots) {
-      alignas(16) E vals[V];
-#pragma unroll
-      for (int v = 0; v < V; ++v) vals[v] = off[v] >= 0 ? wtile[off[v]] : E(0);
-      E* d = dst + r * t.ld_dst + dc;
-      if (full) *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(vals);
-      else
-        for (int v = 0; v < V; ++v)
-          if (dc + v < t.dst_slots) d[v] = vals[v];
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  // the windows of the next two passes are fetched into registers while this pass is gathered and stored; a
+  // lane whose chunk lies beyond the window fetches the window's last chunk instead and drops it
+  constexpr int PC = MAP_LDS_CHUNKS / MAP_LDS_GROUPS;   // 16-byte chunks a lane fetches per pass
+  u32x4_t pre_a[PC], pre_b[PC];
+#define MAP_FETCH(PRE, RB)                                                                          \
+  if ((RB) < r_end) {                                                                               \
+    const long long rn_ = (RB) + wrow;                                                              \
+    const E* sp_ = src + (rn_ < r_end ? rn_ : r_end - 1) * t.ld_src + w0;                           \
+    _Pragma("unroll") for (int i = 0; i < PC; ++i) {                                                \
+      const int ch_ = l16 + i * MAP_LDS_GROUPS;                                                     \
+      PRE[i] = *reinterpret_cast<const u32x4_t*>(sp_ + (ch_ < chunks ? ch_ : chunks - 1) * V);      \
+    }                                                                                               \
   }
+#define MAP_PASS(PRE, RB)                                                                           \
+  {                                                                                                 \
+    const long long r_ = (RB) + wrow;                                                               \
+    _Pragma("unroll") for (int i = 0; i < PC; ++i) {                                                \
+      const int ch_ = l16 + i * MAP_LDS_GROUPS;                                                     \
+      if (ch_ < chunks) *reinterpret_cast<u32x4_t*>(wtile + ch_ * V) = PRE[i];                      \
+    }                                                                                               \
+    MAP_FETCH(PRE, (RB) + 2 * MAP_LDS_ROWS)                                                         \
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");                                          \
+    __builtin_amdgcn_wave_barrier();                                                                \
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");                                          \
+    if (r_ < r_end && dc < t.dst_slots) {                                                           \
+      alignas(16) E vals[V];                                                                        \
+      _Pragma("unroll") for (int v = 0; v < V; ++v) vals[v] = off[v] >= 0 ? wtile[off[v]] : E(0);   \
+      E* d = dst + r_ * t.ld_dst + dc;                                                              \
+      if (full) *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(vals);               \
+      else                                                                                          \
+        for (int v = 0; v < V; ++v)                                                                 \
+          if (dc + v < t.dst_slots) d[v] = vals[v];                                                 \
+    }                                                                                               \
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");                                          \
+    __builtin_amdgcn_wave_barrier();                                                                \
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");                                          \
+  }
+  MAP_FETCH(pre_a, r_begin)
+  MAP_FETCH(pre_b, r_begin + MAP_LDS_ROWS)
+  for (long long rb = r_begin; rb < r_end; rb += 2 * MAP_LDS_ROWS) {
+    MAP_PASS(pre_a, rb)
+    if (rb + MAP_LDS_ROWS < r_end) MAP_PASS(pre_b, rb + MAP_LDS_ROWS)
+  }
+#undef MAP_PASS
+#undef MAP_FETCH
 }
 
 __global__ __launch_bounds__(256) void map_batch_kernel(const MapBatch b) {
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[MAP_LDS_ROWS * MAP_LDS_CHUNKS * 16 + (MAP_LDS_GROUPS * 8 + 2) * 4];
-  static_assert(MAP_LDS_GROUPS * 8 <= 256, "one thread per destination column resolves the source columns");
   const int blk = blockIdx.x;
   int i = 0, hi = b.n_items - 1;          // last item whose first block is <= blk
   while (i < hi) {
@@ -301,7 +348,7 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
       b.first_blk[i] = t.blk_begin;
       if (q.axis == 0) {
         t.vec = aligned16(q.src) && aligned16(q.dst) && q.ld_src % V == 0 && q.ld_dst % V == 0;
-        blk += (t.dst_slots + 3) / 4;
+        blk += (t.dst_slots + MAP_ROWS_PER_BLOCK - 1) / MAP_ROWS_PER_BLOCK;
       } else {
         t.vec = aligned16(q.dst) && q.ld_dst % V == 0;
         // the LDS path reads whole 16-byte chunks of the source rows, up to the end of the last kept chunk

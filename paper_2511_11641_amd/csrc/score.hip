@@ -13,9 +13,8 @@
 #include "common.h"
 
 #define SCORE_MAX_PAIRS 96         // descriptors travel as kernel arguments (about 15 KB)
-#ifndef SCORE_ROWS_PER_BLOCK
 #define SCORE_ROWS_PER_BLOCK 16   // row-norm blocks: 4 waves x 4 rows
-#endif
+#define SCORE_COL_ROWS 256             // rows of a column-norm workgroup (up to SCORE_MAX_PARTS ranges per matrix)
 #define SCORE_COL_LDS (256 * 8 + 32)   // floats: slots x (strip width + 1) for every split of 256 threads into lanes x slots
 
 struct ScorePairDev {
@@ -353,17 +352,9 @@ static ColShape col_shape(const ecospa_pair& q) {
   const int V = q.dtype == ECOSPA_BF16 ? 8 : 4;
   const long long rows = static_cast<long long>(q.groups) * q.n;
   ColShape c;
-#ifdef SCORE_FORCE_LANES
-  c.lanes = SCORE_FORCE_LANES;
-#else
-  c.lanes = 8;
-#endif
-  while (c.lanes > 8 && static_cast<long long>(c.lanes / 2) * V >= rows) c.lanes /= 2;
+  c.lanes = 8;        // one 128-byte line per row: wider strips measured slower (fewer, longer workgroups)
   c.strips = static_cast<int>((rows + c.lanes * V - 1) / (c.lanes * V));
-#ifndef SCORE_FORCE_ROWS
-#define SCORE_FORCE_ROWS 256
-#endif
-  c.parts = (q.d2 + SCORE_FORCE_ROWS - 1) / SCORE_FORCE_ROWS;
+  c.parts = (q.d2 + SCORE_COL_ROWS - 1) / SCORE_COL_ROWS;
   if (c.parts > SCORE_MAX_PARTS) c.parts = SCORE_MAX_PARTS;
   return c;
 }
