@@ -64,7 +64,7 @@ struct MapItemDev {
   int axis;
   int vec;        // 16-byte accesses are legal
   int gx;         // axis 1: blocks along the destination columns
-  int rpb;        // axis 1: rows per block
+  int rpb;        // axis 1: rows per workgroup
   int lds_path;   // axis 1 gather with aligned rows: source window staged through LDS
   int blk_begin;  // first block of this item
 };
@@ -184,8 +184,8 @@ __device__ __forceinline__ void map_cols_lds_block(const MapItemDev& t, int blk,
   const int tid = threadIdx.x;
   const int bx = blk % t.gx, by = blk / t.gx;
   const long long c0 = static_cast<long long>(bx) * CB;
-  const long long r_begin = static_cast<long long>(by) * MAP_LDS_ROWS_TOTAL;
-  const long long r_end = r_begin + MAP_LDS_ROWS_TOTAL < t.other ? r_begin + MAP_LDS_ROWS_TOTAL : t.other;
+  const long long r_begin = static_cast<long long>(by) * t.rpb;
+  const long long r_end = r_begin + t.rpb < t.other ? r_begin + t.rpb : t.other;
   if (tid == 0) { lim[0] = 0x7fffffff; lim[1] = -1; }
   __syncthreads();
   for (int c = tid; c < CB; c += 256) {
@@ -355,7 +355,11 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
         t.lds_path = t.vec && aligned16(q.src) && q.ld_src % V == 0 && (q.scatter ? cmp_slots : full_slots) % V == 0;
         if (t.lds_path) {
           t.gx = static_cast<int>((t.dst_slots + MAP_LDS_GROUPS * V - 1) / (MAP_LDS_GROUPS * V));
-          blk += (q.other_extent + MAP_LDS_ROWS_TOTAL - 1) / MAP_LDS_ROWS_TOTAL * t.gx;
+          // rows per workgroup: fewer when the matrix alone would not fill the chip (a single layer's launch)
+          int rpb = MAP_LDS_ROWS_TOTAL;
+          while (rpb > 2 * MAP_LDS_ROWS && (q.other_extent + rpb - 1) / rpb * t.gx < 1024) rpb /= 2;
+          t.rpb = rpb;
+          blk += (q.other_extent + rpb - 1) / rpb * t.gx;
         } else {
           const int vv = t.vec ? V : 1;
           t.gx = static_cast<int>((t.dst_slots + 256ll * vv - 1) / (256ll * vv));

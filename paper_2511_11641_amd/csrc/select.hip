@@ -18,6 +18,7 @@ struct SelectItemDev {
   int* idx;
   int n, k;
   int blk_begin;   // first workgroup (= group) of this item
+  int groups;        // groups of this item (n <= 64: SELECT_THREADS / 64 of them share a workgroup)
   const int* k_dev;  // optional: per-group kept counts in device memory (then k is unused, the rows of idx
   int ld_idx;        //           are ld_idx apart and the slots behind the kept indices are set to -1)
   int smallest;      // take the k smallest scores instead (the order of the keys reversed, ties still to the lower index)
@@ -74,8 +75,30 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
     if (b.first_blk[mid] <= static_cast<int>(blockIdx.x)) item = mid; else hi = mid - 1;
   }
   const SelectItemDev& t = b.it[item];
-  const int n = t.n, g = blockIdx.x - t.blk_begin;
   const uint32_t flip = t.smallest ? 0xffffffffu : 0u;
+  if (t.n <= 64) {
+    // Small groups (the units of one head): a wavefront ranks a group by direct comparison - the rank of
+    // a unit is the number of units that come before it in the order (larger key, or equal key and lower
+    // index) - and the lanes whose rank is below k write their indices, ascending.  One group per wavefront.
+    const int g = (static_cast<int>(blockIdx.x) - t.blk_begin) * (SELECT_THREADS / 64) + wave;
+    if (g >= t.groups) return;
+    const int lane = tid & 63, n = t.n;
+    const int k = t.k_dev ? t.k_dev[g] : t.k;
+    const uint32_t key = lane < n ? ITEM_KEY(t.scores[static_cast<long long>(g) * n + lane]) : 0u;
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+      const uint32_t kj = __shfl(key, j, 64);
+      rank += (kj > key) || (kj == key && j < lane);
+    }
+    const bool take = lane < n && rank < k;
+    const unsigned long long mask = __ballot(take);
+    int* out = t.idx + static_cast<long long>(g) * (t.k_dev ? t.ld_idx : k);
+    if (take) out[__popcll(mask & ((1ull << lane) - 1ull))] = lane;
+    if (t.k_dev)
+      for (int i = k + lane; i < t.ld_idx; i += 64) out[i] = -1;
+    return;
+  }
+  const int n = t.n, g = blockIdx.x - t.blk_begin;
   const int k = t.k_dev ? t.k_dev[g] : t.k;
   const float* s = t.scores + static_cast<long long>(g) * n;
   int* out = t.idx + static_cast<long long>(g) * (t.k_dev ? t.ld_idx : k);
@@ -93,12 +116,11 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
 
   uint32_t prefix = 0u;   // high bits of the k-th largest key found so far
   int krem = k;           // rank (1-based) of the wanted key among keys matching the prefix
+  for (int i = tid; i < (SELECT_THREADS / 64) * 256; i += SELECT_THREADS) (&whist[0][0])[i] = 0;
+  __syncthreads();
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
     const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
-    for (int i = tid; i < (SELECT_THREADS / 64) * 256; i += SELECT_THREADS) (&whist[0][0])[i] = 0;
-    if (tid == 256) hist[256] = 0;
-    __syncthreads();
     if (cached) {
 #pragma unroll
       for (int j = 0; j < SELECT_CACHE; ++j)
@@ -110,20 +132,28 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
       }
     }
     __syncthreads();
+    // suffix sums hist[d] = number of matching keys with digit >= d: the first four wavefronts own 64 digits
+    // each, add the per-wavefront histograms, scan inside the wavefront, then add the totals of the digits above
+    int suf = 0;
     if (tid < 256) {
-      int c = 0;
 #pragma unroll
-      for (int w = 0; w < SELECT_THREADS / 64; ++w) c += whist[w][tid];
-      hist[tid] = c;
+      for (int w = 0; w < SELECT_THREADS / 64; ++w) suf += whist[w][tid];
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int v = __shfl_down(suf, off, 64);
+        if ((tid & 63) + off < 64) suf += v;
+      }
+      if ((tid & 63) == 0) wave_tot[wave] = suf;
     }
     __syncthreads();
-    // suffix sums: hist[d] = number of matching keys with digit >= d
-    for (int off = 1; off < 256; off <<= 1) {
-      const int v = (tid < 256 && tid + off < 256) ? hist[tid + off] : 0;
-      __syncthreads();
-      if (tid < 256) hist[tid] += v;
-      __syncthreads();
+    if (tid < 256) {
+      for (int w = wave + 1; w < 4; ++w) suf += wave_tot[w];
+      hist[tid] = suf;
+    } else if (tid == 256) {
+      hist[256] = 0;
     }
+    for (int i = tid; i < (SELECT_THREADS / 64) * 256; i += SELECT_THREADS) (&whist[0][0])[i] = 0;   // for the next pass
+    __syncthreads();
     if (tid < 256 && hist[tid] >= krem && hist[tid + 1] < krem) {   // exactly one thread
       s_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
       s_krem = krem - hist[tid + 1];
@@ -131,7 +161,6 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const Selec
     __syncthreads();
     prefix = s_prefix;
     krem = s_krem;
-    __syncthreads();
   }
   const uint32_t T = prefix;   // k-th largest key; take `krem` of the elements equal to it
 
@@ -312,6 +341,11 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_theta_count_kernel(cons
   }
 }
 
+// Workgroups of an item: one per group, or one per SELECT_THREADS / 64 small groups (a wavefront each).
+static int select_blocks(int groups, int n_units) {
+  return n_units <= 64 ? (groups + SELECT_THREADS / 64 - 1) / (SELECT_THREADS / 64) : groups;
+}
+
 static int validate_select(const ecospa_select_item& q) {
   if (!q.scores || !q.idx) return ECOSPA_ERR_NULL;
   if (q.groups < 1 || q.n_units < 1) return ECOSPA_ERR_SHAPE;
@@ -333,9 +367,9 @@ extern "C" int ecospa_select_topk_batch(ecospa_ctx* ctx, const ecospa_select_ite
     long long blk = 0;
     for (int i = 0; i < b.n_items; ++i) {
       const ecospa_select_item& q = items[first + i];
-      b.it[i] = SelectItemDev{q.scores, q.idx, q.n_units, q.k, static_cast<int>(blk), nullptr, 0, 0};
+      b.it[i] = SelectItemDev{q.scores, q.idx, q.n_units, q.k, static_cast<int>(blk), q.groups, nullptr, 0, 0};
       b.first_blk[i] = static_cast<int>(blk);
-      blk += q.groups;
+      blk += select_blocks(q.groups, q.n_units);
       if (blk > (1ll << 30)) return ECOSPA_ERR_SHAPE;
     }
     hipLaunchKernelGGL(select_topk_kernel, dim3(static_cast<unsigned>(blk)), dim3(SELECT_THREADS), 0, ctx->stream, b);
@@ -361,8 +395,8 @@ extern "C" int ecospa_select_theta(ecospa_ctx* ctx, const float* scores, int gro
   SelectBatch b;
   memset(&b, 0, sizeof(b));
   b.n_items = 1;
-  b.it[0] = SelectItemDev{scores, idx, n_units, 0, 0, k_out, n_units, 0};
-  hipLaunchKernelGGL(select_topk_kernel, dim3(groups), dim3(SELECT_THREADS), 0, ctx->stream, b);
+  b.it[0] = SelectItemDev{scores, idx, n_units, 0, 0, groups, k_out, n_units, 0};
+  hipLaunchKernelGGL(select_topk_kernel, dim3(select_blocks(groups, n_units)), dim3(SELECT_THREADS), 0, ctx->stream, b);
   ECOSPA_CHECK_LAUNCH(ctx, "select_topk_kernel");
   return ECOSPA_OK;
 }
@@ -375,7 +409,7 @@ extern "C" int ecospa_select_pairs(ecospa_ctx* ctx, const float* fisher, int n_p
   SelectBatch b;
   memset(&b, 0, sizeof(b));
   b.n_items = 1;
-  b.it[0] = SelectItemDev{fisher, chosen, n_pairs, n_select, 0, nullptr, 0, 1};
+  b.it[0] = SelectItemDev{fisher, chosen, n_pairs, n_select, 0, 1, nullptr, 0, 1};
   hipLaunchKernelGGL(select_topk_kernel, dim3(1), dim3(SELECT_THREADS), 0, ctx->stream, b);
   ECOSPA_CHECK_LAUNCH(ctx, "select_topk_kernel");
   return ECOSPA_OK;
