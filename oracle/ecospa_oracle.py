@@ -227,6 +227,18 @@ def scatter_ragged(cmp, idx, ks, axis: int, n: int, kp: int, unit: int = 1) -> n
     return out.reshape(-1) if vec else (out.T if axis == 0 else out)
 
 
+def individual_keep(w1, w2, n: int, k: int):
+    """The baseline of Appendix A (Def. 2, individual sparsification), for one pair with a single group:
+    the k inner dimensions of W_1 with the largest ||a_j|| and, independently, the k of W_2 with the
+    largest ||b_j|| (ties keep the lower index, as everywhere).  Returns (idx_1, idx_2), ascending int32
+    [1, k] each; gathering W_1 with idx_1 and W_2 with idx_2 re-pairs whatever is left, position by position."""
+    w1, w2 = _f64(w1), _f64(w2)
+    na = np.sqrt((w1 * w1).sum(axis=1))          # ||a_j||: rows of stored W_1
+    nb = np.sqrt((w2 * w2).sum(axis=0))          # ||b_j||: columns of stored W_2
+    assert na.size == n and nb.size == n
+    return select_topk(na[None, :], k), select_topk(nb[None, :], k)
+
+
 def kept_positions(idx, n: int, unit: int = 1) -> np.ndarray:
     """Flat positions, over all groups, of the kept inner dimensions (ascending per group)."""
     idx = np.asarray(idx, dtype=np.int64)

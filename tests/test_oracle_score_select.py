@@ -309,3 +309,22 @@ def test_table7_individual_column_n100(golden_dir):
     assert abs(t1 / trials - want1) / want1 < 0.015
     assert abs(t2 / trials - want2) / want2 < 0.05
     assert abs(100.0 * wins / trials - wantp) < 1.5
+
+
+def test_individual_keep_is_the_independent_argmin_removal():
+    """Def. 2 of Appendix A with one removal: the dropped indices are the argmin of each member's own norms,
+    and the re-paired product is that of numpy's delete (library routines, written independently)."""
+    g = np.random.Generator(np.random.Philox(key=[79, 1]))
+    for n in (5, 40):
+        A, Bm = g.standard_normal((n, n + 3)).T, g.standard_normal((n, n + 2))      # A: (n+3) x n, B: n x (n+2)
+        i1, i2 = O.individual_keep(A.T, Bm.T, n, n - 1)
+        ka, lb = int(np.argmin(np.linalg.norm(A, axis=0))), int(np.argmin(np.linalg.norm(Bm, axis=1)))
+        assert sorted(set(range(n)) - set(i1[0].tolist())) == [ka]
+        assert sorted(set(range(n)) - set(i2[0].tolist())) == [lb]
+        got = O.compact(A.T, i1, 0, n).T @ O.compact(Bm.T, i2, 1, n).T
+        np.testing.assert_allclose(got, np.delete(A, ka, axis=1) @ np.delete(Bm, lb, axis=0), rtol=1e-13, atol=1e-13)
+    # keeping k < n - 1: each member keeps its own k largest norms
+    A, Bm = g.standard_normal((7, 9)), g.standard_normal((9, 4))
+    i1, i2 = O.individual_keep(A.T, Bm.T, 9, 4)
+    assert set(i1[0].tolist()) == set(np.argsort(-np.linalg.norm(A, axis=0), kind="stable")[:4].tolist())
+    assert set(i2[0].tolist()) == set(np.argsort(-np.linalg.norm(Bm, axis=1), kind="stable")[:4].tolist())
