@@ -240,6 +240,27 @@ def second_workload(ctx, name, steps, warmup):
             "speedup_fwd_bwd_vs_dense": ms_de / ms_fb}
 
 
+def inference_sweep(ctx, name, steps):
+    """Forward only (inference) of the layer at batch 1 and batch 32, dense and at three keep ratios: per-layer
+    time, tokens/s and the speed-up over the dense layer run through the same library."""
+    import torch
+    from paper_2511_11641_amd import synth
+    rows = []
+    for Bsz in (1, 32):
+        cfg = dict(synth.CONFIGS[name], B=Bsz)
+        T = Bsz * cfg["L"]
+        ms_dense = None
+        for num, den in ((1, 1), (3, 4), (1, 2), (3, 10)):
+            lay = Layer(ctx, cfg, cfg["seed"], num, den)
+            ms = timed(torch, lay.fwd, steps, 3)
+            ms_dense = ms if ms_dense is None else ms_dense
+            rows.append({"batch": Bsz, "seq_len": cfg["L"], "keep": f"{num}/{den}", "ms_fwd": ms,
+                         "tokens_per_s": T / (ms * 1e-3), "speedup_vs_dense": ms_dense / ms})
+            del lay
+            torch.cuda.empty_cache()
+    return {"workload": name, "pass": "forward only", "rows": rows}
+
+
 def cpu_baseline(cfg, seed, keep_num, keep_den, sample_B):
     """The fp64 oracle, as it stands, on `sample_B` batch elements of the same workload."""
     import os
@@ -372,6 +393,7 @@ def main():
     if not args.no_extras:
         out["prune_24_layers"] = prune_stack(ctx, cfg, 24, 1, 2, 20)
         out["also"] = second_workload(ctx, "c3_llama1b_layer", args.steps, args.warmup)
+        out["inference"] = inference_sweep(ctx, name, 20)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, seed, 1, 2, sample_B=8)
     print(json.dumps(out))
