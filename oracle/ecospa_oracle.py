@@ -44,26 +44,34 @@ def _f64(a):
 # --------------------------------------------------------------------------------------
 # Step 1: per-dimension coupled score (Eq. 10; selection criterion of Eq. 12)
 # --------------------------------------------------------------------------------------
-def coupled_score(kind: int, w1, w2, groups: int, n: int, unit: int = 1, w1b=None) -> np.ndarray:
+def coupled_score(kind: int, w1, w2, groups: int, n: int, unit: int = 1, w1b=None, rep1: int = 1,
+                  rep2: int = 1) -> np.ndarray:
     """upsilon[g, u] = r[g, u] / ||r[g, :]||_2 with r = ||a||_2 * ||b||_2 over each unit.
 
     a_j is stored row j of ``w1`` (of the elementwise product ``w1 * w1b`` for the gated
     FFN); b_j is stored row j of ``w2`` for the QK pair and stored column j of ``w2``
     otherwise.  For ``unit > 1`` the norms are Frobenius norms over the unit's rows/columns.
     An all-zero group scores 0 everywhere.
+
+    Grouped-query attention (Eq. 5): the pairs W_i^Q W_g(i)^K^T of the rep1 query heads of a group
+    share the inner dimensions of one key head, so dimension j leaves all of them together; a_j is then
+    column j of the group's query matrices stacked on each other, i.e. ||a_j||^2 adds the rep1 heads'
+    squared norms (``w1`` holds groups * rep1 heads of n rows, the heads of a group side by side).  In
+    the same way rep2 heads of W^O share one value head (``w2`` holds groups * rep2 heads of n columns).
     """
     w1 = _f64(w1)
     w2 = _f64(w2)
     if kind == PAIR_FFN_GATED:
         w1 = w1 * _f64(w1b)
-    assert n % unit == 0 and w1.shape[0] == groups * n
-    a_sq = (w1 * w1).sum(axis=1)
+    assert n % unit == 0 and w1.shape[0] == groups * rep1 * n
+    a_sq = (w1 * w1).sum(axis=1).reshape(groups, rep1, n).sum(axis=1).reshape(-1)
     if kind == PAIR_QK:
-        assert w2.shape[0] == groups * n
+        assert w2.shape[0] == groups * rep2 * n
         b_sq = (w2 * w2).sum(axis=1)
     else:
-        assert w2.shape[1] == groups * n
+        assert w2.shape[1] == groups * rep2 * n
         b_sq = (w2 * w2).sum(axis=0)
+    b_sq = b_sq.reshape(groups, rep2, n).sum(axis=1).reshape(-1)
     nu = n // unit
     a_u = a_sq.reshape(groups, nu, unit).sum(axis=2)
     b_u = b_sq.reshape(groups, nu, unit).sum(axis=2)
@@ -373,10 +381,14 @@ def attn_fwd(x, wq, wk, wv, wo, B: int, L: int, scale: float, causal: bool,
     wq, wk: [h, k_qk, d]; wv: [h, k_vo, d]; wo: [h, d, k_vo] (head i's columns of W^O);
     optional biases bq, bk: [h, k_qk], bv: [h, k_vo], bo: [d]; angles: [h, L, k_qk/2] or None.
     Y[b] = sum_i softmax(scale * Q_i K_i^T (+ causal mask)) V_i W_o,i^T + b_o.
+    Grouped-query attention (Eq. 5): wk, wv (bk, bv) may hold fewer heads, h_kv dividing h; query head i
+    then uses key/value head g(i) = i // (h / h_kv) (its angles are those of the query head).
     Returns (Y[B*L, d], saved) where saved holds q, k (rotated), v, p, o per (b, head).
     """
     x, wq, wk, wv, wo, bq, bk, bv, bo = map(_f64, (x, wq, wk, wv, wo, bq, bk, bv, bo))
     h = wq.shape[0]
+    m = h // wk.shape[0]                          # query heads per key/value head
+    assert wk.shape[0] * m == h and wv.shape[0] == wk.shape[0]
     d = x.shape[1]
     y = np.zeros((B * L, d))
     sv = {"q": {}, "k": {}, "v": {}, "p": {}, "o": {}}
@@ -385,14 +397,14 @@ def attn_fwd(x, wq, wk, wv, wo, B: int, L: int, scale: float, causal: bool,
         xb = x[b * L:(b + 1) * L]
         for i in range(h):
             q = xb @ wq[i].T
-            k = xb @ wk[i].T
-            v = xb @ wv[i].T
+            k = xb @ wk[i // m].T
+            v = xb @ wv[i // m].T
             if bq is not None:
                 q = q + bq[i]
             if bk is not None:
-                k = k + bk[i]
+                k = k + bk[i // m]
             if bv is not None:
-                v = v + bv[i]
+                v = v + bv[i // m]
             if angles is not None:
                 q = _rotate(q, angles[i])
                 k = _rotate(k, angles[i])
@@ -418,6 +430,7 @@ def attn_bwd(x, dy, wq, wk, wv, wo, B: int, L: int, scale: float, saved, angles=
     """
     x, dy, wq, wk, wv, wo = map(_f64, (x, dy, wq, wk, wv, wo))
     h = wq.shape[0]
+    m = h // wk.shape[0]                          # query heads per key/value head (Eq. 5)
     g = {"dx": np.zeros_like(x), "dwq": np.zeros_like(wq), "dwk": np.zeros_like(wk),
          "dwv": np.zeros_like(wv), "dwo": np.zeros_like(wo),
          "dbq": np.zeros(wq.shape[:2]), "dbk": np.zeros(wk.shape[:2]), "dbv": np.zeros(wv.shape[:2]),
@@ -438,12 +451,12 @@ def attn_bwd(x, dy, wq, wk, wv, wo, B: int, L: int, scale: float, saved, angles=
                 dq = _rotate(dq, -angles[i])
                 dk = _rotate(dk, -angles[i])
             g["dwq"][i] += dq.T @ xb
-            g["dwk"][i] += dk.T @ xb
-            g["dwv"][i] += dv.T @ xb
+            g["dwk"][i // m] += dk.T @ xb
+            g["dwv"][i // m] += dv.T @ xb
             g["dbq"][i] += dq.sum(axis=0)
-            g["dbk"][i] += dk.sum(axis=0)
-            g["dbv"][i] += dv.sum(axis=0)
-            g["dx"][sl] += dq @ wq[i] + dk @ wk[i] + dv @ wv[i]
+            g["dbk"][i // m] += dk.sum(axis=0)
+            g["dbv"][i // m] += dv.sum(axis=0)
+            g["dx"][sl] += dq @ wq[i] + dk @ wk[i // m] + dv @ wv[i // m]
     return g
 
 
