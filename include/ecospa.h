@@ -70,6 +70,12 @@ int ecospa_profile_gemm_read(ecospa_ctx* ctx, int* launches, double* total_ms, d
  *     score[g][u] = r_u / sqrt(sum_{u' in group g} r_{u'}^2)       (0 if the group is all zero).
  * ECOSPA_PAIR_FFN_GATED scores a_j = row j of (w1 (.) w1b), the elementwise product of the
  * gate and up matrices (footnote to Eq. 8).
+ * Grouped-query attention (Eq. 5): the rep1 query heads of a group pair with ONE key head, so inner
+ * dimension j leaves all of them together and ||a_j||^2 adds the squared norms of row j of the rep1 heads
+ * (QK pair: groups = key heads, w1 = W_q with groups*rep1 heads of n rows, the heads of a group side by
+ * side; rep2 = 1).  In the same way rep2 heads of W_o share one value head (VO pair: w1 = W_v with
+ * `groups` heads, w2 = W_o with groups*rep2 heads of n columns).  rep = 0 means 1; rep > 1 only for
+ * the QK and VO kinds.
  * ------------------------------------------------------------------------------------------ */
 typedef struct {
   int kind;            /* ECOSPA_PAIR_*                                                      */
@@ -78,10 +84,11 @@ typedef struct {
   int n;               /* inner dimensions per group before pruning (d_h or d_ff)            */
   int unit;            /* 1, or 2 for rotary blocks; n % unit == 0                           */
   int d1, d2;          /* length of a_j and of b_j                                           */
-  const void* w1;      /* [groups*n, d1], ld1: W_q | W_v | W_in | W_gate                     */
+  const void* w1;      /* [groups*rep1*n, d1], ld1: W_q | W_v | W_in | W_gate                */
   const void* w1b;     /* FFN_GATED: W_up [groups*n, d1], ld1b; otherwise NULL               */
-  const void* w2;      /* QK: W_k [groups*n, d2]; VO/FFN*: W_o | W_out | W_down [d2, groups*n] */
+  const void* w2;      /* QK: W_k [groups*rep2*n, d2]; VO/FFN*: W_o | W_out | W_down [d2, groups*rep2*n] */
   long long ld1, ld1b, ld2;
+  int rep1, rep2;      /* heads of member 1 / member 2 per group (Eq. 5); 0 or 1: one each   */
 } ecospa_pair;
 
 /* Workspace bytes ecospa_coupled_score needs for this batch (host-only query; 0 on bad input). */
@@ -177,15 +184,19 @@ int ecospa_scatter(ecospa_ctx* ctx, const void* src, void* dst, int dtype, int a
  * zeros), so all groups share the padded width kp and the compact matrices stay dense; `k` is not
  * used.  The counts live on the device and cannot be checked on the host: choosing kp >= max_g
  * k_group[g] is the caller's contract (units beyond kp would be dropped).  k_group == NULL: every
- * group keeps k units, ld_idx = 0 means k.  Errors for ragged items: kp < 1 or ld_idx < 1 -> ERR_K. */
+ * group keeps k units, ld_idx = 0 means k.  Errors for ragged items: kp < 1 or ld_idx < 1 -> ERR_K.
+ * Grouped-query attention (Eq. 5): the idx_div query heads of a group keep the dimensions of their shared
+ * key/value head, so W_q's rows and W_o's columns are gathered with groups = query heads and idx_div =
+ * query heads per key/value head (idx: int32[(groups / idx_div) * ld_idx]); groups % idx_div != 0 -> ERR_SHAPE. */
 typedef struct {
   const void* src;
   void* dst;
   int dtype, axis, groups, n, unit, k, kp, scatter;
   long long other_extent, ld_src, ld_dst;
   const int* idx;
-  const int* k_group; /* device int32[groups] or NULL */
+  const int* k_group; /* device int32[groups / idx_div] or NULL */
   int ld_idx;
+  int idx_div;        /* heads that share one index list: group g uses list (and count) g / idx_div; 0 or 1: its own */
 } ecospa_map_item;
 int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* items /*host*/, int n_items);
 
@@ -239,14 +250,17 @@ int ecospa_rope_table_ragged(ecospa_ctx* ctx, const int* idx, int ld_idx, const 
  * rewritten per head as Eq. 4; rotary form Eq. 6; gated FFN of the footnote to Eq. 8).
  *
  * Compact layouts (padding slots hold zeros, so results are exact):
- *   ATTN: w_qkv [(2*h*kp_qk + h*kp_vo), d_model]: rows of W_q (head-major, kp_qk per head), then
+ *   ATTN: w_qkv [((h + h_kv)*kp_qk + h_kv*kp_vo), d_model]: rows of W_q (head-major, kp_qk per head), then
  *         W_k, then W_v (kp_vo per head); b_qkv same length or NULL; w_o [d_model, h*kp_vo]; b_o.
- *         kp_qk, kp_vo are multiples of 16 and at most 128.
+ *         kp_qk, kp_vo are multiples of 16 and at most 128.  h_kv = key/value heads: h for multi-head
+ *         attention (0 means h); under grouped-query attention (Eq. 5) h_kv divides h and query head i
+ *         attends with key/value head i / (h / h_kv).
  *   FFN:  w_1 [kp_ff, d_model] (SWIGLU: [2*kp_ff, d_model], gate rows then up rows); b_1 same
  *         length or NULL; w_2 [d_model, kp_ff]; b_2.  kp_ff is a multiple of 16.
  * scale is the softmax scale (1/sqrt(original d_h) keeps "compact = masked dense").
- * rope_cos/rope_sin: float[h, L, kp_qk/2] from ecospa_rope_table, or NULL for no rotation;
- * pairs are adjacent dimensions (2i, 2i+1).
+ * rope_cos/rope_sin: float[h_kv, L, kp_qk/2] from ecospa_rope_table (one row of angles per key/value head:
+ * the query heads that share it keep the same rotary blocks), or NULL for no rotation; pairs are
+ * adjacent dimensions (2i, 2i+1).
  * ------------------------------------------------------------------------------------------ */
 typedef struct {
   int block;                 /* ECOSPA_BLOCK_ATTN | ECOSPA_BLOCK_FFN */
@@ -263,10 +277,12 @@ typedef struct {
   int kp_ff, act;
   const void *w_1, *b_1, *w_2, *b_2;
   long long ld_w1, ld_w2;
+  /* ATTN, grouped-query attention */
+  int h_kv;                  /* key/value heads; 0: as many as query heads                    */
 } ecospa_block_desc;
 
 /* Activations the forward pass keeps for the backward pass; caller-allocated, dense row-major.
- *   ATTN: qkv [T, 2*h*kp_qk + h*kp_vo] (Q and K after bias and rotation, V after bias),
+ *   ATTN: qkv [T, (h + h_kv)*kp_qk + h_kv*kp_vo] (Q and K after bias and rotation, V after bias),
  *         o [T, h*kp_vo] (per-head attention output), lse float[B*h*L] (log-sum-exp of the
  *         scaled, masked scores per query).
  *   FFN:  hpre [T, kp_ff] (SWIGLU: [T, 2*kp_ff], gate then up pre-activations), act [T, kp_ff]. */

@@ -110,7 +110,8 @@ def select_topk(scores, k: int) -> np.ndarray:
 # --------------------------------------------------------------------------------------
 # Pair-level importance (Eq. 8) and the cumulative-threshold removal rule (Alg. 1)
 # --------------------------------------------------------------------------------------
-def pair_fisher(kind: int, g1, g2, groups: int, n: int, n_samples: float, g1b=None) -> np.ndarray:
+def pair_fisher(kind: int, g1, g2, groups: int, n: int, n_samples: float, g1b=None, rep1: int = 1,
+                rep2: int = 1) -> np.ndarray:
     """I_hat[g] of Eq. 8 for each of the ``groups`` coupled pairs of one layer.
 
     ``g1``, ``g2`` (and ``g1b``) are the loss gradients of the pair's matrices in the storage
@@ -119,16 +120,19 @@ def pair_fisher(kind: int, g1, g2, groups: int, n: int, n_samples: float, g1b=No
     mean of its squared entries, the two means are averaged (the factor 1/2 and 1/|W_k| of
     Eq. 8), and the result is divided by the number of samples |D|.  For the gated FFN the
     first member is the pair (W_gate, W_up) - the paper defines W_1 from both (footnote to
-    Eq. 8) - so its mean runs over the entries of both gradient matrices.
+    Eq. 8) - so its mean runs over the entries of both gradient matrices.  With grouped-query
+    attention (Eq. 5) a member is made of the rep1 (rep2) heads that share the group's inner
+    dimensions, and its mean runs over all of them.
     """
     g1, g2, g1b = _f64(g1), _f64(g2), _f64(g1b)
     out = np.zeros(groups)
     for g in range(groups):
-        rows = slice(g * n, (g + 1) * n)
-        first = g1[rows]
+        rows1 = slice(g * rep1 * n, (g + 1) * rep1 * n)
+        rows2 = slice(g * rep2 * n, (g + 1) * rep2 * n)
+        first = g1[rows1]
         if kind == PAIR_FFN_GATED:
-            first = np.concatenate([first, g1b[rows]])
-        second = g2[rows] if kind == PAIR_QK else g2[:, rows]
+            first = np.concatenate([first, g1b[rows1]])
+        second = g2[rows2] if kind == PAIR_QK else g2[:, rows2]
         out[g] = 0.5 * ((first ** 2).sum() / first.size + (second ** 2).sum() / second.size) / n_samples
     return out
 

@@ -40,7 +40,7 @@ class EcospaError(RuntimeError):
 class Pair(C.Structure):
     _fields_ = [("kind", C.c_int), ("dtype", C.c_int), ("groups", C.c_int), ("n", C.c_int), ("unit", C.c_int),
                 ("d1", C.c_int), ("d2", C.c_int), ("w1", C.c_void_p), ("w1b", C.c_void_p), ("w2", C.c_void_p),
-                ("ld1", C.c_longlong), ("ld1b", C.c_longlong), ("ld2", C.c_longlong)]
+                ("ld1", C.c_longlong), ("ld1b", C.c_longlong), ("ld2", C.c_longlong), ("rep1", C.c_int), ("rep2", C.c_int)]
 
 
 class BlockDesc(C.Structure):
@@ -51,7 +51,7 @@ class BlockDesc(C.Structure):
                 ("ld_wqkv", C.c_longlong), ("ld_wo", C.c_longlong),
                 ("kp_ff", C.c_int), ("act", C.c_int),
                 ("w_1", C.c_void_p), ("b_1", C.c_void_p), ("w_2", C.c_void_p), ("b_2", C.c_void_p),
-                ("ld_w1", C.c_longlong), ("ld_w2", C.c_longlong)]
+                ("ld_w1", C.c_longlong), ("ld_w2", C.c_longlong), ("h_kv", C.c_int)]
 
 
 class SelectItem(C.Structure):
@@ -63,7 +63,7 @@ class MapItem(C.Structure):
     _fields_ = [("src", C.c_void_p), ("dst", C.c_void_p), ("dtype", C.c_int), ("axis", C.c_int), ("groups", C.c_int),
                 ("n", C.c_int), ("unit", C.c_int), ("k", C.c_int), ("kp", C.c_int), ("scatter", C.c_int),
                 ("other_extent", C.c_longlong), ("ld_src", C.c_longlong), ("ld_dst", C.c_longlong),
-                ("idx", C.c_void_p), ("k_group", C.c_void_p), ("ld_idx", C.c_int)]
+                ("idx", C.c_void_p), ("k_group", C.c_void_p), ("ld_idx", C.c_int), ("idx_div", C.c_int)]
 
 
 class AdamwItem(C.Structure):
@@ -231,11 +231,12 @@ class Context:
     # ---- step 1 ------------------------------------------------------------------------------
     @staticmethod
     def make_pair(kind: int, w1: torch.Tensor, w2: torch.Tensor, groups: int, n: int, unit: int = 1,
-                  w1b: Optional[torch.Tensor] = None) -> Pair:
+                  w1b: Optional[torch.Tensor] = None, rep1: int = 1, rep2: int = 1) -> Pair:
+        """rep1 / rep2: heads of the first / second member that share one group's inner dimensions (Eq. 5)."""
         d1 = w1.shape[1]
         d2 = w2.shape[1] if kind == PAIR_QK else w2.shape[0]
         return Pair(kind, dtype_code(w1.dtype), groups, n, unit, d1, d2, _ptr(w1), _ptr(w1b), _ptr(w2),
-                    w1.stride(0), 0 if w1b is None else w1b.stride(0), w2.stride(0))
+                    w1.stride(0), 0 if w1b is None else w1b.stride(0), w2.stride(0), rep1, rep2)
 
     def ecospa_coupled_score(self, pairs: Sequence[Pair], out: Optional[Sequence[torch.Tensor]] = None) -> list[torch.Tensor]:
         """Scores of a batch of pairs, one float32 tensor [groups, n/unit] per pair (written into `out` if given)."""
@@ -304,12 +305,12 @@ class Context:
     @staticmethod
     def map_item(src: torch.Tensor, dst: torch.Tensor, idx: torch.Tensor, axis: int, groups: int, n: int,
                  unit: int = 1, kp: Optional[int] = None, scatter: bool = False,
-                 k_group: Optional[torch.Tensor] = None) -> MapItem:
+                 k_group: Optional[torch.Tensor] = None, idx_div: int = 1) -> MapItem:
         """Descriptor of one gather (or scatter) for :meth:`ecospa_compact_batch`.  With k_group (int32[groups]
         on the device) group g keeps its first k_group[g] entries of idx[g, :] and kp must be given."""
         if k_group is not None:
-            assert kp is not None and k_group.dtype == torch.int32 and k_group.numel() == groups
-            assert idx.dtype == torch.int32 and idx.dim() == 2 and idx.is_contiguous() and idx.shape[0] == groups
+            assert kp is not None and k_group.dtype == torch.int32 and k_group.numel() == groups // idx_div
+            assert idx.dtype == torch.int32 and idx.dim() == 2 and idx.is_contiguous() and idx.shape[0] == groups // idx_div
         k = idx.shape[1] if k_group is None else 0
         kp = k if kp is None else kp
         if src.dim() == 1:
@@ -319,7 +320,7 @@ class Context:
             ld_s, ld_d = src.stride(0), dst.stride(0)
         return MapItem(src.data_ptr(), dst.data_ptr(), dtype_code(src.dtype), axis, groups, n, unit, k, kp,
                        int(scatter), other, ld_s, ld_d, idx.data_ptr(), _ptr(k_group),
-                       idx.shape[1] if k_group is not None else 0)
+                       idx.shape[1] if k_group is not None else 0, idx_div)
 
     def ecospa_compact_ragged(self, src: torch.Tensor, idx: torch.Tensor, k_group: torch.Tensor, axis: int, groups: int,
                               n: int, kp: int, unit: int = 1, scatter: bool = False,

@@ -35,7 +35,12 @@ struct AttnArgs {
   bf16_t* dqkv;        // backward output, same layout as qkv
   int B, L, h, kp_qk, kp_vo, causal;
   float scale;
+  int h_kv;            // key/value heads (grouped-query attention, Eq. 5: query head i uses key/value head i / qpk)
+  int qpk;             // query heads per key/value head, h / h_kv (1: multi-head attention)
 };
+// Column offsets inside a row of the qkv buffer: Q heads, then the key heads, then the value heads.
+__device__ __forceinline__ int k_col(const AttnArgs& a, int kv_head) { return a.h * a.kp_qk + kv_head * a.kp_qk; }
+__device__ __forceinline__ int v_col(const AttnArgs& a, int kv_head) { return (a.h + a.h_kv) * a.kp_qk + kv_head * a.kp_vo; }
 
 // ---------------------------------------------------------------------------------------------
 // LDS tile addressing (element offsets).  Tiles are [rows][D] (D = 32 or 64 dims, 16-byte chunks
@@ -221,8 +226,8 @@ __device__ __forceinline__ void acc_to_tile(bf16_t* tile, int tok_row, int dim_t
 // one XCD (its L2 then holds that head's K and V for all of them), and the starting point of the
 // zigzag moves on every 32 workgroups of an XCD, so that both neighbouring workgroups and workgroups
 // 32 apart - the likely co-residents of a compute unit - differ in weight.
-__device__ __forceinline__ void attn_work_item(const AttnArgs& a, int n_tiles, int& tile, int& head, int& b) {
-  const int id = blockIdx.x, n_bh = a.h * a.B;
+__device__ __forceinline__ void attn_work_item(const AttnArgs& a, int heads, int n_tiles, int& tile, int& head, int& b) {
+  const int id = blockIdx.x, n_bh = heads * a.B;
   int bh, z;
   if ((n_bh & 7) == 0) {
     const int x = id & 7, l = id >> 3;            // XCD, index inside the XCD's share
@@ -234,8 +239,8 @@ __device__ __forceinline__ void attn_work_item(const AttnArgs& a, int n_tiles, i
     z = id - bh * n_tiles;
   }
   tile = (z & 1) ? (z >> 1) : n_tiles - 1 - (z >> 1);
-  head = bh % a.h;
-  b = bh / a.h;
+  head = bh % heads;
+  b = bh / heads;
 }
 
 // Wavefronts per SIMD the register allocation aims at: the narrow (32, 32) heads of a half-kept
@@ -260,7 +265,7 @@ void attn_fwd_kernel(const AttnArgs a) {
 #define Vs(buf) (Vs0 + (buf) * (64 * DV))
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, l32 = lane & 31;
   int qt, head, b;
-  attn_work_item(a, (a.L + 127) / 128, qt, head, b);
+  attn_work_item(a, a.h, (a.L + 127) / 128, qt, head, b);
   const int q0 = qt * 128;
   const long long tok0 = static_cast<long long>(b) * a.L;
   const bf16_t* Qg = a.qkv + head * a.kp_qk;
@@ -269,8 +274,8 @@ void attn_fwd_kernel(const AttnArgs a) {
   // key/value tiles stream straight into LDS, one tile ahead of the one being used
   TileStream<DQ> ks;
   TileStream<DV> vs;
-  ks.init(a.qkv + a.h * a.kp_qk + head * a.kp_qk, a.ld_qkv, a.kp_qk);
-  vs.init(a.qkv + 2 * a.h * a.kp_qk + head * a.kp_vo, a.ld_qkv, a.kp_vo);
+  ks.init(a.qkv + k_col(a, head / a.qpk), a.ld_qkv, a.kp_qk);
+  vs.init(a.qkv + v_col(a, head / a.qpk), a.ld_qkv, a.kp_vo);
   ks.issue(Ks(0), tok0, a.L);
   vs.issue(Vs(0), tok0, a.L);
 
@@ -432,7 +437,7 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
 #define Vs(buf) (Vs0 + (buf) * (64 * DV))
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, l32 = lane & 31;
   int qt, head, b;
-  attn_work_item(a, (a.L + 127) / 128, qt, head, b);
+  attn_work_item(a, a.h, (a.L + 127) / 128, qt, head, b);
   const int q0 = qt * 128;
   const long long tok0 = static_cast<long long>(b) * a.L;
   const bf16_t* Qg = a.qkv + head * a.kp_qk;
@@ -442,8 +447,8 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
   // key/value tiles stream straight into LDS, one tile ahead of the one being used
   TileStream<DQ> ks;
   TileStream<DV> vs;
-  ks.init(a.qkv + a.h * a.kp_qk + head * a.kp_qk, a.ld_qkv, a.kp_qk);
-  vs.init(a.qkv + 2 * a.h * a.kp_qk + head * a.kp_vo, a.ld_qkv, a.kp_vo);
+  ks.init(a.qkv + k_col(a, head / a.qpk), a.ld_qkv, a.kp_qk);
+  vs.init(a.qkv + v_col(a, head / a.qpk), a.ld_qkv, a.kp_vo);
   ks.issue(Ks(0), tok0, a.L);
   vs.issue(Vs(0), tok0, a.L);
 
@@ -557,14 +562,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ
 #define lse_s(buf) (stats + (buf) * 64)
 #define dlt_s(buf) (stats + 128 + (buf) * 64)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, l32 = lane & 31;
-  int kt, head, b;
-  attn_work_item(a, (a.L + 127) / 128, kt, head, b);
-  const int k0 = kt * 128;
+  // one workgroup per (128 keys, key/value head, batch element); the query heads that share the key/value head
+  // (Eq. 5) are walked one after the other, their contributions adding up in the same accumulators
+  int kt, kvh, b;
+  attn_work_item(a, a.h_kv, (a.L + 127) / 128, kt, kvh, b);
+  const int k0 = kt * 128, head0 = kvh * a.qpk;
   const long long tok0 = static_cast<long long>(b) * a.L;
-  const bf16_t* Qg = a.qkv + head * a.kp_qk;
-  const bf16_t* Kg = a.qkv + a.h * a.kp_qk + head * a.kp_qk;
-  const bf16_t* Vg = a.qkv + 2 * a.h * a.kp_qk + head * a.kp_vo;
-  const bf16_t* dOg = a.d_o + head * a.kp_vo;
+  const bf16_t* Kg = a.qkv + k_col(a, kvh);
+  const bf16_t* Vg = a.qkv + v_col(a, kvh);
   const int half = tid >> 7, sub = tid & 127;
 
   bf16x8_t kf[DQ / 16], vf[DV / 16];
@@ -589,7 +594,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ
     for (int s = 0; s < DV / 16; ++s) vf[s] = frag_nat<DV>(KVs, wave * 32 + l32, s, hh);
   }
   const int kw0 = k0 + wave * 32, key_idx = kw0 + l32;
-  const long long stat = (static_cast<long long>(b) * a.h + head) * a.L;
   const float sc = a.scale * LOG2E;
 
   floatx16 dk[DQ / 32], dv[DV / 32];
@@ -608,23 +612,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ
   // delta values travel through a register of threads 0..127 and are parked in LDS one iteration later.
   TileStream<DQ> qs;
   TileStream<DV> ds;
-  qs.init(Qg, a.ld_qkv, a.kp_qk);
-  ds.init(dOg, a.ld_o, a.kp_vo);
   float st = 0.f;
-#define KV_ISSUE(j, buf)                                                                               \
+  const int cnt = n_q - j0, n_it = cnt > 0 ? cnt * a.qpk : 0;   // iterations: query heads of the group x their query tiles
+  // iteration `it` is query tile j0 + it % cnt of query head head0 + it / cnt; a new head re-aims the streams
+#define KV_ISSUE(it, buf)                                                                              \
   do {                                                                                                 \
-    qs.issue(Qs(buf), tok0 + (j) * 64, a.L - (j) * 64);                                                \
-    ds.issue(dOs(buf), tok0 + (j) * 64, a.L - (j) * 64);                                               \
-    if (tid < 128) st = (tid < 64 ? a.lse : a.delta)[stat + min((j) * 64 + (tid & 63), a.L - 1)];      \
+    const int hq_ = head0 + (it) / cnt, j_ = j0 + (it) % cnt;                                          \
+    if ((it) % cnt == 0) {                                                                             \
+      qs.init(a.qkv + hq_ * a.kp_qk, a.ld_qkv, a.kp_qk);                                               \
+      ds.init(a.d_o + hq_ * a.kp_vo, a.ld_o, a.kp_vo);                                                 \
+    }                                                                                                  \
+    qs.issue(Qs(buf), tok0 + j_ * 64, a.L - j_ * 64);                                                  \
+    ds.issue(dOs(buf), tok0 + j_ * 64, a.L - j_ * 64);                                                 \
+    if (tid < 128)                                                                                     \
+      st = (tid < 64 ? a.lse : a.delta)[(static_cast<long long>(b) * a.h + hq_) * a.L +                \
+                                        min(j_ * 64 + (tid & 63), a.L - 1)];                           \
   } while (0)
-  if (j0 < n_q) KV_ISSUE(j0, 0);
-  for (int j = j0; j < n_q; ++j) {
-    const int qb0 = j * 64, cur = (j - j0) & 1;
+  if (n_it > 0) KV_ISSUE(0, 0);
+  for (int it = 0; it < n_it; ++it) {
+    const int j = j0 + it % cnt;
+    const int qb0 = j * 64, cur = it & 1;
     if (tid < 64) lse_s(cur)[tid] = st * LOG2E;
     else if (tid < 128) dlt_s(cur)[tid - 64] = st;
     stream_wait();
-    __syncthreads();    // tile j is in LDS; every wavefront is done with tile j-1, whose buffers are refilled now
-    if (j + 1 < n_q) KV_ISSUE(j + 1, cur ^ 1);
+    __syncthreads();    // this tile is in LDS; every wavefront is done with the one before, whose buffers are refilled now
+    if (it + 1 < n_it) KV_ISSUE(it + 1, cur ^ 1);
     if (a.causal && qb0 + 63 < kw0) continue;          // every query of the tile precedes this wave's keys
     const bool need_mask = (a.causal && qb0 < kw0 + 31) || (qb0 + 64 > a.L) || (kw0 + 32 > a.L);
 #pragma unroll
@@ -690,29 +702,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ
 #pragma unroll
   for (int u = 0; u < DQ / 32; ++u) acc_to_tile<DQ>(KVs, wave * 32 + l32, u, dk[u], a.scale, hh);
   __syncthreads();
-  tile_to_global<DQ>(KVs, 128, a.dqkv + a.h * a.kp_qk + head * a.kp_qk, a.ld_qkv, tok0 + k0, a.L - k0, a.kp_qk);
+  tile_to_global<DQ>(KVs, 128, a.dqkv + k_col(a, kvh), a.ld_qkv, tok0 + k0, a.L - k0, a.kp_qk);
   __syncthreads();
 #pragma unroll
   for (int u = 0; u < DV / 32; ++u) acc_to_tile<DV>(KVs, wave * 32 + l32, u, dv[u], 1.f, hh);
   __syncthreads();
-  tile_to_global<DV>(KVs, 128, a.dqkv + 2 * a.h * a.kp_qk + head * a.kp_vo, a.ld_qkv, tok0 + k0, a.L - k0, a.kp_vo);
+  tile_to_global<DV>(KVs, 128, a.dqkv + v_col(a, kvh), a.ld_qkv, tok0 + k0, a.L - k0, a.kp_vo);
 }
 
 // ---------------------------------------------------------------------------------------------
 // rotary embedding, in place on the Q and K column blocks of a [T, nqkv] buffer (Eq. 6):
 // pair (2i, 2i+1) of head g at position t turns by +angle (forward) or -angle (gradients).
 // ---------------------------------------------------------------------------------------------
+// The tables hold one row of angles per key/value head: the query heads that share it (Eq. 5) keep its blocks.
 __global__ __launch_bounds__(256) void rope_kernel(bf16_t* __restrict__ buf, long long ld, const float* __restrict__ cs,
-                                                   const float* __restrict__ sn, int B, int L, int h, int kp_qk,
+                                                   const float* __restrict__ sn, int B, int L, int h, int h_kv, int kp_qk,
                                                    float sign) {
-  const int cpr = 2 * h * kp_qk / 8;   // 16-byte chunks per token over the Q and K blocks
+  const int cpr = (h + h_kv) * kp_qk / 8;   // 16-byte chunks per token over the Q and K blocks
   const long long e = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
   if (e >= static_cast<long long>(B) * L * cpr) return;
   const long long tok = e / cpr;
   const int c = static_cast<int>(e % cpr);
   const int col = c * 8;
-  const int within = col % (h * kp_qk);
-  const int head = within / kp_qk, i0 = (within % kp_qk) / 2;
+  const int qcols = h * kp_qk;
+  const int head = col < qcols ? (col / kp_qk) / (h / h_kv) : (col - qcols) / kp_qk;   // row of the tables
+  const int i0 = (col % kp_qk) / 2;
   const int t = static_cast<int>(tok % L);
   const long long tab = (static_cast<long long>(head) * L + t) * (kp_qk / 2) + i0;
   const float4 c4 = *reinterpret_cast<const float4*>(cs + tab);
@@ -750,10 +764,11 @@ ATTN_INSTANTIATE(64, 64)
 
 template <int DQ, int DV>
 static void launch_core(int which, const AttnArgs& a, hipStream_t st) {
-  const dim3 grid(static_cast<unsigned>((a.L + 127) / 128) * a.h * a.B);
+  const unsigned tiles = static_cast<unsigned>((a.L + 127) / 128);
+  const dim3 grid(tiles * a.h * a.B), grid_kv(tiles * a.h_kv * a.B);
   if (which == 0) hipLaunchKernelGGL((attn_fwd_kernel<DQ, DV>), grid, dim3(256), 0, st, a);
   else if (which == 1) hipLaunchKernelGGL((attn_bwd_dq_kernel<DQ, DV>), grid, dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<DQ, DV>), grid, dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<DQ, DV>), grid_kv, dim3(256), 0, st, a);
 }
 static int dispatch_core(ecospa_ctx* ctx, int which, const AttnArgs& a) {
   const int dq = pad32(a.kp_qk), dv = pad32(a.kp_vo);
@@ -767,9 +782,10 @@ static int dispatch_core(ecospa_ctx* ctx, int which, const AttnArgs& a) {
 }
 
 static int launch_rope(ecospa_ctx* ctx, const ecospa_block_desc& d, void* buf, long long ld, float sign) {
-  const long long tot = static_cast<long long>(d.B) * d.L * (2 * d.h * d.kp_qk / 8);
+  const int h_kv = attn_h_kv(d);
+  const long long tot = static_cast<long long>(d.B) * d.L * ((d.h + h_kv) * d.kp_qk / 8);
   hipLaunchKernelGGL(rope_kernel, dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream,
-                     static_cast<bf16_t*>(buf), ld, d.rope_cos, d.rope_sin, d.B, d.L, d.h, d.kp_qk, sign);
+                     static_cast<bf16_t*>(buf), ld, d.rope_cos, d.rope_sin, d.B, d.L, d.h, h_kv, d.kp_qk, sign);
   ECOSPA_CHECK_LAUNCH(ctx, "rope_kernel");
   return ECOSPA_OK;
 }
@@ -804,6 +820,7 @@ int attn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, 
   a.qkv = static_cast<const bf16_t*>(qkv); a.ld_qkv = nqkv;
   a.o = static_cast<bf16_t*>(o); a.ld_o = nvo; a.lse = lse;
   a.B = d.B; a.L = d.L; a.h = d.h; a.kp_qk = d.kp_qk; a.kp_vo = d.kp_vo; a.causal = d.causal; a.scale = d.scale;
+  a.h_kv = attn_h_kv(d); a.qpk = d.h / a.h_kv;
   if ((rc = dispatch_core(ctx, 0, a))) return rc;
   return ecospa_gemm(ctx, mk_gemm(d.dtype, T, d.d_model, nvo, o, nvo, 0, d.w_o, d.ld_wo, 0, y, d.d_model, d.b_o));
 }
@@ -826,6 +843,7 @@ static int attn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const
   a.o = static_cast<bf16_t*>(sv.o); a.d_o = static_cast<const bf16_t*>(w.d_o); a.ld_o = nvo;
   a.lse = sv.lse; a.delta = w.delta; a.dqkv = static_cast<bf16_t*>(w.dqkv);
   a.B = d.B; a.L = d.L; a.h = d.h; a.kp_qk = d.kp_qk; a.kp_vo = d.kp_vo; a.causal = d.causal; a.scale = d.scale;
+  a.h_kv = attn_h_kv(d); a.qpk = d.h / a.h_kv;
   {
     const long long tot = static_cast<long long>(T) * d.h;
     hipLaunchKernelGGL(attn_delta_kernel, dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream, a);

@@ -29,4 +29,6 @@ int attn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, 
 int attn_backward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, const void* dy,
                   const ecospa_saved& saved, void* dx, const ecospa_grads& g);
 
-static inline int attn_nqkv(const ecospa_block_desc& d) { return 2 * d.h * d.kp_qk + d.h * d.kp_vo; }
+// key/value heads: fewer than query heads under grouped-query attention (Eq. 5)
+static inline int attn_h_kv(const ecospa_block_desc& d) { return d.h_kv > 0 ? d.h_kv : d.h; }
+static inline int attn_nqkv(const ecospa_block_desc& d) { return (d.h + attn_h_kv(d)) * d.kp_qk + attn_h_kv(d) * d.kp_vo; }

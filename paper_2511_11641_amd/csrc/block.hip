@@ -22,6 +22,7 @@ static int validate_block(const ecospa_block_desc* dp) {
   } else {
     if (d.h < 1 || d.kp_qk < 16 || d.kp_vo < 16 || d.kp_qk % 16 || d.kp_vo % 16 || d.kp_qk > 128 || d.kp_vo > 128)
       return ECOSPA_ERR_SHAPE;
+    if (d.h_kv < 0 || d.h % attn_h_kv(d)) return ECOSPA_ERR_SHAPE;
     if (!d.w_qkv || !d.w_o) return ECOSPA_ERR_NULL;
     if ((d.rope_cos == nullptr) != (d.rope_sin == nullptr)) return ECOSPA_ERR_NULL;
     if (d.ld_wqkv < d.d_model || d.ld_wo < static_cast<long long>(d.h) * d.kp_vo) return ECOSPA_ERR_SHAPE;

@@ -21,12 +21,13 @@ struct MapArgs {
   int scatter;
   const int* k_group;   // ragged kept counts (one per group, device memory) or null: every group keeps k
   int ld_idx;           // distance between the index lists of consecutive groups
+  int idx_div;          // heads that share one index list (grouped-query attention): group g uses list g / idx_div
 };
 
 // Kept count of group g: the ragged count is clamped to what the destination and the index list hold.
 __device__ __forceinline__ int map_kept(const MapArgs& m, int g) {
   if (!m.k_group) return m.k;
-  const int kg = m.k_group[g], cap = m.kp < m.ld_idx ? m.kp : m.ld_idx;
+  const int kg = m.k_group[g / m.idx_div], cap = m.kp < m.ld_idx ? m.kp : m.ld_idx;
   return kg < 0 ? 0 : (kg < cap ? kg : cap);
 }
 
@@ -37,11 +38,11 @@ __device__ __forceinline__ long long map_slot(const MapArgs& m, long long s) {
     const int i = rem / m.unit, u = rem % m.unit;
     if (i >= map_kept(m, g)) return -1;
     return static_cast<long long>(g) * m.n +
-           static_cast<long long>(m.idx[static_cast<long long>(g) * m.ld_idx + i]) * m.unit + u;
+           static_cast<long long>(m.idx[static_cast<long long>(g / m.idx_div) * m.ld_idx + i]) * m.unit + u;
   }
   const int g = static_cast<int>(s / m.n), rem = static_cast<int>(s % m.n);
   const int q = rem / m.unit, u = rem % m.unit;
-  const int* list = m.idx + static_cast<long long>(g) * m.ld_idx;
+  const int* list = m.idx + static_cast<long long>(g / m.idx_div) * m.ld_idx;
   const int kg = map_kept(m, g);
   int lo = 0, hi = kg;   // first position with list[pos] >= q
   while (lo < hi) {
@@ -302,6 +303,7 @@ static int validate_map(const ecospa_map_item& q) {
   if (!dtype_ok(q.dtype)) return ECOSPA_ERR_DTYPE;
   if (q.axis != 0 && q.axis != 1) return ECOSPA_ERR_SHAPE;
   if (q.groups < 1 || q.n < 1 || q.unit < 1 || q.n % q.unit || q.other_extent < 1) return ECOSPA_ERR_SHAPE;
+  if (q.idx_div < 0 || (q.idx_div > 1 && q.groups % q.idx_div)) return ECOSPA_ERR_SHAPE;
   if (q.k_group) {      // ragged: the counts live on the device, only the capacities can be checked here
     if (q.kp < 1 || q.ld_idx < 1) return ECOSPA_ERR_K;
   } else if (q.k < 1 || q.k > q.n / q.unit || q.kp < q.k || (q.ld_idx != 0 && q.ld_idx < q.k)) {
@@ -336,7 +338,7 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
       const ecospa_map_item& q = items[first + i];
       MapItemDev& t = b.it[i];
       t.src = q.src; t.dst = q.dst;
-      t.m = MapArgs{q.idx, q.groups, q.n, q.unit, q.k, q.kp, q.scatter ? 1 : 0, q.k_group, q.ld_idx ? q.ld_idx : q.k};
+      t.m = MapArgs{q.idx, q.groups, q.n, q.unit, q.k, q.kp, q.scatter ? 1 : 0, q.k_group, q.ld_idx ? q.ld_idx : q.k, q.idx_div > 0 ? q.idx_div : 1};
       const long long full_slots = static_cast<long long>(q.groups) * q.n;
       const long long cmp_slots = static_cast<long long>(q.groups) * q.kp * q.unit;
       t.dst_slots = q.scatter ? full_slots : cmp_slots;
@@ -384,7 +386,7 @@ static int mapped_copy(ecospa_ctx* ctx, const void* src, void* dst, int dtype, i
   ecospa_map_item q;
   q.src = src; q.dst = dst; q.dtype = dtype; q.axis = axis; q.groups = groups; q.n = n; q.unit = unit; q.k = k;
   q.kp = kp; q.other_extent = other; q.ld_src = ld_src; q.ld_dst = ld_dst; q.idx = idx; q.scatter = scatter;
-  q.k_group = nullptr; q.ld_idx = 0;
+  q.k_group = nullptr; q.ld_idx = 0; q.idx_div = 0;
   return ecospa_compact_batch(ctx, &q, 1);
 }
 

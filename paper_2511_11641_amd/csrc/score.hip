@@ -24,7 +24,8 @@ struct ScorePairDev {
   long long ld1, ld1b, ld2;
   float* a_sq;     // [rows]            squared norms of a_j
   float* b_sq;     // [rows]            squared norms of b_j (rows of W_k, or columns of w2)
-  int rows;        // groups * n
+  int rows1, rows2;  // rows of w1 (groups * rep1 * n) and rows (QK) or columns of w2 (groups * rep2 * n)
+  int rep1, rep2;    // heads of each member that share one group's inner dimensions (grouped-query attention, Eq. 5); 1 otherwise
   int groups, n, unit;
   int d1, d2;
   int kind, dtype;
@@ -127,23 +128,25 @@ __device__ __forceinline__ void rows_sumsq(const T* r, const T* rb, long long ld
 template <int UR>
 __device__ __forceinline__ float pair_unit_value(const ScorePairDev& p, int g, int u, int unit_rows) {
   float a = 0.f, b = 0.f;
-  if (UR > 0) {
+  if (UR > 0) {        // one head per group on both sides
 #pragma unroll
     for (int j = 0; j < UR; ++j) {
       const int row = g * p.n + u * UR + j;
       a += p.a_sq[row];
 #pragma unroll
       for (int q = 0; q < SCORE_MAX_PARTS; ++q) {
-        const float v = p.b_sq[static_cast<long long>(q < p.col_parts ? q : 0) * p.rows + row];
+        const float v = p.b_sq[static_cast<long long>(q < p.col_parts ? q : 0) * p.rows2 + row];
         b += q < p.col_parts ? v : 0.f;
       }
     }
-  } else {
-    for (int j = 0; j < unit_rows; ++j) {
-      const int row = g * p.n + u * unit_rows + j;
-      a += p.a_sq[row];
-      for (int q = 0; q < p.col_parts; ++q) b += p.b_sq[static_cast<long long>(q) * p.rows + row];
-    }
+  } else {             // any unit, any number of heads sharing the group (Eq. 5): heads, then rows, then row ranges, in order
+    for (int h = 0; h < p.rep1; ++h)
+      for (int j = 0; j < unit_rows; ++j) a += p.a_sq[(g * p.rep1 + h) * p.n + u * unit_rows + j];
+    for (int h = 0; h < p.rep2; ++h)
+      for (int j = 0; j < unit_rows; ++j) {
+        const int row = (g * p.rep2 + h) * p.n + u * unit_rows + j;
+        for (int q = 0; q < p.col_parts; ++q) b += p.b_sq[static_cast<long long>(q) * p.rows2 + row];
+      }
   }
   return p.fisher ? p.fw1 * a + p.fw2 * b : sqrtf(a) * sqrtf(b);
 }
@@ -216,13 +219,14 @@ __device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
     if (wb) vec_ok = vec_ok && (p.ld1b % V == 0) && ((reinterpret_cast<uintptr_t>(wb) & 15u) == 0);
     constexpr int NR = SCORE_ROWS_PER_BLOCK / 4;
     const int row0 = local * SCORE_ROWS_PER_BLOCK + wave * NR;
-    if (row0 < p.rows) {
+    const int rows = second ? p.rows2 : p.rows1;
+    if (row0 < rows) {
       float sums[NR];
-      rows_sumsq<T, NR>(w + row0 * ld, wb ? wb + row0 * p.ld1b : nullptr, ld, p.ld1b, len, p.rows - row0, vec_ok, p.fisher != 0, lane, sums);
+      rows_sumsq<T, NR>(w + row0 * ld, wb ? wb + row0 * p.ld1b : nullptr, ld, p.ld1b, len, rows - row0, vec_ok, p.fisher != 0, lane, sums);
       if (lane == 0) {
 #pragma unroll
         for (int j = 0; j < NR; ++j)
-          if (row0 + j < p.rows) out[row0 + j] = sums[j];
+          if (row0 + j < rows) out[row0 + j] = sums[j];
       }
     }
     return;
@@ -240,7 +244,7 @@ __device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
   float acc[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) acc[i] = 0.f;
-  if (vec_ok && col0 + V <= p.rows) {
+  if (vec_ok && col0 + V <= p.rows2) {
     for (int r0 = r_begin + slot; r0 < r_end; r0 += 8 * S) {     // 8 independent loads in flight
       float a[8][V];
 #pragma unroll
@@ -261,7 +265,7 @@ __device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
     for (int r = r_begin + slot; r < r_end; r += S) {
 #pragma unroll
       for (int i = 0; i < V; ++i)
-        if (col0 + i < p.rows) {
+        if (col0 + i < p.rows2) {
           float a = load_f32<T>(w + static_cast<long long>(r) * p.ld2 + col0 + i);
           acc[i] += a * a;
         }
@@ -271,12 +275,12 @@ __device__ void score_block(const ScorePairDev& p, int blk, float* lds) {
 #pragma unroll
   for (int i = 0; i < V; ++i) lds[slot * (W + 1) + ln * V + i] = acc[i];
   __syncthreads();
-  float* out = p.b_sq + static_cast<long long>(part) * p.rows;
+  float* out = p.b_sq + static_cast<long long>(part) * p.rows2;
   for (int c = tid; c < W; c += 256) {
     float tot = 0.f;
     for (int k = 0; k < S; ++k) tot += lds[k * (W + 1) + c];
     const int col = strip * W + c;
-    if (col < p.rows) out[col] = tot;
+    if (col < p.rows2) out[col] = tot;
   }
 }
 
@@ -309,7 +313,8 @@ __global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_kernel(const S
   const ScorePairDev& p = b.p[blockIdx.y];
   const int local = blockIdx.x, tid = threadIdx.x;
   if (local >= p.fin_blocks) return;
-  const int ur = p.fisher ? 1 : p.unit;              // rows per unit: 1, 2 (rotary blocks), or anything (slow form)
+  // rows per unit: 1, 2 (rotary blocks), or the general form (other units, heads sharing a group)
+  const int ur = (p.rep1 > 1 || p.rep2 > 1) ? 0 : (p.fisher ? 1 : p.unit);
   if (p.groups >= SCORE_FIN_WAVES) {
     const int g = local * SCORE_FIN_WAVES + (tid >> 6);
     if (g >= p.groups) return;
@@ -334,15 +339,21 @@ __global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_kernel(const S
 }
 
 // ------------------------------------------------------------------------------------------
+static inline int pair_rep1(const ecospa_pair& q) { return q.rep1 > 0 ? q.rep1 : 1; }
+static inline int pair_rep2(const ecospa_pair& q) { return q.rep2 > 0 ? q.rep2 : 1; }
+
 static int validate_pair(const ecospa_pair& q) {
   if (q.kind < ECOSPA_PAIR_QK || q.kind > ECOSPA_PAIR_FFN_GATED || !dtype_ok(q.dtype)) return ECOSPA_ERR_DTYPE;
   if (!q.w1 || !q.w2 || (q.kind == ECOSPA_PAIR_FFN_GATED && !q.w1b)) return ECOSPA_ERR_NULL;
   if (q.groups < 1 || q.n < 1 || q.unit < 1 || q.d1 < 1 || q.d2 < 1 || q.n % q.unit) return ECOSPA_ERR_SHAPE;
-  const long long rows = static_cast<long long>(q.groups) * q.n;
-  if (rows > (1ll << 30)) return ECOSPA_ERR_SHAPE;
+  if (q.rep1 < 0 || q.rep2 < 0) return ECOSPA_ERR_SHAPE;
+  if ((pair_rep1(q) > 1 || pair_rep2(q) > 1) && q.kind != ECOSPA_PAIR_QK && q.kind != ECOSPA_PAIR_VO) return ECOSPA_ERR_SHAPE;
+  const long long rows1 = static_cast<long long>(q.groups) * pair_rep1(q) * q.n;
+  const long long rows2 = static_cast<long long>(q.groups) * pair_rep2(q) * q.n;
+  if (rows1 > (1ll << 30) || rows2 > (1ll << 30)) return ECOSPA_ERR_SHAPE;
   if (q.ld1 < q.d1) return ECOSPA_ERR_SHAPE;
   if (q.kind == ECOSPA_PAIR_FFN_GATED && q.ld1b < q.d1) return ECOSPA_ERR_SHAPE;
-  if (q.kind == ECOSPA_PAIR_QK ? q.ld2 < q.d2 : q.ld2 < rows) return ECOSPA_ERR_SHAPE;
+  if (q.kind == ECOSPA_PAIR_QK ? q.ld2 < q.d2 : q.ld2 < rows2) return ECOSPA_ERR_SHAPE;
   return ECOSPA_OK;
 }
 
@@ -350,7 +361,7 @@ static int validate_pair(const ecospa_pair& q) {
 struct ColShape { int lanes, strips, parts; };
 static ColShape col_shape(const ecospa_pair& q) {
   const int V = q.dtype == ECOSPA_BF16 ? 8 : 4;
-  const long long rows = static_cast<long long>(q.groups) * q.n;
+  const long long rows = static_cast<long long>(q.groups) * pair_rep2(q) * q.n;
   ColShape c;
   c.lanes = 8;        // one 128-byte line per row: wider strips measured slower (fewer, longer workgroups)
   c.strips = static_cast<int>((rows + c.lanes * V - 1) / (c.lanes * V));
@@ -360,9 +371,9 @@ static ColShape col_shape(const ecospa_pair& q) {
 }
 
 static size_t pair_ws_bytes(const ecospa_pair& q) {
-  const size_t rows = static_cast<size_t>(q.groups) * q.n;
+  const size_t rows1 = static_cast<size_t>(q.groups) * pair_rep1(q) * q.n, rows2 = static_cast<size_t>(q.groups) * pair_rep2(q) * q.n;
   const size_t parts = q.kind == ECOSPA_PAIR_QK ? 1 : col_shape(q).parts;
-  return align_up(rows * 4, 256) + align_up(parts * rows * 4, 256);   // a_sq, b_sq (partial sums)
+  return align_up(rows1 * 4, 256) + align_up(parts * rows2 * 4, 256);   // a_sq, b_sq (partial sums)
 }
 
 extern "C" size_t ecospa_score_workspace_bytes(const ecospa_pair* pairs, int n_pairs) {
@@ -399,24 +410,25 @@ static int score_run(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, flo
       ScorePairDev& p = b.p[i];
       p.w1 = q.w1; p.w1b = (q.kind == ECOSPA_PAIR_FFN_GATED) ? q.w1b : nullptr; p.w2 = q.w2;
       p.ld1 = q.ld1; p.ld1b = q.ld1b; p.ld2 = q.ld2;
-      p.rows = q.groups * q.n;
+      p.rep1 = pair_rep1(q); p.rep2 = pair_rep2(q);
+      p.rows1 = q.groups * p.rep1 * q.n; p.rows2 = q.groups * p.rep2 * q.n;
       p.groups = q.groups; p.n = q.n; p.unit = q.unit;
       p.d1 = q.d1; p.d2 = q.d2; p.kind = q.kind; p.dtype = q.dtype; p.fisher = fisher;
-      p.a_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows) * 4));
-      const int row_blocks = (p.rows + SCORE_ROWS_PER_BLOCK - 1) / SCORE_ROWS_PER_BLOCK;
+      p.a_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows1) * 4));
+      const int row_blocks = (p.rows1 + SCORE_ROWS_PER_BLOCK - 1) / SCORE_ROWS_PER_BLOCK;
       p.blk_row1 = blk;
       b.first_blk[i] = blk;
       blk += row_blocks;
       p.blk_row2 = blk;
       p.col_lanes = 8; p.col_strips = 1; p.col_parts = 1;
       if (q.kind == ECOSPA_PAIR_QK) {
-        p.b_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows) * 4));
-        blk += row_blocks;
+        p.b_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows2) * 4));
+        blk += (p.rows2 + SCORE_ROWS_PER_BLOCK - 1) / SCORE_ROWS_PER_BLOCK;
         p.blk_col = blk;
       } else {
         const ColShape c = col_shape(q);
         p.col_lanes = c.lanes; p.col_strips = c.strips; p.col_parts = c.parts;
-        p.b_sq = static_cast<float*>(ws.take(static_cast<size_t>(c.parts) * p.rows * 4));
+        p.b_sq = static_cast<float*>(ws.take(static_cast<size_t>(c.parts) * p.rows2 * 4));
         p.blk_col = blk;
         blk += c.strips * c.parts;
       }
@@ -425,8 +437,8 @@ static int score_run(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, flo
       if (p.fin_blocks > fin) fin = p.fin_blocks;
       p.scores = scores[first + i];
       const double members = q.kind == ECOSPA_PAIR_FFN_GATED ? 2.0 : 1.0;   // W_gate and W_up form the first member
-      p.fw1 = fisher ? static_cast<float>(0.5 / (members * q.n * static_cast<double>(q.d1) * n_samples)) : 0.f;
-      p.fw2 = fisher ? static_cast<float>(0.5 / (q.n * static_cast<double>(q.d2) * n_samples)) : 0.f;
+      p.fw1 = fisher ? static_cast<float>(0.5 / (members * p.rep1 * q.n * static_cast<double>(q.d1) * n_samples)) : 0.f;
+      p.fw2 = fisher ? static_cast<float>(0.5 / (static_cast<double>(p.rep2) * q.n * static_cast<double>(q.d2) * n_samples)) : 0.f;
     }
     if (!ws.ok()) return ECOSPA_ERR_WORKSPACE;
     hipLaunchKernelGGL(score_sumsq_kernel, dim3(blk), dim3(256), 0, ctx->stream, b);

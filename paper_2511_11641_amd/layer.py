@@ -96,11 +96,16 @@ class FfnBlock:
 
 
 class AttnBlock:
-    """Compacted attention block: per-head W_q/W_k pairs and W_v/W_o pairs (Eq. 4), optional RoPE."""
+    """Compacted attention block: per-head W_q/W_k pairs and W_v/W_o pairs (Eq. 4), optional RoPE.
+    With h_kv < h (grouped-query attention, Eq. 5) W_k and W_v hold h_kv heads, and the h / h_kv query heads
+    (and heads of W_o) of a group keep the inner dimensions of the key/value head they share."""
 
     def __init__(self, ctx: B.Context, wq, wk, wv, wo, bq, bk, bv, bo, h: int, d_h: int, *, rope: bool,
-                 causal: bool = True, rope_base: float = 10000.0):
+                 causal: bool = True, rope_base: float = 10000.0, h_kv: Optional[int] = None):
         self.ctx, self.h, self.d_h, self.rope, self.causal, self.rope_base = ctx, h, d_h, rope, causal, rope_base
+        self.h_kv = h if h_kv is None else h_kv
+        assert h % self.h_kv == 0
+        self.qpk = h // self.h_kv
         self.wq, self.wk, self.wv, self.wo = wq, wk, wv, wo
         self.bq, self.bk, self.bv, self.bo = bq, bk, bv, bo
         self.d = wq.shape[1]
@@ -108,8 +113,8 @@ class AttnBlock:
 
     def pairs(self):
         mk = B.Context.make_pair
-        return [mk(B.PAIR_QK, self.wq, self.wk, self.h, self.d_h, self.unit),
-                mk(B.PAIR_VO, self.wv, self.wo, self.h, self.d_h, 1)]
+        return [mk(B.PAIR_QK, self.wq, self.wk, self.h_kv, self.d_h, self.unit, rep1=self.qpk),
+                mk(B.PAIR_VO, self.wv, self.wo, self.h_kv, self.d_h, 1, rep2=self.qpk)]
 
     def score(self):
         return self.ctx.ecospa_coupled_score(self.pairs())
@@ -119,7 +124,7 @@ class AttnBlock:
         """Gather the kept dimensions.  With k_qk_group / k_vo_group (int32[h] on the device, the kept counts of the
         cumulative-threshold rule) every head keeps a count of its own: idx_* are then [h, n_units] lists whose first
         k_*_group[g] entries count, and all heads are padded with zeros to the largest count (read back once here)."""
-        c, h, dh, u = self.ctx, self.h, self.d_h, self.unit
+        c, h, hk, dh, u = self.ctx, self.h, self.h_kv, self.d_h, self.unit
         self.idx_qk, self.idx_vo = idx_qk, idx_vo
         self.k_qk_group, self.k_vo_group = k_qk_group, k_vo_group
         self.k_qk_units = idx_qk.shape[1] if k_qk_group is None else int(k_qk_group.max().item())
@@ -127,24 +132,28 @@ class AttnBlock:
         self.kp_qk = B.round_up(self.k_qk_units * u, 16)
         self.kp_vo = B.round_up(self.k_vo, 16)
         kpu = self.kp_qk // u
-        nq, nv = h * self.kp_qk, h * self.kp_vo
+        # compact layout: the h query heads, then the h_kv key heads, then the h_kv value heads; W_o has h heads
+        nq, nk, nv, no = h * self.kp_qk, hk * self.kp_qk, hk * self.kp_vo, h * self.kp_vo
+        self.nq, self.nk = nq, nk
         dt, dev = self.wq.dtype, self.wq.device
-        if getattr(self, "wqkv_c", None) is None or self.wqkv_c.shape[0] != 2 * nq + nv:
-            self.wqkv_c = torch.empty((2 * nq + nv, self.d), dtype=dt, device=dev)
-            self.bqkv_c = None if self.bq is None else torch.empty((2 * nq + nv,), dtype=dt, device=dev)
-            self.wo_c = torch.empty((self.d, nv), dtype=dt, device=dev)
+        if getattr(self, "wqkv_c", None) is None or self.wqkv_c.shape[0] != nq + nk + nv:
+            self.wqkv_c = torch.empty((nq + nk + nv, self.d), dtype=dt, device=dev)
+            self.bqkv_c = None if self.bq is None else torch.empty((nq + nk + nv,), dtype=dt, device=dev)
+            self.wo_c = torch.empty((self.d, no), dtype=dt, device=dev)
 
-        def mq(src, dst, axis):
-            return B.Context.map_item(src, dst, idx_qk, axis, h, dh, u, kpu, k_group=k_qk_group)
+        def mq(src, dst, axis, heads):      # heads that share an index list with (heads // h_kv - 1) others
+            return B.Context.map_item(src, dst, idx_qk, axis, heads, dh, u, kpu, k_group=k_qk_group, idx_div=heads // hk)
 
-        def mv(src, dst, axis):
-            return B.Context.map_item(src, dst, idx_vo, axis, h, dh, 1, self.kp_vo, k_group=k_vo_group)
+        def mv(src, dst, axis, heads):
+            return B.Context.map_item(src, dst, idx_vo, axis, heads, dh, 1, self.kp_vo, k_group=k_vo_group,
+                                      idx_div=heads // hk)
 
-        items = [mq(self.wq, self.wqkv_c[:nq], 0), mq(self.wk, self.wqkv_c[nq:2 * nq], 0), mv(self.wv, self.wqkv_c[2 * nq:], 0)]
+        items = [mq(self.wq, self.wqkv_c[:nq], 0, h), mq(self.wk, self.wqkv_c[nq:nq + nk], 0, hk),
+                 mv(self.wv, self.wqkv_c[nq + nk:], 0, hk)]
         if self.bq is not None:
-            items += [mq(self.bq, self.bqkv_c[:nq], 1), mq(self.bk, self.bqkv_c[nq:2 * nq], 1),
-                      mv(self.bv, self.bqkv_c[2 * nq:], 1)]
-        items.append(mv(self.wo, self.wo_c, 1))
+            items += [mq(self.bq, self.bqkv_c[:nq], 1, h), mq(self.bk, self.bqkv_c[nq:nq + nk], 1, hk),
+                      mv(self.bv, self.bqkv_c[nq + nk:], 1, hk)]
+        items.append(mv(self.wo, self.wo_c, 1, h))
         if not defer:
             c.ecospa_compact_batch(items)
         if self.rope and getattr(self, "cos", None) is not None:     # kept blocks changed: new frequencies
@@ -155,7 +164,7 @@ class AttnBlock:
         if self.k_qk_group is not None:
             return self.ctx.ecospa_rope_table_ragged(self.idx_qk, self.k_qk_group, L, self.kp_qk // 2, self.d_h,
                                                      self.rope_base, out=out)
-        return self.ctx.ecospa_rope_table(self.idx_qk, self.h, L, self.k_qk_units, self.kp_qk // 2, self.d_h,
+        return self.ctx.ecospa_rope_table(self.idx_qk, self.h_kv, L, self.k_qk_units, self.kp_qk // 2, self.d_h,
                                           self.rope_base, out=out)
 
     def alloc(self, Bsz: int, L: int):
@@ -169,6 +178,7 @@ class AttnBlock:
         d = B.BlockDesc()
         d.block, d.dtype, d.B, d.L, d.d_model = B.BLOCK_ATTN, B.dtype_code(dt), Bsz, L, self.d
         d.h, d.kp_qk, d.kp_vo, d.causal = h, self.kp_qk, self.kp_vo, int(self.causal)
+        d.h_kv = self.h_kv
         d.scale = float(self.d_h) ** -0.5
         d.rope_cos, d.rope_sin = B._ptr(self.cos), B._ptr(self.sin)
         d.w_qkv, d.b_qkv, d.w_o, d.b_o = self.wqkv_c.data_ptr(), B._ptr(self.bqkv_c), self.wo_c.data_ptr(), B._ptr(self.bo)

@@ -1,0 +1,114 @@
+"""GPU parity (through the C ABI) of grouped-query coupling (Eq. 5): group-joint scores and pair importances of
+query heads that share a key/value head, gathers with a shared index list, and the attention block forward and
+backward with shared key/value heads, against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ecospa_oracle as O
+from paper_2511_11641_amd import binding as B
+from paper_2511_11641_amd import synth
+from paper_2511_11641_amd.layer import AttnBlock
+from util import assert_close, dev, host, pad_cols, pad_rows
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    return B.Context("cuda:0")
+
+
+def _gqa_layer(seed, Bsz, L, d, h, hkv, dh, dtype, bias):
+    """An attention layer whose W_k, W_v (b_k, b_v) hold hkv heads: the first hkv heads of a seeded h-head layer."""
+    t = synth.attn_layer(seed, Bsz, L, d, h, dh, dtype=dtype, structure="pretrained", bias=bias)
+    for nm in ("wk", "wv"):
+        t[nm] = np.ascontiguousarray(t[nm][:hkv * dh])
+    if bias:
+        for nm in ("bk", "bv"):
+            t[nm] = np.ascontiguousarray(t[nm][:hkv * dh])
+    return t
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("h,hkv,dh,d,unit", [(32, 8, 64, 2048, 2), (16, 4, 64, 1024, 1), (6, 2, 8, 40, 1), (4, 1, 16, 24, 2)])
+def test_group_joint_scores_and_importances(ctx, h, hkv, dh, d, unit, dtype):
+    m = h // hkv
+    t = _gqa_layer(100 + h, 1, 2, d, h, hkv, dh, dtype, False)
+    g = {nm: dev(t[nm], dtype) for nm in ("wq", "wk", "wv", "wo")}
+    mk = B.Context.make_pair
+    pairs = [mk(B.PAIR_QK, g["wq"], g["wk"], hkv, dh, unit, rep1=m), mk(B.PAIR_VO, g["wv"], g["wo"], hkv, dh, 1, rep2=m)]
+    s_qk, s_vo = ctx.ecospa_coupled_score(pairs)
+    assert s_qk.shape == (hkv, dh // unit) and s_vo.shape == (hkv, dh)
+    assert_close(s_qk, O.coupled_score(O.PAIR_QK, t["wq"], t["wk"], hkv, dh, unit, rep1=m), "f32", "QK scores")
+    assert_close(s_vo, O.coupled_score(O.PAIR_VO, t["wv"], t["wo"], hkv, dh, 1, rep2=m), "f32", "VO scores")
+    f_qk, f_vo = ctx.ecospa_pair_fisher(pairs, 64.0)
+    assert_close(f_qk, O.pair_fisher(O.PAIR_QK, t["wq"], t["wk"], hkv, dh, 64.0, rep1=m), "f32", "QK importance")
+    assert_close(f_vo, O.pair_fisher(O.PAIR_VO, t["wv"], t["wo"], hkv, dh, 64.0, rep2=m), "f32", "VO importance")
+
+
+def test_gather_with_a_shared_index_list(ctx):
+    h, hkv, dh, d = 8, 2, 16, 24
+    m = h // hkv
+    rng = np.random.default_rng(5)
+    idx = np.stack([np.sort(rng.choice(dh, 6, replace=False)) for _ in range(hkv)]).astype(np.int32)
+    w = synth.normal(110, 1, (h * dh, d)).astype(np.float32)
+    gi = torch.from_numpy(idx).cuda()
+    out = torch.empty((h * 8, d), device="cuda")
+    ctx.ecospa_compact_batch([B.Context.map_item(torch.from_numpy(w).cuda(), out, gi, 0, h, dh, 1, 8, idx_div=m)])
+    want = pad_rows(O.compact(w, np.repeat(idx, m, axis=0), 0, dh), h, 6, 8)
+    assert np.array_equal(host(out), want.astype(np.float64))
+    wt = np.ascontiguousarray(w.T)
+    out2 = torch.empty((d, h * 8), device="cuda")
+    ctx.ecospa_compact_batch([B.Context.map_item(torch.from_numpy(wt).cuda(), out2, gi, 1, h, dh, 1, 8, idx_div=m)])
+    assert np.array_equal(host(out2), pad_cols(O.compact(wt, np.repeat(idx, m, axis=0), 1, dh), h, 6, 8).astype(np.float64))
+    with pytest.raises(B.EcospaError) as e:
+        ctx.ecospa_compact_batch([B.Context.map_item(torch.from_numpy(w).cuda(), out, gi, 0, h, dh, 1, 8, idx_div=3)])
+    assert e.value.code == B.ERR_SHAPE
+
+
+@pytest.mark.parametrize("h,hkv,d,k_qk,k_vo,rope,causal,L", [(8, 2, 256, 32, 32, False, True, 200), (8, 2, 256, 32, 48, True, True, 200),
+                                                              (6, 3, 192, 64, 64, False, False, 197), (4, 1, 128, 20, 32, True, True, 300),
+                                                              (32, 8, 2048, 32, 32, True, True, 256)])
+def test_gqa_attention_block(ctx, h, hkv, d, k_qk, k_vo, rope, causal, L):
+    Bsz, dh, dtype = 2, 64, "bf16"
+    m, unit = h // hkv, 2 if rope else 1
+    bias = not rope
+    t = _gqa_layer(120 + h, Bsz, L, d, h, hkv, dh, dtype, bias)
+    g = {nm: dev(a, dtype) for nm, a in t.items()}
+    blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g.get("bq"), g.get("bk"), g.get("bv"), g.get("bo"),
+                    h, dh, rope=rope, causal=causal, h_kv=hkv)
+    s_qk, s_vo = blk.score()
+    iq_d = ctx.ecospa_select_topk(s_qk, k_qk // unit)
+    iv_d = ctx.ecospa_select_topk(s_vo, k_vo)
+    iq, iv = O.select_topk(s_qk.cpu().numpy(), k_qk // unit), O.select_topk(s_vo.cpu().numpy(), k_vo)
+    assert np.array_equal(iq_d.cpu().numpy(), iq) and np.array_equal(iv_d.cpu().numpy(), iv)
+    blk.compact(iq_d, iv_d).alloc(Bsz, L)
+    y = blk.fwd(g["x"])
+    dx = blk.bwd(g["x"], g["dy"])
+    torch.cuda.synchronize()
+
+    iq_h, iv_h = np.repeat(iq, m, axis=0), np.repeat(iv, m, axis=0)       # every query head keeps its group's dimensions
+    wq = O.heads_rows(O.compact(t["wq"], iq_h, 0, dh, unit), h)
+    wk = O.heads_rows(O.compact(t["wk"], iq, 0, dh, unit), hkv)
+    wv = O.heads_rows(O.compact(t["wv"], iv, 0, dh), hkv)
+    wo = O.heads_cols(O.compact(t["wo"], iv_h, 1, dh), h)
+    kw = {}
+    if bias:
+        kw = dict(bq=O.compact(t["bq"], iq_h, 0, dh, unit).reshape(h, -1), bk=O.compact(t["bk"], iq, 0, dh, unit).reshape(hkv, -1),
+                  bv=O.compact(t["bv"], iv, 0, dh).reshape(hkv, -1), bo=t["bo"])
+    ang = O.rope_angles(iq_h, L, dh) if rope else None
+    scale = dh ** -0.5
+    yo, sv = O.attn_fwd(t["x"], wq, wk, wv, wo, Bsz, L, scale, causal, angles=ang, **kw)
+    go = O.attn_bwd(t["x"], t["dy"], wq, wk, wv, wo, Bsz, L, scale, sv, angles=ang)
+    assert_close(y, yo, dtype, "y")
+    assert_close(dx, go["dx"], dtype, "dx")
+    kpq, kpv = blk.kp_qk, blk.kp_vo
+    nq, nk = h * kpq, hkv * kpq
+    assert_close(blk.dwqkv_c[:nq], pad_rows(go["dwq"].reshape(h * k_qk, d), h, k_qk, kpq), dtype, "dW_q")
+    assert_close(blk.dwqkv_c[nq:nq + nk], pad_rows(go["dwk"].reshape(hkv * k_qk, d), hkv, k_qk, kpq), dtype, "dW_k")
+    assert_close(blk.dwqkv_c[nq + nk:], pad_rows(go["dwv"].reshape(hkv * k_vo, d), hkv, k_vo, kpv), dtype, "dW_v")
+    assert_close(blk.dwo_c, pad_cols(go["dwo"].transpose(1, 0, 2).reshape(d, h * k_vo), h, k_vo, kpv), dtype, "dW_o")
+    if bias:
+        assert_close(blk.dbqkv_c[nq + nk:], pad_rows(go["dbv"].reshape(-1), hkv, k_vo, kpv), dtype, "db_v")
+        assert_close(blk.dbo, go["dbo"], dtype, "db_o")

@@ -110,3 +110,22 @@ def test_gqa_equals_multi_head_attention_on_replicated_heads():
     np.testing.assert_allclose(g["dx"], g2["dx"], rtol=1e-12, atol=1e-14)
     np.testing.assert_allclose(g["dwk"], g2["dwk"].reshape(hkv, m, dh, d).sum(axis=1), rtol=1e-12, atol=1e-14)
     np.testing.assert_allclose(g["dwv"], g2["dwv"].reshape(hkv, m, dh, d).sum(axis=1), rtol=1e-12, atol=1e-14)
+
+
+def test_pair_importance_of_a_group_is_the_mean_over_all_its_heads():
+    """Eq. 8 with shared heads: each member's mean squared gradient runs over every head of the group - element
+    loops, and the constant-gradient closed form c^2 / |D|."""
+    hkv, m, dh, d, D = 2, 3, 4, 5, 7.0
+    gq = synth.normal(70, 1, (hkv * m * dh, d)).astype(np.float64)
+    gk = synth.normal(70, 2, (hkv * dh, d)).astype(np.float64)
+    go = synth.normal(70, 3, (d, hkv * m * dh)).astype(np.float64)
+    got_qk = O.pair_fisher(O.PAIR_QK, gq, gk, hkv, dh, D, rep1=m)
+    got_vo = O.pair_fisher(O.PAIR_VO, gk, go, hkv, dh, D, rep2=m)
+    for g in range(hkv):
+        s1 = sum(gq[r, c] ** 2 for r in range(g * m * dh, (g + 1) * m * dh) for c in range(d)) / (m * dh * d)
+        s2 = sum(gk[r, c] ** 2 for r in range(g * dh, (g + 1) * dh) for c in range(d)) / (dh * d)
+        s3 = sum(go[r, c] ** 2 for r in range(d) for c in range(g * m * dh, (g + 1) * m * dh)) / (m * dh * d)
+        np.testing.assert_allclose(got_qk[g], 0.5 * (s1 + s2) / D, rtol=1e-13)
+        np.testing.assert_allclose(got_vo[g], 0.5 * (s2 + s3) / D, rtol=1e-13)
+    c = O.pair_fisher(O.PAIR_QK, np.full_like(gq, 0.5), np.full_like(gk, 0.5), hkv, dh, D, rep1=m)
+    np.testing.assert_allclose(c, np.full(hkv, 0.25 / D), rtol=1e-14)
