@@ -24,12 +24,15 @@ def ctx():
     return B.Context("cuda:0")
 
 
-@pytest.mark.parametrize("name", ["c2_gpt2m_layer", "c3_llama1b_layer"])
-def test_full_layer_step_matches_oracle(ctx, name):
+@pytest.mark.parametrize("name,num,den", [("c2_gpt2m_layer", 1, 2), ("c3_llama1b_layer", 1, 2),
+                                          ("c2_gpt2m_layer", 3, 4), ("c2_gpt2m_layer", 3, 10)])
+def test_full_layer_step_matches_oracle(ctx, name, num, den):
+    """Keep ratios 1/2 (both layers), and 3/4 and 3/10 on the GPT-2-Medium-shaped layer (kept head widths 48 and 19:
+    padded compact layouts, unequal tile counts)."""
     cfg = dict(synth.CONFIGS[name])
     Bsz, L, d, h, dh, dff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
     unit = 2 if cfg["rope"] else 1
-    lay = bench.Layer(ctx, cfg, cfg["seed"], 1, 2)
+    lay = bench.Layer(ctx, cfg, cfg["seed"], num, den)
     lay.step()
     torch.cuda.synchronize()
     a, f = lay.host["attn"], lay.host["ffn"]
