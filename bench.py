@@ -73,8 +73,8 @@ class Layer:
         self.x, self.dy = g["x"], g["dy"]
         act = B.ACT_SWIGLU if cfg["gated"] else B.ACT_GELU_ERF
         self.attn = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g.get("bq"), g.get("bk"), g.get("bv"),
-                              g.get("bo"), h, dh, rope=cfg["rope"], causal=True)
-        self.ffn = FfnBlock(ctx, gf["w1"], gf.get("b1"), gf["w2"], gf.get("b2"), act, gf.get("w1b"))
+                              g.get("bo"), h, dh, rope=cfg["rope"], causal=True, transposed=True)
+        self.ffn = FfnBlock(ctx, gf["w1"], gf.get("b1"), gf["w2"], gf.get("b2"), act, gf.get("w1b"), transposed=True)
         unit = 2 if cfg["rope"] else 1
         self.k_qk_units = (dh // unit) * keep_num // keep_den
         self.k_vo = dh * keep_num // keep_den
@@ -99,6 +99,10 @@ class Layer:
     def compact(self):      # one launch for every matrix and bias of the layer
         items = self.attn.compact(self.idx[0], self.idx[1], defer=True) + self.ffn.compact(self.idx[2], defer=True)
         self.ctx.ecospa_compact_batch(items)
+        # transposed copies of the compact weights for the input-gradient contractions (one launch)
+        tr = self.attn.transpose_items() + self.ffn.transpose_items()
+        if tr:
+            self.ctx.ecospa_transpose_batch(tr)
 
     def prune(self):
         self.score()

@@ -233,6 +233,20 @@ typedef struct {
 int ecospa_adamw(ecospa_ctx* ctx, const ecospa_adamw_item* items /*host*/, int n_items,
                  const ecospa_adamw_hyper* hp /*host*/);
 
+/* Transposed copies of (compact) matrices: dst[c, r] = src[r, c] for r < rows, c < cols, any 2- or 4-byte
+ * dtype; all items in one launch; source and destination must not overlap.  The backward pass reads the
+ * compact weights with the contraction index slow (dX = dY W); given a transposed copy beside the matrix
+ * (the *_t fields of ecospa_block_desc) it runs the faster x W^T form.  A copy has to be refreshed
+ * whenever its matrix changes (after ecospa_compact, after ecospa_adamw).
+ * Errors: ERR_NULL, ERR_DTYPE, ERR_SHAPE (extents < 1, ld_src < cols, ld_dst < rows). */
+typedef struct {
+  const void* src;   /* [rows, cols], ld_src */
+  void* dst;         /* [cols, rows], ld_dst */
+  int dtype, rows, cols;
+  long long ld_src, ld_dst;
+} ecospa_transpose_item;
+int ecospa_transpose_batch(ecospa_ctx* ctx, const ecospa_transpose_item* items /*host*/, int n_items);
+
 /* cos/sin tables of the KEPT rotary blocks (Eq. 6; "position matrices are then adjusted to match
  * new dimensions", footnote to Eq. 10): for head g, position t < L, kept block i < k,
  *   angle = t * base^(-2 * idx[g*k+i] / d_h)   with d_h the ORIGINAL head width,
@@ -279,6 +293,12 @@ typedef struct {
   long long ld_w1, ld_w2;
   /* ATTN, grouped-query attention */
   int h_kv;                  /* key/value heads; 0: as many as query heads                    */
+  /* optional transposed copies of the weights for the backward pass (ecospa_transpose_batch), NULL: none.
+   * w_qkv_t [d_model, nqkv], w_o_t [h*kp_vo, d_model], w_1_t [d_model, (1|2)*kp_ff], w_2_t [kp_ff, d_model];
+   * leading dimensions multiples of 8, pointers 16-byte aligned.  Only the input-gradient contractions
+   * read them; the results are those of the untransposed path up to the order of summation. */
+  const void *w_qkv_t, *w_o_t, *w_1_t, *w_2_t;
+  long long ld_wqkvt, ld_wot, ld_w1t, ld_w2t;
 } ecospa_block_desc;
 
 /* Activations the forward pass keeps for the backward pass; caller-allocated, dense row-major.

@@ -27,7 +27,7 @@ EXPORTS = (
     "ecospa_scatter", "ecospa_rope_table", "ecospa_block_workspace_bytes", "ecospa_coupled_fwd",
     "ecospa_coupled_bwd", "ecospa_profile_gemm", "ecospa_profile_gemm_read", "ecospa_contract",
     "ecospa_select_topk_batch", "ecospa_compact_batch", "ecospa_pair_fisher", "ecospa_select_theta",
-    "ecospa_select_pairs", "ecospa_rope_table_ragged", "ecospa_adamw",
+    "ecospa_select_pairs", "ecospa_rope_table_ragged", "ecospa_adamw", "ecospa_transpose_batch",
 )
 
 
@@ -51,7 +51,9 @@ class BlockDesc(C.Structure):
                 ("ld_wqkv", C.c_longlong), ("ld_wo", C.c_longlong),
                 ("kp_ff", C.c_int), ("act", C.c_int),
                 ("w_1", C.c_void_p), ("b_1", C.c_void_p), ("w_2", C.c_void_p), ("b_2", C.c_void_p),
-                ("ld_w1", C.c_longlong), ("ld_w2", C.c_longlong), ("h_kv", C.c_int)]
+                ("ld_w1", C.c_longlong), ("ld_w2", C.c_longlong), ("h_kv", C.c_int),
+                ("w_qkv_t", C.c_void_p), ("w_o_t", C.c_void_p), ("w_1_t", C.c_void_p), ("w_2_t", C.c_void_p),
+                ("ld_wqkvt", C.c_longlong), ("ld_wot", C.c_longlong), ("ld_w1t", C.c_longlong), ("ld_w2t", C.c_longlong)]
 
 
 class SelectItem(C.Structure):
@@ -64,6 +66,11 @@ class MapItem(C.Structure):
                 ("n", C.c_int), ("unit", C.c_int), ("k", C.c_int), ("kp", C.c_int), ("scatter", C.c_int),
                 ("other_extent", C.c_longlong), ("ld_src", C.c_longlong), ("ld_dst", C.c_longlong),
                 ("idx", C.c_void_p), ("k_group", C.c_void_p), ("ld_idx", C.c_int), ("idx_div", C.c_int)]
+
+
+class TransposeItem(C.Structure):
+    _fields_ = [("src", C.c_void_p), ("dst", C.c_void_p), ("dtype", C.c_int), ("rows", C.c_int), ("cols", C.c_int),
+                ("ld_src", C.c_longlong), ("ld_dst", C.c_longlong)]
 
 
 class AdamwItem(C.Structure):
@@ -133,6 +140,8 @@ def load() -> C.CDLL:
     lib.ecospa_rope_table.restype = ci
     lib.ecospa_rope_table_ragged.argtypes = [vp, vp, ci, vp, ci, ci, ci, ci, C.c_double, vp, vp]
     lib.ecospa_rope_table_ragged.restype = ci
+    lib.ecospa_transpose_batch.argtypes = [vp, C.POINTER(TransposeItem), ci]
+    lib.ecospa_transpose_batch.restype = ci
     lib.ecospa_adamw.argtypes = [vp, C.POINTER(AdamwItem), ci, C.POINTER(AdamwHyper)]
     lib.ecospa_adamw.restype = ci
     lib.ecospa_block_workspace_bytes.argtypes = [C.POINTER(BlockDesc)]
@@ -394,6 +403,17 @@ class Context:
                                                       d_h, float(base), cos.data_ptr(), sin.data_ptr()),
                     "ecospa_rope_table_ragged")
         return cos, sin
+
+    @staticmethod
+    def transpose_item(src: torch.Tensor, dst: torch.Tensor) -> TransposeItem:
+        assert src.dim() == 2 and dst.shape == (src.shape[1], src.shape[0]) and src.dtype == dst.dtype
+        return TransposeItem(src.data_ptr(), dst.data_ptr(), dtype_code(src.dtype), src.shape[0], src.shape[1],
+                             src.stride(0), dst.stride(0))
+
+    def ecospa_transpose_batch(self, items: Sequence[TransposeItem]):
+        """dst = src^T for every item, one launch (see :meth:`transpose_item`)."""
+        arr = items if isinstance(items, C.Array) else (TransposeItem * len(items))(*items)
+        self._check(self.lib.ecospa_transpose_batch(self.h, arr, len(arr)), "ecospa_transpose_batch")
 
     # ---- parameter update ----------------------------------------------------------------------
     @staticmethod

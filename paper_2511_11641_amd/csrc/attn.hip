@@ -835,7 +835,9 @@ static int attn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const
   GemmDesc go = mk_gemm(d.dtype, dm, nvo, T, dy, dm, 1, sv.o, nvo, 1, gr.dw_o, gr.ld_dwo, nullptr);
   go.splits = ecospa_gemm_splits(dm, nvo, T); go.partial = w.partial; go.defer_reduce = 1;
   if (gr.dw_o && (rc = ecospa_gemm(ctx, go))) return rc;
-  if ((rc = ecospa_gemm(ctx, mk_gemm(d.dtype, T, nvo, dm, dy, dm, 0, d.w_o, d.ld_wo, 1, w.d_o, nvo, nullptr)))) return rc;
+  if ((rc = ecospa_gemm(ctx, d.w_o_t ? mk_gemm(d.dtype, T, nvo, dm, dy, dm, 0, d.w_o_t, d.ld_wot, 0, w.d_o, nvo, nullptr)   // transposed copy [nvo, d_model]
+                                     : mk_gemm(d.dtype, T, nvo, dm, dy, dm, 0, d.w_o, d.ld_wo, 1, w.d_o, nvo, nullptr))))
+    return rc;
 
   AttnArgs a;
   memset(&a, 0, sizeof(a));
@@ -859,7 +861,8 @@ static int attn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const
   if (gr.dw_qkv && (rc = ecospa_gemm(ctx, gq))) return rc;
 
   // dX = dQKV W_qkv
-  if (dx && (rc = ecospa_gemm(ctx, mk_gemm(d.dtype, T, dm, nqkv, w.dqkv, nqkv, 0, d.w_qkv, d.ld_wqkv, 1, dx, dm, nullptr))))
+  if (dx && (rc = ecospa_gemm(ctx, d.w_qkv_t ? mk_gemm(d.dtype, T, dm, nqkv, w.dqkv, nqkv, 0, d.w_qkv_t, d.ld_wqkvt, 0, dx, dm, nullptr)   // [d_model, nqkv]
+                                             : mk_gemm(d.dtype, T, dm, nqkv, w.dqkv, nqkv, 0, d.w_qkv, d.ld_wqkv, 1, dx, dm, nullptr))))
     return rc;
   AuxBatch aux;
   memset(&aux, 0, sizeof(aux));

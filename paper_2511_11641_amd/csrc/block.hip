@@ -19,6 +19,9 @@ static int validate_block(const ecospa_block_desc* dp) {
     if (!d.w_1 || !d.w_2) return ECOSPA_ERR_NULL;
     if (d.ld_w1 < d.d_model || d.ld_w2 < d.kp_ff) return ECOSPA_ERR_SHAPE;
     if (d.ld_w1 % 8 || d.ld_w2 % 8 || !aligned16(d.w_1) || !aligned16(d.w_2)) return ECOSPA_ERR_ALIGN;
+    const long long nh = static_cast<long long>(d.act == ECOSPA_ACT_SWIGLU ? 2 : 1) * d.kp_ff;
+    if ((d.w_1_t && d.ld_w1t < nh) || (d.w_2_t && d.ld_w2t < d.d_model)) return ECOSPA_ERR_SHAPE;
+    if ((d.w_1_t && (d.ld_w1t % 8 || !aligned16(d.w_1_t))) || (d.w_2_t && (d.ld_w2t % 8 || !aligned16(d.w_2_t)))) return ECOSPA_ERR_ALIGN;
   } else {
     if (d.h < 1 || d.kp_qk < 16 || d.kp_vo < 16 || d.kp_qk % 16 || d.kp_vo % 16 || d.kp_qk > 128 || d.kp_vo > 128)
       return ECOSPA_ERR_SHAPE;
@@ -27,6 +30,8 @@ static int validate_block(const ecospa_block_desc* dp) {
     if ((d.rope_cos == nullptr) != (d.rope_sin == nullptr)) return ECOSPA_ERR_NULL;
     if (d.ld_wqkv < d.d_model || d.ld_wo < static_cast<long long>(d.h) * d.kp_vo) return ECOSPA_ERR_SHAPE;
     if (d.ld_wqkv % 8 || d.ld_wo % 8 || !aligned16(d.w_qkv) || !aligned16(d.w_o)) return ECOSPA_ERR_ALIGN;
+    if ((d.w_qkv_t && d.ld_wqkvt < attn_nqkv(d)) || (d.w_o_t && d.ld_wot < d.d_model)) return ECOSPA_ERR_SHAPE;
+    if ((d.w_qkv_t && (d.ld_wqkvt % 8 || !aligned16(d.w_qkv_t))) || (d.w_o_t && (d.ld_wot % 8 || !aligned16(d.w_o_t)))) return ECOSPA_ERR_ALIGN;
     if (!(d.scale > 0.f)) return ECOSPA_ERR_SHAPE;
   }
   return ECOSPA_OK;
@@ -140,7 +145,8 @@ static int ffn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const 
   int rc;
   // dH = (dY W_2) * act'(H)
   {
-    GemmDesc g = gemm_desc(d.dtype, T, kp, dm, dy, dm, 0, d.w_2, d.ld_w2, 1);
+    GemmDesc g = d.w_2_t ? gemm_desc(d.dtype, T, kp, dm, dy, dm, 0, d.w_2_t, d.ld_w2t, 0)     // transposed copy [kp, d_model]
+                         : gemm_desc(d.dtype, T, kp, dm, dy, dm, 0, d.w_2, d.ld_w2, 1);
     g.epi.c = w.dh; g.epi.ldc = nh; g.epi.h = sv.hpre; g.epi.ldh = nh; g.epi.act = d.act; g.epi.kp = kp;
     g.epi.kind = is_gated(d) ? EPI_DSWIGLU : EPI_DACT;
     if ((rc = ecospa_gemm(ctx, g))) return rc;
@@ -157,7 +163,8 @@ static int ffn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const 
 
   // dX = dH W_1
   if (dx) {
-    GemmDesc g = gemm_desc(d.dtype, T, dm, nh, w.dh, nh, 0, d.w_1, d.ld_w1, 1);
+    GemmDesc g = d.w_1_t ? gemm_desc(d.dtype, T, dm, nh, w.dh, nh, 0, d.w_1_t, d.ld_w1t, 0)   // transposed copy [d_model, nh]
+                         : gemm_desc(d.dtype, T, dm, nh, w.dh, nh, 0, d.w_1, d.ld_w1, 1);
     g.epi.kind = EPI_STORE; g.epi.c = dx; g.epi.ldc = dm;
     if ((rc = ecospa_gemm(ctx, g))) return rc;
   }

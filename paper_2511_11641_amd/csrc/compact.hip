@@ -402,6 +402,114 @@ extern "C" int ecospa_scatter(ecospa_ctx* ctx, const void* src, void* dst, int d
   return mapped_copy(ctx, src, dst, dtype, axis, groups, n, unit, k, kp, other_extent, ld_src, ld_dst, idx, 1);
 }
 
+// ---- transposed copies of compact matrices ------------------------------------------------------------
+// The input-gradient contractions dY W read W with its contraction index slow; with a transposed copy of
+// the (small, compact) matrix beside it they become x W^T contractions like the forward ones, which the
+// matrix-core kernels run faster.  Plain HBM-bound data movement: 64 x 64 tiles through LDS, 16-byte
+// accesses on both sides when the shapes allow; all matrices of a layer in one launch.
+#define TR_MAX_ITEMS 64
+struct TrItemDev {
+  const void* src;
+  void* dst;
+  long long ld_src, ld_dst;
+  int rows, cols;      // of src; dst is [cols, rows]
+  int esize, vec;
+  int tiles_c;         // 64-wide tiles along the columns of src
+  int blk_begin;
+};
+struct TrBatch {
+  int n_items;
+  int first_blk[TR_MAX_ITEMS];
+  TrItemDev it[TR_MAX_ITEMS];
+};
+
+template <typename E>
+__device__ __forceinline__ void transpose_tile(const TrItemDev& t, int local, E* tile /* [64][65] */) {
+  const E* __restrict__ src = static_cast<const E*>(t.src);
+  E* __restrict__ dst = static_cast<E*>(t.dst);
+  const int r0 = (local / t.tiles_c) * 64, c0 = (local % t.tiles_c) * 64;
+  const int tid = threadIdx.x;
+  constexpr int V = 16 / sizeof(E), CH = 64 / V;            // elements per 16 bytes, 16-byte pieces per tile row
+  if (t.vec) {
+    for (int p = tid; p < 64 * CH; p += 256) {
+      const int r = p / CH, c = (p % CH) * V;
+      alignas(16) E x[V];
+      if (r0 + r < t.rows && c0 + c < t.cols)                // cols % V == 0: a piece is inside or outside as a whole
+        *reinterpret_cast<u32x4_t*>(x) = *reinterpret_cast<const u32x4_t*>(src + static_cast<long long>(r0 + r) * t.ld_src + c0 + c);
+      else
+        for (int v = 0; v < V; ++v) x[v] = E(0);
+#pragma unroll
+      for (int v = 0; v < V; ++v) tile[(c + v) * 65 + r] = x[v];
+    }
+    __syncthreads();
+    for (int p = tid; p < 64 * CH; p += 256) {
+      const int c = p / CH, r = (p % CH) * V;                 // row c of dst, V consecutive source rows
+      if (c0 + c < t.cols && r0 + r < t.rows) {
+        alignas(16) E x[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) x[v] = tile[c * 65 + r + v];
+        *reinterpret_cast<u32x4_t*>(dst + static_cast<long long>(c0 + c) * t.ld_dst + r0 + r) = *reinterpret_cast<const u32x4_t*>(x);
+      }
+    }
+  } else {
+    for (int p = tid; p < 64 * 64; p += 256) {
+      const int r = p / 64, c = p % 64;
+      tile[c * 65 + r] = (r0 + r < t.rows && c0 + c < t.cols) ? src[static_cast<long long>(r0 + r) * t.ld_src + c0 + c] : E(0);
+    }
+    __syncthreads();
+    for (int p = tid; p < 64 * 64; p += 256) {
+      const int c = p / 64, r = p % 64;
+      if (c0 + c < t.cols && r0 + r < t.rows) dst[static_cast<long long>(c0 + c) * t.ld_dst + r0 + r] = tile[c * 65 + r];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void transpose_batch_kernel(const TrBatch b) {
+  __shared__ __attribute__((aligned(16))) unsigned char tile_raw[64 * 65 * 4];
+  const int blk = blockIdx.x;
+  int i = 0, hi = b.n_items - 1;          // last item whose first block is <= blk
+  while (i < hi) {
+    const int mid = (i + hi + 1) >> 1;
+    if (b.first_blk[mid] <= blk) i = mid; else hi = mid - 1;
+  }
+  const TrItemDev& t = b.it[i];
+  if (t.esize == 2) transpose_tile<bf16_t>(t, blk - t.blk_begin, reinterpret_cast<bf16_t*>(tile_raw));
+  else transpose_tile<float>(t, blk - t.blk_begin, reinterpret_cast<float*>(tile_raw));
+}
+
+extern "C" int ecospa_transpose_batch(ecospa_ctx* ctx, const ecospa_transpose_item* items, int n_items) {
+  if (!ctx || !items) return ECOSPA_ERR_NULL;
+  if (n_items < 1) return ECOSPA_ERR_SHAPE;
+  for (int i = 0; i < n_items; ++i) {
+    const ecospa_transpose_item& q = items[i];
+    if (!q.src || !q.dst) return ECOSPA_ERR_NULL;
+    if (!dtype_ok(q.dtype)) return ECOSPA_ERR_DTYPE;
+    if (q.rows < 1 || q.cols < 1 || q.ld_src < q.cols || q.ld_dst < q.rows) return ECOSPA_ERR_SHAPE;
+  }
+  for (int first = 0; first < n_items; first += TR_MAX_ITEMS) {
+    TrBatch b;
+    memset(&b, 0, sizeof(b));
+    b.n_items = n_items - first < TR_MAX_ITEMS ? n_items - first : TR_MAX_ITEMS;
+    long long blk = 0;
+    for (int i = 0; i < b.n_items; ++i) {
+      const ecospa_transpose_item& q = items[first + i];
+      TrItemDev& t = b.it[i];
+      t.src = q.src; t.dst = q.dst; t.ld_src = q.ld_src; t.ld_dst = q.ld_dst; t.rows = q.rows; t.cols = q.cols;
+      t.esize = static_cast<int>(dtype_size(q.dtype));
+      const int V = 16 / t.esize;
+      t.vec = aligned16(q.src) && aligned16(q.dst) && q.ld_src % V == 0 && q.ld_dst % V == 0 && q.rows % V == 0 && q.cols % V == 0;
+      t.tiles_c = (q.cols + 63) / 64;
+      t.blk_begin = static_cast<int>(blk);
+      b.first_blk[i] = t.blk_begin;
+      blk += static_cast<long long>((q.rows + 63) / 64) * t.tiles_c;
+      if (blk > (1ll << 30)) return ECOSPA_ERR_SHAPE;
+    }
+    hipLaunchKernelGGL(transpose_batch_kernel, dim3(static_cast<unsigned>(blk)), dim3(256), 0, ctx->stream, b);
+    ECOSPA_CHECK_LAUNCH(ctx, "transpose_batch_kernel");
+  }
+  return ECOSPA_OK;
+}
+
 // ---- cos/sin tables of the kept rotary blocks (Eq. 6) -------------------------------------------
 __global__ void rope_table_kernel(const int* __restrict__ idx, int h, int L, int k, int kp, int d_h, double base,
                                   float* __restrict__ cos_out, float* __restrict__ sin_out,

@@ -15,8 +15,11 @@ from . import binding as B
 class FfnBlock:
     """Compacted FFN pair (W_in / W_out, or W_gate (.) W_up / W_down)."""
 
-    def __init__(self, ctx: B.Context, w1, b1, w2, b2, act: int, w1b=None):
+    def __init__(self, ctx: B.Context, w1, b1, w2, b2, act: int, w1b=None, transposed: bool = False):
+        """transposed: keep transposed copies of the compact matrices for the backward pass (refreshed by
+        :meth:`compact`; after a parameter update call :meth:`refresh_transposed`)."""
         self.ctx, self.act = ctx, act
+        self.transposed = transposed
         self.w1, self.b1, self.w2, self.b2, self.w1b = w1, b1, w2, b2, w1b
         self.n, self.d = w1.shape
         self.gated = act == B.ACT_SWIGLU
@@ -54,15 +57,30 @@ class FfnBlock:
         if self.b1 is not None:       # the up branch of a gated FFN has no bias: its slots stay zero
             items.append(mk(self.b1, self.b1_c[:kp], 1))
         items.append(mk(self.w2, self.w2_c, 1))
+        if self.transposed and (getattr(self, "w1_t", None) is None or self.w1_t.shape[1] != nh):
+            self.w1_t = torch.empty((self.d, nh), dtype=dt, device=dev)
+            self.w2_t = torch.empty((kp, self.d), dtype=dt, device=dev)
         if defer:
             return items
         c.ecospa_compact_batch(items)
+        self.refresh_transposed()
         return self
+
+    def transpose_items(self):
+        if not self.transposed:
+            return []
+        return [B.Context.transpose_item(self.w1_c, self.w1_t), B.Context.transpose_item(self.w2_c, self.w2_t)]
+
+    def refresh_transposed(self):
+        if self.transposed:
+            self.ctx.ecospa_transpose_batch(self.transpose_items())
 
     def desc(self, Bsz: int, L: int) -> B.BlockDesc:
         d = B.BlockDesc()
         d.block, d.dtype, d.B, d.L, d.d_model = B.BLOCK_FFN, B.dtype_code(self.w1.dtype), Bsz, L, self.d
         d.kp_ff, d.act = self.kp, self.act
+        if self.transposed:
+            d.w_1_t, d.w_2_t, d.ld_w1t, d.ld_w2t = self.w1_t.data_ptr(), self.w2_t.data_ptr(), self.w1_t.stride(0), self.w2_t.stride(0)
         d.w_1, d.b_1 = self.w1_c.data_ptr(), B._ptr(self.b1_c)
         d.w_2, d.b_2 = self.w2_c.data_ptr(), B._ptr(self.b2)
         d.ld_w1, d.ld_w2 = self.w1_c.stride(0), self.w2_c.stride(0)
@@ -101,8 +119,9 @@ class AttnBlock:
     (and heads of W_o) of a group keep the inner dimensions of the key/value head they share."""
 
     def __init__(self, ctx: B.Context, wq, wk, wv, wo, bq, bk, bv, bo, h: int, d_h: int, *, rope: bool,
-                 causal: bool = True, rope_base: float = 10000.0, h_kv: Optional[int] = None):
+                 causal: bool = True, rope_base: float = 10000.0, h_kv: Optional[int] = None, transposed: bool = False):
         self.ctx, self.h, self.d_h, self.rope, self.causal, self.rope_base = ctx, h, d_h, rope, causal, rope_base
+        self.transposed = transposed      # transposed copies of the compact matrices for the backward pass
         self.h_kv = h if h_kv is None else h_kv
         assert h % self.h_kv == 0
         self.qpk = h // self.h_kv
@@ -154,11 +173,24 @@ class AttnBlock:
             items += [mq(self.bq, self.bqkv_c[:nq], 1, h), mq(self.bk, self.bqkv_c[nq:nq + nk], 1, hk),
                       mv(self.bv, self.bqkv_c[nq + nk:], 1, hk)]
         items.append(mv(self.wo, self.wo_c, 1, h))
+        if self.transposed and (getattr(self, "wqkv_t", None) is None or self.wqkv_t.shape[1] != nq + nk + nv):
+            self.wqkv_t = torch.empty((self.d, nq + nk + nv), dtype=dt, device=dev)
+            self.wo_t = torch.empty((no, self.d), dtype=dt, device=dev)
         if not defer:
             c.ecospa_compact_batch(items)
+            self.refresh_transposed()
         if self.rope and getattr(self, "cos", None) is not None:     # kept blocks changed: new frequencies
             self._rope_table(self._L, out=(self.cos, self.sin))
         return items if defer else self
+
+    def transpose_items(self):
+        if not self.transposed:
+            return []
+        return [B.Context.transpose_item(self.wqkv_c, self.wqkv_t), B.Context.transpose_item(self.wo_c, self.wo_t)]
+
+    def refresh_transposed(self):
+        if self.transposed:
+            self.ctx.ecospa_transpose_batch(self.transpose_items())
 
     def _rope_table(self, L: int, out=None):
         if self.k_qk_group is not None:
@@ -179,6 +211,9 @@ class AttnBlock:
         d.block, d.dtype, d.B, d.L, d.d_model = B.BLOCK_ATTN, B.dtype_code(dt), Bsz, L, self.d
         d.h, d.kp_qk, d.kp_vo, d.causal = h, self.kp_qk, self.kp_vo, int(self.causal)
         d.h_kv = self.h_kv
+        if self.transposed:
+            d.w_qkv_t, d.w_o_t = self.wqkv_t.data_ptr(), self.wo_t.data_ptr()
+            d.ld_wqkvt, d.ld_wot = self.wqkv_t.stride(0), self.wo_t.stride(0)
         d.scale = float(self.d_h) ** -0.5
         d.rope_cos, d.rope_sin = B._ptr(self.cos), B._ptr(self.sin)
         d.w_qkv, d.b_qkv, d.w_o, d.b_o = self.wqkv_c.data_ptr(), B._ptr(self.bqkv_c), self.wo_c.data_ptr(), B._ptr(self.bo)

@@ -19,7 +19,7 @@ def ctx():
 
 
 def run_attn_case(ctx, seed, Bsz, L, d, h, dh, k_qk, k_vo, *, rope, causal, bias=True, structure="scratch",
-                  wscale=1.0, dtype="bf16"):
+                  wscale=1.0, dtype="bf16", transposed=False):
     """k_qk counts kept dimensions (even when rope: kept rotary blocks = k_qk / 2)."""
     t = synth.attn_layer(seed, Bsz, L, d, h, dh, dtype=dtype, structure=structure, bias=bias)
     if wscale != 1.0:
@@ -32,7 +32,7 @@ def run_attn_case(ctx, seed, Bsz, L, d, h, dh, k_qk, k_vo, *, rope, causal, bias
     iv = O.select_topk(vvo.astype(np.float32), k_vo)
     g = {nm: dev(a, dtype) for nm, a in t.items()}
     blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g.get("bq"), g.get("bk"), g.get("bv"), g.get("bo"),
-                    h, dh, rope=rope, causal=causal)
+                    h, dh, rope=rope, causal=causal, transposed=transposed)
     blk.compact(torch.from_numpy(iq).cuda(), torch.from_numpy(iv).cuda()).alloc(Bsz, L)
     y = blk.fwd(g["x"])
     dx = blk.bwd(g["x"], g["dy"])
@@ -108,6 +108,13 @@ def test_attn_gpt2_medium_heads(ctx):
 def test_attn_llama_heads(ctx):
     """32 heads x 64 at d=2048, RoPE, keep 16 of 32 rotary blocks and 32 of 64 value dims, L=256."""
     run_attn_case(ctx, 35, 2, 256, 2048, 32, 64, 32, 32, rope=True, causal=True, bias=False, structure="pretrained")
+
+
+@pytest.mark.parametrize("k_qk,k_vo,rope", [(32, 32, False), (48, 19, False), (32, 64, True)])
+def test_attn_backward_with_transposed_weight_copies(ctx, k_qk, k_vo, rope):
+    """The input-gradient contractions read transposed copies of the compact weights: same results to tolerance."""
+    run_attn_case(ctx, 33, 2, 200, 256, 4, 64, k_qk, k_vo, rope=rope, causal=True, transposed=True)
+    run_attn_case(ctx, 34, 8, 1024, 1024, 16, 64, 32, 32, rope=rope, causal=True, transposed=True)
 
 
 def test_attn_keep_all_is_dense(ctx):

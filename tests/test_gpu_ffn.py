@@ -21,7 +21,7 @@ def ctx():
     return B.Context("cuda:0")
 
 
-def run_ffn_case(ctx, seed, Bsz, L, d, n, k, act, dtype, structure="scratch", bias=True, wscale=1.0):
+def run_ffn_case(ctx, seed, Bsz, L, d, n, k, act, dtype, structure="scratch", bias=True, wscale=1.0, transposed=False):
     """Oracle scores/selects; both sides compact with the oracle's idx; compare everything."""
     gated = act == "swiglu"
     T = Bsz * L
@@ -34,7 +34,7 @@ def run_ffn_case(ctx, seed, Bsz, L, d, n, k, act, dtype, structure="scratch", bi
     v = O.coupled_score(kind, t["w1"], t["w2"], 1, n, w1b=t.get("w1b"))
     idx_np = O.select_topk(v.astype(np.float32), k)
     g = {nm: dev(a, dtype) for nm, a in t.items()}
-    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), ACT[act][0], g.get("w1b"))
+    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), ACT[act][0], g.get("w1b"), transposed=transposed)
     blk.compact(torch.from_numpy(idx_np).cuda()).alloc(Bsz, L)
     kp = blk.kp
     y = blk.fwd(g["x"])
@@ -106,6 +106,13 @@ def test_ffn_c1_fp32_whole_chain(ctx):
 def test_ffn_model_shapes_bf16(ctx, act, d, n, k, T):
     """GPT-2-Medium and LLaMA-1B FFN widths at 50% keep (token count reduced to keep the oracle quick)."""
     run_ffn_case(ctx, 23, 2, T // 2, d, n, k, act, "bf16", structure="pretrained", bias=(act == "gelu"))
+
+
+@pytest.mark.parametrize("act,d,n,k,T,dtype", [("gelu", 1024, 4096, 2048, 1024, "bf16"), ("swiglu", 2048, 5461, 2730, 512, "bf16"),
+                                              ("gelu", 72, 200, 99, 130, "bf16"), ("gelu", 256, 1024, 512, 512, "f32")])
+def test_ffn_backward_with_transposed_weight_copies(ctx, act, d, n, k, T, dtype):
+    """The input-gradient contractions read transposed copies of the compact weights: same results to tolerance."""
+    run_ffn_case(ctx, 17, 1, T, d, n, k, act, dtype, transposed=True)
 
 
 def test_ffn_scattered_gradients_equal_masked_dense(ctx):

@@ -204,3 +204,20 @@ def test_select_and_compact_batches_match_single_calls(ctx):
     ctx.ecospa_compact_batch([it for it, _ in items])
     for (_, got), w in zip(items, want):
         assert torch.equal(got, w)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,cols,pad", [(2048, 1024, 0), (1536, 1024, 0), (64, 64, 0), (130, 72, 8), (7, 301, 3), (1, 1, 0)])
+def test_transposed_copies_are_exact(ctx, rows, cols, pad, dtype):
+    """dst = src^T, bit for bit (numpy's transpose is the definition), with leading dimensions wider than the rows."""
+    a = synth.round_to(synth.normal(300, rows + cols, (rows, cols + pad)), dtype)
+    src = dev(a, dtype)[:, :cols]
+    dst_full = torch.full((cols, rows + pad), 7.0, dtype=src.dtype, device="cuda")
+    ctx.ecospa_transpose_batch([B.Context.transpose_item(src, dst_full[:, :rows])])
+    assert np.array_equal(host(dst_full[:, :rows]), a[:, :cols].T.astype(np.float64))
+    assert torch.all(dst_full[:, rows:] == 7.0)                         # nothing written past the rows
+    with pytest.raises(B.EcospaError) as e:
+        it = B.Context.transpose_item(src, dst_full[:, :rows])
+        it.ld_dst = rows - 1
+        ctx.ecospa_transpose_batch([it])
+    assert e.value.code == B.ERR_SHAPE
