@@ -314,6 +314,9 @@ def main():
     ap.add_argument("--pmc-reference", action="store_true",
                     help="first run 3 plain device copies of a 128 MiB tensor, so that hardware byte counters read "
                          "under rocprofv3 --pmc can be scaled by what they show for a copy of known size")
+    ap.add_argument("--prune-only", action="store_true",
+                    help="run only the 24-layer pruning pass (score, select, compaction, Eq. 8, threshold rule, AdamW) and "
+                         "print its figures (for profiler runs of the HBM-bound kernels)")
     ap.add_argument("--sparse-only", action="store_true",
                     help="run only the timed sparse steps (for hardware-counter runs) and print a short line")
     args = ap.parse_args()
@@ -341,6 +344,10 @@ def main():
             out_ref.copy_(ref)
         torch.cuda.synchronize()
         del ref, out_ref
+
+    if args.prune_only:
+        print(json.dumps({"prune_24_layers": prune_stack(ctx, cfg, 24, 1, 2, 20)}))
+        return
 
     sparse = Layer(ctx, cfg, seed, 1, 2)
     ms_step = timed(torch, sparse.step, args.steps, args.warmup)
