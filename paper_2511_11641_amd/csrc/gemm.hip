@@ -397,9 +397,15 @@ static bool gemm_prefers_big_tile(int M, int N, int splits) {
 static int gemm_pipe_choice(const GemmDesc& d) {
   if (d.trans_a) return -1;
   const long long tm256 = (d.M + 255) / 256, t256 = tm256 * ((d.N + 255) / 256), t256x128 = tm256 * ((d.N + 127) / 128);
-  if (t256 >= 192) return 5;      // 256x256, 8 wavefronts
+  if (t256 >= 192) {
+    // 256x256 with 8 wavefronts, unless its tiles fill the last round over the 256 compute units so badly that
+    // half-size tiles finish sooner (rounds of work, a half-size tile taken as 0.54 of a whole one)
+    const long long rounds256 = (t256 + 255) / 256, rounds128 = (t256x128 + 255) / 256;
+    if (!d.trans_b && rounds128 * 54 < rounds256 * 100) return 9;
+    return 5;
+  }
   if (d.trans_b) return -1;
-  if (t256x128 >= 192) return 2;  // 256x128, 3-deep ring
+  if (t256x128 >= 192) return 9;  // 256x128, 8 wavefronts, 3-deep ring
   return 4;                       // 128x128
 }
 // Long contractions with a K-slow B operand (K of several thousand, at least a tile per compute unit)
