@@ -385,7 +385,10 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_vec8_kernel(const Gemm
 // pay off when there are enough of them to occupy the 256 CUs.
 static bool gemm_prefers_big_tile(int M, int N, int splits) {
   const long long big = static_cast<long long>((M + 255) / 256) * ((N + 255) / 256) * splits;
-  return big >= 192;
+  const long long small = static_cast<long long>((M + 127) / 128) * ((N + 127) / 128) * splits;
+  // 256x256 tiles when they fill three quarters of the compute units - or two thirds, if the 128x128 tiles
+  // would need more than one round of 512
+  return big >= 192 || (big >= 168 && small > 512);
 }
 
 // Which configuration of the software-pipelined kernel (gemm_pipe.hip) suits a problem, or -1 for the
@@ -447,8 +450,10 @@ static hipError_t launch_tile(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
 int ecospa_gemm_splits(int M, int N, int K) {
   const long long tiles = static_cast<long long>((M + 127) / 128) * ((N + 127) / 128);
   int s = 1;
-  // fill ~2 waves of the 256 CUs while every split keeps at least 512 of K
-  while (tiles * s < 512 && K / (s * 2) >= 512 && s < 32) s *= 2;
+  // Two 128x128 workgroups fit a compute unit, so 512 of them run at once: split K while all splits still fit
+  // that one round and every split keeps at least 512 of K.  More splits than that only add partial sums to
+  // write and reduce (measured on the weight-gradient shapes of both layers).
+  while (tiles * s * 2 <= 512 && K / (s * 2) >= 512 && s < 16) s *= 2;
   return s;
 }
 
