@@ -244,6 +244,32 @@ def second_workload(ctx, name, steps, warmup):
             "speedup_fwd_bwd_vs_dense": ms_de / ms_fb}
 
 
+def torch_dense_layer(name, steps):
+    """Context only: the same dense layer (attention block + FFN block, no norms, no residual) forward+backward
+    through torch-ROCm's own operators (vendor GEMMs, its fused attention), to show that the dense baseline of
+    this library is no strawman.  Nothing of the library runs here."""
+    import torch
+    import torch.nn.functional as F
+    from paper_2511_11641_amd import synth
+    cfg = synth.CONFIGS[name]
+    Bsz, L, d, h, dh, dff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
+    g = lambda *s: (torch.randn(*s, device="cuda") * 0.02).to(torch.bfloat16).requires_grad_(True)
+    wqkv, bqkv, wo, bo, w1, b1, w2, b2 = g(3 * d, d), g(3 * d), g(d, d), g(d), g(dff, d), g(dff), g(d, dff), g(d)
+    x = torch.randn(Bsz * L, d, device="cuda").to(torch.bfloat16).requires_grad_(True)
+    dy = torch.randn(Bsz * L, d, device="cuda").to(torch.bfloat16)
+
+    def step():
+        q, k, v = (t.reshape(Bsz, L, h, dh).transpose(1, 2) for t in F.linear(x, wqkv, bqkv).chunk(3, dim=-1))
+        o = F.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(Bsz * L, d)
+        y1 = F.linear(o, wo, bo)
+        y2 = F.linear(F.gelu(F.linear(y1, w1, b1)), w2, b2)
+        y2.backward(dy)
+
+    ms = timed(torch, step, steps, 3)
+    return {"workload": name, "ms_fwd_bwd": ms, "tokens_per_s": Bsz * L / (ms * 1e-3),
+            "note": "torch-ROCm operators (vendor GEMM library, fused attention), bf16, autograd backward; context for dense_fwd_bwd"}
+
+
 def inference_sweep(ctx, name, steps):
     """Forward only (inference) of the layer at batch 1 and batch 32, dense and at three keep ratios: per-layer
     time, tokens/s and the speed-up over the dense layer run through the same library."""
@@ -405,6 +431,7 @@ def main():
         out["prune_24_layers"] = prune_stack(ctx, cfg, 24, 1, 2, 20)
         out["also"] = second_workload(ctx, "c3_llama1b_layer", args.steps, args.warmup)
         out["inference"] = inference_sweep(ctx, name, 20)
+        out["torch_dense_fwd_bwd"] = torch_dense_layer(name, 20)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, seed, 1, 2, sample_B=8)
     print(json.dumps(out))
