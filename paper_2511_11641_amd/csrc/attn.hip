@@ -834,6 +834,9 @@ static int attn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const
   // dW_o = dY^T O (partials),  dO = dY W_o
   GemmDesc go = mk_gemm(d.dtype, dm, nvo, T, dy, dm, 1, sv.o, nvo, 1, gr.dw_o, gr.ld_dwo, nullptr);
   go.splits = ecospa_gemm_splits(dm, nvo, T); go.partial = w.partial; go.defer_reduce = 1;
+  // the bias gradients are column sums of dY and dQKV, the K-slow operands of the two weight-gradient
+  // contractions: those add them up on the way
+  if (gr.dw_o && gr.db_o) go.colsum = w.colsum;
   if (gr.dw_o && (rc = ecospa_gemm(ctx, go))) return rc;
   if ((rc = ecospa_gemm(ctx, d.w_o_t ? mk_gemm(d.dtype, T, nvo, dm, dy, dm, 0, d.w_o_t, d.ld_wot, 0, w.d_o, nvo, nullptr)   // transposed copy [nvo, d_model]
                                      : mk_gemm(d.dtype, T, nvo, dm, dy, dm, 0, d.w_o, d.ld_wo, 1, w.d_o, nvo, nullptr))))
@@ -858,6 +861,7 @@ static int attn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const
   // dW_qkv = dQKV^T X (partials)
   GemmDesc gq = mk_gemm(d.dtype, nqkv, dm, T, w.dqkv, nqkv, 1, x, dm, 1, gr.dw_qkv, gr.ld_dwqkv, nullptr);
   gq.splits = ecospa_gemm_splits(nqkv, dm, T); gq.partial = w.partial2; gq.defer_reduce = 1;
+  if (gr.dw_qkv && gr.db_qkv) gq.colsum = w.colsum2;
   if (gr.dw_qkv && (rc = ecospa_gemm(ctx, gq))) return rc;
 
   // dX = dQKV W_qkv
@@ -868,8 +872,10 @@ static int attn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const
   memset(&aux, 0, sizeof(aux));
   if (gr.dw_o && go.splits > 1) aux.reduce[aux.n_reduce++] = go;
   if (gr.dw_qkv && gq.splits > 1) aux.reduce[aux.n_reduce++] = gq;
-  if (gr.db_o) aux.colsum[aux.n_colsum++] = AuxColsum{dy, dm, T, dm, d.dtype, gr.db_o};
-  if (gr.db_qkv) aux.colsum[aux.n_colsum++] = AuxColsum{w.dqkv, nqkv, T, nqkv, d.dtype, gr.db_qkv};
+  if (gr.db_o) aux.colsum[aux.n_colsum++] = go.colsum ? AuxColsum{go.colsum, dm, go.splits, dm, ECOSPA_F32, gr.db_o, d.dtype}
+                                                       : AuxColsum{dy, dm, T, dm, d.dtype, gr.db_o, 0};
+  if (gr.db_qkv) aux.colsum[aux.n_colsum++] = gq.colsum ? AuxColsum{gq.colsum, nqkv, gq.splits, nqkv, ECOSPA_F32, gr.db_qkv, d.dtype}
+                                                         : AuxColsum{w.dqkv, nqkv, T, nqkv, d.dtype, gr.db_qkv, 0};
   return ecospa_aux_launch(ctx, aux);
 }
 

@@ -18,6 +18,8 @@ struct BlockWs {           // pieces carved from the caller's workspace
   // shared
   float* partial;          // split-K partials of the first weight-gradient contraction of a backward pass
   float* partial2;         // ... and of the second (both are reduced by the batched tail launch)
+  float* colsum;           // [splits][M] operand column sums of the first weight-gradient contraction (bias gradient)
+  float* colsum2;          // ... and of the second
   size_t total;
 };
 

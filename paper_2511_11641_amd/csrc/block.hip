@@ -43,11 +43,12 @@ void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
   memset(&w, 0, sizeof(w));
   WsCarver c(base ? base : reinterpret_cast<void*>(256), ~static_cast<size_t>(0) >> 1);
   const size_t T = static_cast<size_t>(d.B) * d.L, es = dtype_size(d.dtype), dm = d.d_model;
-  size_t part = 0, part2 = 0;
+  size_t part = 0, part2 = 0, cs = 0, cs2 = 0;
   auto splitk_bytes = [&](int M, int N, int K) {
     const int s = ecospa_gemm_splits(M, N, K);
     return s > 1 ? static_cast<size_t>(s) * M * N * 4 : static_cast<size_t>(0);
   };
+  auto colsum_bytes = [&](int M, int N, int K) { return static_cast<size_t>(ecospa_gemm_splits(M, N, K)) * M * 4; };
   if (d.block == ECOSPA_BLOCK_FFN) {
     const size_t nh = static_cast<size_t>(is_gated(d) ? 2 : 1) * d.kp_ff;
     w.dh = c.take(T * nh * es);
@@ -55,6 +56,8 @@ void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
     w.act_tmp = c.take(T * d.kp_ff * es);
     part = splitk_bytes(d.d_model, d.kp_ff, static_cast<int>(T));
     part2 = splitk_bytes(static_cast<int>(nh), d.d_model, static_cast<int>(T));
+    cs = colsum_bytes(d.d_model, d.kp_ff, static_cast<int>(T));
+    cs2 = colsum_bytes(static_cast<int>(nh), d.d_model, static_cast<int>(T));
   } else {
     const size_t nqkv = attn_nqkv(d), nvo = static_cast<size_t>(d.h) * d.kp_vo;
     w.dqkv = c.take(T * nqkv * es);
@@ -65,9 +68,13 @@ void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
     w.lse_tmp = static_cast<float*>(c.take(static_cast<size_t>(d.B) * d.h * d.L * 4));
     part = splitk_bytes(d.d_model, static_cast<int>(nvo), static_cast<int>(T));
     part2 = splitk_bytes(static_cast<int>(nqkv), d.d_model, static_cast<int>(T));
+    cs = colsum_bytes(d.d_model, static_cast<int>(nvo), static_cast<int>(T));
+    cs2 = colsum_bytes(static_cast<int>(nqkv), d.d_model, static_cast<int>(T));
   }
   w.partial = static_cast<float*>(c.take(part));
   w.partial2 = static_cast<float*>(c.take(part2));
+  w.colsum = static_cast<float*>(c.take(cs));
+  w.colsum2 = static_cast<float*>(c.take(cs2));
   w.total = c.off + 256;
   if (!base) memset(&w, 0, offsetof(BlockWs, total));
 }
@@ -155,10 +162,15 @@ static int ffn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const 
   GemmDesc g2 = gemm_desc(d.dtype, dm, kp, T, dy, dm, 1, sv.act, kp, 1);
   g2.splits = ecospa_gemm_splits(dm, kp, T); g2.partial = w.partial; g2.defer_reduce = 1;
   g2.epi.kind = EPI_STORE; g2.epi.c = gr.dw_2; g2.epi.ldc = gr.ld_dw2;
+  // the bias gradients are column sums of dY and dH: the weight-gradient contractions read exactly these as
+  // their K-slow operand and add them up on the way (bf16 kernels; otherwise a column-sum job below)
+  const bool fused_db = d.dtype == ECOSPA_BF16;
+  if (fused_db && gr.dw_2 && gr.db_2) g2.colsum = w.colsum;
   if (gr.dw_2 && (rc = ecospa_gemm(ctx, g2))) return rc;
   GemmDesc g1 = gemm_desc(d.dtype, nh, dm, T, w.dh, nh, 1, x, dm, 1);
   g1.splits = ecospa_gemm_splits(nh, dm, T); g1.partial = w.partial2; g1.defer_reduce = 1;
   g1.epi.kind = EPI_STORE; g1.epi.c = gr.dw_1; g1.epi.ldc = gr.ld_dw1;
+  if (fused_db && gr.dw_1 && gr.db_1) g1.colsum = w.colsum2;
   if (gr.dw_1 && (rc = ecospa_gemm(ctx, g1))) return rc;
 
   // dX = dH W_1
@@ -172,8 +184,10 @@ static int ffn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const 
   memset(&aux, 0, sizeof(aux));
   if (gr.dw_2 && g2.splits > 1) aux.reduce[aux.n_reduce++] = g2;
   if (gr.dw_1 && g1.splits > 1) aux.reduce[aux.n_reduce++] = g1;
-  if (gr.db_2) aux.colsum[aux.n_colsum++] = AuxColsum{dy, dm, T, dm, d.dtype, gr.db_2};
-  if (gr.db_1) aux.colsum[aux.n_colsum++] = AuxColsum{w.dh, nh, T, nh, d.dtype, gr.db_1};
+  if (gr.db_2) aux.colsum[aux.n_colsum++] = g2.colsum ? AuxColsum{g2.colsum, dm, g2.splits, dm, ECOSPA_F32, gr.db_2, d.dtype}
+                                                       : AuxColsum{dy, dm, T, dm, d.dtype, gr.db_2, 0};
+  if (gr.db_1) aux.colsum[aux.n_colsum++] = g1.colsum ? AuxColsum{g1.colsum, nh, g1.splits, nh, ECOSPA_F32, gr.db_1, d.dtype}
+                                                       : AuxColsum{w.dh, nh, T, nh, d.dtype, gr.db_1, 0};
   return ecospa_aux_launch(ctx, aux);
 }
 

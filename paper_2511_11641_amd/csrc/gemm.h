@@ -40,6 +40,9 @@ struct GemmDesc {
   int splits;        // > 1: split K, fp32 partials in `partial`, reduced in a fixed order
   float* partial;    // [splits][M][N] when splits > 1
   int defer_reduce;  // splits > 1: only write the partials; the caller runs ecospa_gemm_reduce later
+  float* colsum;     // optional, bf16 contractions with a K-slow A operand (dY^T X): [max(splits, 1)][M] column sums of A over
+                     // each split's K range, sum_k A(m, k) - the bias gradient that belongs to the weight gradient, taken
+                     // from the operand on its way through the registers (written by the workgroups of the first tile column)
   GemmEpi epi;
 };
 
@@ -73,6 +76,7 @@ struct AuxColsum {
   long long ldx;
   int M, N, dtype;
   void* out;
+  int out_dtype;     // 0: as X; otherwise the type of `out` (fp32 partial sums reduced into a bf16 gradient)
 };
 struct AuxBatch {
   int n_reduce, n_colsum;

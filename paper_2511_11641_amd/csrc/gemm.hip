@@ -168,6 +168,16 @@ void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   const bf16_t* A = static_cast<const bf16_t*>(d.A);
   const bf16_t* B = static_cast<const bf16_t*>(d.B);
   u32x4 ra[NA], rb[NB];
+  // Column sums of a K-slow A operand (bias gradient, GemmDesc::colsum): a thread's 4(k) x 8(m) sub-blocks keep their
+  // m across the K loop, so it adds up its own eight columns; only the first tile column of the grid does it.
+  constexpr bool CS = TA && TB;                      // the dY^T X form, the only one that asks for it
+  constexpr int NCS = CS ? NA / 4 : 1;
+  const bool do_cs = CS && d.colsum != nullptr && n0 == 0;
+  float cs_acc[NCS][8];
+#pragma unroll
+  for (int b = 0; b < NCS; ++b)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) cs_acc[b][j] = 0.f;
   floatx16 acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
@@ -199,6 +209,15 @@ void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   do {                                                                                             \
     const bool full_ = (k0) + BK <= k_end;                                                         \
     bf16_t* as_ = lds + (buf) * STAGE;                                                             \
+    if (CS && do_cs) {                                                                             \
+      _Pragma("unroll") for (int q_ = 0; q_ < NCS * 4; ++q_) {                                     \
+        const uint32_t w_[4] = {ra[q_].x, ra[q_].y, ra[q_].z, ra[q_].w};                           \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                         \
+          cs_acc[q_ / 4][2 * i_] += __uint_as_float(w_[i_] << 16);                                 \
+          cs_acc[q_ / 4][2 * i_ + 1] += __uint_as_float(w_[i_] & 0xffff0000u);                     \
+        }                                                                                          \
+      }                                                                                            \
+    }                                                                                              \
     if (TA && TRR) sstore_ks<BM, BK, THREADS>(as_, ra);                                            \
     else if (TA) sstore_tr<BM, BK, THREADS>(as_, ra);                                              \
     else if (!(DIRECT_OK && full_)) sstore_kc<BM, BK, THREADS>(as_, ra);                           \
@@ -242,6 +261,28 @@ void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   }
 #undef GEMM_FETCH
 #undef GEMM_STORE
+
+  if (CS && d.colsum != nullptr) {       // uniform over the grid; the operand buffers are idle now
+    float* red = reinterpret_cast<float*>(lds);      // [BK / 4 k-blocks][BM]
+    if (do_cs) {
+#pragma unroll
+      for (int b = 0; b < NCS; ++b) {
+        const int sb = tid + b * THREADS;
+        const int rblk = sb % (BM / 8), kblk = sb / (BM / 8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) red[kblk * BM + rblk * 8 + j] = cs_acc[b][j];
+      }
+    }
+    __syncthreads();
+    if (do_cs)
+      for (int r = tid; r < BM; r += THREADS) {
+        float s = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < BK / 4; ++kb) s += red[kb * BM + r];     // fixed order
+        if (m0 + r < d.M) d.colsum[static_cast<long long>(zsplit) * d.M + m0 + r] = s;
+      }
+    __syncthreads();
+  }
 
   // Epilogue through LDS: each wavefront parks 32 rows x WTN columns of fp32 at a time in its own
   // slice of the (now idle) operand buffers, then every lane handles 8 consecutive columns of a
@@ -461,6 +502,7 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
   if (d.M < 1 || d.N < 1 || d.K < 1) return ECOSPA_ERR_SHAPE;
   if (!d.A || !d.B || !d.epi.c) return ECOSPA_ERR_NULL;
   if (d.splits > 1 && !d.partial) return ECOSPA_ERR_WORKSPACE;
+  if (d.colsum && !(d.dtype == ECOSPA_BF16 && d.trans_a && d.trans_b && d.tile == 0)) return ECOSPA_ERR_SHAPE;
   const int splits = d.splits > 1 ? d.splits : 1;
   if (d.dtype == ECOSPA_BF16) {
     // 16-byte vector loads along the contiguous axis of each operand
@@ -580,7 +622,7 @@ __device__ __forceinline__ void aux_reduce_block(const GemmDesc& d, int blk) {
 // workgroups to hide the latency; the four strips of a line are mapped to workgroup ids that differ
 // by 8, 16 and 24, i.e. to the same XCD, so that the line is fetched into one L2 only.
 #define AUX_LANES 2
-template <typename T>
+template <typename T, typename TO>
 __device__ __forceinline__ void aux_colsum_block(const AuxColsum& c, int blk, float* lds) {
   static_assert(AUX_LANES == 2, "four strips of AUX_LANES x 16 bytes make one 128-byte line");
   constexpr int V = 16 / sizeof(T);          // columns per lane
@@ -640,7 +682,7 @@ __device__ __forceinline__ void aux_colsum_block(const AuxColsum& c, int blk, fl
   part = wave_sum(part);     // lanes of a wavefront = the 64 groups of one column; fixed order
   if (colw < W && grp == 0) {
     const int col = blk * W + colw;
-    if (col < c.N) store_f32<T>(static_cast<T*>(c.out) + col, part);
+    if (col < c.N) store_f32<TO>(static_cast<TO*>(c.out) + col, part);
   }
 }
 
@@ -652,8 +694,10 @@ __global__ __launch_bounds__(AUX_THREADS) void bwd_aux_kernel(const AuxBatchDev 
   const int local = blk - a.blk_begin[j];
   if (j < a.b.n_colsum) {
     const AuxColsum& c = a.b.colsum[j];
-    if (c.dtype == ECOSPA_BF16) aux_colsum_block<bf16_t>(c, local, lds);
-    else aux_colsum_block<float>(c, local, lds);
+    const int od = c.out_dtype ? c.out_dtype : c.dtype;
+    if (c.dtype == ECOSPA_BF16) aux_colsum_block<bf16_t, bf16_t>(c, local, lds);
+    else if (od == ECOSPA_BF16) aux_colsum_block<float, bf16_t>(c, local, lds);
+    else aux_colsum_block<float, float>(c, local, lds);
   } else {
     const GemmDesc& d = a.b.reduce[j - a.b.n_colsum];
     if (d.dtype == ECOSPA_BF16) aux_reduce_block<bf16_t>(d, local);
