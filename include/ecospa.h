@@ -337,9 +337,10 @@ int ecospa_coupled_bwd(ecospa_ctx* ctx, const ecospa_block_desc* desc /*host*/, 
  * So x W^T is (0, 0), dY W is (0, 1) and dY^T X is (1, 1).  bias may be NULL.
  * tile (bf16 only; for tests and tuning): 0 = library's choice; 1 / 2 = 128x128 / 256x256 workgroup
  * tiles staged through registers, K-slow operands transposed on the way to LDS; 3 / 4 = the same with
- * K-slow operands read by transposing LDS reads; 10..16 = configurations of the software-pipelined
- * kernel (direct global->LDS ring; needs K and K/splits to be multiples of its slab depth, else the
- * library falls back to its own choice).
+ * K-slow operands read by transposing LDS reads; 10..19 and 21 = configurations 0..9 and 10 of the
+ * software-pipelined kernel (direct global->LDS ring; needs K and K/splits to be multiples of its slab
+ * depth, else the library falls back to its own choice); 20 = the register-prefetch kernel for long
+ * contractions with a K-slow B.
  * splits: 0 = library's choice, otherwise the number of K splits (partials come from the
  * workspace and are added in a fixed order).
  * bf16 needs 16-byte aligned pointers, N % 8 == 0, leading dimensions % 8 == 0 and the

@@ -234,7 +234,7 @@ extern "C" int ecospa_contract(ecospa_ctx* ctx, int dtype, int M, int N, int K, 
                                const void* bias, int tile, int splits) {
   if (!ctx || !A || !B || !C) return ECOSPA_ERR_NULL;
   if (!dtype_ok(dtype)) return ECOSPA_ERR_DTYPE;
-  if (M < 1 || N < 1 || K < 1 || tile < 0 || tile > 20 || splits < 0 || splits > 64) return ECOSPA_ERR_SHAPE;
+  if (M < 1 || N < 1 || K < 1 || tile < 0 || tile > 21 || splits < 0 || splits > 64) return ECOSPA_ERR_SHAPE;
   if (lda < (trans_a ? M : K) || ldb < (trans_b ? N : K) || ldc < N) return ECOSPA_ERR_SHAPE;
   GemmDesc g = gemm_desc(dtype, M, N, K, A, lda, trans_a ? 1 : 0, B, ldb, trans_b ? 1 : 0);
   g.tile = tile;

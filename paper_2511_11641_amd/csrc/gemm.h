@@ -56,7 +56,7 @@ int ecospa_gemm_splits(int M, int N, int K);
 
 // Software-pipelined kernel for full K slabs (gemm_pipe.hip): configurations 0 .. GEMM_PIPE_CONFIGS-1
 // differ in workgroup tile, slab depth and LDS ring length; d.tile = 10 + configuration forces one.
-#define GEMM_PIPE_CONFIGS 10
+#define GEMM_PIPE_CONFIGS 11
 bool gemm_pipe_ok(const GemmDesc& d, int cfg, int k_chunk);
 hipError_t gemm_pipe_launch(ecospa_ctx* ctx, const GemmDesc& d, int cfg, int k_chunk);
 int gemm_pipe_bk(int cfg);

@@ -442,10 +442,17 @@ static int gemm_pipe_choice(const GemmDesc& d) {
   if (d.trans_a) return -1;
   const long long tm256 = (d.M + 255) / 256, t256 = tm256 * ((d.N + 255) / 256), t256x128 = tm256 * ((d.N + 127) / 128);
   if (t256 >= 192) {
-    // 256x256 with 8 wavefronts, unless its tiles fill the last round over the 256 compute units so badly that
-    // half-size tiles finish sooner (rounds of work, a half-size tile taken as 0.54 of a whole one)
-    const long long rounds256 = (t256 + 255) / 256, rounds128 = (t256x128 + 255) / 256;
-    if (!d.trans_b && rounds128 * 54 < rounds256 * 100) return 9;
+    // 256x256 with 8 wavefronts - unless its tiles fill the last round over the 256 compute units so badly that
+    // narrower tiles finish sooner.  Cost of a choice: rounds of work times the area of a tile (narrower tiles
+    // taken as 2 % and 8 % less efficient per flop); 256x192 serves the widths that are multiples of 192 (the
+    // fused Q|K|V projections of both layers) and K-contiguous operands only.
+    if (!d.trans_b) {
+      const long long t256x192 = tm256 * ((d.N + 191) / 192);
+      const long long c256 = (t256 + 255) / 256 * 256 * 100, c192 = (t256x192 + 255) / 256 * 192 * 102,
+                      c128 = (t256x128 + 255) / 256 * 128 * 108;
+      if (c192 < c256 && c192 <= c128) return 10;
+      if (c128 < c256) return 9;
+    }
     return 5;
   }
   if (d.trans_b) return -1;
@@ -524,7 +531,8 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
     if (prof) (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n], ctx->stream);
     hipError_t le;
     const int k_split = (d.K + splits - 1) / splits;
-    const int cfg = d.tile >= 10 && d.tile < 20 ? d.tile - 10 : (d.tile == 0 ? gemm_pipe_choice(d) : -1);
+    // tile codes: 10-19 and 21 name the configurations 0-9 and 10 of the pipelined kernel, 20 the register-prefetch kernel
+    const int cfg = d.tile >= 10 && d.tile < 20 ? d.tile - 10 : (d.tile == 21 ? 10 : (d.tile == 0 ? gemm_pipe_choice(d) : -1));
     if ((d.tile == 20 || (d.tile == 0 && gemm_prefers_rs(d))) && gemm_rs_ok(d, k_split)) le = gemm_rs_launch(ctx, d, k_split);
     else if (cfg >= 0 && gemm_pipe_ok(d, cfg, k_split)) le = gemm_pipe_launch(ctx, d, cfg, k_split);
     else {

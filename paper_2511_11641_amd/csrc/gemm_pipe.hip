@@ -75,7 +75,7 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   constexpr int NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN, FM = WTM / 32, FN = WTN / 32, KS = BK / 16;
   constexpr int STAGE = (BM + BN) * BK;
-  static_assert(WTN == 64 || WTN == 128, "epilogue handles 64 or 128 columns per wavefront");
+  static_assert(WTN == 64 || WTN == 96 || WTN == 128, "epilogue: 8 columns per lane, whole rows per pass");
   static_assert(KS >= 2 && KS % 2 == 0, "fragment double buffer needs an even number of k steps");
   extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
   lds_bf16_t* lds3 = (lds_bf16_t*)lds;
@@ -212,7 +212,8 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   const bool split = d.splits > 1;
   float* part = split ? d.partial + static_cast<long long>(zsplit) * d.M * d.N : nullptr;
   constexpr int LPR = WTN / 8;          // lanes per row
-  constexpr int RPI = 64 / LPR;         // rows per pass
+  constexpr int RPI = 64 / LPR;         // rows per pass (96 columns: 5 rows, four lanes idle)
+  constexpr int NIT = (32 + RPI - 1) / RPI;
   const int n = n0 + wn * WTN + (lane % LPR) * 8;
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
@@ -225,10 +226,10 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll 1
-    for (int it = 0; it < 32 / RPI; ++it) {
+    for (int it = 0; it < NIT; ++it) {
       const int row = it * RPI + lane / LPR;
       const int m = m0 + wm * WTM + i * 32 + row;
-      if (m >= d.M || n >= d.N) continue;
+      if (lane / LPR >= RPI || row >= 32 || m >= d.M || n >= d.N) continue;
       float v[8];
       const float4 lo = *reinterpret_cast<const float4*>(cs + row * WTN + (lane % LPR) * 8);
       const float4 hi = *reinterpret_cast<const float4*>(cs + row * WTN + (lane % LPR) * 8 + 4);
@@ -259,7 +260,8 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   X(128, 128, 32, 4, 2, 2, 2)    \
   X(256, 256, 32, 4, 2, 4, 2)    \
   X(256, 256, 32, 5, 2, 4, 2)    \
-  X(256, 128, 64, 3, 4, 2, 2)
+  X(256, 128, 64, 3, 4, 2, 2)    \
+  X(256, 192, 64, 2, 4, 2, 2)
 #define PIPE_INSTANTIATE(BM, BN, BK, NS, WGM, WGN, WPE)                                                             \
   template __global__ void gemm_bf16_pipe_kernel<BM, BN, BK, NS, WGM, WGN, WPE, false, false>(const GemmDesc, int, int); \
   template __global__ void gemm_bf16_pipe_kernel<BM, BN, BK, NS, WGM, WGN, WPE, false, true>(const GemmDesc, int, int);  \
@@ -305,6 +307,7 @@ int gemm_pipe_bk(int cfg) {
 bool gemm_pipe_ok(const GemmDesc& d, int cfg, int k_chunk) {
   if (cfg < 0 || cfg >= GEMM_PIPE_CONFIGS) return false;
   if (d.trans_a && !d.trans_b) return false;           // combination not used by the layers
+  if (cfg == 10 && (d.trans_a || d.trans_b)) return false;   // 192 rows do not divide into the K-slow load pattern
   const int bk = gemm_pipe_bk(cfg);
   if (d.K % bk || k_chunk % bk) return false;           // full slabs only
   return d.M >= 8 && d.N >= 8;
@@ -322,6 +325,7 @@ hipError_t gemm_pipe_launch(ecospa_ctx* ctx, const GemmDesc& d, int cfg, int k_c
     case 7: return launch_pipe<256, 256, 32, 4, 2, 4, 2>(ctx, d, k_chunk);
     case 8: return launch_pipe<256, 256, 32, 5, 2, 4, 2>(ctx, d, k_chunk);
     case 9: return launch_pipe<256, 128, 64, 3, 4, 2, 2>(ctx, d, k_chunk);
+    case 10: return launch_pipe<256, 192, 64, 2, 4, 2, 2>(ctx, d, k_chunk);
     default: return hipErrorInvalidValue;
   }
 }
