@@ -333,6 +333,18 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
     MapBatch b;
     memset(&b, 0, sizeof(b));
     b.n_items = n_items - first < MAP_MAX_ITEMS ? n_items - first : MAP_MAX_ITEMS;
+    // workgroups the launch has with the most rows per workgroup: only a launch that would leave the
+    // chip short of work at that size (a single layer's matrices) takes fewer rows per workgroup
+    long long coarse = 0;
+    for (int i = 0; i < b.n_items; ++i) {
+      const ecospa_map_item& q = items[first + i];
+      const long long slots = static_cast<long long>(q.groups) * (q.scatter ? q.n : q.kp * q.unit);
+      const int V = 16 / static_cast<int>(dtype_size(q.dtype));
+      coarse += q.axis == 0 ? (slots + MAP_ROWS_PER_BLOCK - 1) / MAP_ROWS_PER_BLOCK
+                            : (q.other_extent + MAP_LDS_ROWS_TOTAL - 1) / MAP_LDS_ROWS_TOTAL *
+                                  ((slots + MAP_LDS_GROUPS * V - 1) / (MAP_LDS_GROUPS * V));
+    }
+    const bool short_launch = coarse < 4096;
     long long blk = 0;
     for (int i = 0; i < b.n_items; ++i) {
       const ecospa_map_item& q = items[first + i];
@@ -357,9 +369,8 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
         t.lds_path = t.vec && aligned16(q.src) && q.ld_src % V == 0 && (q.scatter ? cmp_slots : full_slots) % V == 0;
         if (t.lds_path) {
           t.gx = static_cast<int>((t.dst_slots + MAP_LDS_GROUPS * V - 1) / (MAP_LDS_GROUPS * V));
-          // rows per workgroup: fewer when the matrix alone would not fill the chip (a single layer's launch)
           int rpb = MAP_LDS_ROWS_TOTAL;
-          while (rpb > 2 * MAP_LDS_ROWS && (q.other_extent + rpb - 1) / rpb * t.gx < 1024) rpb /= 2;
+          while (short_launch && rpb > 2 * MAP_LDS_ROWS && (q.other_extent + rpb - 1) / rpb * t.gx < 1024) rpb /= 2;
           t.rpb = rpb;
           blk += (q.other_extent + rpb - 1) / rpb * t.gx;
         } else {
