@@ -173,7 +173,10 @@ int ecospa_scatter(ecospa_ctx* ctx, const void* src, void* dst, int dtype, int a
                    int unit, int k, int kp, long long other_extent, long long ld_src, long long ld_dst,
                    const int* idx);
 /* Several gathers and/or scatters (every matrix, bias and moment of a layer) in one launch; the
- * fields have the meaning of the arguments above, scatter != 0 selects the inverse direction.
+ * fields have the meaning of the arguments above.  scatter: 0 = gather, 1 = the inverse direction with
+ * zeros in every pruned row/column of dst, 2 = the inverse direction leaving pruned rows/columns of dst
+ * as they are (compact parameters, master copies and moments written back into full-size arrays before
+ * the importance is estimated again, Alg. 1); other values -> ERR_SHAPE.
  * `items` is a host array; all items are validated before anything is launched.  Items must not
  * overlap each other's destinations. */
 /* Ragged kept counts (what the cumulative-threshold rule of Alg. 1 leaves: every head, every pair its

@@ -224,14 +224,21 @@ def compact_ragged(src, idx, ks, axis: int, n: int, kp: int, unit: int = 1) -> n
     return out.reshape(-1) if vec else (out.T if axis == 0 else out)
 
 
-def scatter_ragged(cmp, idx, ks, axis: int, n: int, kp: int, unit: int = 1) -> np.ndarray:
-    """Inverse of :func:`compact_ragged`: kept units back in place, zeros everywhere else."""
+def scatter_ragged(cmp, idx, ks, axis: int, n: int, kp: int, unit: int = 1, base=None) -> np.ndarray:
+    """Inverse of :func:`compact_ragged`: kept units back in place, zeros everywhere else - or, with `base`
+    (a full-size array), the contents of `base` everywhere else: compact parameters and optimizer state
+    written back before the importance is estimated again (Alg. 1: only what was kept has been updated)."""
     cmp = np.asarray(cmp)
     idx = np.asarray(idx)
     groups = idx.shape[0]
     vec = cmp.ndim == 1
     m = cmp.reshape(1, -1) if vec else (cmp.T if axis == 0 else cmp)
-    out = np.zeros((m.shape[0], groups * n), dtype=cmp.dtype)
+    if base is None:
+        out = np.zeros((m.shape[0], groups * n), dtype=cmp.dtype)
+    else:
+        base = np.asarray(base)
+        out = (base.reshape(1, -1) if vec else (base.T if axis == 0 else base)).astype(cmp.dtype, copy=True)
+        assert out.shape == (m.shape[0], groups * n)
     for g in range(groups):
         for i in range(int(ks[g])):
             for u in range(unit):

@@ -231,7 +231,7 @@ class Context:
         assert K == K2
         if out is None:
             out = torch.empty((M, N), dtype=A.dtype, device=A.device)
-        self.reserve(64 * M * N * 4 if splits == 0 else splits * M * N * 4)
+        self.reserve(64 * M * N * 4 if splits == 0 else (splits * M * N * 4 if splits > 1 else 0))     # fp32 partials of a split contraction
         self._check(self.lib.ecospa_contract(self.h, dtype_code(A.dtype), M, N, K, A.data_ptr(), A.stride(0),
                                              int(trans_a), Bm.data_ptr(), Bm.stride(0), int(trans_b), out.data_ptr(),
                                              out.stride(0), _ptr(bias), tile, splits), "ecospa_contract")
@@ -313,9 +313,10 @@ class Context:
     # ---- step 3 ------------------------------------------------------------------------------
     @staticmethod
     def map_item(src: torch.Tensor, dst: torch.Tensor, idx: torch.Tensor, axis: int, groups: int, n: int,
-                 unit: int = 1, kp: Optional[int] = None, scatter: bool = False,
+                 unit: int = 1, kp: Optional[int] = None, scatter: int = 0,
                  k_group: Optional[torch.Tensor] = None, idx_div: int = 1) -> MapItem:
-        """Descriptor of one gather (or scatter) for :meth:`ecospa_compact_batch`.  With k_group (int32[groups]
+        """Descriptor of one gather (scatter = 0), scatter with zero fill (1) or scatter that leaves the pruned
+        slots of dst untouched (2) for :meth:`ecospa_compact_batch`.  With k_group (int32[groups]
         on the device) group g keeps its first k_group[g] entries of idx[g, :] and kp must be given."""
         if k_group is not None:
             assert kp is not None and k_group.dtype == torch.int32 and k_group.numel() == groups // idx_div
@@ -332,9 +333,10 @@ class Context:
                        idx.shape[1] if k_group is not None else 0, idx_div)
 
     def ecospa_compact_ragged(self, src: torch.Tensor, idx: torch.Tensor, k_group: torch.Tensor, axis: int, groups: int,
-                              n: int, kp: int, unit: int = 1, scatter: bool = False,
+                              n: int, kp: int, unit: int = 1, scatter: int = 0,
                               out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        """Gather (or scatter) with ragged kept counts, all groups padded to kp slots."""
+        """Gather (or scatter: 1 zero fill, 2 into the contents of `out`) with ragged kept counts, all groups padded
+        to kp slots."""
         slots = groups * n if scatter else groups * kp * unit
         if out is None:
             shape = (slots,) if src.dim() == 1 else ((slots, src.shape[1]) if axis == 0 else (src.shape[0], slots))

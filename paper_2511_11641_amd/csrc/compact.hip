@@ -2,7 +2,8 @@
 // scatter with zero fill (Def. 1 / Alg. 1 removal; gradients written back to the full layout).
 //
 // Pure data movement, HBM-bound.  Both directions are one "mapped copy": destination slot s
-// along the inner axis takes source slot map(s), or zeros when map(s) < 0.
+// along the inner axis takes source slot map(s), or zeros when map(s) < 0 (the merging scatter leaves
+// such slots as they are: compact parameters and moments written back into their full-size arrays).
 //   gather : s = g*kp*unit + i*unit + u  ->  g*n + idx[g,i]*unit + u   (i < k), else -1 (padding)
 //   scatter: s = g*n + q*unit + u        ->  g*kp*unit + i*unit + u    where idx[g,i] == q (binary
 //            search in the ascending index list), else -1 (pruned)
@@ -18,7 +19,7 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // 16 bytes held
 struct MapArgs {
   const int* idx;
   int groups, n, unit, k, kp;
-  int scatter;
+  int scatter;          // 0 gather, 1 scatter with zero fill, 2 scatter that leaves pruned slots untouched
   const int* k_group;   // ragged kept counts (one per group, device memory) or null: every group keeps k
   int ld_idx;           // distance between the index lists of consecutive groups
   int idx_div;          // heads that share one index list (grouped-query attention): group g uses list g / idx_div
@@ -89,7 +90,10 @@ __device__ __forceinline__ void map_rows_block(const MapItemDev& t, int blk) {
   const long long cols = t.other;
   long long srow[MAP_ROW_PER_WAVE];   // source row, -1: zeros (padding / pruned), -2: no such destination row
 #pragma unroll
-  for (int j = 0; j < MAP_ROW_PER_WAVE; ++j) srow[j] = row0 + j < t.dst_slots ? map_slot(t.m, row0 + j) : -2;
+  for (int j = 0; j < MAP_ROW_PER_WAVE; ++j) {
+    srow[j] = row0 + j < t.dst_slots ? map_slot(t.m, row0 + j) : -2;
+    if (t.m.scatter == 2 && srow[j] == -1) srow[j] = -2;     // merging scatter: a pruned row keeps its contents
+  }
   if (t.vec) {
     constexpr int V = 16 / sizeof(E);
     const u32x4_t zero = {0u, 0u, 0u, 0u};
@@ -139,7 +143,8 @@ __device__ __forceinline__ void map_cols_block(const MapItemDev& t, int blk) {
   for (int v = 0; v < V; ++v) sc[v] = (c0 + v < t.dst_slots) ? map_slot(t.m, c0 + v) : -1;
   const long long r0 = static_cast<long long>(by) * t.rpb;
   const long long r1 = (r0 + t.rpb < t.other) ? r0 + t.rpb : t.other;
-  const bool full = c0 + V <= t.dst_slots;
+  const bool merge = t.m.scatter == 2;          // merging scatter: slots without a source are not written
+  const bool full = c0 + V <= t.dst_slots && !merge;
   for (long long rb = r0; rb < r1; rb += MAP_COL_ROWS) {
     alignas(16) E vals[MAP_COL_ROWS][V];
 #pragma unroll
@@ -158,7 +163,7 @@ __device__ __forceinline__ void map_cols_block(const MapItemDev& t, int blk) {
       } else {
 #pragma unroll
         for (int v = 0; v < V; ++v)
-          if (c0 + v < t.dst_slots) d[v] = vals[q][v];
+          if (c0 + v < t.dst_slots && (sc[v] >= 0 || !merge)) d[v] = vals[q][v];
       }
     }
   }
@@ -302,6 +307,7 @@ static int validate_map(const ecospa_map_item& q) {
   if (!q.src || !q.dst || !q.idx) return ECOSPA_ERR_NULL;
   if (!dtype_ok(q.dtype)) return ECOSPA_ERR_DTYPE;
   if (q.axis != 0 && q.axis != 1) return ECOSPA_ERR_SHAPE;
+  if (q.scatter < 0 || q.scatter > 2) return ECOSPA_ERR_SHAPE;
   if (q.groups < 1 || q.n < 1 || q.unit < 1 || q.n % q.unit || q.other_extent < 1) return ECOSPA_ERR_SHAPE;
   if (q.idx_div < 0 || (q.idx_div > 1 && q.groups % q.idx_div)) return ECOSPA_ERR_SHAPE;
   if (q.k_group) {      // ragged: the counts live on the device, only the capacities can be checked here
@@ -350,7 +356,7 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
       const ecospa_map_item& q = items[first + i];
       MapItemDev& t = b.it[i];
       t.src = q.src; t.dst = q.dst;
-      t.m = MapArgs{q.idx, q.groups, q.n, q.unit, q.k, q.kp, q.scatter ? 1 : 0, q.k_group, q.ld_idx ? q.ld_idx : q.k, q.idx_div > 0 ? q.idx_div : 1};
+      t.m = MapArgs{q.idx, q.groups, q.n, q.unit, q.k, q.kp, q.scatter, q.k_group, q.ld_idx ? q.ld_idx : q.k, q.idx_div > 0 ? q.idx_div : 1};
       const long long full_slots = static_cast<long long>(q.groups) * q.n;
       const long long cmp_slots = static_cast<long long>(q.groups) * q.kp * q.unit;
       t.dst_slots = q.scatter ? full_slots : cmp_slots;
@@ -366,7 +372,7 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
       } else {
         t.vec = aligned16(q.dst) && q.ld_dst % V == 0;
         // the LDS path reads whole 16-byte chunks of the source rows, up to the end of the last kept chunk
-        t.lds_path = t.vec && aligned16(q.src) && q.ld_src % V == 0 && (q.scatter ? cmp_slots : full_slots) % V == 0;
+        t.lds_path = t.vec && q.scatter != 2 && aligned16(q.src) && q.ld_src % V == 0 && (q.scatter ? cmp_slots : full_slots) % V == 0;
         if (t.lds_path) {
           t.gx = static_cast<int>((t.dst_slots + MAP_LDS_GROUPS * V - 1) / (MAP_LDS_GROUPS * V));
           int rpb = MAP_LDS_ROWS_TOTAL;

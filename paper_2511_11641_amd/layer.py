@@ -39,7 +39,7 @@ class FfnBlock:
         entries of idx[1, n] count (read back once here to size the compact matrices)."""
         c = self.ctx
         k = idx.shape[1] if k_group is None else int(k_group.item())
-        self.idx, self.k = idx, k
+        self.idx, self.k, self.k_group = idx, k, k_group
         self.kp = kp = B.round_up(k, 16)
         nh = 2 * kp if self.gated else kp
         dt, dev = self.w1.dtype, self.w1.device
@@ -47,16 +47,7 @@ class FfnBlock:
             self.w1_c = torch.empty((nh, self.d), dtype=dt, device=dev)
             self.b1_c = None if self.b1 is None else torch.zeros((nh,), dtype=dt, device=dev)
             self.w2_c = torch.empty((self.d, kp), dtype=dt, device=dev)
-
-        def mk(src, dst, axis):
-            return B.Context.map_item(src, dst, idx, axis, 1, self.n, 1, kp, k_group=k_group)
-
-        items = [mk(self.w1, self.w1_c[:kp], 0)]
-        if self.gated:
-            items.append(mk(self.w1b, self.w1_c[kp:], 0))
-        if self.b1 is not None:       # the up branch of a gated FFN has no bias: its slots stay zero
-            items.append(mk(self.b1, self.b1_c[:kp], 1))
-        items.append(mk(self.w2, self.w2_c, 1))
+        items = self._map_items(0)
         if self.transposed and (getattr(self, "w1_t", None) is None or self.w1_t.shape[1] != nh):
             self.w1_t = torch.empty((self.d, nh), dtype=dt, device=dev)
             self.w2_t = torch.empty((kp, self.d), dtype=dt, device=dev)
@@ -65,6 +56,22 @@ class FfnBlock:
         c.ecospa_compact_batch(items)
         self.refresh_transposed()
         return self
+
+    def _map_items(self, scatter: int):
+        """Descriptors between every full-size member and its compact counterpart: gathers (0) or scatters (1, 2)."""
+        kp = self.kp
+        members = [(self.w1, self.w1_c[:kp], 0)]
+        if self.gated:
+            members.append((self.w1b, self.w1_c[kp:], 0))
+        if self.b1 is not None:       # the up branch of a gated FFN has no bias: its slots stay zero
+            members.append((self.b1, self.b1_c[:kp], 1))
+        members.append((self.w2, self.w2_c, 1))
+        return [B.Context.map_item(c if scatter else f, f if scatter else c, self.idx, axis, 1, self.n, 1, kp,
+                                   scatter=scatter, k_group=self.k_group) for f, c, axis in members]
+
+    def write_back_items(self):
+        """Scatters of the compact tensors into the full-size ones that leave the pruned rows/columns as they are."""
+        return self._map_items(2)
 
     def transpose_items(self):
         if not self.transposed:
@@ -159,20 +166,7 @@ class AttnBlock:
             self.wqkv_c = torch.empty((nq + nk + nv, self.d), dtype=dt, device=dev)
             self.bqkv_c = None if self.bq is None else torch.empty((nq + nk + nv,), dtype=dt, device=dev)
             self.wo_c = torch.empty((self.d, no), dtype=dt, device=dev)
-
-        def mq(src, dst, axis, heads):      # heads that share an index list with (heads // h_kv - 1) others
-            return B.Context.map_item(src, dst, idx_qk, axis, heads, dh, u, kpu, k_group=k_qk_group, idx_div=heads // hk)
-
-        def mv(src, dst, axis, heads):
-            return B.Context.map_item(src, dst, idx_vo, axis, heads, dh, 1, self.kp_vo, k_group=k_vo_group,
-                                      idx_div=heads // hk)
-
-        items = [mq(self.wq, self.wqkv_c[:nq], 0, h), mq(self.wk, self.wqkv_c[nq:nq + nk], 0, hk),
-                 mv(self.wv, self.wqkv_c[nq + nk:], 0, hk)]
-        if self.bq is not None:
-            items += [mq(self.bq, self.bqkv_c[:nq], 1, h), mq(self.bk, self.bqkv_c[nq:nq + nk], 1, hk),
-                      mv(self.bv, self.bqkv_c[nq + nk:], 1, hk)]
-        items.append(mv(self.wo, self.wo_c, 1, h))
+        items = self._map_items(0)
         if self.transposed and (getattr(self, "wqkv_t", None) is None or self.wqkv_t.shape[1] != nq + nk + nv):
             self.wqkv_t = torch.empty((self.d, nq + nk + nv), dtype=dt, device=dev)
             self.wo_t = torch.empty((no, self.d), dtype=dt, device=dev)
@@ -182,6 +176,31 @@ class AttnBlock:
         if self.rope and getattr(self, "cos", None) is not None:     # kept blocks changed: new frequencies
             self._rope_table(self._L, out=(self.cos, self.sin))
         return items if defer else self
+
+    def _map_items(self, scatter: int):
+        """Descriptors between every full-size member and its compact counterpart: gathers (0) or scatters (1, 2)."""
+        h, hk, dh, u = self.h, self.h_kv, self.d_h, self.unit
+        nq, nk, kpu = self.nq, self.nk, self.kp_qk // u
+
+        def mq(full, cmp, axis, heads):      # heads that share an index list with (heads // h_kv - 1) others
+            return B.Context.map_item(cmp if scatter else full, full if scatter else cmp, self.idx_qk, axis, heads, dh, u, kpu,
+                                      scatter=scatter, k_group=self.k_qk_group, idx_div=heads // hk)
+
+        def mv(full, cmp, axis, heads):
+            return B.Context.map_item(cmp if scatter else full, full if scatter else cmp, self.idx_vo, axis, heads, dh, 1,
+                                      self.kp_vo, scatter=scatter, k_group=self.k_vo_group, idx_div=heads // hk)
+
+        items = [mq(self.wq, self.wqkv_c[:nq], 0, h), mq(self.wk, self.wqkv_c[nq:nq + nk], 0, hk),
+                 mv(self.wv, self.wqkv_c[nq + nk:], 0, hk)]
+        if self.bq is not None:
+            items += [mq(self.bq, self.bqkv_c[:nq], 1, h), mq(self.bk, self.bqkv_c[nq:nq + nk], 1, hk),
+                      mv(self.bv, self.bqkv_c[nq + nk:], 1, hk)]
+        items.append(mv(self.wo, self.wo_c, 1, h))
+        return items
+
+    def write_back_items(self):
+        """Scatters of the compact tensors into the full-size ones that leave the pruned rows/columns as they are."""
+        return self._map_items(2)
 
     def transpose_items(self):
         if not self.transposed:

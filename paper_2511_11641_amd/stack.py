@@ -1,0 +1,244 @@
+"""A stack of pre-norm decoder layers around the library's blocks: the harness of the multi-layer workloads
+(a training step of the whole model with the coupled importance estimated again every so many steps, and
+forward-only inference at several keep ratios).
+
+What runs where.  Through the C ABI: the coupled scores (Eq. 10) of every pair of every layer in one call,
+the selection, the aligned gather of parameters, master copies and optimizer moments (Def. 1, Alg. 1), their
+write-back into the full-size arrays before the next estimate, both blocks' forward and backward
+contractions, the contractions of the output projection onto the vocabulary, and the AdamW update of every
+tensor.  Torch operators: the glue that is the same for a dense and a sparse model and is no part of the
+method - embedding lookup, LayerNorm / RMSNorm (and their backward, through autograd on the one operator),
+residual additions, the cross-entropy loss.
+
+State between two estimates is compact (Alg. 1 removes rows and columns for good; here the full-size arrays
+stay resident so that the next estimate can bring a dimension back): fp32 master weights and both moments
+live in the compact layout and only they are updated; pruned rows/columns of the full-size arrays are
+frozen - no gradient reaches them - until `prune()` writes the compact state back, scores the full-size
+master weights again and gathers the new choice.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+import torch.nn.functional as F
+
+from . import binding as B
+from .layer import AttnBlock, FfnBlock
+
+FAMILIES = ("w", "mst", "m", "v")      # bf16 working copy, fp32 master, first and second moment
+
+
+class _Param:
+    """A glue parameter (embedding, norm gain, output projection): bf16 working copy, fp32 master, moments."""
+
+    def __init__(self, value: torch.Tensor, train: bool):
+        self.w = value.to(torch.bfloat16).contiguous()
+        self.g = None
+        if train:
+            self.mst = self.w.float()
+            self.m, self.v = torch.zeros_like(self.mst), torch.zeros_like(self.mst)
+            self.g = torch.zeros_like(self.w)
+
+    def item(self):
+        return B.Context.adamw_item(self.mst, self.g, self.m, self.v, self.w)
+
+
+class _Layer:
+    pass
+
+
+class DecoderStack:
+    def __init__(self, ctx: B.Context, cfg: dict, n_layers: int, vocab: int, keep=(1, 2), seed: int = 0,
+                 train: bool = True, lr: float = 1e-4, weight_decay: float = 0.01):
+        """cfg: B, L, d, h, d_h, d_ff, gated, rope, bias as in synth.CONFIGS (gated: RMSNorm, no position table;
+        otherwise LayerNorm with a learned position table).  keep = (num, den): every pair keeps
+        floor(n * num / den) of its units; (1, 1) is the dense model through the same code."""
+        self.ctx, self.cfg, self.train = ctx, cfg, train
+        self.Bsz, self.L, self.d, self.h, self.d_h, self.d_ff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
+        self.T = self.Bsz * self.L
+        self.vocab, self.lr, self.wd, self.t = vocab, lr, weight_decay, 0
+        self.rms = bool(cfg["gated"])
+        self.eps = 1e-6 if self.rms else 1e-5
+        gen = torch.Generator(device="cuda").manual_seed(seed)
+        d, h, dh, dff = self.d, self.h, self.d_h, self.d_ff
+
+        def rnd(*shape):
+            return torch.randn(*shape, device="cuda", generator=gen) * 0.02
+
+        fams = FAMILIES if train else ("w",)
+        act = B.ACT_SWIGLU if cfg["gated"] else B.ACT_GELU_ERF
+        unit = 2 if cfg["rope"] else 1
+        num, den = keep
+        self.k = ((dh // unit) * num // den, dh * num // den, dff * num // den)
+        self.layers = []
+        for _ in range(n_layers):
+            ly = _Layer()
+            names = ["wq", "wk", "wv", "wo", "w1", "w2"] + (["w1b"] if cfg["gated"] else [])
+            shapes = {"wq": (h * dh, d), "wk": (h * dh, d), "wv": (h * dh, d), "wo": (d, h * dh), "w1": (dff, d),
+                      "w1b": (dff, d), "w2": (d, dff)}
+            bias_shapes = {"bq": h * dh, "bk": h * dh, "bv": h * dh, "bo": d, "b1": dff, "b2": d} if cfg["bias"] else {}
+            init = {n: rnd(*shapes[n]).to(torch.bfloat16) for n in names}
+            init.update({n: torch.zeros(s, device="cuda", dtype=torch.bfloat16) for n, s in bias_shapes.items()})
+            ly.full, ly.attn, ly.ffn = {}, {}, {}
+            for fam in fams:
+                if fam == "w":
+                    t = init
+                elif fam == "mst":
+                    t = {n: x.float() for n, x in init.items()}
+                else:
+                    t = {n: torch.zeros(x.shape, device="cuda") for n, x in init.items()}
+                ly.full[fam] = t
+                ly.attn[fam] = AttnBlock(ctx, t["wq"], t["wk"], t["wv"], t["wo"], t.get("bq"), t.get("bk"), t.get("bv"),
+                                         t.get("bo"), h, dh, rope=cfg["rope"], causal=True, transposed=(fam == "w" and train))
+                ly.ffn[fam] = FfnBlock(ctx, t["w1"], t.get("b1"), t["w2"], t.get("b2"), act, t.get("w1b"),
+                                       transposed=(fam == "w" and train))
+            ly.idx = [torch.empty((h, self.k[0]), dtype=torch.int32, device="cuda"),
+                      torch.empty((h, self.k[1]), dtype=torch.int32, device="cuda"),
+                      torch.empty((1, self.k[2]), dtype=torch.int32, device="cuda")]
+            ly.norm = [self._norm_params() for _ in range(2)]
+            self.layers.append(ly)
+        self.emb = _Param(rnd(vocab, d), train)
+        self.pos = None if cfg["rope"] else _Param(rnd(self.L, d), train)
+        self.lm = _Param(rnd(vocab, d), train)
+        self.norm_f = self._norm_params()
+        # the pairs that are scored: the fp32 master weights when they exist, else the working copy
+        sf = "mst" if train else "w"
+        self.pairs = [p for ly in self.layers for p in ly.attn[sf].pairs() + [ly.ffn[sf].pair()]]
+        self.pair_arr = (B.Pair * len(self.pairs))(*self.pairs)
+        self.scores = None
+        self.compacted = False
+        self.prune()
+        for ly in self.layers:
+            ly.attn["w"].alloc(self.Bsz, self.L)
+            ly.ffn["w"].alloc(self.Bsz, self.L)
+        if train:
+            self._build_optimizer()
+
+    # ---- glue ---------------------------------------------------------------------------------------
+    def _norm_params(self):
+        ps = [_Param(torch.ones(self.d, device="cuda"), self.train)]
+        if not self.rms:
+            ps.append(_Param(torch.zeros(self.d, device="cuda"), self.train))
+        for p in ps:
+            p.w.requires_grad_(self.train)
+        return ps
+
+    def _norm(self, x, ps):
+        if self.rms:
+            return F.rms_norm(x, (self.d,), ps[0].w, self.eps)
+        return F.layer_norm(x, (self.d,), ps[0].w, ps[1].w, self.eps)
+
+    def _norm_fwd(self, x, ps):
+        """-> (input leaf, output): the operator runs under autograd when training, so that its backward is one call."""
+        if not self.train:
+            return None, self._norm(x, ps)
+        leaf = x.detach().requires_grad_(True)
+        with torch.enable_grad():
+            y = self._norm(leaf, ps)
+        return leaf, y
+
+    @staticmethod
+    def _norm_bwd(leaf, y, ps, dy):
+        grads = torch.autograd.grad(y, [leaf] + [p.w for p in ps], dy)
+        for p, g in zip(ps, grads[1:]):
+            p.g.copy_(g)
+        return grads[0]
+
+    # ---- steps 1-3 for the whole stack -----------------------------------------------------------------
+    def prune(self):
+        """Estimate the importance again and gather the new choice: write the compact state back, score the full-size
+        weights (one call for all pairs of all layers), select (one call), gather every family (one call)."""
+        ctx = self.ctx
+        fams = FAMILIES if self.train else ("w",)
+        if self.compacted and self.train:
+            ctx.ecospa_compact_batch([it for ly in self.layers for fam in fams
+                                      for it in ly.attn[fam].write_back_items() + ly.ffn[fam].write_back_items()])
+        self.scores = ctx.ecospa_coupled_score(self.pair_arr, out=self.scores)
+        sel = [ctx.select_item(s, self.k[i % 3], self.layers[i // 3].idx[i % 3]) for i, s in enumerate(self.scores)]
+        ctx.ecospa_select_topk_batch(sel)
+        items = []
+        for ly in self.layers:
+            for fam in fams:
+                items += ly.attn[fam].compact(ly.idx[0], ly.idx[1], defer=True) + ly.ffn[fam].compact(ly.idx[2], defer=True)
+        ctx.ecospa_compact_batch(items)
+        self._refresh_transposed()
+        self.compacted = True
+
+    def _refresh_transposed(self):
+        tr = [it for ly in self.layers for it in ly.attn["w"].transpose_items() + ly.ffn["w"].transpose_items()]
+        if tr:
+            self.ctx.ecospa_transpose_batch(tr)
+
+    def _build_optimizer(self):
+        """Two groups of tensors: matrices (decoupled weight decay) and vectors - biases, norm gains - without it."""
+        mk, mats, vecs = B.Context.adamw_item, [], []
+        for ly in self.layers:
+            for blk, names in ((ly.attn, (("wqkv_c", "dwqkv_c"), ("wo_c", "dwo_c"), ("bqkv_c", "dbqkv_c"), ("bo", "dbo"))),
+                               (ly.ffn, (("w1_c", "dw1_c"), ("w2_c", "dw2_c"), ("b1_c", "db1_c"), ("b2", "db2")))):
+                for name, grad in names:
+                    if getattr(blk["w"], name) is not None:
+                        (mats if name.startswith("w") else vecs).append(
+                            mk(getattr(blk["mst"], name), getattr(blk["w"], grad), getattr(blk["m"], name),
+                               getattr(blk["v"], name), getattr(blk["w"], name)))
+            vecs += [p.item() for ps in ly.norm for p in ps]
+        vecs += [p.item() for p in self.norm_f]
+        mats += [self.emb.item(), self.lm.item()] + ([] if self.pos is None else [self.pos.item()])
+        self.opt_mats, self.opt_vecs = (B.AdamwItem * len(mats))(*mats), (B.AdamwItem * len(vecs))(*vecs)
+        self.n_params = sum(int(it.n) for it in mats + vecs)
+
+    # ---- forward / backward / update -------------------------------------------------------------------------
+    @torch.no_grad()
+    def forward(self, ids: torch.Tensor, lm_head: bool = True):
+        """ids: int64 [B*L] -> logits bf16 [B*L, vocab] (or the final hidden states with lm_head=False)."""
+        x = self.emb.w[ids]
+        if self.pos is not None:
+            x = (x.view(self.Bsz, self.L, self.d) + self.pos.w).view(self.T, self.d)
+        for ly in self.layers:
+            ly.leaf1, ly.h1 = self._norm_fwd(x, ly.norm[0])
+            x = x + ly.attn["w"].fwd(ly.h1.detach())
+            ly.leaf2, ly.h2 = self._norm_fwd(x, ly.norm[1])
+            x = x + ly.ffn["w"].fwd(ly.h2.detach())
+        self.leaf_f, self.hf = self._norm_fwd(x, self.norm_f)
+        if not lm_head:
+            return self.hf
+        self.logits = self.ctx.ecospa_contract(self.hf.detach(), False, self.lm.w, False, splits=1,
+                                               out=getattr(self, "logits", None))
+        return self.logits
+
+    @torch.no_grad()
+    def backward(self, ids: torch.Tensor, targets: torch.Tensor):
+        """Mean cross-entropy of the last forward's logits against targets; fills every gradient buffer."""
+        ctx = self.ctx
+        lg = self.logits.detach().requires_grad_(True)
+        with torch.enable_grad():
+            loss = F.cross_entropy(lg.float(), targets)
+        (dl,) = torch.autograd.grad(loss, lg)
+        hf = self.hf.detach()
+        ctx.ecospa_contract(dl, True, hf, True, splits=1, out=self.lm.g)              # dW = dlogits^T h
+        dhf = ctx.ecospa_contract(dl, False, self.lm.w, True, splits=1)                # dh = dlogits W
+        dx = self._norm_bwd(self.leaf_f, self.hf, self.norm_f, dhf)
+        for ly in reversed(self.layers):
+            dh2 = ly.ffn["w"].bwd(ly.h2.detach(), dx)
+            dx = dx + self._norm_bwd(ly.leaf2, ly.h2, ly.norm[1], dh2)
+            dh1 = ly.attn["w"].bwd(ly.h1.detach(), dx)
+            dx = dx + self._norm_bwd(ly.leaf1, ly.h1, ly.norm[0], dh1)
+        self.emb.g.zero_()
+        self.emb.g.index_add_(0, ids, dx)
+        if self.pos is not None:
+            self.pos.g.copy_(dx.view(self.Bsz, self.L, self.d).sum(0))
+        return loss.detach()
+
+    def update(self):
+        """AdamW on every compact tensor and glue parameter (fp32 masters and moments, bf16 working copies written by
+        the same kernel), then the transposed copies the backward contractions read."""
+        self.t += 1
+        self.ctx.ecospa_adamw(self.opt_mats, self.t, self.lr, weight_decay=self.wd)
+        self.ctx.ecospa_adamw(self.opt_vecs, self.t, self.lr, weight_decay=0.0)
+        self._refresh_transposed()
+
+    def train_step(self, ids, targets):
+        self.forward(ids)
+        loss = self.backward(ids, targets)
+        self.update()
+        return loss.detach()

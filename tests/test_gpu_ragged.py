@@ -75,6 +75,45 @@ def test_ragged_gather_and_scatter(ctx, dtype, axis, groups, n, unit, other, pad
     assert np.array_equal(host(c2), O.compact_ragged(w, idx, np.minimum(ks, kq), axis, n, kq, unit).astype(np.float64))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("axis", [0, 1])
+@pytest.mark.parametrize("groups,n,unit,other", [(16, 64, 1, 1024), (32, 64, 2, 520), (1, 1000, 1, 333), (5, 12, 2, 7), (3, 40, 1, 4100)])
+def test_merging_scatter_leaves_pruned_slots_untouched(ctx, dtype, axis, groups, n, unit, other):
+    """Compact parameters / moments written back into a full-size array (scatter mode 2): bit for bit the oracle's
+    scatter onto a base, with a kept count per group and with one count for all."""
+    nu = n // unit
+    idx, ks = _ragged_idx(groups * 17 + n, groups, nu)
+    shape_f = (groups * n, other) if axis == 0 else (other, groups * n)
+    shape_c = (groups * nu * unit, other) if axis == 0 else (other, groups * nu * unit)
+    base = synth.round_to(synth.normal(41, 1, shape_f), dtype)
+    c = synth.round_to(synth.normal(41, 2, shape_c), dtype)
+    gi, gk = torch.from_numpy(idx).cuda(), torch.from_numpy(ks).cuda()
+    out = dev(base, dtype).clone()
+    ctx.ecospa_compact_ragged(dev(c, dtype), gi, gk, axis, groups, n, nu, unit, scatter=2, out=out)
+    assert np.array_equal(host(out), O.scatter_ragged(c, idx, ks, axis, n, nu, unit, base=base).astype(np.float64))
+    # one count for every group (no count array), compact layout padded beyond k
+    k = max(1, nu // 2)
+    rng = np.random.default_rng(n)
+    iu = np.stack([np.sort(rng.choice(nu, k, replace=False)) for _ in range(groups)]).astype(np.int32)
+    out = dev(base, dtype).clone()
+    ctx.ecospa_compact_batch([ctx.map_item(dev(c, dtype), out, torch.from_numpy(iu).cuda(), axis, groups, n, unit, nu, scatter=2)])
+    assert np.array_equal(host(out), O.scatter_ragged(c, iu, np.full(groups, k), axis, n, nu, unit, base=base).astype(np.float64))
+
+
+def test_merging_scatter_of_a_vector_and_bad_mode(ctx):
+    groups, n = 4, 24
+    idx, ks = _ragged_idx(5, groups, n)
+    base, c = synth.normal(42, 1, (groups * n,)).astype(np.float32), synth.normal(42, 2, (groups * n,)).astype(np.float32)
+    out = torch.from_numpy(base).cuda()
+    ctx.ecospa_compact_ragged(torch.from_numpy(c).cuda(), torch.from_numpy(idx).cuda(), torch.from_numpy(ks).cuda(), 1, groups, n, n, 1,
+                              scatter=2, out=out)
+    assert np.array_equal(out.cpu().numpy(), O.scatter_ragged(c, idx, ks, 1, n, n, 1, base=base))
+    with pytest.raises(B.EcospaError) as e:
+        ctx.ecospa_compact_ragged(torch.from_numpy(c).cuda(), torch.from_numpy(idx).cuda(), torch.from_numpy(ks).cuda(), 1, groups, n, n, 1,
+                                  scatter=3, out=out)
+    assert e.value.code == B.ERR_SHAPE
+
+
 def test_ragged_vector_and_rope_table(ctx):
     groups, n, L = 6, 32, 50
     idx, ks = _ragged_idx(3, groups, n // 2)

@@ -95,6 +95,33 @@ def test_ragged_scatter_inverts_gather_and_is_its_adjoint(axis, unit):
     np.testing.assert_array_equal(cb, O.compact_ragged(b[None, :], idx, ks, 1, n, kp, unit)[0])
 
 
+@pytest.mark.parametrize("axis", (0, 1))
+@pytest.mark.parametrize("unit", (1, 2))
+def test_scatter_into_a_base_touches_only_the_kept_slots(axis, unit):
+    groups, n = 3, 12
+    idx, ks = _ragged_case(8, groups, n, unit)
+    kp = n // unit
+    shape = (groups * n, 5) if axis == 0 else (5, groups * n)
+    base = synth.normal(14, 1, shape).astype(np.float64)
+    c = synth.normal(14, 2, (groups * kp * unit, 5) if axis == 0 else (5, groups * kp * unit)).astype(np.float64)
+    got = O.scatter_ragged(c, idx, ks, axis, n, kp, unit, base=base)
+    keep = np.zeros(groups * n, dtype=bool)
+    for g in range(groups):
+        for i in idx[g, :ks[g]]:
+            keep[g * n + i * unit:g * n + (i + 1) * unit] = True
+    km = keep[:, None] if axis == 0 else keep[None, :]
+    # outside the kept slots the base survives, inside them the zero-filling scatter's values stand
+    np.testing.assert_array_equal(np.where(km, 0.0, got), np.where(km, 0.0, base))
+    np.testing.assert_array_equal(np.where(km, got, 0.0), O.scatter_ragged(c, idx, ks, axis, n, kp, unit))
+    # gathering again returns what was written (padding slots of c aside), and a base of zeros is the plain scatter
+    back = O.compact_ragged(got, idx, ks, axis, n, kp, unit)
+    np.testing.assert_array_equal(back, O.compact_ragged(O.scatter_ragged(c, idx, ks, axis, n, kp, unit), idx, ks, axis, n, kp, unit))
+    np.testing.assert_array_equal(O.scatter_ragged(c, idx, ks, axis, n, kp, unit, base=np.zeros(shape)),
+                                  O.scatter_ragged(c, idx, ks, axis, n, kp, unit))
+    # writing back what was gathered from the base changes nothing
+    np.testing.assert_array_equal(O.scatter_ragged(O.compact_ragged(base, idx, ks, axis, n, kp, unit), idx, ks, axis, n, kp, unit, base=base), base)
+
+
 # ---- zero padding is exact in the layer maths: a ragged layer equals its padded dense form ---------------
 def test_padded_heads_equal_the_sum_of_ragged_heads():
     """Eq. 4 is a sum over heads, each with an inner width of its own: heads of unequal width computed one
