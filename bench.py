@@ -291,6 +291,73 @@ def inference_sweep(ctx, name, steps):
     return {"workload": name, "pass": "forward only", "rows": rows}
 
 
+def _stack_flops(st, k_qk, k_vo, k_ff, passes):
+    """Model flops of the stack: the layers' contractions and attention (causal at half) plus the output projection."""
+    c = st.cfg
+    per_layer = model_flops(st.T, st.L, st.d, st.h, k_qk, k_vo, k_ff, gated=c["gated"]) / 3.0
+    return passes * (len(st.layers) * per_layer + 2.0 * st.T * st.d * st.vocab)
+
+
+def stack_training(ctx, name, n_layers, vocab, Bsz, L, keeps, steps, rescore_every=200):
+    """Whole-model training step of a stack of `name`-shaped layers (embedding, pre-norm layers, output projection,
+    cross-entropy, AdamW with fp32 master weights): per keep ratio the time of a plain step, of a step that first
+    estimates the coupled importance again (write-back, score, select, gather of all layers), and the throughput with
+    one such step in every `rescore_every`.  Norms, residuals, embedding and loss are torch operators; everything else
+    runs in the library."""
+    import torch
+    from paper_2511_11641_amd import synth
+    from paper_2511_11641_amd.stack import DecoderStack
+    cfg = dict(synth.CONFIGS[name], B=Bsz, L=L)
+    T, rows, dense_ms = Bsz * L, [], None
+    ids = torch.randint(0, vocab, (T,), device="cuda")
+    tgt = torch.roll(ids, -1)
+    for num, den in keeps:
+        st = DecoderStack(ctx, cfg, n_layers, vocab, keep=(num, den), seed=1, train=True)
+        ms_step = timed(torch, lambda: st.train_step(ids, tgt), steps, 2)
+        ms_fwd = timed(torch, lambda: st.forward(ids), steps, 1)
+        ms_bwd = timed(torch, lambda: (st.forward(ids), st.backward(ids, tgt)), steps, 1) - ms_fwd
+        ms_upd = timed(torch, st.update, steps, 1)
+        ms_prune = timed(torch, st.prune, max(2, steps // 2), 1)
+        a, f = st.layers[0].attn["w"], st.layers[0].ffn["w"]
+        fl = _stack_flops(st, a.kp_qk, a.kp_vo, f.kp, 3)
+        dense_ms = ms_step if (num, den) == (1, 1) else dense_ms
+        amort = (rescore_every - 1) * ms_step + (ms_step + ms_prune)
+        rows.append({"keep": f"{num}/{den}", "ms_step": ms_step, "ms_rescore_step": ms_step + ms_prune,
+                     "tokens_per_s": rescore_every * T / (amort * 1e-3), "model_tflops": fl / (ms_step * 1e-3) / 1e12,
+                     "parts_ms": {"fwd": ms_fwd, "bwd": ms_bwd, "adamw_and_transposes": ms_upd, "rescore": ms_prune},
+                     "trained_params_M": st.n_params / 1e6})
+        del st
+        torch.cuda.empty_cache()
+    for r in rows:
+        r["speedup_vs_dense"] = None if dense_ms is None else dense_ms / r["ms_step"]
+    return {"workload": f"{n_layers} x {name}", "batch": Bsz, "seq_len": L, "vocab": vocab,
+            "rescore_every": rescore_every, "rows": rows,
+            "tokens_per_s_formula": "rescore_every * T / ((rescore_every - 1) * ms_step + ms_rescore_step)",
+            "glue": "embedding, norms, residual adds, cross-entropy: torch operators; weights: device RNG, N(0, 0.02)"}
+
+
+def stack_inference(ctx, name, n_layers, vocab, L, keeps, steps):
+    """Forward only of the whole stack (logits for every position) at batch 1 and batch 32."""
+    import torch
+    from paper_2511_11641_amd import synth
+    from paper_2511_11641_amd.stack import DecoderStack
+    rows = []
+    for Bsz in (1, 32):
+        cfg = dict(synth.CONFIGS[name], B=Bsz, L=L)
+        ids = torch.randint(0, vocab, (Bsz * L,), device="cuda")
+        ms_dense = None
+        for num, den in keeps:
+            st = DecoderStack(ctx, cfg, n_layers, vocab, keep=(num, den), seed=1, train=False)
+            ms = timed(torch, lambda: st.forward(ids), steps, 2)
+            ms_layers = timed(torch, lambda: st.forward(ids, lm_head=False), steps, 1)
+            ms_dense = ms if (num, den) == (1, 1) else ms_dense
+            rows.append({"batch": Bsz, "seq_len": L, "keep": f"{num}/{den}", "ms_fwd": ms, "ms_fwd_without_output_projection": ms_layers,
+                         "tokens_per_s": Bsz * L / (ms * 1e-3), "speedup_vs_dense": None if ms_dense is None else ms_dense / ms})
+            del st
+            torch.cuda.empty_cache()
+    return {"workload": f"{n_layers} x {name}", "pass": "forward only, logits for every position", "vocab": vocab, "rows": rows}
+
+
 def cpu_baseline(cfg, seed, keep_num, keep_den, sample_B):
     """The fp64 oracle, as it stands, on `sample_B` batch elements of the same workload."""
     import os
@@ -329,6 +396,18 @@ def cpu_baseline(cfg, seed, keep_num, keep_den, sample_B):
                       f"score+select+compact+fwd+bwd in fp64 numpy, {dt:.1f} s"}
 
 
+def stack_workloads(ctx):
+    """The two whole-model workloads: the LLaMA-1B-shaped 24-layer training step (batch 32 x 256, vocabulary 32000,
+    importance estimated again every 200 steps, 50 % keep, beside the dense model) and the GPT-2-Medium-shaped
+    24-layer sweep over keep ratios (training step at batch 8 x 1024; forward only at batch 1 and 32)."""
+    sweep = ((1, 1), (3, 4), (1, 2), (3, 10))
+    return {
+        "stack_llama1b_train": stack_training(ctx, "c3_llama1b_layer", 24, 32000, 32, 256, ((1, 1), (1, 2)), 4),
+        "stack_gpt2m_train_sweep": stack_training(ctx, "c2_gpt2m_layer", 24, 50304, 8, 1024, sweep, 4),
+        "stack_gpt2m_inference": stack_inference(ctx, "c2_gpt2m_layer", 24, 50304, 1024, sweep, 4),
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -343,6 +422,8 @@ def main():
     ap.add_argument("--prune-only", action="store_true",
                     help="run only the 24-layer pruning pass (score, select, compaction, Eq. 8, threshold rule, AdamW) and "
                          "print its figures (for profiler runs of the HBM-bound kernels)")
+    ap.add_argument("--stacks-only", action="store_true",
+                    help="run only the whole-model workloads (24-layer training step and forward-only sweep) and print their figures")
     ap.add_argument("--sparse-only", action="store_true",
                     help="run only the timed sparse steps (for hardware-counter runs) and print a short line")
     args = ap.parse_args()
@@ -373,6 +454,10 @@ def main():
 
     if args.prune_only:
         print(json.dumps({"prune_24_layers": prune_stack(ctx, cfg, 24, 1, 2, 20)}))
+        return
+
+    if args.stacks_only:
+        print(json.dumps(stack_workloads(ctx)))
         return
 
     sparse = Layer(ctx, cfg, seed, 1, 2)
@@ -432,6 +517,7 @@ def main():
         out["also"] = second_workload(ctx, "c3_llama1b_layer", args.steps, args.warmup)
         out["inference"] = inference_sweep(ctx, name, 20)
         out["torch_dense_fwd_bwd"] = torch_dense_layer(name, 20)
+        out.update(stack_workloads(ctx))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, seed, 1, 2, sample_B=8)
     print(json.dumps(out))

@@ -456,7 +456,13 @@ static int gemm_pipe_choice(const GemmDesc& d) {
     return 5;
   }
   if (d.trans_b) return -1;
-  if (t256x128 >= 192) return 9;  // 256x128, 8 wavefronts, 3-deep ring
+  if (t256x128 >= 192) {
+    // 256x128 (8 wavefronts, 3-deep ring) - or 256x192 when its tiles fit one round where the narrower ones need
+    // two (output widths a little above a multiple of 256: what an FFN keeps at a keep ratio like 3/10)
+    const long long t256x192 = tm256 * ((d.N + 191) / 192);
+    const long long c192 = (t256x192 + 255) / 256 * 192 * 102, c128 = (t256x128 + 255) / 256 * 128 * 108;
+    return c192 < c128 ? 10 : 9;
+  }
   return 4;                       // 128x128
 }
 // Long contractions with a K-slow B operand (K of several thousand, at least a tile per compute unit)

@@ -66,6 +66,15 @@ class DecoderStack:
         def rnd(*shape):
             return torch.randn(*shape, device="cuda", generator=gen) * 0.02
 
+        def rows_aligned(t):
+            """The same matrix with its leading dimension padded to a multiple of 32 elements, so that rows start on
+            16-byte boundaries whatever the dtype (d_ff = 5461 otherwise puts W_down on the element-wise copy paths)."""
+            if t.dim() != 2 or t.shape[1] % 32 == 0:
+                return t
+            buf = torch.zeros((t.shape[0], B.round_up(t.shape[1], 32)), dtype=t.dtype, device=t.device)
+            buf[:, :t.shape[1]] = t
+            return buf[:, :t.shape[1]]
+
         fams = FAMILIES if train else ("w",)
         act = B.ACT_SWIGLU if cfg["gated"] else B.ACT_GELU_ERF
         unit = 2 if cfg["rope"] else 1
@@ -83,11 +92,11 @@ class DecoderStack:
             ly.full, ly.attn, ly.ffn = {}, {}, {}
             for fam in fams:
                 if fam == "w":
-                    t = init
+                    t = {n: rows_aligned(x) for n, x in init.items()}
                 elif fam == "mst":
-                    t = {n: x.float() for n, x in init.items()}
+                    t = {n: rows_aligned(x.float()) for n, x in init.items()}
                 else:
-                    t = {n: torch.zeros(x.shape, device="cuda") for n, x in init.items()}
+                    t = {n: rows_aligned(torch.zeros(x.shape, device="cuda")) for n, x in init.items()}
                 ly.full[fam] = t
                 ly.attn[fam] = AttnBlock(ctx, t["wq"], t["wk"], t["wv"], t["wo"], t.get("bq"), t.get("bk"), t.get("bv"),
                                          t.get("bo"), h, dh, rope=cfg["rope"], causal=True, transposed=(fam == "w" and train))
@@ -146,29 +155,46 @@ class DecoderStack:
         return grads[0]
 
     # ---- steps 1-3 for the whole stack -----------------------------------------------------------------
-    def prune(self):
-        """Estimate the importance again and gather the new choice: write the compact state back, score the full-size
-        weights (one call for all pairs of all layers), select (one call), gather every family (one call)."""
+    def _descriptors(self):
+        """Descriptor arrays of the stack's batched calls, built once: every buffer they name lives as long as the stack."""
         ctx = self.ctx
         fams = FAMILIES if self.train else ("w",)
-        if self.compacted and self.train:
-            ctx.ecospa_compact_batch([it for ly in self.layers for fam in fams
-                                      for it in ly.attn[fam].write_back_items() + ly.ffn[fam].write_back_items()])
-        self.scores = ctx.ecospa_coupled_score(self.pair_arr, out=self.scores)
+        self.scores = ctx.ecospa_coupled_score(self.pair_arr)
         sel = [ctx.select_item(s, self.k[i % 3], self.layers[i // 3].idx[i % 3]) for i, s in enumerate(self.scores)]
-        ctx.ecospa_select_topk_batch(sel)
-        items = []
+        gather, back = [], []
         for ly in self.layers:
-            for fam in fams:
-                items += ly.attn[fam].compact(ly.idx[0], ly.idx[1], defer=True) + ly.ffn[fam].compact(ly.idx[2], defer=True)
-        ctx.ecospa_compact_batch(items)
+            for fam in fams:          # compact() with defer=True also sizes the family's compact buffers
+                gather += ly.attn[fam].compact(ly.idx[0], ly.idx[1], defer=True) + ly.ffn[fam].compact(ly.idx[2], defer=True)
+                if self.train:
+                    back += ly.attn[fam].write_back_items() + ly.ffn[fam].write_back_items()
+        tr = [it for ly in self.layers for it in ly.attn["w"].transpose_items() + ly.ffn["w"].transpose_items()]
+        self._sel = (B.SelectItem * len(sel))(*sel)
+        self._gather = (B.MapItem * len(gather))(*gather)
+        self._back = (B.MapItem * len(back))(*back) if back else None
+        self._tr = (B.TransposeItem * len(tr))(*tr) if tr else None
+
+    def prune(self):
+        """Estimate the importance again and gather the new choice: write the compact state back into the full-size
+        arrays (not before the first estimate), score the full-size weights (one call for all pairs of all layers),
+        select (one call), gather every family (one call), refresh the transposed copies and the rotary tables."""
+        ctx = self.ctx
+        if getattr(self, "_gather", None) is None:
+            self._descriptors()
+        if self.compacted and self._back is not None:
+            ctx.ecospa_compact_batch(self._back)
+        ctx.ecospa_coupled_score(self.pair_arr, out=self.scores)
+        ctx.ecospa_select_topk_batch(self._sel)
+        ctx.ecospa_compact_batch(self._gather)
         self._refresh_transposed()
+        if self.cfg["rope"] and self.compacted:      # kept rotary blocks changed: new frequencies (the first tables come with alloc)
+            for ly in self.layers:
+                a = ly.attn["w"]
+                a._rope_table(a._L, out=(a.cos, a.sin))
         self.compacted = True
 
     def _refresh_transposed(self):
-        tr = [it for ly in self.layers for it in ly.attn["w"].transpose_items() + ly.ffn["w"].transpose_items()]
-        if tr:
-            self.ctx.ecospa_transpose_batch(tr)
+        if self._tr is not None:
+            self.ctx.ecospa_transpose_batch(self._tr)
 
     def _build_optimizer(self):
         """Two groups of tensors: matrices (decoupled weight decay) and vectors - biases, norm gains - without it."""
