@@ -424,6 +424,8 @@ def main():
                          "print its figures (for profiler runs of the HBM-bound kernels)")
     ap.add_argument("--stacks-only", action="store_true",
                     help="run only the whole-model workloads (24-layer training step and forward-only sweep) and print their figures")
+    ap.add_argument("--stack-step-only", action="store_true",
+                    help="run only the LLaMA-1B-shaped 24-layer training workload at 50 %% keep (for profiler runs)")
     ap.add_argument("--sparse-only", action="store_true",
                     help="run only the timed sparse steps (for hardware-counter runs) and print a short line")
     args = ap.parse_args()
@@ -456,6 +458,9 @@ def main():
         print(json.dumps({"prune_24_layers": prune_stack(ctx, cfg, 24, 1, 2, 20)}))
         return
 
+    if args.stack_step_only:
+        print(json.dumps({"stack_llama1b_train": stack_training(ctx, "c3_llama1b_layer", 24, 32000, 32, 256, ((1, 2),), 4)}))
+        return
     if args.stacks_only:
         print(json.dumps(stack_workloads(ctx)))
         return

@@ -40,7 +40,9 @@ class FfnBlock:
         c = self.ctx
         k = idx.shape[1] if k_group is None else int(k_group.item())
         self.idx, self.k, self.k_group = idx, k, k_group
-        self.kp = kp = B.round_up(k, 16)
+        # padded width: a multiple of the contraction kernels' slab depth (64) once that costs little, so that the
+        # contractions over the kept units (the second FFN matrix, the input gradient) can take the pipelined kernel
+        self.kp = kp = B.round_up(k, 64 if k >= 512 else 16)
         nh = 2 * kp if self.gated else kp
         dt, dev = self.w1.dtype, self.w1.device
         if getattr(self, "w1_c", None) is None or self.w1_c.shape[0] != nh:     # buffers are reused across re-compactions
