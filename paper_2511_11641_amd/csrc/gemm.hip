@@ -467,9 +467,15 @@ static int gemm_pipe_choice(const GemmDesc& d) {
 }
 // Long contractions with a K-slow B operand (K of several thousand, at least a tile per compute unit)
 // run fastest on the two-slab register prefetch of gemm_rs.hip.
+static int gemm_rs_tt_plan(int M, int N, int K, bool* ok);
 static bool gemm_prefers_rs(const GemmDesc& d) {
+  if (d.trans_a) {      // dY^T X: when the split count is the one planned for this kernel
+    bool ok;
+    const int s = gemm_rs_tt_plan(d.M, d.N, d.K, &ok);
+    return d.trans_b && ok && (d.splits > 1 ? d.splits : 1) == s;
+  }
   const long long t256 = static_cast<long long>((d.M + 255) / 256) * ((d.N + 255) / 256);
-  return !d.trans_a && d.trans_b && d.splits <= 1 && d.K >= 4096 && t256 >= 192;
+  return d.trans_b && d.splits <= 1 && d.K >= 4096 && t256 >= 192;
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int WPE, bool TRR>
@@ -501,7 +507,24 @@ static hipError_t launch_tile(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Weight-gradient contractions (dY^T X: K = tokens, few output tiles) on the register-prefetch kernel of
+// gemm_rs.hip: 256x256 tiles, one workgroup per compute unit, so K is split until the tiles fill one round of
+// 256 - at most 4 ways and with at least 1024 of K per split (beyond that the partial sums cost more than the
+// better tile gains; measured on the layer and stack shapes).  *ok: the plan fills at least 68 % of the rounds it
+// needs and the kernel's full-slab condition holds.
+static int gemm_rs_tt_plan(int M, int N, int K, bool* ok) {
+  const long long t256 = static_cast<long long>((M + 255) / 256) * ((N + 255) / 256);
+  int s = 1;
+  while (t256 * s * 2 <= 256 && K / (s * 2) >= 1024 && s < 4) s *= 2;
+  const long long wg = t256 * s, rounds = (wg + 255) / 256;
+  *ok = K >= 4096 && K % (64 * s) == 0 && wg * 100 >= rounds * 256 * 68;
+  return s;
+}
+
 int ecospa_gemm_splits(int M, int N, int K) {
+  bool rs;
+  const int s_rs = gemm_rs_tt_plan(M, N, K, &rs);
+  if (rs) return s_rs;
   const long long tiles = static_cast<long long>((M + 127) / 128) * ((N + 127) / 128);
   int s = 1;
   // Two 128x128 workgroups fit a compute unit, so 512 of them run at once: split K while all splits still fit

@@ -74,7 +74,7 @@ struct RsOperand {
   }
 };
 
-template <bool TB>
+template <bool TA, bool TB>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   constexpr int BM = 256, BN = 256, BK = 64, WGN = 2;
@@ -97,10 +97,29 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   const int k_end = min(d.K, k_begin + k_chunk);
   const int nk = (k_end - k_begin) / BK;               // full slabs only (checked on the host)
 
-  RsOperand<BM, false> oa;
+  RsOperand<BM, TA> oa;
   RsOperand<BN, TB> ob;
   oa.init(static_cast<const bf16_t*>(d.A), d.lda, m0, d.M, k_begin);
   ob.init(static_cast<const bf16_t*>(d.B), d.ldb, n0, d.N, k_begin);
+
+  // Column sums of a K-slow A (dY^T X: the bias gradient is the column sum of dY): the first tile column adds up
+  // the pieces it moves anyway.  A thread's pieces all cover the same 8 columns, m0 + (lane % 32) * 8 ...
+  constexpr bool CS = TA && TB;
+  const bool do_cs = CS && d.colsum && n0 == 0;
+  float cs_acc[CS ? 8 : 1];
+  if constexpr (CS) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) cs_acc[j] = 0.f;
+  }
+  auto cs_add = [&](const u32x4& v) {
+    if constexpr (CS) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        cs_acc[2 * q] += __uint_as_float(v[q] << 16);
+        cs_acc[2 * q + 1] += __uint_as_float(v[q] & 0xffff0000u);
+      }
+    }
+  };
 
   floatx16 acc[FM][FN];
 #pragma unroll
@@ -122,12 +141,16 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) oa.store(lds, i, ra[0][i]);
+  if (do_cs) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) cs_add(ra[0][i]);
+  }
 #pragma unroll
   for (int i = 0; i < 8; ++i) ob.store(lds + BM * BK, i, rb[0][i]);
   __syncthreads();
   bf16x8_t fa[2][FM], fb[2][FN];
 #pragma unroll
-  for (int i = 0; i < FM; ++i) fa[0][i] = read_frag<BM, BK, false>(lds, wm * WTM + i * 32, 0);
+  for (int i = 0; i < FM; ++i) fa[0][i] = read_frag<BM, BK, TA>(lds, wm * WTM + i * 32, 0);
 #pragma unroll
   for (int j = 0; j < FN; ++j) fb[0][j] = read_frag<BN, BK, TB>(lds + BM * BK, wn * WTN + j * 32, 0);
 
@@ -141,6 +164,7 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
     bf16_t* bs_nxt = as_nxt + BM * BK;
     const bool adv = t + 3 < nk;                       // the slab after the one loaded now exists
     const long long adv_a = adv ? oa.step : 0, adv_b = adv ? ob.step : 0;
+    const bool cs_now = do_cs && t + 1 < nk;           // the slab written to LDS here is a real one, not the repeat past the end
     rs_static_for<0, KS>([&](auto s_) {
       constexpr int s = decltype(s_)::value;
       constexpr int cur = s & 1, nxt = cur ^ 1;
@@ -162,13 +186,14 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
         constexpr int i = m / FN, j = m % FN;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (m < FM) fa[nxt][m] = read_frag<BM, BK, false>(fa_src, wm * WTM + m * 32, sn);
+        if constexpr (m < FM) fa[nxt][m] = read_frag<BM, BK, TA>(fa_src, wm * WTM + m * 32, sn);
         else if constexpr (m < FM + FN) fb[nxt][m - FM] = read_frag<BN, BK, TB>(fb_src, wn * WTN + (m - FM) * 32, sn);
         if constexpr (s == 0) {
           if constexpr (m < 8) ra[P][m] = oa.load(m, adv_a);
           else rb[P][m - 8] = ob.load(m - 8, adv_b);
         } else if constexpr (s == 1 && (m & 1)) {
           oa.store(as_nxt, m >> 1, ra[Q][m >> 1]);
+          if (cs_now) cs_add(ra[Q][m >> 1]);
         } else if constexpr (s == 2 && (m & 1)) {
           ob.store(bs_nxt, m >> 1, rb[Q][m >> 1]);
         }
@@ -183,6 +208,26 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   }
   if (t < nk) slab(std::integral_constant<int, 0>{}, t);
   __syncthreads();   // operand buffers are idle from here on
+
+  if constexpr (CS) {
+    if (do_cs) {     // the same for the whole workgroup
+      // eight partial sums per column (two slab-row halves in each of the four wavefronts), added in a fixed order
+      float* red = reinterpret_cast<float*>(lds);
+      const int part_id = wave * 2 + (lane >> 5), c = lane & 31;
+      const bool own = m0 + c * 8 + 8 <= d.M;      // beyond the ragged edge the loads were clamped onto another thread's columns
+#pragma unroll
+      for (int j = 0; j < 8; ++j) red[part_id * BM + c * 8 + j] = own ? cs_acc[j] : 0.f;
+      __syncthreads();
+      const int r = threadIdx.x;
+      if (m0 + r < d.M) {
+        float sum = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) sum += red[q * BM + r];
+        d.colsum[static_cast<long long>(zsplit) * d.M + m0 + r] = sum;
+      }
+      __syncthreads();
+    }
+  }
 
   // Epilogue through LDS: each wavefront parks 32 rows x 128 columns of fp32 at a time in its own
   // slice of the operand buffers, then every lane handles 8 consecutive columns of a row (16-byte
@@ -228,12 +273,13 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
 }
 
 // instantiated explicitly (see gemm_pipe.hip)
-template __global__ void gemm_bf16_rs_kernel<false>(const GemmDesc, int, int);
-template __global__ void gemm_bf16_rs_kernel<true>(const GemmDesc, int, int);
+template __global__ void gemm_bf16_rs_kernel<false, false>(const GemmDesc, int, int);
+template __global__ void gemm_bf16_rs_kernel<false, true>(const GemmDesc, int, int);
+template __global__ void gemm_bf16_rs_kernel<true, true>(const GemmDesc, int, int);
 
 // ---------------------------------------------------------------------------------------------
 bool gemm_rs_ok(const GemmDesc& d, int k_chunk) {
-  if (d.trans_a) return false;                          // A is K-contiguous in every use of this kernel
+  if (d.trans_a && !d.trans_b) return false;            // combination not used by the layers
   if (d.K % 64 || k_chunk % 64) return false;           // full slabs only
   return d.M >= 8 && d.N >= 8;
 }
@@ -243,9 +289,9 @@ hipError_t gemm_rs_launch(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
   const int splits = d.splits > 1 ? d.splits : 1;
   const dim3 grid(tm * tn * splits), block(256);
   const int lds_bytes = 2 * (256 + 256) * 64 * static_cast<int>(sizeof(bf16_t));   // also covers the epilogue staging
-#define RS_LAUNCH(TB)                                                                                          \
+#define RS_LAUNCH(TA, TB)                                                                                      \
   do {                                                                                                         \
-    auto kern = gemm_bf16_rs_kernel<TB>;                                                                       \
+    auto kern = gemm_bf16_rs_kernel<TA, TB>;                                                                   \
     static bool attr_set = false;                                                                              \
     if (!attr_set) {                                                                                           \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
@@ -255,8 +301,9 @@ hipError_t gemm_rs_launch(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
     }                                                                                                          \
     hipLaunchKernelGGL(kern, grid, block, lds_bytes, ctx->stream, d, tn, k_chunk);                             \
   } while (0)
-  if (d.trans_b) RS_LAUNCH(true);
-  else RS_LAUNCH(false);
+  if (d.trans_a) RS_LAUNCH(true, true);
+  else if (d.trans_b) RS_LAUNCH(false, true);
+  else RS_LAUNCH(false, false);
 #undef RS_LAUNCH
   return hipGetLastError();
 }

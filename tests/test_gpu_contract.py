@@ -92,14 +92,17 @@ def test_contract_bf16_pipelined_split_k(ctx, cfg):
     assert torch.equal(got, again)
 
 
-@pytest.mark.parametrize("tb", [False, True])
+@pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, True)])
 @pytest.mark.parametrize("M,N,K", [(520, 264, 192), (256, 512, 64), (304, 136, 512), (1000, 520, 128)])
-def test_contract_bf16_register_staged_prefetch(ctx, M, N, K, tb):
+def test_contract_bf16_register_staged_prefetch(ctx, M, N, K, ta, tb):
     """The two-slab register-prefetch kernel (tile = 20): ragged M and N, one slab, two, three (odd count:
-    the unrolled slab pair plus a tail) and many, B K-contiguous or K-slow."""
-    a, b, bias, want = _operands(47, M, N, K, False, tb, "bf16")
-    got = ctx.ecospa_contract(dev(a, "bf16"), False, dev(b, "bf16"), tb, dev(bias, "bf16"), tile=20, splits=1)
+    the unrolled slab pair plus a tail) and many; x W^T, dY W and dY^T X operand forms."""
+    a, b, bias, want = _operands(47, M, N, K, ta, tb, "bf16")
+    got = ctx.ecospa_contract(dev(a, "bf16"), ta, dev(b, "bf16"), tb, dev(bias, "bf16"), tile=20, splits=1)
     assert_close(got, want, "bf16", "register-staged prefetch")
+    if ta:      # split along K: fp32 partial sums added in a fixed order
+        got = ctx.ecospa_contract(dev(a, "bf16"), ta, dev(b, "bf16"), tb, dev(bias, "bf16"), tile=20, splits=2 if K >= 128 else 1)
+        assert_close(got, want, "bf16", "register-staged prefetch, split")
 
 
 def test_contract_bf16_register_staged_prefetch_split_k(ctx):

@@ -77,6 +77,15 @@ def test_ffn_small_ragged(ctx, act, dtype):
     run_ffn_case(ctx, 21, 3, 111, 136, 301, 149, act, dtype, wscale=8.0)
 
 
+@pytest.mark.parametrize("act,bias,transposed", [("gelu", True, False), ("swiglu", False, True)])
+def test_ffn_long_token_axis_wide_weight_gradients(ctx, act, bias, transposed):
+    """4096 tokens, 3072 kept units of 3200, d = 1024: weight gradients with enough 256x256 tiles that their
+    contraction over the tokens runs on the register-prefetch kernel (split two or four ways), where the bias
+    gradients are the column sums that kernel adds up on the way."""
+    errs = run_ffn_case(ctx, 29, 4, 1024, 1024, 3200, 3072, act, "bf16", bias=bias, wscale=4.0, transposed=transposed)
+    assert max(errs.values()) <= 2e-2
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_ffn_keep_all_is_dense(ctx, dtype):
     run_ffn_case(ctx, 22, 2, 64, 64, 128, 128, "gelu", dtype, wscale=8.0)
