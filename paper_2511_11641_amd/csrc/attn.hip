@@ -802,6 +802,12 @@ static GemmDesc mk_gemm(int dtype, int M, int N, int K, const void* A, long long
   return g;
 }
 
+// a contraction whose rows are the tokens: K is split when there are too few of them to fill the chip
+static int token_gemm(ecospa_ctx* ctx, const BlockWs& w, GemmDesc g) {
+  block_token_split(g, w);
+  return ecospa_gemm(ctx, g);
+}
+
 int attn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, const void* x, void* y,
                  const ecospa_saved* saved) {
   if (d.dtype != ECOSPA_BF16) return ECOSPA_ERR_DTYPE;   // the attention core is bf16 MFMA only
@@ -812,7 +818,7 @@ int attn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, 
   if (!qkv || !o || !lse) return ECOSPA_ERR_NULL;
   if (!aligned16(qkv) || !aligned16(o)) return ECOSPA_ERR_ALIGN;
   int rc;
-  if ((rc = ecospa_gemm(ctx, mk_gemm(d.dtype, T, nqkv, d.d_model, x, d.d_model, 0, d.w_qkv, d.ld_wqkv, 0, qkv, nqkv, d.b_qkv))))
+  if ((rc = token_gemm(ctx, w, mk_gemm(d.dtype, T, nqkv, d.d_model, x, d.d_model, 0, d.w_qkv, d.ld_wqkv, 0, qkv, nqkv, d.b_qkv))))
     return rc;
   if (d.rope_cos && (rc = launch_rope(ctx, d, qkv, nqkv, 1.f))) return rc;
   AttnArgs a;
@@ -822,7 +828,7 @@ int attn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, 
   a.B = d.B; a.L = d.L; a.h = d.h; a.kp_qk = d.kp_qk; a.kp_vo = d.kp_vo; a.causal = d.causal; a.scale = d.scale;
   a.h_kv = attn_h_kv(d); a.qpk = d.h / a.h_kv;
   if ((rc = dispatch_core(ctx, 0, a))) return rc;
-  return ecospa_gemm(ctx, mk_gemm(d.dtype, T, d.d_model, nvo, o, nvo, 0, d.w_o, d.ld_wo, 0, y, d.d_model, d.b_o));
+  return token_gemm(ctx, w, mk_gemm(d.dtype, T, d.d_model, nvo, o, nvo, 0, d.w_o, d.ld_wo, 0, y, d.d_model, d.b_o));
 }
 
 // dW_o and dW_qkv are split-K contractions whose partials are reduced, together with the two
@@ -838,7 +844,7 @@ static int attn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const
   // contractions: those add them up on the way
   if (gr.dw_o && gr.db_o) go.colsum = w.colsum;
   if (gr.dw_o && (rc = ecospa_gemm(ctx, go))) return rc;
-  if ((rc = ecospa_gemm(ctx, d.w_o_t ? mk_gemm(d.dtype, T, nvo, dm, dy, dm, 0, d.w_o_t, d.ld_wot, 0, w.d_o, nvo, nullptr)   // transposed copy [nvo, d_model]
+  if ((rc = token_gemm(ctx, w, d.w_o_t ? mk_gemm(d.dtype, T, nvo, dm, dy, dm, 0, d.w_o_t, d.ld_wot, 0, w.d_o, nvo, nullptr)   // transposed copy [nvo, d_model]
                                      : mk_gemm(d.dtype, T, nvo, dm, dy, dm, 0, d.w_o, d.ld_wo, 1, w.d_o, nvo, nullptr))))
     return rc;
 
@@ -865,7 +871,7 @@ static int attn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const
   if (gr.dw_qkv && (rc = ecospa_gemm(ctx, gq))) return rc;
 
   // dX = dQKV W_qkv
-  if (dx && (rc = ecospa_gemm(ctx, d.w_qkv_t ? mk_gemm(d.dtype, T, dm, nqkv, w.dqkv, nqkv, 0, d.w_qkv_t, d.ld_wqkvt, 0, dx, dm, nullptr)   // [d_model, nqkv]
+  if (dx && (rc = token_gemm(ctx, w, d.w_qkv_t ? mk_gemm(d.dtype, T, dm, nqkv, w.dqkv, nqkv, 0, d.w_qkv_t, d.ld_wqkvt, 0, dx, dm, nullptr)   // [d_model, nqkv]
                                              : mk_gemm(d.dtype, T, dm, nqkv, w.dqkv, nqkv, 0, d.w_qkv, d.ld_wqkv, 1, dx, dm, nullptr))))
     return rc;
   AuxBatch aux;

@@ -20,8 +20,19 @@ struct BlockWs {           // pieces carved from the caller's workspace
   float* partial2;         // ... and of the second (both are reduced by the batched tail launch)
   float* colsum;           // [splits][M] operand column sums of the first weight-gradient contraction (bias gradient)
   float* colsum2;          // ... and of the second
+  float* partial_x;        // split-K partials of a forward or input-gradient contraction (few tokens only), one at a time
   size_t total;
 };
+
+// K split of a contraction over few tokens (x W^T, dY W): partials from the workspace, reduced right after the launch.
+static inline void block_token_split(GemmDesc& g, const BlockWs& w) {
+  const int s = g.dtype == ECOSPA_BF16 ? ecospa_gemm_token_splits(g.M, g.N, g.K) : 1;
+  if (s > 1 && w.partial_x) { g.splits = s; g.partial = w.partial_x; }
+}
+static inline size_t block_token_split_bytes(int M, int N, int K) {
+  const int s = ecospa_gemm_token_splits(M, N, K);
+  return s > 1 ? static_cast<size_t>(s) * M * N * 4 : 0;
+}
 
 // Lay out the workspace for a validated descriptor; base may be NULL to only measure.
 void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w);

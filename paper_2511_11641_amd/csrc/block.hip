@@ -43,7 +43,8 @@ void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
   memset(&w, 0, sizeof(w));
   WsCarver c(base ? base : reinterpret_cast<void*>(256), ~static_cast<size_t>(0) >> 1);
   const size_t T = static_cast<size_t>(d.B) * d.L, es = dtype_size(d.dtype), dm = d.d_model;
-  size_t part = 0, part2 = 0, cs = 0, cs2 = 0;
+  size_t part = 0, part2 = 0, cs = 0, cs2 = 0, px = 0;
+  const int Ti = static_cast<int>(T);
   auto splitk_bytes = [&](int M, int N, int K) {
     const int s = ecospa_gemm_splits(M, N, K);
     return s > 1 ? static_cast<size_t>(s) * M * N * 4 : static_cast<size_t>(0);
@@ -58,6 +59,8 @@ void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
     part2 = splitk_bytes(static_cast<int>(nh), d.d_model, static_cast<int>(T));
     cs = colsum_bytes(d.d_model, d.kp_ff, static_cast<int>(T));
     cs2 = colsum_bytes(static_cast<int>(nh), d.d_model, static_cast<int>(T));
+    px = max_sz(max_sz(block_token_split_bytes(Ti, static_cast<int>(nh), d.d_model), block_token_split_bytes(Ti, d.d_model, d.kp_ff)),
+                max_sz(block_token_split_bytes(Ti, d.kp_ff, d.d_model), block_token_split_bytes(Ti, d.d_model, static_cast<int>(nh))));
   } else {
     const size_t nqkv = attn_nqkv(d), nvo = static_cast<size_t>(d.h) * d.kp_vo;
     w.dqkv = c.take(T * nqkv * es);
@@ -70,7 +73,10 @@ void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
     part2 = splitk_bytes(static_cast<int>(nqkv), d.d_model, static_cast<int>(T));
     cs = colsum_bytes(d.d_model, static_cast<int>(nvo), static_cast<int>(T));
     cs2 = colsum_bytes(static_cast<int>(nqkv), d.d_model, static_cast<int>(T));
+    px = max_sz(max_sz(block_token_split_bytes(Ti, static_cast<int>(nqkv), d.d_model), block_token_split_bytes(Ti, d.d_model, static_cast<int>(nvo))),
+                max_sz(block_token_split_bytes(Ti, static_cast<int>(nvo), d.d_model), block_token_split_bytes(Ti, d.d_model, static_cast<int>(nqkv))));
   }
+  w.partial_x = px ? static_cast<float*>(c.take(px)) : nullptr;
   w.partial = static_cast<float*>(c.take(part));
   w.partial2 = static_cast<float*>(c.take(part2));
   w.colsum = static_cast<float*>(c.take(cs));
@@ -120,6 +126,7 @@ static int ffn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockW
   int rc;
   GemmDesc g = gemm_desc(d.dtype, T, nh, d.d_model, x, d.d_model, 0, d.w_1, d.ld_w1, 0);
   g.epi.c = hpre; g.epi.ldc = nh; g.epi.bias = d.b_1;
+  block_token_split(g, w);
   if (is_gated(d)) {
     g.epi.kind = EPI_STORE;
     if ((rc = ecospa_gemm(ctx, g))) return rc;
@@ -141,6 +148,7 @@ static int ffn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockW
   }
   GemmDesc g2 = gemm_desc(d.dtype, T, d.d_model, kp, act, kp, 0, d.w_2, d.ld_w2, 0);
   g2.epi.kind = EPI_STORE; g2.epi.c = y; g2.epi.ldc = d.d_model; g2.epi.bias = d.b_2;
+  block_token_split(g2, w);
   return ecospa_gemm(ctx, g2);
 }
 
@@ -156,6 +164,7 @@ static int ffn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const 
                          : gemm_desc(d.dtype, T, kp, dm, dy, dm, 0, d.w_2, d.ld_w2, 1);
     g.epi.c = w.dh; g.epi.ldc = nh; g.epi.h = sv.hpre; g.epi.ldh = nh; g.epi.act = d.act; g.epi.kp = kp;
     g.epi.kind = is_gated(d) ? EPI_DSWIGLU : EPI_DACT;
+    block_token_split(g, w);
     if ((rc = ecospa_gemm(ctx, g))) return rc;
   }
   // dW_2 = dY^T A,  dW_1 = dH^T X
@@ -178,6 +187,7 @@ static int ffn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const 
     GemmDesc g = d.w_1_t ? gemm_desc(d.dtype, T, dm, nh, w.dh, nh, 0, d.w_1_t, d.ld_w1t, 0)   // transposed copy [d_model, nh]
                          : gemm_desc(d.dtype, T, dm, nh, w.dh, nh, 0, d.w_1, d.ld_w1, 1);
     g.epi.kind = EPI_STORE; g.epi.c = dx; g.epi.ldc = dm;
+    block_token_split(g, w);
     if ((rc = ecospa_gemm(ctx, g))) return rc;
   }
   AuxBatch aux;

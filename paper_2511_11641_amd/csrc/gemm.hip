@@ -534,6 +534,13 @@ int ecospa_gemm_splits(int M, int N, int K) {
   return s;
 }
 
+int ecospa_gemm_token_splits(int M, int N, int K) {
+  const long long tiles = static_cast<long long>((M + 127) / 128) * ((N + 127) / 128);
+  int s = 1;
+  while (tiles * s * 2 <= 256 && K / (s * 2) >= 256 && s < 8) s *= 2;
+  return s;
+}
+
 int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
   if (d.M < 1 || d.N < 1 || d.K < 1) return ECOSPA_ERR_SHAPE;
   if (!d.A || !d.B || !d.epi.c) return ECOSPA_ERR_NULL;

@@ -86,6 +86,14 @@ def test_ffn_long_token_axis_wide_weight_gradients(ctx, act, bias, transposed):
     assert max(errs.values()) <= 2e-2
 
 
+@pytest.mark.parametrize("act,transposed", [("gelu", False), ("gelu", True), ("swiglu", True)])
+def test_ffn_few_tokens_split_contractions(ctx, act, transposed):
+    """256 tokens at d = 1024 (inference at batch 1 and the like): the forward and input-gradient contractions have
+    too few output tiles for the chip and run split along K, partial sums added in a fixed order before the epilogue
+    (bias, activation and its stored input, activation derivative)."""
+    run_ffn_case(ctx, 30, 1, 256, 1024, 2048, 1024, act, "bf16", wscale=4.0, transposed=transposed)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_ffn_keep_all_is_dense(ctx, dtype):
     run_ffn_case(ctx, 22, 2, 64, 64, 128, 128, "gelu", dtype, wscale=8.0)
