@@ -2,6 +2,7 @@
 // the argument validation, the workspace layout, the FFN block (Eq. 3; gated form of the footnote
 // to Eq. 8) and the dispatch of the C-ABI entry points; the attention block lives in attn.hip.
 #include "block.h"
+#include "gemm_epi.h"
 
 static bool is_gated(const ecospa_block_desc& d) { return d.act == ECOSPA_ACT_SWIGLU; }
 
@@ -106,6 +107,22 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const T* __restrict__ hpre,
   store_f32<T>(act + m * lda + n, g * act_sigmoid(g) * u);
 }
 
+// bf16, eight units per thread with 16-byte accesses (kp and both leading dimensions are multiples of 8)
+__global__ __launch_bounds__(256) void swiglu_vec8_kernel(const bf16_t* __restrict__ hpre, long long ldh,
+                                                          bf16_t* __restrict__ act, long long lda, long long rows, int kp) {
+  const int kv = kp / 8;
+  const long long e = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
+  if (e >= rows * kv) return;
+  const long long m = e / kv;
+  const int n = static_cast<int>(e % kv) * 8;
+  float g[8], u[8];
+  unpack8(*reinterpret_cast<const uint4*>(hpre + m * ldh + n), g);
+  unpack8(*reinterpret_cast<const uint4*>(hpre + m * ldh + kp + n), u);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) g[i] = g[i] * act_sigmoid(g[i]) * u[i];
+  *reinterpret_cast<uint4*>(act + m * lda + n) = pack8(g);
+}
+
 static GemmDesc gemm_desc(int dtype, int M, int N, int K, const void* A, long long lda, int ta, const void* B,
                           long long ldb, int tb) {
   GemmDesc g;
@@ -132,7 +149,11 @@ static int ffn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockW
     if ((rc = ecospa_gemm(ctx, g))) return rc;
     const long long tot = static_cast<long long>(T) * kp;
     const unsigned grid = static_cast<unsigned>((tot + 255) / 256);
-    if (d.dtype == ECOSPA_BF16)
+    if (d.dtype == ECOSPA_BF16 && kp % 8 == 0 && aligned16(hpre) && aligned16(act))
+      hipLaunchKernelGGL(swiglu_vec8_kernel, dim3(static_cast<unsigned>((tot / 8 + 255) / 256)), dim3(256), 0, ctx->stream,
+                         static_cast<const bf16_t*>(hpre), static_cast<long long>(nh), static_cast<bf16_t*>(act),
+                         static_cast<long long>(kp), static_cast<long long>(T), kp);
+    else if (d.dtype == ECOSPA_BF16)
       hipLaunchKernelGGL((swiglu_kernel<bf16_t>), dim3(grid), dim3(256), 0, ctx->stream, static_cast<const bf16_t*>(hpre),
                          static_cast<long long>(nh), static_cast<bf16_t*>(act), static_cast<long long>(kp),
                          static_cast<long long>(T), kp);
