@@ -318,6 +318,12 @@ def stack_training(ctx, name, n_layers, vocab, Bsz, L, keeps, steps, rescore_eve
         ms_bwd = timed(torch, lambda: (st.forward(ids), st.backward(ids, tgt)), steps, 1) - ms_fwd
         ms_upd = timed(torch, st.update, steps, 1)
         ms_prune = timed(torch, st.prune, max(2, steps // 2), 1)
+        # the contraction kernels inside two whole steps: per-launch events on the library's stream
+        ctx.ecospa_profile_gemm(True)
+        st.train_step(ids, tgt)
+        st.train_step(ids, tgt)
+        n_launch, gemm_ms, gemm_flop = ctx.ecospa_profile_gemm_read()
+        ctx.ecospa_profile_gemm(False)
         a, f = st.layers[0].attn["w"], st.layers[0].ffn["w"]
         fl = _stack_flops(st, a.kp_qk, a.kp_vo, f.kp, 3)
         dense_ms = ms_step if (num, den) == (1, 1) else dense_ms
@@ -325,6 +331,9 @@ def stack_training(ctx, name, n_layers, vocab, Bsz, L, keeps, steps, rescore_eve
         rows.append({"keep": f"{num}/{den}", "ms_step": ms_step, "ms_rescore_step": ms_step + ms_prune,
                      "tokens_per_s": rescore_every * T / (amort * 1e-3), "model_tflops": fl / (ms_step * 1e-3) / 1e12,
                      "parts_ms": {"fwd": ms_fwd, "bwd": ms_bwd, "adamw_and_transposes": ms_upd, "rescore": ms_prune},
+                     "contractions": {"launches_per_step": n_launch // 2, "ms_per_step": gemm_ms / 2,
+                                      "tflops": gemm_flop / (gemm_ms * 1e-3) / 1e12,
+                                      "frac_of_mfma_peak": gemm_flop / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
                      "trained_params_M": st.n_params / 1e6})
         del st
         torch.cuda.empty_cache()
