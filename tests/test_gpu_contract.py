@@ -4,9 +4,10 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import ecospa_oracle as O
 from paper_2511_11641_amd import binding as B
 from paper_2511_11641_amd import synth
-from util import assert_close, dev
+from util import assert_close, dev, host
 
 pytestmark = pytest.mark.gpu
 
@@ -62,6 +63,27 @@ def test_contract_model_shapes_auto_tile(ctx):
         a, b, bias, want = _operands(44, M, N, K, ta, tb, "bf16")
         got = ctx.ecospa_contract(dev(a, "bf16"), ta, dev(b, "bf16"), tb, dev(bias, "bf16"))
         assert_close(got, want, "bf16", f"{M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("M,N,K,ta,tb", [(5504, 2048, 8192, True, True),      # gate|up weight gradient of the LLaMA-1B-shaped FFN: register-prefetch kernel
+                                          (2048, 2752, 8192, True, True),      # W_down gradient: the same kernel, K split in two
+                                          (8192, 1280, 1024, False, False),    # FFN kept at 3/10: 256x192 tiles
+                                          (8192, 2048, 2752, False, False)])   # contraction over 2752 kept units (43 whole slabs)
+def test_contract_stack_shapes_sampled(ctx, M, N, K, ta, tb):
+    """Full-size contractions of the multi-layer workloads through the library's own choice of kernel, tile and
+    split, checked on a sampled 96 x 96 block of outputs computed in fp64 from the same bf16 operands."""
+    a = synth.round_to(synth.normal(49, 310, (K, M) if ta else (M, K)), "bf16")
+    b = synth.round_to(synth.normal(49, 311, (K, N) if tb else (N, K)), "bf16")
+    got = ctx.ecospa_contract(dev(a, "bf16"), ta, dev(b, "bf16"), tb)
+    rng = np.random.default_rng(M + N)
+    ms = np.sort(np.concatenate([rng.choice(M, 92, replace=False), [0, M - 1, M // 256 * 256 - 1, min(M - 1, M // 256 * 256)]]))
+    ns = np.sort(np.concatenate([rng.choice(N, 92, replace=False), [0, N - 1, N // 256 * 256 - 1, min(N - 1, N // 256 * 256)]]))
+    am = (a[:, ms].T if ta else a[ms]).astype(np.float64)
+    bm = (b[:, ns].T if tb else b[ns]).astype(np.float64)
+    want = am @ bm.T
+    block = host(got[torch.from_numpy(ms).cuda()][:, torch.from_numpy(ns).cuda()])
+    assert O.rel_fro(block, want) <= 2e-2
+    assert np.abs(block - want).max() <= 2e-2 * np.abs(want).max() + 1e-6
 
 
 def test_contract_alignment_errors(ctx):
