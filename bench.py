@@ -378,27 +378,35 @@ def cpu_baseline(cfg, seed, keep_num, keep_den, sample_B):
     except Exception:
         cores = os.cpu_count() or 1
     L, d, h, dh, dff = (cfg[k] for k in ("L", "d", "h", "d_h", "d_ff"))
-    a = synth.attn_layer(seed, sample_B, L, d, h, dh, dtype=cfg["dtype"], bias=cfg["bias"])
-    f = synth.ffn_layer(seed + 1000, 1, d, dff, gated=cfg["gated"], dtype=cfg["dtype"], bias=cfg["bias"])
+    gated, rope, bias = cfg["gated"], cfg["rope"], cfg["bias"]
+    a = synth.attn_layer(seed, sample_B, L, d, h, dh, dtype=cfg["dtype"], bias=bias)
+    f = synth.ffn_layer(seed + 1000, 1, d, dff, gated=gated, dtype=cfg["dtype"], bias=bias)
     dy = a["dy"]
+    unit = 2 if rope else 1
+    act = O.ACT_SWIGLU if gated else O.ACT_GELU_ERF
     t0 = time.perf_counter()
-    vq = O.coupled_score(O.PAIR_QK, a["wq"], a["wk"], h, dh)
+    vq = O.coupled_score(O.PAIR_QK, a["wq"], a["wk"], h, dh, unit)
     vv = O.coupled_score(O.PAIR_VO, a["wv"], a["wo"], h, dh)
-    vf = O.coupled_score(O.PAIR_FFN, f["w1"], f["w2"], 1, dff)
-    iq = O.select_topk(vq.astype(np.float32), dh * keep_num // keep_den)
+    vf = O.coupled_score(O.PAIR_FFN_GATED if gated else O.PAIR_FFN, f["w1"], f["w2"], 1, dff, w1b=f.get("w1b"))
+    iq = O.select_topk(vq.astype(np.float32), (dh // unit) * keep_num // keep_den)
     iv = O.select_topk(vv.astype(np.float32), dh * keep_num // keep_den)
     iff = O.select_topk(vf.astype(np.float32), dff * keep_num // keep_den)
-    wq = O.heads_rows(O.compact(a["wq"], iq, 0, dh), h)
-    wk = O.heads_rows(O.compact(a["wk"], iq, 0, dh), h)
+    wq = O.heads_rows(O.compact(a["wq"], iq, 0, dh, unit), h)
+    wk = O.heads_rows(O.compact(a["wk"], iq, 0, dh, unit), h)
     wv = O.heads_rows(O.compact(a["wv"], iv, 0, dh), h)
     wo = O.heads_cols(O.compact(a["wo"], iv, 1, dh), h)
-    kw = dict(bq=O.compact(a["bq"], iq, 0, dh).reshape(h, -1), bk=O.compact(a["bk"], iq, 0, dh).reshape(h, -1),
-              bv=O.compact(a["bv"], iv, 0, dh).reshape(h, -1), bo=a["bo"])
-    w1, b1, w2 = O.compact(f["w1"], iff, 0, dff), O.compact(f["b1"], iff, 0, dff), O.compact(f["w2"], iff, 1, dff)
-    y1, sv = O.attn_fwd(a["x"], wq, wk, wv, wo, sample_B, L, dh ** -0.5, True, **kw)
-    _, sv2 = O.ffn_fwd(y1, w1, b1, w2, f["b2"], O.ACT_GELU_ERF)
-    g2 = O.ffn_bwd(y1, dy, w1, w2, O.ACT_GELU_ERF, sv2)
-    O.attn_bwd(a["x"], g2["dx"], wq, wk, wv, wo, sample_B, L, dh ** -0.5, sv)
+    kw, b1, b2 = {}, None, None
+    if bias:
+        kw = dict(bq=O.compact(a["bq"], iq, 0, dh, unit).reshape(h, -1), bk=O.compact(a["bk"], iq, 0, dh, unit).reshape(h, -1),
+                  bv=O.compact(a["bv"], iv, 0, dh).reshape(h, -1), bo=a["bo"])
+        b1, b2 = O.compact(f["b1"], iff, 0, dff), f["b2"]
+    angles = O.rope_angles(iq, L, dh) if rope else None
+    w1, w2 = O.compact(f["w1"], iff, 0, dff), O.compact(f["w2"], iff, 1, dff)
+    w1b = O.compact(f["w1b"], iff, 0, dff) if gated else None
+    y1, sv = O.attn_fwd(a["x"], wq, wk, wv, wo, sample_B, L, dh ** -0.5, True, angles=angles, **kw)
+    _, sv2 = O.ffn_fwd(y1, w1, b1, w2, b2, act, w1b=w1b)
+    g2 = O.ffn_bwd(y1, dy, w1, w2, act, sv2, w1b=w1b)
+    O.attn_bwd(a["x"], g2["dx"], wq, wk, wv, wo, sample_B, L, dh ** -0.5, sv, angles=angles)
     dt = time.perf_counter() - t0
     return {"value": sample_B * L / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"{sample_B} of {cfg['B']} batch elements (seq {L}) of the same layer, whole path "
@@ -494,6 +502,22 @@ def main():
     ctx.ecospa_profile_gemm(False)
     gemm_tflops = gemm_flop / (gemm_ms * 1e-3) / 1e12
 
+    # the attention core on its own (it is bound by exponentials and conversions on the vector ALU, not by the
+    # matrix units): forward time minus the time of the contraction launches inside the same forward passes
+    ctx.ecospa_profile_gemm(True)
+    for _ in range(args.steps):
+        sparse.fwd()
+    _, gemm_ms_fwd, _ = ctx.ecospa_profile_gemm_read()
+    ctx.ecospa_profile_gemm(False)
+    core_us = (parts["fwd"] - gemm_ms_fwd / args.steps) * 1e3
+    exps = Bsz * h * L * (L + 1) / 2.0
+    exp_peak = 256 * 4 * 16 / 4 * 2.4e9          # compute units x SIMDs x lanes per clock, transcendentals at quarter rate
+    attention_core = {"fwd_us": core_us, "exponentials": exps, "exp_per_s": exps / (core_us * 1e-6),
+                      "frac_of_transcendental_peak": exps / (core_us * 1e-6) / exp_peak,
+                      "note": "causal softmax exponentials of the forward pass; k_qk = k_vo = 32 gives only 128 matrix flops per "
+                              "exponential, so this kernel is priced against the vector ALU (about 25 other vector operations per "
+                              "exponential: scaling, running maximum, conversions), not against the MFMA peak"}
+
     fl_sparse = model_flops(T, L, d, h, sparse.attn.kp_qk, sparse.attn.kp_vo, sparse.ffn.kp)
     del sparse
     torch.cuda.empty_cache()
@@ -517,6 +541,7 @@ def main():
         "speedup_fwd_bwd_vs_dense": ms_dense_fb / ms_fb,
         "speedup_whole_step_vs_dense_fwd_bwd": ms_dense_fb / ms_step,
         "parts_ms": parts,
+        "attention_core": attention_core,
         "score_gbs": w_bytes / (parts["score"] * 1e-3) / 1e9,
         "compact_gbs": w_bytes / (parts["compact"] * 1e-3) / 1e9,   # kept bytes read + kept bytes written
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_{pipe,mfma,rs}_kernel", "achieved": gemm_tflops,
@@ -534,6 +559,17 @@ def main():
         out.update(stack_workloads(ctx))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, seed, 1, 2, sample_B=8)
+        if not args.no_extras:
+            # the oracle beside the multi-layer workloads: one layer timed, the stack figure is 24 times that
+            # (no embedding, norms, output projection or optimizer) - extrapolated, not measured
+            note = "EXTRAPOLATED: 24 x the oracle's time for one layer at 50 % keep (layers only), not a measured stack run"
+            out["stack_gpt2m_train_sweep"]["cpu_oracle_extrapolated"] = {
+                "tokens_per_s": out["cpu_baseline"]["value"] / 24, "cores": out["cpu_baseline"]["cores"], "note": note}
+            c3 = dict(synth.CONFIGS["c3_llama1b_layer"])
+            cb3 = cpu_baseline(c3, c3["seed"], 1, 2, sample_B=4)
+            out["also"]["cpu_baseline"] = cb3
+            out["stack_llama1b_train"]["cpu_oracle_extrapolated"] = {
+                "tokens_per_s": cb3["value"] / 24, "cores": cb3["cores"], "note": note}
     print(json.dumps(out))
 
 
