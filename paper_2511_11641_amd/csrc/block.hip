@@ -43,7 +43,7 @@ static size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
 void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
   memset(&w, 0, sizeof(w));
   WsCarver c(base ? base : reinterpret_cast<void*>(256), ~static_cast<size_t>(0) >> 1);
-  const size_t T = static_cast<size_t>(d.B) * d.L, es = dtype_size(d.dtype), dm = d.d_model;
+  const size_t T = static_cast<size_t>(d.B) * d.L, es = dtype_size(d.dtype);
   size_t part = 0, part2 = 0, cs = 0, cs2 = 0, px = 0;
   const int Ti = static_cast<int>(T);
   auto splitk_bytes = [&](int M, int N, int K) {

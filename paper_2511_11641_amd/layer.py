@@ -152,14 +152,13 @@ class AttnBlock:
         """Gather the kept dimensions.  With k_qk_group / k_vo_group (int32[h] on the device, the kept counts of the
         cumulative-threshold rule) every head keeps a count of its own: idx_* are then [h, n_units] lists whose first
         k_*_group[g] entries count, and all heads are padded with zeros to the largest count (read back once here)."""
-        c, h, hk, dh, u = self.ctx, self.h, self.h_kv, self.d_h, self.unit
+        c, h, hk, u = self.ctx, self.h, self.h_kv, self.unit
         self.idx_qk, self.idx_vo = idx_qk, idx_vo
         self.k_qk_group, self.k_vo_group = k_qk_group, k_vo_group
         self.k_qk_units = idx_qk.shape[1] if k_qk_group is None else int(k_qk_group.max().item())
         self.k_vo = idx_vo.shape[1] if k_vo_group is None else int(k_vo_group.max().item())
         self.kp_qk = B.round_up(self.k_qk_units * u, 16)
         self.kp_vo = B.round_up(self.k_vo, 16)
-        kpu = self.kp_qk // u
         # compact layout: the h query heads, then the h_kv key heads, then the h_kv value heads; W_o has h heads
         nq, nk, nv, no = h * self.kp_qk, hk * self.kp_qk, hk * self.kp_vo, h * self.kp_vo
         self.nq, self.nk = nq, nk
