@@ -55,7 +55,8 @@ int ecospa_gemm_reduce(ecospa_ctx* ctx, const GemmDesc& d);
 int ecospa_gemm_splits(int M, int N, int K);
 // The same question for the contractions whose M is the token count (x W^T and dY W): with few tokens (inference
 // at batch 1) their output has too few tiles for the chip, and K is split until the 128x128 tiles reach a
-// workgroup per compute unit, keeping at least 256 of K per split; 1 for the training shapes.
+// workgroup per compute unit, keeping at least 1024 of K per split (shorter splits lose more to the partial sums
+// than they gain: measured on the batch-1 forward of the 24-layer stack); 1 for the training shapes.
 int ecospa_gemm_token_splits(int M, int N, int K);
 
 // Software-pipelined kernel for full K slabs (gemm_pipe.hip): configurations 0 .. GEMM_PIPE_CONFIGS-1

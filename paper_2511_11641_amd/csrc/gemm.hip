@@ -463,7 +463,8 @@ static int gemm_pipe_choice(const GemmDesc& d) {
     const long long c192 = (t256x192 + 255) / 256 * 192 * 102, c128 = (t256x128 + 255) / 256 * 128 * 108;
     return c192 < c128 ? 10 : 9;
   }
-  return 4;                       // 128x128
+  return 6;                       // 128x128 with 32-deep slabs in a ring of four: more loads in flight than two 64-deep slabs, which
+                                  // matters when a compute unit holds one such workgroup (measured on the few-token shapes)
 }
 // Long contractions with a K-slow B operand (K of several thousand, at least a tile per compute unit)
 // run fastest on the two-slab register prefetch of gemm_rs.hip.
@@ -537,7 +538,7 @@ int ecospa_gemm_splits(int M, int N, int K) {
 int ecospa_gemm_token_splits(int M, int N, int K) {
   const long long tiles = static_cast<long long>((M + 127) / 128) * ((N + 127) / 128);
   int s = 1;
-  while (tiles * s * 2 <= 256 && K / (s * 2) >= 256 && s < 8) s *= 2;
+  while (tiles * s * 2 <= 256 && K / (s * 2) >= 1024 && s < 8) s *= 2;
   return s;
 }
 

@@ -119,8 +119,8 @@ def test_attn_backward_with_transposed_weight_copies(ctx, k_qk, k_vo, rope):
 
 @pytest.mark.parametrize("rope,transposed", [(False, False), (True, True)])
 def test_attn_few_tokens_split_contractions(ctx, rope, transposed):
-    """2 x 128 tokens at d = 1024: projections, output projection and their input gradients run split along K."""
-    run_attn_case(ctx, 36, 2, 128, 1024, 16, 64, 32, 32, rope=rope, causal=True, transposed=transposed)
+    """2 x 128 tokens at d = 2048: the projections and the gradient of the attention output run split along K."""
+    run_attn_case(ctx, 36, 2, 128, 2048, 16, 64, 32, 32, rope=rope, causal=True, transposed=transposed)
 
 
 def test_attn_keep_all_is_dense(ctx):

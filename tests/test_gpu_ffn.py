@@ -88,10 +88,10 @@ def test_ffn_long_token_axis_wide_weight_gradients(ctx, act, bias, transposed):
 
 @pytest.mark.parametrize("act,transposed", [("gelu", False), ("gelu", True), ("swiglu", True)])
 def test_ffn_few_tokens_split_contractions(ctx, act, transposed):
-    """256 tokens at d = 1024 (inference at batch 1 and the like): the forward and input-gradient contractions have
-    too few output tiles for the chip and run split along K, partial sums added in a fixed order before the epilogue
-    (bias, activation and its stored input, activation derivative)."""
-    run_ffn_case(ctx, 30, 1, 256, 1024, 2048, 1024, act, "bf16", wscale=4.0, transposed=transposed)
+    """256 tokens at d = 2048, 2048 kept units (inference at batch 1 and the like): the forward and input-gradient
+    contractions have too few output tiles for the chip and run split along K (two splits of 1024), partial sums added
+    in a fixed order before the epilogue (bias, activation and its stored input, activation derivative)."""
+    run_ffn_case(ctx, 30, 1, 256, 2048, 4096, 2048, act, "bf16", wscale=4.0, transposed=transposed)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
