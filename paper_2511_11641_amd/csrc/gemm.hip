@@ -443,13 +443,14 @@ static int gemm_pipe_choice(const GemmDesc& d) {
   const long long tm256 = (d.M + 255) / 256, t256 = tm256 * ((d.N + 255) / 256), t256x128 = tm256 * ((d.N + 127) / 128);
   if (t256 >= 192) {
     // 256x256 with 8 wavefronts - unless its tiles fill the last round over the 256 compute units so badly that
-    // narrower tiles finish sooner.  Cost of a choice: rounds of work times the area of a tile (narrower tiles
-    // taken as 2 % and 8 % less efficient per flop); 256x192 serves the widths that are multiples of 192 (the
-    // fused Q|K|V projections of both layers) and K-contiguous operands only.
+    // narrower tiles finish sooner.  Cost of a choice: rounds of work times the area of a tile, the 256x128 tiles
+    // taken as 7 % and the 256x192 tiles (two ring slots only) as 17 % less efficient per flop (fitted to cold-cache
+    // timings of the layer shapes); 256x192 serves the widths that are multiples of 192 (the fused Q|K|V
+    // projections of both layers) and K-contiguous operands only.
     if (!d.trans_b) {
       const long long t256x192 = tm256 * ((d.N + 191) / 192);
-      const long long c256 = (t256 + 255) / 256 * 256 * 100, c192 = (t256x192 + 255) / 256 * 192 * 102,
-                      c128 = (t256x128 + 255) / 256 * 128 * 108;
+      const long long c256 = (t256 + 255) / 256 * 256 * 100, c192 = (t256x192 + 255) / 256 * 192 * 117,
+                      c128 = (t256x128 + 255) / 256 * 128 * 107;
       if (c192 < c256 && c192 <= c128) return 10;
       if (c128 < c256) return 9;
     }
@@ -460,7 +461,7 @@ static int gemm_pipe_choice(const GemmDesc& d) {
     // 256x128 (8 wavefronts, 3-deep ring) - or 256x192 when its tiles fit one round where the narrower ones need
     // two (output widths a little above a multiple of 256: what an FFN keeps at a keep ratio like 3/10)
     const long long t256x192 = tm256 * ((d.N + 191) / 192);
-    const long long c192 = (t256x192 + 255) / 256 * 192 * 102, c128 = (t256x128 + 255) / 256 * 128 * 108;
+    const long long c192 = (t256x192 + 255) / 256 * 192 * 117, c128 = (t256x128 + 255) / 256 * 128 * 107;
     return c192 < c128 ? 10 : 9;
   }
   return 6;                       // 128x128 with 32-deep slabs in a ring of four: more loads in flight than two 64-deep slabs, which
