@@ -69,6 +69,31 @@ def test_compact_validation(lib, ctx):
         assert call(axis=1, ls=8, ld=8) == B.ERR_SHAPE   # axis 1 needs ld >= slots
 
 
+def test_map_item_validation(lib, ctx):
+    """Batched gathers/scatters: every item is validated before anything is launched (the pointers are never touched)."""
+    def item(**kw):
+        a = dict(src=256, dst=512, dtype=B.F32, axis=0, groups=4, n=8, unit=1, k=4, kp=4, scatter=0, other=16, ls=16, ld=16,
+                 idx=768, k_group=None, ld_idx=0, idx_div=0)
+        a.update(kw)
+        return B.MapItem(a["src"], a["dst"], a["dtype"], a["axis"], a["groups"], a["n"], a["unit"], a["k"], a["kp"], a["scatter"],
+                         a["other"], a["ls"], a["ld"], a["idx"], a["k_group"], a["ld_idx"], a["idx_div"])
+
+    def call(*items):
+        arr = (B.MapItem * len(items))(*items)
+        return lib.ecospa_compact_batch(ctx, arr, len(items))
+
+    assert call(item(scatter=3)) == B.ERR_SHAPE              # 0 gather, 1 zero-filling scatter, 2 merging scatter
+    assert call(item(scatter=-1)) == B.ERR_SHAPE
+    assert call(item(), item(dst=None)) == B.ERR_NULL        # a bad item anywhere in the batch stops the whole call
+    assert call(item(k_group=1024, kp=0, ld_idx=8)) == B.ERR_K       # ragged: capacities must be positive
+    assert call(item(k_group=1024, kp=4, ld_idx=0)) == B.ERR_K
+    assert call(item(idx_div=3)) == B.ERR_SHAPE              # heads per shared index list must divide the heads
+    assert call(item(ld_idx=3)) == B.ERR_K                   # index lists closer together than k
+    assert lib.ecospa_compact_batch(ctx, None, 1) == B.ERR_NULL
+    arr = (B.MapItem * 1)(item())
+    assert lib.ecospa_compact_batch(ctx, arr, 0) == B.ERR_SHAPE
+
+
 def test_score_validation(lib, ctx):
     p = B.Pair(B.PAIR_FFN, B.F32, 1, 8, 1, 4, 4, 256, None, 512, 4, 0, 8)
     arr = (B.Pair * 1)(p)
