@@ -86,6 +86,14 @@ def test_ffn_long_token_axis_wide_weight_gradients(ctx, act, bias, transposed):
     assert max(errs.values()) <= 2e-2
 
 
+def test_ffn_wide_units_long_model_dimension(ctx):
+    """4096 tokens, d = 2048, all 4096 units kept: x W_1^T and dY W_2 have a full round of 256x256 tiles with the bias +
+    GELU epilogue (both outputs) and the GELU-derivative epilogue, and the weight gradients run split two ways on the
+    register-prefetch kernel."""
+    errs = run_ffn_case(ctx, 31, 4, 1024, 2048, 4096, 4096, "gelu", "bf16", wscale=3.0, transposed=True)
+    assert max(errs.values()) <= 2e-2
+
+
 @pytest.mark.parametrize("act,transposed", [("gelu", False), ("gelu", True), ("swiglu", True)])
 def test_ffn_few_tokens_split_contractions(ctx, act, transposed):
     """256 tokens at d = 2048, 2048 kept units (inference at batch 1 and the like): the forward and input-gradient
