@@ -86,6 +86,14 @@ def test_ffn_long_token_axis_wide_weight_gradients(ctx, act, bias, transposed):
     assert max(errs.values()) <= 2e-2
 
 
+def test_ffn_weight_gradients_with_a_ragged_tile_row(ctx):
+    """1100 kept units (padded to 1152 = 4.5 tiles of 256) at d = 2304 over 4096 tokens: the weight gradients run split
+    four ways on the register-prefetch kernel with a half-empty last tile row, whose bias-gradient column sums must
+    not count the columns beyond the edge twice."""
+    errs = run_ffn_case(ctx, 32, 4, 1024, 2304, 1500, 1100, "gelu", "bf16", wscale=4.0)
+    assert max(errs.values()) <= 2e-2
+
+
 def test_ffn_wide_units_long_model_dimension(ctx):
     """4096 tokens, d = 2048, all 4096 units kept: x W_1^T and dY W_2 have a full round of 256x256 tiles with the bias +
     GELU epilogue (both outputs) and the GELU-derivative epilogue, and the weight gradients run split two ways on the
