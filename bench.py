@@ -219,6 +219,41 @@ def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps):
             "timing": "device-side events, descriptors prebuilt"}
 
 
+def fp32_pair_workload(ctx, steps):
+    """The fp32 single FFN pair (512 tokens, d = 256, 1024 inner dimensions, half kept): score, select, gather,
+    forward and backward.  0.8 GFLOP on the vector ALU (fp32 has no place on the bf16 matrix path): ten short launches
+    whose contraction loops are bound by load latency, not arithmetic; time only."""
+    import torch
+    from paper_2511_11641_amd import binding as B, synth
+    from paper_2511_11641_amd.layer import FfnBlock
+    cfg = synth.CONFIGS["c1_ffn_f32"]
+    T, d, n = cfg["T"], cfg["d"], cfg["n"]
+    t = synth.ffn_layer(cfg["seed"], T, d, n, dtype="f32")
+    g = {nm: torch.from_numpy(a).cuda() for nm, a in t.items()}
+    blk = FfnBlock(ctx, g["w1"], g["b1"], g["w2"], g["b2"], B.ACT_GELU_ERF)
+    k = synth.keep_count(n, 1, 2)
+    idx = torch.empty((1, k), dtype=torch.int32, device="cuda")
+    pair = [blk.pair()]
+    scores = ctx.ecospa_coupled_score(pair)
+
+    def prune():
+        ctx.ecospa_coupled_score(pair, out=scores)
+        ctx.ecospa_select_topk_batch([ctx.select_item(scores[0], k, idx)])
+        blk.compact(idx)
+
+    prune()
+    blk.alloc(1, T)
+
+    def step():
+        prune()
+        blk.fwd(g["x"])
+        blk.bwd(g["x"], g["dy"])
+
+    ms = timed(torch, step, steps, 3)
+    return {"workload": "c1_ffn_f32", "dtype": "f32", "tokens": T, "keep": f"{k}/{n}", "ms_per_step": ms,
+            "tokens_per_s": T / (ms * 1e-3), "note": "0.8 GFLOP in ten short launches on the vector ALU: latency-bound, reported as a time only"}
+
+
 def second_workload(ctx, name, steps, warmup):
     """The LLaMA-1B-shaped layer (RoPE, SwiGLU, no biases) through the same path: whole step at 50 % keep,
     fwd+bwd alone, and the dense layer (same library at k = n)."""
@@ -554,6 +589,7 @@ def main():
     if not args.no_extras:
         out["prune_24_layers"] = prune_stack(ctx, cfg, 24, 1, 2, 20)
         out["also"] = second_workload(ctx, "c3_llama1b_layer", args.steps, args.warmup)
+        out["fp32_pair"] = fp32_pair_workload(ctx, args.steps)
         out["inference"] = inference_sweep(ctx, name, 20)
         out["torch_dense_fwd_bwd"] = torch_dense_layer(name, 20)
         out.update(stack_workloads(ctx))

@@ -328,8 +328,13 @@ void gemm_bf16_mfma_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void gemm_valu_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
-  __shared__ float As[16][64 + 4];
-  __shared__ float Bs[16][64 + 4];
+  // 64 x 64 tile, 32-deep slabs; the 16 operand elements a thread moves per slab are fetched one slab ahead with
+  // unconditional loads from clamped addresses (all in flight together, none behind a branch) and dropped by a
+  // select where they lie outside the problem: these problems are small, so nothing but the loads' own
+  // parallelism hides their latency.
+  constexpr int BK = 32, NL = 64 * BK / 256;
+  __shared__ float As[BK][64 + 4];
+  __shared__ float Bs[BK][64 + 4];
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const int m0 = (blockIdx.x / tiles_n) * 64, n0 = (blockIdx.x % tiles_n) * 64;
   const int k_begin = blockIdx.z * k_chunk;
@@ -342,30 +347,39 @@ __global__ __launch_bounds__(256) void gemm_valu_kernel(const GemmDesc d, int ti
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
 
-  for (int k0 = k_begin; k0 < k_end; k0 += 16) {
+  float ra[NL], rb[NL];
+  auto fetch = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NL; ++i) {
       const int e = tid + i * 256;
       {
-        const int kk = d.trans_a ? e >> 6 : e & 15, r = d.trans_a ? e & 63 : e >> 4;
+        const int kk = d.trans_a ? e >> 6 : e & (BK - 1), r = d.trans_a ? e & 63 : e / BK;
         const int gm = m0 + r, gk = k0 + kk;
-        float v = 0.f;
-        if (gm < d.M && gk < k_end)
-          v = load_f32<T>(A + (d.trans_a ? static_cast<long long>(gk) * d.lda + gm : static_cast<long long>(gm) * d.lda + gk));
-        As[kk][r] = v;
+        const long long cm = min(gm, d.M - 1), ck = min(gk, k_end - 1);
+        const float v = load_f32<T>(A + (d.trans_a ? ck * d.lda + cm : cm * d.lda + ck));
+        ra[i] = (gm < d.M && gk < k_end) ? v : 0.f;
       }
       {
-        const int kk = d.trans_b ? e >> 6 : e & 15, r = d.trans_b ? e & 63 : e >> 4;
+        const int kk = d.trans_b ? e >> 6 : e & (BK - 1), r = d.trans_b ? e & 63 : e / BK;
         const int gn = n0 + r, gk = k0 + kk;
-        float v = 0.f;
-        if (gn < d.N && gk < k_end)
-          v = load_f32<T>(B + (d.trans_b ? static_cast<long long>(gk) * d.ldb + gn : static_cast<long long>(gn) * d.ldb + gk));
-        Bs[kk][r] = v;
+        const long long cn = min(gn, d.N - 1), ck = min(gk, k_end - 1);
+        const float v = load_f32<T>(B + (d.trans_b ? ck * d.ldb + cn : cn * d.ldb + ck));
+        rb[i] = (gn < d.N && gk < k_end) ? v : 0.f;
       }
     }
-    __syncthreads();
+  };
+  if (k_begin < k_end) fetch(k_begin);
+  for (int k0 = k_begin; k0 < k_end; k0 += BK) {
 #pragma unroll
-    for (int kk = 0; kk < 16; ++kk) {
+    for (int i = 0; i < NL; ++i) {
+      const int e = tid + i * 256;
+      As[d.trans_a ? e >> 6 : e & (BK - 1)][d.trans_a ? e & 63 : e / BK] = ra[i];
+      Bs[d.trans_b ? e >> 6 : e & (BK - 1)][d.trans_b ? e & 63 : e / BK] = rb[i];
+    }
+    __syncthreads();
+    if (k0 + BK < k_end) fetch(k0 + BK);      // the same for the whole workgroup
+#pragma unroll
+    for (int kk = 0; kk < BK; ++kk) {
       float a[4], b[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
@@ -593,7 +607,7 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
   } else if (d.dtype == ECOSPA_F32) {
     const int tm = (d.M + 63) / 64, tn = (d.N + 63) / 64;
     int k_chunk = (d.K + splits - 1) / splits;
-    k_chunk = (k_chunk + 15) / 16 * 16;
+    k_chunk = (k_chunk + 31) / 32 * 32;
     hipLaunchKernelGGL((gemm_valu_kernel<float>), dim3(tm * tn, 1, splits), dim3(256), 0, ctx->stream, d, tn, k_chunk);
     ECOSPA_CHECK_LAUNCH(ctx, "gemm_valu_kernel");
   } else {
