@@ -79,7 +79,9 @@ class Layer:
         self.k_qk_units = (dh // unit) * keep_num // keep_den
         self.k_vo = dh * keep_num // keep_den
         self.k_ff = dff * keep_num // keep_den
-        self.pairs = self.attn.pairs() + [self.ffn.pair()]
+        pairs = self.attn.pairs() + [self.ffn.pair()]
+        self.pairs = (B.Pair * len(pairs))(*pairs)
+        self.scores = self._sel = self._map = self._tr = None     # descriptor arrays are built once: every buffer they name persists
         self.idx = [torch.empty((h, self.k_qk_units), dtype=torch.int32, device="cuda"),
                     torch.empty((h, self.k_vo), dtype=torch.int32, device="cuda"),
                     torch.empty((1, self.k_ff), dtype=torch.int32, device="cuda")]
@@ -89,20 +91,27 @@ class Layer:
 
     # steps 1-3
     def score(self):
-        self.scores = self.ctx.ecospa_coupled_score(self.pairs)
+        self.scores = self.ctx.ecospa_coupled_score(self.pairs, out=self.scores)
 
     def select(self):       # one launch for the three pairs
-        mk = self.ctx.select_item
-        self.ctx.ecospa_select_topk_batch([mk(s, k, out) for s, k, out in
-                                           zip(self.scores, (self.k_qk_units, self.k_vo, self.k_ff), self.idx)])
+        if self._sel is None:
+            mk = self.ctx.select_item
+            sel = [mk(s, k, out) for s, k, out in zip(self.scores, (self.k_qk_units, self.k_vo, self.k_ff), self.idx)]
+            self._sel = (self.B_.SelectItem * len(sel))(*sel)
+        self.ctx.ecospa_select_topk_batch(self._sel)
 
     def compact(self):      # one launch for every matrix and bias of the layer
-        items = self.attn.compact(self.idx[0], self.idx[1], defer=True) + self.ffn.compact(self.idx[2], defer=True)
-        self.ctx.ecospa_compact_batch(items)
+        if self._map is None:
+            items = self.attn.compact(self.idx[0], self.idx[1], defer=True) + self.ffn.compact(self.idx[2], defer=True)
+            self._map = (self.B_.MapItem * len(items))(*items)
+            tr = self.attn.transpose_items() + self.ffn.transpose_items()
+            self._tr = (self.B_.TransposeItem * len(tr))(*tr) if tr else None
+        elif self.attn.rope:    # the kept rotary blocks may have changed: their cos/sin tables again
+            self.attn._rope_table(self.attn._L, out=(self.attn.cos, self.attn.sin))
+        self.ctx.ecospa_compact_batch(self._map)
         # transposed copies of the compact weights for the input-gradient contractions (one launch)
-        tr = self.attn.transpose_items() + self.ffn.transpose_items()
-        if tr:
-            self.ctx.ecospa_transpose_batch(tr)
+        if self._tr is not None:
+            self.ctx.ecospa_transpose_batch(self._tr)
 
     def prune(self):
         self.score()
