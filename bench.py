@@ -29,10 +29,11 @@ HBM_PEAK_GBS = 8000.0
 GEMM_TRAFFIC = ("c7413d6571d2e57e", 80.6e6)
 
 
-def model_flops(T, L, d, h, k_qk, k_vo, k_ff, causal=True, gated=False):
+def model_flops(T, L, d, h, k_qk, k_vo, k_ff, causal=True, gated=False, h_kv=None):
     """fwd+bwd model flops of one layer (backward = 2x forward, recomputation not counted,
-    causal attention counted at half; a gated FFN has three matrices)."""
-    proj = 2 * T * d * (2 * h * k_qk + h * k_vo) + 2 * T * d * h * k_vo
+    causal attention counted at half; a gated FFN has three matrices; h_kv < h: shared key/value heads)."""
+    h_kv = h if h_kv is None else h_kv
+    proj = 2 * T * d * ((h + h_kv) * k_qk + h_kv * k_vo) + 2 * T * d * h * k_vo
     attn = (2 * T * L * h * (k_qk + k_vo)) * (0.5 if causal else 1.0)
     ffn = (3 if gated else 2) * 2 * T * d * k_ff
     return 3.0 * (proj + attn + ffn)
@@ -72,8 +73,13 @@ class Layer:
         gf = {k: up(v) for k, v in f.items() if k not in ("x", "dy")}
         self.x, self.dy = g["x"], g["dy"]
         act = B.ACT_SWIGLU if cfg["gated"] else B.ACT_GELU_ERF
+        hkv = cfg.get("h_kv", h)          # grouped-query attention (Eq. 5): the first h_kv heads of W_k, W_v serve as the shared ones
+        if hkv != h:
+            for nm in ("wk", "wv", "bk", "bv"):
+                if g.get(nm) is not None:
+                    g[nm] = g[nm][:hkv * dh].contiguous()
         self.attn = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g.get("bq"), g.get("bk"), g.get("bv"),
-                              g.get("bo"), h, dh, rope=cfg["rope"], causal=True, transposed=True)
+                              g.get("bo"), h, dh, rope=cfg["rope"], causal=True, transposed=True, h_kv=hkv)
         self.ffn = FfnBlock(ctx, gf["w1"], gf.get("b1"), gf["w2"], gf.get("b2"), act, gf.get("w1b"), transposed=True)
         unit = 2 if cfg["rope"] else 1
         self.k_qk_units = (dh // unit) * keep_num // keep_den
@@ -82,8 +88,8 @@ class Layer:
         pairs = self.attn.pairs() + [self.ffn.pair()]
         self.pairs = (B.Pair * len(pairs))(*pairs)
         self.scores = self._sel = self._map = self._tr = None     # descriptor arrays are built once: every buffer they name persists
-        self.idx = [torch.empty((h, self.k_qk_units), dtype=torch.int32, device="cuda"),
-                    torch.empty((h, self.k_vo), dtype=torch.int32, device="cuda"),
+        self.idx = [torch.empty((hkv, self.k_qk_units), dtype=torch.int32, device="cuda"),
+                    torch.empty((hkv, self.k_vo), dtype=torch.int32, device="cuda"),
                     torch.empty((1, self.k_ff), dtype=torch.int32, device="cuda")]
         self.prune()
         self.attn.alloc(Bsz, L)
@@ -263,26 +269,29 @@ def fp32_pair_workload(ctx, steps):
             "tokens_per_s": T / (ms * 1e-3), "note": "0.8 GFLOP in ten short launches on the vector ALU: latency-bound, reported as a time only"}
 
 
-def second_workload(ctx, name, steps, warmup):
+def second_workload(ctx, name, steps, warmup, h_kv=None):
     """The LLaMA-1B-shaped layer (RoPE, SwiGLU, no biases) through the same path: whole step at 50 % keep,
-    fwd+bwd alone, and the dense layer (same library at k = n)."""
+    fwd+bwd alone, and the dense layer (same library at k = n).  With h_kv: the same layer with that many shared
+    key/value heads (grouped-query attention, Eq. 5)."""
     import torch
     from paper_2511_11641_amd import synth
     cfg = dict(synth.CONFIGS[name])
+    if h_kv is not None:
+        cfg["h_kv"] = h_kv
     Bsz, L, d, h, dh, dff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
     T = Bsz * L
     sp = Layer(ctx, cfg, cfg["seed"], 1, 2)
     ms_step = timed(torch, sp.step, steps, warmup)
     ms_fb = timed(torch, lambda: (sp.fwd(), sp.bwd()), steps, 2)
-    fl_sp = model_flops(T, L, d, h, sp.attn.kp_qk, sp.attn.kp_vo, sp.ffn.kp, gated=cfg["gated"])
+    fl_sp = model_flops(T, L, d, h, sp.attn.kp_qk, sp.attn.kp_vo, sp.ffn.kp, gated=cfg["gated"], h_kv=h_kv)
     del sp
     torch.cuda.empty_cache()
     de = Layer(ctx, cfg, cfg["seed"], 1, 1)
     ms_de = timed(torch, lambda: (de.fwd(), de.bwd()), steps, warmup)
-    fl_de = model_flops(T, L, d, h, dh, dh, dff, gated=cfg["gated"])
+    fl_de = model_flops(T, L, d, h, dh, dh, dff, gated=cfg["gated"], h_kv=h_kv)
     del de
     torch.cuda.empty_cache()
-    return {"workload": name, "batch": Bsz, "seq_len": L, "ms_per_step": ms_step, "tokens_per_s": T / (ms_step * 1e-3),
+    return {"workload": name if h_kv is None else f"{name}, {h_kv} key/value heads", "batch": Bsz, "seq_len": L, "ms_per_step": ms_step, "tokens_per_s": T / (ms_step * 1e-3),
             "fwd_bwd": {"ms": ms_fb, "tokens_per_s": T / (ms_fb * 1e-3), "model_tflops": fl_sp / (ms_fb * 1e-3) / 1e12},
             "dense_fwd_bwd": {"ms": ms_de, "tokens_per_s": T / (ms_de * 1e-3), "model_tflops": fl_de / (ms_de * 1e-3) / 1e12},
             "speedup_fwd_bwd_vs_dense": ms_de / ms_fb}
@@ -600,6 +609,7 @@ def main():
         out["prune_24_layers"] = prune_stack(ctx, cfg, 24, 1, 2, 20)
         out["also"] = second_workload(ctx, "c3_llama1b_layer", args.steps, args.warmup)
         out["fp32_pair"] = fp32_pair_workload(ctx, args.steps)
+        out["gqa_layer"] = second_workload(ctx, "c3_llama1b_layer", args.steps, args.warmup, h_kv=8)
         out["inference"] = inference_sweep(ctx, name, 20)
         out["torch_dense_fwd_bwd"] = torch_dense_layer(name, 20)
         out.update(stack_workloads(ctx))
