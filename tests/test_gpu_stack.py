@@ -196,8 +196,9 @@ def test_training_state_stays_compact_and_is_written_back(ctx, cfg):
     assert all(np.isfinite(more)) and more[-1] < losses[0]
 
 
-def test_inference_stack_forward_only(ctx):
-    st = DecoderStack(ctx, GPT, n_layers=2, vocab=VOCAB, keep=(3, 10), seed=7, train=False)
+@pytest.mark.parametrize("cfg", [GPT, LLAMA], ids=["gpt2_like", "llama_like"])
+def test_inference_stack_forward_only(ctx, cfg):
+    st = DecoderStack(ctx, cfg, n_layers=2, vocab=VOCAB, keep=(3, 10), seed=7, train=False)
     ids = torch.randint(0, VOCAB, (st.T,), device="cuda")
     logits = st.forward(ids)
     assert logits.shape == (st.T, VOCAB) and bool(torch.isfinite(logits.float()).all())
