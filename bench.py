@@ -125,9 +125,9 @@ class Layer:
         self.compact()
 
     # steps 4-5
-    def fwd(self):
-        y1 = self.attn.fwd(self.x)
-        return self.ffn.fwd(y1)
+    def fwd(self, save=True):
+        y1 = self.attn.fwd(self.x, save)
+        return self.ffn.fwd(y1, save)
 
     def bwd(self):
         d1 = self.ffn.bwd(self.attn.y, self.dy)
@@ -335,7 +335,7 @@ def inference_sweep(ctx, name, steps):
         ms_dense = None
         for num, den in ((1, 1), (3, 4), (1, 2), (3, 10)):
             lay = Layer(ctx, cfg, cfg["seed"], num, den)
-            ms = timed(torch, lay.fwd, steps, 3)
+            ms = timed(torch, lambda: lay.fwd(save=False), steps, 3)
             ms_dense = ms if ms_dense is None else ms_dense
             rows.append({"batch": Bsz, "seq_len": cfg["L"], "keep": f"{num}/{den}", "ms_fwd": ms,
                          "tokens_per_s": T / (ms * 1e-3), "speedup_vs_dense": ms_dense / ms})

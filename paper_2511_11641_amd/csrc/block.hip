@@ -162,6 +162,11 @@ static int ffn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockW
                          static_cast<long long>(nh), static_cast<float*>(act), static_cast<long long>(kp),
                          static_cast<long long>(T), kp);
     ECOSPA_CHECK_LAUNCH(ctx, "swiglu_kernel");
+  } else if (!saved) {
+    // forward only: nothing will ask for the activation's input, so it is not written
+    g.epi.kind = EPI_ACT; g.epi.act = d.act;
+    g.epi.c = act; g.epi.ldc = kp;
+    if ((rc = ecospa_gemm(ctx, g))) return rc;
   } else {
     g.epi.kind = EPI_BIAS_ACT; g.epi.act = d.act;
     g.epi.c2 = act; g.epi.ldc2 = kp;

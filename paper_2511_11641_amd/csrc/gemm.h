@@ -13,6 +13,7 @@ enum {
   EPI_BIAS_ACT = 1,  // h = acc + bias[n]; c[m,n] = h; c2[m,n] = gelu(h)
   EPI_DACT = 2,      // c[m,n] = acc * gelu'(h[m,n])
   EPI_DSWIGLU = 3,   // g = h[m,n], u = h[m,n+kp]; c[m,n] = acc*u*dsilu(g); c[m,n+kp] = acc*silu(g)
+  EPI_ACT = 4,       // c[m,n] = gelu(acc + bias[n]): forward only, the activation's input is not kept
 };
 
 struct GemmEpi {

@@ -22,6 +22,10 @@ __device__ __forceinline__ void epi_apply(const GemmEpi& e, int m, int n, float 
       store_f32<T>(c + off, acc);
       store_f32<T>(static_cast<T*>(e.c2) + static_cast<long long>(m) * e.ldc2 + n, act_gelu(acc, e.act));
     } break;
+    case EPI_ACT: {
+      if (e.bias) acc += load_f32<T>(static_cast<const T*>(e.bias) + n);
+      store_f32<T>(c + off, act_gelu(acc, e.act));
+    } break;
     case EPI_DACT: {
       const float h = load_f32<T>(static_cast<const T*>(e.h) + static_cast<long long>(m) * e.ldh + n);
       store_f32<T>(c + off, acc * act_gelu_grad(h, e.act));
@@ -69,6 +73,16 @@ __device__ __forceinline__ void epi_apply_vec8(const GemmEpi& e, int m, int n, f
       for (int i = 0; i < 8; ++i) a[i] = act_gelu(v[i], e.act);
       *reinterpret_cast<uint4*>(static_cast<bf16_t*>(e.c2) + static_cast<long long>(m) * e.ldc2 + n) = pack8(a);
     }
+  } else if (e.kind == EPI_ACT) {
+    if (e.bias) {
+      float b[8];
+      unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.bias) + n), b);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] += b[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = act_gelu(v[i], e.act);
+    *reinterpret_cast<uint4*>(c) = pack8(v);
   } else if (e.kind == EPI_DACT) {
     float h[8];
     unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.h) + static_cast<long long>(m) * e.ldh + n), h);

@@ -114,8 +114,10 @@ class FfnBlock:
         self._desc = self.desc(Bsz, L)
         return self
 
-    def fwd(self, x):
-        return self.ctx.ecospa_coupled_fwd(self._desc, x, self.y, self.saved)
+    def fwd(self, x, save: bool = True):
+        """save=False: forward only - the library keeps nothing for a backward pass (intermediates live in its
+        workspace, the activation's input is not written at all)."""
+        return self.ctx.ecospa_coupled_fwd(self._desc, x, self.y, self.saved if save else None)
 
     def bwd(self, x, dy):
         self.ctx.ecospa_coupled_bwd(self._desc, x, dy, self.saved, self.dx, self.grads)
@@ -255,8 +257,9 @@ class AttnBlock:
         self.grads = g
         return self
 
-    def fwd(self, x):
-        return self.ctx.ecospa_coupled_fwd(self._desc, x, self.y, self.saved)
+    def fwd(self, x, save: bool = True):
+        """save=False: forward only - Q, K, V, the attention output and the row statistics live in the workspace."""
+        return self.ctx.ecospa_coupled_fwd(self._desc, x, self.y, self.saved if save else None)
 
     def bwd(self, x, dy):
         self.ctx.ecospa_coupled_bwd(self._desc, x, dy, self.saved, self.dx, self.grads)

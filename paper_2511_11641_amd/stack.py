@@ -222,9 +222,9 @@ class DecoderStack:
             x = (x.view(self.Bsz, self.L, self.d) + self.pos.w).view(self.T, self.d)
         for ly in self.layers:
             ly.leaf1, ly.h1 = self._norm_fwd(x, ly.norm[0])
-            x = x + ly.attn["w"].fwd(ly.h1.detach())
+            x = x + ly.attn["w"].fwd(ly.h1.detach(), save=self.train)
             ly.leaf2, ly.h2 = self._norm_fwd(x, ly.norm[1])
-            x = x + ly.ffn["w"].fwd(ly.h2.detach())
+            x = x + ly.ffn["w"].fwd(ly.h2.detach(), save=self.train)
         self.leaf_f, self.hf = self._norm_fwd(x, self.norm_f)
         if not lm_head:
             return self.hf

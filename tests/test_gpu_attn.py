@@ -123,6 +123,25 @@ def test_attn_few_tokens_split_contractions(ctx, rope, transposed):
     run_attn_case(ctx, 36, 2, 128, 2048, 16, 64, 32, 32, rope=rope, causal=True, transposed=transposed)
 
 
+@pytest.mark.parametrize("rope,L,d", [(False, 200, 256), (True, 128, 2048)])
+def test_attn_forward_only_keeps_nothing_and_agrees(ctx, rope, L, d):
+    """Forward without saved tensors (inference): bit for bit the training forward's output."""
+    h, dh = (4, 64) if d == 256 else (16, 64)
+    t = synth.attn_layer(37, 2, L, d, h, dh, dtype="bf16")
+    g = {nm: dev(a, "bf16") for nm, a in t.items()}
+    blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g["bq"], g["bk"], g["bv"], g["bo"], h, dh, rope=rope, causal=True)
+    rng = np.random.default_rng(L)
+    units = dh // (2 if rope else 1)
+    iq = torch.from_numpy(np.stack([np.sort(rng.choice(units, units // 2, replace=False)) for _ in range(h)]).astype(np.int32)).cuda()
+    iv = torch.from_numpy(np.stack([np.sort(rng.choice(dh, 32, replace=False)) for _ in range(h)]).astype(np.int32)).cuda()
+    blk.compact(iq, iv).alloc(2, L)
+    y_train = blk.fwd(g["x"]).clone()
+    blk.qkv.fill_(float("nan"))
+    y_inf = blk.fwd(g["x"], save=False)
+    assert torch.equal(y_inf, y_train)
+    assert bool(torch.isnan(blk.qkv.float()).all())
+
+
 def test_attn_keep_all_is_dense(ctx):
     run_attn_case(ctx, 36, 2, 256, 256, 4, 64, 64, 64, rope=True, causal=True, wscale=4.0)
 

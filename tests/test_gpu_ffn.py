@@ -86,6 +86,26 @@ def test_ffn_long_token_axis_wide_weight_gradients(ctx, act, bias, transposed):
     assert max(errs.values()) <= 2e-2
 
 
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+@pytest.mark.parametrize("dtype,T,d,n,k", [("bf16", 333, 136, 301, 149), ("bf16", 256, 2048, 4096, 2048), ("f32", 130, 72, 200, 99)])
+def test_ffn_forward_only_keeps_nothing_and_agrees(ctx, act, dtype, T, d, n, k):
+    """Forward without saved tensors (inference): the same output, bit for bit, as the training forward - the
+    activation is computed from the same accumulators, only its input is not written."""
+    gated = act == "swiglu"
+    t = synth.ffn_layer(33, T, d, n, gated=gated, dtype=dtype)
+    rng = np.random.default_rng(T)
+    idx = torch.from_numpy(np.sort(rng.choice(n, k, replace=False)).astype(np.int32)[None, :]).cuda()
+    g = {nm: dev(a, dtype) for nm, a in t.items()}
+    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), ACT[act][0], g.get("w1b"))
+    blk.compact(idx).alloc(1, T)
+    y_train = blk.fwd(g["x"]).clone()
+    blk.hpre.fill_(float("nan"))
+    blk.act_buf.fill_(float("nan"))
+    y_inf = blk.fwd(g["x"], save=False)
+    assert torch.equal(y_inf, y_train)
+    assert bool(torch.isnan(blk.hpre.float()).all()) and bool(torch.isnan(blk.act_buf.float()).all())   # untouched
+
+
 def test_ffn_weight_gradients_with_a_ragged_tile_row(ctx):
     """1100 kept units (padded to 1152 = 4.5 tiles of 256) at d = 2304 over 4096 tokens: the weight gradients run split
     four ways on the register-prefetch kernel with a half-empty last tile row, whose bias-gradient column sums must
