@@ -142,6 +142,31 @@ def test_attn_forward_only_keeps_nothing_and_agrees(ctx, rope, L, d):
     assert bool(torch.isnan(blk.qkv.float()).all())
 
 
+def test_attn_backward_with_optional_outputs(ctx):
+    """The input gradient alone and the weight/bias gradients without it equal what the full backward writes."""
+    h, dh, L, d = 4, 64, 200, 256
+    t = synth.attn_layer(38, 2, L, d, h, dh, dtype="bf16")
+    g = {nm: dev(a, "bf16") for nm, a in t.items()}
+    blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g["bq"], g["bk"], g["bv"], g["bo"], h, dh, rope=True, causal=True)
+    rng = np.random.default_rng(9)
+    iq = torch.from_numpy(np.stack([np.sort(rng.choice(dh // 2, 16, replace=False)) for _ in range(h)]).astype(np.int32)).cuda()
+    iv = torch.from_numpy(np.stack([np.sort(rng.choice(dh, 32, replace=False)) for _ in range(h)]).astype(np.int32)).cuda()
+    blk.compact(iq, iv).alloc(2, L)
+    blk.fwd(g["x"])
+    dx = blk.bwd(g["x"], g["dy"]).clone()
+    names = ("dwqkv_c", "dbqkv_c", "dwo_c", "dbo")
+    full = {nm: getattr(blk, nm).clone() for nm in names}
+    for nm in names:
+        getattr(blk, nm).fill_(float("nan"))
+    only_dx = torch.full_like(dx, float("nan"))
+    ctx.ecospa_coupled_bwd(blk._desc, g["x"], g["dy"], blk.saved, only_dx, B.Grads())
+    assert torch.equal(only_dx, dx)
+    assert all(bool(torch.isnan(getattr(blk, nm).float()).all()) for nm in names)
+    ctx.ecospa_coupled_bwd(blk._desc, g["x"], g["dy"], blk.saved, None, blk.grads)
+    for nm, want in full.items():
+        assert torch.equal(getattr(blk, nm), want), nm
+
+
 def test_attn_keep_all_is_dense(ctx):
     run_attn_case(ctx, 36, 2, 256, 256, 4, 64, 64, 64, rope=True, causal=True, wscale=4.0)
 

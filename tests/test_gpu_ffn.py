@@ -106,6 +106,39 @@ def test_ffn_forward_only_keeps_nothing_and_agrees(ctx, act, dtype, T, d, n, k):
     assert bool(torch.isnan(blk.hpre.float()).all()) and bool(torch.isnan(blk.act_buf.float()).all())   # untouched
 
 
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+def test_ffn_backward_with_optional_outputs(ctx, act):
+    """Every gradient pointer is optional: the input gradient alone, the weight gradients without it, and bias
+    gradients without their weight gradients (their own column-sum pass) equal what the full backward writes."""
+    T, d, n, k = 520, 264, 400, 200
+    t = synth.ffn_layer(34, T, d, n, gated=act == "swiglu", dtype="bf16")
+    g = {nm: dev(a, "bf16") for nm, a in t.items()}
+    idx = torch.from_numpy(np.sort(np.random.default_rng(5).choice(n, k, replace=False)).astype(np.int32)[None, :]).cuda()
+    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), ACT[act][0], g.get("w1b"))
+    blk.compact(idx).alloc(1, T)
+    blk.fwd(g["x"])
+    dx = blk.bwd(g["x"], g["dy"]).clone()
+    full = {nm: getattr(blk, nm).clone() for nm in ("dw1_c", "dw2_c", "db1_c", "db2")}
+    for nm in full:
+        getattr(blk, nm).fill_(float("nan"))
+    # input gradient only
+    only_dx = torch.full_like(dx, float("nan"))
+    ctx.ecospa_coupled_bwd(blk._desc, g["x"], g["dy"], blk.saved, only_dx, B.Grads())
+    assert torch.equal(only_dx, dx)
+    assert all(bool(torch.isnan(getattr(blk, nm).float()).all()) for nm in full)
+    # everything but the input gradient
+    ctx.ecospa_coupled_bwd(blk._desc, g["x"], g["dy"], blk.saved, None, blk.grads)
+    for nm, want in full.items():
+        assert torch.equal(getattr(blk, nm), want), nm
+    # bias gradients without the weight gradients
+    gr = B.Grads()
+    gr.db_1, gr.db_2 = blk.db1_c.data_ptr(), blk.db2.data_ptr()
+    blk.db1_c.fill_(float("nan")); blk.db2.fill_(float("nan"))
+    ctx.ecospa_coupled_bwd(blk._desc, g["x"], g["dy"], blk.saved, None, gr)
+    from util import TOL
+    assert O.rel_fro(host(blk.db1_c), host(full["db1_c"])) <= TOL["bf16"] and O.rel_fro(host(blk.db2), host(full["db2"])) <= TOL["bf16"]
+
+
 def test_ffn_weight_gradients_with_a_ragged_tile_row(ctx):
     """1100 kept units (padded to 1152 = 4.5 tiles of 256) at d = 2304 over 4096 tokens: the weight gradients run split
     four ways on the register-prefetch kernel with a half-empty last tile row, whose bias-gradient column sums must
