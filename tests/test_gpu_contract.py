@@ -86,6 +86,24 @@ def test_contract_stack_shapes_sampled(ctx, M, N, K, ta, tb):
     assert np.abs(block - want).max() <= 2e-2 * np.abs(want).max() + 1e-6
 
 
+def test_contract_launch_profile_counts_flops_and_time(ctx):
+    """The per-launch event profile the benchmark's roofline figure comes from: launches counted, 2MNK flops each,
+    a positive device time; nothing is recorded while it is switched off."""
+    a, b, bias, _ = _operands(50, 512, 256, 128, False, False, "bf16")
+    ga, gb = dev(a, "bf16"), dev(b, "bf16")
+    ctx.ecospa_profile_gemm(True)
+    for _ in range(3):
+        ctx.ecospa_contract(ga, False, gb, False, splits=1)
+    n, ms, flop = ctx.ecospa_profile_gemm_read()
+    assert n == 3 and flop == 3 * 2.0 * 512 * 256 * 128 and 0.0 < ms < 50.0
+    ctx.ecospa_profile_gemm(False)
+    ctx.ecospa_contract(ga, False, gb, False, splits=1)
+    ctx.ecospa_profile_gemm(True)
+    n, ms, flop = ctx.ecospa_profile_gemm_read()
+    assert n == 0 and flop == 0.0
+    ctx.ecospa_profile_gemm(False)
+
+
 def test_contract_alignment_errors(ctx):
     a = torch.zeros((64, 72), dtype=torch.bfloat16, device="cuda")
     b = torch.zeros((60, 72), dtype=torch.bfloat16, device="cuda")     # N = 60 is not a multiple of 8
