@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the MFMA contraction kernel, averaged over the 12 launches of one sparse
 # step, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/): (sha256 prefix of csrc/gemm*, bytes).
 # Reported only while the kernel source still has that hash; otherwise null.
-GEMM_TRAFFIC = ("913076f1d31921c6", 80.6e6)
+GEMM_TRAFFIC = ("2e0a4d1b1b034747", 79.2e6)
 
 
 def model_flops(T, L, d, h, k_qk, k_vo, k_ff, causal=True, gated=False, h_kv=None):

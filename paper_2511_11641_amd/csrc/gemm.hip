@@ -544,9 +544,9 @@ int ecospa_gemm_splits(int M, int N, int K) {
   const long long tiles = static_cast<long long>((M + 127) / 128) * ((N + 127) / 128);
   int s = 1;
   // Two 128x128 workgroups fit a compute unit, so 512 of them run at once: split K while all splits still fit
-  // that one round and every split keeps at least 512 of K.  More splits than that only add partial sums to
-  // write and reduce (measured on the weight-gradient shapes of both layers).
-  while (tiles * s * 2 <= 512 && K / (s * 2) >= 512 && s < 16) s *= 2;
+  // that one round and every split keeps at least 512 of K, eight ways at most.  More splits than that only add
+  // partial sums to write and reduce (measured on the weight-gradient shapes of both layers, inside their steps).
+  while (tiles * s * 2 <= 512 && K / (s * 2) >= 512 && s < 8) s *= 2;
   return s;
 }
 
