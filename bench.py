@@ -283,7 +283,8 @@ def second_workload(ctx, name, steps, warmup, h_kv=None):
     sp = Layer(ctx, cfg, cfg["seed"], 1, 2)
     ms_step = timed(torch, sp.step, steps, warmup)
     ms_fb = timed(torch, lambda: (sp.fwd(), sp.bwd()), steps, 2)
-    fl_sp = model_flops(T, L, d, h, sp.attn.kp_qk, sp.attn.kp_vo, sp.ffn.kp, gated=cfg["gated"], h_kv=h_kv)
+    # model flops count the kept dimensions, not the zero padding of the compact layout
+    fl_sp = model_flops(T, L, d, h, sp.attn.k_qk_units * sp.attn.unit, sp.attn.k_vo, sp.ffn.k, gated=cfg["gated"], h_kv=h_kv)
     del sp
     torch.cuda.empty_cache()
     de = Layer(ctx, cfg, cfg["seed"], 1, 1)
@@ -378,7 +379,7 @@ def stack_training(ctx, name, n_layers, vocab, Bsz, L, keeps, steps, rescore_eve
         n_launch, gemm_ms, gemm_flop = ctx.ecospa_profile_gemm_read()
         ctx.ecospa_profile_gemm(False)
         a, f = st.layers[0].attn["w"], st.layers[0].ffn["w"]
-        fl = _stack_flops(st, a.kp_qk, a.kp_vo, f.kp, 3)
+        fl = _stack_flops(st, a.k_qk_units * a.unit, a.k_vo, f.k, 3)      # kept dimensions, not the padding
         dense_ms = ms_step if (num, den) == (1, 1) else dense_ms
         amort = (rescore_every - 1) * ms_step + (ms_step + ms_prune)
         rows.append({"keep": f"{num}/{den}", "ms_step": ms_step, "ms_rescore_step": ms_step + ms_prune,
@@ -572,7 +573,7 @@ def main():
                               "exponential, so this kernel is priced against the vector ALU (about 25 other vector operations per "
                               "exponential: scaling, running maximum, conversions), not against the MFMA peak"}
 
-    fl_sparse = model_flops(T, L, d, h, sparse.attn.kp_qk, sparse.attn.kp_vo, sparse.ffn.kp)
+    fl_sparse = model_flops(T, L, d, h, sparse.attn.k_qk_units * sparse.attn.unit, sparse.attn.k_vo, sparse.ffn.k)
     del sparse
     torch.cuda.empty_cache()
 
