@@ -97,3 +97,22 @@ def test_full_layer_step_matches_oracle(ctx, name, num, den):
     assert_close(lay.ffn.db2, gf["db2"], "bf16", "db_2")
     if not cfg["gated"]:
         assert_close(lay.ffn.db1_c, want_db1, "bf16", "db_1")
+
+
+@pytest.mark.parametrize("name", ["c2_gpt2m_layer", "c3_llama1b_layer"])
+def test_full_layer_step_is_reproducible_bit_for_bit(ctx, name):
+    """No float atomics anywhere on the path (split-K partials, bias-gradient column sums, dK/dV are all added in
+    a fixed order): two steps from the same inputs give identical bits in every output."""
+    cfg = dict(synth.CONFIGS[name])
+    lay = bench.Layer(ctx, cfg, cfg["seed"], 1, 2)
+    runs = []
+    for _ in range(2):
+        lay.step()
+        torch.cuda.synchronize()
+        a, f = lay.attn, lay.ffn
+        outs = [lay.scores[0], lay.scores[2], lay.idx[0], lay.idx[2], a.y, f.y, f.dx, a.dx, a.dwqkv_c, a.dwo_c, f.dw1_c, f.dw2_c]
+        if cfg["bias"]:
+            outs += [a.dbqkv_c, a.dbo, f.db1_c, f.db2]
+        runs.append([t.clone() for t in outs])
+    for i, (x, y) in enumerate(zip(*runs)):
+        assert torch.equal(x, y), f"output {i} differs between two runs"
