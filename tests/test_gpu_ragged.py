@@ -100,6 +100,25 @@ def test_merging_scatter_leaves_pruned_slots_untouched(ctx, dtype, axis, groups,
     assert np.array_equal(host(out), O.scatter_ragged(c, iu, np.full(groups, k), axis, n, nu, unit, base=base).astype(np.float64))
 
 
+@pytest.mark.parametrize("axis", [0, 1])
+@pytest.mark.parametrize("mode", [1, 2])
+def test_scatter_with_a_shared_index_list_per_head_group(ctx, axis, mode):
+    """Grouped-query layout (Eq. 5): 8 query heads in groups of 2 share 4 index lists; both scatters (zero fill, and
+    onto the existing contents) agree with the oracle run on the index lists repeated per head."""
+    groups, div, n, k, other = 8, 2, 64, 24, 200
+    rng = np.random.default_rng(77)
+    idx = np.stack([np.sort(rng.choice(n, k, replace=False)) for _ in range(groups // div)]).astype(np.int32)
+    rep = np.repeat(idx, div, axis=0)
+    shape_f = (groups * n, other) if axis == 0 else (other, groups * n)
+    shape_c = (groups * k, other) if axis == 0 else (other, groups * k)
+    base = synth.round_to(synth.normal(43, 1, shape_f), "bf16")
+    c = synth.round_to(synth.normal(43, 2, shape_c), "bf16")
+    out = dev(base, "bf16").clone()
+    ctx.ecospa_compact_batch([ctx.map_item(dev(c, "bf16"), out, torch.from_numpy(idx).cuda(), axis, groups, n, 1, k, scatter=mode, idx_div=div)])
+    want = O.scatter_ragged(c, rep, np.full(groups, k), axis, n, k, 1, base=base if mode == 2 else None)
+    assert np.array_equal(host(out), want.astype(np.float64))
+
+
 def test_merging_scatter_of_a_vector_and_bad_mode(ctx):
     groups, n = 4, 24
     idx, ks = _ragged_idx(5, groups, n)
