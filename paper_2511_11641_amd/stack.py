@@ -51,17 +51,18 @@ class _Layer:
 class DecoderStack:
     def __init__(self, ctx: B.Context, cfg: dict, n_layers: int, vocab: int, keep=(1, 2), seed: int = 0,
                  train: bool = True, lr: float = 1e-4, weight_decay: float = 0.01):
-        """cfg: B, L, d, h, d_h, d_ff, gated, rope, bias as in synth.CONFIGS (gated: RMSNorm, no position table;
+        """cfg: B, L, d, h, d_h, d_ff, gated, rope, bias as in synth.CONFIGS, optionally h_kv (gated: RMSNorm, no position table;
         otherwise LayerNorm with a learned position table).  keep = (num, den): every pair keeps
         floor(n * num / den) of its units; (1, 1) is the dense model through the same code."""
         self.ctx, self.cfg, self.train = ctx, cfg, train
         self.Bsz, self.L, self.d, self.h, self.d_h, self.d_ff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
+        self.h_kv = cfg.get("h_kv", self.h)      # fewer key/value heads than query heads: grouped-query attention (Eq. 5)
         self.T = self.Bsz * self.L
         self.vocab, self.lr, self.wd, self.t = vocab, lr, weight_decay, 0
         self.rms = bool(cfg["gated"])
         self.eps = 1e-6 if self.rms else 1e-5
         gen = torch.Generator(device="cuda").manual_seed(seed)
-        d, h, dh, dff = self.d, self.h, self.d_h, self.d_ff
+        d, h, dh, dff, hkv = self.d, self.h, self.d_h, self.d_ff, self.h_kv
 
         def rnd(*shape):
             return torch.randn(*shape, device="cuda", generator=gen) * 0.02
@@ -84,9 +85,9 @@ class DecoderStack:
         for _ in range(n_layers):
             ly = _Layer()
             names = ["wq", "wk", "wv", "wo", "w1", "w2"] + (["w1b"] if cfg["gated"] else [])
-            shapes = {"wq": (h * dh, d), "wk": (h * dh, d), "wv": (h * dh, d), "wo": (d, h * dh), "w1": (dff, d),
+            shapes = {"wq": (h * dh, d), "wk": (hkv * dh, d), "wv": (hkv * dh, d), "wo": (d, h * dh), "w1": (dff, d),
                       "w1b": (dff, d), "w2": (d, dff)}
-            bias_shapes = {"bq": h * dh, "bk": h * dh, "bv": h * dh, "bo": d, "b1": dff, "b2": d} if cfg["bias"] else {}
+            bias_shapes = {"bq": h * dh, "bk": hkv * dh, "bv": hkv * dh, "bo": d, "b1": dff, "b2": d} if cfg["bias"] else {}
             init = {n: rnd(*shapes[n]).to(torch.bfloat16) for n in names}
             init.update({n: torch.zeros(s, device="cuda", dtype=torch.bfloat16) for n, s in bias_shapes.items()})
             ly.full, ly.attn, ly.ffn = {}, {}, {}
@@ -99,11 +100,12 @@ class DecoderStack:
                     t = {n: rows_aligned(torch.zeros(x.shape, device="cuda")) for n, x in init.items()}
                 ly.full[fam] = t
                 ly.attn[fam] = AttnBlock(ctx, t["wq"], t["wk"], t["wv"], t["wo"], t.get("bq"), t.get("bk"), t.get("bv"),
-                                         t.get("bo"), h, dh, rope=cfg["rope"], causal=True, transposed=(fam == "w" and train))
+                                         t.get("bo"), h, dh, rope=cfg["rope"], causal=True, transposed=(fam == "w" and train),
+                                         h_kv=hkv)
                 ly.ffn[fam] = FfnBlock(ctx, t["w1"], t.get("b1"), t["w2"], t.get("b2"), act, t.get("w1b"),
                                        transposed=(fam == "w" and train))
-            ly.idx = [torch.empty((h, self.k[0]), dtype=torch.int32, device="cuda"),
-                      torch.empty((h, self.k[1]), dtype=torch.int32, device="cuda"),
+            ly.idx = [torch.empty((hkv, self.k[0]), dtype=torch.int32, device="cuda"),
+                      torch.empty((hkv, self.k[1]), dtype=torch.int32, device="cuda"),
                       torch.empty((1, self.k[2]), dtype=torch.int32, device="cuda")]
             ly.norm = [self._norm_params() for _ in range(2)]
             self.layers.append(ly)

@@ -16,6 +16,7 @@ pytestmark = pytest.mark.gpu
 
 GPT = dict(B=2, L=64, d=128, h=2, d_h=64, d_ff=256, gated=False, rope=False, bias=True)
 LLAMA = dict(B=2, L=64, d=128, h=2, d_h=64, d_ff=264, gated=True, rope=True, bias=False)
+LLAMA_GQA = dict(LLAMA, h=4, h_kv=2, d=256)      # two query heads per key/value head
 VOCAB = 512
 
 
@@ -63,17 +64,21 @@ def _reference(st: DecoderStack, ids, targets):
     causal = torch.ones(L, L, dtype=torch.bool, device="cuda").tril()
     for li, ly in enumerate(st.layers):
         unit = 2 if cfg["rope"] else 1
-        mqk = _kept_mask(ly.idx[0], h, dh, unit).float()
-        mvo = _kept_mask(ly.idx[1], h, dh, 1).float()
+        hkv = st.h_kv
+        rep = h // hkv          # a group's query heads (and heads of W_o) keep the dimensions of their key/value head
+        mk_, mv_ = _kept_mask(ly.idx[0], hkv, dh, unit).float(), _kept_mask(ly.idx[1], hkv, dh, 1).float()
+        mqk = mk_.view(hkv, 1, dh).expand(hkv, rep, dh).reshape(-1)
+        mvo = mv_.view(hkv, 1, dh).expand(hkv, rep, dh).reshape(-1)
         mff = _kept_mask(ly.idx[2], 1, st.d_ff, 1).float()
         f = ly.full["w"]
-        wq, wk = leaf(f"{li}.wq", f["wq"]) * mqk[:, None], leaf(f"{li}.wk", f["wk"]) * mqk[:, None]
-        wv, wo = leaf(f"{li}.wv", f["wv"]) * mvo[:, None], leaf(f"{li}.wo", f["wo"]) * mvo[None, :]
+        wq, wk = leaf(f"{li}.wq", f["wq"]) * mqk[:, None], leaf(f"{li}.wk", f["wk"]) * mk_[:, None]
+        wv, wo = leaf(f"{li}.wv", f["wv"]) * mv_[:, None], leaf(f"{li}.wo", f["wo"]) * mvo[None, :]
         h1 = norm(x, ly.norm[0], f"{li}.n1")
         q, k, v = h1 @ wq.T, h1 @ wk.T, h1 @ wv.T
         if cfg["bias"]:
-            q, k, v = q + leaf(f"{li}.bq", f["bq"]) * mqk, k + leaf(f"{li}.bk", f["bk"]) * mqk, v + leaf(f"{li}.bv", f["bv"]) * mvo
-        q, k, v = (t.view(Bsz, L, h, dh) for t in (q, k, v))
+            q, k, v = q + leaf(f"{li}.bq", f["bq"]) * mqk, k + leaf(f"{li}.bk", f["bk"]) * mk_, v + leaf(f"{li}.bv", f["bv"]) * mv_
+        q = q.view(Bsz, L, h, dh)
+        k, v = (t.view(Bsz, L, hkv, dh).repeat_interleave(rep, dim=2) for t in (k, v))
         if cfg["rope"]:
             q, k = _rope(q, L, dh), _rope(k, L, dh)
         s = torch.einsum("blhd,bmhd->bhlm", q, k) * dh ** -0.5
@@ -104,7 +109,7 @@ def _rel(got, want):
     return O.rel_fro(host(got), host(want))
 
 
-@pytest.mark.parametrize("cfg", [GPT, LLAMA], ids=["gpt2_like", "llama_like"])
+@pytest.mark.parametrize("cfg", [GPT, LLAMA, LLAMA_GQA], ids=["gpt2_like", "llama_like", "llama_gqa"])
 @pytest.mark.parametrize("keep", [(1, 1), (1, 2)], ids=["dense", "half"])
 def test_stack_matches_masked_dense_torch_model(ctx, cfg, keep):
     st = DecoderStack(ctx, cfg, n_layers=2, vocab=VOCAB, keep=keep, seed=3)
@@ -128,10 +133,11 @@ def test_stack_matches_masked_dense_torch_model(ctx, cfg, keep):
         kq, kv, kf = a.k_qk_units * unit, a.k_vo, f.k
         # compact gradients against the reference's gradients gathered with the same indices; pruned entries of the
         # reference carry no gradient (their partner row/column is zero)
-        gq = O.compact(host(leaves[f"{li}.wq"].grad), ly.idx[0].cpu().numpy(), 0, st.d_h, unit)
+        rep = st.h // st.h_kv
+        gq = O.compact(host(leaves[f"{li}.wq"].grad), np.repeat(ly.idx[0].cpu().numpy(), rep, axis=0), 0, st.d_h, unit)
         got = host(a.dwqkv_c[:a.nq]).reshape(st.h, a.kp_qk, st.d)[:, :kq].reshape(-1, st.d)
         assert O.rel_fro(got, gq) <= tol, f"layer {li} dW_q"
-        go = O.compact(host(leaves[f"{li}.wo"].grad), ly.idx[1].cpu().numpy(), 1, st.d_h, 1)
+        go = O.compact(host(leaves[f"{li}.wo"].grad), np.repeat(ly.idx[1].cpu().numpy(), rep, axis=0), 1, st.d_h, 1)
         got = host(a.dwo_c).reshape(st.d, st.h, a.kp_vo)[:, :, :kv].reshape(st.d, -1)
         assert O.rel_fro(got, go) <= tol, f"layer {li} dW_o"
         g1 = O.compact(host(leaves[f"{li}.w1"].grad), ly.idx[2].cpu().numpy(), 0, st.d_ff, 1)
