@@ -1,8 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the coupled-sparse hot path on one MI355X.
 
-A "step" is one pass of the whole path over one batch of a GPT-2-Medium-shaped layer
-(d=1024, 16 heads x 64, d_ff=4096, GELU, batch 8 x seq 1024, bf16):
+A "step" is one pass of the whole path over one batch of a LLaMA-1B-shaped layer
+(d=2048, 32 heads x 64, SwiGLU d_ff=5461, RoPE, batch 16 x seq 256, bf16) - the larger of the two layer
+configurations the metric names; the GPT-2-Medium-shaped layer (d=1024, 16 heads x 64, d_ff=4096, GELU,
+batch 8 x seq 1024) runs through the same code right after it and is reported inside `roofline` and `also`:
     score the QK, VO and FFN pairs (one batched call) -> select top-k at 50% keep (one call) ->
     compact every matrix (one call) -> attention fwd -> FFN fwd -> FFN bwd -> attention bwd.
 Inputs are seeded synthetic tensors (weights N(0, 0.02^2), activations N(0, 1)) that are
@@ -23,10 +25,12 @@ METRIC = "coupled-sparse layer fwd+bwd tokens/s & TFLOP/s vs dense, 50% sparsity
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the MFMA contraction kernel, averaged over the 12 launches of one sparse
-# step, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/): (sha256 prefix of csrc/gemm*, bytes).
-# Reported only while the kernel source still has that hash; otherwise null.
-GEMM_TRAFFIC = ("2e0a4d1b1b034747", 79.2e6)
+# HBM bytes per launch of the MFMA contraction kernels, averaged over the contraction launches of one sparse
+# step of the headline workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/):
+# (sha256 prefix of csrc/gemm*, bytes).  Reported only while the kernel sources still have that hash; otherwise null.
+GEMM_TRAFFIC = ("", 0.0)
+HEADLINE = "c3_llama1b_layer"
+SECOND = "c2_gpt2m_layer"
 
 
 def model_flops(T, L, d, h, k_qk, k_vo, k_ff, causal=True, gated=False, h_kv=None):
@@ -269,10 +273,11 @@ def fp32_pair_workload(ctx, steps):
             "tokens_per_s": T / (ms * 1e-3), "note": "0.8 GFLOP in ten short launches on the vector ALU: latency-bound, reported as a time only"}
 
 
-def second_workload(ctx, name, steps, warmup, h_kv=None):
-    """The LLaMA-1B-shaped layer (RoPE, SwiGLU, no biases) through the same path: whole step at 50 % keep,
-    fwd+bwd alone, and the dense layer (same library at k = n).  With h_kv: the same layer with that many shared
-    key/value heads (grouped-query attention, Eq. 5)."""
+def layer_workload(ctx, name, steps, warmup, h_kv=None, detail=True):
+    """One layer configuration through the whole path: the timed sparse step at 50 % keep (`ms_per_step`), its parts,
+    fwd+bwd alone, the dense layer (same library at k = n), and - with detail - the contraction kernels' own launch
+    times (HIP events on the library's stream around every launch, in steps run again after the timed region) and the
+    attention core's forward time.  With h_kv: the same layer with that many shared key/value heads (Eq. 5)."""
     import torch
     from paper_2511_11641_amd import synth
     cfg = dict(synth.CONFIGS[name])
@@ -282,20 +287,77 @@ def second_workload(ctx, name, steps, warmup, h_kv=None):
     T = Bsz * L
     sp = Layer(ctx, cfg, cfg["seed"], 1, 2)
     ms_step = timed(torch, sp.step, steps, warmup)
+    out = {"workload": name if h_kv is None else f"{name}, {h_kv} key/value heads", "batch": Bsz, "seq_len": L,
+           "ms_per_step": ms_step, "tokens_per_s": T / (ms_step * 1e-3)}
+    if detail:
+        # break-down of the same step, each part timed on its own with device-side events (on the host clock the three
+        # short pruning calls would show their Python marshalling rather than their kernels)
+        parts = {nm: timed_gpu(torch, fn, steps, 2) for nm, fn in
+                 (("score", sp.score), ("select", sp.select), ("compact", sp.compact), ("fwd", sp.fwd), ("bwd", sp.bwd))}
+        out["parts_ms"] = parts
     ms_fb = timed(torch, lambda: (sp.fwd(), sp.bwd()), steps, 2)
     # model flops count the kept dimensions, not the zero padding of the compact layout
     fl_sp = model_flops(T, L, d, h, sp.attn.k_qk_units * sp.attn.unit, sp.attn.k_vo, sp.ffn.k, gated=cfg["gated"], h_kv=h_kv)
+    out["fwd_bwd"] = {"ms": ms_fb, "tokens_per_s": T / (ms_fb * 1e-3), "model_tflops": fl_sp / (ms_fb * 1e-3) / 1e12}
+    if detail:
+        ctx.ecospa_profile_gemm(True)
+        for _ in range(steps):
+            sp.step()
+        n_launch, gemm_ms, gemm_flop = ctx.ecospa_profile_gemm_read()
+        ctx.ecospa_profile_gemm(False)
+        gemm_tflops = gemm_flop / (gemm_ms * 1e-3) / 1e12
+        out["contractions"] = {"achieved": gemm_tflops, "frac": gemm_tflops / MFMA_BF16_PEAK_TFLOPS, "launches": n_launch,
+                               "launches_per_step": n_launch // max(steps, 1),
+                               "avg_launch_us": gemm_ms * 1e3 / max(n_launch, 1), "flop_per_launch_avg": gemm_flop / max(n_launch, 1),
+                               "us_per_step": gemm_ms * 1e3 / max(steps, 1)}
+        # the attention core on its own (bound by exponentials and conversions on the vector ALU, not by the matrix
+        # units): forward time minus the time of the contraction launches inside the same forward passes
+        ctx.ecospa_profile_gemm(True)
+        for _ in range(steps):
+            sp.fwd()
+        _, gemm_ms_fwd, _ = ctx.ecospa_profile_gemm_read()
+        ctx.ecospa_profile_gemm(False)
+        core_us = (parts["fwd"] - gemm_ms_fwd / steps) * 1e3
+        exps = Bsz * h * L * (L + 1) / 2.0
+        exp_peak = 256 * 4 * 16 / 4 * 2.4e9          # compute units x SIMDs x lanes per clock, transcendentals at quarter rate
+        out["attention_core"] = {"fwd_us": core_us, "exponentials": exps, "exp_per_s": exps / (core_us * 1e-6),
+                                 "frac_of_transcendental_peak": exps / (core_us * 1e-6) / exp_peak,
+                                 "note": "causal softmax exponentials of the forward pass (incl. the rotary pass where there is one); "
+                                         "at 32 kept dimensions a head has only 128 matrix flops per exponential, so the core is priced "
+                                         "against the vector ALU, not the MFMA peak"}
+        w_bytes = 2 * (4 * d * d + (3 if cfg["gated"] else 2) * d * dff)     # every weight of the three pairs, bf16
+        out["score_gbs"] = w_bytes / (parts["score"] * 1e-3) / 1e9
+        out["compact_gbs"] = w_bytes / (parts["compact"] * 1e-3) / 1e9        # kept bytes read + kept bytes written (+ transposed copies)
     del sp
     torch.cuda.empty_cache()
-    de = Layer(ctx, cfg, cfg["seed"], 1, 1)
+    de = Layer(ctx, cfg, cfg["seed"], 1, 1)        # same library at k = n: the dense layer
     ms_de = timed(torch, lambda: (de.fwd(), de.bwd()), steps, warmup)
     fl_de = model_flops(T, L, d, h, dh, dh, dff, gated=cfg["gated"], h_kv=h_kv)
     del de
     torch.cuda.empty_cache()
-    return {"workload": name if h_kv is None else f"{name}, {h_kv} key/value heads", "batch": Bsz, "seq_len": L, "ms_per_step": ms_step, "tokens_per_s": T / (ms_step * 1e-3),
-            "fwd_bwd": {"ms": ms_fb, "tokens_per_s": T / (ms_fb * 1e-3), "model_tflops": fl_sp / (ms_fb * 1e-3) / 1e12},
-            "dense_fwd_bwd": {"ms": ms_de, "tokens_per_s": T / (ms_de * 1e-3), "model_tflops": fl_de / (ms_de * 1e-3) / 1e12},
-            "speedup_fwd_bwd_vs_dense": ms_de / ms_fb}
+    out["dense_fwd_bwd"] = {"ms": ms_de, "tokens_per_s": T / (ms_de * 1e-3), "model_tflops": fl_de / (ms_de * 1e-3) / 1e12}
+    out["speedup_fwd_bwd_vs_dense"] = ms_de / ms_fb
+    out["speedup_whole_step_vs_dense_fwd_bwd"] = ms_de / ms_step
+    return out
+
+
+def hbm_ceilings(ctx, nbytes, steps=10):
+    """What plain kernels reach on this GPU over a buffer of the size the 24-layer pruning pass reads: a streaming read
+    and a 1:1 copy (the library's own probe kernels and, for the copy, torch's device copy as a second opinion)."""
+    import torch
+    n = int(nbytes) // 16 * 16
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    sink = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    t_read = timed_gpu(torch, lambda: ctx.ecospa_hbm_probe(src, sink, False), steps, 3)
+    dst.zero_()
+    t_copy = timed_gpu(torch, lambda: ctx.ecospa_hbm_probe(src, dst, True), steps, 3)
+    ok = bool(torch.equal(src, dst))
+    t_tcopy = timed_gpu(torch, lambda: dst.copy_(src), steps, 3)
+    del src, dst
+    torch.cuda.empty_cache()
+    return {"bytes": n, "read_gbs": n / t_read / 1e6, "copy_gbs": 2 * n / t_copy / 1e6, "torch_copy_gbs": 2 * n / t_tcopy / 1e6,
+            "copy_checked": ok, "note": "plain streaming read / 1:1 copy (bytes read + bytes written) of a buffer of this size, same run"}
 
 
 def torch_dense_layer(name, steps):
@@ -499,6 +561,7 @@ def main():
                     help="run only the LLaMA-1B-shaped 24-layer training workload at 50 %% keep (for profiler runs)")
     ap.add_argument("--sparse-only", action="store_true",
                     help="run only the timed sparse steps (for hardware-counter runs) and print a short line")
+    ap.add_argument("--workload", default=None, help="with --sparse-only: c3_llama1b_layer (default) or c2_gpt2m_layer")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU hot path only: run it with --gpus 1 "
@@ -510,12 +573,13 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs an MI355X: no GPU is visible.", file=sys.stderr)
         sys.exit(2)
-    name = "c2_gpt2m_layer"
+    name = HEADLINE
     cfg = dict(synth.CONFIGS[name])
     seed = cfg["seed"]
     ctx = B.Context("cuda:0")
     Bsz, L, d, h, dh, dff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
     T = Bsz * L
+    c2 = dict(synth.CONFIGS[SECOND])
 
     if args.pmc_reference:      # a plain device copy reads 128 MiB and writes 128 MiB per launch
         ref = torch.zeros((65536, 1024), dtype=torch.bfloat16, device="cuda")
@@ -526,7 +590,7 @@ def main():
         del ref, out_ref
 
     if args.prune_only:
-        print(json.dumps({"prune_24_layers": prune_stack(ctx, cfg, 24, 1, 2, 20)}))
+        print(json.dumps({"prune_24_layers": prune_stack(ctx, c2, 24, 1, 2, 20)}))
         return
 
     if args.stack_step_only:
@@ -536,97 +600,87 @@ def main():
         print(json.dumps(stack_workloads(ctx)))
         return
 
-    sparse = Layer(ctx, cfg, seed, 1, 2)
-    ms_step = timed(torch, sparse.step, args.steps, args.warmup)
     if args.sparse_only:
-        print(json.dumps({"ms_per_step": ms_step, "steps": args.steps, "warmup": args.warmup}))
+        wl = args.workload or name
+        sparse = Layer(ctx, dict(synth.CONFIGS[wl]), synth.CONFIGS[wl]["seed"], 1, 2)
+        ms_step = timed(torch, sparse.step, args.steps, args.warmup)
+        print(json.dumps({"workload": wl, "ms_per_step": ms_step, "steps": args.steps, "warmup": args.warmup}))
         return
 
-    # break-down of the same step, each part timed on its own with device-side events (not part of `value`; on the host
-    # clock the three short pruning calls would show their Python marshalling rather than their kernels)
-    parts = {nm: timed_gpu(torch, fn, args.steps, 2) for nm, fn in
-             (("score", sparse.score), ("select", sparse.select), ("compact", sparse.compact),
-              ("fwd", sparse.fwd), ("bwd", sparse.bwd))}
-    ms_fb = timed(torch, lambda: (sparse.fwd(), sparse.bwd()), args.steps, 2)
+    main_wl = layer_workload(ctx, name, args.steps, args.warmup)
+    ms_step = main_wl["ms_per_step"]
+    gm = main_wl["contractions"]
+    second = layer_workload(ctx, SECOND, args.steps, args.warmup)
+    g2 = second["contractions"]
 
-    # dominant kernel: the bf16 MFMA contraction; per-launch events on the library's own stream
-    ctx.ecospa_profile_gemm(True)
-    for _ in range(args.steps):
-        sparse.step()
-    n_launch, gemm_ms, gemm_flop = ctx.ecospa_profile_gemm_read()
-    ctx.ecospa_profile_gemm(False)
-    gemm_tflops = gemm_flop / (gemm_ms * 1e-3) / 1e12
+    # the HBM-bound steps on a whole model's weights (24 layers, 604 MB), beside what plain kernels reach on the same bytes
+    prune = prune_stack(ctx, c2, 24, 1, 2, 20)
+    ceil = hbm_ceilings(ctx, prune["weights_MB"] * 1e6)
+    hbm = {"peak_gbs": HBM_PEAK_GBS, "workload": "steps 1-3 over 24 GPT-2-Medium-shaped layers, one call each",
+           "weights_MB": prune["weights_MB"], "read_ceiling_gbs": ceil["read_gbs"],
+           "copy_ceiling_gbs": max(ceil["copy_gbs"], ceil["torch_copy_gbs"]), "ceilings": ceil,
+           "score": {"us": prune["score"]["us"], "gbs": prune["score"]["gbs"], "frac_of_peak": prune["score"]["frac_of_hbm_peak"],
+                     "frac_of_read_ceiling": prune["score"]["gbs"] / ceil["read_gbs"]},
+           "select": {"us": prune["select"]["us"]},
+           "compact": {"us": prune["compact"]["us"], "kept_gbs": prune["compact"]["kept_gbs"],
+                       "traffic_gbs": prune["compact"]["traffic_gbs"],
+                       "frac_of_peak_kept": prune["compact"]["kept_gbs"] / HBM_PEAK_GBS,
+                       "frac_of_peak_traffic": prune["compact"]["frac_of_hbm_peak"],
+                       "frac_of_copy_ceiling_kept": prune["compact"]["kept_gbs"] / max(ceil["copy_gbs"], ceil["torch_copy_gbs"]),
+                       "frac_of_copy_ceiling_traffic": prune["compact"]["traffic_gbs"] / max(ceil["copy_gbs"], ceil["torch_copy_gbs"])}}
 
-    # the attention core on its own (it is bound by exponentials and conversions on the vector ALU, not by the
-    # matrix units): forward time minus the time of the contraction launches inside the same forward passes
-    ctx.ecospa_profile_gemm(True)
-    for _ in range(args.steps):
-        sparse.fwd()
-    _, gemm_ms_fwd, _ = ctx.ecospa_profile_gemm_read()
-    ctx.ecospa_profile_gemm(False)
-    core_us = (parts["fwd"] - gemm_ms_fwd / args.steps) * 1e3
-    exps = Bsz * h * L * (L + 1) / 2.0
-    exp_peak = 256 * 4 * 16 / 4 * 2.4e9          # compute units x SIMDs x lanes per clock, transcendentals at quarter rate
-    attention_core = {"fwd_us": core_us, "exponentials": exps, "exp_per_s": exps / (core_us * 1e-6),
-                      "frac_of_transcendental_peak": exps / (core_us * 1e-6) / exp_peak,
-                      "note": "causal softmax exponentials of the forward pass; k_qk = k_vo = 32 gives only 128 matrix flops per "
-                              "exponential, so this kernel is priced against the vector ALU (about 25 other vector operations per "
-                              "exponential: scaling, running maximum, conversions), not against the MFMA peak"}
-
-    fl_sparse = model_flops(T, L, d, h, sparse.attn.k_qk_units * sparse.attn.unit, sparse.attn.k_vo, sparse.ffn.k)
-    del sparse
-    torch.cuda.empty_cache()
-
-    dense = Layer(ctx, cfg, seed, 1, 1)        # same library at k = n: the dense layer
-    ms_dense_fb = timed(torch, lambda: (dense.fwd(), dense.bwd()), args.steps, args.warmup)
-    fl_dense = model_flops(T, L, d, h, dh, dh, dff)
-    del dense
-
-    w_bytes = 2 * (4 * d * d + 2 * d * dff)     # every weight of the three pairs, bf16
     out = {
         "metric": METRIC, "value": T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": name, "layer": "GPT-2-Medium shaped: d=1024, 16 heads x 64, d_ff=4096, GELU, causal",
-                   "batch": Bsz, "seq_len": L, "keep": "1/2 per coupled pair (k_qk=32, k_vo=32, k_ff=2048)",
-                   "step": "score+select+compact+attn/ffn fwd+bwd"},
-        "fwd_bwd": {"ms": ms_fb, "tokens_per_s": T / (ms_fb * 1e-3), "model_tflops": fl_sparse / (ms_fb * 1e-3) / 1e12},
-        "dense_fwd_bwd": {"ms": ms_dense_fb, "tokens_per_s": T / (ms_dense_fb * 1e-3),
-                          "model_tflops": fl_dense / (ms_dense_fb * 1e-3) / 1e12},
-        "speedup_fwd_bwd_vs_dense": ms_dense_fb / ms_fb,
-        "speedup_whole_step_vs_dense_fwd_bwd": ms_dense_fb / ms_step,
-        "parts_ms": parts,
-        "attention_core": attention_core,
-        "score_gbs": w_bytes / (parts["score"] * 1e-3) / 1e9,
-        "compact_gbs": w_bytes / (parts["compact"] * 1e-3) / 1e9,   # kept bytes read + kept bytes written
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_{pipe,mfma,rs}_kernel", "achieved": gemm_tflops,
-                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": gemm_traffic(),
-                     "launches": n_launch, "avg_launch_us": gemm_ms * 1e3 / max(n_launch, 1),
-                     "flop_per_launch_avg": gemm_flop / max(n_launch, 1),
-                     "measured": f"HIP events around each launch, {args.steps} steps re-run after the timed region"},
+        "config": {"workload": name, "layer": "LLaMA-1B shaped: d=2048, 32 heads x 64, SwiGLU d_ff=5461, RoPE, causal, no biases",
+                   "batch": Bsz, "seq_len": L, "keep": "1/2 per coupled pair (16 of 32 rotary blocks, k_vo=32, k_ff=2730)",
+                   "step": "score+select+compact+attn/ffn fwd+bwd",
+                   "second_workload": SECOND + " (same path; its figures are in roofline." + SECOND + " and in also)"},
+        "fwd_bwd": main_wl["fwd_bwd"], "dense_fwd_bwd": main_wl["dense_fwd_bwd"],
+        "speedup_fwd_bwd_vs_dense": main_wl["speedup_fwd_bwd_vs_dense"],
+        "speedup_whole_step_vs_dense_fwd_bwd": main_wl["speedup_whole_step_vs_dense_fwd_bwd"],
+        "parts_ms": main_wl["parts_ms"], "attention_core": main_wl["attention_core"],
+        "score_gbs": main_wl["score_gbs"], "compact_gbs": main_wl["compact_gbs"],
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_{pipe,mfma,rs}_kernel", "achieved": gm["achieved"],
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gm["frac"], "traffic": gemm_traffic(),
+                     "launches": gm["launches"], "launches_per_step": gm["launches_per_step"], "avg_launch_us": gm["avg_launch_us"],
+                     "flop_per_launch_avg": gm["flop_per_launch_avg"],
+                     "measured": f"HIP events around each launch, {args.steps} steps re-run after the timed region",
+                     "step": {"ms_per_step": ms_step, "fwd_bwd_ms": main_wl["fwd_bwd"]["ms"], "dense_fwd_bwd_ms": main_wl["dense_fwd_bwd"]["ms"],
+                              "speedup_fwd_bwd_vs_dense": main_wl["speedup_fwd_bwd_vs_dense"],
+                              "model_tflops_fwd_bwd": main_wl["fwd_bwd"]["model_tflops"],
+                              "attention_core_fwd_us": main_wl["attention_core"]["fwd_us"]},
+                     SECOND: {"achieved": g2["achieved"], "frac": g2["frac"], "avg_launch_us": g2["avg_launch_us"],
+                              "launches_per_step": g2["launches_per_step"], "flop_per_launch_avg": g2["flop_per_launch_avg"],
+                              "ms_per_step": second["ms_per_step"], "tokens_per_s": second["tokens_per_s"],
+                              "fwd_bwd_ms": second["fwd_bwd"]["ms"], "dense_fwd_bwd_ms": second["dense_fwd_bwd"]["ms"],
+                              "speedup_fwd_bwd_vs_dense": second["speedup_fwd_bwd_vs_dense"],
+                              "model_tflops_fwd_bwd": second["fwd_bwd"]["model_tflops"],
+                              "attention_core_fwd_us": second["attention_core"]["fwd_us"], "parts_ms": second["parts_ms"]},
+                     "hbm": hbm},
+        "also": second,
+        "prune_24_layers": prune,
     }
     if not args.no_extras:
-        out["prune_24_layers"] = prune_stack(ctx, cfg, 24, 1, 2, 20)
-        out["also"] = second_workload(ctx, "c3_llama1b_layer", args.steps, args.warmup)
         out["fp32_pair"] = fp32_pair_workload(ctx, args.steps)
-        out["gqa_layer"] = second_workload(ctx, "c3_llama1b_layer", args.steps, args.warmup, h_kv=8)
-        out["inference"] = inference_sweep(ctx, name, 20)
-        out["torch_dense_fwd_bwd"] = torch_dense_layer(name, 20)
+        out["gqa_layer"] = layer_workload(ctx, "c3_llama1b_layer", args.steps, args.warmup, h_kv=8, detail=False)
+        out["inference"] = inference_sweep(ctx, SECOND, 20)
+        out["torch_dense_fwd_bwd"] = torch_dense_layer(SECOND, 20)
         out.update(stack_workloads(ctx))
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, seed, 1, 2, sample_B=8)
+        # the fp64 oracle on the whole batch of the headline layer, and of the second one (inside the same object)
+        cb = cpu_baseline(cfg, seed, 1, 2, sample_B=cfg["B"])
+        cb[SECOND] = cpu_baseline(c2, c2["seed"], 1, 2, sample_B=c2["B"])
+        out["cpu_baseline"] = cb
         if not args.no_extras:
             # the oracle beside the multi-layer workloads: one layer timed, the stack figure is 24 times that
             # (no embedding, norms, output projection or optimizer) - extrapolated, not measured
             note = "EXTRAPOLATED: 24 x the oracle's time for one layer at 50 % keep (layers only), not a measured stack run"
             out["stack_gpt2m_train_sweep"]["cpu_oracle_extrapolated"] = {
-                "tokens_per_s": out["cpu_baseline"]["value"] / 24, "cores": out["cpu_baseline"]["cores"], "note": note}
-            c3 = dict(synth.CONFIGS["c3_llama1b_layer"])
-            cb3 = cpu_baseline(c3, c3["seed"], 1, 2, sample_B=4)
-            out["also"]["cpu_baseline"] = cb3
+                "tokens_per_s": cb[SECOND]["value"] / 24, "cores": cb["cores"], "note": note}
             out["stack_llama1b_train"]["cpu_oracle_extrapolated"] = {
-                "tokens_per_s": cb3["value"] / 24, "cores": cb3["cores"], "note": note}
+                "tokens_per_s": cb["value"] / 24, "cores": cb["cores"], "note": note}
     print(json.dumps(out))
 
 

@@ -60,6 +60,13 @@ const char* ecospa_last_error(const ecospa_ctx* ctx);
 int ecospa_profile_gemm(ecospa_ctx* ctx, int enable);
 int ecospa_profile_gemm_read(ecospa_ctx* ctx, int* launches, double* total_ms, double* total_flop);
 
+/* Measurement aid: what a plain kernel reaches on this GPU's memory, the ceiling the HBM-bound steps (score: read
+ * only; compaction: read and write) are priced against.  mode 0: `bytes` bytes of src are read once with 16-byte
+ * loads and nothing is written (dst: at least 4 writable bytes, left as they are for any ordinary buffer content);
+ * mode 1: src is copied to dst.  bytes a multiple of 16, pointers 16-byte aligned (dst in mode 0: 4-byte).
+ * Errors: ERR_NULL, ERR_SHAPE (mode, bytes), ERR_ALIGN. */
+int ecospa_hbm_probe(ecospa_ctx* ctx, const void* src, void* dst, size_t bytes, int mode);
+
 /* ------------------------------------------------------------------------------------------
  * Step 1 - per-dimension coupled importance score (paper Eq. 10; selection criterion Eq. 12).
  *
@@ -203,6 +210,16 @@ typedef struct {
 } ecospa_map_item;
 int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* items /*host*/, int n_items);
 
+/* Debugging aid for the caller's contract on index lists (Def. 1 keeps the remaining terms in their original order:
+ * ascending, in range).  Checks on the device, for each of `groups` lists (list g starts at idx + g*ld_idx), that its
+ * first k entries - or k_group[g] entries when k_group != NULL (device int32[groups]; a count outside [0, ld_idx] is
+ * itself an error) - lie in [0, n_units) and ascend strictly.  Unlike every other entry point it WAITS for the
+ * context's stream (one flag word is copied back), so it belongs in tests and debug builds, not in timed paths.
+ * Needs 4 bytes of workspace (its first word is clobbered).  Returns ECOSPA_ERR_INDEX if any list is bad.
+ * Errors before anything is launched: ERR_NULL; groups/n_units/ld_idx < 1 -> ERR_SHAPE; k outside
+ * [1, min(ld_idx, n_units)] with k_group == NULL -> ERR_K; no workspace -> ERR_WORKSPACE. */
+int ecospa_check_indices(ecospa_ctx* ctx, const int* idx, int groups, int ld_idx, int k, const int* k_group, int n_units);
+
 /* ------------------------------------------------------------------------------------------
  * Parameter update on the compact tensors (Alg. 1: "Update W", and the optimizer moments of a removed
  * row/column are removed with it - after ecospa_compact of the parameters, their master copies and both
@@ -269,7 +286,8 @@ int ecospa_rope_table_ragged(ecospa_ctx* ctx, const int* idx, int ld_idx, const 
  * Compact layouts (padding slots hold zeros, so results are exact):
  *   ATTN: w_qkv [((h + h_kv)*kp_qk + h_kv*kp_vo), d_model]: rows of W_q (head-major, kp_qk per head), then
  *         W_k, then W_v (kp_vo per head); b_qkv same length or NULL; w_o [d_model, h*kp_vo]; b_o.
- *         kp_qk, kp_vo are multiples of 16 and at most 128.  h_kv = key/value heads: h for multi-head
+ *         kp_qk, kp_vo are multiples of 16 and at most 64 (wider heads -> ERR_SHAPE, before anything is
+ *         launched).  h_kv = key/value heads: h for multi-head
  *         attention (0 means h); under grouped-query attention (Eq. 5) h_kv divides h and query head i
  *         attends with key/value head i / (h / h_kv).
  *   FFN:  w_1 [kp_ff, d_model] (SWIGLU: [2*kp_ff, d_model], gate rows then up rows); b_1 same
@@ -352,6 +370,10 @@ int ecospa_coupled_bwd(ecospa_ctx* ctx, const ecospa_block_desc* desc /*host*/, 
 int ecospa_contract(ecospa_ctx* ctx, int dtype, int M, int N, int K, const void* A, long long lda, int trans_a,
                     const void* B, long long ldb, int trans_b, void* C, long long ldc, const void* bias, int tile,
                     int splits);
+
+/* Workspace bytes ecospa_contract needs for this problem (host-only query): the fp32 partial sums of its K splits,
+ * `splits` as passed to ecospa_contract (0 = the library's choice); 0 when K is not split or on bad input. */
+size_t ecospa_contract_workspace_bytes(int dtype, int M, int N, int K, int splits);
 
 #ifdef __cplusplus
 }

@@ -28,6 +28,7 @@ EXPORTS = (
     "ecospa_coupled_bwd", "ecospa_profile_gemm", "ecospa_profile_gemm_read", "ecospa_contract",
     "ecospa_select_topk_batch", "ecospa_compact_batch", "ecospa_pair_fisher", "ecospa_select_theta",
     "ecospa_select_pairs", "ecospa_rope_table_ragged", "ecospa_adamw", "ecospa_transpose_batch",
+    "ecospa_check_indices", "ecospa_contract_workspace_bytes", "ecospa_hbm_probe",
 )
 
 
@@ -156,6 +157,12 @@ def load() -> C.CDLL:
     lib.ecospa_profile_gemm_read.restype = ci
     lib.ecospa_contract.argtypes = [vp, ci, ci, ci, ci, vp, ll, ci, vp, ll, ci, vp, ll, vp, ci, ci]
     lib.ecospa_contract.restype = ci
+    lib.ecospa_check_indices.argtypes = [vp, vp, ci, ci, ci, vp, ci]
+    lib.ecospa_check_indices.restype = ci
+    lib.ecospa_contract_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.ecospa_contract_workspace_bytes.restype = sz
+    lib.ecospa_hbm_probe.argtypes = [vp, vp, vp, sz, ci]
+    lib.ecospa_hbm_probe.restype = ci
     _lib = lib
     return lib
 
@@ -222,6 +229,11 @@ class Context:
                     "ecospa_profile_gemm_read")
         return n.value, ms.value, fl.value
 
+    def ecospa_hbm_probe(self, src: torch.Tensor, dst: torch.Tensor, copy: bool):
+        """Measurement aid: read src once (copy=False; dst is a small sink) or copy it to dst."""
+        nbytes = src.numel() * src.element_size()
+        self._check(self.lib.ecospa_hbm_probe(self.h, src.data_ptr(), dst.data_ptr(), nbytes, int(copy)), "ecospa_hbm_probe")
+
     def ecospa_contract(self, A: torch.Tensor, trans_a: bool, Bm: torch.Tensor, trans_b: bool,
                         bias: Optional[torch.Tensor] = None, tile: int = 0, splits: int = 0,
                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
@@ -231,7 +243,7 @@ class Context:
         assert K == K2
         if out is None:
             out = torch.empty((M, N), dtype=A.dtype, device=A.device)
-        self.reserve(64 * M * N * 4 if splits == 0 else (splits * M * N * 4 if splits > 1 else 0))     # fp32 partials of a split contraction
+        self.reserve(self.lib.ecospa_contract_workspace_bytes(dtype_code(A.dtype), M, N, K, splits))     # fp32 partials of a split contraction
         self._check(self.lib.ecospa_contract(self.h, dtype_code(A.dtype), M, N, K, A.data_ptr(), A.stride(0),
                                              int(trans_a), Bm.data_ptr(), Bm.stride(0), int(trans_b), out.data_ptr(),
                                              out.stride(0), _ptr(bias), tile, splits), "ecospa_contract")
@@ -309,6 +321,18 @@ class Context:
         groups, n_units = scores.shape
         assert scores.dtype == torch.float32 and scores.is_contiguous() and idx.dtype == torch.int32
         return SelectItem(scores.data_ptr(), groups, n_units, k, idx.data_ptr())
+
+    def ecospa_check_indices(self, idx: torch.Tensor, n_units: int, k_group: Optional[torch.Tensor] = None) -> bool:
+        """Debugging aid (waits for the stream): True if every list idx[g, :k] (k = idx.shape[1], or k_group[g]) is
+        strictly ascending with entries in [0, n_units)."""
+        assert idx.dtype == torch.int32 and idx.dim() == 2 and idx.is_contiguous()
+        self.reserve(256)
+        rc = self.lib.ecospa_check_indices(self.h, idx.data_ptr(), idx.shape[0], idx.shape[1], idx.shape[1], _ptr(k_group),
+                                           n_units)
+        if rc == ERR_INDEX:
+            return False
+        self._check(rc, "ecospa_check_indices")
+        return True
 
     # ---- step 3 ------------------------------------------------------------------------------
     @staticmethod

@@ -24,7 +24,8 @@ static int validate_block(const ecospa_block_desc* dp) {
     if ((d.w_1_t && d.ld_w1t < nh) || (d.w_2_t && d.ld_w2t < d.d_model)) return ECOSPA_ERR_SHAPE;
     if ((d.w_1_t && (d.ld_w1t % 8 || !aligned16(d.w_1_t))) || (d.w_2_t && (d.ld_w2t % 8 || !aligned16(d.w_2_t)))) return ECOSPA_ERR_ALIGN;
   } else {
-    if (d.h < 1 || d.kp_qk < 16 || d.kp_vo < 16 || d.kp_qk % 16 || d.kp_vo % 16 || d.kp_qk > 128 || d.kp_vo > 128)
+    // head widths: multiples of 16 up to 64 (the attention core is built for 32- and 64-wide padded heads)
+    if (d.h < 1 || d.kp_qk < 16 || d.kp_vo < 16 || d.kp_qk % 16 || d.kp_vo % 16 || d.kp_qk > 64 || d.kp_vo > 64)
       return ECOSPA_ERR_SHAPE;
     if (d.h_kv < 0 || d.h % attn_h_kv(d)) return ECOSPA_ERR_SHAPE;
     if (!d.w_qkv || !d.w_o) return ECOSPA_ERR_NULL;
@@ -265,6 +266,12 @@ extern "C" int ecospa_coupled_bwd(ecospa_ctx* ctx, const ecospa_block_desc* desc
 }
 
 // ---------------------------------------------------------------------------------------------
+extern "C" size_t ecospa_contract_workspace_bytes(int dtype, int M, int N, int K, int splits) {
+  if (!dtype_ok(dtype) || M < 1 || N < 1 || K < 1 || splits < 0 || splits > 64) return 0;
+  const int s = splits == 0 ? ecospa_gemm_splits(M, N, K) : splits;
+  return s > 1 ? static_cast<size_t>(s) * M * N * 4 : 0;
+}
+
 extern "C" int ecospa_contract(ecospa_ctx* ctx, int dtype, int M, int N, int K, const void* A, long long lda,
                                int trans_a, const void* B, long long ldb, int trans_b, void* C, long long ldc,
                                const void* bias, int tile, int splits) {

@@ -5,6 +5,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "../../include/ecospa.h"
 
 #define ECOSPA_PROF_MAX 4096   // GEMM launches that one profiling window can hold
@@ -37,6 +39,24 @@ static inline int hip_fail(ecospa_ctx* ctx, hipError_t e, const char* where) {
     hipError_t e__ = hipGetLastError();                         \
     if (e__ != hipSuccess) return hip_fail(ctx, e__, where);    \
   } while (0)
+
+// A kernel that needs more than 64 KB of dynamic LDS has its limit raised once per device before its first launch
+// there.  One object per kernel (a function-local static of the launch code); safe to use from several host threads:
+// the attribute call is idempotent, so two threads that race only set the same value twice.
+struct LdsAttrOnce {
+  std::atomic<unsigned long long> done{0};     // one bit per device ordinal (mod 64)
+  hipError_t ensure(const void* kern, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    done.fetch_or(bit, std::memory_order_release);
+    return hipSuccess;
+  }
+};
 
 // Carve 256-byte aligned pieces out of the caller's workspace.
 struct WsCarver {

@@ -421,6 +421,44 @@ extern "C" int ecospa_scatter(ecospa_ctx* ctx, const void* src, void* dst, int d
   return mapped_copy(ctx, src, dst, dtype, axis, groups, n, unit, k, kp, other_extent, ld_src, ld_dst, idx, 1);
 }
 
+// ---- debugging aid: the caller's contract on index lists, checked on the device -------------------------------
+__global__ __launch_bounds__(256) void idx_flag_clear_kernel(int* flag) { if (threadIdx.x == 0) *flag = 0; }
+__global__ __launch_bounds__(256) void idx_check_kernel(const int* __restrict__ idx, int groups, int ld_idx, int k,
+                                                        const int* __restrict__ k_group, int n_units, int* flag) {
+  const long long e = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
+  if (e >= static_cast<long long>(groups) * ld_idx) return;
+  const int g = static_cast<int>(e / ld_idx), i = static_cast<int>(e % ld_idx);
+  int kg = k;
+  if (k_group) {
+    kg = k_group[g];
+    if (kg < 0 || kg > ld_idx) { *flag = 1; return; }     // a count the list cannot hold
+  }
+  if (i >= kg) return;
+  const int v = idx[e];
+  const bool bad = v < 0 || v >= n_units || (i > 0 && idx[e - 1] >= v);
+  if (bad) *flag = 1;       // every writer stores the same value
+}
+
+extern "C" int ecospa_check_indices(ecospa_ctx* ctx, const int* idx, int groups, int ld_idx, int k, const int* k_group,
+                                    int n_units) {
+  if (!ctx || !idx) return ECOSPA_ERR_NULL;
+  if (groups < 1 || n_units < 1 || ld_idx < 1 || static_cast<long long>(groups) * ld_idx > (1ll << 31) - 1) return ECOSPA_ERR_SHAPE;
+  if (!k_group && (k < 1 || k > ld_idx || k > n_units)) return ECOSPA_ERR_K;
+  if (!ctx->ws || ctx->ws_bytes < sizeof(int)) return ECOSPA_ERR_WORKSPACE;
+  int* flag = static_cast<int*>(ctx->ws);
+  hipLaunchKernelGGL(idx_flag_clear_kernel, dim3(1), dim3(64), 0, ctx->stream, flag);
+  ECOSPA_CHECK_LAUNCH(ctx, "idx_flag_clear_kernel");
+  const long long tot = static_cast<long long>(groups) * ld_idx;
+  hipLaunchKernelGGL(idx_check_kernel, dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream, idx, groups,
+                     ld_idx, k, k_group, n_units, flag);
+  ECOSPA_CHECK_LAUNCH(ctx, "idx_check_kernel");
+  int host_flag = 0;
+  hipError_t e = hipMemcpyAsync(&host_flag, flag, sizeof(int), hipMemcpyDeviceToHost, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e, "ecospa_check_indices");
+  return host_flag ? ECOSPA_ERR_INDEX : ECOSPA_OK;
+}
+
 // ---- transposed copies of compact matrices ------------------------------------------------------------
 // The input-gradient contractions dY W read W with its contraction index slow; with a transposed copy of
 // the (small, compact) matrix beside it they become x W^T contractions like the forward ones, which the

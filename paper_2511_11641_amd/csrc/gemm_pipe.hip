@@ -281,12 +281,10 @@ static hipError_t launch_pipe(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
 #define LAUNCH_TT(TA, TB)                                                                                      \
   do {                                                                                                         \
     auto kern = gemm_bf16_pipe_kernel<BM, BN, BK, NS, WGM, WGN, WPE, TA, TB>;                                  \
-    static bool attr_set = false;                                                                              \
-    if (!attr_set && lds_bytes > 64 * 1024) {                                                                  \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)); \
+    static LdsAttrOnce attr_once;                                                                              \
+    if (lds_bytes > 64 * 1024) {                                                                               \
+      hipError_t e = attr_once.ensure(reinterpret_cast<const void*>(kern), static_cast<int>(lds_bytes));       \
       if (e != hipSuccess) return e;                                                                           \
-      attr_set = true;                                                                                         \
     }                                                                                                          \
     hipLaunchKernelGGL(kern, grid, block, lds_bytes, ctx->stream, d, tn, k_chunk);                             \
   } while (0)

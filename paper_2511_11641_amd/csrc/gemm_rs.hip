@@ -292,12 +292,10 @@ hipError_t gemm_rs_launch(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
 #define RS_LAUNCH(TA, TB)                                                                                      \
   do {                                                                                                         \
     auto kern = gemm_bf16_rs_kernel<TA, TB>;                                                                   \
-    static bool attr_set = false;                                                                              \
-    if (!attr_set) {                                                                                           \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);               \
+    static LdsAttrOnce attr_once;                                                                              \
+    {                                                                                                          \
+      hipError_t e = attr_once.ensure(reinterpret_cast<const void*>(kern), lds_bytes);                         \
       if (e != hipSuccess) return e;                                                                           \
-      attr_set = true;                                                                                         \
     }                                                                                                          \
     hipLaunchKernelGGL(kern, grid, block, lds_bytes, ctx->stream, d, tn, k_chunk);                             \
   } while (0)

@@ -32,27 +32,35 @@ class FfnBlock:
     def score(self) -> torch.Tensor:
         return self.ctx.ecospa_coupled_score([self.pair()])[0]
 
-    def compact(self, idx: torch.Tensor, defer: bool = False, k_group: Optional[torch.Tensor] = None):
+    def compact(self, idx: torch.Tensor, defer: bool = False, k_group: Optional[torch.Tensor] = None,
+                k_max: Optional[int] = None):
         """Gather the kept rows/columns named by idx[1, k] into the padded compact layout (one launch).
         With defer=True the gather descriptors are returned instead, for a larger batch.  With k_group
         (int32[1] on the device, the kept count of the cumulative-threshold rule) only the first k_group[0]
-        entries of idx[1, n] count (read back once here to size the compact matrices)."""
+        entries of idx[1, n] count; the count stays on the device, so the caller names an upper bound k_max
+        (>= k_group[0]) that sizes the compact matrices - units beyond it would be dropped.
+        A call that changes the padded width after :meth:`alloc` allocates the block's buffers again."""
         c = self.ctx
-        k = idx.shape[1] if k_group is None else int(k_group.item())
+        if k_group is not None and k_max is None:
+            raise ValueError("ragged compaction needs k_max: the kept count lives on the device")
+        k = idx.shape[1] if k_group is None else int(k_max)
         self.idx, self.k, self.k_group = idx, k, k_group
         # padded width: a multiple of the contraction kernels' slab depth (64) once that costs little, so that the
         # contractions over the kept units (the second FFN matrix, the input gradient) can take the pipelined kernel
         self.kp = kp = B.round_up(k, 64 if k >= 512 else 16)
         nh = 2 * kp if self.gated else kp
         dt, dev = self.w1.dtype, self.w1.device
-        if getattr(self, "w1_c", None) is None or self.w1_c.shape[0] != nh:     # buffers are reused across re-compactions
+        resized = getattr(self, "w1_c", None) is None or self.w1_c.shape[0] != nh
+        if resized:     # buffers are reused across re-compactions of the same width
             self.w1_c = torch.empty((nh, self.d), dtype=dt, device=dev)
             self.b1_c = None if self.b1 is None else torch.zeros((nh,), dtype=dt, device=dev)
             self.w2_c = torch.empty((self.d, kp), dtype=dt, device=dev)
+            if self.transposed:
+                self.w1_t = torch.empty((self.d, nh), dtype=dt, device=dev)
+                self.w2_t = torch.empty((kp, self.d), dtype=dt, device=dev)
+            if getattr(self, "_alloc_shape", None) is not None:     # descriptors, saved activations, gradients follow the new width
+                self.alloc(*self._alloc_shape)
         items = self._map_items(0)
-        if self.transposed and (getattr(self, "w1_t", None) is None or self.w1_t.shape[1] != nh):
-            self.w1_t = torch.empty((self.d, nh), dtype=dt, device=dev)
-            self.w2_t = torch.empty((kp, self.d), dtype=dt, device=dev)
         if defer:
             return items
         c.ecospa_compact_batch(items)
@@ -98,6 +106,7 @@ class FfnBlock:
     def alloc(self, Bsz: int, L: int):
         T, dt, dev = Bsz * L, self.w1.dtype, self.w1.device
         nh = 2 * self.kp if self.gated else self.kp
+        self._alloc_shape = (Bsz, L)
         self.hpre = torch.empty((T, nh), dtype=dt, device=dev)
         self.act_buf = torch.empty((T, self.kp), dtype=dt, device=dev)
         self.saved = B.Saved(None, None, None, self.hpre.data_ptr(), self.act_buf.data_ptr())
@@ -150,34 +159,44 @@ class AttnBlock:
         return self.ctx.ecospa_coupled_score(self.pairs())
 
     def compact(self, idx_qk: torch.Tensor, idx_vo: torch.Tensor, defer: bool = False,
-                k_qk_group: Optional[torch.Tensor] = None, k_vo_group: Optional[torch.Tensor] = None):
+                k_qk_group: Optional[torch.Tensor] = None, k_vo_group: Optional[torch.Tensor] = None,
+                k_qk_max: Optional[int] = None, k_vo_max: Optional[int] = None):
         """Gather the kept dimensions.  With k_qk_group / k_vo_group (int32[h] on the device, the kept counts of the
         cumulative-threshold rule) every head keeps a count of its own: idx_* are then [h, n_units] lists whose first
-        k_*_group[g] entries count, and all heads are padded with zeros to the largest count (read back once here)."""
+        k_*_group[g] entries count, and all heads are padded with zeros to k_qk_max units / k_vo_max dimensions - upper
+        bounds on the counts that the caller names (the counts stay on the device; units beyond the bound would be dropped).
+        A call that changes a padded width after :meth:`alloc` allocates the block's buffers and tables again."""
         c, h, hk, u = self.ctx, self.h, self.h_kv, self.unit
+        if (k_qk_group is not None and k_qk_max is None) or (k_vo_group is not None and k_vo_max is None):
+            raise ValueError("ragged compaction needs k_qk_max / k_vo_max: the kept counts live on the device")
         self.idx_qk, self.idx_vo = idx_qk, idx_vo
         self.k_qk_group, self.k_vo_group = k_qk_group, k_vo_group
-        self.k_qk_units = idx_qk.shape[1] if k_qk_group is None else int(k_qk_group.max().item())
-        self.k_vo = idx_vo.shape[1] if k_vo_group is None else int(k_vo_group.max().item())
+        self.k_qk_units = idx_qk.shape[1] if k_qk_group is None else int(k_qk_max)
+        self.k_vo = idx_vo.shape[1] if k_vo_group is None else int(k_vo_max)
         self.kp_qk = B.round_up(self.k_qk_units * u, 16)
         self.kp_vo = B.round_up(self.k_vo, 16)
         # compact layout: the h query heads, then the h_kv key heads, then the h_kv value heads; W_o has h heads
         nq, nk, nv, no = h * self.kp_qk, hk * self.kp_qk, hk * self.kp_vo, h * self.kp_vo
         self.nq, self.nk = nq, nk
         dt, dev = self.wq.dtype, self.wq.device
-        if getattr(self, "wqkv_c", None) is None or self.wqkv_c.shape[0] != nq + nk + nv:
+        resized = (getattr(self, "wqkv_c", None) is None or self.wqkv_c.shape[0] != nq + nk + nv
+                   or self.wo_c.shape[1] != no)
+        if resized:
             self.wqkv_c = torch.empty((nq + nk + nv, self.d), dtype=dt, device=dev)
             self.bqkv_c = None if self.bq is None else torch.empty((nq + nk + nv,), dtype=dt, device=dev)
             self.wo_c = torch.empty((self.d, no), dtype=dt, device=dev)
+            if self.transposed:
+                self.wqkv_t = torch.empty((self.d, nq + nk + nv), dtype=dt, device=dev)
+                self.wo_t = torch.empty((no, self.d), dtype=dt, device=dev)
         items = self._map_items(0)
-        if self.transposed and (getattr(self, "wqkv_t", None) is None or self.wqkv_t.shape[1] != nq + nk + nv):
-            self.wqkv_t = torch.empty((self.d, nq + nk + nv), dtype=dt, device=dev)
-            self.wo_t = torch.empty((no, self.d), dtype=dt, device=dev)
         if not defer:
             c.ecospa_compact_batch(items)
             self.refresh_transposed()
-        if self.rope and getattr(self, "cos", None) is not None:     # kept blocks changed: new frequencies
-            self._rope_table(self._L, out=(self.cos, self.sin))
+        if getattr(self, "_alloc_shape", None) is not None:
+            if resized:       # descriptors, saved activations, gradients and the rotary tables follow the new widths
+                self.alloc(*self._alloc_shape)
+            elif self.rope:   # same widths, but the kept blocks may have changed: new frequencies in place
+                self._rope_table(self._L, out=(self.cos, self.sin))
         return items if defer else self
 
     def _map_items(self, scatter: int):
@@ -227,6 +246,7 @@ class AttnBlock:
         nqkv, nv = self.wqkv_c.shape[0], h * self.kp_vo
         self.cos = self.sin = None
         self._L = L
+        self._alloc_shape = (Bsz, L)
         if self.rope:
             self.cos, self.sin = self._rope_table(L)
         d = B.BlockDesc()

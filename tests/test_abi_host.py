@@ -137,3 +137,46 @@ def test_block_validation(lib, ctx):
     a.h, a.kp_qk, a.kp_vo, a.scale, a.w_qkv, a.w_o, a.ld_wqkv, a.ld_wo = 2, 16, 24, 0.125, 256, 512, 64, 64
     assert lib.ecospa_coupled_fwd(ctx, C.byref(a), 1024, 2048, None) == B.ERR_SHAPE   # kp_vo % 16
     assert lib.ecospa_set_workspace(ctx, 257, 1024) == B.ERR_ALIGN
+
+
+def test_attention_heads_wider_than_64_are_rejected_before_any_launch(lib, ctx):
+    """The attention core is built for padded head widths up to 64: a wider head is a validation error of the
+    descriptor itself (workspace query included), not something found after the projections have been launched."""
+    a = B.BlockDesc()
+    a.block, a.dtype, a.B, a.L, a.d_model = B.BLOCK_ATTN, B.BF16, 2, 16, 256
+    a.h, a.kp_qk, a.kp_vo, a.scale, a.w_qkv, a.w_o, a.ld_wqkv, a.ld_wo = 2, 32, 32, 0.125, 256, 512, 256, 160
+    assert lib.ecospa_block_workspace_bytes(C.byref(a)) > 0
+    for kq, kv in ((80, 32), (32, 80), (128, 128), (96, 64)):
+        b = B.BlockDesc.from_buffer_copy(a)
+        b.kp_qk, b.kp_vo = kq, kv
+        assert lib.ecospa_block_workspace_bytes(C.byref(b)) == 0
+        # no workspace is attached and the data pointers are bogus: ERR_SHAPE must come first, from validation alone
+        assert lib.ecospa_coupled_fwd(ctx, C.byref(b), 1024, 2048, None) == B.ERR_SHAPE
+        sv, gr = B.Saved(4096, 8192, 12288, None, None), B.Grads()
+        assert lib.ecospa_coupled_bwd(ctx, C.byref(b), 1024, 2048, C.byref(sv), 4096, C.byref(gr)) == B.ERR_SHAPE
+    b = B.BlockDesc.from_buffer_copy(a)
+    b.kp_qk, b.kp_vo = 64, 48
+    assert lib.ecospa_block_workspace_bytes(C.byref(b)) > 0
+
+
+def test_check_indices_validation(lib, ctx):
+    f = lib.ecospa_check_indices
+    assert f(None, 256, 1, 8, 4, None, 8) == B.ERR_NULL
+    assert f(ctx, None, 1, 8, 4, None, 8) == B.ERR_NULL
+    assert f(ctx, 256, 0, 8, 4, None, 8) == B.ERR_SHAPE
+    assert f(ctx, 256, 1, 0, 4, None, 8) == B.ERR_SHAPE
+    assert f(ctx, 256, 1, 8, 0, None, 8) == B.ERR_K
+    assert f(ctx, 256, 1, 8, 9, None, 16) == B.ERR_K          # more entries than the list holds
+    assert f(ctx, 256, 1, 8, 8, None, 4) == B.ERR_K           # more entries than there are units
+    assert f(ctx, 256, 1, 8, 4, None, 8) == B.ERR_WORKSPACE   # needs a flag word; nothing was launched
+
+
+def test_contract_workspace_query(lib):
+    q = lib.ecospa_contract_workspace_bytes
+    assert q(B.BF16, 1024, 2048, 8192, 4) == 4 * 1024 * 2048 * 4
+    assert q(B.BF16, 1024, 2048, 8192, 1) == 0
+    own = q(B.BF16, 1024, 2048, 8192, 0)
+    assert own % (1024 * 2048 * 4) == 0 and own <= 8 * 1024 * 2048 * 4
+    # an output as large as a vocabulary projection: the library's own choice never reserves tens of gigabytes
+    assert q(B.BF16, 8192, 32000, 2048, 0) <= 8 * 8192 * 32000 * 4
+    assert q(7, 8, 8, 8, 0) == 0 and q(B.BF16, 0, 8, 8, 0) == 0 and q(B.BF16, 8, 8, 8, 65) == 0

@@ -175,7 +175,7 @@ def test_attention_block_with_a_kept_count_per_head(ctx, rope, theta):
     assert np.array_equal(kq_d.cpu().numpy(), kq) and np.array_equal(iq_d.cpu().numpy(), iq)
     assert np.array_equal(kv_d.cpu().numpy(), kv) and np.array_equal(iv_d.cpu().numpy(), iv)
     assert kq.min() < kq.max() and kv.min() < kv.max(), "the case must be ragged"
-    blk.compact(iq_d, iv_d, k_qk_group=kq_d, k_vo_group=kv_d).alloc(Bsz, L)
+    blk.compact(iq_d, iv_d, k_qk_group=kq_d, k_vo_group=kv_d, k_qk_max=int(kq.max()), k_vo_max=int(kv.max())).alloc(Bsz, L)
     assert blk.kp_qk >= kq.max() * unit and blk.kp_vo >= kv.max()
     y = blk.fwd(g["x"])
     dx = blk.bwd(g["x"], g["dy"])
@@ -233,7 +233,7 @@ def test_ffn_block_with_the_threshold_rule(ctx, gated):
     idx, k = O.select_theta(s.cpu().numpy(), theta)
     assert np.array_equal(k_d.cpu().numpy(), k) and np.array_equal(idx_d.cpu().numpy(), idx)
     assert 1 < k[0] < n
-    blk.compact(idx_d, k_group=k_d).alloc(1, T)
+    blk.compact(idx_d, k_group=k_d, k_max=int(k[0])).alloc(1, T)
     y = blk.fwd(g["x"])
     dx = blk.bwd(g["x"], g["dy"])
     torch.cuda.synchronize()
@@ -248,3 +248,68 @@ def test_ffn_block_with_the_threshold_rule(ctx, gated):
     assert_close(dx, go["dx"], dtype, "dx")
     assert_close(blk.dw2_c[:, :k[0]], go["dw2"], dtype, "dW_2")
     assert not host(blk.dw2_c[:, k[0]:]).any()
+
+
+# ---- re-compaction after alloc(): the kept counts of the threshold rule change from one estimate to the next -------
+def test_blocks_follow_a_change_of_width_between_compactions(ctx):
+    """Under the cumulative-threshold rule the kept counts differ at every estimate, so the padded widths of a block
+    change while its buffers already exist: wider, then narrower than the first time, forward and backward each time
+    against the oracle at the new width."""
+    Bsz, L, d, h, dh, n, dtype = 2, 96, 128, 4, 64, 640, "bf16"
+    ta = synth.attn_layer(60, Bsz, L, d, h, dh, dtype=dtype, structure="pretrained", bias=False)
+    tf = synth.ffn_layer(61, Bsz * L, d, n, gated=False, dtype=dtype, structure="pretrained", bias=True)
+    ga = {nm: dev(a, dtype) for nm, a in ta.items()}
+    gf = {nm: dev(a, dtype) for nm, a in tf.items()}
+    attn = AttnBlock(ctx, ga["wq"], ga["wk"], ga["wv"], ga["wo"], None, None, None, None, h, dh, rope=True, causal=True, transposed=True)
+    ffn = FfnBlock(ctx, gf["w1"], gf["b1"], gf["w2"], gf["b2"], B.ACT_GELU_ERF, transposed=True)
+    s_qk, s_vo = attn.score()
+    s_ff = ffn.score()
+    scale = dh ** -0.5
+    first = True
+    widths = []
+    for theta in (0.7, 0.95, 0.4):       # 0.95 keeps more (wider buffers), 0.4 fewer (narrower) than the first estimate
+        iq_d, kq_d = ctx.ecospa_select_theta(s_qk, theta)
+        iv_d, kv_d = ctx.ecospa_select_theta(s_vo, theta)
+        if_d, kf_d = ctx.ecospa_select_theta(s_ff, theta)
+        iq, kq = O.select_theta(s_qk.cpu().numpy(), theta)
+        iv, kv = O.select_theta(s_vo.cpu().numpy(), theta)
+        iff, kf = O.select_theta(s_ff.cpu().numpy(), theta)
+        attn.compact(iq_d, iv_d, k_qk_group=kq_d, k_vo_group=kv_d, k_qk_max=int(kq.max()), k_vo_max=int(kv.max()))
+        ffn.compact(if_d, k_group=kf_d, k_max=int(kf[0]))
+        if first:
+            attn.alloc(Bsz, L)
+            ffn.alloc(1, Bsz * L)
+            first = False
+        widths.append((attn.kp_qk, attn.kp_vo, ffn.kp))
+        # every buffer follows the widths of this compaction
+        assert attn.qkv.shape[1] == attn.wqkv_c.shape[0] == 2 * h * attn.kp_qk + h * attn.kp_vo
+        assert attn.cos.shape == (h, L, attn.kp_qk // 2) and attn.dwo_c.shape == attn.wo_c.shape == (d, h * attn.kp_vo)
+        assert ffn.hpre.shape[1] == ffn.kp == ffn.w2_c.shape[1] == ffn.dw2_c.shape[1] and ffn._desc.kp_ff == ffn.kp
+        assert attn._desc.kp_qk == attn.kp_qk and attn._desc.w_qkv == attn.wqkv_c.data_ptr()
+        y = attn.fwd(ga["x"])
+        dx = attn.bwd(ga["x"], ga["dy"])
+        y2 = ffn.fwd(gf["x"])
+        dx2 = ffn.bwd(gf["x"], gf["dy"])
+        torch.cuda.synchronize()
+        yo, dxo = np.zeros((Bsz * L, d)), np.zeros((Bsz * L, d))
+        for i in range(h):          # one head at a time at its own width
+            rq, rv = iq[i:i + 1, :kq[i]], iv[i:i + 1, :kv[i]]
+            sl = slice(i * dh, (i + 1) * dh)
+            wq, wk = (O.compact(ta[nm][sl], rq, 0, dh, 2)[None] for nm in ("wq", "wk"))
+            wv, wo = O.compact(ta["wv"][sl], rv, 0, dh)[None], O.compact(ta["wo"][:, sl], rv, 1, dh)[None]
+            ang = O.rope_angles(rq, L, dh)
+            yi, sv = O.attn_fwd(ta["x"], wq, wk, wv, wo, Bsz, L, scale, True, angles=ang)
+            yo += yi
+            dxo += O.attn_bwd(ta["x"], ta["dy"], wq, wk, wv, wo, Bsz, L, scale, sv, angles=ang)["dx"]
+        assert_close(y, yo, dtype, f"attention y at theta {theta}")
+        assert_close(dx, dxo, dtype, f"attention dx at theta {theta}")
+        sel = iff[:, :kf[0]]
+        w1, b1, w2 = O.compact(tf["w1"], sel, 0, n), O.compact(tf["b1"], sel, 0, n), O.compact(tf["w2"], sel, 1, n)
+        yo, sv = O.ffn_fwd(tf["x"], w1, b1, w2, tf["b2"], O.ACT_GELU_ERF)
+        go = O.ffn_bwd(tf["x"], tf["dy"], w1, w2, O.ACT_GELU_ERF, sv)
+        assert_close(y2, yo, dtype, f"ffn y at theta {theta}")
+        assert_close(dx2, go["dx"], dtype, f"ffn dx at theta {theta}")
+        assert_close(ffn.dw1_c[:kf[0]], go["dw1"], dtype, f"ffn dW_1 at theta {theta}")
+        assert not host(ffn.dw1_c[kf[0]:]).any()
+    assert widths[1] != widths[0] and widths[2] != widths[1], widths      # the case did change widths both ways
+    assert widths[1][2] > widths[0][2] > widths[2][2]

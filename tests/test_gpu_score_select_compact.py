@@ -30,8 +30,6 @@ FFN_SHAPES = [  # (n, d, gated)
 @pytest.mark.parametrize("structure", ["scratch", "pretrained"])
 @pytest.mark.parametrize("n,d,gated", FFN_SHAPES)
 def test_score_ffn(ctx, n, d, gated, structure, dtype):
-    if n >= 4096 and (dtype == "f32" or structure == "scratch"):
-        pytest.skip("large shapes once")
     t = synth.ffn_layer(3, 4, d, n, gated=gated, dtype=dtype, structure=structure, bias=False)
     kind = O.PAIR_FFN_GATED if gated else O.PAIR_FFN
     want = O.coupled_score(kind, t["w1"], t["w2"], 1, n, w1b=t.get("w1b"))
@@ -221,3 +219,29 @@ def test_transposed_copies_are_exact(ctx, rows, cols, pad, dtype):
         it.ld_dst = rows - 1
         ctx.ecospa_transpose_batch([it])
     assert e.value.code == B.ERR_SHAPE
+
+
+# ---- the debugging aid for the caller's contract on index lists ----------------------------------------
+def test_check_indices_accepts_what_select_writes_and_names_bad_lists(ctx):
+    s = torch.rand((6, 100), device="cuda")
+    idx = ctx.ecospa_select_topk(s, 37)
+    assert ctx.ecospa_check_indices(idx, 100)
+    bad = idx.clone()
+    bad[3, 10] = bad[3, 9]                      # not strictly ascending
+    assert not ctx.ecospa_check_indices(bad, 100)
+    bad = idx.clone()
+    bad[5, 36] = 100                            # out of range
+    assert not ctx.ecospa_check_indices(bad, 100)
+    bad = idx.clone()
+    bad[0, 0] = -1
+    assert not ctx.ecospa_check_indices(bad, 100)
+    # ragged lists: only the first k_group[g] entries count, what lies behind them may be anything (-1 padding)
+    idx_t, k_t = ctx.ecospa_select_theta(s / s.sum(dim=1, keepdim=True), 0.8)
+    assert ctx.ecospa_check_indices(idx_t, 100, k_group=k_t)
+    k_bad = k_t.clone()
+    k_bad[2] = 101                              # a count the list cannot hold
+    assert not ctx.ecospa_check_indices(idx_t, 100, k_group=k_bad)
+    k_bad = k_t.clone()
+    k_bad[1] = min(int(k_t[1]) + 1, 100)        # reaches into the -1 padding (unless the row kept everything)
+    if int(k_t[1]) < 100:
+        assert not ctx.ecospa_check_indices(idx_t, 100, k_group=k_bad)

@@ -23,9 +23,37 @@ def host(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
+ROW_FACTOR = 8.0      # a single row or column may be this many times worse than the whole tensor's bound
+ELEM_FACTOR = 16.0    # ... and a single element this many, relative to the tensor's RMS element
+
+
 def assert_close(got, want, dtype, what=""):
-    err = O.rel_fro(host(got) if isinstance(got, torch.Tensor) else got, want)
-    assert err <= TOL[dtype], f"{what}: rel Frobenius error {err:.3e} > {TOL[dtype]:.0e}"
+    """The stated tolerance is the relative Frobenius error of the whole tensor.  A norm over everything would let
+    one bad row, one bad column (a tile edge) or one garbage element of a large output through, so three local bounds
+    stand beside it: every row's and every column's error against the RMS row / column norm of the expected tensor
+    (ROW_FACTOR x tolerance), and every element's error against the RMS element (ELEM_FACTOR x tolerance)."""
+    g = host(got) if isinstance(got, torch.Tensor) else np.asarray(got, dtype=np.float64)
+    w = np.asarray(want, dtype=np.float64)
+    assert g.shape == w.shape, f"{what}: shape {g.shape} != {w.shape}"
+    tol = TOL[dtype]
+    err = O.rel_fro(g, w)
+    assert err <= tol, f"{what}: rel Frobenius error {err:.3e} > {tol:.0e}"
+    fro = float(np.sqrt((w * w).sum()))
+    if fro > 0.0 and w.size > 1:
+        diff = g - w
+        rms = fro / np.sqrt(w.size)
+        worst = float(np.abs(diff).max())
+        assert worst <= ELEM_FACTOR * tol * rms, \
+            f"{what}: element error {worst:.3e} > {ELEM_FACTOR * tol:.1e} x RMS element {rms:.3e} at {np.unravel_index(np.abs(diff).argmax(), w.shape)}"
+        if w.ndim >= 2:
+            d2 = diff.reshape(-1, w.shape[-1])
+            rows, cols = d2.shape
+            row_err = np.sqrt((d2 * d2).sum(axis=1)) / (fro / np.sqrt(rows))
+            col_err = np.sqrt((d2 * d2).sum(axis=0)) / (fro / np.sqrt(cols))
+            assert row_err.max() <= ROW_FACTOR * tol, \
+                f"{what}: row {int(row_err.argmax())} error {row_err.max():.3e} > {ROW_FACTOR * tol:.1e} (of the RMS row norm)"
+            assert col_err.max() <= ROW_FACTOR * tol, \
+                f"{what}: column {int(col_err.argmax())} error {col_err.max():.3e} > {ROW_FACTOR * tol:.1e} (of the RMS column norm)"
     return err
 
 
