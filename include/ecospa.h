@@ -360,8 +360,10 @@ int ecospa_coupled_bwd(ecospa_ctx* ctx, const ecospa_block_desc* desc /*host*/, 
  * tiles staged through registers, K-slow operands transposed on the way to LDS; 3 / 4 = the same with
  * K-slow operands read by transposing LDS reads; 10..19 and 21 = configurations 0..9 and 10 of the
  * software-pipelined kernel (direct global->LDS ring; needs K and K/splits to be multiples of its slab
- * depth, else the library falls back to its own choice); 20 = the register-prefetch kernel for long
- * contractions with a K-slow B.
+ * depth, else the library falls back to its own choice); 20 = the register-prefetch kernel (256x256 tiles) for long
+ * contractions with a K-slow B; 30..38 = the same kernel for dY^T X (both operands K-slow) with tiles 256x256,
+ * 192x256, 256x192, 128x256, 256x128, 192x192, 128x192, 192x128, 128x128 (needs K and the K range of a split to be
+ * multiples of 64).
  * splits: 0 = library's choice, otherwise the number of K splits (partials come from the
  * workspace and are added in a fixed order).
  * bf16 needs 16-byte aligned pointers, N % 8 == 0, leading dimensions % 8 == 0 and the
@@ -370,6 +372,14 @@ int ecospa_coupled_bwd(ecospa_ctx* ctx, const ecospa_block_desc* desc /*host*/, 
 int ecospa_contract(ecospa_ctx* ctx, int dtype, int M, int N, int K, const void* A, long long lda, int trans_a,
                     const void* B, long long ldb, int trans_b, void* C, long long ldc, const void* bias, int tile,
                     int splits);
+
+/* The dY^T X form of ecospa_contract (bf16, both operands K-slow: A[K, M], B[K, N]) together with the column sums of
+ * its A operand, colsum[m] = sum_k A(m, k) (float[M]) - the bias gradient that a backward pass gets from the weight-
+ * gradient contraction that reads dY anyway.  Exposed for tests of every tile shape (tile: 0, 1..4, 20, 30..38 as in
+ * ecospa_contract).  Workspace: splits * M floats (256-byte rounded) plus the partial products of a split contraction.
+ * Errors as ecospa_contract. */
+int ecospa_contract_colsum(ecospa_ctx* ctx, int M, int N, int K, const void* A, long long lda, const void* B,
+                           long long ldb, void* C, long long ldc, float* colsum, int tile, int splits);
 
 /* Workspace bytes ecospa_contract needs for this problem (host-only query): the fp32 partial sums of its K splits,
  * `splits` as passed to ecospa_contract (0 = the library's choice); 0 when K is not split or on bad input. */

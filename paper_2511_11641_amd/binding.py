@@ -28,7 +28,7 @@ EXPORTS = (
     "ecospa_coupled_bwd", "ecospa_profile_gemm", "ecospa_profile_gemm_read", "ecospa_contract",
     "ecospa_select_topk_batch", "ecospa_compact_batch", "ecospa_pair_fisher", "ecospa_select_theta",
     "ecospa_select_pairs", "ecospa_rope_table_ragged", "ecospa_adamw", "ecospa_transpose_batch",
-    "ecospa_check_indices", "ecospa_contract_workspace_bytes", "ecospa_hbm_probe",
+    "ecospa_check_indices", "ecospa_contract_workspace_bytes", "ecospa_hbm_probe", "ecospa_contract_colsum",
 )
 
 
@@ -161,6 +161,8 @@ def load() -> C.CDLL:
     lib.ecospa_check_indices.restype = ci
     lib.ecospa_contract_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.ecospa_contract_workspace_bytes.restype = sz
+    lib.ecospa_contract_colsum.argtypes = [vp, ci, ci, ci, vp, ll, vp, ll, vp, ll, vp, ci, ci]
+    lib.ecospa_contract_colsum.restype = ci
     lib.ecospa_hbm_probe.argtypes = [vp, vp, vp, sz, ci]
     lib.ecospa_hbm_probe.restype = ci
     _lib = lib
@@ -248,6 +250,21 @@ class Context:
                                              int(trans_a), Bm.data_ptr(), Bm.stride(0), int(trans_b), out.data_ptr(),
                                              out.stride(0), _ptr(bias), tile, splits), "ecospa_contract")
         return out
+
+    def ecospa_contract_colsum(self, A: torch.Tensor, Bm: torch.Tensor, tile: int = 0, splits: int = 0):
+        """dY^T X form: A[K, M], Bm[K, N] (bf16) -> (C[M, N] bf16, colsum[M] fp32 = column sums of A)."""
+        K, M = A.shape
+        K2, N = Bm.shape
+        assert K == K2 and A.dtype == torch.bfloat16
+        out = torch.empty((M, N), dtype=A.dtype, device=A.device)
+        cs = torch.empty((M,), dtype=torch.float32, device=A.device)
+        sp = max(splits, 1) if splits else 8
+        rows = sp * ((N + 127) // 128)          # at most one row of partial sums per split and 128-wide tile column
+        self.reserve(round_up(rows * M * 4, 256) + self.lib.ecospa_contract_workspace_bytes(BF16, M, N, K, splits) + 256)
+        self._check(self.lib.ecospa_contract_colsum(self.h, M, N, K, A.data_ptr(), A.stride(0), Bm.data_ptr(), Bm.stride(0),
+                                                    out.data_ptr(), out.stride(0), cs.data_ptr(), tile, splits),
+                    "ecospa_contract_colsum")
+        return out, cs
 
     # ---- step 1 ------------------------------------------------------------------------------
     @staticmethod

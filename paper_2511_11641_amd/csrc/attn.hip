@@ -878,9 +878,9 @@ static int attn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const
   memset(&aux, 0, sizeof(aux));
   if (gr.dw_o && go.splits > 1) aux.reduce[aux.n_reduce++] = go;
   if (gr.dw_qkv && gq.splits > 1) aux.reduce[aux.n_reduce++] = gq;
-  if (gr.db_o) aux.colsum[aux.n_colsum++] = go.colsum ? AuxColsum{go.colsum, dm, go.splits, dm, ECOSPA_F32, gr.db_o, d.dtype}
+  if (gr.db_o) aux.colsum[aux.n_colsum++] = go.colsum ? AuxColsum{go.colsum, dm, ecospa_gemm_colsum_rows(go), dm, ECOSPA_F32, gr.db_o, d.dtype}
                                                        : AuxColsum{dy, dm, T, dm, d.dtype, gr.db_o, 0};
-  if (gr.db_qkv) aux.colsum[aux.n_colsum++] = gq.colsum ? AuxColsum{gq.colsum, nqkv, gq.splits, nqkv, ECOSPA_F32, gr.db_qkv, d.dtype}
+  if (gr.db_qkv) aux.colsum[aux.n_colsum++] = gq.colsum ? AuxColsum{gq.colsum, nqkv, ecospa_gemm_colsum_rows(gq), nqkv, ECOSPA_F32, gr.db_qkv, d.dtype}
                                                          : AuxColsum{w.dqkv, nqkv, T, nqkv, d.dtype, gr.db_qkv, 0};
   return ecospa_aux_launch(ctx, aux);
 }

@@ -18,7 +18,7 @@ struct BlockWs {           // pieces carved from the caller's workspace
   // shared
   float* partial;          // split-K partials of the first weight-gradient contraction of a backward pass
   float* partial2;         // ... and of the second (both are reduced by the batched tail launch)
-  float* colsum;           // [splits][M] operand column sums of the first weight-gradient contraction (bias gradient)
+  float* colsum;           // [rows][M] partial operand column sums of the first weight-gradient contraction (bias gradient)
   float* colsum2;          // ... and of the second
   float* partial_x;        // split-K partials of a forward or input-gradient contraction (few tokens only), one at a time
   size_t total;
@@ -33,6 +33,8 @@ static inline size_t block_token_split_bytes(int M, int N, int K) {
   const int s = ecospa_gemm_token_splits(M, N, K);
   return s > 1 ? static_cast<size_t>(s) * M * N * 4 : 0;
 }
+
+int block_colsum_rows(int dtype, int M, int N, int K);
 
 // Lay out the workspace for a validated descriptor; base may be NULL to only measure.
 void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w);

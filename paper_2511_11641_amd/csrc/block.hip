@@ -41,6 +41,15 @@ static int validate_block(const ecospa_block_desc* dp) {
 
 static size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
 
+// Rows of partial column sums that the weight-gradient contraction dY^T X of this shape writes (library's own plan).
+int block_colsum_rows(int dtype, int M, int N, int K) {
+  GemmDesc g;
+  memset(&g, 0, sizeof(g));
+  g.dtype = dtype; g.M = M; g.N = N; g.K = K; g.lda = M; g.ldb = N; g.trans_a = g.trans_b = 1;
+  g.splits = ecospa_gemm_splits(M, N, K);
+  return ecospa_gemm_colsum_rows(g);
+}
+
 void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
   memset(&w, 0, sizeof(w));
   WsCarver c(base ? base : reinterpret_cast<void*>(256), ~static_cast<size_t>(0) >> 1);
@@ -51,7 +60,7 @@ void block_ws_layout(const ecospa_block_desc& d, void* base, BlockWs& w) {
     const int s = ecospa_gemm_splits(M, N, K);
     return s > 1 ? static_cast<size_t>(s) * M * N * 4 : static_cast<size_t>(0);
   };
-  auto colsum_bytes = [&](int M, int N, int K) { return static_cast<size_t>(ecospa_gemm_splits(M, N, K)) * M * 4; };
+  auto colsum_bytes = [&](int M, int N, int K) { return static_cast<size_t>(block_colsum_rows(d.dtype, M, N, K)) * M * 4; };
   if (d.block == ECOSPA_BLOCK_FFN) {
     const size_t nh = static_cast<size_t>(is_gated(d) ? 2 : 1) * d.kp_ff;
     w.dh = c.take(T * nh * es);
@@ -221,9 +230,9 @@ static int ffn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const 
   memset(&aux, 0, sizeof(aux));
   if (gr.dw_2 && g2.splits > 1) aux.reduce[aux.n_reduce++] = g2;
   if (gr.dw_1 && g1.splits > 1) aux.reduce[aux.n_reduce++] = g1;
-  if (gr.db_2) aux.colsum[aux.n_colsum++] = g2.colsum ? AuxColsum{g2.colsum, dm, g2.splits, dm, ECOSPA_F32, gr.db_2, d.dtype}
+  if (gr.db_2) aux.colsum[aux.n_colsum++] = g2.colsum ? AuxColsum{g2.colsum, dm, ecospa_gemm_colsum_rows(g2), dm, ECOSPA_F32, gr.db_2, d.dtype}
                                                        : AuxColsum{dy, dm, T, dm, d.dtype, gr.db_2, 0};
-  if (gr.db_1) aux.colsum[aux.n_colsum++] = g1.colsum ? AuxColsum{g1.colsum, nh, g1.splits, nh, ECOSPA_F32, gr.db_1, d.dtype}
+  if (gr.db_1) aux.colsum[aux.n_colsum++] = g1.colsum ? AuxColsum{g1.colsum, nh, ecospa_gemm_colsum_rows(g1), nh, ECOSPA_F32, gr.db_1, d.dtype}
                                                        : AuxColsum{w.dh, nh, T, nh, d.dtype, gr.db_1, 0};
   return ecospa_aux_launch(ctx, aux);
 }
@@ -277,7 +286,7 @@ extern "C" int ecospa_contract(ecospa_ctx* ctx, int dtype, int M, int N, int K, 
                                const void* bias, int tile, int splits) {
   if (!ctx || !A || !B || !C) return ECOSPA_ERR_NULL;
   if (!dtype_ok(dtype)) return ECOSPA_ERR_DTYPE;
-  if (M < 1 || N < 1 || K < 1 || tile < 0 || tile > 21 || splits < 0 || splits > 64) return ECOSPA_ERR_SHAPE;
+  if (M < 1 || N < 1 || K < 1 || tile < 0 || tile > 38 || (tile > 21 && tile < 30) || splits < 0 || splits > 64) return ECOSPA_ERR_SHAPE;
   if (lda < (trans_a ? M : K) || ldb < (trans_b ? N : K) || ldc < N) return ECOSPA_ERR_SHAPE;
   GemmDesc g = gemm_desc(dtype, M, N, K, A, lda, trans_a ? 1 : 0, B, ldb, trans_b ? 1 : 0);
   g.tile = tile;
@@ -289,4 +298,32 @@ extern "C" int ecospa_contract(ecospa_ctx* ctx, int dtype, int M, int N, int K, 
     g.partial = static_cast<float*>(ctx->ws);
   }
   return ecospa_gemm(ctx, g);
+}
+
+// dY^T X with the column sums of its K-slow A operand (the bias gradient that belongs to the weight gradient), as the
+// backward passes use it; exposed for tests of every tile shape.
+extern "C" int ecospa_contract_colsum(ecospa_ctx* ctx, int M, int N, int K, const void* A, long long lda, const void* B,
+                                      long long ldb, void* C, long long ldc, float* colsum, int tile, int splits) {
+  if (!ctx || !A || !B || !C || !colsum) return ECOSPA_ERR_NULL;
+  if (M < 1 || N < 1 || K < 1 || tile < 0 || tile > 38 || (tile > 21 && tile < 30) || splits < 0 || splits > 64) return ECOSPA_ERR_SHAPE;
+  if (lda < M || ldb < N || ldc < N) return ECOSPA_ERR_SHAPE;
+  GemmDesc g = gemm_desc(ECOSPA_BF16, M, N, K, A, lda, 1, B, ldb, 1);
+  g.splits = splits == 0 ? ecospa_gemm_splits(M, N, K) : splits;
+  const int sp = g.splits > 1 ? g.splits : 1;
+  g.epi.kind = EPI_STORE; g.epi.c = C; g.epi.ldc = ldc;
+  g.tile = tile;
+  // workspace: [rows][M] partial column sums, then the fp32 partial products of a split contraction
+  const int rows = ecospa_gemm_colsum_rows(g);
+  const size_t cs_bytes = align_up(static_cast<size_t>(rows) * M * 4, 256);
+  const size_t need = cs_bytes + (sp > 1 ? static_cast<size_t>(sp) * M * N * 4 : 0);
+  if (!ctx->ws || ctx->ws_bytes < need) return ECOSPA_ERR_WORKSPACE;
+  g.colsum = static_cast<float*>(ctx->ws);
+  if (sp > 1) { g.partial = reinterpret_cast<float*>(static_cast<char*>(ctx->ws) + cs_bytes); g.defer_reduce = 1; }
+  const int rc = ecospa_gemm(ctx, g);
+  if (rc) return rc;
+  AuxBatch aux;
+  memset(&aux, 0, sizeof(aux));
+  if (sp > 1) aux.reduce[aux.n_reduce++] = g;
+  aux.colsum[aux.n_colsum++] = AuxColsum{g.colsum, M, rows, M, ECOSPA_F32, colsum, ECOSPA_F32};
+  return ecospa_aux_launch(ctx, aux);
 }

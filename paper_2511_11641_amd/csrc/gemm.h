@@ -41,14 +41,16 @@ struct GemmDesc {
   int splits;        // > 1: split K, fp32 partials in `partial`, reduced in a fixed order
   float* partial;    // [splits][M][N] when splits > 1
   int defer_reduce;  // splits > 1: only write the partials; the caller runs ecospa_gemm_reduce later
-  float* colsum;     // optional, bf16 contractions with a K-slow A operand (dY^T X): [max(splits, 1)][M] column sums of A over
-                     // each split's K range, sum_k A(m, k) - the bias gradient that belongs to the weight gradient, taken
-                     // from the operand on its way through the registers (written by the workgroups of the first tile column)
+  float* colsum;     // optional, bf16 contractions with a K-slow A operand (dY^T X): [ecospa_gemm_colsum_rows(d)][M] partial
+                     // column sums of A, sum_k A(m, k) over disjoint parts of K - the bias gradient that belongs to the
+                     // weight gradient, taken from the operand on its way through the registers; the rows add up to the sums
   GemmEpi epi;
 };
 
 // Launch on ctx->stream.  bf16 runs on MFMA tiles; fp32 on a vector-ALU tile kernel.
 int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d);
+// Rows (of M floats) of the partial column sums that the launch of d writes to d.colsum.
+int ecospa_gemm_colsum_rows(const GemmDesc& d);
 // Second half of a split-K contraction launched with defer_reduce: fixed-order sum of the partials,
 // then the epilogue.  Same descriptor as the first half.
 int ecospa_gemm_reduce(ecospa_ctx* ctx, const GemmDesc& d);
@@ -67,10 +69,19 @@ bool gemm_pipe_ok(const GemmDesc& d, int cfg, int k_chunk);
 hipError_t gemm_pipe_launch(ecospa_ctx* ctx, const GemmDesc& d, int cfg, int k_chunk);
 int gemm_pipe_bk(int cfg);
 
-// Register-staged kernel with a two-slab prefetch (gemm_rs.hip): 256x256x64 tiles, four wavefronts;
-// A K-contiguous, B either way; d.tile = 20 forces it.
+// Register-staged kernel with a two-slab prefetch (gemm_rs.hip): bm x bn x 64 tiles, four wavefronts.
+// 256 x 256: A K-contiguous with B either way, or both K-slow; the narrower shapes (bm, bn from 128, 192, 256)
+// are built for dY^T X only.  d.tile = 20 forces 256 x 256, d.tile = 30 + i shape i of GEMM_RS_SHAPES.
 bool gemm_rs_ok(const GemmDesc& d, int k_chunk);
-hipError_t gemm_rs_launch(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk);
+bool gemm_rs_shape_ok(int bm, int bn);
+hipError_t gemm_rs_launch(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk, int bm, int bn);
+#define GEMM_RS_NSHAPES 9
+static const int GEMM_RS_SHAPES[GEMM_RS_NSHAPES][2] = {{256, 256}, {192, 256}, {256, 192}, {128, 256}, {256, 128},
+                                                       {192, 192}, {128, 192}, {192, 128}, {128, 128}};
+// Plan of a weight-gradient contraction dY^T X (M x N outputs, K = tokens): tile shape and number of K splits that
+// finish soonest on 256 compute units by a cost model fitted to measurements; false if the problem does not suit
+// the kernel (K not a multiple of 64, too short).
+bool gemm_tt_plan(int M, int N, int K, int* bm, int* bn, int* splits);
 
 // The small jobs that follow the contractions of a backward pass, batched into ONE launch (each of
 // them alone would be bound by the fixed cost of a launch): fixed-order reductions of split-K

@@ -483,15 +483,9 @@ static int gemm_pipe_choice(const GemmDesc& d) {
 }
 // Long contractions with a K-slow B operand (K of several thousand, at least a tile per compute unit)
 // run fastest on the two-slab register prefetch of gemm_rs.hip.
-static int gemm_rs_tt_plan(int M, int N, int K, bool* ok);
-static bool gemm_prefers_rs(const GemmDesc& d) {
-  if (d.trans_a) {      // dY^T X: when the split count is the one planned for this kernel
-    bool ok;
-    const int s = gemm_rs_tt_plan(d.M, d.N, d.K, &ok);
-    return d.trans_b && ok && (d.splits > 1 ? d.splits : 1) == s;
-  }
+static bool gemm_prefers_rs_nt(const GemmDesc& d) {
   const long long t256 = static_cast<long long>((d.M + 255) / 256) * ((d.N + 255) / 256);
-  return d.trans_b && d.splits <= 1 && d.K >= 4096 && t256 >= 192;
+  return !d.trans_a && d.trans_b && d.splits <= 1 && d.K >= 4096 && t256 >= 192;
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int WPE, bool TRR>
@@ -522,23 +516,45 @@ static hipError_t launch_tile(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
 
 // ---------------------------------------------------------------------------------------------
 // Weight-gradient contractions (dY^T X: K = tokens, few output tiles) on the register-prefetch kernel of
-// gemm_rs.hip: 256x256 tiles, one workgroup per compute unit, so K is split until the tiles fill one round of
-// 256 - at most 4 ways and with at least 1024 of K per split (beyond that the partial sums cost more than the
-// better tile gains; measured on the layer and stack shapes).  *ok: the plan fills at least 68 % of the rounds it
-// needs and the kernel's full-slab condition holds.
-static int gemm_rs_tt_plan(int M, int N, int K, bool* ok) {
-  const long long t256 = static_cast<long long>((M + 255) / 256) * ((N + 255) / 256);
-  int s = 1;
-  while (t256 * s * 2 <= 256 && K / (s * 2) >= 1024 && s < 4) s *= 2;
-  const long long wg = t256 * s, rounds = (wg + 255) / 256;
-  *ok = K >= 4096 && K % (64 * s) == 0 && wg * 100 >= rounds * 256 * 68;
-  return s;
+// gemm_rs.hip: one workgroup per compute unit, so the tile shape (bm, bn from 128, 192, 256) and the number of K
+// splits are chosen together to finish soonest on 256 compute units.  Cost of a choice, in microseconds, fitted to
+// per-workgroup timings of every shape on this GPU (both operands K-slow; the loop is bound by moving the operands,
+// hence the term in bm + bn beside the one in bm * bn):
+//   slab (64 of K)  = 0.05 + 0.9 (bm + bn) / 512 + 0.73 bm bn / 256^2
+//   epilogue        = 0.3 + 8.1 bm bn / 256^2          (all workgroups of a round write at once)
+//   rounds          = ceil(tiles * splits / 256), each round = slabs per split * slab + epilogue
+//   split K         = a later pass over the partial sums: 3 + (splits * M * N * 4 + M * N * 2) bytes at 4 TB/s
+// A split keeps at least 512 of K.
+bool gemm_tt_plan(int M, int N, int K, int* bm_out, int* bn_out, int* splits_out) {
+  if (K % 64 || K < 1024 || M < 8 || N < 8) return false;
+  const int slabs = K / 64;
+  double best = 0.0;
+  bool found = false;
+  for (int q = 0; q < GEMM_RS_NSHAPES; ++q) {
+    const int bm = GEMM_RS_SHAPES[q][0], bn = GEMM_RS_SHAPES[q][1];
+    const long long tiles = static_cast<long long>((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    const double area = static_cast<double>(bm) * bn / 65536.0;
+    const double slab = 0.05 + 0.9 * (bm + bn) / 512.0 + 0.73 * area, epi = 0.3 + 8.1 * area;
+    for (int sp = 1; sp <= 8; ++sp) {
+      const int per = (slabs + sp - 1) / sp;                 // slabs of the first splits; the last one takes the rest
+      if (per * (sp - 1) >= slabs || (sp > 1 && per < 8)) continue;
+      const long long wg = tiles * sp, rounds = (wg + 255) / 256;
+      const double mn = static_cast<double>(M) * N;
+      const double red = sp > 1 ? 3.0 + (sp * mn * 4.0 + mn * 2.0) / 4.0e6 : 0.0;
+      const double t = 3.0 + rounds * (per * slab + epi) + red;
+      if (!found || t < best) {
+        found = true;
+        best = t;
+        *bm_out = bm; *bn_out = bn; *splits_out = sp;
+      }
+    }
+  }
+  return found;
 }
 
 int ecospa_gemm_splits(int M, int N, int K) {
-  bool rs;
-  const int s_rs = gemm_rs_tt_plan(M, N, K, &rs);
-  if (rs) return s_rs;
+  int bm, bn, sp;
+  if (gemm_tt_plan(M, N, K, &bm, &bn, &sp)) return sp;
   const long long tiles = static_cast<long long>((M + 127) / 128) * ((N + 127) / 128);
   int s = 1;
   // Two 128x128 workgroups fit a compute unit, so 512 of them run at once: split K while all splits still fit
@@ -555,11 +571,44 @@ int ecospa_gemm_token_splits(int M, int N, int K) {
   return s;
 }
 
+// Which kernel a bf16 contraction goes to: the register-prefetch kernel with tile rs_bm x rs_bn (rs_bm = 0: not that
+// one), else configuration cfg of the pipelined kernel (cfg < 0: neither - the register-staged kernel).
+// tile codes: 10-19 and 21 name the configurations 0-9 and 10 of the pipelined kernel, 20 the register-prefetch
+// kernel with 256 x 256 tiles, 30 + i the same kernel with shape i of GEMM_RS_SHAPES (dY^T X only).
+static void gemm_route(const GemmDesc& d, int splits, int* k_split_out, int* cfg_out, int* rs_bm_out, int* rs_bn_out) {
+  // K range of a split: whole 64-deep slabs, the first splits take one slab more when the slabs do not divide
+  const int k_split = d.K % 64 == 0 ? (d.K / 64 + splits - 1) / splits * 64 : (d.K + splits - 1) / splits;
+  const bool no_empty_split = static_cast<long long>(k_split) * (splits - 1) < d.K;
+  int cfg = d.tile >= 10 && d.tile < 20 ? d.tile - 10 : (d.tile == 21 ? 10 : (d.tile == 0 ? gemm_pipe_choice(d) : -1));
+  int rs_bm = 0, rs_bn = 0;
+  if (d.tile == 20) { rs_bm = rs_bn = 256; }
+  else if (d.tile >= 30 && d.tile < 30 + GEMM_RS_NSHAPES && d.trans_a && d.trans_b) { rs_bm = GEMM_RS_SHAPES[d.tile - 30][0]; rs_bn = GEMM_RS_SHAPES[d.tile - 30][1]; }
+  else if (d.tile == 0 && d.trans_a && d.trans_b) {
+    int sp;      // dY^T X: the planned shape, when the caller split K as planned
+    if (!(gemm_tt_plan(d.M, d.N, d.K, &rs_bm, &rs_bn, &sp) && sp == splits)) rs_bm = rs_bn = 0;
+  } else if (d.tile == 0 && gemm_prefers_rs_nt(d)) { rs_bm = rs_bn = 256; }
+  if (!(rs_bm && gemm_rs_ok(d, k_split) && no_empty_split)) rs_bm = rs_bn = 0;
+  if (!(cfg >= 0 && gemm_pipe_ok(d, cfg, k_split) && no_empty_split)) cfg = -1;
+  *k_split_out = k_split; *cfg_out = cfg; *rs_bm_out = rs_bm; *rs_bn_out = rs_bn;
+}
+
+// Rows of the partial column-sum matrix (GemmDesc::colsum) that the launch of d writes, M floats each: one per K split,
+// times the tile columns when the register-prefetch kernel runs it (there every tile column adds up its share of the
+// slabs).  The caller sizes the buffer with it and adds the rows up in order.
+int ecospa_gemm_colsum_rows(const GemmDesc& d) {
+  const int splits = d.splits > 1 ? d.splits : 1;
+  if (d.dtype != ECOSPA_BF16) return splits;
+  int k_split, cfg, rs_bm, rs_bn;
+  gemm_route(d, splits, &k_split, &cfg, &rs_bm, &rs_bn);
+  return rs_bm ? splits * ((d.N + rs_bn - 1) / rs_bn) : splits;
+}
+
 int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
   if (d.M < 1 || d.N < 1 || d.K < 1) return ECOSPA_ERR_SHAPE;
   if (!d.A || !d.B || !d.epi.c) return ECOSPA_ERR_NULL;
   if (d.splits > 1 && !d.partial) return ECOSPA_ERR_WORKSPACE;
-  if (d.colsum && !(d.dtype == ECOSPA_BF16 && d.trans_a && d.trans_b && d.tile == 0)) return ECOSPA_ERR_SHAPE;
+  // column sums of the A operand: the dY^T X form on the kernels that stage A through registers (not the pipelined one)
+  if (d.colsum && !(d.dtype == ECOSPA_BF16 && d.trans_a && d.trans_b && (d.tile <= 4 || d.tile == 20 || d.tile >= 30))) return ECOSPA_ERR_SHAPE;
   const int splits = d.splits > 1 ? d.splits : 1;
   if (d.dtype == ECOSPA_BF16) {
     // 16-byte vector loads along the contiguous axis of each operand
@@ -580,11 +629,10 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
     const bool prof = ctx->prof_on && ctx->prof_n < ctx->prof_cap;
     if (prof) (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n], ctx->stream);
     hipError_t le;
-    const int k_split = (d.K + splits - 1) / splits;
-    // tile codes: 10-19 and 21 name the configurations 0-9 and 10 of the pipelined kernel, 20 the register-prefetch kernel
-    const int cfg = d.tile >= 10 && d.tile < 20 ? d.tile - 10 : (d.tile == 21 ? 10 : (d.tile == 0 ? gemm_pipe_choice(d) : -1));
-    if ((d.tile == 20 || (d.tile == 0 && gemm_prefers_rs(d))) && gemm_rs_ok(d, k_split)) le = gemm_rs_launch(ctx, d, k_split);
-    else if (cfg >= 0 && gemm_pipe_ok(d, cfg, k_split)) le = gemm_pipe_launch(ctx, d, cfg, k_split);
+    int k_split, cfg, rs_bm, rs_bn;
+    gemm_route(d, splits, &k_split, &cfg, &rs_bm, &rs_bn);
+    if (rs_bm) le = gemm_rs_launch(ctx, d, k_split, rs_bm, rs_bn);
+    else if (cfg >= 0) le = gemm_pipe_launch(ctx, d, cfg, k_split);
     else {
       // register-staged kernel; tile 1/2 = 128/256 tiles with K-slow operands transposed on the way to
       // LDS, 3/4 = the same tiles with K-slow operands read by transposing LDS reads.  Measured: the

@@ -4,7 +4,8 @@
 //   K-contiguous tile [rows][BK]:  pc = kc ^ f(row), f periodic in 16 rows (the 16 rows one
 //                                  ds_read_b128 pass touches land on 16 different 16-byte groups);
 //   K-slow tile [BK][rows]:        pc = c ^ ((k & 3) << 2) (the four k rows that one transposing
-//                                  read gathers land on four different 64-byte groups).
+//                                  read gathers land on four different 64-byte groups); rows of 192
+//                                  elements rotate the chunk index instead (see ks_off).
 #pragma once
 #include "gemm_epi.h"
 
@@ -30,7 +31,16 @@ __device__ __forceinline__ int kc_off(int row, int kc) {
 // ---- K-slow tile [BK][RT] -------------------------------------------------------------------------
 template <int RT>
 __device__ __forceinline__ int ks_off(int k, int c) {
-  return k * RT + ((c ^ ((k & 3) << 2)) << 3);
+  if constexpr (RT % 128 == 0) {
+    return k * RT + ((c ^ ((k & 3) << 2)) << 3);
+  } else {
+    // 192-element rows (384 bytes) hold 24 chunks: an XOR would leave the row, so the chunk index is rotated by
+    // 4 * (k % 4) instead; with the row pitch of 96 banks the four k rows of a transposing read then start at
+    // banks 0, 48, 32 and 16 (mod 64)
+    constexpr int CPR = RT / 8;
+    const int pc = c + ((k & 3) << 2);
+    return k * RT + ((pc >= CPR ? pc - CPR : pc) << 3);
+  }
 }
 
 // Fragment of a 32-row block for k step s (16 wide): lane l holds row l % 32, k = 8 * (l / 32) + 0..7.

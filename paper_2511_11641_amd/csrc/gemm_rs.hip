@@ -1,16 +1,20 @@
-// bf16 contraction with a register-staged, two-slab-deep prefetch: 256x256x64 workgroup tiles, four
-// wavefronts of 128x128 (one per SIMD, accumulators in the AGPR half of the register file).
+// bf16 contraction with a register-staged, two-slab-deep prefetch: BM x BN x 64 workgroup tiles (BM, BN from
+// 128, 192, 256), four wavefronts of (BM/2) x (BN/2) (one per SIMD, accumulators in the AGPR half of the
+// register file).
 //
 // Operand slabs travel global -> VGPR -> LDS.  The loads of slab t+2 are issued while slab t is
 // multiplied and sit in registers for a whole slab before they are written to the LDS buffer that
 // slab t-1 has just freed, so a load has more than one slab time (about 1.3 us) to come back from
-// L2 or HBM - with two 64 KB LDS buffers a direct global->LDS load can only be issued one slab
+// L2 or HBM - with two LDS buffers a direct global->LDS load can only be issued one slab
 // ahead.  Four wavefronts of 128x128 read (128+128) x 64 operand elements from LDS per slab each,
 // a third less than eight wavefronts of 128x64.
 //
-// Per slab and wavefront: 64 MFMAs in four 16-wide k steps.  Behind each MFMA goes one small piece of
+// The narrower tiles exist for the weight-gradient contractions dY^T X: few output tiles and a long K, so the
+// tile shape and the number of K splits are chosen to fill the 256 compute units (gemm_tt_plan in gemm.hip).
+//
+// Per slab and wavefront: FM*FN MFMAs in each of four 16-wide k steps.  Behind each MFMA goes a share of
 // the other work, in a fixed order (sched_barrier keeps the compiler from regrouping it):
-//   k step 0: the 16 global loads of slab t+2, fragment reads of k step 1
+//   k step 0: the global loads of slab t+2, fragment reads of k step 1
 //   k step 1: LDS writes of the A part of slab t+1, fragment reads of k step 2
 //   k step 2: LDS writes of the B part of slab t+1, fragment reads of k step 3
 //   k step 3: barrier (slab t+1 complete in LDS, slab t no longer read), fragment reads of slab t+1
@@ -30,35 +34,44 @@ __device__ __forceinline__ void rs_static_for(F&& f) {
   }
 }
 
-// The eight 16-byte pieces of one operand slab that a thread moves: where they come from and where
-// they go in the LDS tile.
+// The ROWS / 32 16-byte pieces of one operand slab that a thread moves: where they come from and where
+// they go in the LDS tile.  Piece i of a thread is number (wave * PER + i) * 64 + lane of the slab's pieces.
 template <int ROWS, bool KSLOW>
 struct RsOperand {
-  const bf16_t* src[8];
+  static constexpr int PER = ROWS / 32;
+  // LDS offsets repeat with a period of NDST pieces (the swizzles repeat every 16 tile rows / 4 slab rows):
+  // piece i sits at dst[i % NDST] + (i / NDST) * STRIDE
+  static constexpr int NDST = !KSLOW ? 2 : (ROWS == 256 ? 2 : (ROWS == 128 ? 1 : 3));
+  static constexpr int STRIDE = NDST * 512;
+  static_assert(ROWS == 128 || ROWS == 192 || ROWS == 256, "tile extents that are built");
+  static_assert(PER % NDST == 0, "whole periods");
+  const bf16_t* src[PER];
   long long step;     // elements per slab
-  int dst[2];         // LDS element offset of piece 0 and piece 1; piece i sits at dst[i & 1] + (i / 2) * 1024
+  int dst[NDST];
   __device__ __forceinline__ void init(const bf16_t* base, long long ld, int r0, int R, int k0) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (!KSLOW) {
-      // piece i: tile rows (wave * 8 + i) * 8 + lane / 8, 16-byte chunk lane % 8 of the 64-wide slab row
+    if constexpr (!KSLOW) {
+      // piece i: tile rows (wave * PER + i) * 8 + lane / 8, 16-byte chunk lane % 8 of the 64-wide slab row
       const int rl = lane >> 3, kc = lane & 7;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int row = (wave * 8 + i) * 8 + rl;
+      for (int i = 0; i < PER; ++i) {
+        const int row = (wave * PER + i) * 8 + rl;
         src[i] = base + static_cast<long long>(min(r0 + row, R - 1)) * ld + k0 + kc * 8;
       }
-      dst[0] = kc_off<64>(wave * 64 + rl, kc);
-      dst[1] = kc_off<64>(wave * 64 + 8 + rl, kc);
+      dst[0] = kc_off<64>(wave * PER * 8 + rl, kc);
+      dst[1] = kc_off<64>(wave * PER * 8 + 8 + rl, kc);
       step = 64;
     } else {
-      // piece i: slab rows k = (wave * 8 + i) * 2 + lane / 32, 16-byte chunk lane % 32 of the ROWS-wide row
-      static_assert(ROWS == 256, "one K-slow slab row = 32 chunks");
-      const int kl = lane >> 5, c = lane & 31;
-      const int col = min(r0 + c * 8, R - 8);
+      // piece i: slab row k = p / (ROWS / 8), chunk c = p % (ROWS / 8) of the ROWS-wide row, p its number
+      constexpr int CPR = ROWS / 8;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) src[i] = base + static_cast<long long>(k0 + (wave * 8 + i) * 2 + kl) * ld + col;
-      dst[0] = ks_off<ROWS>(wave * 16 + kl, c);
-      dst[1] = ks_off<ROWS>(wave * 16 + 2 + kl, c);
+      for (int i = 0; i < PER; ++i) {
+        const int p = (wave * PER + i) * 64 + lane;
+        const int k = p / CPR, c = p - k * CPR;
+        const int col = min(r0 + c * 8, R - 8);
+        src[i] = base + static_cast<long long>(k0 + k) * ld + col;
+        if (i < NDST) dst[i] = ks_off<ROWS>(k, c);
+      }
       step = 64 * ld;
     }
   }
@@ -68,18 +81,18 @@ struct RsOperand {
     return v;
   }
   __device__ __forceinline__ void store(bf16_t* tile, int i, const u32x4& v) const {
-    // pieces i and i + 2 are 16 tile rows (K-contiguous: 16 * 64 elements) or 4 slab rows (K-slow:
-    // 4 * 256 elements) apart: 1024 elements either way, and the swizzle repeats with that period
-    *reinterpret_cast<u32x4*>(tile + dst[i & 1] + (i >> 1) * 1024) = v;
+    *reinterpret_cast<u32x4*>(tile + dst[i % NDST] + (i / NDST) * STRIDE) = v;
   }
 };
 
-template <bool TA, bool TB>
+template <int BM, int BN, bool TA, bool TB>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
-  constexpr int BM = 256, BN = 256, BK = 64, WGN = 2;
-  constexpr int WTM = 128, WTN = 128, FM = 4, FN = 4, KS = 4, NM = FM * FN;
+  constexpr int BK = 64, WGN = 2;
+  constexpr int WTM = BM / 2, WTN = BN / 2, FM = WTM / 32, FN = WTN / 32, KS = 4, NM = FM * FN;
   constexpr int STAGE = (BM + BN) * BK;
+  constexpr int PA = BM / 32, PB = BN / 32;            // 16-byte pieces per thread and slab
+  static_assert(FM + FN <= NM, "a fragment slot per MFMA");
   extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -102,21 +115,29 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   oa.init(static_cast<const bf16_t*>(d.A), d.lda, m0, d.M, k_begin);
   ob.init(static_cast<const bf16_t*>(d.B), d.ldb, n0, d.N, k_begin);
 
-  // Column sums of a K-slow A (dY^T X: the bias gradient is the column sum of dY): the first tile column adds up
-  // the pieces it moves anyway.  A thread's pieces all cover the same 8 columns, m0 + (lane % 32) * 8 ...
+  // Column sums of a K-slow A (dY^T X: the bias gradient is the column sum of dY), added up from the pieces a thread
+  // moves anyway.  A wavefront that is alone on its SIMD pays for every vector instruction, so the work is shared out:
+  // the workgroup of tile column j takes the slabs whose number is j modulo the tile columns, and writes row
+  // (split * tile columns + j) of the partial sums.  Piece i of a thread covers the same 8 columns as piece i + NDST.
   constexpr bool CS = TA && TB;
-  const bool do_cs = CS && d.colsum && n0 == 0;
-  float cs_acc[CS ? 8 : 1];
+  constexpr int NCS = CS ? RsOperand<BM, TA>::NDST : 1;
+  const bool do_cs = CS && d.colsum;
+  const int tile_col = in_band / band_rows;
+  int cs_next = tile_col;                              // next slab of this split whose pieces are added
+  float cs_acc[NCS][CS ? 8 : 1];
   if constexpr (CS) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) cs_acc[j] = 0.f;
+    for (int q = 0; q < NCS; ++q)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) cs_acc[q][j] = 0.f;
   }
-  auto cs_add = [&](const u32x4& v) {
+  auto cs_add = [&](auto i_, const u32x4& v) {
     if constexpr (CS) {
+      constexpr int q0 = decltype(i_)::value % NCS;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        cs_acc[2 * q] += __uint_as_float(v[q] << 16);
-        cs_acc[2 * q + 1] += __uint_as_float(v[q] & 0xffff0000u);
+        cs_acc[q0][2 * q] += __uint_as_float(v[q] << 16);
+        cs_acc[q0][2 * q + 1] += __uint_as_float(v[q] & 0xffff0000u);
       }
     }
   };
@@ -130,23 +151,23 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // prologue: slabs 0 and 1 into registers (a slab beyond the last repeats it), slab 0 on into LDS
-  u32x4 ra[2][8], rb[2][8];
+  u32x4 ra[2][PA], rb[2][PB];
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
     const bool adv = p + 1 < nk;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) ra[p][i] = oa.load(i, adv ? oa.step : 0);
+    for (int i = 0; i < PA; ++i) ra[p][i] = oa.load(i, adv ? oa.step : 0);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) rb[p][i] = ob.load(i, adv ? ob.step : 0);
+    for (int i = 0; i < PB; ++i) rb[p][i] = ob.load(i, adv ? ob.step : 0);
   }
 #pragma unroll
-  for (int i = 0; i < 8; ++i) oa.store(lds, i, ra[0][i]);
-  if (do_cs) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) cs_add(ra[0][i]);
+  for (int i = 0; i < PA; ++i) oa.store(lds, i, ra[0][i]);
+  if (do_cs && cs_next == 0) {
+    rs_static_for<0, PA>([&](auto i_) { cs_add(i_, ra[0][decltype(i_)::value]); });
+    cs_next += tiles_n;
   }
 #pragma unroll
-  for (int i = 0; i < 8; ++i) ob.store(lds + BM * BK, i, rb[0][i]);
+  for (int i = 0; i < PB; ++i) ob.store(lds + BM * BK, i, rb[0][i]);
   __syncthreads();
   bf16x8_t fa[2][FM], fb[2][FN];
 #pragma unroll
@@ -164,7 +185,8 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
     bf16_t* bs_nxt = as_nxt + BM * BK;
     const bool adv = t + 3 < nk;                       // the slab after the one loaded now exists
     const long long adv_a = adv ? oa.step : 0, adv_b = adv ? ob.step : 0;
-    const bool cs_now = do_cs && t + 1 < nk;           // the slab written to LDS here is a real one, not the repeat past the end
+    const bool cs_now = do_cs && t + 1 < nk && t + 1 == cs_next;   // slab t+1 (a real one, not the repeat past the end) is this workgroup's
+    if (cs_now) cs_next += tiles_n;
     rs_static_for<0, KS>([&](auto s_) {
       constexpr int s = decltype(s_)::value;
       constexpr int cur = s & 1, nxt = cur ^ 1;
@@ -181,6 +203,8 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
       const bf16_t* fa_src = last ? as_nxt : as_cur;
       const bf16_t* fb_src = last ? bs_nxt : bs_cur;
       constexpr int sn = last ? 0 : s + 1;
+      // the other work of this k step, dealt evenly over the MFMA slots
+      constexpr int NOPS = s == 0 ? PA + PB : (s == 1 ? PA : (s == 2 ? PB : 0));
       rs_static_for<0, NM>([&](auto m_) {
         constexpr int m = decltype(m_)::value;
         constexpr int i = m / FN, j = m % FN;
@@ -188,15 +212,19 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (m < FM) fa[nxt][m] = read_frag<BM, BK, TA>(fa_src, wm * WTM + m * 32, sn);
         else if constexpr (m < FM + FN) fb[nxt][m - FM] = read_frag<BN, BK, TB>(fb_src, wn * WTN + (m - FM) * 32, sn);
-        if constexpr (s == 0) {
-          if constexpr (m < 8) ra[P][m] = oa.load(m, adv_a);
-          else rb[P][m - 8] = ob.load(m - 8, adv_b);
-        } else if constexpr (s == 1 && (m & 1)) {
-          oa.store(as_nxt, m >> 1, ra[Q][m >> 1]);
-          if (cs_now) cs_add(ra[Q][m >> 1]);
-        } else if constexpr (s == 2 && (m & 1)) {
-          ob.store(bs_nxt, m >> 1, rb[Q][m >> 1]);
-        }
+        constexpr int O0 = m * NOPS / NM, O1 = (m + 1) * NOPS / NM;
+        rs_static_for<O0, O1>([&](auto o_) {
+          constexpr int o = decltype(o_)::value;
+          if constexpr (s == 0) {
+            if constexpr (o < PA) ra[P][o] = oa.load(o, adv_a);
+            else rb[P][o - PA] = ob.load(o - PA, adv_b);
+          } else if constexpr (s == 1) {
+            oa.store(as_nxt, o, ra[Q][o]);
+            if (cs_now) cs_add(o_, ra[Q][o]);
+          } else if constexpr (s == 2) {
+            ob.store(bs_nxt, o, rb[Q][o]);
+          }
+        });
         __builtin_amdgcn_sched_barrier(0);
       });
     });
@@ -211,25 +239,33 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
 
   if constexpr (CS) {
     if (do_cs) {     // the same for the whole workgroup
-      // eight partial sums per column (two slab-row halves in each of the four wavefronts), added in a fixed order
-      float* red = reinterpret_cast<float*>(lds);
-      const int part_id = wave * 2 + (lane >> 5), c = lane & 31;
-      const bool own = m0 + c * 8 + 8 <= d.M;      // beyond the ragged edge the loads were clamped onto another thread's columns
+      // Every thread parks its partial sums; column r then adds those of the threads that moved its 8-column chunk, in
+      // a fixed order.  Piece q of thread (wave, lane) covers chunk (q * 64 + lane) % CPR (a wave's pieces start at a
+      // multiple of CPR), so the threads of chunk c are the lanes congruent to c - 64 q modulo CPR of every wavefront.
+      constexpr int CPR = BM / 8;
+      float* red = reinterpret_cast<float*>(lds);                          // [256][NCS][8]
 #pragma unroll
-      for (int j = 0; j < 8; ++j) red[part_id * BM + c * 8 + j] = own ? cs_acc[j] : 0.f;
+      for (int q = 0; q < NCS; ++q)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) red[(threadIdx.x * NCS + q) * 8 + j] = cs_acc[q][j];
       __syncthreads();
       const int r = threadIdx.x;
-      if (m0 + r < d.M) {
+      if (r < BM && m0 + r < d.M) {
         float sum = 0.f;
+        const int c = r >> 3, j = r & 7;
+        for (int w = 0; w < 4; ++w)
 #pragma unroll
-        for (int q = 0; q < 8; ++q) sum += red[q * BM + r];
-        d.colsum[static_cast<long long>(zsplit) * d.M + m0 + r] = sum;
+          for (int q = 0; q < NCS; ++q) {
+            const int l0 = ((c - q * 64) % CPR + CPR) % CPR;
+            for (int l = l0; l < 64; l += CPR) sum += red[((w * 64 + l) * NCS + q) * 8 + j];
+          }
+        d.colsum[(static_cast<long long>(zsplit) * tiles_n + tile_col) * d.M + m0 + r] = sum;
       }
       __syncthreads();
     }
   }
 
-  // Epilogue through LDS: each wavefront parks 32 rows x 128 columns of fp32 at a time in its own
+  // Epilogue through LDS: each wavefront parks 32 rows x WTN columns of fp32 at a time in its own
   // slice of the operand buffers, then every lane handles 8 consecutive columns of a row (16-byte
   // global accesses).  Accumulator layout of a 32x32 tile: column = lane % 32,
   // row = 8 * (r / 4) + 4 * (lane / 32) + r % 4.
@@ -237,7 +273,8 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   const bool split = d.splits > 1;
   float* part = split ? d.partial + static_cast<long long>(zsplit) * d.M * d.N : nullptr;
   constexpr int LPR = WTN / 8;          // lanes per row
-  constexpr int RPI = 64 / LPR;         // rows per pass
+  constexpr int RPI = 64 / LPR;         // rows per pass (96 columns: 5 rows, four lanes idle)
+  constexpr int NIT = (32 + RPI - 1) / RPI;
   const int n = n0 + wn * WTN + (lane % LPR) * 8;
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
@@ -250,10 +287,10 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll 1
-    for (int it = 0; it < 32 / RPI; ++it) {
+    for (int it = 0; it < NIT; ++it) {
       const int row = it * RPI + lane / LPR;
       const int m = m0 + wm * WTM + i * 32 + row;
-      if (m >= d.M || n >= d.N) continue;
+      if (lane / LPR >= RPI || row >= 32 || m >= d.M || n >= d.N) continue;
       float v[8];
       const float4 lo = *reinterpret_cast<const float4*>(cs + row * WTN + (lane % LPR) * 8);
       const float4 hi = *reinterpret_cast<const float4*>(cs + row * WTN + (lane % LPR) * 8 + 4);
@@ -272,10 +309,14 @@ void gemm_bf16_rs_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   }
 }
 
-// instantiated explicitly (see gemm_pipe.hip)
-template __global__ void gemm_bf16_rs_kernel<false, false>(const GemmDesc, int, int);
-template __global__ void gemm_bf16_rs_kernel<false, true>(const GemmDesc, int, int);
-template __global__ void gemm_bf16_rs_kernel<true, true>(const GemmDesc, int, int);
+// The shapes that are built, instantiated explicitly (see gemm_pipe.hip): 256 x 256 for all three operand forms,
+// the narrower ones for dY^T X.
+#define RS_TT_SHAPES(X) X(256, 256) X(192, 256) X(256, 192) X(128, 256) X(256, 128) X(192, 192) X(128, 192) X(192, 128) X(128, 128)
+template __global__ void gemm_bf16_rs_kernel<256, 256, false, false>(const GemmDesc, int, int);
+template __global__ void gemm_bf16_rs_kernel<256, 256, false, true>(const GemmDesc, int, int);
+#define RS_INSTANTIATE_TT(BM, BN) template __global__ void gemm_bf16_rs_kernel<BM, BN, true, true>(const GemmDesc, int, int);
+RS_TT_SHAPES(RS_INSTANTIATE_TT)
+#undef RS_INSTANTIATE_TT
 
 // ---------------------------------------------------------------------------------------------
 bool gemm_rs_ok(const GemmDesc& d, int k_chunk) {
@@ -284,24 +325,40 @@ bool gemm_rs_ok(const GemmDesc& d, int k_chunk) {
   return d.M >= 8 && d.N >= 8;
 }
 
-hipError_t gemm_rs_launch(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
-  const int tm = (d.M + 255) / 256, tn = (d.N + 255) / 256;
+template <int BM, int BN, bool TA, bool TB>
+static hipError_t rs_launch_shape(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk) {
+  const int tm = (d.M + BM - 1) / BM, tn = (d.N + BN - 1) / BN;
   const int splits = d.splits > 1 ? d.splits : 1;
   const dim3 grid(tm * tn * splits), block(256);
-  const int lds_bytes = 2 * (256 + 256) * 64 * static_cast<int>(sizeof(bf16_t));   // also covers the epilogue staging
-#define RS_LAUNCH(TA, TB)                                                                                      \
-  do {                                                                                                         \
-    auto kern = gemm_bf16_rs_kernel<TA, TB>;                                                                   \
-    static LdsAttrOnce attr_once;                                                                              \
-    {                                                                                                          \
-      hipError_t e = attr_once.ensure(reinterpret_cast<const void*>(kern), lds_bytes);                         \
-      if (e != hipSuccess) return e;                                                                           \
-    }                                                                                                          \
-    hipLaunchKernelGGL(kern, grid, block, lds_bytes, ctx->stream, d, tn, k_chunk);                             \
-  } while (0)
-  if (d.trans_a) RS_LAUNCH(true, true);
-  else if (d.trans_b) RS_LAUNCH(false, true);
-  else RS_LAUNCH(false, false);
-#undef RS_LAUNCH
+  // two operand buffers; they also cover the epilogue staging (4 x 32 x BN/2 floats) and the column-sum scratch
+  // (256 x 3 x 9 words at most)
+  constexpr int operand_bytes = 2 * (BM + BN) * 64 * static_cast<int>(sizeof(bf16_t));
+  constexpr int lds_bytes = operand_bytes > 32768 ? operand_bytes : 32768;
+  auto kern = gemm_bf16_rs_kernel<BM, BN, TA, TB>;
+  static LdsAttrOnce attr_once;
+  if (lds_bytes > 64 * 1024) {
+    hipError_t e = attr_once.ensure(reinterpret_cast<const void*>(kern), lds_bytes);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(kern, grid, block, lds_bytes, ctx->stream, d, tn, k_chunk);
   return hipGetLastError();
+}
+
+bool gemm_rs_shape_ok(int bm, int bn) {
+#define RS_SHAPE_CHECK(BM, BN) if (bm == BM && bn == BN) return true;
+  RS_TT_SHAPES(RS_SHAPE_CHECK)
+#undef RS_SHAPE_CHECK
+  return false;
+}
+
+hipError_t gemm_rs_launch(ecospa_ctx* ctx, const GemmDesc& d, int k_chunk, int bm, int bn) {
+  if (d.trans_a) {
+#define RS_SHAPE_LAUNCH(BM, BN) if (bm == BM && bn == BN) return rs_launch_shape<BM, BN, true, true>(ctx, d, k_chunk);
+    RS_TT_SHAPES(RS_SHAPE_LAUNCH)
+#undef RS_SHAPE_LAUNCH
+    return hipErrorInvalidValue;
+  }
+  if (bm != 256 || bn != 256) return hipErrorInvalidValue;
+  if (d.trans_b) return rs_launch_shape<256, 256, false, true>(ctx, d, k_chunk);
+  return rs_launch_shape<256, 256, false, false>(ctx, d, k_chunk);
 }

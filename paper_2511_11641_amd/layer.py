@@ -15,10 +15,14 @@ from . import binding as B
 class FfnBlock:
     """Compacted FFN pair (W_in / W_out, or W_gate (.) W_up / W_down)."""
 
-    def __init__(self, ctx: B.Context, w1, b1, w2, b2, act: int, w1b=None, transposed: bool = False):
+    def __init__(self, ctx: B.Context, w1, b1, w2, b2, act: int, w1b=None, transposed: bool = False,
+                 bias_grads: Optional[bool] = None):
         """transposed: keep transposed copies of the compact matrices for the backward pass (refreshed by
-        :meth:`compact`; after a parameter update call :meth:`refresh_transposed`)."""
+        :meth:`compact`; after a parameter update call :meth:`refresh_transposed`).  bias_grads: ask the backward pass
+        for the bias gradients (default: for the biases the block has; True: all of them - they are column sums of the
+        upstream gradients and exist with or without a bias)."""
         self.ctx, self.act = ctx, act
+        self.bias_grads = bias_grads
         self.transposed = transposed
         self.w1, self.b1, self.w2, self.b2, self.w1b = w1, b1, w2, b2, w1b
         self.n, self.d = w1.shape
@@ -114,10 +118,13 @@ class FfnBlock:
         self.dx = torch.empty((T, self.d), dtype=dt, device=dev)
         self.dw1_c = torch.empty_like(self.w1_c)
         self.dw2_c = torch.empty_like(self.w2_c)
-        self.db1_c = torch.empty((nh,), dtype=dt, device=dev)
-        self.db2 = torch.empty((self.d,), dtype=dt, device=dev)
+        # bias gradients only for the biases the block has (a missing pointer tells the library to skip the sums)
+        want1 = self.b1 is not None if self.bias_grads is None else self.bias_grads
+        want2 = self.b2 is not None if self.bias_grads is None else self.bias_grads
+        self.db1_c = torch.empty((nh,), dtype=dt, device=dev) if want1 else None
+        self.db2 = torch.empty((self.d,), dtype=dt, device=dev) if want2 else None
         g = B.Grads()
-        g.dw_1, g.db_1, g.dw_2, g.db_2 = (t.data_ptr() for t in (self.dw1_c, self.db1_c, self.dw2_c, self.db2))
+        g.dw_1, g.db_1, g.dw_2, g.db_2 = (B._ptr(t) for t in (self.dw1_c, self.db1_c, self.dw2_c, self.db2))
         g.ld_dw1, g.ld_dw2 = self.dw1_c.stride(0), self.dw2_c.stride(0)
         self.grads = g
         self._desc = self.desc(Bsz, L)
@@ -139,8 +146,11 @@ class AttnBlock:
     (and heads of W_o) of a group keep the inner dimensions of the key/value head they share."""
 
     def __init__(self, ctx: B.Context, wq, wk, wv, wo, bq, bk, bv, bo, h: int, d_h: int, *, rope: bool,
-                 causal: bool = True, rope_base: float = 10000.0, h_kv: Optional[int] = None, transposed: bool = False):
+                 causal: bool = True, rope_base: float = 10000.0, h_kv: Optional[int] = None, transposed: bool = False,
+                 bias_grads: Optional[bool] = None):
+        """bias_grads: ask the backward pass for the bias gradients (default: for the biases the block has)."""
         self.ctx, self.h, self.d_h, self.rope, self.causal, self.rope_base = ctx, h, d_h, rope, causal, rope_base
+        self.bias_grads = bias_grads
         self.transposed = transposed      # transposed copies of the compact matrices for the backward pass
         self.h_kv = h if h_kv is None else h_kv
         assert h % self.h_kv == 0
@@ -268,11 +278,13 @@ class AttnBlock:
         self.y = torch.empty((T, self.d), dtype=dt, device=dev)
         self.dx = torch.empty((T, self.d), dtype=dt, device=dev)
         self.dwqkv_c = torch.empty_like(self.wqkv_c)
-        self.dbqkv_c = torch.empty((nqkv,), dtype=dt, device=dev)
+        want_qkv = self.bq is not None if self.bias_grads is None else self.bias_grads
+        want_o = self.bo is not None if self.bias_grads is None else self.bias_grads
+        self.dbqkv_c = torch.empty((nqkv,), dtype=dt, device=dev) if want_qkv else None
         self.dwo_c = torch.empty_like(self.wo_c)
-        self.dbo = torch.empty((self.d,), dtype=dt, device=dev)
+        self.dbo = torch.empty((self.d,), dtype=dt, device=dev) if want_o else None
         g = B.Grads()
-        g.dw_qkv, g.db_qkv, g.dw_o, g.db_o = (t.data_ptr() for t in (self.dwqkv_c, self.dbqkv_c, self.dwo_c, self.dbo))
+        g.dw_qkv, g.db_qkv, g.dw_o, g.db_o = (B._ptr(t) for t in (self.dwqkv_c, self.dbqkv_c, self.dwo_c, self.dbo))
         g.ld_dwqkv, g.ld_dwo = self.dwqkv_c.stride(0), self.dwo_c.stride(0)
         self.grads = g
         return self

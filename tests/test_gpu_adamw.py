@@ -108,14 +108,14 @@ def test_removal_loop_with_optimizer_state(ctx):
     T, d, n, k1, k2 = 256, 128, 512, 384, 256
     t = synth.ffn_layer(80, T, d, n, dtype="bf16", structure="pretrained", bias=False)
     g = {nm: dev(a, "bf16") for nm, a in t.items()}
-    full = FfnBlock(ctx, g["w1"], None, g["w2"], None, B.ACT_GELU_ERF)
+    full = FfnBlock(ctx, g["w1"], None, g["w2"], None, B.ACT_GELU_ERF, bias_grads=True)
     idx1_d = ctx.ecospa_select_topk(full.score(), k1)
     idx1 = idx1_d.cpu().numpy()
     # state in the compact layout: master copies of the gathered weights, zero moments
     mw1 = ctx.ecospa_compact(g["w1"].float(), idx1_d, 0, 1, n)
     mw2 = ctx.ecospa_compact(g["w2"].float(), idx1_d, 1, 1, n)
     st = {"w1": [mw1, torch.zeros_like(mw1), torch.zeros_like(mw1)], "w2": [mw2, torch.zeros_like(mw2), torch.zeros_like(mw2)]}
-    blk = FfnBlock(ctx, mw1.to(torch.bfloat16), None, mw2.to(torch.bfloat16), None, B.ACT_GELU_ERF)
+    blk = FfnBlock(ctx, mw1.to(torch.bfloat16), None, mw2.to(torch.bfloat16), None, B.ACT_GELU_ERF, bias_grads=True)
     all_units = torch.arange(k1, dtype=torch.int32, device="cuda")[None, :].contiguous()
     blk.compact(all_units).alloc(1, T)
 
@@ -158,7 +158,7 @@ def test_removal_loop_with_optimizer_state(ctx):
         for a, b in zip(before[nm], new[nm]):
             assert np.array_equal(host(b), O.compact(a, idx2, axis, k1)), "kept state is carried over bit for bit"
         st[nm] = new[nm]
-    blk2 = FfnBlock(ctx, st["w1"][0].to(torch.bfloat16), None, st["w2"][0].to(torch.bfloat16), None, B.ACT_GELU_ERF)
+    blk2 = FfnBlock(ctx, st["w1"][0].to(torch.bfloat16), None, st["w2"][0].to(torch.bfloat16), None, B.ACT_GELU_ERF, bias_grads=True)
     blk2.compact(torch.arange(k2, dtype=torch.int32, device="cuda")[None, :].contiguous()).alloc(1, T)
     train_step(blk2, 2)
     # the surviving units are a subset of the first selection, in the original numbering

@@ -32,7 +32,7 @@ def run_attn_case(ctx, seed, Bsz, L, d, h, dh, k_qk, k_vo, *, rope, causal, bias
     iv = O.select_topk(vvo.astype(np.float32), k_vo)
     g = {nm: dev(a, dtype) for nm, a in t.items()}
     blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g.get("bq"), g.get("bk"), g.get("bv"), g.get("bo"),
-                    h, dh, rope=rope, causal=causal, transposed=transposed)
+                    h, dh, rope=rope, causal=causal, transposed=transposed, bias_grads=True)
     blk.compact(torch.from_numpy(iq).cuda(), torch.from_numpy(iv).cuda()).alloc(Bsz, L)
     y = blk.fwd(g["x"])
     dx = blk.bwd(g["x"], g["dy"])
@@ -129,7 +129,7 @@ def test_attn_forward_only_keeps_nothing_and_agrees(ctx, rope, L, d):
     h, dh = (4, 64) if d == 256 else (16, 64)
     t = synth.attn_layer(37, 2, L, d, h, dh, dtype="bf16")
     g = {nm: dev(a, "bf16") for nm, a in t.items()}
-    blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g["bq"], g["bk"], g["bv"], g["bo"], h, dh, rope=rope, causal=True)
+    blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g["bq"], g["bk"], g["bv"], g["bo"], h, dh, rope=rope, causal=True, bias_grads=True)
     rng = np.random.default_rng(L)
     units = dh // (2 if rope else 1)
     iq = torch.from_numpy(np.stack([np.sort(rng.choice(units, units // 2, replace=False)) for _ in range(h)]).astype(np.int32)).cuda()
@@ -147,7 +147,7 @@ def test_attn_backward_with_optional_outputs(ctx):
     h, dh, L, d = 4, 64, 200, 256
     t = synth.attn_layer(38, 2, L, d, h, dh, dtype="bf16")
     g = {nm: dev(a, "bf16") for nm, a in t.items()}
-    blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g["bq"], g["bk"], g["bv"], g["bo"], h, dh, rope=True, causal=True)
+    blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g["bq"], g["bk"], g["bv"], g["bo"], h, dh, rope=True, causal=True, bias_grads=True)
     rng = np.random.default_rng(9)
     iq = torch.from_numpy(np.stack([np.sort(rng.choice(dh // 2, 16, replace=False)) for _ in range(h)]).astype(np.int32)).cuda()
     iv = torch.from_numpy(np.stack([np.sort(rng.choice(dh, 32, replace=False)) for _ in range(h)]).astype(np.int32)).cuda()
@@ -174,7 +174,7 @@ def test_attn_keep_all_is_dense(ctx):
 def test_attn_is_deterministic(ctx):
     t = synth.attn_layer(37, 2, 300, 128, 2, 64, dtype="bf16")
     g = {nm: dev(a, "bf16") for nm, a in t.items()}
-    blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g["bq"], g["bk"], g["bv"], g["bo"], 2, 64, rope=False)
+    blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g["bq"], g["bk"], g["bv"], g["bo"], 2, 64, rope=False, bias_grads=True)
     idx = torch.arange(0, 64, 2, dtype=torch.int32).repeat(2, 1).cuda()
     blk.compact(idx, idx).alloc(2, 300)
     outs = []
@@ -189,7 +189,7 @@ def test_attn_is_deterministic(ctx):
 def test_attn_fp32_is_reported_unsupported(ctx):
     t = synth.attn_layer(38, 1, 16, 64, 2, 32, dtype="f32")
     g = {nm: dev(a, "f32") for nm, a in t.items()}
-    blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], None, None, None, None, 2, 32, rope=False)
+    blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], None, None, None, None, 2, 32, rope=False, bias_grads=True)
     idx = torch.arange(16, dtype=torch.int32).repeat(2, 1).cuda()
     blk.compact(idx, idx).alloc(1, 16)
     with pytest.raises(B.EcospaError) as e:

@@ -149,3 +149,43 @@ def test_contract_bf16_register_staged_prefetch_split_k(ctx):
     a, b, bias, want = _operands(48, 264, 520, 1024, False, True, "bf16")
     got = ctx.ecospa_contract(dev(a, "bf16"), False, dev(b, "bf16"), True, dev(bias, "bf16"), tile=20, splits=4)
     assert_close(got, want, "bf16", "split k")
+
+
+RS_SHAPES = [(256, 256), (192, 256), (256, 192), (128, 256), (256, 128), (192, 192), (128, 192), (192, 128), (128, 128)]
+
+
+@pytest.mark.parametrize("shape", range(9), ids=[f"{a}x{b}" for a, b in RS_SHAPES])
+@pytest.mark.parametrize("M,N,K,splits", [(520, 264, 192, 1),      # ragged M and N, three slabs (slab pair + tail)
+                                           (256, 512, 64, 1),       # one slab
+                                           (304, 136, 128, 1),      # two slabs
+                                           (1000, 776, 640, 1),     # several tiles on both axes, ten slabs
+                                           (392, 648, 320, 3),      # five slabs split 2 + 2 + 1
+                                           (200, 1048, 1024, 4)])
+def test_contract_bf16_weight_gradient_tile_shapes(ctx, M, N, K, splits, shape):
+    """dY^T X (both operands K-slow) on every tile shape of the register-prefetch kernel (tile = 30 + shape), with the
+    column sums of the A operand that the backward passes take from the same launch (the bias gradient)."""
+    a, b, _, _ = _operands(51, M, N, K, True, True, "bf16")
+    want = a.astype(np.float64).T @ b.astype(np.float64)
+    got, cs = ctx.ecospa_contract_colsum(dev(a, "bf16"), dev(b, "bf16"), tile=30 + shape, splits=splits)
+    assert_close(got, want, "bf16", f"{RS_SHAPES[shape]} x{splits}")
+    assert_close(cs, a.astype(np.float64).sum(axis=0), "f32", "column sums of A")
+    again, cs2 = ctx.ecospa_contract_colsum(dev(a, "bf16"), dev(b, "bf16"), tile=30 + shape, splits=splits)
+    assert torch.equal(got, again) and torch.equal(cs, cs2)
+
+
+@pytest.mark.parametrize("M,N,K", [(1024, 2048, 8192), (1536, 1024, 8192), (5504, 2048, 4096), (2048, 2752, 4096), (3072, 2048, 4096),
+                                   (2048, 1024, 4096), (4096, 1024, 8192), (520, 264, 1088)])
+def test_contract_weight_gradient_own_plan(ctx, M, N, K):
+    """The layers' weight-gradient shapes through the library's own choice of tile shape and K split: sampled outputs in
+    fp64 from the same operands, and the fused column sums of A."""
+    a = synth.round_to(synth.normal(52, 320, (K, M)), "bf16")
+    b = synth.round_to(synth.normal(52, 321, (K, N)), "bf16")
+    got, cs = ctx.ecospa_contract_colsum(dev(a, "bf16"), dev(b, "bf16"))
+    rng = np.random.default_rng(M * 7 + N)
+    edge = lambda n: [0, n - 1, n // 256 * 256 - 1, min(n - 1, n // 256 * 256), n // 192 * 192 - 1, min(n - 1, n // 192 * 192)]
+    ms = np.unique(np.concatenate([rng.choice(M, 90, replace=False), edge(M)]))
+    ns = np.unique(np.concatenate([rng.choice(N, 90, replace=False), edge(N)]))
+    want = a[:, ms].astype(np.float64).T @ b[:, ns].astype(np.float64)
+    block = host(got[torch.from_numpy(ms).cuda()][:, torch.from_numpy(ns).cuda()])
+    assert_close(block, want, "bf16", "sampled block")
+    assert_close(cs, a.astype(np.float64).sum(axis=0), "f32", "column sums of A")

@@ -34,7 +34,7 @@ def run_ffn_case(ctx, seed, Bsz, L, d, n, k, act, dtype, structure="scratch", bi
     v = O.coupled_score(kind, t["w1"], t["w2"], 1, n, w1b=t.get("w1b"))
     idx_np = O.select_topk(v.astype(np.float32), k)
     g = {nm: dev(a, dtype) for nm, a in t.items()}
-    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), ACT[act][0], g.get("w1b"), transposed=transposed)
+    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), ACT[act][0], g.get("w1b"), transposed=transposed, bias_grads=True)
     blk.compact(torch.from_numpy(idx_np).cuda()).alloc(Bsz, L)
     kp = blk.kp
     y = blk.fwd(g["x"])
@@ -96,7 +96,7 @@ def test_ffn_forward_only_keeps_nothing_and_agrees(ctx, act, dtype, T, d, n, k):
     rng = np.random.default_rng(T)
     idx = torch.from_numpy(np.sort(rng.choice(n, k, replace=False)).astype(np.int32)[None, :]).cuda()
     g = {nm: dev(a, dtype) for nm, a in t.items()}
-    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), ACT[act][0], g.get("w1b"))
+    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), ACT[act][0], g.get("w1b"), bias_grads=True)
     blk.compact(idx).alloc(1, T)
     y_train = blk.fwd(g["x"]).clone()
     blk.hpre.fill_(float("nan"))
@@ -114,7 +114,7 @@ def test_ffn_backward_with_optional_outputs(ctx, act):
     t = synth.ffn_layer(34, T, d, n, gated=act == "swiglu", dtype="bf16")
     g = {nm: dev(a, "bf16") for nm, a in t.items()}
     idx = torch.from_numpy(np.sort(np.random.default_rng(5).choice(n, k, replace=False)).astype(np.int32)[None, :]).cuda()
-    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), ACT[act][0], g.get("w1b"))
+    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), ACT[act][0], g.get("w1b"), bias_grads=True)
     blk.compact(idx).alloc(1, T)
     blk.fwd(g["x"])
     dx = blk.bwd(g["x"], g["dy"]).clone()
@@ -177,7 +177,7 @@ def test_ffn_c1_fp32_whole_chain(ctx):
     k = synth.keep_count(n, 1, 2)
     t = synth.ffn_layer(cfg["seed"], T, d, n, dtype="f32")
     g = {nm: dev(a) for nm, a in t.items()}
-    blk = FfnBlock(ctx, g["w1"], g["b1"], g["w2"], g["b2"], B.ACT_GELU_ERF)
+    blk = FfnBlock(ctx, g["w1"], g["b1"], g["w2"], g["b2"], B.ACT_GELU_ERF, bias_grads=True)
     sc = blk.score()
     want_sc = O.coupled_score(O.PAIR_FFN, t["w1"], t["w2"], 1, n)
     assert_close(sc, want_sc, "f32", "score")
@@ -209,7 +209,7 @@ def test_ffn_scattered_gradients_equal_masked_dense(ctx):
     idx_np = O.select_topk(v.astype(np.float32), k)
     idx = torch.from_numpy(idx_np).cuda()
     g = {nm: dev(a, dtype) for nm, a in t.items()}
-    blk = FfnBlock(ctx, g["w1"], g["b1"], g["w2"], g["b2"], B.ACT_GELU_ERF).compact(idx).alloc(1, T)
+    blk = FfnBlock(ctx, g["w1"], g["b1"], g["w2"], g["b2"], B.ACT_GELU_ERF, bias_grads=True).compact(idx).alloc(1, T)
     blk.fwd(g["x"])
     blk.bwd(g["x"], g["dy"])
     full_dw1 = ctx.ecospa_scatter(blk.dw1_c, idx, 0, 1, n, 1, blk.kp)
@@ -227,7 +227,7 @@ def test_ffn_is_deterministic(ctx):
     t = synth.ffn_layer(25, 512, 128, 256, dtype="bf16")
     g = {nm: dev(a, "bf16") for nm, a in t.items()}
     idx = torch.arange(0, 256, 2, dtype=torch.int32).view(1, -1).cuda()
-    blk = FfnBlock(ctx, g["w1"], g["b1"], g["w2"], g["b2"], B.ACT_GELU_ERF).compact(idx).alloc(2, 256)
+    blk = FfnBlock(ctx, g["w1"], g["b1"], g["w2"], g["b2"], B.ACT_GELU_ERF, bias_grads=True).compact(idx).alloc(2, 256)
     outs = []
     for _ in range(2):
         blk.fwd(g["x"])

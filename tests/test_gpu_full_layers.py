@@ -73,10 +73,13 @@ def test_full_layer_step_matches_oracle(ctx, name, num, den):
     assert_close(lay.attn.dwqkv_c, want_dwqkv, "bf16", "dW_qkv")
     want_dwo = pad_cols(np.concatenate(list(ga["dwo"]), axis=1), h, kv, kpv)
     assert_close(lay.attn.dwo_c, want_dwo, "bf16", "dW_o")
-    assert_close(lay.attn.dbo, ga["dbo"], "bf16", "db_o")
-    want_db = np.concatenate([pad_rows(ga["dbq"].reshape(-1, 1), h, kq, kpq), pad_rows(ga["dbk"].reshape(-1, 1), h, kq, kpq),
-                              pad_rows(ga["dbv"].reshape(-1, 1), h, kv, kpv)])[:, 0]
-    assert_close(lay.attn.dbqkv_c, want_db, "bf16", "db_qkv")
+    if cfg["bias"]:      # a block without biases asks for no bias gradients
+        assert_close(lay.attn.dbo, ga["dbo"], "bf16", "db_o")
+        want_db = np.concatenate([pad_rows(ga["dbq"].reshape(-1, 1), h, kq, kpq), pad_rows(ga["dbk"].reshape(-1, 1), h, kq, kpq),
+                                  pad_rows(ga["dbv"].reshape(-1, 1), h, kv, kpv)])[:, 0]
+        assert_close(lay.attn.dbqkv_c, want_db, "bf16", "db_qkv")
+    else:
+        assert lay.attn.dbo is None and lay.attn.dbqkv_c is None
 
     # FFN block on the attention output the GPU produced
     x2 = host(lay.attn.y)
@@ -94,8 +97,8 @@ def test_full_layer_step_matches_oracle(ctx, name, num, den):
         want_dw1 = np.concatenate([want_dw1, pad_rows(gf["dw1b"], 1, kf, kpf)])
     assert_close(lay.ffn.dw1_c, want_dw1, "bf16", "dW_1")
     assert_close(lay.ffn.dw2_c, pad_cols(gf["dw2"], 1, kf, kpf), "bf16", "dW_2")
-    assert_close(lay.ffn.db2, gf["db2"], "bf16", "db_2")
-    if not cfg["gated"]:
+    if cfg["bias"]:
+        assert_close(lay.ffn.db2, gf["db2"], "bf16", "db_2")
         assert_close(lay.ffn.db1_c, want_db1, "bf16", "db_1")
 
 

@@ -77,7 +77,7 @@ def test_gqa_attention_block(ctx, h, hkv, d, k_qk, k_vo, rope, causal, L):
     t = _gqa_layer(120 + h, Bsz, L, d, h, hkv, dh, dtype, bias)
     g = {nm: dev(a, dtype) for nm, a in t.items()}
     blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g.get("bq"), g.get("bk"), g.get("bv"), g.get("bo"),
-                    h, dh, rope=rope, causal=causal, h_kv=hkv)
+                    h, dh, rope=rope, causal=causal, h_kv=hkv, bias_grads=True)
     s_qk, s_vo = blk.score()
     iq_d = ctx.ecospa_select_topk(s_qk, k_qk // unit)
     iv_d = ctx.ecospa_select_topk(s_vo, k_vo)

@@ -165,7 +165,7 @@ def test_attention_block_with_a_kept_count_per_head(ctx, rope, theta):
     unit = 2 if rope else 1
     g = {nm: dev(a, dtype) for nm, a in t.items()}
     blk = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g.get("bq"), g.get("bk"), g.get("bv"), g.get("bo"),
-                    h, dh, rope=rope, causal=True)
+                    h, dh, rope=rope, causal=True, bias_grads=True)
     s_qk, s_vo = blk.score()
     iq_d, kq_d = ctx.ecospa_select_theta(s_qk, theta)
     iv_d, kv_d = ctx.ecospa_select_theta(s_vo, theta)
@@ -227,7 +227,7 @@ def test_ffn_block_with_the_threshold_rule(ctx, gated):
     t = synth.ffn_layer(51, T, d, n, gated=gated, dtype=dtype, structure="pretrained", bias=not gated)
     g = {nm: dev(a, dtype) for nm, a in t.items()}
     act = B.ACT_SWIGLU if gated else B.ACT_GELU_ERF
-    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), act, g.get("w1b"))
+    blk = FfnBlock(ctx, g["w1"], g.get("b1"), g["w2"], g.get("b2"), act, g.get("w1b"), bias_grads=True)
     s = blk.score()
     idx_d, k_d = ctx.ecospa_select_theta(s, theta)
     idx, k = O.select_theta(s.cpu().numpy(), theta)
@@ -260,8 +260,8 @@ def test_blocks_follow_a_change_of_width_between_compactions(ctx):
     tf = synth.ffn_layer(61, Bsz * L, d, n, gated=False, dtype=dtype, structure="pretrained", bias=True)
     ga = {nm: dev(a, dtype) for nm, a in ta.items()}
     gf = {nm: dev(a, dtype) for nm, a in tf.items()}
-    attn = AttnBlock(ctx, ga["wq"], ga["wk"], ga["wv"], ga["wo"], None, None, None, None, h, dh, rope=True, causal=True, transposed=True)
-    ffn = FfnBlock(ctx, gf["w1"], gf["b1"], gf["w2"], gf["b2"], B.ACT_GELU_ERF, transposed=True)
+    attn = AttnBlock(ctx, ga["wq"], ga["wk"], ga["wv"], ga["wo"], None, None, None, None, h, dh, rope=True, causal=True, transposed=True, bias_grads=True)
+    ffn = FfnBlock(ctx, gf["w1"], gf["b1"], gf["w2"], gf["b2"], B.ACT_GELU_ERF, transposed=True, bias_grads=True)
     s_qk, s_vo = attn.score()
     s_ff = ffn.score()
     scale = dh ** -0.5
