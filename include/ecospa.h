@@ -107,6 +107,18 @@ size_t ecospa_score_workspace_bytes(const ecospa_pair* pairs /*host*/, int n_pai
 int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs /*host*/, int n_pairs,
                          float* const* scores /*host*/);
 
+/* ecospa_coupled_score for callers that cannot allocate device memory or attach a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same scores from the same kernels, with the
+ * partial sums kept in a fixed array inside the library's device image (2 MiB per GPU, held until the process ends;
+ * ecospa_coupled_score_static_max_bytes() returns the limit).  The call allocates nothing and does not touch the
+ * context's workspace.  A batch whose ecospa_score_workspace_bytes() exceeds the limit -> ERR_WORKSPACE, before
+ * anything is launched (2 MiB holds about six LLaMA-1B-shaped layers' pairs; larger batches go through
+ * ecospa_coupled_score).  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two contexts) race; calls on one stream are ordered and safe.  Other errors as ecospa_coupled_score. */
+size_t ecospa_coupled_score_static_max_bytes(void);
+int ecospa_coupled_score_static(ecospa_ctx* ctx, const ecospa_pair* pairs /*host*/, int n_pairs,
+                                float* const* scores /*host*/);
+
 /* ------------------------------------------------------------------------------------------
  * Step 2 - keep the k most important units of every group (Sec. 3.2: "rank upsilon_i ... remove
  * those insignificant pairs"; Alg. 1's removal loop with the count fixed by the caller).

@@ -29,6 +29,7 @@ EXPORTS = (
     "ecospa_select_topk_batch", "ecospa_compact_batch", "ecospa_pair_fisher", "ecospa_select_theta",
     "ecospa_select_pairs", "ecospa_rope_table_ragged", "ecospa_adamw", "ecospa_transpose_batch",
     "ecospa_check_indices", "ecospa_contract_workspace_bytes", "ecospa_hbm_probe", "ecospa_contract_colsum",
+    "ecospa_coupled_score_static", "ecospa_coupled_score_static_max_bytes",
 )
 
 
@@ -161,6 +162,10 @@ def load() -> C.CDLL:
     lib.ecospa_check_indices.restype = ci
     lib.ecospa_contract_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.ecospa_contract_workspace_bytes.restype = sz
+    lib.ecospa_coupled_score_static.argtypes = [vp, C.POINTER(Pair), ci, C.POINTER(vp)]
+    lib.ecospa_coupled_score_static.restype = ci
+    lib.ecospa_coupled_score_static_max_bytes.argtypes = []
+    lib.ecospa_coupled_score_static_max_bytes.restype = sz
     lib.ecospa_contract_colsum.argtypes = [vp, ci, ci, ci, vp, ll, vp, ll, vp, ll, vp, ci, ci]
     lib.ecospa_contract_colsum.restype = ci
     lib.ecospa_hbm_probe.argtypes = [vp, vp, vp, sz, ci]
@@ -285,6 +290,14 @@ class Context:
             out = [torch.empty((p.groups, p.n // max(p.unit, 1)), dtype=torch.float32, device=self.device) for p in arr]
         ptrs = (C.c_void_p * len(arr))(*[o.data_ptr() for o in out])
         self._check(self.lib.ecospa_coupled_score(self.h, arr, len(arr), ptrs), "ecospa_coupled_score")
+        return list(out)
+
+    def ecospa_coupled_score_static(self, pairs: Sequence[Pair], out: Sequence[torch.Tensor]) -> list[torch.Tensor]:
+        """ecospa_coupled_score for callers that cannot allocate: the caller brings the score tensors, the partial sums
+        live in the library's own fixed device array (nothing is reserved or allocated here)."""
+        arr = pairs if isinstance(pairs, C.Array) else (Pair * len(pairs))(*pairs)
+        ptrs = (C.c_void_p * len(arr))(*[o.data_ptr() for o in out])
+        self._check(self.lib.ecospa_coupled_score_static(self.h, arr, len(arr), ptrs), "ecospa_coupled_score_static")
         return list(out)
 
     def ecospa_pair_fisher(self, grads: Sequence[Pair], n_samples: float,

@@ -387,8 +387,7 @@ extern "C" size_t ecospa_score_workspace_bytes(const ecospa_pair* pairs, int n_p
 }
 
 // Shared driver of Eq. 10 (fisher = 0: `pairs` are weights) and Eq. 8 (fisher = 1: `pairs` are gradients).
-static int score_run(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, float* const* scores, int fisher,
-                     float n_samples) {
+static int score_validate(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, float* const* scores) {
   if (!ctx || !pairs || !scores) return ECOSPA_ERR_NULL;
   if (n_pairs < 1) return ECOSPA_ERR_SHAPE;
   for (int i = 0; i < n_pairs; ++i) {
@@ -396,9 +395,16 @@ static int score_run(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, flo
     if (rc) return rc;
     if (!scores[i]) return ECOSPA_ERR_NULL;
   }
+  return ECOSPA_OK;
+}
+
+// `scratch` / `scratch_bytes`: device memory for the partial squared sums (the caller's workspace, or the library's
+// own fixed array); the arguments have been validated.
+static int score_run(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, float* const* scores, int fisher,
+                     float n_samples, void* scratch, size_t scratch_bytes) {
   const size_t need = ecospa_score_workspace_bytes(pairs, n_pairs);
-  if (!ctx->ws || ctx->ws_bytes < need) return ECOSPA_ERR_WORKSPACE;
-  WsCarver ws(ctx->ws, ctx->ws_bytes);
+  if (!scratch || scratch_bytes < need) return ECOSPA_ERR_WORKSPACE;
+  WsCarver ws(scratch, scratch_bytes);
 
   for (int first = 0; first < n_pairs; first += SCORE_MAX_PAIRS) {
     ScoreBatch b;
@@ -450,11 +456,65 @@ static int score_run(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, flo
 }
 
 extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, float* const* scores) {
-  return score_run(ctx, pairs, n_pairs, scores, 0, 1.f);
+  const int rc = score_validate(ctx, pairs, n_pairs, scores);
+  if (rc) return rc;
+  return score_run(ctx, pairs, n_pairs, scores, 0, 1.f, ctx->ws, ctx->ws_bytes);
 }
 
 extern "C" int ecospa_pair_fisher(ecospa_ctx* ctx, const ecospa_pair* grads, int n_pairs, float n_samples,
                                   float* const* fisher) {
   if (!(n_samples > 0.f)) return ECOSPA_ERR_SHAPE;
-  return score_run(ctx, grads, n_pairs, fisher, 1, n_samples);
+  const int rc = score_validate(ctx, grads, n_pairs, fisher);
+  if (rc) return rc;
+  return score_run(ctx, grads, n_pairs, fisher, 1, n_samples, ctx->ws, ctx->ws_bytes);
+}
+
+// ------------------------------------------------------------------------------------------
+// The same scores for callers that can neither allocate device memory nor hand over a workspace: the partial
+// squared sums live in a fixed array in the library's own device image.  Host code never uses the array's name
+// as an address: the device address is asked for once per device and kept.
+#define SCORE_STATIC_BYTES (2u << 20)
+static __device__ __align__(256) unsigned char scratch[SCORE_STATIC_BYTES];
+
+#define SCORE_MAX_DEVICES 64
+static void* scratch_dev_ptr[SCORE_MAX_DEVICES];       // per device ordinal; written once, under the lock
+static std::atomic<unsigned long long> scratch_known{0};
+static std::atomic_flag scratch_lock = ATOMIC_FLAG_INIT;
+
+// Device address of `scratch` on the current device (asked for on the first call there).
+static hipError_t score_static_ptr(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= SCORE_MAX_DEVICES) return hipErrorInvalidDevice;
+  const unsigned long long bit = 1ull << dev;
+  if (!(scratch_known.load(std::memory_order_acquire) & bit)) {
+    while (scratch_lock.test_and_set(std::memory_order_acquire)) {}
+    if (!(scratch_known.load(std::memory_order_relaxed) & bit)) {
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e == hipSuccess) {
+        scratch_dev_ptr[dev] = p;
+        scratch_known.fetch_or(bit, std::memory_order_release);
+      }
+    }
+    scratch_lock.clear(std::memory_order_release);
+    if (e != hipSuccess) return e;
+  }
+  *out = scratch_dev_ptr[dev];
+  return hipSuccess;
+}
+
+extern "C" size_t ecospa_coupled_score_static_max_bytes(void) { return SCORE_STATIC_BYTES; }
+
+extern "C" int ecospa_coupled_score_static(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, float* const* scores) {
+  const int rc = score_validate(ctx, pairs, n_pairs, scores);
+  if (rc) return rc;
+  if (ecospa_score_workspace_bytes(pairs, n_pairs) > SCORE_STATIC_BYTES) return ECOSPA_ERR_WORKSPACE;
+  void* p = nullptr;
+  const hipError_t e = score_static_ptr(&p);
+  if (e != hipSuccess) return hip_fail(ctx, e, "hipGetSymbolAddress(scratch)");
+  // every slot of the partial sums that the finishing launch reads is written by the first launch of the same call,
+  // so nothing has to be cleared between calls
+  return score_run(ctx, pairs, n_pairs, scores, 0, 1.f, p, SCORE_STATIC_BYTES);
 }

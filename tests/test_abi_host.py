@@ -180,3 +180,22 @@ def test_contract_workspace_query(lib):
     # an output as large as a vocabulary projection: the library's own choice never reserves tens of gigabytes
     assert q(B.BF16, 8192, 32000, 2048, 0) <= 8 * 8192 * 32000 * 4
     assert q(7, 8, 8, 8, 0) == 0 and q(B.BF16, 0, 8, 8, 0) == 0 and q(B.BF16, 8, 8, 8, 65) == 0
+
+
+def test_static_scratch_score_validates_before_touching_the_device(lib, ctx):
+    """The entry point that allocates nothing: bad arguments and batches beyond its fixed scratch array are refused by
+    host checks alone (no GPU is needed to get these answers)."""
+    f = lib.ecospa_coupled_score_static
+    assert lib.ecospa_coupled_score_static_max_bytes() == 2 << 20
+    p = B.Pair(B.PAIR_FFN, B.F32, 1, 8, 1, 4, 4, 256, None, 512, 4, 0, 8)
+    arr = (B.Pair * 1)(p)
+    out = (C.c_void_p * 1)(1024)
+    assert f(None, arr, 1, out) == B.ERR_NULL
+    assert f(ctx, None, 1, out) == B.ERR_NULL
+    assert f(ctx, arr, 0, out) == B.ERR_SHAPE
+    assert f(ctx, arr, 1, (C.c_void_p * 1)(None)) == B.ERR_NULL
+    bad = B.Pair(B.PAIR_FFN, B.F32, 1, 8, 3, 4, 4, 256, None, 512, 4, 0, 8)
+    assert f(ctx, (B.Pair * 1)(bad), 1, out) == B.ERR_SHAPE
+    big = B.Pair(B.PAIR_FFN, B.F32, 1, 300000, 1, 8, 8, 256, None, 512, 8, 0, 300000)
+    assert lib.ecospa_score_workspace_bytes((B.Pair * 1)(big), 1) > lib.ecospa_coupled_score_static_max_bytes()
+    assert f(ctx, (B.Pair * 1)(big), 1, out) == B.ERR_WORKSPACE
