@@ -341,6 +341,23 @@ def layer_workload(ctx, name, steps, warmup, h_kv=None, detail=True):
     return out
 
 
+def mfma_ceiling(ctx):
+    """What the matrix units alone sustain on this GPU with operands like the workload's (N(0, 1) bf16 values): about
+    0.1 s of back-to-back pure-MFMA launches, so that the clock has settled under the power limit."""
+    import torch
+    src = torch.randn(65536, device="cuda").to(torch.bfloat16)
+    sink = torch.empty(65536, dtype=torch.float32, device="cuda")
+    zero = torch.zeros_like(src)
+    out = {}
+    for nm, buf in (("normal_operands", src), ("zero_operands", zero)):
+        fl = ctx.ecospa_mfma_probe(buf, sink, 2000)
+        ms = timed_gpu(torch, lambda: ctx.ecospa_mfma_probe(buf, sink, 2000), 60, 20)
+        out[nm + "_tflops"] = fl / (ms * 1e-3) / 1e12
+    out["note"] = ("pure v_mfma_f32_32x32x16_bf16 loop on all 1024 SIMDs, no memory traffic, same run; with all-zero operands the "
+                   "matrix units draw less power and the clock stays higher")
+    return out
+
+
 def hbm_ceilings(ctx, nbytes, steps=10):
     """What plain kernels reach on this GPU over a buffer of the size the 24-layer pruning pass reads: a streaming read
     and a 1:1 copy (the library's own probe kernels and, for the copy, torch's device copy as a second opinion)."""
@@ -629,6 +646,7 @@ def main():
                        "frac_of_copy_ceiling_kept": prune["compact"]["kept_gbs"] / max(ceil["copy_gbs"], ceil["torch_copy_gbs"]),
                        "frac_of_copy_ceiling_traffic": prune["compact"]["traffic_gbs"] / max(ceil["copy_gbs"], ceil["torch_copy_gbs"])}}
 
+    mfma = mfma_ceiling(ctx)
     out = {
         "metric": METRIC, "value": T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
@@ -658,6 +676,8 @@ def main():
                               "speedup_fwd_bwd_vs_dense": second["speedup_fwd_bwd_vs_dense"],
                               "model_tflops_fwd_bwd": second["fwd_bwd"]["model_tflops"],
                               "attention_core_fwd_us": second["attention_core"]["fwd_us"], "parts_ms": second["parts_ms"]},
+                     "sustained_mfma": mfma,
+                     "frac_of_sustained_mfma": gm["achieved"] / mfma["normal_operands_tflops"],
                      "hbm": hbm},
         "also": second,
         "prune_24_layers": prune,

@@ -67,6 +67,14 @@ int ecospa_profile_gemm_read(ecospa_ctx* ctx, int* launches, double* total_ms, d
  * Errors: ERR_NULL, ERR_SHAPE (mode, bytes), ERR_ALIGN. */
 int ecospa_hbm_probe(ecospa_ctx* ctx, const void* src, void* dst, size_t bytes, int mode);
 
+/* Measurement aid: what the matrix units alone sustain on this GPU.  256 workgroups of four wavefronts (one per SIMD of
+ * every compute unit) each issue `iters` rounds of 16 independent bf16 32x32x16 MFMAs on operand bits taken from src
+ * (64 KiB, e.g. normally distributed bf16 values: the power the matrix units draw, and with it the clock the GPU
+ * settles at, depends on the operand bits), with no memory traffic inside the loop.  sink: float[65536], written once.
+ * *flop (host, may be NULL) receives the flops of the launch.  The caller times it.  Errors: ERR_NULL, ERR_SHAPE
+ * (iters outside [1, 2^24]), ERR_ALIGN. */
+int ecospa_mfma_probe(ecospa_ctx* ctx, const void* src, float* sink, int iters, double* flop /*host*/);
+
 /* ------------------------------------------------------------------------------------------
  * Step 1 - per-dimension coupled importance score (paper Eq. 10; selection criterion Eq. 12).
  *
@@ -302,8 +310,9 @@ int ecospa_rope_table_ragged(ecospa_ctx* ctx, const int* idx, int ld_idx, const 
  *         launched).  h_kv = key/value heads: h for multi-head
  *         attention (0 means h); under grouped-query attention (Eq. 5) h_kv divides h and query head i
  *         attends with key/value head i / (h / h_kv).
- *   FFN:  w_1 [kp_ff, d_model] (SWIGLU: [2*kp_ff, d_model], gate rows then up rows); b_1 same
- *         length or NULL; w_2 [d_model, kp_ff]; b_2.  kp_ff is a multiple of 16.
+ *   FFN:  w_1 [kp_ff, d_model] (SWIGLU: [2*kp_ff, d_model], row 2i = gate unit i, row 2i+1 = up unit i, so that a
+ *         tile of the first contraction holds whole (gate, up) pairs and the product is formed in its epilogue);
+ *         b_1 same length and order or NULL; w_2 [d_model, kp_ff]; b_2.  kp_ff is a multiple of 16.
  * scale is the softmax scale (1/sqrt(original d_h) keeps "compact = masked dense").
  * rope_cos/rope_sin: float[h_kv, L, kp_qk/2] from ecospa_rope_table (one row of angles per key/value head:
  * the query heads that share it keep the same rotary blocks), or NULL for no rotation; pairs are
@@ -338,7 +347,8 @@ typedef struct {
  *   ATTN: qkv [T, (h + h_kv)*kp_qk + h_kv*kp_vo] (Q and K after bias and rotation, V after bias),
  *         o [T, h*kp_vo] (per-head attention output), lse float[B*h*L] (log-sum-exp of the
  *         scaled, masked scores per query).
- *   FFN:  hpre [T, kp_ff] (SWIGLU: [T, 2*kp_ff], gate then up pre-activations), act [T, kp_ff]. */
+ *   FFN:  hpre [T, kp_ff] (SWIGLU: [T, 2*kp_ff], (gate, up) pre-activation pairs in the order of w_1's rows),
+ *         act [T, kp_ff]. */
 typedef struct {
   void *qkv, *o;
   float* lse;

@@ -28,7 +28,7 @@ EXPORTS = (
     "ecospa_coupled_bwd", "ecospa_profile_gemm", "ecospa_profile_gemm_read", "ecospa_contract",
     "ecospa_select_topk_batch", "ecospa_compact_batch", "ecospa_pair_fisher", "ecospa_select_theta",
     "ecospa_select_pairs", "ecospa_rope_table_ragged", "ecospa_adamw", "ecospa_transpose_batch",
-    "ecospa_check_indices", "ecospa_contract_workspace_bytes", "ecospa_hbm_probe", "ecospa_contract_colsum",
+    "ecospa_check_indices", "ecospa_contract_workspace_bytes", "ecospa_hbm_probe", "ecospa_contract_colsum", "ecospa_mfma_probe",
     "ecospa_coupled_score_static", "ecospa_coupled_score_static_max_bytes",
 )
 
@@ -168,6 +168,8 @@ def load() -> C.CDLL:
     lib.ecospa_coupled_score_static_max_bytes.restype = sz
     lib.ecospa_contract_colsum.argtypes = [vp, ci, ci, ci, vp, ll, vp, ll, vp, ll, vp, ci, ci]
     lib.ecospa_contract_colsum.restype = ci
+    lib.ecospa_mfma_probe.argtypes = [vp, vp, vp, ci, C.POINTER(C.c_double)]
+    lib.ecospa_mfma_probe.restype = ci
     lib.ecospa_hbm_probe.argtypes = [vp, vp, vp, sz, ci]
     lib.ecospa_hbm_probe.restype = ci
     _lib = lib
@@ -240,6 +242,13 @@ class Context:
         """Measurement aid: read src once (copy=False; dst is a small sink) or copy it to dst."""
         nbytes = src.numel() * src.element_size()
         self._check(self.lib.ecospa_hbm_probe(self.h, src.data_ptr(), dst.data_ptr(), nbytes, int(copy)), "ecospa_hbm_probe")
+
+    def ecospa_mfma_probe(self, src: torch.Tensor, sink: torch.Tensor, iters: int) -> float:
+        """Measurement aid: launch the pure-MFMA loop on operand bits from src (>= 64 KiB); returns the flops of the launch."""
+        assert src.numel() * src.element_size() >= 65536 and sink.dtype == torch.float32 and sink.numel() >= 65536
+        fl = C.c_double()
+        self._check(self.lib.ecospa_mfma_probe(self.h, src.data_ptr(), sink.data_ptr(), int(iters), C.byref(fl)), "ecospa_mfma_probe")
+        return fl.value
 
     def ecospa_contract(self, A: torch.Tensor, trans_a: bool, Bm: torch.Tensor, trans_b: bool,
                         bias: Optional[torch.Tensor] = None, tile: int = 0, splits: int = 0,

@@ -37,6 +37,8 @@ struct AttnArgs {
   float scale;
   int h_kv;            // key/value heads (grouped-query attention, Eq. 5: query head i uses key/value head i / qpk)
   int qpk;             // query heads per key/value head, h / h_kv (1: multi-head attention)
+  const float *rope_cos, *rope_sin;   // backward: tables [h_kv, L, kp_qk / 2] of the rotary form (Eq. 6), or null - the gradients
+                                      // of the rotated Q and K are turned back (angle -t theta) as they are written
 };
 // Column offsets inside a row of the qkv buffer: Q heads, then the key heads, then the value heads.
 __device__ __forceinline__ int k_col(const AttnArgs& a, int kv_head) { return a.h * a.kp_qk + kv_head * a.kp_qk; }
@@ -199,6 +201,35 @@ __device__ __forceinline__ void tile_to_global(const bf16_t* tile, int rows, bf1
     const int r = c / (D / 8), ch = c % (D / 8);
     if (r < rows_valid && ch * 8 < kp)
       *reinterpret_cast<u32x4*>(base + (row0 + r) * ld + ch * 8) = *reinterpret_cast<const u32x4*>(tile + nat_off<D>(r, ch));
+  }
+}
+// The same for gradients of rotated queries or keys: every adjacent pair (2i, 2i+1) of token t is turned by -angle(t, i)
+// on the way out (Eq. 6: the forward pass turned Q and K by +angle).  tab: the head's rows of the tables, [L][kp / 2];
+// pos0: position in the sequence of tile row 0.
+template <int D>
+__device__ __forceinline__ void tile_to_global_unrope(const bf16_t* tile, int rows, bf16_t* __restrict__ base, long long ld,
+                                                      long long row0, int rows_valid, int kp, const float* __restrict__ cs,
+                                                      const float* __restrict__ sn, int pos0) {
+  for (int c = threadIdx.x; c < rows * (D / 8); c += 256) {
+    const int r = c / (D / 8), ch = c % (D / 8);
+    if (r < rows_valid && ch * 8 < kp) {
+      const u32x4 x = *reinterpret_cast<const u32x4*>(tile + nat_off<D>(r, ch));
+      const long long tab = static_cast<long long>(pos0 + r) * (kp / 2) + ch * 4;
+      const float4 c4 = *reinterpret_cast<const float4*>(cs + tab);
+      const float4 s4 = *reinterpret_cast<const float4*>(sn + tab);
+      const float cv[4] = {c4.x, c4.y, c4.z, c4.w}, sv[4] = {s4.x, s4.y, s4.z, s4.w};
+      const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+      typedef float floatx8 __attribute__((ext_vector_type(8)));
+      floatx8 y;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float x0 = __uint_as_float(w[i] << 16), x1 = __uint_as_float(w[i] & 0xffff0000u);
+        y[2 * i] = x0 * cv[i] + x1 * sv[i];
+        y[2 * i + 1] = x1 * cv[i] - x0 * sv[i];
+      }
+      const bf16x8_t b = __builtin_convertvector(y, bf16x8_t);
+      *reinterpret_cast<u32x4*>(base + (row0 + r) * ld + ch * 8) = __builtin_bit_cast(u32x4, b);
+    }
   }
 }
 // Park a transposed accumulator (column = token lane%32, rows = dims) in a natural LDS tile.
@@ -397,31 +428,6 @@ void attn_fwd_kernel(const AttnArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// delta[b,h,t] = sum_dv dO * O
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_delta_kernel(const AttnArgs a) {
-  const long long e = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
-  const long long T = static_cast<long long>(a.B) * a.L;
-  if (e >= T * a.h) return;
-  const long long tok = e / a.h;
-  const int head = static_cast<int>(e % a.h);
-  const bf16_t* o = a.o + tok * a.ld_o + head * a.kp_vo;
-  const bf16_t* g = a.d_o + tok * a.ld_o + head * a.kp_vo;
-  float s = 0.f;
-  for (int c = 0; c < a.kp_vo; c += 8) {
-    const u32x4 x = *reinterpret_cast<const u32x4*>(o + c), y = *reinterpret_cast<const u32x4*>(g + c);
-    const uint32_t xw[4] = {x.x, x.y, x.z, x.w}, yw[4] = {y.x, y.y, y.z, y.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      s += __uint_as_float(xw[i] << 16) * __uint_as_float(yw[i] << 16);
-      s += __uint_as_float(xw[i] & 0xffff0000u) * __uint_as_float(yw[i] & 0xffff0000u);
-    }
-  }
-  const int bb = static_cast<int>(tok / a.L), t = static_cast<int>(tok % a.L);
-  a.delta[(static_cast<long long>(bb) * a.h + head) * a.L + t] = s;
-}
-
-// ---------------------------------------------------------------------------------------------
 // backward, dQ: one workgroup per (128 queries, head, batch), loop over key tiles
 //   S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - delta), dQ^T += K^T dS^T
 // ---------------------------------------------------------------------------------------------
@@ -476,7 +482,27 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
   const int qw0 = q0 + wave * 32, q_idx = qw0 + l32;
   const long long stat = (static_cast<long long>(b) * a.h + head) * a.L;
   const float lse2 = q_idx < a.L ? a.lse[stat + q_idx] * LOG2E : 0.f;
-  const float dlt = q_idx < a.L ? a.delta[stat + q_idx] : 0.f;
+  // delta = rowsum(dO * O) of this lane's query: the lane holds its half of the dO row as MFMA fragments and fetches the
+  // matching pieces of the O row; the other half sits in lane ^ 32.  The kernel over key tiles reads the sums from memory.
+  float dlt = 0.f;
+  {
+    const bf16_t* orow = a.o + (tok0 + min(q_idx, a.L - 1)) * a.ld_o + head * a.kp_vo;
+#pragma unroll
+    for (int s = 0; s < DV / 16; ++s) {
+      const int dim = 16 * s + 8 * hh;
+      const u32x4 ov = *reinterpret_cast<const u32x4*>(orow + min(dim, a.kp_vo - 8));
+      const u32x4 gv = __builtin_bit_cast(u32x4, dof[s]);
+      float part = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        part += __uint_as_float(ov[i] << 16) * __uint_as_float(gv[i] << 16);
+        part += __uint_as_float(ov[i] & 0xffff0000u) * __uint_as_float(gv[i] & 0xffff0000u);
+      }
+      dlt += dim < a.kp_vo ? part : 0.f;       // dims beyond the kept width: dO was zeroed there, O's stand-in is dropped
+    }
+    dlt += __shfl_xor(dlt, 32, 64);
+    if (hh == 0 && q_idx < a.L) a.delta[stat + q_idx] = dlt;
+  }
   const float sc = a.scale * LOG2E;
 
   floatx16 dq[DQ / 32];
@@ -540,7 +566,12 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
 #pragma unroll
   for (int u = 0; u < DQ / 32; ++u) acc_to_tile<DQ>(Qs, wave * 32 + l32, u, dq[u], a.scale, hh);
   __syncthreads();
-  tile_to_global<DQ>(Qs, 128, a.dqkv + head * a.kp_qk, a.ld_qkv, tok0 + q0, a.L - q0, a.kp_qk);
+  if (a.rope_cos) {
+    const long long tb = static_cast<long long>(head / a.qpk) * a.L * (a.kp_qk / 2);
+    tile_to_global_unrope<DQ>(Qs, 128, a.dqkv + head * a.kp_qk, a.ld_qkv, tok0 + q0, a.L - q0, a.kp_qk, a.rope_cos + tb, a.rope_sin + tb, q0);
+  } else {
+    tile_to_global<DQ>(Qs, 128, a.dqkv + head * a.kp_qk, a.ld_qkv, tok0 + q0, a.L - q0, a.kp_qk);
+  }
 #undef Ks
 #undef Vs
 }
@@ -702,47 +733,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ
 #pragma unroll
   for (int u = 0; u < DQ / 32; ++u) acc_to_tile<DQ>(KVs, wave * 32 + l32, u, dk[u], a.scale, hh);
   __syncthreads();
-  tile_to_global<DQ>(KVs, 128, a.dqkv + k_col(a, kvh), a.ld_qkv, tok0 + k0, a.L - k0, a.kp_qk);
+  if (a.rope_cos) {
+    const long long tb = static_cast<long long>(kvh) * a.L * (a.kp_qk / 2);
+    tile_to_global_unrope<DQ>(KVs, 128, a.dqkv + k_col(a, kvh), a.ld_qkv, tok0 + k0, a.L - k0, a.kp_qk, a.rope_cos + tb, a.rope_sin + tb, k0);
+  } else {
+    tile_to_global<DQ>(KVs, 128, a.dqkv + k_col(a, kvh), a.ld_qkv, tok0 + k0, a.L - k0, a.kp_qk);
+  }
   __syncthreads();
 #pragma unroll
   for (int u = 0; u < DV / 32; ++u) acc_to_tile<DV>(KVs, wave * 32 + l32, u, dv[u], 1.f, hh);
   __syncthreads();
   tile_to_global<DV>(KVs, 128, a.dqkv + v_col(a, kvh), a.ld_qkv, tok0 + k0, a.L - k0, a.kp_vo);
-}
-
-// ---------------------------------------------------------------------------------------------
-// rotary embedding, in place on the Q and K column blocks of a [T, nqkv] buffer (Eq. 6):
-// pair (2i, 2i+1) of head g at position t turns by +angle (forward) or -angle (gradients).
-// ---------------------------------------------------------------------------------------------
-// The tables hold one row of angles per key/value head: the query heads that share it (Eq. 5) keep its blocks.
-__global__ __launch_bounds__(256) void rope_kernel(bf16_t* __restrict__ buf, long long ld, const float* __restrict__ cs,
-                                                   const float* __restrict__ sn, int B, int L, int h, int h_kv, int kp_qk,
-                                                   float sign) {
-  const int cpr = (h + h_kv) * kp_qk / 8;   // 16-byte chunks per token over the Q and K blocks
-  const long long e = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
-  if (e >= static_cast<long long>(B) * L * cpr) return;
-  const long long tok = e / cpr;
-  const int c = static_cast<int>(e % cpr);
-  const int col = c * 8;
-  const int qcols = h * kp_qk;
-  const int head = col < qcols ? (col / kp_qk) / (h / h_kv) : (col - qcols) / kp_qk;   // row of the tables
-  const int i0 = (col % kp_qk) / 2;
-  const int t = static_cast<int>(tok % L);
-  const long long tab = (static_cast<long long>(head) * L + t) * (kp_qk / 2) + i0;
-  const float4 c4 = *reinterpret_cast<const float4*>(cs + tab);
-  const float4 s4 = *reinterpret_cast<const float4*>(sn + tab);
-  const float cv[4] = {c4.x, c4.y, c4.z, c4.w}, sv[4] = {s4.x, s4.y, s4.z, s4.w};
-  u32x4* p = reinterpret_cast<u32x4*>(buf + tok * ld + col);
-  const u32x4 v = *p;
-  uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float x0 = __uint_as_float(w[i] << 16), x1 = __uint_as_float(w[i] & 0xffff0000u);
-    const float s = sign * sv[i];
-    const float y0 = x0 * cv[i] - x1 * s, y1 = x0 * s + x1 * cv[i];
-    w[i] = static_cast<uint32_t>(f32_to_bf16(y0)) | (static_cast<uint32_t>(f32_to_bf16(y1)) << 16);
-  }
-  *p = u32x4{w[0], w[1], w[2], w[3]};
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -781,15 +782,6 @@ static int dispatch_core(ecospa_ctx* ctx, int which, const AttnArgs& a) {
   return ECOSPA_OK;
 }
 
-static int launch_rope(ecospa_ctx* ctx, const ecospa_block_desc& d, void* buf, long long ld, float sign) {
-  const int h_kv = attn_h_kv(d);
-  const long long tot = static_cast<long long>(d.B) * d.L * ((d.h + h_kv) * d.kp_qk / 8);
-  hipLaunchKernelGGL(rope_kernel, dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream,
-                     static_cast<bf16_t*>(buf), ld, d.rope_cos, d.rope_sin, d.B, d.L, d.h, h_kv, d.kp_qk, sign);
-  ECOSPA_CHECK_LAUNCH(ctx, "rope_kernel");
-  return ECOSPA_OK;
-}
-
 static GemmDesc mk_gemm(int dtype, int M, int N, int K, const void* A, long long lda, int ta, const void* B,
                         long long ldb, int tb, void* C, long long ldc, const void* bias) {
   GemmDesc g;
@@ -818,9 +810,17 @@ int attn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockWs& w, 
   if (!qkv || !o || !lse) return ECOSPA_ERR_NULL;
   if (!aligned16(qkv) || !aligned16(o)) return ECOSPA_ERR_ALIGN;
   int rc;
-  if ((rc = token_gemm(ctx, w, mk_gemm(d.dtype, T, nqkv, d.d_model, x, d.d_model, 0, d.w_qkv, d.ld_wqkv, 0, qkv, nqkv, d.b_qkv))))
-    return rc;
-  if (d.rope_cos && (rc = launch_rope(ctx, d, qkv, nqkv, 1.f))) return rc;
+  {
+    GemmDesc g = mk_gemm(d.dtype, T, nqkv, d.d_model, x, d.d_model, 0, d.w_qkv, d.ld_wqkv, 0, qkv, nqkv, d.b_qkv);
+    if (d.rope_cos) {      // the rotation of Q and K (Eq. 6) rides on the projection's epilogue
+      const int hkv = attn_h_kv(d);
+      g.epi.kind = EPI_ROPE;
+      g.epi.rope_cos = d.rope_cos; g.epi.rope_sin = d.rope_sin;
+      g.epi.rope_cols = (d.h + hkv) * d.kp_qk; g.epi.rope_kp = d.kp_qk; g.epi.rope_L = d.L;
+      g.epi.rope_hq = d.h; g.epi.rope_qpk = d.h / hkv;
+    }
+    if ((rc = token_gemm(ctx, w, g))) return rc;
+  }
   AttnArgs a;
   memset(&a, 0, sizeof(a));
   a.qkv = static_cast<const bf16_t*>(qkv); a.ld_qkv = nqkv;
@@ -855,14 +855,10 @@ static int attn_backward_body(ecospa_ctx* ctx, const ecospa_block_desc& d, const
   a.lse = sv.lse; a.delta = w.delta; a.dqkv = static_cast<bf16_t*>(w.dqkv);
   a.B = d.B; a.L = d.L; a.h = d.h; a.kp_qk = d.kp_qk; a.kp_vo = d.kp_vo; a.causal = d.causal; a.scale = d.scale;
   a.h_kv = attn_h_kv(d); a.qpk = d.h / a.h_kv;
-  {
-    const long long tot = static_cast<long long>(T) * d.h;
-    hipLaunchKernelGGL(attn_delta_kernel, dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream, a);
-    ECOSPA_CHECK_LAUNCH(ctx, "attn_delta_kernel");
-  }
-  if ((rc = dispatch_core(ctx, 2, a))) return rc;
+  a.rope_cos = d.rope_cos; a.rope_sin = d.rope_sin;
+  // the kernel over query tiles also leaves delta = rowsum(dO * O) for the kernel over key tiles
   if ((rc = dispatch_core(ctx, 1, a))) return rc;
-  if (d.rope_cos && (rc = launch_rope(ctx, d, w.dqkv, nqkv, -1.f))) return rc;
+  if ((rc = dispatch_core(ctx, 2, a))) return rc;
 
   // dW_qkv = dQKV^T X (partials)
   GemmDesc gq = mk_gemm(d.dtype, nqkv, dm, T, w.dqkv, nqkv, 1, x, dm, 1, gr.dw_qkv, gr.ld_dwqkv, nullptr);

@@ -106,6 +106,8 @@ extern "C" size_t ecospa_block_workspace_bytes(const ecospa_block_desc* desc) {
 // ---------------------------------------------------------------------------------------------
 // FFN
 // ---------------------------------------------------------------------------------------------
+// Gated activation on pre-activations whose columns come in (gate, up) pairs (fp32 path; bf16 has it in the epilogue
+// of the first contraction).
 template <typename T>
 __global__ __launch_bounds__(256) void swiglu_kernel(const T* __restrict__ hpre, long long ldh, T* __restrict__ act,
                                                      long long lda, long long rows, int kp) {
@@ -113,24 +115,8 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const T* __restrict__ hpre,
   if (e >= rows * kp) return;
   const long long m = e / kp;
   const int n = static_cast<int>(e % kp);
-  const float g = load_f32<T>(hpre + m * ldh + n), u = load_f32<T>(hpre + m * ldh + kp + n);
+  const float g = load_f32<T>(hpre + m * ldh + 2 * n), u = load_f32<T>(hpre + m * ldh + 2 * n + 1);
   store_f32<T>(act + m * lda + n, g * act_sigmoid(g) * u);
-}
-
-// bf16, eight units per thread with 16-byte accesses (kp and both leading dimensions are multiples of 8)
-__global__ __launch_bounds__(256) void swiglu_vec8_kernel(const bf16_t* __restrict__ hpre, long long ldh,
-                                                          bf16_t* __restrict__ act, long long lda, long long rows, int kp) {
-  const int kv = kp / 8;
-  const long long e = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
-  if (e >= rows * kv) return;
-  const long long m = e / kv;
-  const int n = static_cast<int>(e % kv) * 8;
-  float g[8], u[8];
-  unpack8(*reinterpret_cast<const uint4*>(hpre + m * ldh + n), g);
-  unpack8(*reinterpret_cast<const uint4*>(hpre + m * ldh + kp + n), u);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) g[i] = g[i] * act_sigmoid(g[i]) * u[i];
-  *reinterpret_cast<uint4*>(act + m * lda + n) = pack8(g);
 }
 
 static GemmDesc gemm_desc(int dtype, int M, int N, int K, const void* A, long long lda, int ta, const void* B,
@@ -154,23 +140,21 @@ static int ffn_forward(ecospa_ctx* ctx, const ecospa_block_desc& d, const BlockW
   GemmDesc g = gemm_desc(d.dtype, T, nh, d.d_model, x, d.d_model, 0, d.w_1, d.ld_w1, 0);
   g.epi.c = hpre; g.epi.ldc = nh; g.epi.bias = d.b_1;
   block_token_split(g, w);
-  if (is_gated(d)) {
+  if (is_gated(d) && d.dtype == ECOSPA_BF16) {
+    // gate and up rows alternate in w_1, so every output tile holds whole (gate, up) pairs: the product is formed in
+    // the epilogue; forward only (no saved activations) the pre-activations are not written at all
+    g.epi.kind = EPI_SWIGLU;
+    g.epi.c = saved ? hpre : nullptr;
+    g.epi.c2 = act; g.epi.ldc2 = kp;
+    if (!aligned16(hpre) || (reinterpret_cast<uintptr_t>(act) & 7u)) return ECOSPA_ERR_ALIGN;
+    if ((rc = ecospa_gemm(ctx, g))) return rc;
+  } else if (is_gated(d)) {
     g.epi.kind = EPI_STORE;
     if ((rc = ecospa_gemm(ctx, g))) return rc;
     const long long tot = static_cast<long long>(T) * kp;
-    const unsigned grid = static_cast<unsigned>((tot + 255) / 256);
-    if (d.dtype == ECOSPA_BF16 && kp % 8 == 0 && aligned16(hpre) && aligned16(act))
-      hipLaunchKernelGGL(swiglu_vec8_kernel, dim3(static_cast<unsigned>((tot / 8 + 255) / 256)), dim3(256), 0, ctx->stream,
-                         static_cast<const bf16_t*>(hpre), static_cast<long long>(nh), static_cast<bf16_t*>(act),
-                         static_cast<long long>(kp), static_cast<long long>(T), kp);
-    else if (d.dtype == ECOSPA_BF16)
-      hipLaunchKernelGGL((swiglu_kernel<bf16_t>), dim3(grid), dim3(256), 0, ctx->stream, static_cast<const bf16_t*>(hpre),
-                         static_cast<long long>(nh), static_cast<bf16_t*>(act), static_cast<long long>(kp),
-                         static_cast<long long>(T), kp);
-    else
-      hipLaunchKernelGGL((swiglu_kernel<float>), dim3(grid), dim3(256), 0, ctx->stream, static_cast<const float*>(hpre),
-                         static_cast<long long>(nh), static_cast<float*>(act), static_cast<long long>(kp),
-                         static_cast<long long>(T), kp);
+    hipLaunchKernelGGL((swiglu_kernel<float>), dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream,
+                       static_cast<const float*>(hpre), static_cast<long long>(nh), static_cast<float*>(act),
+                       static_cast<long long>(kp), static_cast<long long>(T), kp);
     ECOSPA_CHECK_LAUNCH(ctx, "swiglu_kernel");
   } else if (!saved) {
     // forward only: nothing will ask for the activation's input, so it is not written

@@ -14,6 +14,10 @@ enum {
   EPI_DACT = 2,      // c[m,n] = acc * gelu'(h[m,n])
   EPI_DSWIGLU = 3,   // g = h[m,n], u = h[m,n+kp]; c[m,n] = acc*u*dsilu(g); c[m,n+kp] = acc*silu(g)
   EPI_ACT = 4,       // c[m,n] = gelu(acc + bias[n]): forward only, the activation's input is not kept
+  EPI_ROPE = 5,      // c[m,n] = acc + bias[n], with the adjacent column pairs (2i, 2i+1) of the first rope_cols columns
+                     // turned by the angle of (row m % rope_L, pair) - the rotary form of the Q and K projections (bf16)
+  EPI_SWIGLU = 6,    // columns come in (gate, up) pairs: h = acc (+ bias) is stored to c[m, n] (2 kp wide, when c is
+                     // set) and silu(gate) * up to c2[m, n / 2] (kp wide) - the gated FFN's first contraction (bf16)
 };
 
 struct GemmEpi {
@@ -26,6 +30,11 @@ struct GemmEpi {
   const void* h;
   long long ldh;
   int kp;
+  // EPI_ROPE: cos/sin tables float[rope_rows][rope_L][rope_kp / 2]; column n < rope_cols belongs to head n / rope_kp,
+  // the query heads (the first rope_hq heads) share the table row of their key/value head: row head / rope_qpk for a
+  // query head, head - rope_hq for a key head
+  const float *rope_cos, *rope_sin;
+  int rope_cols, rope_kp, rope_L, rope_hq, rope_qpk;
 };
 
 struct GemmDesc {

@@ -605,7 +605,7 @@ int ecospa_gemm_colsum_rows(const GemmDesc& d) {
 
 int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
   if (d.M < 1 || d.N < 1 || d.K < 1) return ECOSPA_ERR_SHAPE;
-  if (!d.A || !d.B || !d.epi.c) return ECOSPA_ERR_NULL;
+  if (!d.A || !d.B || (!d.epi.c && d.epi.kind != EPI_SWIGLU)) return ECOSPA_ERR_NULL;      // the gated epilogue may skip its first output
   if (d.splits > 1 && !d.partial) return ECOSPA_ERR_WORKSPACE;
   // column sums of the A operand: the dY^T X form on the kernels that stage A through registers (not the pipelined one)
   if (d.colsum && !(d.dtype == ECOSPA_BF16 && d.trans_a && d.trans_b && (d.tile <= 4 || d.tile == 20 || d.tile >= 30))) return ECOSPA_ERR_SHAPE;
@@ -617,6 +617,9 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
     if (!aligned16(d.A) || !aligned16(d.B)) return ECOSPA_ERR_ALIGN;
     // the epilogue moves 8 columns at a time
     if (d.N % 8 || d.epi.ldc % 8 || !aligned16(d.epi.c)) return ECOSPA_ERR_ALIGN;
+    if (d.epi.kind == EPI_SWIGLU && (!d.epi.c2 || d.epi.ldc2 % 4 || (reinterpret_cast<uintptr_t>(d.epi.c2) & 7u))) return ECOSPA_ERR_ALIGN;
+    if (d.epi.kind == EPI_ROPE && (!d.epi.rope_cos || !d.epi.rope_sin || !aligned16(d.epi.rope_cos) || !aligned16(d.epi.rope_sin) ||
+                                   d.epi.rope_kp % 8 || d.epi.rope_cols % 8 || d.epi.rope_L < 1 || d.epi.rope_qpk < 1)) return ECOSPA_ERR_ALIGN;
     if (d.epi.bias && !aligned16(d.epi.bias)) return ECOSPA_ERR_ALIGN;
     if (d.epi.kind == EPI_BIAS_ACT && (!d.epi.c2 || d.epi.ldc2 % 8 || !aligned16(d.epi.c2))) return ECOSPA_ERR_ALIGN;
     if ((d.epi.kind == EPI_DACT || d.epi.kind == EPI_DSWIGLU) && (!d.epi.h || d.epi.ldh % 8 || !aligned16(d.epi.h)))
@@ -651,6 +654,7 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
     }
     ECOSPA_CHECK_LAUNCH(ctx, "gemm_bf16_mfma_kernel");
   } else if (d.dtype == ECOSPA_F32) {
+    if (d.epi.kind == EPI_ROPE || d.epi.kind == EPI_SWIGLU) return ECOSPA_ERR_DTYPE;
     const int tm = (d.M + 63) / 64, tn = (d.N + 63) / 64;
     int k_chunk = (d.K + splits - 1) / splits;
     k_chunk = (k_chunk + 31) / 32 * 32;
@@ -665,7 +669,7 @@ int ecospa_gemm(ecospa_ctx* ctx, const GemmDesc& d) {
 
 int ecospa_gemm_reduce(ecospa_ctx* ctx, const GemmDesc& d) {
   if (d.splits <= 1) return ECOSPA_OK;
-  if (!d.partial || !d.epi.c) return ECOSPA_ERR_NULL;
+  if (!d.partial || (!d.epi.c && d.epi.kind != EPI_SWIGLU)) return ECOSPA_ERR_NULL;
   const long long tot = static_cast<long long>(d.M) * d.N;
   if (d.dtype == ECOSPA_BF16)
     hipLaunchKernelGGL(gemm_splitk_reduce_vec8_kernel, dim3(static_cast<unsigned>((tot / 8 + 255) / 256)), dim3(256), 0,
@@ -828,7 +832,7 @@ int ecospa_aux_launch(ecospa_ctx* ctx, const AuxBatch& b) {
   }
   for (int i = 0; i < b.n_reduce; ++i, ++j) {
     const GemmDesc& d = b.reduce[i];
-    if (d.splits <= 1 || !d.partial || !d.epi.c) return ECOSPA_ERR_NULL;
+    if (d.splits <= 1 || !d.partial || (!d.epi.c && d.epi.kind != EPI_SWIGLU)) return ECOSPA_ERR_NULL;
     if (!dtype_ok(d.dtype)) return ECOSPA_ERR_DTYPE;
     a.blk_begin[j] = static_cast<int>(blk);
     const long long items = static_cast<long long>(d.M) * d.N / (d.dtype == ECOSPA_BF16 ? 8 : 1);

@@ -30,13 +30,15 @@ __device__ __forceinline__ void epi_apply(const GemmEpi& e, int m, int n, float 
       const float h = load_f32<T>(static_cast<const T*>(e.h) + static_cast<long long>(m) * e.ldh + n);
       store_f32<T>(c + off, acc * act_gelu_grad(h, e.act));
     } break;
-    case EPI_DSWIGLU: {
-      const T* hp = static_cast<const T*>(e.h) + static_cast<long long>(m) * e.ldh + n;
-      const float g = load_f32<T>(hp), u = load_f32<T>(hp + e.kp);
+    case EPI_DSWIGLU: {      // unit n: gate and up pre-activations in columns 2n and 2n + 1 of h, their gradients likewise in c
+      const T* hp = static_cast<const T*>(e.h) + static_cast<long long>(m) * e.ldh + 2 * n;
+      const float g = load_f32<T>(hp), u = load_f32<T>(hp + 1);
       const float sg = act_sigmoid(g);
-      store_f32<T>(c + off, acc * u * sg * (1.f + g * (1.f - sg)));
-      store_f32<T>(c + off + e.kp, acc * g * sg);
+      T* cp = c + static_cast<long long>(m) * e.ldc + 2 * n;
+      store_f32<T>(cp, acc * u * sg * (1.f + g * (1.f - sg)));
+      store_f32<T>(cp + 1, acc * g * sg);
     } break;
+    default: break;          // EPI_ROPE, EPI_SWIGLU: bf16 only (vector epilogue)
   }
 }
 
@@ -57,9 +59,35 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
   const bf16x8_t b = __builtin_convertvector(v, bf16x8_t);   // round to nearest even (v_cvt_pk_bf16_f32)
   return __builtin_bit_cast(uint4, b);
 }
+// Rotary turn of the four adjacent pairs in v (columns n .. n+7 of row m), sign = +1 forward, -1 for gradients.
+__device__ __forceinline__ void rope_turn8(const float* __restrict__ cs, const float* __restrict__ sn, long long tab, float sign,
+                                           float (&v)[8]) {
+  const float4 c4 = *reinterpret_cast<const float4*>(cs + tab);
+  const float4 s4 = *reinterpret_cast<const float4*>(sn + tab);
+  const float cv[4] = {c4.x, c4.y, c4.z, c4.w}, sv[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float x0 = v[2 * i], x1 = v[2 * i + 1], s = sign * sv[i];
+    v[2 * i] = x0 * cv[i] - x1 * s;
+    v[2 * i + 1] = x0 * s + x1 * cv[i];
+  }
+}
 __device__ __forceinline__ void epi_apply_vec8(const GemmEpi& e, int m, int n, float (&v)[8]) {
   bf16_t* c = static_cast<bf16_t*>(e.c) + static_cast<long long>(m) * e.ldc + n;
-  if (e.kind == EPI_STORE || e.kind == EPI_BIAS_ACT) {
+  if (e.kind == EPI_ROPE) {
+    if (e.bias) {
+      float b[8];
+      unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.bias) + n), b);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] += b[i];
+    }
+    if (n < e.rope_cols) {
+      const int head = n / e.rope_kp, row = head < e.rope_hq ? head / e.rope_qpk : head - e.rope_hq;
+      const long long tab = (static_cast<long long>(row) * e.rope_L + m % e.rope_L) * (e.rope_kp / 2) + (n % e.rope_kp) / 2;
+      rope_turn8(e.rope_cos, e.rope_sin, tab, 1.f, v);
+    }
+    *reinterpret_cast<uint4*>(c) = pack8(v);
+  } else if (e.kind == EPI_STORE || e.kind == EPI_BIAS_ACT) {
     if (e.bias) {
       float b[8];
       unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.bias) + n), b);
@@ -89,19 +117,36 @@ __device__ __forceinline__ void epi_apply_vec8(const GemmEpi& e, int m, int n, f
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] *= act_gelu_grad(h[i], e.act);
     *reinterpret_cast<uint4*>(c) = pack8(v);
-  } else {  // EPI_DSWIGLU
-    const bf16_t* hp = static_cast<const bf16_t*>(e.h) + static_cast<long long>(m) * e.ldh + n;
-    float g[8], u[8], dg[8], du[8];
-    unpack8(*reinterpret_cast<const uint4*>(hp), g);
-    unpack8(*reinterpret_cast<const uint4*>(hp + e.kp), u);
+  } else if (e.kind == EPI_SWIGLU) {
+    // columns n .. n+7 are four (gate, up) pairs: units n/2 .. n/2+3
+    if (e.bias) {
+      float b[8];
+      unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.bias) + n), b);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] += b[i];
+    }
+    if (e.c) *reinterpret_cast<uint4*>(c) = pack8(v);
+    typedef float floatx4 __attribute__((ext_vector_type(4)));
+    typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+    floatx4 a;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = v[2 * i] * act_sigmoid(v[2 * i]) * v[2 * i + 1];
+    *reinterpret_cast<bf16x4_t*>(static_cast<bf16_t*>(e.c2) + static_cast<long long>(m) * e.ldc2 + (n >> 1)) = __builtin_convertvector(a, bf16x4_t);
+  } else {  // EPI_DSWIGLU: units n .. n+7, their (gate, up) pairs in columns 2n .. 2n+15 of h and of c
+    const bf16_t* hp = static_cast<const bf16_t*>(e.h) + static_cast<long long>(m) * e.ldh + 2 * n;
+    bf16_t* cp = static_cast<bf16_t*>(e.c) + static_cast<long long>(m) * e.ldc + 2 * n;
+    float p[2][8], o[2][8];
+    unpack8(*reinterpret_cast<const uint4*>(hp), p[0]);
+    unpack8(*reinterpret_cast<const uint4*>(hp + 8), p[1]);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const float sg = act_sigmoid(g[i]);
-      dg[i] = v[i] * u[i] * sg * (1.f + g[i] * (1.f - sg));
-      du[i] = v[i] * g[i] * sg;
+      const float g = p[i >> 2][2 * (i & 3)], u = p[i >> 2][2 * (i & 3) + 1];
+      const float sg = act_sigmoid(g);
+      o[i >> 2][2 * (i & 3)] = v[i] * u * sg * (1.f + g * (1.f - sg));
+      o[i >> 2][2 * (i & 3) + 1] = v[i] * g * sg;
     }
-    *reinterpret_cast<uint4*>(c) = pack8(dg);
-    *reinterpret_cast<uint4*>(c + e.kp) = pack8(du);
+    *reinterpret_cast<uint4*>(cp) = pack8(o[0]);
+    *reinterpret_cast<uint4*>(cp + 8) = pack8(o[1]);
   }
 }
 

@@ -48,3 +48,44 @@ extern "C" int ecospa_hbm_probe(ecospa_ctx* ctx, const void* src, void* dst, siz
   ECOSPA_CHECK_LAUNCH(ctx, "hbm_probe_kernel");
   return ECOSPA_OK;
 }
+
+// The matrix units alone: every wavefront of 256 workgroups (one per compute unit, one wavefront per SIMD) issues
+// `iters` rounds of 16 independent v_mfma_f32_32x32x16_bf16 on operands taken from `src` - no memory traffic inside
+// the loop.  With operands like real activations the clock settles below its maximum (the power drawn by the matrix
+// units depends on the operand bits), so the rate this loop sustains, not the data-sheet peak, is what a contraction
+// kernel on this GPU can approach.
+typedef __bf16 probe_bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float probe_floatx16 __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void mfma_probe_kernel(const u32x4_t* __restrict__ src, float* __restrict__ sink, int iters) {
+  probe_bf16x8_t a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a[i] = __builtin_bit_cast(probe_bf16x8_t, src[(threadIdx.x * 8 + i) & 4095]);
+    b[i] = __builtin_bit_cast(probe_bf16x8_t, src[(threadIdx.x * 8 + 4 + i) & 4095]);
+  }
+  probe_floatx16 acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[i >> 2], acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+extern "C" int ecospa_mfma_probe(ecospa_ctx* ctx, const void* src, float* sink, int iters, double* flop) {
+  if (!ctx || !src || !sink) return ECOSPA_ERR_NULL;
+  if (iters < 1 || iters > (1 << 24)) return ECOSPA_ERR_SHAPE;
+  if (!aligned16(src)) return ECOSPA_ERR_ALIGN;
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(256), dim3(256), 0, ctx->stream, static_cast<const u32x4_t*>(src), sink, iters);
+  ECOSPA_CHECK_LAUNCH(ctx, "mfma_probe_kernel");
+  if (flop) *flop = 256.0 * 4.0 * iters * 16.0 * 2.0 * 32.0 * 32.0 * 16.0;
+  return ECOSPA_OK;
+}

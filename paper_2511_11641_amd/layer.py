@@ -71,14 +71,26 @@ class FfnBlock:
         self.refresh_transposed()
         return self
 
+    def gate_rows(self, t: torch.Tensor) -> torch.Tensor:
+        """The gate (or only) half of a tensor laid out like the compact first matrix or its bias: the gated block keeps
+        gate unit i in row 2i and up unit i in row 2i + 1, so that one output tile of the first contraction holds whole
+        (gate, up) pairs."""
+        return t[0::2] if self.gated else t
+
+    def up_rows(self, t: torch.Tensor) -> torch.Tensor:
+        return t[1::2]
+
     def _map_items(self, scatter: int):
         """Descriptors between every full-size member and its compact counterpart: gathers (0) or scatters (1, 2)."""
         kp = self.kp
-        members = [(self.w1, self.w1_c[:kp], 0)]
+        members = [(self.w1, self.gate_rows(self.w1_c), 0)]
         if self.gated:
-            members.append((self.w1b, self.w1_c[kp:], 0))
+            members.append((self.w1b, self.up_rows(self.w1_c), 0))
         if self.b1 is not None:       # the up branch of a gated FFN has no bias: its slots stay zero
-            members.append((self.b1, self.b1_c[:kp], 1))
+            if self.gated:            # every second slot: a [kp, 1] matrix with a row pitch of 2
+                members.append((self.b1.view(-1, 1), self.b1_c.view(kp, 2)[:, :1], 0))
+            else:
+                members.append((self.b1, self.b1_c, 1))
         members.append((self.w2, self.w2_c, 1))
         return [B.Context.map_item(c if scatter else f, f if scatter else c, self.idx, axis, 1, self.n, 1, kp,
                                    scatter=scatter, k_group=self.k_group) for f, c, axis in members]

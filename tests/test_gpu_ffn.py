@@ -8,7 +8,7 @@ from oracle import ecospa_oracle as O
 from paper_2511_11641_amd import binding as B
 from paper_2511_11641_amd import synth
 from paper_2511_11641_amd.layer import FfnBlock
-from util import assert_close, dev, host, pad_cols, pad_rows
+from util import assert_close, dev, host, pad_cols, pad_rows, interleave_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -49,18 +49,18 @@ def run_ffn_case(ctx, seed, Bsz, L, d, n, k, act, dtype, structure="scratch", bi
     errs = {"y": assert_close(y, yo, dtype, "y"), "dx": assert_close(dx, go["dx"], dtype, "dx")}
     dw1 = pad_rows(go["dw1"], 1, k, kp)
     if gated:
-        dw1 = np.concatenate([dw1, pad_rows(go["dw1b"], 1, k, kp)], axis=0)
+        dw1 = interleave_rows(dw1, pad_rows(go["dw1b"], 1, k, kp))
     errs["dw1"] = assert_close(blk.dw1_c, dw1, dtype, "dw1")
     errs["dw2"] = assert_close(blk.dw2_c, pad_cols(go["dw2"], 1, k, kp), dtype, "dw2")
     db1 = pad_rows(go["db1"], 1, k, kp)
     if gated:
         # the up branch has no bias in the oracle; its column sums are sum_t dH_u
-        db1 = np.concatenate([db1, pad_rows(_dhu_colsum(t, w2c, sv), 1, k, kp)])
+        db1 = interleave_rows(db1, pad_rows(_dhu_colsum(t, w2c, sv), 1, k, kp))
     errs["db1"] = assert_close(blk.db1_c, db1, dtype, "db1")
     errs["db2"] = assert_close(blk.db2, go["db2"], dtype, "db2")
     # padding slots hold exact zeros
     if kp > k:
-        assert torch.all(blk.dw1_c[k:kp] == 0) and torch.all(blk.dw2_c[:, k:] == 0)
+        assert torch.all(blk.dw1_c[(2 * k if gated else k):] == 0) and torch.all(blk.dw2_c[:, k:] == 0)
     return errs
 
 

@@ -14,7 +14,7 @@ import bench
 from oracle import ecospa_oracle as O
 from paper_2511_11641_amd import binding as B
 from paper_2511_11641_amd import synth
-from util import assert_close, host, pad_cols, pad_rows
+from util import assert_close, host, pad_cols, pad_rows, interleave_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -94,7 +94,7 @@ def test_full_layer_step_matches_oracle(ctx, name, num, den):
     want_dw1 = pad_rows(gf["dw1"], 1, kf, kpf)
     want_db1 = pad_rows(gf["db1"].reshape(-1, 1), 1, kf, kpf)[:, 0]
     if cfg["gated"]:
-        want_dw1 = np.concatenate([want_dw1, pad_rows(gf["dw1b"], 1, kf, kpf)])
+        want_dw1 = interleave_rows(want_dw1, pad_rows(gf["dw1b"], 1, kf, kpf))
     assert_close(lay.ffn.dw1_c, want_dw1, "bf16", "dW_1")
     assert_close(lay.ffn.dw2_c, pad_cols(gf["dw2"], 1, kf, kpf), "bf16", "dW_2")
     if cfg["bias"]:

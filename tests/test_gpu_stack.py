@@ -141,7 +141,7 @@ def test_stack_matches_masked_dense_torch_model(ctx, cfg, keep):
         got = host(a.dwo_c).reshape(st.d, st.h, a.kp_vo)[:, :, :kv].reshape(st.d, -1)
         assert O.rel_fro(got, go) <= tol, f"layer {li} dW_o"
         g1 = O.compact(host(leaves[f"{li}.w1"].grad), ly.idx[2].cpu().numpy(), 0, st.d_ff, 1)
-        assert O.rel_fro(host(f.dw1_c[:kf]), g1) <= tol, f"layer {li} dW_1"
+        assert O.rel_fro(host(f.gate_rows(f.dw1_c)[:kf]), g1) <= tol, f"layer {li} dW_1"
         g2 = O.compact(host(leaves[f"{li}.w2"].grad), ly.idx[2].cpu().numpy(), 1, st.d_ff, 1)
         assert O.rel_fro(host(f.dw2_c[:, :kf]), g2) <= tol, f"layer {li} dW_2"
         assert _rel(ly.norm[0][0].g, leaves[f"{li}.n1.g"].grad) <= tol
@@ -171,7 +171,7 @@ def test_training_state_stays_compact_and_is_written_back(ctx, cfg):
         for n, t in ly.full["mst"].items():
             if n not in ("bo", "b2"):                    # the output biases belong to no pair: they train in place
                 assert torch.equal(t, w0[n]), n
-    cm = [{"w1": ly.ffn["mst"].w1_c.clone(), "m_w2": ly.ffn["m"].w2_c.clone(), "wq": ly.attn["mst"].wqkv_c.clone()} for ly in st.layers]
+    cm = [{"w1": ly.ffn["mst"].gate_rows(ly.ffn["mst"].w1_c).clone(), "m_w2": ly.ffn["m"].w2_c.clone(), "wq": ly.attn["mst"].wqkv_c.clone()} for ly in st.layers]
     st.prune()
     for li, (ly, w0) in enumerate(zip(st.layers, init)):
         unit = 2 if cfg["rope"] else 1
@@ -194,9 +194,9 @@ def test_training_state_stays_compact_and_is_written_back(ctx, cfg):
         s = st.ctx.ecospa_coupled_score([ly.ffn["mst"].pair()])[0]
         assert np.array_equal(ly.idx[2].cpu().numpy(), O.select_topk(s.cpu().numpy(), kf))
         new_ff = ly.idx[2][0].long()
-        assert torch.equal(ly.ffn["mst"].w1_c[:kf], full["w1"][new_ff])
+        assert torch.equal(ly.ffn["mst"].gate_rows(ly.ffn["mst"].w1_c)[:kf], full["w1"][new_ff])
         assert torch.equal(ly.ffn["v"].w2_c[:, :kf], ly.full["v"]["w2"][:, new_ff])
-        assert torch.equal(ly.ffn["w"].w1_c[:kf], ly.full["w"]["w1"][new_ff])
+        assert torch.equal(ly.ffn["w"].gate_rows(ly.ffn["w"].w1_c)[:kf], ly.full["w"]["w1"][new_ff])
     # and training goes on from the new compact state
     more = [float(st.train_step(ids, tgt)) for _ in range(3)]
     assert all(np.isfinite(more)) and more[-1] < losses[0]

@@ -138,8 +138,8 @@ def test_two_layer_step_against_the_oracle(ctx, cfg):
         rel(host(a.dwo_c).reshape(st.d, st.h, a.kp_vo)[:, :, :kv].transpose(1, 0, 2), g["attn"]["dwo"], f"layer {li} dW_o")
         rel(f.dw2_c[:, :kf], g["ffn"]["dw2"], f"layer {li} dW_2")
         if cfg["gated"]:
-            rel(f.dw1_c[:kf], g["ffn"]["dw1"], f"layer {li} dW_gate")
-            rel(f.dw1_c[f.kp:f.kp + kf], g["ffn"]["dw1b"], f"layer {li} dW_up")
+            rel(f.gate_rows(f.dw1_c)[:kf], g["ffn"]["dw1"], f"layer {li} dW_gate")
+            rel(f.up_rows(f.dw1_c)[:kf], g["ffn"]["dw1b"], f"layer {li} dW_up")
         else:
             rel(f.dw1_c[:kf], g["ffn"]["dw1"], f"layer {li} dW_1")
             rel(f.db1_c[:kf], g["ffn"]["db1"], f"layer {li} db_1")

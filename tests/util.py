@@ -67,3 +67,12 @@ def pad_rows(a, groups, k, kp):
 
 def pad_cols(a, groups, k, kp):
     return np.ascontiguousarray(pad_rows(np.asarray(a).T, groups, k, kp).T)
+
+
+def interleave_rows(a, b):
+    """Rows a[0], b[0], a[1], b[1], ...: the compact layout of a gated FFN's first matrix (gate unit i in row 2i, up
+    unit i in row 2i + 1) from its two halves."""
+    a, b = np.asarray(a), np.asarray(b)
+    out = np.empty((2 * a.shape[0],) + a.shape[1:], dtype=a.dtype)
+    out[0::2], out[1::2] = a, b
+    return out
