@@ -63,7 +63,7 @@ class Layer:
     def __init__(self, ctx, cfg, seed, keep_num, keep_den):
         import torch
         from paper_2511_11641_amd import binding as B, synth
-        from paper_2511_11641_amd.layer import AttnBlock, FfnBlock
+        from paper_2511_11641_amd.layer import AttnBlock, FfnBlock, rows_aligned
         self.torch, self.B_ = torch, B
         self.ctx, self.cfg = ctx, cfg
         Bsz, L, d, h, dh, dff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
@@ -75,6 +75,7 @@ class Layer:
         up = lambda arr: None if arr is None else torch.from_numpy(arr).to(tdt).cuda()
         g = {k: up(v) for k, v in a.items()}
         gf = {k: up(v) for k, v in f.items() if k not in ("x", "dy")}
+        gf["w2"] = rows_aligned(gf["w2"])        # rows of W_out on 16-byte boundaries (d_ff = 5461 is odd)
         self.x, self.dy = g["x"], g["dy"]
         act = B.ACT_SWIGLU if cfg["gated"] else B.ACT_GELU_ERF
         hkv = cfg.get("h_kv", h)          # grouped-query attention (Eq. 5): the first h_kv heads of W_k, W_v serve as the shared ones

@@ -205,7 +205,11 @@ int ecospa_scatter(ecospa_ctx* ctx, const void* src, void* dst, int dtype, int a
  * as they are (compact parameters, master copies and moments written back into full-size arrays before
  * the importance is estimated again, Alg. 1); other values -> ERR_SHAPE.
  * `items` is a host array; all items are validated before anything is launched.  Items must not
- * overlap each other's destinations. */
+ * overlap each other's destinations.
+ * Reading contract of the column gathers (axis 1): rows are fetched in whole 16-byte pieces when src is 16-byte
+ * aligned and ld_src is a multiple of 16 bytes that covers the inner extent rounded up to 16 bytes - a caller that
+ * gives such an ld_src promises that every row, the last one included, is backed by memory up to that rounded extent
+ * (a matrix with an odd inner width, stored with a padded leading dimension, then takes the fast path). */
 /* Ragged kept counts (what the cumulative-threshold rule of Alg. 1 leaves: every head, every pair its
  * own k): k_group != NULL names a device int32[groups] array (k_out of ecospa_select_theta), ld_idx the
  * distance between the index lists of consecutive groups (idx: int32[groups * ld_idx], as written by

@@ -373,8 +373,10 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
         blk += (t.dst_slots + MAP_ROWS_PER_BLOCK - 1) / MAP_ROWS_PER_BLOCK;
       } else {
         t.vec = aligned16(q.dst) && q.ld_dst % V == 0;
-        // the LDS path reads whole 16-byte chunks of the source rows, up to the end of the last kept chunk
-        t.lds_path = t.vec && q.scatter != 2 && aligned16(q.src) && q.ld_src % V == 0 && (q.scatter ? cmp_slots : full_slots) % V == 0;
+        // the LDS path reads whole 16-byte chunks of the source rows, up to the end of the last kept chunk: the row's
+        // storage (its leading dimension) must reach that far
+        const long long src_slots = q.scatter ? cmp_slots : full_slots;
+        t.lds_path = t.vec && q.scatter != 2 && aligned16(q.src) && q.ld_src % V == 0 && q.ld_src >= (src_slots + V - 1) / V * V;
         if (t.lds_path) {
           t.gx = static_cast<int>((t.dst_slots + MAP_LDS_GROUPS * V - 1) / (MAP_LDS_GROUPS * V));
           int rpb = MAP_LDS_ROWS_TOTAL;

@@ -12,6 +12,17 @@ import torch
 from . import binding as B
 
 
+def rows_aligned(t: torch.Tensor) -> torch.Tensor:
+    """The same matrix with its leading dimension padded to a multiple of 32 elements, so that every row starts on a
+    16-byte boundary whatever the dtype: the score, gather and transpose kernels then move 16 bytes per lane (an inner
+    width such as d_ff = 5461 otherwise puts W_down on their element-wise paths)."""
+    if t.dim() != 2 or t.shape[1] % 32 == 0:
+        return t
+    buf = torch.zeros((t.shape[0], B.round_up(t.shape[1], 32)), dtype=t.dtype, device=t.device)
+    buf[:, :t.shape[1]] = t
+    return buf[:, :t.shape[1]]
+
+
 class FfnBlock:
     """Compacted FFN pair (W_in / W_out, or W_gate (.) W_up / W_down)."""
 

@@ -24,7 +24,7 @@ import torch
 import torch.nn.functional as F
 
 from . import binding as B
-from .layer import AttnBlock, FfnBlock
+from .layer import AttnBlock, FfnBlock, rows_aligned
 
 FAMILIES = ("w", "mst", "m", "v")      # bf16 working copy, fp32 master, first and second moment
 
@@ -66,15 +66,6 @@ class DecoderStack:
 
         def rnd(*shape):
             return torch.randn(*shape, device="cuda", generator=gen) * 0.02
-
-        def rows_aligned(t):
-            """The same matrix with its leading dimension padded to a multiple of 32 elements, so that rows start on
-            16-byte boundaries whatever the dtype (d_ff = 5461 otherwise puts W_down on the element-wise copy paths)."""
-            if t.dim() != 2 or t.shape[1] % 32 == 0:
-                return t
-            buf = torch.zeros((t.shape[0], B.round_up(t.shape[1], 32)), dtype=t.dtype, device=t.device)
-            buf[:, :t.shape[1]] = t
-            return buf[:, :t.shape[1]]
 
         fams = FAMILIES if train else ("w",)
         act = B.ACT_SWIGLU if cfg["gated"] else B.ACT_GELU_ERF

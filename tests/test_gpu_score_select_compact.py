@@ -245,3 +245,25 @@ def test_check_indices_accepts_what_select_writes_and_names_bad_lists(ctx):
     k_bad[1] = min(int(k_t[1]) + 1, 100)        # reaches into the -1 padding (unless the row kept everything)
     if int(k_t[1]) < 100:
         assert not ctx.ecospa_check_indices(idx_t, 100, k_group=k_bad)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("n,k", [(1073, 536), (5461, 2730), (37, 11)])
+def test_column_gather_of_an_odd_width_with_padded_rows(ctx, n, k, dtype):
+    """A second member with an odd inner width (d_ff = 5461) stored with a padded leading dimension: its column gather
+    takes the path that fetches whole 16-byte pieces; bit-exact against the oracle, scatter back included."""
+    rows = 70
+    w = synth.round_to(synth.normal(61, 330, (rows, n)), dtype)
+    idx = np.sort(np.random.default_rng(n).choice(n, k, replace=False)).astype(np.int32)[None, :]
+    ld = (n + 31) // 32 * 32
+    buf = torch.full((rows, ld), 7.0, dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device="cuda")
+    buf[:, :n] = dev(w, dtype)
+    src = buf[:, :n]
+    kp = (k + 15) // 16 * 16
+    got = ctx.ecospa_compact(src, torch.from_numpy(idx).cuda(), 1, 1, n, kp=kp)
+    want = pad_cols(O.compact(w, idx, 1, n), 1, k, kp)
+    assert np.array_equal(host(got), want.astype(np.float64))
+    back = torch.full((rows, ld), 3.0, dtype=buf.dtype, device="cuda")
+    ctx.ecospa_scatter(got, torch.from_numpy(idx).cuda(), 1, 1, n, kp=kp, out=back[:, :n])
+    assert np.array_equal(host(back[:, :n]), O.scatter(O.compact(w, idx, 1, n), idx, 1, n).astype(np.float64))
+    assert bool((back[:, n:] == 3.0).all())          # the padding of the rows is not touched
