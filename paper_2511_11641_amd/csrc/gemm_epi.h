@@ -1,5 +1,6 @@
 // Device-side epilogues shared by the contraction kernels (not part of the C ABI).
 #pragma once
+#include <type_traits>
 #include "gemm.h"
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -60,10 +61,7 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
   return __builtin_bit_cast(uint4, b);
 }
 // Rotary turn of the four adjacent pairs in v (columns n .. n+7 of row m), sign = +1 forward, -1 for gradients.
-__device__ __forceinline__ void rope_turn8(const float* __restrict__ cs, const float* __restrict__ sn, long long tab, float sign,
-                                           float (&v)[8]) {
-  const float4 c4 = *reinterpret_cast<const float4*>(cs + tab);
-  const float4 s4 = *reinterpret_cast<const float4*>(sn + tab);
+__device__ __forceinline__ void rope_turn8(const float4& c4, const float4& s4, float sign, float (&v)[8]) {
   const float cv[4] = {c4.x, c4.y, c4.z, c4.w}, sv[4] = {s4.x, s4.y, s4.z, s4.w};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -72,59 +70,87 @@ __device__ __forceinline__ void rope_turn8(const float* __restrict__ cs, const f
     v[2 * i + 1] = x0 * s + x1 * cv[i];
   }
 }
-__device__ __forceinline__ void epi_apply_vec8(const GemmEpi& e, int m, int n, float (&v)[8]) {
-  bf16_t* c = static_cast<bf16_t*>(e.c) + static_cast<long long>(m) * e.ldc + n;
-  if (e.kind == EPI_ROPE) {
-    if (e.bias) {
-      float b[8];
-      unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.bias) + n), b);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] += b[i];
-    }
+
+// What an epilogue reads from global memory for one group of 8 columns besides the accumulators: the saved
+// pre-activations (EPI_DACT: one 16-byte word, EPI_DSWIGLU: two) or the rotation table entries (EPI_ROPE: four
+// cosines, four sines).  A kernel that loads them rows ahead of their use keeps their latency off the path of every
+// row (on this target a wait for a load also waits for the stores issued before it).
+// The epilogue kind is a template argument of the *_k functions, so that a kernel that branches on it once gets
+// straight-line code per kind; the functions without the suffix branch per call.
+struct EpiSide { uint4 a, b; };
+__device__ __forceinline__ constexpr bool epi_has_side(int kind) { return kind == EPI_DACT || kind == EPI_DSWIGLU || kind == EPI_ROPE; }
+template <int KIND>
+__device__ __forceinline__ void epi_side_load_k(const GemmEpi& e, int m, int n, EpiSide& s) {
+  if constexpr (KIND == EPI_ROPE) {
     if (n < e.rope_cols) {
       const int head = n / e.rope_kp, row = head < e.rope_hq ? head / e.rope_qpk : head - e.rope_hq;
       const long long tab = (static_cast<long long>(row) * e.rope_L + m % e.rope_L) * (e.rope_kp / 2) + (n % e.rope_kp) / 2;
-      rope_turn8(e.rope_cos, e.rope_sin, tab, 1.f, v);
+      s.a = *reinterpret_cast<const uint4*>(e.rope_cos + tab);
+      s.b = *reinterpret_cast<const uint4*>(e.rope_sin + tab);
     }
-    *reinterpret_cast<uint4*>(c) = pack8(v);
-  } else if (e.kind == EPI_STORE || e.kind == EPI_BIAS_ACT) {
-    if (e.bias) {
-      float b[8];
-      unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.bias) + n), b);
+  } else if constexpr (KIND == EPI_DACT) {
+    s.a = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.h) + static_cast<long long>(m) * e.ldh + n);
+  } else if constexpr (KIND == EPI_DSWIGLU) {
+    const bf16_t* hp = static_cast<const bf16_t*>(e.h) + static_cast<long long>(m) * e.ldh + 2 * n;
+    s.a = *reinterpret_cast<const uint4*>(hp);
+    s.b = *reinterpret_cast<const uint4*>(hp + 8);
+  }
+}
+// The bias of columns n .. n+7 for the epilogues that add one (the same for every row a lane handles).
+__device__ __forceinline__ bool epi_bias_load(const GemmEpi& e, int n, float (&b)[8]) {
+  if (!e.bias || e.kind == EPI_DACT || e.kind == EPI_DSWIGLU) return false;
+  unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.bias) + n), b);
+  return true;
+}
+// Columns n .. n+7 of row m with the bias and the side inputs already in registers.
+template <int KIND>
+__device__ __forceinline__ void epi_apply_vec8_k(const GemmEpi& e, int m, int n, float (&v)[8], bool has_bias, const float (&b)[8],
+                                                 const EpiSide& sd) {
+  bf16_t* c = static_cast<bf16_t*>(e.c) + static_cast<long long>(m) * e.ldc + n;
+  if constexpr (KIND != EPI_DACT && KIND != EPI_DSWIGLU) {
+    if (has_bias) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) v[i] += b[i];
     }
+  }
+  if constexpr (KIND == EPI_ROPE) {
+    if (n < e.rope_cols) rope_turn8(__builtin_bit_cast(float4, sd.a), __builtin_bit_cast(float4, sd.b), 1.f, v);
     *reinterpret_cast<uint4*>(c) = pack8(v);
-    if (e.kind == EPI_BIAS_ACT) {
-      float a[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) a[i] = act_gelu(v[i], e.act);
-      *reinterpret_cast<uint4*>(static_cast<bf16_t*>(e.c2) + static_cast<long long>(m) * e.ldc2 + n) = pack8(a);
-    }
-  } else if (e.kind == EPI_ACT) {
-    if (e.bias) {
-      float b[8];
-      unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.bias) + n), b);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] += b[i];
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = act_gelu(v[i], e.act);
+  } else if constexpr (KIND == EPI_STORE) {
     *reinterpret_cast<uint4*>(c) = pack8(v);
-  } else if (e.kind == EPI_DACT) {
+  } else if constexpr (KIND == EPI_BIAS_ACT) {
+    *reinterpret_cast<uint4*>(c) = pack8(v);
+    float a[8];
+    if (e.act == ECOSPA_ACT_GELU_TANH) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) a[i] = act_gelu(v[i], ECOSPA_ACT_GELU_TANH);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) a[i] = act_gelu(v[i], ECOSPA_ACT_GELU_ERF);
+    }
+    *reinterpret_cast<uint4*>(static_cast<bf16_t*>(e.c2) + static_cast<long long>(m) * e.ldc2 + n) = pack8(a);
+  } else if constexpr (KIND == EPI_ACT) {
+    if (e.act == ECOSPA_ACT_GELU_TANH) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = act_gelu(v[i], ECOSPA_ACT_GELU_TANH);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = act_gelu(v[i], ECOSPA_ACT_GELU_ERF);
+    }
+    *reinterpret_cast<uint4*>(c) = pack8(v);
+  } else if constexpr (KIND == EPI_DACT) {
     float h[8];
-    unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.h) + static_cast<long long>(m) * e.ldh + n), h);
+    unpack8(sd.a, h);
+    if (e.act == ECOSPA_ACT_GELU_TANH) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] *= act_gelu_grad(h[i], e.act);
-    *reinterpret_cast<uint4*>(c) = pack8(v);
-  } else if (e.kind == EPI_SWIGLU) {
-    // columns n .. n+7 are four (gate, up) pairs: units n/2 .. n/2+3
-    if (e.bias) {
-      float b[8];
-      unpack8(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(e.bias) + n), b);
+      for (int i = 0; i < 8; ++i) v[i] *= act_gelu_grad(h[i], ECOSPA_ACT_GELU_TANH);
+    } else {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] += b[i];
+      for (int i = 0; i < 8; ++i) v[i] *= act_gelu_grad(h[i], ECOSPA_ACT_GELU_ERF);
     }
+    *reinterpret_cast<uint4*>(c) = pack8(v);
+  } else if constexpr (KIND == EPI_SWIGLU) {
+    // columns n .. n+7 are four (gate, up) pairs: units n/2 .. n/2+3
     if (e.c) *reinterpret_cast<uint4*>(c) = pack8(v);
     typedef float floatx4 __attribute__((ext_vector_type(4)));
     typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
@@ -133,11 +159,11 @@ __device__ __forceinline__ void epi_apply_vec8(const GemmEpi& e, int m, int n, f
     for (int i = 0; i < 4; ++i) a[i] = v[2 * i] * act_sigmoid(v[2 * i]) * v[2 * i + 1];
     *reinterpret_cast<bf16x4_t*>(static_cast<bf16_t*>(e.c2) + static_cast<long long>(m) * e.ldc2 + (n >> 1)) = __builtin_convertvector(a, bf16x4_t);
   } else {  // EPI_DSWIGLU: units n .. n+7, their (gate, up) pairs in columns 2n .. 2n+15 of h and of c
-    const bf16_t* hp = static_cast<const bf16_t*>(e.h) + static_cast<long long>(m) * e.ldh + 2 * n;
+    static_assert(KIND == EPI_DSWIGLU, "epilogue kind");
     bf16_t* cp = static_cast<bf16_t*>(e.c) + static_cast<long long>(m) * e.ldc + 2 * n;
     float p[2][8], o[2][8];
-    unpack8(*reinterpret_cast<const uint4*>(hp), p[0]);
-    unpack8(*reinterpret_cast<const uint4*>(hp + 8), p[1]);
+    unpack8(sd.a, p[0]);
+    unpack8(sd.b, p[1]);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float g = p[i >> 2][2 * (i & 3)], u = p[i >> 2][2 * (i & 3) + 1];
@@ -149,4 +175,27 @@ __device__ __forceinline__ void epi_apply_vec8(const GemmEpi& e, int m, int n, f
     *reinterpret_cast<uint4*>(cp + 8) = pack8(o[1]);
   }
 }
-
+// Calls f with the epilogue kind as a compile-time constant (std::integral_constant).
+template <typename F>
+__device__ __forceinline__ void epi_dispatch(int kind, F&& f) {
+  switch (kind) {
+    case EPI_STORE: f(std::integral_constant<int, EPI_STORE>{}); break;
+    case EPI_BIAS_ACT: f(std::integral_constant<int, EPI_BIAS_ACT>{}); break;
+    case EPI_ACT: f(std::integral_constant<int, EPI_ACT>{}); break;
+    case EPI_DACT: f(std::integral_constant<int, EPI_DACT>{}); break;
+    case EPI_DSWIGLU: f(std::integral_constant<int, EPI_DSWIGLU>{}); break;
+    case EPI_ROPE: f(std::integral_constant<int, EPI_ROPE>{}); break;
+    case EPI_SWIGLU: f(std::integral_constant<int, EPI_SWIGLU>{}); break;
+    default: break;
+  }
+}
+__device__ __forceinline__ void epi_apply_vec8(const GemmEpi& e, int m, int n, float (&v)[8]) {
+  float b[8];
+  const bool has_bias = epi_bias_load(e, n, b);
+  epi_dispatch(e.kind, [&](auto k_) __attribute__((always_inline)) {
+    constexpr int KIND = decltype(k_)::value;
+    EpiSide sd;
+    epi_side_load_k<KIND>(e, m, n, sd);
+    epi_apply_vec8_k<KIND>(e, m, n, v, has_bias, b, sd);
+  });
+}

@@ -215,8 +215,10 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   constexpr int RPI = 64 / LPR;         // rows per pass (96 columns: 5 rows, four lanes idle)
   constexpr int NIT = (32 + RPI - 1) / RPI;
   const int n = n0 + wn * WTN + (lane % LPR) * 8;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
+  const bool lane_on = lane / LPR < RPI && n < d.N;
+  const int mw = m0 + wm * WTM;
+  auto park = [&](auto i_) __attribute__((always_inline)) {   // accumulators of row block i -> this wavefront's LDS slice
+    constexpr int i = decltype(i_)::value;
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -225,27 +227,75 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  auto unpark = [&]() __attribute__((always_inline)) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  if (split) {
+    static_for<0, FM>([&](auto i_) __attribute__((always_inline)) {
+      park(i_);
 #pragma unroll 1
-    for (int it = 0; it < NIT; ++it) {
-      const int row = it * RPI + lane / LPR;
-      const int m = m0 + wm * WTM + i * 32 + row;
-      if (lane / LPR >= RPI || row >= 32 || m >= d.M || n >= d.N) continue;
+      for (int it = 0; it < NIT; ++it) {
+        const int row = it * RPI + lane / LPR;
+        const int m = mw + decltype(i_)::value * 32 + row;
+        if (!lane_on || row >= 32 || m >= d.M) continue;
+        float* p = part + static_cast<long long>(m) * d.N + n;
+        *reinterpret_cast<float4*>(p) = *reinterpret_cast<const float4*>(cs + row * WTN + (lane % LPR) * 8);
+        *reinterpret_cast<float4*>(p + 4) = *reinterpret_cast<const float4*>(cs + row * WTN + (lane % LPR) * 8 + 4);
+      }
+      unpark();
+    });
+    return;
+  }
+  // A lane keeps its 8 columns for every row: their bias is loaded once.  The epilogue kind is branched on once, here,
+  // so that each kind runs straight-line code.
+  float bias[8];
+  const bool has_bias = lane_on && epi_bias_load(d.epi, n, bias);
+  epi_dispatch(d.epi.kind, [&](auto kind_) __attribute__((always_inline)) {
+    constexpr int KIND = decltype(kind_)::value;
+    auto one_row = [&](int m, int row, const EpiSide sd) __attribute__((always_inline)) {
       float v[8];
       const float4 lo = *reinterpret_cast<const float4*>(cs + row * WTN + (lane % LPR) * 8);
       const float4 hi = *reinterpret_cast<const float4*>(cs + row * WTN + (lane % LPR) * 8 + 4);
       v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
-      if (split) {
-        float* p = part + static_cast<long long>(m) * d.N + n;
-        *reinterpret_cast<float4*>(p) = lo;
-        *reinterpret_cast<float4*>(p + 4) = hi;
-      } else {
-        epi_apply_vec8(d.epi, m, n, v);
-      }
+      epi_apply_vec8_k<KIND>(d.epi, m, n, v, has_bias, bias, sd);
+    };
+    if constexpr (epi_has_side(KIND)) {
+      // The inputs read beside the accumulators (saved pre-activations, rotation tables) run one 32-row block ahead:
+      // those of block 0 are requested before anything else, and as soon as a row is done the same registers request
+      // that row's inputs of the next block - so a load has a block's worth of work to land behind.
+      EpiSide sd[NIT];
+      auto request = [&](auto i_, auto it_) __attribute__((always_inline)) {
+        constexpr int i = decltype(i_)::value, it = decltype(it_)::value;
+        const int row = it * RPI + lane / LPR, m = mw + i * 32 + row;
+        if (lane_on && row < 32 && m < d.M) epi_side_load_k<KIND>(d.epi, m, n, sd[it]);
+      };
+      static_for<0, NIT>([&](auto it_) __attribute__((always_inline)) { request(std::integral_constant<int, 0>{}, it_); });
+      static_for<0, FM>([&](auto i_) __attribute__((always_inline)) {
+        constexpr int i = decltype(i_)::value;
+        park(i_);
+        static_for<0, NIT>([&](auto it_) __attribute__((always_inline)) {
+          constexpr int it = decltype(it_)::value;
+          const int row = it * RPI + lane / LPR, m = mw + i * 32 + row;
+          if (lane_on && row < 32 && m < d.M) one_row(m, row, sd[it]);
+          if constexpr (i + 1 < FM) request(std::integral_constant<int, i + 1>{}, it_);
+        });
+        unpark();
+      });
+    } else {
+      static_for<0, FM>([&](auto i_) __attribute__((always_inline)) {
+        park(i_);
+#pragma unroll 1
+        for (int it = 0; it < NIT; ++it) {
+          const int row = it * RPI + lane / LPR, m = mw + decltype(i_)::value * 32 + row;
+          if (lane_on && row < 32 && m < d.M) one_row(m, row, EpiSide{});
+        }
+        unpark();
+      });
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  }
+  });
 }
 
 // The configurations that are built.  They are instantiated explicitly: left to implicit
