@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the MFMA contraction kernels, averaged over the contraction launches of one sparse
 # step of the headline workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/):
 # (sha256 prefix of csrc/gemm*, bytes).  Reported only while the kernel sources still have that hash; otherwise null.
-GEMM_TRAFFIC = ("", 0.0)
+GEMM_TRAFFIC = ("08d5b540d783c615", 139.0e6)
 HEADLINE = "c3_llama1b_layer"
 SECOND = "c2_gpt2m_layer"
 
