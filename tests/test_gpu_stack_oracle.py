@@ -9,7 +9,7 @@ import torch
 from oracle import ecospa_oracle as O
 from paper_2511_11641_amd import binding as B
 from paper_2511_11641_amd.stack import DecoderStack
-from model_glue import ln_bwd, ln_fwd, rms_bwd, rms_fwd
+from oracle.glue_oracle import ln_bwd, ln_fwd, rms_bwd, rms_fwd
 from util import assert_close, host
 
 pytestmark = pytest.mark.gpu
