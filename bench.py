@@ -476,7 +476,7 @@ def stack_training(ctx, name, n_layers, vocab, Bsz, L, keeps, steps, rescore_eve
     return {"workload": f"{n_layers} x {name}", "batch": Bsz, "seq_len": L, "vocab": vocab,
             "rescore_every": rescore_every, "rows": rows,
             "tokens_per_s_formula": "rescore_every * T / ((rescore_every - 1) * ms_step + ms_rescore_step)",
-            "glue": "embedding, norms, residual adds, cross-entropy: torch operators; weights: device RNG, N(0, 0.02)"}
+            "glue": "embedding, norms with the residual adds, cross-entropy: the library's kernels (no torch operator in a step); weights: device RNG, N(0, 0.02)"}
 
 
 def stack_inference(ctx, name, n_layers, vocab, L, keeps, steps):

@@ -411,6 +411,49 @@ int ecospa_contract_colsum(ecospa_ctx* ctx, int M, int N, int K, const void* A, 
  * `splits` as passed to ecospa_contract (0 = the library's choice); 0 when K is not split or on bad input. */
 size_t ecospa_contract_workspace_bytes(int dtype, int M, int N, int K, int splits);
 
+/* ------------------------------------------------------------------------------------------
+ * Layer glue.  The operators between the two blocks of a pre-norm decoder layer and around the stack: normalisation
+ * with the residual addition in front of it, embedding lookup, mean cross-entropy.  The method leaves them as they
+ * are - only the coupled pairs lose dimensions (Sec. 3.1; Alg. 1 touches the pairs' matrices alone) - and they are
+ * the same for a dense and a sparse model; they are part of the library so that a whole training step of a stack
+ * (the workloads of Sec. 4.1) runs in its kernels.  bf16 storage, fp32 arithmetic, every result rounded once; all
+ * reductions in a fixed order (results repeat bit for bit).  Device pointers, rows contiguous (row r of a [T, d]
+ * tensor at offset r * d), 16-byte aligned; everything asynchronous on the context's stream.
+ * Errors, before any launch: ERR_NULL; ERR_DTYPE (dtype other than ECOSPA_BF16); ERR_SHAPE (T < 1, d < 8, d % 8,
+ * d > 4096, unknown kind, V > 65536, a leading dimension below V, T % L != 0 with a position table);
+ * ERR_ALIGN (a pointer off a 16-byte boundary, a leading dimension % 8); ERR_WORKSPACE (ecospa_norm_bwd).
+ *
+ * ecospa_norm_fwd: s = x + res (res NULL: s = x), rounded to bf16 and written to x_out when res is given (x_out may
+ *   be x itself); kind RMS: y = s / sqrt(mean(s^2) + eps) * gain; kind LAYER: y = (s - mean(s)) / sqrt(var(s) + eps)
+ *   * gain + bias (biased variance; bias NULL: none).  stat (NULL: not kept; float[T] for RMS: the reciprocal root,
+ *   float[2T] for LAYER: mean, reciprocal root per row) is what ecospa_norm_bwd needs.
+ * ecospa_norm_bwd: x = the s of the forward call.  dx = dres + the gradient through the normalisation (dres NULL:
+ *   none; dx may be dres itself), dgain[d] (and dbias[d] for LAYER, NULL: not wanted) in bf16.  Workspace:
+ *   ecospa_norm_bwd_workspace_bytes(T, d).
+ * ecospa_embed_fwd: out[t] = table[ids[t]] (+ pos[t mod L], pos NULL: none; then T % L == 0); ids are int64; an id
+ *   outside [0, vocab) reads as a zero row.
+ * ecospa_embed_bwd: dtable[vocab, d] is written whole: row v = the sum of dx[t] over the positions t with
+ *   ids[t] == v, added in position order in fp32 (zero for ids that do not occur; ids outside the table are
+ *   skipped); dpos[L, d] = sum over the sequences of dx (NULL: not wanted).  d <= 4096.
+ * ecospa_xent: row_loss[t] = log sum_j exp(logits[t, j]) - logits[t, targets[t]], *loss = mean over the T rows
+ *   (device float), dlogits[t, j] = (softmax(logits[t])[j] - [j == targets[t]]) / T in bf16 (NULL: loss only;
+ *   may be logits itself).  targets are int64; a target outside [0, V) makes its row count as zero loss and zero
+ *   gradient (the mean still divides by T).  ldl, ldd: leading dimensions in elements.
+ * ------------------------------------------------------------------------------------------ */
+#define ECOSPA_NORM_RMS 0
+#define ECOSPA_NORM_LAYER 1
+int ecospa_norm_fwd(ecospa_ctx* ctx, int kind, int T, int d, int dtype, const void* x, const void* res, void* x_out,
+                    const void* gain, const void* bias, float eps, void* y, float* stat);
+int ecospa_norm_bwd(ecospa_ctx* ctx, int kind, int T, int d, int dtype, const void* x, const void* gain,
+                    const float* stat, const void* dy, const void* dres, void* dx, void* dgain, void* dbias);
+size_t ecospa_norm_bwd_workspace_bytes(int T, int d);
+int ecospa_embed_fwd(ecospa_ctx* ctx, int T, int d, int vocab, int dtype, const long long* ids, const void* table,
+                     const void* pos, int L, void* out);
+int ecospa_embed_bwd(ecospa_ctx* ctx, int T, int d, int vocab, int dtype, const long long* ids, const void* dx,
+                     void* dtable, void* dpos, int L);
+int ecospa_xent(ecospa_ctx* ctx, int T, int V, int dtype, const void* logits, long long ldl, const long long* targets,
+                void* dlogits, long long ldd, float* row_loss, float* loss);
+
 #ifdef __cplusplus
 }
 #endif

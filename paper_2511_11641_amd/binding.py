@@ -30,7 +30,9 @@ EXPORTS = (
     "ecospa_select_pairs", "ecospa_rope_table_ragged", "ecospa_adamw", "ecospa_transpose_batch",
     "ecospa_check_indices", "ecospa_contract_workspace_bytes", "ecospa_hbm_probe", "ecospa_contract_colsum", "ecospa_mfma_probe",
     "ecospa_coupled_score_static", "ecospa_coupled_score_static_max_bytes",
+    "ecospa_norm_fwd", "ecospa_norm_bwd", "ecospa_norm_bwd_workspace_bytes", "ecospa_embed_fwd", "ecospa_embed_bwd", "ecospa_xent",
 )
+NORM_RMS, NORM_LAYER = 0, 1
 
 
 class EcospaError(RuntimeError):
@@ -171,6 +173,18 @@ def load() -> C.CDLL:
     lib.ecospa_mfma_probe.argtypes = [vp, vp, vp, ci, C.POINTER(C.c_double)]
     lib.ecospa_mfma_probe.restype = ci
     lib.ecospa_hbm_probe.argtypes = [vp, vp, vp, sz, ci]
+    lib.ecospa_norm_fwd.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, C.c_float, vp, vp]
+    lib.ecospa_norm_fwd.restype = ci
+    lib.ecospa_norm_bwd.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.ecospa_norm_bwd.restype = ci
+    lib.ecospa_norm_bwd_workspace_bytes.argtypes = [ci, ci]
+    lib.ecospa_norm_bwd_workspace_bytes.restype = sz
+    lib.ecospa_embed_fwd.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, ci, vp]
+    lib.ecospa_embed_fwd.restype = ci
+    lib.ecospa_embed_bwd.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, ci]
+    lib.ecospa_embed_bwd.restype = ci
+    lib.ecospa_xent.argtypes = [vp, ci, ci, ci, vp, ll, vp, vp, ll, vp, vp]
+    lib.ecospa_xent.restype = ci
     lib.ecospa_hbm_probe.restype = ci
     _lib = lib
     return lib
@@ -479,6 +493,56 @@ class Context:
         """dst = src^T for every item, one launch (see :meth:`transpose_item`)."""
         arr = items if isinstance(items, C.Array) else (TransposeItem * len(items))(*items)
         self._check(self.lib.ecospa_transpose_batch(self.h, arr, len(arr)), "ecospa_transpose_batch")
+
+    # ---- layer glue ----------------------------------------------------------------------------
+    def ecospa_norm_fwd(self, kind: int, x: torch.Tensor, gain: torch.Tensor, bias: Optional[torch.Tensor], eps: float,
+                        y: torch.Tensor, res: Optional[torch.Tensor] = None, x_out: Optional[torch.Tensor] = None,
+                        stat: Optional[torch.Tensor] = None):
+        """y = norm(x + res); x + res -> x_out; the row statistics -> stat (float32 [T] for RMS, [T, 2] for LayerNorm).
+        All [T, d] tensors contiguous bf16."""
+        T, d = x.shape
+        assert all(t is None or (t.is_contiguous() and t.shape == x.shape) for t in (x, y, res, x_out))
+        self._check(self.lib.ecospa_norm_fwd(self.h, kind, T, d, dtype_code(x.dtype), x.data_ptr(), _ptr(res), _ptr(x_out),
+                                             gain.data_ptr(), _ptr(bias), float(eps), y.data_ptr(), _ptr(stat)), "ecospa_norm_fwd")
+        return y
+
+    def ecospa_norm_bwd(self, kind: int, x: torch.Tensor, gain: torch.Tensor, stat: torch.Tensor, dy: torch.Tensor,
+                        dx: torch.Tensor, dgain: torch.Tensor, dbias: Optional[torch.Tensor] = None,
+                        dres: Optional[torch.Tensor] = None):
+        """dx = dres + the gradient of the normalisation; dgain (and dbias) = the parameter gradients."""
+        T, d = x.shape
+        assert all(t is None or (t.is_contiguous() and t.shape == x.shape) for t in (x, dy, dx, dres))
+        self.reserve(self.lib.ecospa_norm_bwd_workspace_bytes(T, d))
+        self._check(self.lib.ecospa_norm_bwd(self.h, kind, T, d, dtype_code(x.dtype), x.data_ptr(), gain.data_ptr(), stat.data_ptr(),
+                                             dy.data_ptr(), _ptr(dres), dx.data_ptr(), dgain.data_ptr(), _ptr(dbias)), "ecospa_norm_bwd")
+        return dx
+
+    def ecospa_embed_fwd(self, ids: torch.Tensor, table: torch.Tensor, out: torch.Tensor, pos: Optional[torch.Tensor] = None):
+        """out[t] = table[ids[t]] (+ pos[t mod L]); ids int64."""
+        assert ids.dtype == torch.int64 and ids.is_contiguous() and table.is_contiguous() and out.is_contiguous()
+        T, (V, d) = ids.numel(), table.shape
+        self._check(self.lib.ecospa_embed_fwd(self.h, T, d, V, dtype_code(table.dtype), ids.data_ptr(), table.data_ptr(), _ptr(pos),
+                                              0 if pos is None else pos.shape[0], out.data_ptr()), "ecospa_embed_fwd")
+        return out
+
+    def ecospa_embed_bwd(self, ids: torch.Tensor, dx: torch.Tensor, dtable: torch.Tensor, dpos: Optional[torch.Tensor] = None):
+        """dtable[v] = sum of dx[t] over ids[t] == v (the whole table is written); dpos[l] = sum over the sequences."""
+        assert ids.dtype == torch.int64 and ids.is_contiguous() and dx.is_contiguous() and dtable.is_contiguous()
+        T, (V, d) = ids.numel(), dtable.shape
+        self._check(self.lib.ecospa_embed_bwd(self.h, T, d, V, dtype_code(dx.dtype), ids.data_ptr(), dx.data_ptr(), dtable.data_ptr(),
+                                              _ptr(dpos), 0 if dpos is None else dpos.shape[0]), "ecospa_embed_bwd")
+
+    def ecospa_xent(self, logits: torch.Tensor, targets: torch.Tensor, row_loss: torch.Tensor, loss: torch.Tensor,
+                    dlogits: Optional[torch.Tensor] = None):
+        """Mean cross-entropy of the rows of logits [T, V] (bf16, row stride free) against int64 targets: the row losses,
+        the mean (a device float) and dlogits of the mean (may be logits itself)."""
+        assert targets.dtype == torch.int64 and targets.is_contiguous() and logits.stride(1) == 1
+        assert row_loss.dtype == torch.float32 and loss.dtype == torch.float32
+        T, V = logits.shape
+        self._check(self.lib.ecospa_xent(self.h, T, V, dtype_code(logits.dtype), logits.data_ptr(), logits.stride(0), targets.data_ptr(),
+                                         _ptr(dlogits), 0 if dlogits is None else dlogits.stride(0), row_loss.data_ptr(),
+                                         loss.data_ptr()), "ecospa_xent")
+        return loss
 
     # ---- parameter update ----------------------------------------------------------------------
     @staticmethod

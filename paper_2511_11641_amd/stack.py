@@ -5,10 +5,11 @@ forward-only inference at several keep ratios).
 What runs where.  Through the C ABI: the coupled scores (Eq. 10) of every pair of every layer in one call,
 the selection, the aligned gather of parameters, master copies and optimizer moments (Def. 1, Alg. 1), their
 write-back into the full-size arrays before the next estimate, both blocks' forward and backward
-contractions, the contractions of the output projection onto the vocabulary, and the AdamW update of every
-tensor.  Torch operators: the glue that is the same for a dense and a sparse model and is no part of the
-method - embedding lookup, LayerNorm / RMSNorm (and their backward, through autograd on the one operator),
-residual additions, the cross-entropy loss.
+contractions, the contractions of the output projection onto the vocabulary, the AdamW update of every
+tensor, and the glue that is the same for a dense and a sparse model and is no part of the method -
+embedding lookup and its gradient, LayerNorm / RMSNorm with the residual addition in front of them and
+their backward, the cross-entropy loss.  Torch allocates the buffers (once, when the stack is built) and
+owns the stream; no torch operator runs in a forward pass, a backward pass or an update.
 
 State between two estimates is compact (Alg. 1 removes rows and columns for good; here the full-size arrays
 stay resident so that the next estimate can bring a dimension back): fp32 master weights and both moments
@@ -21,7 +22,6 @@ from __future__ import annotations
 from typing import Optional
 
 import torch
-import torch.nn.functional as F
 
 from . import binding as B
 from .layer import AttnBlock, FfnBlock, rows_aligned
@@ -114,6 +114,7 @@ class DecoderStack:
         for ly in self.layers:
             ly.attn["w"].alloc(self.Bsz, self.L)
             ly.ffn["w"].alloc(self.Bsz, self.L)
+        self._alloc_glue()
         if train:
             self._build_optimizer()
 
@@ -122,30 +123,42 @@ class DecoderStack:
         ps = [_Param(torch.ones(self.d, device="cuda"), self.train)]
         if not self.rms:
             ps.append(_Param(torch.zeros(self.d, device="cuda"), self.train))
-        for p in ps:
-            p.w.requires_grad_(self.train)
         return ps
 
-    def _norm(self, x, ps):
-        if self.rms:
-            return F.rms_norm(x, (self.d,), ps[0].w, self.eps)
-        return F.layer_norm(x, (self.d,), ps[0].w, ps[1].w, self.eps)
+    def _alloc_glue(self):
+        """Activations of the glue, allocated once: per normalisation its input (the residual stream at that point), its
+        output and its row statistics; the stream's gradient ping-pongs between two buffers."""
+        T, d, dev = self.T, self.d, "cuda"
+        bf = lambda *shape: torch.empty(shape, dtype=torch.bfloat16, device=dev)
+        st = lambda: torch.empty((T,) if self.rms else (T, 2), dtype=torch.float32, device=dev) if self.train else None
+        n_norm = 2 * len(self.layers) + 1
+        self.x0 = bf(T, d)                                         # embedding output
+        keep = n_norm if self.train else 1                          # inference: one buffer serves every normalisation
+        self.xs = [bf(T, d) for _ in range(keep)]                  # input of normalisation i (x0 itself for i = 0)
+        self.hs = [bf(T, d) for _ in range(keep)]                  # its output
+        self.stats = [st() for _ in range(keep)]
+        self.logits = bf(T, self.vocab)
+        if self.train:
+            self.dxa, self.dxb = bf(T, d), bf(T, d)
+            self.row_loss = torch.empty(T, dtype=torch.float32, device=dev)
+            self.loss = torch.zeros((), dtype=torch.float32, device=dev)
+            self.dhf = bf(T, d)
 
-    def _norm_fwd(self, x, ps):
-        """-> (input leaf, output): the operator runs under autograd when training, so that its backward is one call."""
-        if not self.train:
-            return None, self._norm(x, ps)
-        leaf = x.detach().requires_grad_(True)
-        with torch.enable_grad():
-            y = self._norm(leaf, ps)
-        return leaf, y
+    def _norm_fwd(self, i, ps, x, res):
+        """Normalisation i of the stack on x + res -> (the sum, the normalised rows)."""
+        j = i if self.train else 0
+        kind = B.NORM_RMS if self.rms else B.NORM_LAYER
+        x_out = self.xs[j] if res is not None else None
+        self.ctx.ecospa_norm_fwd(kind, x, ps[0].w, None if self.rms else ps[1].w, self.eps, self.hs[j], res=res, x_out=x_out,
+                                 stat=self.stats[j])
+        if res is None:
+            self.xs[j] = x
+        return self.xs[j], self.hs[j]
 
-    @staticmethod
-    def _norm_bwd(leaf, y, ps, dy):
-        grads = torch.autograd.grad(y, [leaf] + [p.w for p in ps], dy)
-        for p, g in zip(ps, grads[1:]):
-            p.g.copy_(g)
-        return grads[0]
+    def _norm_bwd(self, i, ps, dy, dres, dx):
+        kind = B.NORM_RMS if self.rms else B.NORM_LAYER
+        return self.ctx.ecospa_norm_bwd(kind, self.xs[i], ps[0].w, self.stats[i], dy, dx, ps[0].g,
+                                        dbias=None if self.rms else ps[1].g, dres=dres)
 
     # ---- steps 1-3 for the whole stack -----------------------------------------------------------------
     def _descriptors(self):
@@ -210,43 +223,38 @@ class DecoderStack:
     @torch.no_grad()
     def forward(self, ids: torch.Tensor, lm_head: bool = True):
         """ids: int64 [B*L] -> logits bf16 [B*L, vocab] (or the final hidden states with lm_head=False)."""
-        x = self.emb.w[ids]
-        if self.pos is not None:
-            x = (x.view(self.Bsz, self.L, self.d) + self.pos.w).view(self.T, self.d)
-        for ly in self.layers:
-            ly.leaf1, ly.h1 = self._norm_fwd(x, ly.norm[0])
-            x = x + ly.attn["w"].fwd(ly.h1.detach(), save=self.train)
-            ly.leaf2, ly.h2 = self._norm_fwd(x, ly.norm[1])
-            x = x + ly.ffn["w"].fwd(ly.h2.detach(), save=self.train)
-        self.leaf_f, self.hf = self._norm_fwd(x, self.norm_f)
+        ctx = self.ctx
+        x = ctx.ecospa_embed_fwd(ids, self.emb.w, self.x0, pos=None if self.pos is None else self.pos.w)
+        res = None                       # the block output that the next normalisation adds to the stream first
+        for li, ly in enumerate(self.layers):
+            x, ly.h1 = self._norm_fwd(2 * li, ly.norm[0], x, res)
+            res = ly.attn["w"].fwd(ly.h1, save=self.train)
+            x, ly.h2 = self._norm_fwd(2 * li + 1, ly.norm[1], x, res)
+            res = ly.ffn["w"].fwd(ly.h2, save=self.train)
+        _, self.hf = self._norm_fwd(2 * len(self.layers), self.norm_f, x, res)
         if not lm_head:
             return self.hf
-        self.logits = self.ctx.ecospa_contract(self.hf.detach(), False, self.lm.w, False, splits=1,
-                                               out=getattr(self, "logits", None))
+        ctx.ecospa_contract(self.hf, False, self.lm.w, False, splits=1, out=self.logits)
         return self.logits
 
     @torch.no_grad()
     def backward(self, ids: torch.Tensor, targets: torch.Tensor):
-        """Mean cross-entropy of the last forward's logits against targets; fills every gradient buffer."""
-        ctx = self.ctx
-        lg = self.logits.detach().requires_grad_(True)
-        with torch.enable_grad():
-            loss = F.cross_entropy(lg.float(), targets)
-        (dl,) = torch.autograd.grad(loss, lg)
-        hf = self.hf.detach()
-        ctx.ecospa_contract(dl, True, hf, True, splits=1, out=self.lm.g)              # dW = dlogits^T h
-        dhf = ctx.ecospa_contract(dl, False, self.lm.w, True, splits=1)                # dh = dlogits W
-        dx = self._norm_bwd(self.leaf_f, self.hf, self.norm_f, dhf)
-        for ly in reversed(self.layers):
-            dh2 = ly.ffn["w"].bwd(ly.h2.detach(), dx)
-            dx = dx + self._norm_bwd(ly.leaf2, ly.h2, ly.norm[1], dh2)
-            dh1 = ly.attn["w"].bwd(ly.h1.detach(), dx)
-            dx = dx + self._norm_bwd(ly.leaf1, ly.h1, ly.norm[0], dh1)
-        self.emb.g.zero_()
-        self.emb.g.index_add_(0, ids, dx)
-        if self.pos is not None:
-            self.pos.g.copy_(dx.view(self.Bsz, self.L, self.d).sum(0))
-        return loss.detach()
+        """Mean cross-entropy of the last forward's logits against targets; fills every gradient buffer.  The logits
+        buffer holds their gradient afterwards."""
+        ctx, nl = self.ctx, len(self.layers)
+        ctx.ecospa_xent(self.logits, targets, self.row_loss, self.loss, dlogits=self.logits)
+        dl = self.logits
+        ctx.ecospa_contract(dl, True, self.hf, True, splits=1, out=self.lm.g)         # dW = dlogits^T h
+        ctx.ecospa_contract(dl, False, self.lm.w, True, splits=1, out=self.dhf)       # dh = dlogits W
+        dx, spare = self._norm_bwd(2 * nl, self.norm_f, self.dhf, None, self.dxa), self.dxb
+        for li in reversed(range(nl)):
+            ly = self.layers[li]
+            dh2 = ly.ffn["w"].bwd(ly.h2, dx)
+            dx, spare = self._norm_bwd(2 * li + 1, ly.norm[1], dh2, dx, spare), dx
+            dh1 = ly.attn["w"].bwd(ly.h1, dx)
+            dx, spare = self._norm_bwd(2 * li, ly.norm[0], dh1, dx, spare), dx
+        ctx.ecospa_embed_bwd(ids, dx, self.emb.g, dpos=None if self.pos is None else self.pos.g)
+        return self.loss
 
     def update(self):
         """AdamW on every compact tensor and glue parameter (fp32 masters and moments, bf16 working copies written by
@@ -260,4 +268,4 @@ class DecoderStack:
         self.forward(ids)
         loss = self.backward(ids, targets)
         self.update()
-        return loss.detach()
+        return loss

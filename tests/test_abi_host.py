@@ -199,3 +199,33 @@ def test_static_scratch_score_validates_before_touching_the_device(lib, ctx):
     big = B.Pair(B.PAIR_FFN, B.F32, 1, 300000, 1, 8, 8, 256, None, 512, 8, 0, 300000)
     assert lib.ecospa_score_workspace_bytes((B.Pair * 1)(big), 1) > lib.ecospa_coupled_score_static_max_bytes()
     assert f(ctx, (B.Pair * 1)(big), 1, out) == B.ERR_WORKSPACE
+
+
+def test_glue_validation(lib, ctx):
+    p = 4096      # any 16-byte aligned non-null value: nothing is launched on a validation error
+    nf, nb = lib.ecospa_norm_fwd, lib.ecospa_norm_bwd
+    assert nf(ctx, B.NORM_RMS, 4, 64, B.BF16, None, None, None, p, None, 1e-6, p, None) == B.ERR_NULL
+    assert nf(ctx, B.NORM_RMS, 4, 64, B.BF16, p, p, None, p, None, 1e-6, p, None) == B.ERR_NULL       # res without x_out
+    assert nf(ctx, B.NORM_RMS, 4, 64, B.F32, p, None, None, p, None, 1e-6, p, None) == B.ERR_DTYPE
+    assert nf(ctx, 2, 4, 64, B.BF16, p, None, None, p, None, 1e-6, p, None) == B.ERR_SHAPE
+    assert nf(ctx, B.NORM_RMS, 0, 64, B.BF16, p, None, None, p, None, 1e-6, p, None) == B.ERR_SHAPE
+    assert nf(ctx, B.NORM_RMS, 4, 60, B.BF16, p, None, None, p, None, 1e-6, p, None) == B.ERR_SHAPE
+    assert nf(ctx, B.NORM_RMS, 4, 4104, B.BF16, p, None, None, p, None, 1e-6, p, None) == B.ERR_SHAPE
+    assert nf(ctx, B.NORM_RMS, 4, 64, B.BF16, p + 2, None, None, p, None, 1e-6, p, None) == B.ERR_ALIGN
+    assert nb(ctx, B.NORM_LAYER, 4, 64, B.BF16, p, p, None, p, None, p, p, p) == B.ERR_NULL          # no statistics
+    assert nb(ctx, B.NORM_LAYER, 4, 64, B.BF16, p, p, p, p, None, p, p, p) == B.ERR_WORKSPACE        # none attached
+    assert lib.ecospa_norm_bwd_workspace_bytes(8192, 2048) >= 512 * 2 * 2048 * 4
+    assert lib.ecospa_norm_bwd_workspace_bytes(0, 2048) == 0
+    ef, eb = lib.ecospa_embed_fwd, lib.ecospa_embed_bwd
+    assert ef(ctx, 8, 64, 100, B.BF16, None, p, None, 0, p) == B.ERR_NULL
+    assert ef(ctx, 8, 64, 100, B.BF16, p, p, p, 3, p) == B.ERR_SHAPE                                  # 8 positions, table of 3
+    assert ef(ctx, 8, 12, 100, B.BF16, p, p, None, 0, p) == B.ERR_SHAPE
+    assert ef(ctx, 8, 64, 100, B.F32, p, p, None, 0, p) == B.ERR_DTYPE
+    assert eb(ctx, 8, 8192, 100, B.BF16, p, p, p, None, 0) == B.ERR_SHAPE
+    assert eb(ctx, 8, 64, 100, B.BF16, p, p + 8, p, None, 0) == B.ERR_ALIGN
+    xe = lib.ecospa_xent
+    assert xe(ctx, 4, 100, B.BF16, p, 104, p, None, 0, None, p) == B.ERR_NULL
+    assert xe(ctx, 4, 100, B.BF16, p, 96, p, None, 0, p, p) == B.ERR_SHAPE                            # rows overlap
+    assert xe(ctx, 4, 70000, B.BF16, p, 70000, p, None, 0, p, p) == B.ERR_SHAPE
+    assert xe(ctx, 4, 100, B.BF16, p, 100, p, None, 0, p, p) == B.ERR_ALIGN                           # leading dimension % 8
+    assert xe(ctx, 4, 100, B.F32, p, 104, p, None, 0, p, p) == B.ERR_DTYPE

@@ -108,7 +108,7 @@ def test_two_layer_step_against_the_oracle(ctx, cfg):
             s = st.scores[3 * li + j]
             assert_close(s, want[j], "f32", f"layer {li} score {j}")
             assert np.array_equal(ly.idx[j].cpu().numpy(), O.select_topk(s.cpu().numpy(), st.k[j]))
-    logits = st.forward(ids)
+    logits = st.forward(ids).clone()      # backward turns the buffer into the gradient of the logits
     loss = st.backward(ids, tgt)
     torch.cuda.synchronize()
     o = _oracle_step(st, ids.cpu().numpy(), tgt.cpu().numpy())
