@@ -436,8 +436,8 @@ def stack_training(ctx, name, n_layers, vocab, Bsz, L, keeps, steps, rescore_eve
     """Whole-model training step of a stack of `name`-shaped layers (embedding, pre-norm layers, output projection,
     cross-entropy, AdamW with fp32 master weights): per keep ratio the time of a plain step, of a step that first
     estimates the coupled importance again (write-back, score, select, gather of all layers), and the throughput with
-    one such step in every `rescore_every`.  Norms, residuals, embedding and loss are torch operators; everything else
-    runs in the library."""
+    one such step in every `rescore_every`.  Every kernel of a step is the library's (norms, residuals, embedding and
+    loss included); torch allocates and draws the initial weights."""
     import torch
     from paper_2511_11641_amd import synth
     from paper_2511_11641_amd.stack import DecoderStack
@@ -547,6 +547,40 @@ def cpu_baseline(cfg, seed, keep_num, keep_den, sample_B):
                       f"score+select+compact+fwd+bwd in fp64 numpy, {dt:.1f} s"}
 
 
+def stack_shrink_schedule(ctx, name, n_layers, vocab, Bsz, L, schedule, steps):
+    """Alg. 1 with removal for good on a stack of `name`-shaped layers: built dense, the full-size arrays released, then
+    shrunk stage by stage from its own compact state (parameters, fp32 master copies and both moments together).  Per
+    stage: the time of the shrinking call, of a training step afterwards, and the device memory the process holds
+    (weights in all four families, gradients, the activations of one step, the workspace)."""
+    import torch
+    from paper_2511_11641_amd import synth
+    from paper_2511_11641_amd.stack import DecoderStack
+    cfg = dict(synth.CONFIGS[name], B=Bsz, L=L)
+    T = Bsz * L
+    ids = torch.randint(0, vocab, (T,), device="cuda")
+    tgt = torch.roll(ids, -1)
+    torch.cuda.empty_cache()
+    base = torch.cuda.memory_allocated()
+    st = DecoderStack(ctx, cfg, n_layers, vocab, keep=(1, 1), seed=1, train=True, permanent=True)
+    rows = []
+    for num, den in schedule:
+        ms_shrink = None
+        if (num, den) != (1, 1):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            st.shrink((num, den))
+            torch.cuda.synchronize()
+            ms_shrink = (time.perf_counter() - t0) * 1e3
+        ms_step = timed(torch, lambda: st.train_step(ids, tgt), steps, 1)
+        rows.append({"keep": f"{num}/{den}", "ms_shrink": ms_shrink, "ms_step": ms_step, "tokens_per_s": T / (ms_step * 1e-3),
+                     "resident_GB": (torch.cuda.memory_allocated() - base) / 1e9, "trained_params_M": st.n_params / 1e6})
+    del st
+    torch.cuda.empty_cache()
+    return {"workload": f"{n_layers} x {name}, removal for good", "batch": Bsz, "seq_len": L, "vocab": vocab, "rows": rows,
+            "note": "resident_GB: device memory held by the stack (four families of every kept tensor, gradients, one step's "
+                    "activations, workspace); the dense stage holds no second full-size copy either"}
+
+
 def stack_workloads(ctx):
     """The two whole-model workloads: the LLaMA-1B-shaped 24-layer training step (batch 32 x 256, vocabulary 32000,
     importance estimated again every 200 steps, 50 % keep, beside the dense model) and the GPT-2-Medium-shaped
@@ -556,6 +590,7 @@ def stack_workloads(ctx):
         "stack_llama1b_train": stack_training(ctx, "c3_llama1b_layer", 24, 32000, 32, 256, ((1, 1), (1, 2)), 4),
         "stack_gpt2m_train_sweep": stack_training(ctx, "c2_gpt2m_layer", 24, 50304, 8, 1024, sweep, 4),
         "stack_gpt2m_inference": stack_inference(ctx, "c2_gpt2m_layer", 24, 50304, 1024, sweep, 4),
+        "stack_llama1b_shrink": stack_shrink_schedule(ctx, "c3_llama1b_layer", 24, 32000, 32, 256, ((1, 1), (3, 4), (1, 2)), 3),
     }
 
 

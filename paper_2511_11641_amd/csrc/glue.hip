@@ -225,17 +225,35 @@ __global__ __launch_bounds__(GLUE_NORM_THREADS) void norm_bwd_kernel(const NormB
     }
   }
 }
-// dgain[c] (and dbias[c]) = the partial rows of all workgroups added in order, rounded once.
-__global__ __launch_bounds__(256) void norm_bwd_finish_kernel(const float* part, int blocks, int d, int layer, bf16_t* dgain, bf16_t* dbias) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= d) return;
+// dgain[c] (and dbias[c]) = the partial rows of all workgroups, rounded once.  A workgroup takes 64 columns: its 16
+// wavefronts each add a contiguous sixteenth of the partial rows (eight loads in flight per lane), then the sixteen
+// sums are added in order - a fixed order altogether.
+#define GLUE_FIN_SLICES 16
+__global__ __launch_bounds__(64 * GLUE_FIN_SLICES) void norm_bwd_finish_kernel(const float* part, int blocks, int d, int layer,
+                                                                               bf16_t* dgain, bf16_t* dbias) {
+  __shared__ float red[2][GLUE_FIN_SLICES][64];
+  const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
+  const int per = (blocks + GLUE_FIN_SLICES - 1) / GLUE_FIN_SLICES;
+  const int b0 = slice * per, b1 = min(blocks, b0 + per);
   float sg = 0.f, sb = 0.f;
-  for (int b = 0; b < blocks; ++b) {
-    sg += part[(static_cast<long long>(b) * 2) * d + c];
-    if (layer) sb += part[(static_cast<long long>(b) * 2 + 1) * d + c];
+  if (c < d) {
+#pragma unroll 8
+    for (int b = b0; b < b1; ++b) {
+      sg += part[(static_cast<long long>(b) * 2) * d + c];
+      if (layer) sb += part[(static_cast<long long>(b) * 2 + 1) * d + c];
+    }
   }
-  dgain[c] = f32_to_bf16(sg);
-  if (layer && dbias) dbias[c] = f32_to_bf16(sb);
+  red[0][slice][lane] = sg;
+  red[1][slice][lane] = sb;
+  __syncthreads();
+  if (slice == 0 && c < d) {
+    float tg = 0.f, tb = 0.f;
+#pragma unroll
+    for (int q = 0; q < GLUE_FIN_SLICES; ++q) { tg += red[0][q][lane]; tb += red[1][q][lane]; }
+    dgain[c] = f32_to_bf16(tg);
+    if (layer && dbias) dbias[c] = f32_to_bf16(tb);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -493,7 +511,7 @@ extern "C" int ecospa_norm_bwd(ecospa_ctx* ctx, int kind, int T, int d, int dtyp
   else NORM_BWD_LAUNCH(GLUE_MAXC);
 #undef NORM_BWD_LAUNCH
   ECOSPA_CHECK_LAUNCH(ctx, "norm_bwd_kernel");
-  hipLaunchKernelGGL(norm_bwd_finish_kernel, dim3((d + 255) / 256), dim3(256), 0, ctx->stream, part, blocks, d, a.layer,
+  hipLaunchKernelGGL(norm_bwd_finish_kernel, dim3((d + 63) / 64), dim3(64 * GLUE_FIN_SLICES), 0, ctx->stream, part, blocks, d, a.layer,
                      static_cast<bf16_t*>(dgain), static_cast<bf16_t*>(dbias));
   ECOSPA_CHECK_LAUNCH(ctx, "norm_bwd_finish_kernel");
   return ECOSPA_OK;

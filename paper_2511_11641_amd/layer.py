@@ -39,6 +39,7 @@ class FfnBlock:
         self.n, self.d = w1.shape
         self.gated = act == B.ACT_SWIGLU
         self.idx = None
+        self.rebased = False      # True: the block's own tensors are views of its compact ones (see rebase)
 
     def pair(self) -> B.Pair:
         kind = B.PAIR_FFN_GATED if self.gated else B.PAIR_FFN
@@ -65,8 +66,9 @@ class FfnBlock:
         self.kp = kp = B.round_up(k, 64 if k >= 512 else 16)
         nh = 2 * kp if self.gated else kp
         dt, dev = self.w1.dtype, self.w1.device
-        resized = getattr(self, "w1_c", None) is None or self.w1_c.shape[0] != nh
-        if resized:     # buffers are reused across re-compactions of the same width
+        assert k_group is None or not self.rebased, "a block that was rebased shrinks by fixed counts"
+        resized = getattr(self, "w1_c", None) is None or self.w1_c.shape[0] != nh or self.rebased
+        if resized:     # buffers are reused across re-compactions of the same width (never the ones a rebased block reads)
             self.w1_c = torch.empty((nh, self.d), dtype=dt, device=dev)
             self.b1_c = None if self.b1 is None else torch.zeros((nh,), dtype=dt, device=dev)
             self.w2_c = torch.empty((self.d, kp), dtype=dt, device=dev)
@@ -80,6 +82,21 @@ class FfnBlock:
             return items
         c.ecospa_compact_batch(items)
         self.refresh_transposed()
+        return self
+
+    def rebase(self):
+        """Alg. 1's removal for good: the compact tensors become the block's own and what they were gathered from is
+        let go (its memory is free once the caller drops its references too).  The next :meth:`compact` then takes
+        indices into the present compact layout (positions 0 .. k-1 of the kept units, in order) and gathers into
+        fresh buffers; padding units have zero weights, score zero and are never kept.  No write-back exists from here on."""
+        kp = self.kp
+        self.w1 = self.gate_rows(self.w1_c)
+        self.w1b = self.up_rows(self.w1_c) if self.gated else None
+        if self.b1 is not None:
+            self.b1 = self.b1_c.view(kp, 2)[:, 0] if self.gated else self.b1_c
+        self.w2 = self.w2_c
+        self.n = kp
+        self.rebased = True
         return self
 
     def gate_rows(self, t: torch.Tensor) -> torch.Tensor:
@@ -108,6 +125,7 @@ class FfnBlock:
 
     def write_back_items(self):
         """Scatters of the compact tensors into the full-size ones that leave the pruned rows/columns as they are."""
+        assert not self.rebased, "no full-size tensors to write back to"
         return self._map_items(2)
 
     def transpose_items(self):
@@ -182,11 +200,23 @@ class AttnBlock:
         self.bq, self.bk, self.bv, self.bo = bq, bk, bv, bo
         self.d = wq.shape[1]
         self.unit = 2 if rope else 1
+        self.n_qk = self.n_vo = d_h     # inner width per head of the tensors the block gathers from (d_h until rebase)
+        self.rebased = False
+        self.orig_qk = None             # rebased: original rotary block of every unit the block gathers from, int32 [h_kv, units]
 
     def pairs(self):
         mk = B.Context.make_pair
-        return [mk(B.PAIR_QK, self.wq, self.wk, self.h_kv, self.d_h, self.unit, rep1=self.qpk),
-                mk(B.PAIR_VO, self.wv, self.wo, self.h_kv, self.d_h, 1, rep2=self.qpk)]
+        return [mk(B.PAIR_QK, self.wq, self.wk, self.h_kv, self.n_qk, self.unit, rep1=self.qpk),
+                mk(B.PAIR_VO, self.wv, self.wo, self.h_kv, self.n_vo, 1, rep2=self.qpk)]
+
+    def track_rotary_blocks(self):
+        """Before the first :meth:`compact` of a block that will be rebased: keep, beside the index lists, the original
+        rotary block of every kept unit - the frequencies of Eq. 6 belong to the original positions, however often the
+        block shrinks."""
+        if self.rope and self.orig_qk is None:
+            n_units = self.n_qk // self.unit
+            self.orig_qk = torch.arange(n_units, dtype=torch.int32, device=self.wq.device).repeat(self.h_kv, 1).contiguous()
+        return self
 
     def score(self):
         return self.ctx.ecospa_coupled_score(self.pairs())
@@ -212,8 +242,11 @@ class AttnBlock:
         nq, nk, nv, no = h * self.kp_qk, hk * self.kp_qk, hk * self.kp_vo, h * self.kp_vo
         self.nq, self.nk = nq, nk
         dt, dev = self.wq.dtype, self.wq.device
+        assert (k_qk_group is None and k_vo_group is None) or not self.rebased, "a block that was rebased shrinks by fixed counts"
         resized = (getattr(self, "wqkv_c", None) is None or self.wqkv_c.shape[0] != nq + nk + nv
-                   or self.wo_c.shape[1] != no)
+                   or self.wo_c.shape[1] != no or self.rebased)
+        if self.orig_qk is not None:    # original rotary blocks of the kept units: gathered like everything else
+            self.rope_idx = torch.empty((hk, self.k_qk_units), dtype=torch.int32, device=dev)
         if resized:
             self.wqkv_c = torch.empty((nq + nk + nv, self.d), dtype=dt, device=dev)
             self.bqkv_c = None if self.bq is None else torch.empty((nq + nk + nv,), dtype=dt, device=dev)
@@ -234,15 +267,15 @@ class AttnBlock:
 
     def _map_items(self, scatter: int):
         """Descriptors between every full-size member and its compact counterpart: gathers (0) or scatters (1, 2)."""
-        h, hk, dh, u = self.h, self.h_kv, self.d_h, self.unit
+        h, hk, u = self.h, self.h_kv, self.unit
         nq, nk, kpu = self.nq, self.nk, self.kp_qk // u
 
         def mq(full, cmp, axis, heads):      # heads that share an index list with (heads // h_kv - 1) others
-            return B.Context.map_item(cmp if scatter else full, full if scatter else cmp, self.idx_qk, axis, heads, dh, u, kpu,
+            return B.Context.map_item(cmp if scatter else full, full if scatter else cmp, self.idx_qk, axis, heads, self.n_qk, u, kpu,
                                       scatter=scatter, k_group=self.k_qk_group, idx_div=heads // hk)
 
         def mv(full, cmp, axis, heads):
-            return B.Context.map_item(cmp if scatter else full, full if scatter else cmp, self.idx_vo, axis, heads, dh, 1,
+            return B.Context.map_item(cmp if scatter else full, full if scatter else cmp, self.idx_vo, axis, heads, self.n_vo, 1,
                                       self.kp_vo, scatter=scatter, k_group=self.k_vo_group, idx_div=heads // hk)
 
         items = [mq(self.wq, self.wqkv_c[:nq], 0, h), mq(self.wk, self.wqkv_c[nq:nq + nk], 0, hk),
@@ -251,11 +284,33 @@ class AttnBlock:
             items += [mq(self.bq, self.bqkv_c[:nq], 1, h), mq(self.bk, self.bqkv_c[nq:nq + nk], 1, hk),
                       mv(self.bv, self.bqkv_c[nq + nk:], 1, hk)]
         items.append(mv(self.wo, self.wo_c, 1, h))
+        if self.orig_qk is not None and not scatter:      # the int32 table moves as 4-byte words
+            items.append(B.Context.map_item(self.orig_qk.view(torch.float32).view(-1), self.rope_idx.view(torch.float32).view(-1),
+                                            self.idx_qk, 1, hk, self.orig_qk.shape[1], 1, self.k_qk_units))
         return items
 
     def write_back_items(self):
         """Scatters of the compact tensors into the full-size ones that leave the pruned rows/columns as they are."""
+        assert not self.rebased, "no full-size tensors to write back to"
         return self._map_items(2)
+
+    def rebase(self):
+        """Alg. 1's removal for good: the compact tensors become the block's own and what they were gathered from is
+        let go.  The next :meth:`compact` takes indices into the present compact layout of every head (positions
+        0 .. k-1 of its kept units, in order) and gathers into fresh buffers; padding units have zero weights and are
+        never kept.  The attention scale and the rotary frequencies stay those of the original head width and block
+        positions (call :meth:`track_rotary_blocks` before the first compaction).  No write-back from here on."""
+        assert self.k_qk_group is None and self.k_vo_group is None, "fixed kept counts only"
+        assert not self.rope or self.orig_qk is not None, "track_rotary_blocks() before the first compaction"
+        nq, nk = self.nq, self.nk
+        self.wq, self.wk, self.wv, self.wo = self.wqkv_c[:nq], self.wqkv_c[nq:nq + nk], self.wqkv_c[nq + nk:], self.wo_c
+        if self.bq is not None:
+            self.bq, self.bk, self.bv = self.bqkv_c[:nq], self.bqkv_c[nq:nq + nk], self.bqkv_c[nq + nk:]
+        self.n_qk, self.n_vo = self.kp_qk, self.kp_vo
+        if self.rope:
+            self.orig_qk = self.rope_idx
+        self.rebased = True
+        return self
 
     def transpose_items(self):
         if not self.transposed:
@@ -270,7 +325,8 @@ class AttnBlock:
         if self.k_qk_group is not None:
             return self.ctx.ecospa_rope_table_ragged(self.idx_qk, self.k_qk_group, L, self.kp_qk // 2, self.d_h,
                                                      self.rope_base, out=out)
-        return self.ctx.ecospa_rope_table(self.idx_qk, self.h_kv, L, self.k_qk_units, self.kp_qk // 2, self.d_h,
+        blocks = self.idx_qk if self.orig_qk is None else self.rope_idx      # original block positions of the kept units
+        return self.ctx.ecospa_rope_table(blocks, self.h_kv, L, self.k_qk_units, self.kp_qk // 2, self.d_h,
                                           self.rope_base, out=out)
 
     def alloc(self, Bsz: int, L: int):

@@ -11,11 +11,15 @@ embedding lookup and its gradient, LayerNorm / RMSNorm with the residual additio
 their backward, the cross-entropy loss.  Torch allocates the buffers (once, when the stack is built) and
 owns the stream; no torch operator runs in a forward pass, a backward pass or an update.
 
-State between two estimates is compact (Alg. 1 removes rows and columns for good; here the full-size arrays
-stay resident so that the next estimate can bring a dimension back): fp32 master weights and both moments
-live in the compact layout and only they are updated; pruned rows/columns of the full-size arrays are
-frozen - no gradient reaches them - until `prune()` writes the compact state back, scores the full-size
-master weights again and gathers the new choice.
+State between two estimates is compact: fp32 master weights and both moments live in the compact layout
+and only they are updated.  Two ways to estimate again:
+  * `prune()` (default): the full-size arrays stay resident so that a later estimate can bring a dimension
+    back; pruned rows/columns are frozen - no gradient reaches them - until `prune()` writes the compact
+    state back, scores the full-size master weights again and gathers the new choice;
+  * `shrink(keep)` with `permanent=True`: Alg. 1 as printed - rows and columns are removed for good.  The
+    full-size arrays are released after the first gather; every later call scores the compact master
+    weights, keeps fewer units of what is left and gathers parameters, master copies and both moments
+    from the compact layout into a smaller one, so the resident state falls with the kept fraction.
 """
 from __future__ import annotations
 
@@ -50,11 +54,11 @@ class _Layer:
 
 class DecoderStack:
     def __init__(self, ctx: B.Context, cfg: dict, n_layers: int, vocab: int, keep=(1, 2), seed: int = 0,
-                 train: bool = True, lr: float = 1e-4, weight_decay: float = 0.01):
+                 train: bool = True, lr: float = 1e-4, weight_decay: float = 0.01, permanent: bool = False):
         """cfg: B, L, d, h, d_h, d_ff, gated, rope, bias as in synth.CONFIGS, optionally h_kv (gated: RMSNorm, no position table;
         otherwise LayerNorm with a learned position table).  keep = (num, den): every pair keeps
         floor(n * num / den) of its units; (1, 1) is the dense model through the same code."""
-        self.ctx, self.cfg, self.train = ctx, cfg, train
+        self.ctx, self.cfg, self.train, self.permanent = ctx, cfg, train, permanent
         self.Bsz, self.L, self.d, self.h, self.d_h, self.d_ff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
         self.h_kv = cfg.get("h_kv", self.h)      # fewer key/value heads than query heads: grouped-query attention (Eq. 5)
         self.T = self.Bsz * self.L
@@ -95,6 +99,8 @@ class DecoderStack:
                                          h_kv=hkv)
                 ly.ffn[fam] = FfnBlock(ctx, t["w1"], t.get("b1"), t["w2"], t.get("b2"), act, t.get("w1b"),
                                        transposed=(fam == "w" and train))
+                if permanent:
+                    ly.attn[fam].track_rotary_blocks()
             ly.idx = [torch.empty((hkv, self.k[0]), dtype=torch.int32, device="cuda"),
                       torch.empty((hkv, self.k[1]), dtype=torch.int32, device="cuda"),
                       torch.empty((1, self.k[2]), dtype=torch.int32, device="cuda")]
@@ -111,6 +117,8 @@ class DecoderStack:
         self.scores = None
         self.compacted = False
         self.prune()
+        if permanent:
+            self._rebase()
         for ly in self.layers:
             ly.attn["w"].alloc(self.Bsz, self.L)
             ly.ffn["w"].alloc(self.Bsz, self.L)
@@ -171,7 +179,7 @@ class DecoderStack:
         for ly in self.layers:
             for fam in fams:          # compact() with defer=True also sizes the family's compact buffers
                 gather += ly.attn[fam].compact(ly.idx[0], ly.idx[1], defer=True) + ly.ffn[fam].compact(ly.idx[2], defer=True)
-                if self.train:
+                if self.train and not self.permanent:
                     back += ly.attn[fam].write_back_items() + ly.ffn[fam].write_back_items()
         tr = [it for ly in self.layers for it in ly.attn["w"].transpose_items() + ly.ffn["w"].transpose_items()]
         self._sel = (B.SelectItem * len(sel))(*sel)
@@ -184,6 +192,7 @@ class DecoderStack:
         arrays (not before the first estimate), score the full-size weights (one call for all pairs of all layers),
         select (one call), gather every family (one call), refresh the transposed copies and the rotary tables."""
         ctx = self.ctx
+        assert not (self.permanent and self.compacted), "a stack that removes for good estimates again through shrink()"
         if getattr(self, "_gather", None) is None:
             self._descriptors()
         if self.compacted and self._back is not None:
@@ -192,11 +201,45 @@ class DecoderStack:
         ctx.ecospa_select_topk_batch(self._sel)
         ctx.ecospa_compact_batch(self._gather)
         self._refresh_transposed()
-        if self.cfg["rope"] and self.compacted:      # kept rotary blocks changed: new frequencies (the first tables come with alloc)
+        if self.cfg["rope"]:      # kept rotary blocks changed: new frequencies (the first tables come with alloc)
             for ly in self.layers:
                 a = ly.attn["w"]
-                a._rope_table(a._L, out=(a.cos, a.sin))
+                if getattr(a, "cos", None) is not None:
+                    a._rope_table(a._L, out=(a.cos, a.sin))
         self.compacted = True
+
+    def _rebase(self):
+        """The compact tensors of every family become the blocks' own; the arrays they were gathered from are released."""
+        for ly in self.layers:
+            for fam in ly.attn:
+                ly.attn[fam].rebase()
+                ly.ffn[fam].rebase()
+            ly.full = None
+
+    def shrink(self, keep):
+        """Alg. 1's step for a stack that removes for good: score the compact master weights of every pair, keep
+        floor(n * num / den) units of the ORIGINAL n of every pair (no more than are left), gather every family from its
+        compact layout into a smaller one (one call each for scores, selection, gathers, transposed copies), rebuild the
+        activations, descriptors and optimizer lists for the new widths, and release the larger buffers."""
+        assert self.permanent and self.compacted
+        num, den = keep
+        unit = 2 if self.cfg["rope"] else 1
+        k_new = ((self.d_h // unit) * num // den, self.d_h * num // den, self.d_ff * num // den)
+        assert all(0 < a <= b for a, b in zip(k_new, self.k)), "the kept counts only fall"
+        self.k = k_new
+        sf = "mst" if self.train else "w"
+        for ly in self.layers:
+            ly.idx = [torch.empty((self.h_kv, k_new[0]), dtype=torch.int32, device="cuda"),
+                      torch.empty((self.h_kv, k_new[1]), dtype=torch.int32, device="cuda"),
+                      torch.empty((1, k_new[2]), dtype=torch.int32, device="cuda")]
+        self.pairs = [p for ly in self.layers for p in ly.attn[sf].pairs() + [ly.ffn[sf].pair()]]
+        self.pair_arr = (B.Pair * len(self.pairs))(*self.pairs)
+        self.compacted = False              # prune() below is a first gather from the blocks' own (compact) tensors
+        self._gather = None
+        self.prune()
+        self._rebase()
+        if self.train:
+            self._build_optimizer()
 
     def _refresh_transposed(self):
         if self._tr is not None:
