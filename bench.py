@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the MFMA contraction kernels, averaged over the contraction launches of one sparse
 # step of the headline workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/):
 # (sha256 prefix of csrc/gemm*, bytes).  Reported only while the kernel sources still have that hash; otherwise null.
-GEMM_TRAFFIC = ("08d5b540d783c615", 139.0e6)
+GEMM_TRAFFIC = ("dd9340b531ff765c", 139.1e6)
 HEADLINE = "c3_llama1b_layer"
 SECOND = "c2_gpt2m_layer"
 
@@ -63,7 +63,7 @@ class Layer:
     def __init__(self, ctx, cfg, seed, keep_num, keep_den):
         import torch
         from paper_2511_11641_amd import binding as B, synth
-        from paper_2511_11641_amd.layer import AttnBlock, FfnBlock, rows_aligned
+        from paper_2511_11641_amd.layer import AttnBlock, FfnBlock
         self.torch, self.B_ = torch, B
         self.ctx, self.cfg = ctx, cfg
         Bsz, L, d, h, dh, dff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
@@ -75,7 +75,10 @@ class Layer:
         up = lambda arr: None if arr is None else torch.from_numpy(arr).to(tdt).cuda()
         g = {k: up(v) for k, v in a.items()}
         gf = {k: up(v) for k, v in f.items() if k not in ("x", "dy")}
-        gf["w2"] = rows_aligned(gf["w2"])        # rows of W_out on 16-byte boundaries (d_ff = 5461 is odd)
+        # W_o and W_out stored with their units as rows ([h d_h, d], [d_ff, d]: the orientation of B in App. A.1), so that
+        # steps 1-3 read and gather rows only; the [d, kp] matrices of the forward pass come out of a transposing copy
+        g["wo"] = g["wo"].t().contiguous()
+        gf["w2"] = gf["w2"].t().contiguous()
         self.x, self.dy = g["x"], g["dy"]
         act = B.ACT_SWIGLU if cfg["gated"] else B.ACT_GELU_ERF
         hkv = cfg.get("h_kv", h)          # grouped-query attention (Eq. 5): the first h_kv heads of W_k, W_v serve as the shared ones
@@ -84,8 +87,8 @@ class Layer:
                 if g.get(nm) is not None:
                     g[nm] = g[nm][:hkv * dh].contiguous()
         self.attn = AttnBlock(ctx, g["wq"], g["wk"], g["wv"], g["wo"], g.get("bq"), g.get("bk"), g.get("bv"),
-                              g.get("bo"), h, dh, rope=cfg["rope"], causal=True, transposed=True, h_kv=hkv)
-        self.ffn = FfnBlock(ctx, gf["w1"], gf.get("b1"), gf["w2"], gf.get("b2"), act, gf.get("w1b"), transposed=True)
+                              g.get("bo"), h, dh, rope=cfg["rope"], causal=True, transposed=True, h_kv=hkv, wo_rows=True)
+        self.ffn = FfnBlock(ctx, gf["w1"], gf.get("b1"), gf["w2"], gf.get("b2"), act, gf.get("w1b"), transposed=True, w2_rows=True)
         unit = 2 if cfg["rope"] else 1
         self.k_qk_units = (dh // unit) * keep_num // keep_den
         self.k_vo = dh * keep_num // keep_den
@@ -115,12 +118,13 @@ class Layer:
         if self._map is None:
             items = self.attn.compact(self.idx[0], self.idx[1], defer=True) + self.ffn.compact(self.idx[2], defer=True)
             self._map = (self.B_.MapItem * len(items))(*items)
-            tr = self.attn.transpose_items() + self.ffn.transpose_items()
+            tr = self.attn.post_gather_items() + self.ffn.post_gather_items()
             self._tr = (self.B_.TransposeItem * len(tr))(*tr) if tr else None
         elif self.attn.rope:    # the kept rotary blocks may have changed: their cos/sin tables again
             self.attn._rope_table(self.attn._L, out=(self.attn.cos, self.attn.sin))
         self.ctx.ecospa_compact_batch(self._map)
-        # transposed copies of the compact weights for the input-gradient contractions (one launch)
+        # transposed copies (one launch): of the gathered rows of W_o / W_out for the forward pass, of the other
+        # compact matrices for the input-gradient contractions
         if self._tr is not None:
             self.ctx.ecospa_transpose_batch(self._tr)
 
@@ -169,10 +173,12 @@ def timed_gpu(torch, fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
-def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps):
+def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps, rows=True, extras=True):
     """Steps 1-3 on a stack of n_layers layers of the same shape (the re-scoring pass of a whole model):
     one batched score call, one select call, one compaction call; descriptors are built once, so
-    the device-side times are not hidden behind the host."""
+    the device-side times are not hidden behind the host.  rows: W_o and W_out are stored with their units as rows
+    (every gather a row gather; the [d, kp] forms come from the transposing copies timed as `transposes`);
+    otherwise in the Linear layout [out, in] (their kept units are gathered by column)."""
     import ctypes as C
     import torch
     from paper_2511_11641_amd import binding as B
@@ -181,9 +187,9 @@ def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps):
     g = lambda *s: (torch.randn(*s, device="cuda") * 0.02).to(torch.bfloat16)
     layers = []
     for _ in range(n_layers):
-        a = AttnBlock(ctx, g(h * dh, d), g(h * dh, d), g(h * dh, d), g(d, h * dh), g(h * dh), g(h * dh), g(h * dh), g(d),
-                      h, dh, rope=False)
-        f = FfnBlock(ctx, g(dff, d), g(dff), g(d, dff), g(d), B.ACT_GELU_ERF)
+        a = AttnBlock(ctx, g(h * dh, d), g(h * dh, d), g(h * dh, d), g(h * dh, d) if rows else g(d, h * dh), g(h * dh), g(h * dh),
+                      g(h * dh), g(d), h, dh, rope=False, transposed=True, wo_rows=rows)
+        f = FfnBlock(ctx, g(dff, d), g(dff), g(dff, d) if rows else g(d, dff), g(d), B.ACT_GELU_ERF, transposed=True, w2_rows=rows)
         layers.append((a, f))
     pairs = [p for a, f in layers for p in a.pairs() + [f.pair()]]
     pair_arr = (B.Pair * len(pairs))(*pairs)
@@ -197,9 +203,26 @@ def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps):
     for li, (a, f) in enumerate(layers):
         items += a.compact(idx[3 * li], idx[3 * li + 1], defer=True) + f.compact(idx[3 * li + 2], defer=True)
     item_arr = (B.MapItem * len(items))(*items)
+    tr = [t for a, f in layers for t in a.post_gather_items() + f.post_gather_items()]
+    tr_arr = (B.TransposeItem * len(tr))(*tr)
     t_score = timed_gpu(torch, lambda: ctx.ecospa_coupled_score(pair_arr, out=scores), steps, 3)
     t_select = timed_gpu(torch, lambda: ctx.ecospa_select_topk_batch(sel_arr), steps, 3)
     t_compact = timed_gpu(torch, lambda: ctx.ecospa_compact_batch(item_arr), steps, 3)
+    t_tr = timed_gpu(torch, lambda: ctx.ecospa_transpose_batch(tr_arr), steps, 3)
+    w_bytes = n_layers * 2 * (4 * d * d + 2 * d * dff)
+    keep = keep_num / keep_den
+    cols = 0 if rows else n_layers * 2 * (d * d + d * dff)  # the members gathered by column: W_o, W_2
+    traffic = 2 * keep * (w_bytes - cols) + (1 + keep) * cols
+    head = {"layers": n_layers, "weights_MB": w_bytes / 1e6, "second_members": "units as rows" if rows else "Linear layout [out, in]",
+            "score": {"us": t_score * 1e3, "gbs": w_bytes / t_score / 1e6, "frac_of_hbm_peak": w_bytes / t_score / 1e6 / HBM_PEAK_GBS},
+            "select": {"us": t_select * 1e3},
+            "compact": {"us": t_compact * 1e3, "kept_gbs": 2 * keep * w_bytes / t_compact / 1e6,
+                        "traffic_gbs": traffic / t_compact / 1e6,
+                        "frac_of_hbm_peak": traffic / t_compact / 1e6 / HBM_PEAK_GBS,
+                        "note": "kept bytes read + written; traffic adds the whole 128-byte lines a column gather has to fetch (none with units as rows)"},
+            "transposes": {"us": t_tr * 1e3, "note": "the transposing copies a training block keeps beside its compact matrices (4 per layer), either layout"}}
+    if not extras:
+        return head
     # the two other pieces of Alg. 1: pair-level importance (Eq. 8; the weights stand in for gradient
     # tensors of the same shapes) and the cumulative-threshold rule on the FFN scores
     fisher = ctx.ecospa_pair_fisher(pair_arr, 8192.0)
@@ -219,17 +242,7 @@ def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps):
     opt_arr = (B.AdamwItem * len(opt_items))(*opt_items)
     t_adamw = timed_gpu(torch, lambda: ctx.ecospa_adamw(opt_arr, 10, 1e-3), steps, 3)
     adamw_bytes = n_par * (2 + 3 * 4 + 3 * 4 + 2)
-    w_bytes = n_layers * 2 * (4 * d * d + 2 * d * dff)
-    keep = keep_num / keep_den
-    cols = n_layers * 2 * (d * d + d * dff)                 # the members gathered by column: W_o, W_2
-    traffic = 2 * keep * (w_bytes - cols) + (1 + keep) * cols
-    return {"layers": n_layers, "weights_MB": w_bytes / 1e6,
-            "score": {"us": t_score * 1e3, "gbs": w_bytes / t_score / 1e6, "frac_of_hbm_peak": w_bytes / t_score / 1e6 / HBM_PEAK_GBS},
-            "select": {"us": t_select * 1e3},
-            "compact": {"us": t_compact * 1e3, "kept_gbs": 2 * keep * w_bytes / t_compact / 1e6,
-                        "traffic_gbs": traffic / t_compact / 1e6,
-                        "frac_of_hbm_peak": traffic / t_compact / 1e6 / HBM_PEAK_GBS,
-                        "note": "kept bytes read + written; traffic adds the whole 128-byte lines a column gather has to fetch"},
+    return {**head,
             "pair_fisher": {"us": t_fisher * 1e3, "gbs": w_bytes / t_fisher / 1e6,
                             "frac_of_hbm_peak": w_bytes / t_fisher / 1e6 / HBM_PEAK_GBS},
             "select_theta": {"us": t_theta * 1e3, "rows": n_layers, "units": dff, "theta": 0.9},
@@ -643,7 +656,9 @@ def main():
         del ref, out_ref
 
     if args.prune_only:
-        print(json.dumps({"prune_24_layers": prune_stack(ctx, c2, 24, 1, 2, 20)}))
+        out = prune_stack(ctx, c2, 24, 1, 2, 20)
+        out["linear_layout"] = prune_stack(ctx, c2, 24, 1, 2, 20, rows=False, extras=False)
+        print(json.dumps({"prune_24_layers": out}))
         return
 
     if args.stack_step_only:
@@ -668,6 +683,7 @@ def main():
 
     # the HBM-bound steps on a whole model's weights (24 layers, 604 MB), beside what plain kernels reach on the same bytes
     prune = prune_stack(ctx, c2, 24, 1, 2, 20)
+    prune["linear_layout"] = prune_stack(ctx, c2, 24, 1, 2, 20, rows=False, extras=False)   # W_o, W_out as [out, in]: column gathers
     ceil = hbm_ceilings(ctx, prune["weights_MB"] * 1e6)
     hbm = {"peak_gbs": HBM_PEAK_GBS, "workload": "steps 1-3 over 24 GPT-2-Medium-shaped layers, one call each",
            "weights_MB": prune["weights_MB"], "read_ceiling_gbs": ceil["read_gbs"],

@@ -104,6 +104,10 @@ typedef struct {
   const void* w2;      /* QK: W_k [groups*rep2*n, d2]; VO/FFN*: W_o | W_out | W_down [d2, groups*rep2*n] */
   long long ld1, ld1b, ld2;
   int rep1, rep2;      /* heads of member 1 / member 2 per group (Eq. 5); 0 or 1: one each   */
+  int w2_rows;         /* VO/FFN*: nonzero = the second member is stored with its units as rows,
+                          [groups*rep2*n, d2] with ld2 >= d2 - b_j is row j, the orientation of B in
+                          App. A.1 (and how GPT-2 checkpoints keep W_out) - so both members are read
+                          along rows and the kept units are gathered as rows (axis 0)          */
 } ecospa_pair;
 
 /* Workspace bytes ecospa_coupled_score needs for this batch (host-only query; 0 on bad input). */

@@ -44,7 +44,8 @@ class EcospaError(RuntimeError):
 class Pair(C.Structure):
     _fields_ = [("kind", C.c_int), ("dtype", C.c_int), ("groups", C.c_int), ("n", C.c_int), ("unit", C.c_int),
                 ("d1", C.c_int), ("d2", C.c_int), ("w1", C.c_void_p), ("w1b", C.c_void_p), ("w2", C.c_void_p),
-                ("ld1", C.c_longlong), ("ld1b", C.c_longlong), ("ld2", C.c_longlong), ("rep1", C.c_int), ("rep2", C.c_int)]
+                ("ld1", C.c_longlong), ("ld1b", C.c_longlong), ("ld2", C.c_longlong), ("rep1", C.c_int), ("rep2", C.c_int),
+                ("w2_rows", C.c_int)]
 
 
 class BlockDesc(C.Structure):
@@ -297,12 +298,13 @@ class Context:
     # ---- step 1 ------------------------------------------------------------------------------
     @staticmethod
     def make_pair(kind: int, w1: torch.Tensor, w2: torch.Tensor, groups: int, n: int, unit: int = 1,
-                  w1b: Optional[torch.Tensor] = None, rep1: int = 1, rep2: int = 1) -> Pair:
-        """rep1 / rep2: heads of the first / second member that share one group's inner dimensions (Eq. 5)."""
+                  w1b: Optional[torch.Tensor] = None, rep1: int = 1, rep2: int = 1, w2_rows: bool = False) -> Pair:
+        """rep1 / rep2: heads of the first / second member that share one group's inner dimensions (Eq. 5).
+        w2_rows: the second member of a VO / FFN pair is stored with its units as rows ([units, d])."""
         d1 = w1.shape[1]
-        d2 = w2.shape[1] if kind == PAIR_QK else w2.shape[0]
+        d2 = w2.shape[1] if (kind == PAIR_QK or w2_rows) else w2.shape[0]
         return Pair(kind, dtype_code(w1.dtype), groups, n, unit, d1, d2, _ptr(w1), _ptr(w1b), _ptr(w2),
-                    w1.stride(0), 0 if w1b is None else w1b.stride(0), w2.stride(0), rep1, rep2)
+                    w1.stride(0), 0 if w1b is None else w1b.stride(0), w2.stride(0), rep1, rep2, int(w2_rows))
 
     def ecospa_coupled_score(self, pairs: Sequence[Pair], out: Optional[Sequence[torch.Tensor]] = None) -> list[torch.Tensor]:
         """Scores of a batch of pairs, one float32 tensor [groups, n/unit] per pair (written into `out` if given)."""

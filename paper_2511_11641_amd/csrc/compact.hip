@@ -7,7 +7,8 @@
 //   gather : s = g*kp*unit + i*unit + u  ->  g*n + idx[g,i]*unit + u   (i < k), else -1 (padding)
 //   scatter: s = g*n + q*unit + u        ->  g*kp*unit + i*unit + u    where idx[g,i] == q (binary
 //            search in the ascending index list), else -1 (pruned)
-// Rows (axis 0) are copied four at a time by a wavefront with 16-byte accesses; for columns (axis 1)
+// Rows (axis 0) are copied two at a time by a wavefront with 16-byte accesses (four loads in flight per lane; more rows
+// per wavefront - fewer, longer-lived workgroups - measured slower, one row too); for columns (axis 1)
 // each thread owns a fixed set of destination columns, resolves their sources once and then
 // walks down the rows, so that the stores are full 16-byte coalesced writes.  A batch of copies
 // (all matrices, biases and tables of a layer) runs as ONE launch: launches of this size are
@@ -78,7 +79,7 @@ struct MapBatch {
 static_assert(sizeof(MapBatch) <= 16384, "kernel arguments of one launch");
 
 // ---- axis 0: a wavefront copies MAP_ROW_PER_WAVE destination rows at a time, the loads of all of them in flight
-#define MAP_ROW_PER_WAVE 4
+#define MAP_ROW_PER_WAVE 2
 #define MAP_ROWS_PER_BLOCK (4 * MAP_ROW_PER_WAVE)
 template <typename E>
 __device__ __forceinline__ void map_rows_block(const MapItemDev& t, int blk) {

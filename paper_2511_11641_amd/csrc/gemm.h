@@ -12,7 +12,7 @@ enum {
   EPI_STORE = 0,     // c[m,n] = acc (+ bias[n])
   EPI_BIAS_ACT = 1,  // h = acc + bias[n]; c[m,n] = h; c2[m,n] = gelu(h)
   EPI_DACT = 2,      // c[m,n] = acc * gelu'(h[m,n])
-  EPI_DSWIGLU = 3,   // g = h[m,n], u = h[m,n+kp]; c[m,n] = acc*u*dsilu(g); c[m,n+kp] = acc*silu(g)
+  EPI_DSWIGLU = 3,   // unit n: g = h[m,2n], u = h[m,2n+1] (interleaved pairs); c[m,2n] = acc*u*dsilu(g); c[m,2n+1] = acc*silu(g)
   EPI_ACT = 4,       // c[m,n] = gelu(acc + bias[n]): forward only, the activation's input is not kept
   EPI_ROPE = 5,      // c[m,n] = acc + bias[n], with the adjacent column pairs (2i, 2i+1) of the first rope_cols columns
                      // turned by the angle of (row m % rope_L, pair) - the rotary form of the Q and K projections (bf16)

@@ -342,6 +342,9 @@ __global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_kernel(const S
 static inline int pair_rep1(const ecospa_pair& q) { return q.rep1 > 0 ? q.rep1 : 1; }
 static inline int pair_rep2(const ecospa_pair& q) { return q.rep2 > 0 ? q.rep2 : 1; }
 
+// the second member's units are rows (W_k always; W_o / W_out / W_down when the caller stores them that way)
+static inline bool pair_w2_rows(const ecospa_pair& q) { return q.kind == ECOSPA_PAIR_QK || q.w2_rows != 0; }
+
 static int validate_pair(const ecospa_pair& q) {
   if (q.kind < ECOSPA_PAIR_QK || q.kind > ECOSPA_PAIR_FFN_GATED || !dtype_ok(q.dtype)) return ECOSPA_ERR_DTYPE;
   if (!q.w1 || !q.w2 || (q.kind == ECOSPA_PAIR_FFN_GATED && !q.w1b)) return ECOSPA_ERR_NULL;
@@ -353,7 +356,7 @@ static int validate_pair(const ecospa_pair& q) {
   if (rows1 > (1ll << 30) || rows2 > (1ll << 30)) return ECOSPA_ERR_SHAPE;
   if (q.ld1 < q.d1) return ECOSPA_ERR_SHAPE;
   if (q.kind == ECOSPA_PAIR_FFN_GATED && q.ld1b < q.d1) return ECOSPA_ERR_SHAPE;
-  if (q.kind == ECOSPA_PAIR_QK ? q.ld2 < q.d2 : q.ld2 < rows2) return ECOSPA_ERR_SHAPE;
+  if (pair_w2_rows(q) ? q.ld2 < q.d2 : q.ld2 < rows2) return ECOSPA_ERR_SHAPE;
   return ECOSPA_OK;
 }
 
@@ -372,7 +375,7 @@ static ColShape col_shape(const ecospa_pair& q) {
 
 static size_t pair_ws_bytes(const ecospa_pair& q) {
   const size_t rows1 = static_cast<size_t>(q.groups) * pair_rep1(q) * q.n, rows2 = static_cast<size_t>(q.groups) * pair_rep2(q) * q.n;
-  const size_t parts = q.kind == ECOSPA_PAIR_QK ? 1 : col_shape(q).parts;
+  const size_t parts = pair_w2_rows(q) ? 1 : col_shape(q).parts;
   return align_up(rows1 * 4, 256) + align_up(parts * rows2 * 4, 256);   // a_sq, b_sq (partial sums)
 }
 
@@ -427,7 +430,7 @@ static int score_run(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, flo
       blk += row_blocks;
       p.blk_row2 = blk;
       p.col_lanes = 8; p.col_strips = 1; p.col_parts = 1;
-      if (q.kind == ECOSPA_PAIR_QK) {
+      if (pair_w2_rows(q)) {
         p.b_sq = static_cast<float*>(ws.take(static_cast<size_t>(p.rows2) * 4));
         blk += (p.rows2 + SCORE_ROWS_PER_BLOCK - 1) / SCORE_ROWS_PER_BLOCK;
         p.blk_col = blk;

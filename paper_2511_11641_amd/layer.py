@@ -27,8 +27,11 @@ class FfnBlock:
     """Compacted FFN pair (W_in / W_out, or W_gate (.) W_up / W_down)."""
 
     def __init__(self, ctx: B.Context, w1, b1, w2, b2, act: int, w1b=None, transposed: bool = False,
-                 bias_grads: Optional[bool] = None):
-        """transposed: keep transposed copies of the compact matrices for the backward pass (refreshed by
+                 bias_grads: Optional[bool] = None, w2_rows: bool = False):
+        """w2_rows: the second matrix is stored with its units as rows, [n, d] (the orientation of B in App. A.1; how
+        GPT-2 checkpoints keep W_out): it is then scored along rows and its kept units are gathered as rows into the
+        transposed compact copy, from which the [d, kp] matrix of the forward pass is written by a transposing copy -
+        no column gather anywhere.  transposed: keep transposed copies of the compact matrices for the backward pass (refreshed by
         :meth:`compact`; after a parameter update call :meth:`refresh_transposed`).  bias_grads: ask the backward pass
         for the bias gradients (default: for the biases the block has; True: all of them - they are column sums of the
         upstream gradients and exist with or without a bias)."""
@@ -36,6 +39,7 @@ class FfnBlock:
         self.bias_grads = bias_grads
         self.transposed = transposed
         self.w1, self.b1, self.w2, self.b2, self.w1b = w1, b1, w2, b2, w1b
+        self.w2_rows = w2_rows
         self.n, self.d = w1.shape
         self.gated = act == B.ACT_SWIGLU
         self.idx = None
@@ -43,7 +47,7 @@ class FfnBlock:
 
     def pair(self) -> B.Pair:
         kind = B.PAIR_FFN_GATED if self.gated else B.PAIR_FFN
-        return B.Context.make_pair(kind, self.w1, self.w2, 1, self.n, 1, self.w1b)
+        return B.Context.make_pair(kind, self.w1, self.w2, 1, self.n, 1, self.w1b, w2_rows=self.w2_rows)
 
     def score(self) -> torch.Tensor:
         return self.ctx.ecospa_coupled_score([self.pair()])[0]
@@ -74,6 +78,7 @@ class FfnBlock:
             self.w2_c = torch.empty((self.d, kp), dtype=dt, device=dev)
             if self.transposed:
                 self.w1_t = torch.empty((self.d, nh), dtype=dt, device=dev)
+            if self.transposed or self.w2_rows:
                 self.w2_t = torch.empty((kp, self.d), dtype=dt, device=dev)
             if getattr(self, "_alloc_shape", None) is not None:     # descriptors, saved activations, gradients follow the new width
                 self.alloc(*self._alloc_shape)
@@ -81,8 +86,22 @@ class FfnBlock:
         if defer:
             return items
         c.ecospa_compact_batch(items)
-        self.refresh_transposed()
+        post = self.post_gather_items()
+        if post:
+            c.ecospa_transpose_batch(post)
         return self
+
+    def post_gather_items(self):
+        """Transposing copies that complete a gather: the transposed copies for the backward pass, and - with the
+        second matrix stored units-as-rows - its [d, kp] form for the forward pass out of the gathered rows."""
+        items = []
+        if self.transposed:
+            items.append(B.Context.transpose_item(self.w1_c, self.w1_t))
+        if self.w2_rows:
+            items.append(B.Context.transpose_item(self.w2_t, self.w2_c))
+        elif self.transposed:
+            items.append(B.Context.transpose_item(self.w2_c, self.w2_t))
+        return items
 
     def rebase(self):
         """Alg. 1's removal for good: the compact tensors become the block's own and what they were gathered from is
@@ -94,7 +113,7 @@ class FfnBlock:
         self.w1b = self.up_rows(self.w1_c) if self.gated else None
         if self.b1 is not None:
             self.b1 = self.b1_c.view(kp, 2)[:, 0] if self.gated else self.b1_c
-        self.w2 = self.w2_c
+        self.w2 = self.w2_t if self.w2_rows else self.w2_c
         self.n = kp
         self.rebased = True
         return self
@@ -119,16 +138,18 @@ class FfnBlock:
                 members.append((self.b1.view(-1, 1), self.b1_c.view(kp, 2)[:, :1], 0))
             else:
                 members.append((self.b1, self.b1_c, 1))
-        members.append((self.w2, self.w2_c, 1))
+        members.append((self.w2, self.w2_t, 0) if self.w2_rows else (self.w2, self.w2_c, 1))
         return [B.Context.map_item(c if scatter else f, f if scatter else c, self.idx, axis, 1, self.n, 1, kp,
                                    scatter=scatter, k_group=self.k_group) for f, c, axis in members]
 
     def write_back_items(self):
         """Scatters of the compact tensors into the full-size ones that leave the pruned rows/columns as they are."""
         assert not self.rebased, "no full-size tensors to write back to"
+        assert not self.w2_rows or self.transposed, "rows of the second matrix come from its transposed copy: keep it fresh (transposed=True)"
         return self._map_items(2)
 
     def transpose_items(self):
+        """Transposed copies out of the compact matrices (after a parameter update)."""
         if not self.transposed:
             return []
         return [B.Context.transpose_item(self.w1_c, self.w1_t), B.Context.transpose_item(self.w2_c, self.w2_t)]
@@ -188,8 +209,9 @@ class AttnBlock:
 
     def __init__(self, ctx: B.Context, wq, wk, wv, wo, bq, bk, bv, bo, h: int, d_h: int, *, rope: bool,
                  causal: bool = True, rope_base: float = 10000.0, h_kv: Optional[int] = None, transposed: bool = False,
-                 bias_grads: Optional[bool] = None):
-        """bias_grads: ask the backward pass for the bias gradients (default: for the biases the block has)."""
+                 bias_grads: Optional[bool] = None, wo_rows: bool = False):
+        """bias_grads: ask the backward pass for the bias gradients (default: for the biases the block has).
+        wo_rows: W_o is stored with its units as rows, [h * d_h, d] (see FfnBlock's w2_rows)."""
         self.ctx, self.h, self.d_h, self.rope, self.causal, self.rope_base = ctx, h, d_h, rope, causal, rope_base
         self.bias_grads = bias_grads
         self.transposed = transposed      # transposed copies of the compact matrices for the backward pass
@@ -197,6 +219,7 @@ class AttnBlock:
         assert h % self.h_kv == 0
         self.qpk = h // self.h_kv
         self.wq, self.wk, self.wv, self.wo = wq, wk, wv, wo
+        self.wo_rows = wo_rows
         self.bq, self.bk, self.bv, self.bo = bq, bk, bv, bo
         self.d = wq.shape[1]
         self.unit = 2 if rope else 1
@@ -207,7 +230,7 @@ class AttnBlock:
     def pairs(self):
         mk = B.Context.make_pair
         return [mk(B.PAIR_QK, self.wq, self.wk, self.h_kv, self.n_qk, self.unit, rep1=self.qpk),
-                mk(B.PAIR_VO, self.wv, self.wo, self.h_kv, self.n_vo, 1, rep2=self.qpk)]
+                mk(B.PAIR_VO, self.wv, self.wo, self.h_kv, self.n_vo, 1, rep2=self.qpk, w2_rows=self.wo_rows)]
 
     def track_rotary_blocks(self):
         """Before the first :meth:`compact` of a block that will be rebased: keep, beside the index lists, the original
@@ -253,11 +276,14 @@ class AttnBlock:
             self.wo_c = torch.empty((self.d, no), dtype=dt, device=dev)
             if self.transposed:
                 self.wqkv_t = torch.empty((self.d, nq + nk + nv), dtype=dt, device=dev)
+            if self.transposed or self.wo_rows:
                 self.wo_t = torch.empty((no, self.d), dtype=dt, device=dev)
         items = self._map_items(0)
         if not defer:
             c.ecospa_compact_batch(items)
-            self.refresh_transposed()
+            post = self.post_gather_items()
+            if post:
+                c.ecospa_transpose_batch(post)
         if getattr(self, "_alloc_shape", None) is not None:
             if resized:       # descriptors, saved activations, gradients and the rotary tables follow the new widths
                 self.alloc(*self._alloc_shape)
@@ -283,7 +309,7 @@ class AttnBlock:
         if self.bq is not None:
             items += [mq(self.bq, self.bqkv_c[:nq], 1, h), mq(self.bk, self.bqkv_c[nq:nq + nk], 1, hk),
                       mv(self.bv, self.bqkv_c[nq + nk:], 1, hk)]
-        items.append(mv(self.wo, self.wo_c, 1, h))
+        items.append(mv(self.wo, self.wo_t, 0, h) if self.wo_rows else mv(self.wo, self.wo_c, 1, h))
         if self.orig_qk is not None and not scatter:      # the int32 table moves as 4-byte words
             items.append(B.Context.map_item(self.orig_qk.view(torch.float32).view(-1), self.rope_idx.view(torch.float32).view(-1),
                                             self.idx_qk, 1, hk, self.orig_qk.shape[1], 1, self.k_qk_units))
@@ -292,7 +318,19 @@ class AttnBlock:
     def write_back_items(self):
         """Scatters of the compact tensors into the full-size ones that leave the pruned rows/columns as they are."""
         assert not self.rebased, "no full-size tensors to write back to"
+        assert not self.wo_rows or self.transposed, "rows of W_o come from its transposed copy: keep it fresh (transposed=True)"
         return self._map_items(2)
+
+    def post_gather_items(self):
+        """Transposing copies that complete a gather (see FfnBlock.post_gather_items)."""
+        items = []
+        if self.transposed:
+            items.append(B.Context.transpose_item(self.wqkv_c, self.wqkv_t))
+        if self.wo_rows:
+            items.append(B.Context.transpose_item(self.wo_t, self.wo_c))
+        elif self.transposed:
+            items.append(B.Context.transpose_item(self.wo_c, self.wo_t))
+        return items
 
     def rebase(self):
         """Alg. 1's removal for good: the compact tensors become the block's own and what they were gathered from is
@@ -303,7 +341,8 @@ class AttnBlock:
         assert self.k_qk_group is None and self.k_vo_group is None, "fixed kept counts only"
         assert not self.rope or self.orig_qk is not None, "track_rotary_blocks() before the first compaction"
         nq, nk = self.nq, self.nk
-        self.wq, self.wk, self.wv, self.wo = self.wqkv_c[:nq], self.wqkv_c[nq:nq + nk], self.wqkv_c[nq + nk:], self.wo_c
+        self.wq, self.wk, self.wv = self.wqkv_c[:nq], self.wqkv_c[nq:nq + nk], self.wqkv_c[nq + nk:]
+        self.wo = self.wo_t if self.wo_rows else self.wo_c
         if self.bq is not None:
             self.bq, self.bk, self.bv = self.bqkv_c[:nq], self.bqkv_c[nq:nq + nk], self.bqkv_c[nq + nk:]
         self.n_qk, self.n_vo = self.kp_qk, self.kp_vo

@@ -109,6 +109,13 @@ def test_score_validation(lib, ctx):
     bad = B.Pair(B.PAIR_FFN, B.F32, 1, 8, 1, 4, 4, 256, None, 512, 4, 0, 7)
     assert lib.ecospa_coupled_score(ctx, (B.Pair * 1)(bad), 1, out) == B.ERR_SHAPE  # ld2 < groups*n
     assert lib.ecospa_score_workspace_bytes((B.Pair * 1)(bad), 1) == 0
+    # second member stored with its units as rows: ld2 counts against d2 = 4, not against the 8 units
+    rows = B.Pair(B.PAIR_FFN, B.F32, 1, 8, 1, 4, 4, 256, None, 512, 4, 0, 4, 0, 0, 1)
+    assert lib.ecospa_coupled_score(ctx, (B.Pair * 1)(rows), 1, out) == B.ERR_WORKSPACE
+    bad = B.Pair(B.PAIR_FFN, B.F32, 1, 8, 1, 4, 4, 256, None, 512, 4, 0, 3, 0, 0, 1)
+    assert lib.ecospa_coupled_score(ctx, (B.Pair * 1)(bad), 1, out) == B.ERR_SHAPE
+    # ... and needs no partial sums per row range: a smaller workspace than the column form
+    assert lib.ecospa_score_workspace_bytes((B.Pair * 1)(rows), 1) <= lib.ecospa_score_workspace_bytes(arr, 1)
 
 
 def test_block_validation(lib, ctx):
