@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the MFMA contraction kernels, averaged over the contraction launches of one sparse
 # step of the headline workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/):
 # (sha256 prefix of csrc/gemm*, bytes).  Reported only while the kernel sources still have that hash; otherwise null.
-GEMM_TRAFFIC = ("dd9340b531ff765c", 139.1e6)
+GEMM_TRAFFIC = ("4cc5e299fbc0ab02", 139.1e6)
 HEADLINE = "c3_llama1b_layer"
 SECOND = "c2_gpt2m_layer"
 
@@ -706,6 +706,7 @@ def main():
         "config": {"workload": name, "layer": "LLaMA-1B shaped: d=2048, 32 heads x 64, SwiGLU d_ff=5461, RoPE, causal, no biases",
                    "batch": Bsz, "seq_len": L, "keep": "1/2 per coupled pair (16 of 32 rotary blocks, k_vo=32, k_ff=2730)",
                    "step": "score+select+compact+attn/ffn fwd+bwd",
+                   "storage": "W_q, W_k, W_v, W_gate, W_up as [out, in]; W_o and W_down with their units as rows, [units, d]",
                    "second_workload": SECOND + " (same path; its figures are in roofline." + SECOND + " and in also)"},
         "fwd_bwd": main_wl["fwd_bwd"], "dense_fwd_bwd": main_wl["dense_fwd_bwd"],
         "speedup_fwd_bwd_vs_dense": main_wl["speedup_fwd_bwd_vs_dense"],

@@ -23,41 +23,48 @@
 template <int RT, int BK, int NW, bool KSLOW>
 struct TileLoads {
   static constexpr int PER = RT * BK * 2 / 1024 / NW;
-  const bf16_t* src[PER];   // this lane's source of instruction i for the current slab
-  long long step;           // elements to advance per slab
-  __device__ __forceinline__ void init(const bf16_t* base, long long ld, int r0, int R, int k0) {
+  // Addresses are a wavefront-uniform base (the tile's current slab; lives in scalar registers and is advanced by
+  // scalar adds) plus a per-lane byte offset that never changes: no vector instruction is spent on addressing in
+  // the main loop (on this target a vector instruction of a wavefront takes issue time from its own MFMAs).
+  const char* base;
+  unsigned off[PER];        // this lane's byte offset of instruction i inside the slab
+  long long step;           // bytes to advance per slab
+  __device__ __forceinline__ void init(const bf16_t* mat, long long ld, int r0, int R, int k0) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (!KSLOW) {
       constexpr int CPR = BK / 8, RPI = 64 / CPR;
       const int r = lane / CPR, pc = lane % CPR;
+      base = reinterpret_cast<const char*>(mat + static_cast<long long>(r0) * ld + k0);
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
         const int row = (wave * PER + i) * RPI + r;
         const int kc = pc ^ kc_swz<BK>(row);
-        const int gr = min(r0 + row, R - 1);
-        src[i] = base + static_cast<long long>(gr) * ld + k0 + kc * 8;
+        const int gr = min(r0 + row, R - 1) - r0;          // rows past the end repeat the last one
+        off[i] = static_cast<unsigned>((static_cast<long long>(gr) * ld + kc * 8) * 2);
       }
-      step = BK;
+      step = BK * 2;
     } else {
       constexpr int CPR = RT / 8, KPI = 64 / CPR;
       const int kl = lane / CPR, pc = lane % CPR;
+      base = reinterpret_cast<const char*>(mat + static_cast<long long>(k0) * ld + r0);
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
         const int k = (wave * PER + i) * KPI + kl;
         const int c = pc ^ ((k & 3) << 2);
-        const int col = min(r0 + c * 8, R - 8);
-        src[i] = base + static_cast<long long>(k0 + k) * ld + col;
+        const int col = min(r0 + c * 8, R - 8) - r0;
+        off[i] = static_cast<unsigned>((static_cast<long long>(k) * ld + col) * 2);
       }
-      step = static_cast<long long>(BK) * ld;
+      step = static_cast<long long>(BK) * ld * 2;
     }
   }
-  // issue instruction i of the current slab into `tile` (LDS, start of this operand's tile)
-  // `adv` is `step` while a further slab exists and 0 afterwards: the loads of the last slab are then
-  // simply repeated (into ring buffers nobody reads any more), which keeps the main loop branch free.
+  // issue instruction i of the current slab into `tile` (LDS, start of this operand's tile); the last one of a
+  // slab moves the base on.  `adv` is `step` while a further slab exists and 0 afterwards: the loads of the last slab
+  // are then simply repeated (into ring buffers nobody reads any more), which keeps the main loop branch free.
   __device__ __forceinline__ void issue(int i, lds_bf16_t* tile, long long adv) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    __builtin_amdgcn_global_load_lds(src[i], tile + (wave * PER + i) * 512, 16, 0, 0);
-    src[i] += adv;
+    asm volatile("" : "+v"(off[i]));   // keeps the offset a 32-bit register at the load: address = scalar base + lane offset
+    __builtin_amdgcn_global_load_lds(reinterpret_cast<const void*>(base + off[i]), tile + (wave * PER + i) * 512, 16, 0, 0);
+    if (i == PER - 1) base += adv;
   }
 };
 
@@ -146,17 +153,19 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
   constexpr int LSTEPS = NS == 2 ? 1 : KS - 1;         // k steps that issue loads
   constexpr int LPS = (LPW + LSTEPS - 1) / LSTEPS;
   static_assert(FM + FN <= FM * FN, "a fragment slot per MFMA");
-  int buf = 0;   // ring position of slab t
-  for (int t = 0; t < nk; ++t) {
-    const int buf_issue = buf == 0 ? NS - 1 : buf - 1; // (t + NS - 1) % NS
-    const int buf_next = buf + 1 == NS ? 0 : buf + 1;
+  // One slab.  The ring position of slab t is a compile-time constant (the loop below walks NS slabs per round), so
+  // every LDS address is a per-lane base plus an immediate: nothing is added up in vector registers per slab.
+  auto slab = [&](auto buf_, int t) __attribute__((always_inline)) {
+    constexpr int buf = decltype(buf_)::value;          // t % NS
+    constexpr int buf_issue = buf == 0 ? NS - 1 : buf - 1;   // (t + NS - 1) % NS
+    constexpr int buf_next = buf + 1 == NS ? 0 : buf + 1;
     const bool adv = t + NS < nk;                      // the slab after the one issued now exists
     const long long adv_a = adv ? la.step : 0, adv_b = adv ? lb.step : 0;
     // One k step = FM*FN MFMAs in source order; behind MFMA m go fragment m of the next k step (FM
     // A fragments, then FN B fragments) and this step's share of the global->LDS loads, fenced with
     // sched_barrier so that a wavefront that is alone on its SIMD keeps the matrix pipe fed while it
     // issues everything else.
-    auto kstep = [&](auto s_) {
+    auto kstep = [&](auto s_) __attribute__((always_inline)) {
       constexpr int s = decltype(s_)::value;
       constexpr int cur = s & 1, nxt = cur ^ 1;
       constexpr bool last = s + 1 == KS;
@@ -176,7 +185,7 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
       const bf16_t* as_ = lds + (last ? buf_next : buf) * STAGE;
       const bf16_t* bs_ = as_ + BM * BK;
       constexpr int sn = last ? 0 : s + 1;
-      static_for<0, NM>([&](auto m_) {
+      static_for<0, NM>([&](auto m_) __attribute__((always_inline)) {
         constexpr int m = decltype(m_)::value;
         constexpr int i = m / FN, j = m % FN;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
@@ -197,8 +206,13 @@ void gemm_bf16_pipe_kernel(const GemmDesc d, int tiles_n, int k_chunk) {
       kstep(std::integral_constant<int, 3>{});
     }
     static_assert(KS == 2 || KS == 4, "k steps per slab");
-    buf = buf_next;
-  }
+  };
+  int t = 0;
+  for (; t + NS <= nk; t += NS)
+    static_for<0, NS>([&](auto b_) __attribute__((always_inline)) { slab(b_, t + decltype(b_)::value); });
+  static_for<0, NS - 1>([&](auto b_) __attribute__((always_inline)) {      // the last nk % NS slabs (t is a multiple of NS here)
+    if (t + decltype(b_)::value < nk) slab(b_, t + decltype(b_)::value);
+  });
 #undef PIPE_ISSUE
 #undef PIPE_FRAGS
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));

@@ -45,39 +45,46 @@ struct RsOperand {
   static constexpr int STRIDE = NDST * 512;
   static_assert(ROWS == 128 || ROWS == 192 || ROWS == 256, "tile extents that are built");
   static_assert(PER % NDST == 0, "whole periods");
-  const bf16_t* src[PER];
-  long long step;     // elements per slab
+  // Addresses: a wavefront-uniform base (the current slab; scalar registers, advanced by scalar adds) plus a per-lane
+  // byte offset that never changes - a wavefront that is alone on its SIMD pays MFMA time for every vector instruction.
+  const char* base;
+  unsigned off[PER];
+  long long step;     // bytes per slab
   int dst[NDST];
-  __device__ __forceinline__ void init(const bf16_t* base, long long ld, int r0, int R, int k0) {
+  __device__ __forceinline__ void init(const bf16_t* mat, long long ld, int r0, int R, int k0) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if constexpr (!KSLOW) {
       // piece i: tile rows (wave * PER + i) * 8 + lane / 8, 16-byte chunk lane % 8 of the 64-wide slab row
       const int rl = lane >> 3, kc = lane & 7;
+      base = reinterpret_cast<const char*>(mat + static_cast<long long>(r0) * ld + k0);
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
         const int row = (wave * PER + i) * 8 + rl;
-        src[i] = base + static_cast<long long>(min(r0 + row, R - 1)) * ld + k0 + kc * 8;
+        off[i] = static_cast<unsigned>((static_cast<long long>(min(r0 + row, R - 1) - r0) * ld + kc * 8) * 2);
       }
       dst[0] = kc_off<64>(wave * PER * 8 + rl, kc);
       dst[1] = kc_off<64>(wave * PER * 8 + 8 + rl, kc);
-      step = 64;
+      step = 64 * 2;
     } else {
       // piece i: slab row k = p / (ROWS / 8), chunk c = p % (ROWS / 8) of the ROWS-wide row, p its number
       constexpr int CPR = ROWS / 8;
+      base = reinterpret_cast<const char*>(mat + static_cast<long long>(k0) * ld + r0);
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
         const int p = (wave * PER + i) * 64 + lane;
         const int k = p / CPR, c = p - k * CPR;
-        const int col = min(r0 + c * 8, R - 8);
-        src[i] = base + static_cast<long long>(k0 + k) * ld + col;
+        const int col = min(r0 + c * 8, R - 8) - r0;
+        off[i] = static_cast<unsigned>((static_cast<long long>(k) * ld + col) * 2);
         if (i < NDST) dst[i] = ks_off<ROWS>(k, c);
       }
-      step = 64 * ld;
+      step = 64 * ld * 2;
     }
   }
+  // piece i of the current slab; the last piece of a slab moves the base on by `adv` (the step, or 0 past the end)
   __device__ __forceinline__ u32x4 load(int i, long long adv) {
-    const u32x4 v = *reinterpret_cast<const u32x4*>(src[i]);
-    src[i] += adv;
+    asm volatile("" : "+v"(off[i]));   // keeps the offset a 32-bit register at the load: address = scalar base + lane offset
+    const u32x4 v = *reinterpret_cast<const u32x4*>(base + off[i]);
+    if (i == PER - 1) base += adv;
     return v;
   }
   __device__ __forceinline__ void store(bf16_t* tile, int i, const u32x4& v) const {
