@@ -682,8 +682,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ
       for (int s = 0; s < DV / 16; ++s)
         pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat<DV>(dOs(cur), t * 32 + l32, s, hh), vf[s], pacc, 0, 0, 0);
       floatx16 pr;
-      // a query sees this lane's key if key <= q (causal) and both are inside the sequence
-      const int q_min = key_idx >= a.L ? 0x7fffffff : (a.causal ? key_idx : 0);
+      if (need_mask) {        // wave-uniform: only tiles on the diagonal or at the end of the sequence pay for the selects
+        // a query sees this lane's key if key <= q (causal) and both are inside the sequence
+        const int q_min = key_idx >= a.L ? 0x7fffffff : (a.causal ? key_idx : 0);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int q = qb0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
+          sacc[r] = (q < q_min || q >= a.L) ? -INFINITY : sacc[r];
+        }
+      }
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int qrow = t * 32 + g * 8 + hh * 4;
@@ -693,12 +700,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int r = g * 4 + i;
-          float sv = sacc[r];
-          if (need_mask) {      // wave-uniform; selects only
-            const int q = qb0 + qrow + i;
-            sv = (q < q_min || q >= a.L) ? -INFINITY : sv;
-          }
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv, sc, -lsv[i]));
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[r], sc, -lsv[i]));
           pr[r] = p;
           sacc[r] = p * (pacc[r] - dlv[i]);
         }
