@@ -9,200 +9,19 @@
 // Only integer comparisons, integer LDS atomics and integer scans: bit-exact.
 #include "common.h"
 
-#define SELECT_THREADS 1024
-#define SELECT_CACHE 8          // score keys a thread keeps in registers
-#define SELECT_MAX_ITEMS 96    // descriptors travel as kernel arguments
+#include "select_dev.h"
 
-struct SelectItemDev {
-  const float* scores;
-  int* idx;
-  int n, k;
-  int blk_begin;   // first workgroup (= group) of this item
-  int groups;        // groups of this item (n <= 64: SELECT_THREADS / 64 of them share a workgroup)
-  const int* k_dev;  // optional: per-group kept counts in device memory (then k is unused, the rows of idx
-  int ld_idx;        //           are ld_idx apart and the slots behind the kept indices are set to -1)
-  int smallest;      // take the k smallest scores instead (the order of the keys reversed, ties still to the lower index)
-};
-struct SelectBatch {
-  int n_items;
-  int first_blk[SELECT_MAX_ITEMS];   // blk_begin of every item, side by side: the search for a group's item stays in a few cache lines
-  SelectItemDev it[SELECT_MAX_ITEMS];
-};
-
-__device__ __forceinline__ uint32_t score_key(float x) {
-  uint32_t u = __float_as_uint(x);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;   // NaN: lowest
-  if (u == 0x80000000u) u = 0u;                      // -0 -> +0
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// Exclusive prefix sum of `v` over the block's threads in thread order, and the block total.
-__device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int& total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int up = __shfl_up(inc, off, 64);
-    if (lane >= off) inc += up;
-  }
-  __syncthreads();   // protect wave_tot from the previous use
-  if (lane == 63) wave_tot[wave] = inc;
-  __syncthreads();
-  int before = 0, tot = 0;
-#pragma unroll
-  for (int w = 0; w < SELECT_THREADS / 64; ++w) {
-    const int c = wave_tot[w];
-    if (w < wave) before += c;
-    tot += c;
-  }
-  total = tot;
-  return before + inc - v;
-}
-
-#define ITEM_KEY(x) (score_key(x) ^ flip)
 __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const SelectBatch b) {
-  // one histogram per wavefront: normalised scores share their top key bits, so a single histogram
-  // would serialise nearly every atomic of the first pass on a few counters
-  __shared__ int whist[SELECT_THREADS / 64][256];
-  __shared__ int hist[257];
-  __shared__ int wave_tot[SELECT_THREADS / 64];
-  __shared__ uint32_t s_prefix;
-  __shared__ int s_krem;
-  const int tid = threadIdx.x, wave = tid >> 6;
+  __shared__ SelectShared sh;
   int item = 0, hi = b.n_items - 1;       // last item whose first block is <= blockIdx.x
   while (item < hi) {
     const int mid = (item + hi + 1) >> 1;
     if (b.first_blk[mid] <= static_cast<int>(blockIdx.x)) item = mid; else hi = mid - 1;
   }
   const SelectItemDev& t = b.it[item];
-  const uint32_t flip = t.smallest ? 0xffffffffu : 0u;
-  if (t.n <= 64) {
-    // Small groups (the units of one head): a wavefront ranks a group by direct comparison - the rank of
-    // a unit is the number of units that come before it in the order (larger key, or equal key and lower
-    // index) - and the lanes whose rank is below k write their indices, ascending.  One group per wavefront.
-    const int g = (static_cast<int>(blockIdx.x) - t.blk_begin) * (SELECT_THREADS / 64) + wave;
-    if (g >= t.groups) return;
-    const int lane = tid & 63, n = t.n;
-    const int k = t.k_dev ? t.k_dev[g] : t.k;
-    const uint32_t key = lane < n ? ITEM_KEY(t.scores[static_cast<long long>(g) * n + lane]) : 0u;
-    int rank = 0;
-    for (int j = 0; j < n; ++j) {
-      const uint32_t kj = __shfl(key, j, 64);
-      rank += (kj > key) || (kj == key && j < lane);
-    }
-    const bool take = lane < n && rank < k;
-    const unsigned long long mask = __ballot(take);
-    int* out = t.idx + static_cast<long long>(g) * (t.k_dev ? t.ld_idx : k);
-    if (take) out[__popcll(mask & ((1ull << lane) - 1ull))] = lane;
-    if (t.k_dev)
-      for (int i = k + lane; i < t.ld_idx; i += 64) out[i] = -1;
-    return;
-  }
-  const int n = t.n, g = blockIdx.x - t.blk_begin;
-  const int k = t.k_dev ? t.k_dev[g] : t.k;
-  const float* s = t.scores + static_cast<long long>(g) * n;
-  int* out = t.idx + static_cast<long long>(g) * (t.k_dev ? t.ld_idx : k);
-
-  // this thread's contiguous run of indices; runs of up to SELECT_CACHE elements (groups of up to
-  // SELECT_THREADS * SELECT_CACHE units) are read once and kept in registers for all passes
-  const int per = (n + SELECT_THREADS - 1) / SELECT_THREADS;
-  const int i0 = min(tid * per, n), i1 = min(i0 + per, n);
-  const bool cached = per <= SELECT_CACHE;
-  uint32_t kc[SELECT_CACHE];
-  if (cached) {
-#pragma unroll
-    for (int j = 0; j < SELECT_CACHE; ++j) kc[j] = i0 + j < i1 ? ITEM_KEY(s[i0 + j]) : 0u;
-  }
-
-  uint32_t prefix = 0u;   // high bits of the k-th largest key found so far
-  int krem = k;           // rank (1-based) of the wanted key among keys matching the prefix
-  for (int i = tid; i < (SELECT_THREADS / 64) * 256; i += SELECT_THREADS) (&whist[0][0])[i] = 0;
-  __syncthreads();
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
-    if (cached) {
-#pragma unroll
-      for (int j = 0; j < SELECT_CACHE; ++j)
-        if (i0 + j < i1 && (kc[j] & hi_mask) == prefix) atomicAdd(&whist[wave][(kc[j] >> shift) & 255u], 1);
-    } else {
-      for (int i = i0; i < i1; ++i) {
-        const uint32_t key = ITEM_KEY(s[i]);
-        if ((key & hi_mask) == prefix) atomicAdd(&whist[wave][(key >> shift) & 255u], 1);
-      }
-    }
-    __syncthreads();
-    // suffix sums hist[d] = number of matching keys with digit >= d: the first four wavefronts own 64 digits
-    // each, add the per-wavefront histograms, scan inside the wavefront, then add the totals of the digits above
-    int suf = 0;
-    if (tid < 256) {
-#pragma unroll
-      for (int w = 0; w < SELECT_THREADS / 64; ++w) suf += whist[w][tid];
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int v = __shfl_down(suf, off, 64);
-        if ((tid & 63) + off < 64) suf += v;
-      }
-      if ((tid & 63) == 0) wave_tot[wave] = suf;
-    }
-    __syncthreads();
-    if (tid < 256) {
-      for (int w = wave + 1; w < 4; ++w) suf += wave_tot[w];
-      hist[tid] = suf;
-    } else if (tid == 256) {
-      hist[256] = 0;
-    }
-    for (int i = tid; i < (SELECT_THREADS / 64) * 256; i += SELECT_THREADS) (&whist[0][0])[i] = 0;   // for the next pass
-    __syncthreads();
-    if (tid < 256 && hist[tid] >= krem && hist[tid + 1] < krem) {   // exactly one thread
-      s_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
-      s_krem = krem - hist[tid + 1];
-    }
-    __syncthreads();
-    prefix = s_prefix;
-    krem = s_krem;
-  }
-  const uint32_t T = prefix;   // k-th largest key; take `krem` of the elements equal to it
-
-  int n_eq = 0, n_gt = 0;
-  if (cached) {
-#pragma unroll
-    for (int j = 0; j < SELECT_CACHE; ++j)
-      if (i0 + j < i1) { n_eq += kc[j] == T; n_gt += kc[j] > T; }
-  } else {
-    for (int i = i0; i < i1; ++i) {
-      const uint32_t key = ITEM_KEY(s[i]);
-      n_eq += key == T;
-      n_gt += key > T;
-    }
-  }
-  int tot;
-  const int eq_before = block_exclusive_scan(n_eq, wave_tot, tot);
-  const int eq_take = max(0, min(n_eq, krem - eq_before));       // ties of this run that are kept
-  int pos = block_exclusive_scan(n_gt + eq_take, wave_tot, tot);
-  int eq_left = eq_take;
-  if (cached) {
-#pragma unroll
-    for (int j = 0; j < SELECT_CACHE; ++j) {
-      if (i0 + j >= i1) continue;
-      bool take = kc[j] > T;
-      if (kc[j] == T && eq_left > 0) { take = true; --eq_left; }
-      if (take && pos < k) out[pos++] = i0 + j;
-    }
-  } else {
-    for (int i = i0; i < i1; ++i) {
-      const uint32_t key = ITEM_KEY(s[i]);
-      bool take = key > T;
-      if (key == T && eq_left > 0) { take = true; --eq_left; }
-      if (take && pos < k) out[pos++] = i;
-    }
-  }
-  if (t.k_dev)
-    for (int i = k + tid; i < t.ld_idx; i += SELECT_THREADS) out[i] = -1;
+  select_item_block(t, static_cast<int>(blockIdx.x) - t.blk_begin, sh);
 }
 
-// ---------------------------------------------------------------------------------------------
-#undef ITEM_KEY
 
 // ---------------------------------------------------------------------------------------------
 // Cumulative-threshold rule (Alg. 1's inner loop): how many units of a group stay when the smallest
