@@ -95,7 +95,7 @@ class Layer:
         self.k_ff = dff * keep_num // keep_den
         pairs = self.attn.pairs() + [self.ffn.pair()]
         self.pairs = (B.Pair * len(pairs))(*pairs)
-        self.scores = self._sel = self._map = self._tr = None     # descriptor arrays are built once: every buffer they name persists
+        self.scores = self._sel = self._map = self._tr = self._k = None     # descriptor arrays are built once: every buffer they name persists
         self.idx = [torch.empty((hkv, self.k_qk_units), dtype=torch.int32, device="cuda"),
                     torch.empty((hkv, self.k_vo), dtype=torch.int32, device="cuda"),
                     torch.empty((1, self.k_ff), dtype=torch.int32, device="cuda")]
@@ -128,9 +128,20 @@ class Layer:
         if self._tr is not None:
             self.ctx.ecospa_transpose_batch(self._tr)
 
+    def score_select(self):     # steps 1 and 2 in two launches (the team that finishes a group's scores selects from them)
+        if self._k is None:
+            import ctypes as C
+            self.score()
+            n = len(self.scores)
+            self._k = (C.c_int * n)(self.k_qk_units, self.k_vo, self.k_ff)
+            self._sp = (C.c_void_p * n)(*[t.data_ptr() for t in self.scores])
+            self._ip = (C.c_void_p * n)(*[t.data_ptr() for t in self.idx])
+            self.ctx.reserve(self.ctx.lib.ecospa_score_workspace_bytes(self.pairs, n))
+        self.ctx._check(self.ctx.lib.ecospa_score_select(self.ctx.h, self.pairs, len(self.pairs), self._sp, self._k, self._ip),
+                        "ecospa_score_select")
+
     def prune(self):
-        self.score()
-        self.select()
+        self.score_select()
         self.compact()
 
     # steps 4-5
@@ -188,8 +199,9 @@ def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps, rows=True, extras
     layers = []
     for _ in range(n_layers):
         a = AttnBlock(ctx, g(h * dh, d), g(h * dh, d), g(h * dh, d), g(h * dh, d) if rows else g(d, h * dh), g(h * dh), g(h * dh),
-                      g(h * dh), g(d), h, dh, rope=False, transposed=True, wo_rows=rows)
-        f = FfnBlock(ctx, g(dff, d), g(dff), g(dff, d) if rows else g(d, dff), g(d), B.ACT_GELU_ERF, transposed=True, w2_rows=rows)
+                      g(h * dh), g(d), h, dh, rope=False, transposed=True, wo_rows=rows, gather_transposed=False)
+        f = FfnBlock(ctx, g(dff, d), g(dff), g(dff, d) if rows else g(d, dff), g(d), B.ACT_GELU_ERF, transposed=True, w2_rows=rows,
+                     gather_transposed=False)
         layers.append((a, f))
     pairs = [p for a, f in layers for p in a.pairs() + [f.pair()]]
     pair_arr = (B.Pair * len(pairs))(*pairs)
@@ -209,6 +221,19 @@ def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps, rows=True, extras
     t_select = timed_gpu(torch, lambda: ctx.ecospa_select_topk_batch(sel_arr), steps, 3)
     t_compact = timed_gpu(torch, lambda: ctx.ecospa_compact_batch(item_arr), steps, 3)
     t_tr = timed_gpu(torch, lambda: ctx.ecospa_transpose_batch(tr_arr), steps, 3)
+    # the same gathers writing their transposed copies themselves (one launch for both; column gathers keep their pass)
+    for a, f in layers:
+        a.gather_transposed = f.gather_transposed = True
+    fused = [it for a, f in layers for it in a._map_items(0) + f._map_items(0)]
+    fused_arr = (B.MapItem * len(fused))(*fused)
+    rest = [t for a, f in layers for t in a.post_gather_items() + f.post_gather_items()]
+    rest_arr = (B.TransposeItem * len(rest))(*rest) if rest else None
+
+    def gather_all():
+        ctx.ecospa_compact_batch(fused_arr)
+        if rest_arr is not None:
+            ctx.ecospa_transpose_batch(rest_arr)
+    t_fused = timed_gpu(torch, gather_all, steps, 3)
     w_bytes = n_layers * 2 * (4 * d * d + 2 * d * dff)
     keep = keep_num / keep_den
     cols = 0 if rows else n_layers * 2 * (d * d + d * dff)  # the members gathered by column: W_o, W_2
@@ -220,7 +245,10 @@ def prune_stack(ctx, cfg, n_layers, keep_num, keep_den, steps, rows=True, extras
                         "traffic_gbs": traffic / t_compact / 1e6,
                         "frac_of_hbm_peak": traffic / t_compact / 1e6 / HBM_PEAK_GBS,
                         "note": "kept bytes read + written; traffic adds the whole 128-byte lines a column gather has to fetch (none with units as rows)"},
-            "transposes": {"us": t_tr * 1e3, "note": "the transposing copies a training block keeps beside its compact matrices (4 per layer), either layout"}}
+            "transposes": {"us": t_tr * 1e3, "note": "the transposing copies a training block keeps beside its compact matrices (4 per layer), either layout"},
+            "compact_with_transposed_copies": {"us": t_fused * 1e3, "bytes_gbs": 3 * keep * w_bytes / t_fused / 1e6,
+                                               "note": "row gathers that write the transposed copy themselves (kept bytes read once, written twice), "
+                                                       "against compact + transposes as two passes"}}
     if not extras:
         return head
     # the two other pieces of Alg. 1: pair-level importance (Eq. 8; the weights stand in for gradient
@@ -307,7 +335,10 @@ def layer_workload(ctx, name, steps, warmup, h_kv=None, detail=True):
         # break-down of the same step, each part timed on its own with device-side events (on the host clock the three
         # short pruning calls would show their Python marshalling rather than their kernels)
         parts = {nm: timed_gpu(torch, fn, steps, 2) for nm, fn in
-                 (("score", sp.score), ("select", sp.select), ("compact", sp.compact), ("fwd", sp.fwd), ("bwd", sp.bwd))}
+                 (("score", sp.score), ("select", sp.select), ("score_select", sp.score_select), ("compact", sp.compact),
+                  ("fwd", sp.fwd), ("bwd", sp.bwd))}
+        # score and select are the two steps as separate calls (three launches); the timed step takes them through
+        # ecospa_score_select (two launches): score_select
         out["parts_ms"] = parts
     ms_fb = timed(torch, lambda: (sp.fwd(), sp.bwd()), steps, 2)
     # model flops count the kept dimensions, not the zero padding of the compact layout

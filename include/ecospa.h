@@ -149,6 +149,16 @@ typedef struct {
 } ecospa_select_item;
 int ecospa_select_topk_batch(ecospa_ctx* ctx, const ecospa_select_item* items /*host*/, int n_items);
 
+/* Steps 1 and 2 together (Eq. 10, then Sec. 3.2's ranking with the count fixed by the caller), for callers that
+ * re-estimate few pairs at a time (one layer): scores[p] as ecospa_coupled_score writes them, and idx[p] (host array
+ * of device pointers, int32[groups_p * k[p]]) the k[p] (host array) best units of every group of pair p, as
+ * ecospa_select_topk would choose them from those scores.  The team that finishes a group's scores selects from
+ * them in the same launch: two launches in all instead of three.  Workspace as ecospa_coupled_score.
+ * Errors, before anything is launched: those of ecospa_coupled_score; ERR_NULL (k, idx, idx[p]);
+ * k[p] < 1 or k[p] > n_p / unit_p -> ERR_K. */
+int ecospa_score_select(ecospa_ctx* ctx, const ecospa_pair* pairs /*host*/, int n_pairs, float* const* scores /*host*/,
+                        const int* k /*host*/, int* const* idx /*host*/);
+
 /* ------------------------------------------------------------------------------------------
  * Pair-level importance and the cumulative-threshold rule (the two remaining pieces of Alg. 1).
  *
@@ -235,6 +245,16 @@ typedef struct {
   const int* k_group; /* device int32[groups / idx_div] or NULL */
   int ld_idx;
   int idx_div;        /* heads that share one index list: group g uses list (and count) g / idx_div; 0 or 1: its own */
+  void* dst_t;        /* row gathers (axis 0, scatter 0) only, NULL: none - the transposed copy of dst written by the same
+                         launch: dst_t[c * ld_dst_t + s] = dst[s * ld_dst + c] for every destination row s (padding
+                         rows included) and c < other_extent; ld_dst_t >= groups * kp * unit.  It replaces an
+                         ecospa_transpose_batch pass over the freshly gathered matrix.  Must not overlap src or dst. */
+  long long ld_dst_t;
+  const void* src_b;  /* row gathers of single rows (axis 0, scatter 0, unit 1) only, NULL: none - a second source of the
+                         shape and leading dimension of src whose kept rows are interleaved with those of src:
+                         destination row 2s is row map(s) of src, row 2s + 1 the same row of src_b, so dst has
+                         2 * groups * kp rows (the (gate, up) row pairs of a gated FFN's first matrix from W_gate and
+                         W_up in one copy); dst_t, if given, is the transposed copy of that interleaved matrix. */
 } ecospa_map_item;
 int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* items /*host*/, int n_items);
 

@@ -30,6 +30,7 @@ EXPORTS = (
     "ecospa_select_pairs", "ecospa_rope_table_ragged", "ecospa_adamw", "ecospa_transpose_batch",
     "ecospa_check_indices", "ecospa_contract_workspace_bytes", "ecospa_hbm_probe", "ecospa_contract_colsum", "ecospa_mfma_probe",
     "ecospa_coupled_score_static", "ecospa_coupled_score_static_max_bytes",
+    "ecospa_score_select",
     "ecospa_norm_fwd", "ecospa_norm_bwd", "ecospa_norm_bwd_workspace_bytes", "ecospa_embed_fwd", "ecospa_embed_bwd", "ecospa_xent",
 )
 NORM_RMS, NORM_LAYER = 0, 1
@@ -70,7 +71,8 @@ class MapItem(C.Structure):
     _fields_ = [("src", C.c_void_p), ("dst", C.c_void_p), ("dtype", C.c_int), ("axis", C.c_int), ("groups", C.c_int),
                 ("n", C.c_int), ("unit", C.c_int), ("k", C.c_int), ("kp", C.c_int), ("scatter", C.c_int),
                 ("other_extent", C.c_longlong), ("ld_src", C.c_longlong), ("ld_dst", C.c_longlong),
-                ("idx", C.c_void_p), ("k_group", C.c_void_p), ("ld_idx", C.c_int), ("idx_div", C.c_int)]
+                ("idx", C.c_void_p), ("k_group", C.c_void_p), ("ld_idx", C.c_int), ("idx_div", C.c_int),
+                ("dst_t", C.c_void_p), ("ld_dst_t", C.c_longlong), ("src_b", C.c_void_p)]
 
 
 class TransposeItem(C.Structure):
@@ -165,6 +167,8 @@ def load() -> C.CDLL:
     lib.ecospa_check_indices.restype = ci
     lib.ecospa_contract_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.ecospa_contract_workspace_bytes.restype = sz
+    lib.ecospa_score_select.argtypes = [vp, C.POINTER(Pair), ci, C.POINTER(vp), C.POINTER(ci), C.POINTER(vp)]
+    lib.ecospa_score_select.restype = ci
     lib.ecospa_coupled_score_static.argtypes = [vp, C.POINTER(Pair), ci, C.POINTER(vp)]
     lib.ecospa_coupled_score_static.restype = ci
     lib.ecospa_coupled_score_static_max_bytes.argtypes = []
@@ -317,6 +321,22 @@ class Context:
         self._check(self.lib.ecospa_coupled_score(self.h, arr, len(arr), ptrs), "ecospa_coupled_score")
         return list(out)
 
+    def ecospa_score_select(self, pairs: Sequence[Pair], k: Sequence[int], scores: Optional[Sequence[torch.Tensor]] = None,
+                            idx: Optional[Sequence[torch.Tensor]] = None):
+        """Steps 1 and 2 of a batch of pairs in two launches: (scores, idx) with scores[p] float32 [groups, n/unit] and
+        idx[p] int32 [groups, k[p]] (written into the given tensors if any)."""
+        arr = pairs if isinstance(pairs, C.Array) else (Pair * len(pairs))(*pairs)
+        self.reserve(self.lib.ecospa_score_workspace_bytes(arr, len(arr)))
+        if scores is None:
+            scores = [torch.empty((p.groups, p.n // max(p.unit, 1)), dtype=torch.float32, device=self.device) for p in arr]
+        if idx is None:
+            idx = [torch.empty((p.groups, int(kk)), dtype=torch.int32, device=self.device) for p, kk in zip(arr, k)]
+        sp = (C.c_void_p * len(arr))(*[o.data_ptr() for o in scores])
+        ip = (C.c_void_p * len(arr))(*[o.data_ptr() for o in idx])
+        ka = (C.c_int * len(arr))(*[int(kk) for kk in k])
+        self._check(self.lib.ecospa_score_select(self.h, arr, len(arr), sp, ka, ip), "ecospa_score_select")
+        return list(scores), list(idx)
+
     def ecospa_coupled_score_static(self, pairs: Sequence[Pair], out: Sequence[torch.Tensor]) -> list[torch.Tensor]:
         """ecospa_coupled_score for callers that cannot allocate: the caller brings the score tensors, the partial sums
         live in the library's own fixed device array (nothing is reserved or allocated here)."""
@@ -393,10 +413,14 @@ class Context:
     @staticmethod
     def map_item(src: torch.Tensor, dst: torch.Tensor, idx: torch.Tensor, axis: int, groups: int, n: int,
                  unit: int = 1, kp: Optional[int] = None, scatter: int = 0,
-                 k_group: Optional[torch.Tensor] = None, idx_div: int = 1) -> MapItem:
+                 k_group: Optional[torch.Tensor] = None, idx_div: int = 1,
+                 dst_t: Optional[torch.Tensor] = None, src_b: Optional[torch.Tensor] = None) -> MapItem:
         """Descriptor of one gather (scatter = 0), scatter with zero fill (1) or scatter that leaves the pruned
         slots of dst untouched (2) for :meth:`ecospa_compact_batch`.  With k_group (int32[groups]
-        on the device) group g keeps its first k_group[g] entries of idx[g, :] and kp must be given."""
+        on the device) group g keeps its first k_group[g] entries of idx[g, :] and kp must be given.  dst_t (row gathers
+        only): the transposed copy of dst, [other, slots], written by the same launch.  src_b (row gathers only): a
+        second source like src; dst then takes the kept rows of both, interleaved (row 2s from src, 2s + 1 from src_b)."""
+        assert src_b is None or (src_b.shape == src.shape and src_b.stride(0) == src.stride(0) and src_b.dtype == src.dtype)
         if k_group is not None:
             assert kp is not None and k_group.dtype == torch.int32 and k_group.numel() == groups // idx_div
             assert idx.dtype == torch.int32 and idx.dim() == 2 and idx.is_contiguous() and idx.shape[0] == groups // idx_div
@@ -409,7 +433,8 @@ class Context:
             ld_s, ld_d = src.stride(0), dst.stride(0)
         return MapItem(src.data_ptr(), dst.data_ptr(), dtype_code(src.dtype), axis, groups, n, unit, k, kp,
                        int(scatter), other, ld_s, ld_d, idx.data_ptr(), _ptr(k_group),
-                       idx.shape[1] if k_group is not None else 0, idx_div)
+                       idx.shape[1] if k_group is not None else 0, idx_div,
+                       _ptr(dst_t), 0 if dst_t is None else dst_t.stride(0), _ptr(src_b))
 
     def ecospa_compact_ragged(self, src: torch.Tensor, idx: torch.Tensor, k_group: torch.Tensor, axis: int, groups: int,
                               n: int, kp: int, unit: int = 1, scatter: int = 0,

@@ -61,16 +61,21 @@ __device__ __forceinline__ long long map_slot(const MapArgs& m, long long s) {
 struct MapItemDev {
   const void* src;
   void* dst;
+  void* dst_t;    // axis 0 gather: also the transposed copy of dst, [other, dst_slots] (null: none)
+  const void* src_b;   // axis 0 gather: second source, its rows interleaved with those of src (null: none)
   MapArgs m;
-  long long dst_slots, other, ld_src, ld_dst;
-  int esize;      // 2 or 4 bytes per element
-  int axis;
-  int vec;        // 16-byte accesses are legal
-  int gx;         // axis 1: blocks along the destination columns
+  long long ld_src, ld_dst, ld_dst_t;
+  int other;
+  int dst_slots;
+  int gx;         // axis 1: blocks along the destination columns; with dst_t: 64-wide tiles along the columns
   int rpb;        // axis 1: rows per workgroup
-  int lds_path;   // axis 1 gather with aligned rows: source window staged through LDS
   int blk_begin;  // first block of this item
+  unsigned char esize;      // 2 or 4 bytes per element
+  unsigned char axis;
+  unsigned char vec;        // 16-byte accesses are legal
+  unsigned char lds_path;   // axis 1 gather with aligned rows: source window staged through LDS
 };
+static_assert(sizeof(MapItemDev) == 128, "descriptor size");
 struct MapBatch {
   int n_items;
   int first_blk[MAP_MAX_ITEMS];   // blk_begin of every item, side by side: the search for a block's item stays in a few cache lines
@@ -90,6 +95,16 @@ __device__ __forceinline__ void map_rows_block(const MapItemDev& t, int blk) {
   if (row0 >= t.dst_slots) return;
   const long long cols = t.other;
   long long srow[MAP_ROW_PER_WAVE];   // source row, -1: zeros (padding / pruned), -2: no such destination row
+  if (t.src_b) {      // two sources interleaved row by row: MAP_ROW_PER_WAVE == 2, one destination row from each
+    static_assert(MAP_ROW_PER_WAVE == 2, "a wavefront's two rows are one interleaved pair");
+    const E* __restrict__ srcs[2] = {src, static_cast<const E*>(t.src_b)};
+    const long long sr = row0 < t.dst_slots ? map_slot(t.m, row0 >> 1) : -2;
+    if (sr == -2) return;
+    for (int j = 0; j < 2; ++j)
+      for (long long c = lane; c < cols; c += 64)      // rare shape (no transposed copy wanted): plain element copies
+        dst[(row0 + j) * t.ld_dst + c] = sr >= 0 ? srcs[j][sr * t.ld_src + c] : E(0);
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < MAP_ROW_PER_WAVE; ++j) {
     srow[j] = row0 + j < t.dst_slots ? map_slot(t.m, row0 + j) : -2;
@@ -126,6 +141,63 @@ __device__ __forceinline__ void map_rows_block(const MapItemDev& t, int blk) {
       if (srow[j] > -2)
         for (long long c = lane; c < cols; c += 64)
           dst[(row0 + j) * t.ld_dst + c] = srow[j] >= 0 ? src[srow[j] * t.ld_src + c] : E(0);
+  }
+}
+
+// ---- axis 0 with a transposed copy: a workgroup gathers a tile of 64 destination rows x 64 columns, stores it as it
+// is and, through a padded LDS tile, transposed - the transposed copies the contractions want beside a compact matrix
+// come out of the gather itself instead of a second pass that reads the compact matrix again.
+template <typename E>
+__device__ __forceinline__ void map_rows_tr_block(const MapItemDev& t, int blk, unsigned char* lds_raw) {
+  E* tile = reinterpret_cast<E*>(lds_raw);                                   // [64][65]
+  long long* srow = reinterpret_cast<long long*>(lds_raw + 64 * 65 * 4);     // [64]: source row, -1: zeros
+  const E* __restrict__ src = static_cast<const E*>(t.src);
+  E* __restrict__ dst = static_cast<E*>(t.dst);
+  E* __restrict__ dst_t = static_cast<E*>(t.dst_t);
+  const int tid = threadIdx.x;
+  const int r0 = (blk / t.gx) * 64, c0 = (blk % t.gx) * 64;
+  const int rows = t.dst_slots, cols = t.other;
+  const E* __restrict__ src_b = t.src_b ? static_cast<const E*>(t.src_b) : src;
+  // two sources interleaved row by row (src_b): destination row s is row map(s / 2) of src (s even) or of src_b
+  if (tid < 64) srow[tid] = r0 + tid < rows ? map_slot(t.m, t.src_b ? (r0 + tid) >> 1 : r0 + tid) : -1;
+  __syncthreads();
+  constexpr int V = 16 / sizeof(E), CH = 64 / V;            // elements per 16 bytes, 16-byte pieces per tile row
+  if (t.vec) {
+    const u32x4_t zero = {0u, 0u, 0u, 0u};
+    for (int p = tid; p < 64 * CH; p += 256) {
+      const int r = p / CH, c = (p % CH) * V;
+      const long long sr = srow[r];
+      const bool inside = r0 + r < rows && c0 + c < cols;   // cols % V == 0: a piece is inside or outside as a whole
+      union { u32x4_t v; E e[V]; } x;
+      x.v = zero;
+      if (inside && sr >= 0) x.v = *reinterpret_cast<const u32x4_t*>(((r & 1) ? src_b : src) + sr * t.ld_src + c0 + c);
+      if (inside) *reinterpret_cast<u32x4_t*>(dst + static_cast<long long>(r0 + r) * t.ld_dst + c0 + c) = x.v;
+#pragma unroll
+      for (int v = 0; v < V; ++v) tile[(c + v) * 65 + r] = x.e[v];
+    }
+    __syncthreads();
+    for (int p = tid; p < 64 * CH; p += 256) {
+      const int c = p / CH, r = (p % CH) * V;                 // row c of dst_t, V consecutive destination rows
+      if (c0 + c < cols && r0 + r < rows) {
+        union { u32x4_t v; E e[V]; } x;
+#pragma unroll
+        for (int v = 0; v < V; ++v) x.e[v] = tile[c * 65 + r + v];
+        *reinterpret_cast<u32x4_t*>(dst_t + static_cast<long long>(c0 + c) * t.ld_dst_t + r0 + r) = x.v;
+      }
+    }
+  } else {
+    for (int p = tid; p < 64 * 64; p += 256) {
+      const int r = p / 64, c = p % 64;
+      const bool inside = r0 + r < rows && c0 + c < cols;
+      const E x = (inside && srow[r] >= 0) ? ((r & 1) ? src_b : src)[srow[r] * t.ld_src + c0 + c] : E(0);
+      if (inside) dst[static_cast<long long>(r0 + r) * t.ld_dst + c0 + c] = x;
+      tile[c * 65 + r] = x;
+    }
+    __syncthreads();
+    for (int p = tid; p < 64 * 64; p += 256) {
+      const int c = p / 64, r = p % 64;
+      if (c0 + c < cols && r0 + r < rows) dst_t[static_cast<long long>(c0 + c) * t.ld_dst_t + r0 + r] = tile[c * 65 + r];
+    }
   }
 }
 
@@ -282,7 +354,8 @@ __device__ __forceinline__ void map_cols_lds_block(const MapItemDev& t, int blk,
 }
 
 __global__ __launch_bounds__(256) void map_batch_kernel(const MapBatch b) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[MAP_LDS_ROWS * MAP_LDS_CHUNKS * 16 + (MAP_LDS_GROUPS * 8 + 2) * 4];
+  constexpr int LDS_COLS = MAP_LDS_ROWS * MAP_LDS_CHUNKS * 16 + (MAP_LDS_GROUPS * 8 + 2) * 4, LDS_TR = 64 * 65 * 4 + 64 * 8;
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[LDS_COLS > LDS_TR ? LDS_COLS : LDS_TR];
   const int blk = blockIdx.x;
   int i = 0, hi = b.n_items - 1;          // last item whose first block is <= blk
   while (i < hi) {
@@ -291,7 +364,10 @@ __global__ __launch_bounds__(256) void map_batch_kernel(const MapBatch b) {
   }
   const MapItemDev& t = b.it[i];
   const int local = blk - t.blk_begin;
-  if (t.axis == 0) {
+  if (t.dst_t) {
+    if (t.esize == 2) map_rows_tr_block<bf16_t>(t, local, lds_raw);
+    else map_rows_tr_block<float>(t, local, lds_raw);
+  } else if (t.axis == 0) {
     if (t.esize == 2) map_rows_block<bf16_t>(t, local);
     else map_rows_block<float>(t, local);
   } else if (t.lds_path) {
@@ -323,6 +399,13 @@ static int validate_map(const ecospa_map_item& q) {
   if (full_slots > (1ll << 31) - 1 || cmp_slots > (1ll << 31) - 1) return ECOSPA_ERR_SHAPE;
   const long long src_slots = q.scatter ? cmp_slots : full_slots;
   const long long dst_slots = q.scatter ? full_slots : cmp_slots;
+  if (q.other_extent > (1ll << 31) - 1) return ECOSPA_ERR_SHAPE;
+  if (q.src_b) {      // interleaved sources: row gathers of single rows
+    if (q.axis != 0 || q.scatter != 0 || q.unit != 1 || 2 * cmp_slots > (1ll << 31) - 1) return ECOSPA_ERR_SHAPE;
+  }
+  if (q.dst_t) {      // the transposed copy comes out of row gathers only
+    if (q.axis != 0 || q.scatter != 0 || q.ld_dst_t < (q.src_b ? 2 : 1) * dst_slots) return ECOSPA_ERR_SHAPE;
+  }
   if (q.axis == 0) {
     if (q.ld_src < q.other_extent || q.ld_dst < q.other_extent) return ECOSPA_ERR_SHAPE;
   } else {
@@ -362,14 +445,20 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
       t.m = MapArgs{q.idx, q.groups, q.n, q.unit, q.k, q.kp, q.scatter, q.k_group, q.ld_idx ? q.ld_idx : q.k, q.idx_div > 0 ? q.idx_div : 1};
       const long long full_slots = static_cast<long long>(q.groups) * q.n;
       const long long cmp_slots = static_cast<long long>(q.groups) * q.kp * q.unit;
-      t.dst_slots = q.scatter ? full_slots : cmp_slots;
-      t.other = q.other_extent; t.ld_src = q.ld_src; t.ld_dst = q.ld_dst;
-      t.esize = static_cast<int>(dtype_size(q.dtype));
-      t.axis = q.axis;
+      t.dst_slots = static_cast<int>(q.scatter ? full_slots : (q.src_b ? 2 : 1) * cmp_slots);
+      t.other = static_cast<int>(q.other_extent); t.ld_src = q.ld_src; t.ld_dst = q.ld_dst;
+      t.dst_t = q.dst_t; t.ld_dst_t = q.ld_dst_t; t.src_b = q.src_b;
+      t.esize = static_cast<unsigned char>(dtype_size(q.dtype));
+      t.axis = static_cast<unsigned char>(q.axis);
       const int V = 16 / t.esize;
       t.blk_begin = static_cast<int>(blk);
       b.first_blk[i] = t.blk_begin;
-      if (q.axis == 0) {
+      if (q.dst_t) {
+        t.vec = aligned16(q.src) && aligned16(q.src_b) && aligned16(q.dst) && aligned16(q.dst_t) && q.ld_src % V == 0 && q.ld_dst % V == 0 &&
+                q.ld_dst_t % V == 0 && t.dst_slots % V == 0 && q.other_extent % V == 0;
+        t.gx = static_cast<int>((q.other_extent + 63) / 64);
+        blk += static_cast<long long>((t.dst_slots + 63) / 64) * t.gx;
+      } else if (q.axis == 0) {
         t.vec = aligned16(q.src) && aligned16(q.dst) && q.ld_src % V == 0 && q.ld_dst % V == 0;
         blk += (t.dst_slots + MAP_ROWS_PER_BLOCK - 1) / MAP_ROWS_PER_BLOCK;
       } else {
@@ -408,7 +497,7 @@ static int mapped_copy(ecospa_ctx* ctx, const void* src, void* dst, int dtype, i
   ecospa_map_item q;
   q.src = src; q.dst = dst; q.dtype = dtype; q.axis = axis; q.groups = groups; q.n = n; q.unit = unit; q.k = k;
   q.kp = kp; q.other_extent = other; q.ld_src = ld_src; q.ld_dst = ld_dst; q.idx = idx; q.scatter = scatter;
-  q.k_group = nullptr; q.ld_idx = 0; q.idx_div = 0;
+  q.k_group = nullptr; q.ld_idx = 0; q.idx_div = 0; q.dst_t = nullptr; q.ld_dst_t = 0; q.src_b = nullptr;
   return ecospa_compact_batch(ctx, &q, 1);
 }
 

@@ -11,6 +11,7 @@
 // scores: r = |a||b|, group L2 norm, normalised scores (or the weighted sums of Eq. 8).
 // No floating-point atomics; all reduction orders are fixed.
 #include "common.h"
+#include "select_dev.h"
 
 #define SCORE_MAX_PAIRS 96         // descriptors travel as kernel arguments (about 15 KB)
 #define SCORE_ROWS_PER_BLOCK 16   // row-norm blocks: 4 waves x 4 rows
@@ -338,6 +339,58 @@ __global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_kernel(const S
   else score_finish_group<0>(p, local, tid, SCORE_FIN_THREADS, total);
 }
 
+// Steps 1 and 2 in one finishing launch: the workgroup (or wavefront) that has written a group's scores goes on to
+// select the group's k best units - the scores are still in its cache, and one launch and its start-up are gone.
+// The team of a group follows the selection's rule (a wavefront for groups of up to 64 units, else a workgroup).
+#define SCORE_SEL_PAIRS 48        // pairs per launch of the combined form: both argument structs stay inside 16 KB
+struct ScoreSelect {
+  int k[SCORE_SEL_PAIRS];
+  int* idx[SCORE_SEL_PAIRS];
+};
+static_assert(sizeof(ScoreBatch) + sizeof(ScoreSelect) <= 16384, "kernel arguments of one launch");
+static_assert(SCORE_FIN_THREADS == SELECT_THREADS, "one team shape for both halves");
+
+__global__ __launch_bounds__(SCORE_FIN_THREADS) void score_finish_select_kernel(const ScoreBatch b, const ScoreSelect s) {
+  __shared__ SelectShared sh;
+  __shared__ float red[SCORE_FIN_WAVES];
+  const ScorePairDev& p = b.p[blockIdx.y];
+  const int local = blockIdx.x, tid = threadIdx.x;
+  const int nu = p.n / p.unit;
+  const bool wave_team = nu <= 64;
+  const int blocks = wave_team ? (p.groups + SCORE_FIN_WAVES - 1) / SCORE_FIN_WAVES : p.groups;
+  if (local >= blocks) return;      // the whole workgroup leaves together
+  const int ur = (p.rep1 > 1 || p.rep2 > 1) ? 0 : p.unit;
+  if (wave_team) {
+    const int g = local * SCORE_FIN_WAVES + (tid >> 6);
+    if (g < p.groups) {
+      auto total = [](float v) { return wave_sum(v); };
+      if (ur == 1) score_finish_group<1>(p, g, tid & 63, 64, total);
+      else if (ur == 2) score_finish_group<2>(p, g, tid & 63, 64, total);
+      else score_finish_group<0>(p, g, tid & 63, 64, total);
+    }
+  } else {
+    auto total = [&](float v) {
+      v = wave_sum(v);
+      if ((tid & 63) == 0) red[tid >> 6] = v;
+      __syncthreads();
+      float tot = 0.f;
+#pragma unroll
+      for (int w = 0; w < SCORE_FIN_WAVES; ++w) tot += red[w];
+      return tot;
+    };
+    if (ur == 1) score_finish_group<1>(p, local, tid, SCORE_FIN_THREADS, total);
+    else if (ur == 2) score_finish_group<2>(p, local, tid, SCORE_FIN_THREADS, total);
+    else score_finish_group<0>(p, local, tid, SCORE_FIN_THREADS, total);
+  }
+  __threadfence_block();      // the scores were written by other threads of this team
+  __syncthreads();
+  SelectItemDev t;
+  t.scores = p.scores; t.idx = s.idx[blockIdx.y];
+  t.n = nu; t.k = s.k[blockIdx.y];
+  t.blk_begin = 0; t.groups = p.groups; t.k_dev = nullptr; t.ld_idx = t.k; t.smallest = 0;
+  select_item_block(t, local, sh);
+}
+
 // ------------------------------------------------------------------------------------------
 static inline int pair_rep1(const ecospa_pair& q) { return q.rep1 > 0 ? q.rep1 : 1; }
 static inline int pair_rep2(const ecospa_pair& q) { return q.rep2 > 0 ? q.rep2 : 1; }
@@ -403,20 +456,30 @@ static int score_validate(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs
 
 // `scratch` / `scratch_bytes`: device memory for the partial squared sums (the caller's workspace, or the library's
 // own fixed array); the arguments have been validated.
+// With `sel_k` / `sel_idx` (host arrays, one entry per pair) the finishing launch also selects (step 2).
 static int score_run(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, float* const* scores, int fisher,
-                     float n_samples, void* scratch, size_t scratch_bytes) {
+                     float n_samples, void* scratch, size_t scratch_bytes, const int* sel_k = nullptr,
+                     int* const* sel_idx = nullptr) {
   const size_t need = ecospa_score_workspace_bytes(pairs, n_pairs);
   if (!scratch || scratch_bytes < need) return ECOSPA_ERR_WORKSPACE;
   WsCarver ws(scratch, scratch_bytes);
 
-  for (int first = 0; first < n_pairs; first += SCORE_MAX_PAIRS) {
+  const int chunk = sel_k ? SCORE_SEL_PAIRS : SCORE_MAX_PAIRS;
+  for (int first = 0; first < n_pairs; first += chunk) {
     ScoreBatch b;
     memset(&b, 0, sizeof(b));
-    b.n_pairs = (n_pairs - first < SCORE_MAX_PAIRS) ? n_pairs - first : SCORE_MAX_PAIRS;
-    int blk = 0, fin = 0;
+    b.n_pairs = (n_pairs - first < chunk) ? n_pairs - first : chunk;
+    int blk = 0, fin = 0, fin_sel = 0;
+    ScoreSelect sel;
     for (int i = 0; i < b.n_pairs; ++i) {
       const ecospa_pair& q = pairs[first + i];
       ScorePairDev& p = b.p[i];
+      if (sel_k) {
+        sel.k[i] = sel_k[first + i];
+        sel.idx[i] = sel_idx[first + i];
+        const int team_blocks = q.n / q.unit <= 64 ? (q.groups + SCORE_FIN_WAVES - 1) / SCORE_FIN_WAVES : q.groups;
+        if (team_blocks > fin_sel) fin_sel = team_blocks;
+      }
       p.w1 = q.w1; p.w1b = (q.kind == ECOSPA_PAIR_FFN_GATED) ? q.w1b : nullptr; p.w2 = q.w2;
       p.ld1 = q.ld1; p.ld1b = q.ld1b; p.ld2 = q.ld2;
       p.rep1 = pair_rep1(q); p.rep2 = pair_rep2(q);
@@ -452,8 +515,13 @@ static int score_run(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, flo
     if (!ws.ok()) return ECOSPA_ERR_WORKSPACE;
     hipLaunchKernelGGL(score_sumsq_kernel, dim3(blk), dim3(256), 0, ctx->stream, b);
     ECOSPA_CHECK_LAUNCH(ctx, "score_sumsq_kernel");
-    hipLaunchKernelGGL(score_finish_kernel, dim3(fin, b.n_pairs), dim3(SCORE_FIN_THREADS), 0, ctx->stream, b);
-    ECOSPA_CHECK_LAUNCH(ctx, "score_finish_kernel");
+    if (sel_k) {
+      hipLaunchKernelGGL(score_finish_select_kernel, dim3(fin_sel, b.n_pairs), dim3(SCORE_FIN_THREADS), 0, ctx->stream, b, sel);
+      ECOSPA_CHECK_LAUNCH(ctx, "score_finish_select_kernel");
+    } else {
+      hipLaunchKernelGGL(score_finish_kernel, dim3(fin, b.n_pairs), dim3(SCORE_FIN_THREADS), 0, ctx->stream, b);
+      ECOSPA_CHECK_LAUNCH(ctx, "score_finish_kernel");
+    }
   }
   return ECOSPA_OK;
 }
@@ -462,6 +530,19 @@ extern "C" int ecospa_coupled_score(ecospa_ctx* ctx, const ecospa_pair* pairs, i
   const int rc = score_validate(ctx, pairs, n_pairs, scores);
   if (rc) return rc;
   return score_run(ctx, pairs, n_pairs, scores, 0, 1.f, ctx->ws, ctx->ws_bytes);
+}
+
+extern "C" int ecospa_score_select(ecospa_ctx* ctx, const ecospa_pair* pairs, int n_pairs, float* const* scores,
+                                   const int* k, int* const* idx) {
+  const int rc = score_validate(ctx, pairs, n_pairs, scores);
+  if (rc) return rc;
+  if (!k || !idx) return ECOSPA_ERR_NULL;
+  for (int i = 0; i < n_pairs; ++i) {
+    if (!idx[i]) return ECOSPA_ERR_NULL;
+    if (k[i] < 1 || k[i] > pairs[i].n / pairs[i].unit) return ECOSPA_ERR_K;
+    if (static_cast<long long>(pairs[i].groups) * (pairs[i].n / pairs[i].unit) > (1ll << 31) - 1) return ECOSPA_ERR_SHAPE;
+  }
+  return score_run(ctx, pairs, n_pairs, scores, 0, 1.f, ctx->ws, ctx->ws_bytes, k, idx);
 }
 
 extern "C" int ecospa_pair_fisher(ecospa_ctx* ctx, const ecospa_pair* grads, int n_pairs, float n_samples,

@@ -30,35 +30,41 @@ __device__ __forceinline__ uint32_t score_key(float x) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Exclusive prefix sum of `v` over the block's threads in thread order, and the block total.
-__device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int& total) {
+// Inclusive prefix sum over the lanes of a wavefront by lane-permutation (DPP) adds: inside the rows of 16, then the last
+// lane of rows 0 and 2 into rows 1 and 3, then lane 31 into the upper half - nothing goes through LDS.
+#define ECOSPA_DPP_IADD(v, ctrl, rows) ((v) + __builtin_amdgcn_update_dpp(0, (v), (ctrl), (rows), 0xF, false))
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);   // row_shr:1, lanes without a source add 0
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);   // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);   // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);   // row_shr:8
+  v = ECOSPA_DPP_IADD(v, 0x142, 0xA);                              // row_bcast:15 into rows 1 and 3
+  v = ECOSPA_DPP_IADD(v, 0x143, 0xC);                              // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
+// Exclusive prefix sums of `a` and of `b` over the block's threads in thread order (one pass for both).
+// `wave_tot` holds 2 x (SELECT_THREADS / 64) ints and must not be in use by another scan one barrier earlier.
+__device__ __forceinline__ void block_exclusive_scan2(int a, int b, int* wave_tot, int& a_before, int& b_before) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int up = __shfl_up(inc, off, 64);
-    if (lane >= off) inc += up;
-  }
-  __syncthreads();   // protect wave_tot from the previous use
-  if (lane == 63) wave_tot[wave] = inc;
+  const int ia = wave_inclusive_scan(a), ib = wave_inclusive_scan(b);
+  if (lane == 63) { wave_tot[2 * wave] = ia; wave_tot[2 * wave + 1] = ib; }
   __syncthreads();
-  int before = 0, tot = 0;
+  int ba = 0, bb = 0;
 #pragma unroll
   for (int w = 0; w < SELECT_THREADS / 64; ++w) {
-    const int c = wave_tot[w];
-    if (w < wave) before += c;
-    tot += c;
+    const int ca = wave_tot[2 * w], cb = wave_tot[2 * w + 1];
+    if (w < wave) { ba += ca; bb += cb; }
   }
-  total = tot;
-  return before + inc - v;
+  a_before = ba + ia - a;
+  b_before = bb + ib - b;
 }
 
 // LDS of one selecting workgroup.  One histogram per wavefront: normalised scores share their top key bits, so a
 // single histogram would serialise nearly every atomic of the first pass on a few counters.
 struct SelectShared {
   int whist[SELECT_THREADS / 64][256];
-  int hist[257];
-  int wave_tot[SELECT_THREADS / 64];
+  int wave_tot[2 * (SELECT_THREADS / 64)];
   uint32_t s_prefix;
   int s_krem;
 };
@@ -66,7 +72,6 @@ struct SelectShared {
 // The work of workgroup number `blk` of item t (all SELECT_THREADS threads of the workgroup call it).
 __device__ __forceinline__ void select_item_block(const SelectItemDev& t, int blk, SelectShared& sh) {
   auto& whist = sh.whist;
-  auto& hist = sh.hist;
   auto& wave_tot = sh.wave_tot;
   uint32_t& s_prefix = sh.s_prefix;
   int& s_krem = sh.s_krem;
@@ -83,7 +88,7 @@ __device__ __forceinline__ void select_item_block(const SelectItemDev& t, int bl
     const uint32_t key = lane < n ? ITEM_KEY(t.scores[static_cast<long long>(g) * n + lane]) : 0u;
     int rank = 0;
     for (int j = 0; j < n; ++j) {
-      const uint32_t kj = __shfl(key, j, 64);
+      const uint32_t kj = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(key), j));   // j is uniform: no LDS crossbar
       rank += (kj > key) || (kj == key && j < lane);
     }
     const bool take = lane < n && rank < k;
@@ -128,31 +133,25 @@ __device__ __forceinline__ void select_item_block(const SelectItemDev& t, int bl
       }
     }
     __syncthreads();
-    // suffix sums hist[d] = number of matching keys with digit >= d: the first four wavefronts own 64 digits
-    // each, add the per-wavefront histograms, scan inside the wavefront, then add the totals of the digits above
-    int suf = 0;
+    // suffix sums suf[d] = number of matching keys with digit >= d: the first four wavefronts own 64 digits each, add
+    // the per-wavefront histograms (and clear them for the next pass), scan inside the wavefront by lane permutations,
+    // then add the totals of the digits above.  Exactly one digit has suf[d] >= krem > suf[d + 1] = suf[d] - cnt[d].
+    int cnt = 0, suf = 0;
     if (tid < 256) {
 #pragma unroll
-      for (int w = 0; w < SELECT_THREADS / 64; ++w) suf += whist[w][tid];
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int v = __shfl_down(suf, off, 64);
-        if ((tid & 63) + off < 64) suf += v;
-      }
-      if ((tid & 63) == 0) wave_tot[wave] = suf;
+      for (int w = 0; w < SELECT_THREADS / 64; ++w) { cnt += whist[w][tid]; whist[w][tid] = 0; }
+      const int inc = wave_inclusive_scan(cnt);
+      const int tot = __builtin_amdgcn_readlane(inc, 63);
+      suf = tot - inc + cnt;
+      if ((tid & 63) == 0) wave_tot[wave] = tot;
     }
     __syncthreads();
     if (tid < 256) {
       for (int w = wave + 1; w < 4; ++w) suf += wave_tot[w];
-      hist[tid] = suf;
-    } else if (tid == 256) {
-      hist[256] = 0;
-    }
-    for (int i = tid; i < (SELECT_THREADS / 64) * 256; i += SELECT_THREADS) (&whist[0][0])[i] = 0;   // for the next pass
-    __syncthreads();
-    if (tid < 256 && hist[tid] >= krem && hist[tid + 1] < krem) {   // exactly one thread
-      s_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
-      s_krem = krem - hist[tid + 1];
+      if (suf >= krem && suf - cnt < krem) {
+        s_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
+        s_krem = krem - (suf - cnt);
+      }
     }
     __syncthreads();
     prefix = s_prefix;
@@ -172,11 +171,11 @@ __device__ __forceinline__ void select_item_block(const SelectItemDev& t, int bl
       n_gt += key > T;
     }
   }
-  int tot;
-  const int eq_before = block_exclusive_scan(n_eq, wave_tot, tot);
-  const int eq_take = max(0, min(n_eq, krem - eq_before));       // ties of this run that are kept
-  int pos = block_exclusive_scan(n_gt + eq_take, wave_tot, tot);
-  int eq_left = eq_take;
+  // the ties are kept in index order until `krem` of them are: min(ties before this run, krem) of those before it
+  int eq_before, gt_before;
+  block_exclusive_scan2(n_eq, n_gt, wave_tot, eq_before, gt_before);
+  int eq_left = max(0, min(n_eq, krem - eq_before));       // ties of this run that are kept
+  int pos = gt_before + min(eq_before, krem);
   if (cached) {
 #pragma unroll
     for (int j = 0; j < SELECT_CACHE; ++j) {

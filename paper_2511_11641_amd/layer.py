@@ -27,15 +27,18 @@ class FfnBlock:
     """Compacted FFN pair (W_in / W_out, or W_gate (.) W_up / W_down)."""
 
     def __init__(self, ctx: B.Context, w1, b1, w2, b2, act: int, w1b=None, transposed: bool = False,
-                 bias_grads: Optional[bool] = None, w2_rows: bool = False):
+                 bias_grads: Optional[bool] = None, w2_rows: bool = False, gather_transposed: bool = True):
         """w2_rows: the second matrix is stored with its units as rows, [n, d] (the orientation of B in App. A.1; how
         GPT-2 checkpoints keep W_out): it is then scored along rows and its kept units are gathered as rows into the
         transposed compact copy, from which the [d, kp] matrix of the forward pass is written by a transposing copy -
         no column gather anywhere.  transposed: keep transposed copies of the compact matrices for the backward pass (refreshed by
         :meth:`compact`; after a parameter update call :meth:`refresh_transposed`).  bias_grads: ask the backward pass
         for the bias gradients (default: for the biases the block has; True: all of them - they are column sums of the
-        upstream gradients and exist with or without a bias)."""
+        upstream gradients and exist with or without a bias).  gather_transposed: row gathers write the transposed
+        copy of their result themselves (one launch for a compaction) instead of leaving it to a transposing copy
+        afterwards (:meth:`post_gather_items` then lists only what is left)."""
         self.ctx, self.act = ctx, act
+        self.gather_transposed = gather_transposed
         self.bias_grads = bias_grads
         self.transposed = transposed
         self.w1, self.b1, self.w2, self.b2, self.w1b = w1, b1, w2, b2, w1b
@@ -95,10 +98,12 @@ class FfnBlock:
         """Transposing copies that complete a gather: the transposed copies for the backward pass, and - with the
         second matrix stored units-as-rows - its [d, kp] form for the forward pass out of the gathered rows."""
         items = []
-        if self.transposed:
+        fused = self.gather_transposed
+        if self.transposed and not fused:
             items.append(B.Context.transpose_item(self.w1_c, self.w1_t))
         if self.w2_rows:
-            items.append(B.Context.transpose_item(self.w2_t, self.w2_c))
+            if not fused:
+                items.append(B.Context.transpose_item(self.w2_t, self.w2_c))
         elif self.transposed:
             items.append(B.Context.transpose_item(self.w2_c, self.w2_t))
         return items
@@ -130,17 +135,22 @@ class FfnBlock:
     def _map_items(self, scatter: int):
         """Descriptors between every full-size member and its compact counterpart: gathers (0) or scatters (1, 2)."""
         kp = self.kp
-        members = [(self.w1, self.gate_rows(self.w1_c), 0)]
-        if self.gated:
-            members.append((self.w1b, self.up_rows(self.w1_c), 0))
+        fused = self.gather_transposed and not scatter      # gathers that write their transposed copies themselves
+        # (full-size tensor, compact tensor, axis, transposed copy of the compact tensor, second interleaved source)
+        if self.gated and fused and self.transposed:        # (gate, up) row pairs out of both matrices in one copy
+            members = [(self.w1, self.w1_c, 0, self.w1_t, self.w1b)]
+        else:
+            members = [(self.w1, self.gate_rows(self.w1_c), 0, self.w1_t if fused and self.transposed and not self.gated else None, None)]
+            if self.gated:
+                members.append((self.w1b, self.up_rows(self.w1_c), 0, None, None))
         if self.b1 is not None:       # the up branch of a gated FFN has no bias: its slots stay zero
             if self.gated:            # every second slot: a [kp, 1] matrix with a row pitch of 2
-                members.append((self.b1.view(-1, 1), self.b1_c.view(kp, 2)[:, :1], 0))
+                members.append((self.b1.view(-1, 1), self.b1_c.view(kp, 2)[:, :1], 0, None, None))
             else:
-                members.append((self.b1, self.b1_c, 1))
-        members.append((self.w2, self.w2_t, 0) if self.w2_rows else (self.w2, self.w2_c, 1))
+                members.append((self.b1, self.b1_c, 1, None, None))
+        members.append((self.w2, self.w2_t, 0, self.w2_c if fused else None, None) if self.w2_rows else (self.w2, self.w2_c, 1, None, None))
         return [B.Context.map_item(c if scatter else f, f if scatter else c, self.idx, axis, 1, self.n, 1, kp,
-                                   scatter=scatter, k_group=self.k_group) for f, c, axis in members]
+                                   scatter=scatter, k_group=self.k_group, dst_t=ct, src_b=fb) for f, c, axis, ct, fb in members]
 
     def write_back_items(self):
         """Scatters of the compact tensors into the full-size ones that leave the pruned rows/columns as they are."""
@@ -209,10 +219,12 @@ class AttnBlock:
 
     def __init__(self, ctx: B.Context, wq, wk, wv, wo, bq, bk, bv, bo, h: int, d_h: int, *, rope: bool,
                  causal: bool = True, rope_base: float = 10000.0, h_kv: Optional[int] = None, transposed: bool = False,
-                 bias_grads: Optional[bool] = None, wo_rows: bool = False):
+                 bias_grads: Optional[bool] = None, wo_rows: bool = False, gather_transposed: bool = True):
         """bias_grads: ask the backward pass for the bias gradients (default: for the biases the block has).
-        wo_rows: W_o is stored with its units as rows, [h * d_h, d] (see FfnBlock's w2_rows)."""
+        wo_rows: W_o is stored with its units as rows, [h * d_h, d]; gather_transposed: row gathers write their
+        transposed copies themselves (see FfnBlock)."""
         self.ctx, self.h, self.d_h, self.rope, self.causal, self.rope_base = ctx, h, d_h, rope, causal, rope_base
+        self.gather_transposed = gather_transposed
         self.bias_grads = bias_grads
         self.transposed = transposed      # transposed copies of the compact matrices for the backward pass
         self.h_kv = h if h_kv is None else h_kv
@@ -296,20 +308,24 @@ class AttnBlock:
         h, hk, u = self.h, self.h_kv, self.unit
         nq, nk, kpu = self.nq, self.nk, self.kp_qk // u
 
-        def mq(full, cmp, axis, heads):      # heads that share an index list with (heads // h_kv - 1) others
+        fused = self.gather_transposed and not scatter      # gathers that write their transposed copies themselves
+
+        def mq(full, cmp, axis, heads, cmp_t=None):      # heads that share an index list with (heads // h_kv - 1) others
             return B.Context.map_item(cmp if scatter else full, full if scatter else cmp, self.idx_qk, axis, heads, self.n_qk, u, kpu,
-                                      scatter=scatter, k_group=self.k_qk_group, idx_div=heads // hk)
+                                      scatter=scatter, k_group=self.k_qk_group, idx_div=heads // hk, dst_t=cmp_t)
 
-        def mv(full, cmp, axis, heads):
+        def mv(full, cmp, axis, heads, cmp_t=None):
             return B.Context.map_item(cmp if scatter else full, full if scatter else cmp, self.idx_vo, axis, heads, self.n_vo, 1,
-                                      self.kp_vo, scatter=scatter, k_group=self.k_vo_group, idx_div=heads // hk)
+                                      self.kp_vo, scatter=scatter, k_group=self.k_vo_group, idx_div=heads // hk, dst_t=cmp_t)
 
-        items = [mq(self.wq, self.wqkv_c[:nq], 0, h), mq(self.wk, self.wqkv_c[nq:nq + nk], 0, hk),
-                 mv(self.wv, self.wqkv_c[nq + nk:], 0, hk)]
+        qkv_t = self.wqkv_t if fused and self.transposed else None      # [d, nq + nk + nv]: every member writes its columns
+        col = lambda a, b: None if qkv_t is None else qkv_t[:, a:b]
+        items = [mq(self.wq, self.wqkv_c[:nq], 0, h, col(0, nq)), mq(self.wk, self.wqkv_c[nq:nq + nk], 0, hk, col(nq, nq + nk)),
+                 mv(self.wv, self.wqkv_c[nq + nk:], 0, hk, col(nq + nk, None))]
         if self.bq is not None:
             items += [mq(self.bq, self.bqkv_c[:nq], 1, h), mq(self.bk, self.bqkv_c[nq:nq + nk], 1, hk),
                       mv(self.bv, self.bqkv_c[nq + nk:], 1, hk)]
-        items.append(mv(self.wo, self.wo_t, 0, h) if self.wo_rows else mv(self.wo, self.wo_c, 1, h))
+        items.append(mv(self.wo, self.wo_t, 0, h, self.wo_c if fused else None) if self.wo_rows else mv(self.wo, self.wo_c, 1, h))
         if self.orig_qk is not None and not scatter:      # the int32 table moves as 4-byte words
             items.append(B.Context.map_item(self.orig_qk.view(torch.float32).view(-1), self.rope_idx.view(torch.float32).view(-1),
                                             self.idx_qk, 1, hk, self.orig_qk.shape[1], 1, self.k_qk_units))
@@ -324,10 +340,12 @@ class AttnBlock:
     def post_gather_items(self):
         """Transposing copies that complete a gather (see FfnBlock.post_gather_items)."""
         items = []
-        if self.transposed:
+        fused = self.gather_transposed
+        if self.transposed and not fused:
             items.append(B.Context.transpose_item(self.wqkv_c, self.wqkv_t))
         if self.wo_rows:
-            items.append(B.Context.transpose_item(self.wo_t, self.wo_c))
+            if not fused:
+                items.append(B.Context.transpose_item(self.wo_t, self.wo_c))
         elif self.transposed:
             items.append(B.Context.transpose_item(self.wo_c, self.wo_t))
         return items

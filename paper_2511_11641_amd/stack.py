@@ -96,9 +96,9 @@ class DecoderStack:
                 ly.full[fam] = t
                 ly.attn[fam] = AttnBlock(ctx, t["wq"], t["wk"], t["wv"], t["wo"], t.get("bq"), t.get("bk"), t.get("bv"),
                                          t.get("bo"), h, dh, rope=cfg["rope"], causal=True, transposed=(fam == "w" and train),
-                                         h_kv=hkv)
+                                         h_kv=hkv, gather_transposed=False)
                 ly.ffn[fam] = FfnBlock(ctx, t["w1"], t.get("b1"), t["w2"], t.get("b2"), act, t.get("w1b"),
-                                       transposed=(fam == "w" and train))
+                                       transposed=(fam == "w" and train), gather_transposed=False)
                 if permanent:
                     ly.attn[fam].track_rotary_blocks()
             ly.idx = [torch.empty((hkv, self.k[0]), dtype=torch.int32, device="cuda"),

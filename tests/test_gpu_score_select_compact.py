@@ -6,7 +6,7 @@ import torch
 from oracle import ecospa_oracle as O
 from paper_2511_11641_amd import binding as B
 from paper_2511_11641_amd import synth
-from util import assert_close, dev, host, pad_cols, pad_rows
+from util import assert_close, dev, host, interleave_rows, pad_cols, pad_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -267,3 +267,81 @@ def test_column_gather_of_an_odd_width_with_padded_rows(ctx, n, k, dtype):
     ctx.ecospa_scatter(got, torch.from_numpy(idx).cuda(), 1, 1, n, kp=kp, out=back[:, :n])
     assert np.array_equal(host(back[:, :n]), O.scatter(O.compact(w, idx, 1, n), idx, 1, n).astype(np.float64))
     assert bool((back[:, n:] == 3.0).all())          # the padding of the rows is not touched
+
+
+# ---- row gathers that write their transposed copy themselves, interleaved second source -------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("groups,n,unit,k,kp,other", [(1, 1024, 1, 512, 512, 256), (16, 64, 1, 19, 32, 1024),
+                                                      (32, 64, 2, 16, 16, 2048), (1, 5461, 1, 2730, 2736, 520),
+                                                      (3, 10, 1, 4, 4, 7), (2, 12, 2, 3, 5, 9), (1, 200, 1, 77, 80, 136)])
+def test_row_gather_with_transposed_copy(ctx, groups, n, unit, k, kp, other, dtype):
+    nu = n // unit
+    sc = np.abs(synth.normal(17, 301, (groups, nu))).astype(np.float32)
+    idx_np = O.select_topk(sc, k)
+    idx = torch.from_numpy(idx_np).cuda()
+    src_np = synth.round_to(synth.normal(17, 302, (groups * n, other)), dtype)
+    src = dev(src_np, dtype)
+    want = pad_rows(O.compact(src_np, idx_np, 0, n, unit), groups, k * unit, kp * unit)
+    slots = groups * kp * unit
+    dst = torch.full((slots, other), 7.0, dtype=src.dtype, device="cuda")
+    # a transposed copy wider than the matrix (the columns of a larger buffer), the slots beside it untouched
+    dst_t_buf = torch.full((other, slots + 8), 7.0, dtype=src.dtype, device="cuda")
+    ctx.ecospa_compact_batch([ctx.map_item(src, dst, idx, 0, groups, n, unit, kp, dst_t=dst_t_buf[:, :slots])])
+    np.testing.assert_array_equal(host(dst), want)
+    np.testing.assert_array_equal(host(dst_t_buf[:, :slots]), want.T)
+    assert bool((dst_t_buf[:, slots:] == 7.0).all())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n,k,kp,other,with_t", [(1024, 512, 512, 256, True), (5461, 2730, 2736, 520, True),
+                                                 (37, 18, 32, 8, True), (37, 18, 32, 9, True), (200, 77, 80, 136, False)])
+def test_row_gather_of_two_interleaved_sources(ctx, n, k, kp, other, with_t, dtype):
+    """(gate, up) row pairs of a gated FFN's first matrix out of W_gate and W_up in one copy."""
+    sc = np.abs(synth.normal(19, 401, (1, n))).astype(np.float32)
+    idx_np = O.select_topk(sc, k)
+    idx = torch.from_numpy(idx_np).cuda()
+    a_np = synth.round_to(synth.normal(19, 402, (n, other)), dtype)
+    b_np = synth.round_to(synth.normal(19, 403, (n, other)), dtype)
+    a, b = dev(a_np, dtype), dev(b_np, dtype)
+    want = interleave_rows(pad_rows(O.compact(a_np, idx_np, 0, n, 1), 1, k, kp), pad_rows(O.compact(b_np, idx_np, 0, n, 1), 1, k, kp))
+    dst = torch.full((2 * kp, other), 7.0, dtype=a.dtype, device="cuda")
+    dst_t = torch.full((other, 2 * kp), 7.0, dtype=a.dtype, device="cuda") if with_t else None
+    ctx.ecospa_compact_batch([ctx.map_item(a, dst, idx, 0, 1, n, 1, kp, dst_t=dst_t, src_b=b)])
+    np.testing.assert_array_equal(host(dst), want)
+    if with_t:
+        np.testing.assert_array_equal(host(dst_t), want.T)
+
+
+def test_row_gather_with_transposed_copy_ragged_counts_and_shared_lists(ctx):
+    """Per-group kept counts from device memory and heads that share an index list (Eq. 5), transposed copy included."""
+    groups, n, kp, other, div = 8, 64, 32, 200, 2
+    rng = np.random.default_rng(5)
+    kg = rng.integers(0, kp + 1, size=groups // div).astype(np.int32)
+    idx_np = np.full((groups // div, n), -1, dtype=np.int32)
+    for g in range(groups // div):
+        idx_np[g, :kg[g]] = np.sort(rng.choice(n, size=kg[g], replace=False))
+    src_np = synth.round_to(synth.normal(21, 1, (groups * n, other)), "bf16")
+    want = np.zeros((groups * kp, other))
+    for g in range(groups):
+        rows = idx_np[g // div, :kg[g // div]]
+        want[g * kp:g * kp + len(rows)] = src_np[g * n + rows]
+    src = dev(src_np, "bf16")
+    dst = torch.empty((groups * kp, other), dtype=torch.bfloat16, device="cuda")
+    dst_t = torch.empty((other, groups * kp), dtype=torch.bfloat16, device="cuda")
+    ctx.ecospa_compact_batch([ctx.map_item(src, dst, torch.from_numpy(idx_np).cuda(), 0, groups, n, 1, kp,
+                                           k_group=torch.from_numpy(kg).cuda(), idx_div=div, dst_t=dst_t)])
+    np.testing.assert_array_equal(host(dst), want)
+    np.testing.assert_array_equal(host(dst_t), want.T)
+
+
+def test_transposed_copy_only_with_row_gathers(ctx):
+    src = torch.zeros((64, 16), device="cuda")
+    idx = torch.arange(8, dtype=torch.int32, device="cuda").view(1, 8)
+    dst_t = torch.zeros((64, 8), device="cuda")
+    for axis, scatter in ((1, 0), (0, 1)):
+        dst = torch.zeros((64, 8) if axis == 1 else (64, 16), device="cuda")
+        item = ctx.map_item(dst if scatter else src, src if scatter else dst, idx, axis, 1, 64 if scatter or axis == 0 else 16, 1, 8,
+                            scatter=scatter, dst_t=dst_t)
+        with pytest.raises(B.EcospaError) as e:
+            ctx.ecospa_compact_batch([item])
+        assert e.value.code == B.ERR_SHAPE
