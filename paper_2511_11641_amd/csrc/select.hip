@@ -11,6 +11,8 @@
 
 #include "select_dev.h"
 
+#define SELECT_CACHE 8          // scores a thread of the threshold kernel keeps in registers
+
 __global__ __launch_bounds__(SELECT_THREADS) void select_topk_kernel(const SelectBatch b) {
   __shared__ SelectShared sh;
   int item = 0, hi = b.n_items - 1;       // last item whose first block is <= blockIdx.x

@@ -4,7 +4,6 @@
 #include "common.h"
 
 #define SELECT_THREADS 1024
-#define SELECT_CACHE 8          // score keys a thread keeps in registers
 #define SELECT_MAX_ITEMS 96    // descriptors travel as kernel arguments
 
 struct SelectItemDev {
@@ -69,50 +68,30 @@ struct SelectShared {
   int s_krem;
 };
 #define ITEM_KEY(x) (score_key(x) ^ flip)
-// The work of workgroup number `blk` of item t (all SELECT_THREADS threads of the workgroup call it).
-__device__ __forceinline__ void select_item_block(const SelectItemDev& t, int blk, SelectShared& sh) {
+// A group of more than 64 units by one workgroup.  CACHE: score keys a thread keeps in registers (its contiguous run of
+// indices is read once for all passes); 0: longer runs are read again in every pass.
+template <int CACHE>
+__device__ __forceinline__ void select_large_group(const SelectItemDev& t, int blk, SelectShared& sh) {
   auto& whist = sh.whist;
   auto& wave_tot = sh.wave_tot;
   uint32_t& s_prefix = sh.s_prefix;
   int& s_krem = sh.s_krem;
   const int tid = threadIdx.x, wave = tid >> 6;
   const uint32_t flip = t.smallest ? 0xffffffffu : 0u;
-  if (t.n <= 64) {
-    // Small groups (the units of one head): a wavefront ranks a group by direct comparison - the rank of
-    // a unit is the number of units that come before it in the order (larger key, or equal key and lower
-    // index) - and the lanes whose rank is below k write their indices, ascending.  One group per wavefront.
-    const int g = blk * (SELECT_THREADS / 64) + wave;
-    if (g >= t.groups) return;
-    const int lane = tid & 63, n = t.n;
-    const int k = t.k_dev ? t.k_dev[g] : t.k;
-    const uint32_t key = lane < n ? ITEM_KEY(t.scores[static_cast<long long>(g) * n + lane]) : 0u;
-    int rank = 0;
-    for (int j = 0; j < n; ++j) {
-      const uint32_t kj = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(key), j));   // j is uniform: no LDS crossbar
-      rank += (kj > key) || (kj == key && j < lane);
-    }
-    const bool take = lane < n && rank < k;
-    const unsigned long long mask = __ballot(take);
-    int* out = t.idx + static_cast<long long>(g) * (t.k_dev ? t.ld_idx : k);
-    if (take) out[__popcll(mask & ((1ull << lane) - 1ull))] = lane;
-    if (t.k_dev)
-      for (int i = k + lane; i < t.ld_idx; i += 64) out[i] = -1;
-    return;
-  }
+  constexpr bool cached = CACHE > 0;
+  constexpr int NC = CACHE > 0 ? CACHE : 1;
   const int n = t.n, g = blk;
   const int k = t.k_dev ? t.k_dev[g] : t.k;
   const float* s = t.scores + static_cast<long long>(g) * n;
   int* out = t.idx + static_cast<long long>(g) * (t.k_dev ? t.ld_idx : k);
 
-  // this thread's contiguous run of indices; runs of up to SELECT_CACHE elements (groups of up to
-  // SELECT_THREADS * SELECT_CACHE units) are read once and kept in registers for all passes
+  // this thread's contiguous run of indices
   const int per = (n + SELECT_THREADS - 1) / SELECT_THREADS;
   const int i0 = min(tid * per, n), i1 = min(i0 + per, n);
-  const bool cached = per <= SELECT_CACHE;
-  uint32_t kc[SELECT_CACHE];
+  uint32_t kc[NC];
   if (cached) {
 #pragma unroll
-    for (int j = 0; j < SELECT_CACHE; ++j) kc[j] = i0 + j < i1 ? ITEM_KEY(s[i0 + j]) : 0u;
+    for (int j = 0; j < NC; ++j) kc[j] = i0 + j < i1 ? ITEM_KEY(s[i0 + j]) : 0u;
   }
 
   uint32_t prefix = 0u;   // high bits of the k-th largest key found so far
@@ -124,7 +103,7 @@ __device__ __forceinline__ void select_item_block(const SelectItemDev& t, int bl
     const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
     if (cached) {
 #pragma unroll
-      for (int j = 0; j < SELECT_CACHE; ++j)
+      for (int j = 0; j < NC; ++j)
         if (i0 + j < i1 && (kc[j] & hi_mask) == prefix) atomicAdd(&whist[wave][(kc[j] >> shift) & 255u], 1);
     } else {
       for (int i = i0; i < i1; ++i) {
@@ -162,7 +141,7 @@ __device__ __forceinline__ void select_item_block(const SelectItemDev& t, int bl
   int n_eq = 0, n_gt = 0;
   if (cached) {
 #pragma unroll
-    for (int j = 0; j < SELECT_CACHE; ++j)
+    for (int j = 0; j < NC; ++j)
       if (i0 + j < i1) { n_eq += kc[j] == T; n_gt += kc[j] > T; }
   } else {
     for (int i = i0; i < i1; ++i) {
@@ -178,7 +157,7 @@ __device__ __forceinline__ void select_item_block(const SelectItemDev& t, int bl
   int pos = gt_before + min(eq_before, krem);
   if (cached) {
 #pragma unroll
-    for (int j = 0; j < SELECT_CACHE; ++j) {
+    for (int j = 0; j < NC; ++j) {
       if (i0 + j >= i1) continue;
       bool take = kc[j] > T;
       if (kc[j] == T && eq_left > 0) { take = true; --eq_left; }
@@ -194,6 +173,39 @@ __device__ __forceinline__ void select_item_block(const SelectItemDev& t, int bl
   }
   if (t.k_dev)
     for (int i = k + tid; i < t.ld_idx; i += SELECT_THREADS) out[i] = -1;
+}
+
+// The work of workgroup number `blk` of item t (all SELECT_THREADS threads of the workgroup call it).
+__device__ __forceinline__ void select_item_block(const SelectItemDev& t, int blk, SelectShared& sh) {
+  const int tid = threadIdx.x, wave = tid >> 6;
+  const uint32_t flip = t.smallest ? 0xffffffffu : 0u;
+  if (t.n <= 64) {
+    // Small groups (the units of one head): a wavefront ranks a group by direct comparison - the rank of
+    // a unit is the number of units that come before it in the order (larger key, or equal key and lower
+    // index) - and the lanes whose rank is below k write their indices, ascending.  One group per wavefront.
+    const int g = blk * (SELECT_THREADS / 64) + wave;
+    if (g >= t.groups) return;
+    const int lane = tid & 63, n = t.n;
+    const int k = t.k_dev ? t.k_dev[g] : t.k;
+    const uint32_t key = lane < n ? ITEM_KEY(t.scores[static_cast<long long>(g) * n + lane]) : 0u;
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+      const uint32_t kj = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(key), j));   // j is uniform: no LDS crossbar
+      rank += (kj > key) || (kj == key && j < lane);
+    }
+    const bool take = lane < n && rank < k;
+    const unsigned long long mask = __ballot(take);
+    int* out = t.idx + static_cast<long long>(g) * (t.k_dev ? t.ld_idx : k);
+    if (take) out[__popcll(mask & ((1ull << lane) - 1ull))] = lane;
+    if (t.k_dev)
+      for (int i = k + lane; i < t.ld_idx; i += 64) out[i] = -1;
+    return;
+  }
+  // runs of up to 8 units per thread (groups of up to 8192) or of up to 32 (32768) stay in registers
+  const int per = (t.n + SELECT_THREADS - 1) / SELECT_THREADS;
+  if (per <= 8) select_large_group<8>(t, blk, sh);
+  else if (per <= 32) select_large_group<32>(t, blk, sh);
+  else select_large_group<0>(t, blk, sh);
 }
 
 #undef ITEM_KEY
