@@ -156,42 +156,22 @@ __device__ __forceinline__ bf16x8_t acc_to_frag(const floatx16& a, int half) {
   return __builtin_convertvector(f, bf16x8_t);
 }
 
-// A thread's 4-token x 8-dim piece ("sub-block") of a [64 tokens][D dims] tile lives in four
-// 16-byte registers: one load per token.  A tile has 16 * D/8 sub-blocks.
+// The MFMA fragments of a lane's own row of a row-major matrix, straight from memory: fragment s of lane (l32, hh) is
+// the 16-byte chunk 2s + hh of row l32 of the wavefront's 32 rows - what frag_nat() would read from an LDS copy of
+// the tile, without the copy and its barrier.  Unconditional loads from clamped (always valid) addresses; rows beyond
+// the sequence end (`row_ok` false; `row` is then any valid row) and dims beyond the kept width come out as zeros.
 template <int D>
-__device__ __forceinline__ void sub_load(u32x4 (&v)[4], const bf16_t* __restrict__ base, long long ld, long long row0,
-                                         int rows_valid, int kp, int sub) {
-  // Unconditional loads from clamped (always valid) addresses; what lies outside the tile is zeroed
-  // by sub_mask() just before the registers go to LDS, so that nothing waits for the loads here.
-  // row0 + rows_valid - 1 is the last token of the sequence whatever the tile, so the clamp is safe
-  // even for tiles that start beyond the sequence end.
-  const int tblk = sub / (D / 8), dblk = sub % (D / 8);
-  const int dc = min(dblk * 8, kp - 8);
+__device__ __forceinline__ void own_row_load(u32x4 (&v)[D / 16], const bf16_t* __restrict__ base, long long ld, long long row,
+                                             int kp, int hh) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = tblk * 4 + i;
-    v[i] = *reinterpret_cast<const u32x4*>(base + (row0 + min(r, rows_valid - 1)) * ld + dc);
-  }
-}
-// Zero the rows beyond the sequence end and the dims beyond the kept width (same arguments as the
-// sub_load() that filled v); a tile that lies fully inside skips the selects (uniform branch).
-template <int D>
-__device__ __forceinline__ void sub_mask(u32x4 (&v)[4], int rows_valid, int kp, int sub) {
-  if (rows_valid >= 64 && kp >= D) return;
-  const int tblk = sub / (D / 8), dblk = sub % (D / 8);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = tblk * 4 + i;
-    v[i] = (r < rows_valid && dblk * 8 < kp) ? v[i] : u32x4{0u, 0u, 0u, 0u};
-  }
+  for (int s = 0; s < D / 16; ++s) v[s] = *reinterpret_cast<const u32x4*>(base + row * ld + min(16 * s + 8 * hh, kp - 8));
 }
 template <int D>
-__device__ __forceinline__ void sub_store_nat(const u32x4 (&v)[4], bf16_t* tile, int sub) {
-  const int tblk = sub / (D / 8), dblk = sub % (D / 8);
+__device__ __forceinline__ void own_row_frags(bf16x8_t (&f)[D / 16], const u32x4 (&v)[D / 16], bool row_ok, int kp, int hh) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(tile + nat_off<D>(tblk * 4 + i, dblk)) = v[i];
+  for (int s = 0; s < D / 16; ++s)
+    f[s] = __builtin_bit_cast(bf16x8_t, (row_ok && 16 * s + 8 * hh < kp) ? v[s] : u32x4{0u, 0u, 0u, 0u});
 }
-#define SUBS(D) (16 * ((D) / 8))
 
 // Write a [ROWS][D] natural LDS tile to global rows row0.. (only rows < rows_valid, dims < kp).
 template <int D>
@@ -289,7 +269,7 @@ void attn_fwd_kernel(const AttnArgs a) {
   // object it touches and then holds each read of a stream buffer back until the direct loads into the
   // other half of that buffer have landed.
   __shared__ __attribute__((aligned(16))) bf16_t lds_all[128 * DMAX + 2 * 64 * DQ + 2 * 64 * DV];
-  bf16_t* const Qs = lds_all;                                      // Q tile, later the O staging tile
+  bf16_t* const Qs = lds_all;                                      // O staging tile
   bf16_t* const Ks0 = Qs + 128 * DMAX;        // [2][64 * DQ]
   bf16_t* const Vs0 = Ks0 + 2 * 64 * DQ;      // [2][64 * DV]
 #define Ks(buf) (Ks0 + (buf) * (64 * DQ))
@@ -300,7 +280,6 @@ void attn_fwd_kernel(const AttnArgs a) {
   const int q0 = qt * 128;
   const long long tok0 = static_cast<long long>(b) * a.L;
   const bf16_t* Qg = a.qkv + head * a.kp_qk;
-  const int half = tid >> 7, sub = tid & 127;
 
   // key/value tiles stream straight into LDS, one tile ahead of the one being used
   TileStream<DQ> ks;
@@ -310,19 +289,16 @@ void attn_fwd_kernel(const AttnArgs a) {
   ks.issue(Ks(0), tok0, a.L);
   vs.issue(Vs(0), tok0, a.L);
 
-  // Q tile: two 64-row halves, one per half of the workgroup (rows and dims outside are zeroed)
-  if (sub < SUBS(DQ)) {
-    u32x4 pre[4];
-    sub_load<DQ>(pre, Qg, a.ld_qkv, tok0 + q0 + half * 64, a.L - q0 - half * 64, a.kp_qk, sub);
-    sub_mask<DQ>(pre, a.L - q0 - half * 64, a.kp_qk, sub);
-    sub_store_nat<DQ>(pre, Qs + half * 64 * DQ, sub);
-  }
+  // Q: every lane takes the fragments of its own query row straight from memory (rows and dims outside are zeroed)
   const int kv_end = a.causal ? min(a.L, q0 + 128) : a.L;
   const int n_kv = (kv_end + 63) / 64;
-  __syncthreads();
   bf16x8_t qf[DQ / 16];
-#pragma unroll
-  for (int s = 0; s < DQ / 16; ++s) qf[s] = frag_nat<DQ>(Qs, wave * 32 + l32, s, hh);
+  {
+    const int qrow = q0 + wave * 32 + l32;
+    u32x4 qraw[DQ / 16];
+    own_row_load<DQ>(qraw, Qg, a.ld_qkv, tok0 + min(qrow, a.L - 1), a.kp_qk, hh);
+    own_row_frags<DQ>(qf, qraw, qrow < a.L, a.kp_qk, hh);
+  }
 
   // oacc: O^T (dims x queries); lacc: the softmax denominators, accumulated by the matrix unit from
   // the same rounded probabilities as the numerator (an all-ones operand in place of V^T, so every
@@ -418,7 +394,7 @@ void attn_fwd_kernel(const AttnArgs a) {
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   if (hh == 0 && q_idx < a.L)
     a.lse[(static_cast<long long>(b) * a.h + head) * a.L + q_idx] = (m_run * sc + __log2f(l_tot)) * LN2;
-  // O staging (the Q fragments live in registers, so the Q tile can be overwritten)
+  // O staging
 #pragma unroll
   for (int u = 0; u < DV / 32; ++u) acc_to_tile<DV>(Qs, wave * 32 + l32, u, oacc[u], inv, hh);
   __syncthreads();
@@ -436,7 +412,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ
 void attn_bwd_dq_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
   __shared__ __attribute__((aligned(16))) bf16_t lds_all[128 * DMAX + 2 * 64 * DQ + 2 * 64 * DV];   // one object: see attn_fwd_kernel
-  bf16_t* const Qs = lds_all;                                      // Q tile, then dO tile, then dQ staging
+  bf16_t* const Qs = lds_all;                                      // dQ staging tile
   bf16_t* const Ks0 = Qs + 128 * DMAX;        // [2][64 * DQ]
   bf16_t* const Vs0 = Ks0 + 2 * 64 * DQ;      // [2][64 * DV]
 #define Ks(buf) (Ks0 + (buf) * (64 * DQ))
@@ -448,7 +424,6 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
   const long long tok0 = static_cast<long long>(b) * a.L;
   const bf16_t* Qg = a.qkv + head * a.kp_qk;
   const bf16_t* dOg = a.d_o + head * a.kp_vo;
-  const int half = tid >> 7, sub = tid & 127;
 
   // key/value tiles stream straight into LDS, one tile ahead of the one being used
   TileStream<DQ> ks;
@@ -458,47 +433,34 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
   ks.issue(Ks(0), tok0, a.L);
   vs.issue(Vs(0), tok0, a.L);
 
-  bf16x8_t qf[DQ / 16], dof[DV / 16];
-  {
-    u32x4 pre[4];
-    if (sub < SUBS(DQ)) {
-      sub_load<DQ>(pre, Qg, a.ld_qkv, tok0 + q0 + half * 64, a.L - q0 - half * 64, a.kp_qk, sub);
-      sub_mask<DQ>(pre, a.L - q0 - half * 64, a.kp_qk, sub);
-      sub_store_nat<DQ>(pre, Qs + half * 64 * DQ, sub);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int s = 0; s < DQ / 16; ++s) qf[s] = frag_nat<DQ>(Qs, wave * 32 + l32, s, hh);
-    __syncthreads();
-    if (sub < SUBS(DV)) {
-      sub_load<DV>(pre, dOg, a.ld_o, tok0 + q0 + half * 64, a.L - q0 - half * 64, a.kp_vo, sub);
-      sub_mask<DV>(pre, a.L - q0 - half * 64, a.kp_vo, sub);
-      sub_store_nat<DV>(pre, Qs + half * 64 * DV, sub);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int s = 0; s < DV / 16; ++s) dof[s] = frag_nat<DV>(Qs, wave * 32 + l32, s, hh);
-  }
+  // Nothing of the prologue goes through LDS: every lane takes the fragments of its own query row of Q and of dO, its
+  // pieces of the O row and the row's log-sum-exp straight from memory, all requested before the first wait.
   const int qw0 = q0 + wave * 32, q_idx = qw0 + l32;
   const long long stat = (static_cast<long long>(b) * a.h + head) * a.L;
-  const float lse2 = q_idx < a.L ? a.lse[stat + q_idx] * LOG2E : 0.f;
-  // delta = rowsum(dO * O) of this lane's query: the lane holds its half of the dO row as MFMA fragments and fetches the
-  // matching pieces of the O row; the other half sits in lane ^ 32.  The kernel over key tiles reads the sums from memory.
+  const long long qrow = tok0 + min(q_idx, a.L - 1);
+  bf16x8_t qf[DQ / 16], dof[DV / 16];
+  u32x4 qraw[DQ / 16], doraw[DV / 16], ov[DV / 16];
+  own_row_load<DQ>(qraw, Qg, a.ld_qkv, qrow, a.kp_qk, hh);
+  own_row_load<DV>(doraw, dOg, a.ld_o, qrow, a.kp_vo, hh);
+  own_row_load<DV>(ov, a.o + head * a.kp_vo, a.ld_o, qrow, a.kp_vo, hh);
+  const float lse_raw = a.lse[stat + min(q_idx, a.L - 1)];
+  own_row_frags<DQ>(qf, qraw, q_idx < a.L, a.kp_qk, hh);
+  own_row_frags<DV>(dof, doraw, q_idx < a.L, a.kp_vo, hh);
+  const float lse2 = q_idx < a.L ? lse_raw * LOG2E : 0.f;
+  // delta = rowsum(dO * O) of this lane's query from its half of the two rows; the other half sits in lane ^ 32.  The
+  // kernel over key tiles reads the sums from memory.  (dO is zero beyond the kept width, so O's stand-in there drops out.)
   float dlt = 0.f;
   {
-    const bf16_t* orow = a.o + (tok0 + min(q_idx, a.L - 1)) * a.ld_o + head * a.kp_vo;
 #pragma unroll
     for (int s = 0; s < DV / 16; ++s) {
-      const int dim = 16 * s + 8 * hh;
-      const u32x4 ov = *reinterpret_cast<const u32x4*>(orow + min(dim, a.kp_vo - 8));
       const u32x4 gv = __builtin_bit_cast(u32x4, dof[s]);
       float part = 0.f;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        part += __uint_as_float(ov[i] << 16) * __uint_as_float(gv[i] << 16);
-        part += __uint_as_float(ov[i] & 0xffff0000u) * __uint_as_float(gv[i] & 0xffff0000u);
+        part += __uint_as_float(ov[s][i] << 16) * __uint_as_float(gv[i] << 16);
+        part += __uint_as_float(ov[s][i] & 0xffff0000u) * __uint_as_float(gv[i] & 0xffff0000u);
       }
-      dlt += dim < a.kp_vo ? part : 0.f;       // dims beyond the kept width: dO was zeroed there, O's stand-in is dropped
+      dlt += 16 * s + 8 * hh < a.kp_vo ? part : 0.f;
     }
     dlt += __shfl_xor(dlt, 32, 64);
     if (hh == 0 && q_idx < a.L) a.delta[stat + q_idx] = dlt;
@@ -584,7 +546,7 @@ template <int DQ, int DV>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ, DV, 3), ATTN_WPE(DQ, DV, 3)))) void attn_bwd_dkdv_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
   __shared__ __attribute__((aligned(16))) bf16_t lds_all[128 * DMAX + 2 * 64 * DQ + 2 * 64 * DV + 512];   // one object: see attn_fwd_kernel
-  bf16_t* const KVs = lds_all;                                     // K tile, V tile, then output staging
+  bf16_t* const KVs = lds_all;                                     // output staging tile
   bf16_t* const Qs0 = KVs + 128 * DMAX;       // [2][64 * DQ]
   bf16_t* const dOs0 = Qs0 + 2 * 64 * DQ;     // [2][64 * DV]
   float* const stats = reinterpret_cast<float*>(dOs0 + 2 * 64 * DV);   // [2][64] log-sum-exp, [2][64] delta
@@ -601,28 +563,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ
   const long long tok0 = static_cast<long long>(b) * a.L;
   const bf16_t* Kg = a.qkv + k_col(a, kvh);
   const bf16_t* Vg = a.qkv + v_col(a, kvh);
-  const int half = tid >> 7, sub = tid & 127;
 
+  // every lane takes the fragments of its own key row of K and of V straight from memory (nothing through LDS)
   bf16x8_t kf[DQ / 16], vf[DV / 16];
-  u32x4 pre[4];
   {
-    if (sub < SUBS(DQ)) {
-      sub_load<DQ>(pre, Kg, a.ld_qkv, tok0 + k0 + half * 64, a.L - k0 - half * 64, a.kp_qk, sub);
-      sub_mask<DQ>(pre, a.L - k0 - half * 64, a.kp_qk, sub);
-      sub_store_nat<DQ>(pre, KVs + half * 64 * DQ, sub);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int s = 0; s < DQ / 16; ++s) kf[s] = frag_nat<DQ>(KVs, wave * 32 + l32, s, hh);
-    __syncthreads();
-    if (sub < SUBS(DV)) {
-      sub_load<DV>(pre, Vg, a.ld_qkv, tok0 + k0 + half * 64, a.L - k0 - half * 64, a.kp_vo, sub);
-      sub_mask<DV>(pre, a.L - k0 - half * 64, a.kp_vo, sub);
-      sub_store_nat<DV>(pre, KVs + half * 64 * DV, sub);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int s = 0; s < DV / 16; ++s) vf[s] = frag_nat<DV>(KVs, wave * 32 + l32, s, hh);
+    const int krow = k0 + wave * 32 + l32;
+    u32x4 kraw[DQ / 16], vraw[DV / 16];
+    own_row_load<DQ>(kraw, Kg, a.ld_qkv, tok0 + min(krow, a.L - 1), a.kp_qk, hh);
+    own_row_load<DV>(vraw, Vg, a.ld_qkv, tok0 + min(krow, a.L - 1), a.kp_vo, hh);
+    own_row_frags<DQ>(kf, kraw, krow < a.L, a.kp_qk, hh);
+    own_row_frags<DV>(vf, vraw, krow < a.L, a.kp_vo, hh);
   }
   const int kw0 = k0 + wave * 32, key_idx = kw0 + l32;
   const float sc = a.scale * LOG2E;
