@@ -315,7 +315,7 @@ def fp32_pair_workload(ctx, steps):
             "tokens_per_s": T / (ms * 1e-3), "note": "0.8 GFLOP in ten short launches on the vector ALU: latency-bound, reported as a time only"}
 
 
-def layer_workload(ctx, name, steps, warmup, h_kv=None, detail=True):
+def layer_workload(ctx, name, steps, warmup, h_kv=None, detail=True, keep=(1, 2)):
     """One layer configuration through the whole path: the timed sparse step at 50 % keep (`ms_per_step`), its parts,
     fwd+bwd alone, the dense layer (same library at k = n), and - with detail - the contraction kernels' own launch
     times (HIP events on the library's stream around every launch, in steps run again after the timed region) and the
@@ -327,7 +327,7 @@ def layer_workload(ctx, name, steps, warmup, h_kv=None, detail=True):
         cfg["h_kv"] = h_kv
     Bsz, L, d, h, dh, dff = (cfg[k] for k in ("B", "L", "d", "h", "d_h", "d_ff"))
     T = Bsz * L
-    sp = Layer(ctx, cfg, cfg["seed"], 1, 2)
+    sp = Layer(ctx, cfg, cfg["seed"], keep[0], keep[1])
     ms_step = timed(torch, sp.step, steps, warmup)
     out = {"workload": name if h_kv is None else f"{name}, {h_kv} key/value heads", "batch": Bsz, "seq_len": L,
            "ms_per_step": ms_step, "tokens_per_s": T / (ms_step * 1e-3)}
@@ -769,6 +769,9 @@ def main():
     if not args.no_extras:
         out["fp32_pair"] = fp32_pair_workload(ctx, args.steps)
         out["gqa_layer"] = layer_workload(ctx, "c3_llama1b_layer", args.steps, args.warmup, h_kv=8, detail=False)
+        # the paper's larger pre-training shape (32 heads of 128 dims): dense and keep 3/4 run the 128-wide attention kernels
+        out["llama7b_layer"] = {f"keep_{n}_{m}": layer_workload(ctx, "llama7b_layer", 20, 3, detail=False, keep=(n, m))
+                                for n, m in ((1, 2), (3, 4))}
         out["inference"] = inference_sweep(ctx, SECOND, 20)
         out["torch_dense_fwd_bwd"] = torch_dense_layer(SECOND, 20)
         out.update(stack_workloads(ctx))

@@ -334,8 +334,8 @@ int ecospa_rope_table_ragged(ecospa_ctx* ctx, const int* idx, int ld_idx, const 
  * Compact layouts (padding slots hold zeros, so results are exact):
  *   ATTN: w_qkv [((h + h_kv)*kp_qk + h_kv*kp_vo), d_model]: rows of W_q (head-major, kp_qk per head), then
  *         W_k, then W_v (kp_vo per head); b_qkv same length or NULL; w_o [d_model, h*kp_vo]; b_o.
- *         kp_qk, kp_vo are multiples of 16 and at most 64 (wider heads -> ERR_SHAPE, before anything is
- *         launched).  h_kv = key/value heads: h for multi-head
+ *         kp_qk, kp_vo are multiples of 16 and at most 128 (wider heads -> ERR_SHAPE, before anything is
+ *         launched; the attention core runs a head in a 32-, 64- or 128-wide kernel, whichever holds it).  h_kv = key/value heads: h for multi-head
  *         attention (0 means h); under grouped-query attention (Eq. 5) h_kv divides h and query head i
  *         attends with key/value head i / (h / h_kv).
  *   FFN:  w_1 [kp_ff, d_model] (SWIGLU: [2*kp_ff, d_model], row 2i = gate unit i, row 2i+1 = up unit i, so that a

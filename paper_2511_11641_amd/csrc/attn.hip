@@ -256,7 +256,7 @@ __device__ __forceinline__ void attn_work_item(const AttnArgs& a, int heads, int
 
 // Wavefronts per SIMD the register allocation aims at: the narrow (32, 32) heads of a half-kept
 // layer need few registers, and more resident workgroups hide their barrier and LDS latencies.
-#define ATTN_WPE(DQ, DV, narrow) ((DQ) + (DV) <= 64 ? (narrow) : 2)
+#define ATTN_WPE(DQ, DV, narrow) ((DQ) + (DV) <= 64 ? (narrow) : ((DQ) > 64 || (DV) > 64 ? 1 : 2))
 
 // ---------------------------------------------------------------------------------------------
 // forward: one workgroup per (128 queries, head, batch); 4 wavefronts x 32 queries
@@ -268,7 +268,7 @@ void attn_fwd_kernel(const AttnArgs a) {
   // One LDS object per kernel, carved by hand: with several, the compiler tags every LDS access with the
   // object it touches and then holds each read of a stream buffer back until the direct loads into the
   // other half of that buffer have landed.
-  __shared__ __attribute__((aligned(16))) bf16_t lds_all[128 * DMAX + 2 * 64 * DQ + 2 * 64 * DV];
+  extern __shared__ __attribute__((aligned(16))) bf16_t lds_all[];     // attn_lds_bytes<DQ, DV>(0)
   bf16_t* const Qs = lds_all;                                      // O staging tile
   bf16_t* const Ks0 = Qs + 128 * DMAX;        // [2][64 * DQ]
   bf16_t* const Vs0 = Ks0 + 2 * 64 * DQ;      // [2][64 * DV]
@@ -411,7 +411,7 @@ template <int DQ, int DV>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ, DV, 4), ATTN_WPE(DQ, DV, 4))))
 void attn_bwd_dq_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
-  __shared__ __attribute__((aligned(16))) bf16_t lds_all[128 * DMAX + 2 * 64 * DQ + 2 * 64 * DV];   // one object: see attn_fwd_kernel
+  extern __shared__ __attribute__((aligned(16))) bf16_t lds_all[];     // one object: see attn_fwd_kernel; attn_lds_bytes<DQ, DV>(1)
   bf16_t* const Qs = lds_all;                                      // dQ staging tile
   bf16_t* const Ks0 = Qs + 128 * DMAX;        // [2][64 * DQ]
   bf16_t* const Vs0 = Ks0 + 2 * 64 * DQ;      // [2][64 * DV]
@@ -545,7 +545,7 @@ void attn_bwd_dq_kernel(const AttnArgs a) {
 template <int DQ, int DV>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ, DV, 3), ATTN_WPE(DQ, DV, 3)))) void attn_bwd_dkdv_kernel(const AttnArgs a) {
   constexpr int DMAX = DQ > DV ? DQ : DV;
-  __shared__ __attribute__((aligned(16))) bf16_t lds_all[128 * DMAX + 2 * 64 * DQ + 2 * 64 * DV + 512];   // one object: see attn_fwd_kernel
+  extern __shared__ __attribute__((aligned(16))) bf16_t lds_all[];     // one object: see attn_fwd_kernel; attn_lds_bytes<DQ, DV>(2)
   bf16_t* const KVs = lds_all;                                     // output staging tile
   bf16_t* const Qs0 = KVs + 128 * DMAX;       // [2][64 * DQ]
   bf16_t* const dOs0 = Qs0 + 2 * 64 * DQ;     // [2][64 * DV]
@@ -701,7 +701,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-static int pad32(int kp) { return (kp + 31) / 32 * 32; }
 
 // The head-width combinations that are built, instantiated explicitly (left to implicit instantiation
 // from the launch code, the host side of this compiler can drop some of the kernel stubs).
@@ -713,24 +712,52 @@ ATTN_INSTANTIATE(32, 32)
 ATTN_INSTANTIATE(32, 64)
 ATTN_INSTANTIATE(64, 32)
 ATTN_INSTANTIATE(64, 64)
+ATTN_INSTANTIATE(32, 128)
+ATTN_INSTANTIATE(64, 128)
+ATTN_INSTANTIATE(128, 32)
+ATTN_INSTANTIATE(128, 64)
+ATTN_INSTANTIATE(128, 128)
 #undef ATTN_INSTANTIATE
 
+// LDS of a kernel (which: 0 forward, 1 dQ, 2 dK/dV): the staging tile, the two double-buffered stream tiles, and for
+// dK/dV the row statistics of two query tiles.
 template <int DQ, int DV>
-static void launch_core(int which, const AttnArgs& a, hipStream_t st) {
+static constexpr int attn_lds_bytes(int which) {
+  return (128 * (DQ > DV ? DQ : DV) + 2 * 64 * DQ + 2 * 64 * DV + (which == 2 ? 512 : 0)) * 2;
+}
+
+template <int DQ, int DV>
+static hipError_t launch_core(int which, const AttnArgs& a, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((a.L + 127) / 128);
   const dim3 grid(tiles * a.h * a.B), grid_kv(tiles * a.h_kv * a.B);
-  if (which == 0) hipLaunchKernelGGL((attn_fwd_kernel<DQ, DV>), grid, dim3(256), 0, st, a);
-  else if (which == 1) hipLaunchKernelGGL((attn_bwd_dq_kernel<DQ, DV>), grid, dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<DQ, DV>), grid_kv, dim3(256), 0, st, a);
+  const int lds = attn_lds_bytes<DQ, DV>(which);
+#define ATTN_LAUNCH(kern, g)                                                                      \
+  do {                                                                                            \
+    static LdsAttrOnce attr_once;                                                                 \
+    if (lds > 64 * 1024) {                                                                        \
+      const hipError_t e = attr_once.ensure(reinterpret_cast<const void*>(kern), lds);            \
+      if (e != hipSuccess) return e;                                                              \
+    }                                                                                             \
+    hipLaunchKernelGGL(kern, g, dim3(256), lds, st, a);                                           \
+  } while (0)
+  if (which == 0) ATTN_LAUNCH((attn_fwd_kernel<DQ, DV>), grid);
+  else if (which == 1) ATTN_LAUNCH((attn_bwd_dq_kernel<DQ, DV>), grid);
+  else ATTN_LAUNCH((attn_bwd_dkdv_kernel<DQ, DV>), grid_kv);
+#undef ATTN_LAUNCH
+  return hipGetLastError();
 }
+// Kernel width of a padded head width: 32, 64 or 128 dims (a 96-wide head runs in the 128-wide kernel: the swizzle
+// of the LDS tiles wants a power of two).
+static int attn_width(int kp) { return kp <= 32 ? 32 : (kp <= 64 ? 64 : 128); }
 static int dispatch_core(ecospa_ctx* ctx, int which, const AttnArgs& a) {
-  const int dq = pad32(a.kp_qk), dv = pad32(a.kp_vo);
-  if (dq > 64 || dv > 64) return ECOSPA_ERR_SHAPE;   // head widths above 64 are not built
-  if (dq == 32 && dv == 32) launch_core<32, 32>(which, a, ctx->stream);
-  else if (dq == 32 && dv == 64) launch_core<32, 64>(which, a, ctx->stream);
-  else if (dq == 64 && dv == 32) launch_core<64, 32>(which, a, ctx->stream);
-  else launch_core<64, 64>(which, a, ctx->stream);
-  ECOSPA_CHECK_LAUNCH(ctx, "attention core kernel");
+  if (a.kp_qk > 128 || a.kp_vo > 128) return ECOSPA_ERR_SHAPE;   // rejected by the block validation before anything is launched
+  const int dq = attn_width(a.kp_qk), dv = attn_width(a.kp_vo);
+  hipError_t e = hipSuccess;
+#define ATTN_CASE(Q, V) if (dq == Q && dv == V) e = launch_core<Q, V>(which, a, ctx->stream);
+  ATTN_CASE(32, 32) else ATTN_CASE(32, 64) else ATTN_CASE(64, 32) else ATTN_CASE(64, 64)
+  else ATTN_CASE(32, 128) else ATTN_CASE(64, 128) else ATTN_CASE(128, 32) else ATTN_CASE(128, 64) else ATTN_CASE(128, 128)
+#undef ATTN_CASE
+  if (e != hipSuccess) return hip_fail(ctx, e, "attention core kernel");
   return ECOSPA_OK;
 }
 

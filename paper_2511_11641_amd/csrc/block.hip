@@ -24,8 +24,8 @@ static int validate_block(const ecospa_block_desc* dp) {
     if ((d.w_1_t && d.ld_w1t < nh) || (d.w_2_t && d.ld_w2t < d.d_model)) return ECOSPA_ERR_SHAPE;
     if ((d.w_1_t && (d.ld_w1t % 8 || !aligned16(d.w_1_t))) || (d.w_2_t && (d.ld_w2t % 8 || !aligned16(d.w_2_t)))) return ECOSPA_ERR_ALIGN;
   } else {
-    // head widths: multiples of 16 up to 64 (the attention core is built for 32- and 64-wide padded heads)
-    if (d.h < 1 || d.kp_qk < 16 || d.kp_vo < 16 || d.kp_qk % 16 || d.kp_vo % 16 || d.kp_qk > 64 || d.kp_vo > 64)
+    // head widths: multiples of 16 up to 128 (the attention core is built for 32-, 64- and 128-wide padded heads)
+    if (d.h < 1 || d.kp_qk < 16 || d.kp_vo < 16 || d.kp_qk % 16 || d.kp_vo % 16 || d.kp_qk > 128 || d.kp_vo > 128)
       return ECOSPA_ERR_SHAPE;
     if (d.h_kv < 0 || d.h % attn_h_kv(d)) return ECOSPA_ERR_SHAPE;
     if (!d.w_qkv || !d.w_o) return ECOSPA_ERR_NULL;

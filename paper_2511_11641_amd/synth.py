@@ -160,4 +160,8 @@ CONFIGS = {
     # LLaMA-1B-shaped layer, bf16
     "c3_llama1b_layer": dict(kind="layer", seed=2, B=16, L=256, d=2048, h=32, d_h=64, d_ff=5461,
                              gated=True, dtype="bf16", act="swiglu", rope=True, bias=False),
+    # LLaMA-7B-shaped layer (the paper's second pre-training model: 32 heads of 128 dims), bf16; not one of the metric's
+    # configurations - the shape whose dense form and keep ratios above 1/2 need the 128-wide attention kernels
+    "llama7b_layer": dict(kind="layer", seed=3, B=4, L=512, d=4096, h=32, d_h=128, d_ff=11008,
+                          gated=True, dtype="bf16", act="swiglu", rope=True, bias=False),
 }

@@ -146,14 +146,14 @@ def test_block_validation(lib, ctx):
     assert lib.ecospa_set_workspace(ctx, 257, 1024) == B.ERR_ALIGN
 
 
-def test_attention_heads_wider_than_64_are_rejected_before_any_launch(lib, ctx):
-    """The attention core is built for padded head widths up to 64: a wider head is a validation error of the
+def test_attention_heads_wider_than_128_are_rejected_before_any_launch(lib, ctx):
+    """The attention core is built for padded head widths up to 128: a wider head is a validation error of the
     descriptor itself (workspace query included), not something found after the projections have been launched."""
     a = B.BlockDesc()
     a.block, a.dtype, a.B, a.L, a.d_model = B.BLOCK_ATTN, B.BF16, 2, 16, 256
     a.h, a.kp_qk, a.kp_vo, a.scale, a.w_qkv, a.w_o, a.ld_wqkv, a.ld_wo = 2, 32, 32, 0.125, 256, 512, 256, 160
     assert lib.ecospa_block_workspace_bytes(C.byref(a)) > 0
-    for kq, kv in ((80, 32), (32, 80), (128, 128), (96, 64)):
+    for kq, kv in ((144, 32), (32, 144), (256, 256), (160, 64)):
         b = B.BlockDesc.from_buffer_copy(a)
         b.kp_qk, b.kp_vo = kq, kv
         assert lib.ecospa_block_workspace_bytes(C.byref(b)) == 0
@@ -162,8 +162,10 @@ def test_attention_heads_wider_than_64_are_rejected_before_any_launch(lib, ctx):
         sv, gr = B.Saved(4096, 8192, 12288, None, None), B.Grads()
         assert lib.ecospa_coupled_bwd(ctx, C.byref(b), 1024, 2048, C.byref(sv), 4096, C.byref(gr)) == B.ERR_SHAPE
     b = B.BlockDesc.from_buffer_copy(a)
-    b.kp_qk, b.kp_vo = 64, 48
-    assert lib.ecospa_block_workspace_bytes(C.byref(b)) > 0
+    for kq, kv in ((64, 48), (80, 32), (96, 128), (128, 128)):
+        b.kp_qk, b.kp_vo = kq, kv
+        b.ld_wo = 2 * kv
+        assert lib.ecospa_block_workspace_bytes(C.byref(b)) > 0
 
 
 def test_check_indices_validation(lib, ctx):

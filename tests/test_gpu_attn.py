@@ -96,6 +96,19 @@ def test_attn_small_rope(ctx, k_qk, k_vo):
     run_attn_case(ctx, 32, 2, 130, 128, 4, 64, k_qk, k_vo, rope=True, causal=True, bias=False, wscale=6.0)
 
 
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("k_qk,k_vo", [(128, 128), (96, 80), (72, 32), (32, 112), (128, 64), (64, 100)])
+def test_attn_heads_of_128_dims_no_rope(ctx, k_qk, k_vo, causal):
+    """Heads of 128 dims (the LLaMA-7B shape), dense and at keep ratios that leave more than 64: the 128-wide kernels,
+    alone and mixed with the narrower ones on the other side of the pair."""
+    run_attn_case(ctx, 41, 2, 200, 256, 2, 128, k_qk, k_vo, rope=False, causal=causal, wscale=4.0)
+
+
+@pytest.mark.parametrize("k_qk,k_vo,transposed", [(128, 128, False), (96, 72, True), (80, 128, False)])
+def test_attn_heads_of_128_dims_rope(ctx, k_qk, k_vo, transposed):
+    run_attn_case(ctx, 42, 2, 300, 256, 3, 128, k_qk, k_vo, rope=True, causal=True, bias=False, wscale=4.0, transposed=transposed)
+
+
 def test_attn_tiny_sequence(ctx):
     run_attn_case(ctx, 33, 3, 5, 64, 2, 64, 32, 32, rope=True, causal=True, wscale=6.0)
 
