@@ -45,14 +45,16 @@ __device__ __forceinline__ int k_col(const AttnArgs& a, int kv_head) { return a.
 __device__ __forceinline__ int v_col(const AttnArgs& a, int kv_head) { return (a.h + a.h_kv) * a.kp_qk + kv_head * a.kp_vo; }
 
 // ---------------------------------------------------------------------------------------------
-// LDS tile addressing (element offsets).  Tiles are [rows][D] (D = 32 or 64 dims, 16-byte chunks
+// LDS tile addressing (element offsets).  Tiles are [rows][D] (D = 32, 64 or 128 dims, 16-byte chunks
 // XOR-swizzled by row) and are read two ways:
 //   frag_nat: ds_read_b128, lane (l32, hh) takes chunk 2s+hh of row l32 - sixteen consecutive rows
 //             of one chunk column must fall on sixteen different 16-byte bank groups;
 //   frag_trn: ds_read_b64_tr_b16, a 16-lane group takes 4 rows x 16 dims - the four rows must fall
 //             on four different 64-byte bank groups.
 // D = 64 (128-byte rows): swizzle (row % 8) ^ bit 3 of row ^ (bit 1 of row) << 2 serves both;
-// D = 32 (64-byte rows, a transposing read covers whole rows): (row / 4) % 4.
+// D = 32 (64-byte rows, a transposing read covers whole rows): (row / 4) % 4;
+// D = 128 (256-byte rows): the swizzle of D = 64 on the low three bits of the chunk number - a bijection of the row's
+// sixteen chunks that leaves two-way conflicts on the direct reads (the 128-wide kernels are the rare, wide shapes).
 // ---------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) bf16_t lds_bf16_t;
 typedef short shortx4_t __attribute__((ext_vector_type(4)));
@@ -64,7 +66,7 @@ __device__ __forceinline__ int nat_swz(int row) {
   return D >= 64 ? ((row & 7) ^ ((row >> 3) & 1) ^ (((row >> 1) & 1) << 2)) : ((row >> 2) & 3);
 }
 template <int D>
-__device__ __forceinline__ int nat_off(int row, int chunk) {   // [rows][D], D in {32, 64}
+__device__ __forceinline__ int nat_off(int row, int chunk) {   // [rows][D], D in {32, 64, 128}
   return row * D + ((chunk ^ nat_swz<D>(row)) << 3);
 }
 template <int D>
