@@ -657,24 +657,52 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ATTN_WPE(DQ
           sacc[r] = p * (pacc[r] - dlv[i]);
         }
       }
-      TrnRegs dor[2][DV / 32], qr[2][DQ / 32];
+      if constexpr (DQ + DV <= 192) {
+        TrnRegs dor[2][DV / 32], qr[2][DQ / 32];
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
+        for (int s2 = 0; s2 < 2; ++s2) {
 #pragma unroll
-        for (int u = 0; u < DV / 32; ++u) trn_issue<DV>(dor[s2][u], dOs(cur), u * 32, t * 2 + s2);
+          for (int u = 0; u < DV / 32; ++u) trn_issue<DV>(dor[s2][u], dOs(cur), u * 32, t * 2 + s2);
 #pragma unroll
-        for (int u = 0; u < DQ / 32; ++u) trn_issue<DQ>(qr[s2][u], Qs(cur), u * 32, t * 2 + s2);
-      }
-      trn_wait();
+          for (int u = 0; u < DQ / 32; ++u) trn_issue<DQ>(qr[s2][u], Qs(cur), u * 32, t * 2 + s2);
+        }
+        trn_wait();
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        const bf16x8_t pf = acc_to_frag(pr, s2), df = acc_to_frag(sacc, s2);
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8_t pf = acc_to_frag(pr, s2), df = acc_to_frag(sacc, s2);
 #pragma unroll
-        for (int u = 0; u < DV / 32; ++u)
-          dv[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trn_frag(dor[s2][u]), pf, dv[u], 0, 0, 0);
+          for (int u = 0; u < DV / 32; ++u)
+            dv[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trn_frag(dor[s2][u]), pf, dv[u], 0, 0, 0);
 #pragma unroll
-        for (int u = 0; u < DQ / 32; ++u)
-          dk[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trn_frag(qr[s2][u]), df, dk[u], 0, 0, 0);
+          for (int u = 0; u < DQ / 32; ++u)
+            dk[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trn_frag(qr[s2][u]), df, dk[u], 0, 0, 0);
+        }
+      } else {
+        // two 128-wide sides: the transposed fragments of one operand and one 16-query step at a time, or they would
+        // not fit the registers
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          {
+            TrnRegs dor[DV / 32];
+#pragma unroll
+            for (int u = 0; u < DV / 32; ++u) trn_issue<DV>(dor[u], dOs(cur), u * 32, t * 2 + s2);
+            trn_wait();
+            const bf16x8_t pf = acc_to_frag(pr, s2);
+#pragma unroll
+            for (int u = 0; u < DV / 32; ++u)
+              dv[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trn_frag(dor[u]), pf, dv[u], 0, 0, 0);
+          }
+          {
+            TrnRegs qr[DQ / 32];
+#pragma unroll
+            for (int u = 0; u < DQ / 32; ++u) trn_issue<DQ>(qr[u], Qs(cur), u * 32, t * 2 + s2);
+            trn_wait();
+            const bf16x8_t df = acc_to_frag(sacc, s2);
+#pragma unroll
+            for (int u = 0; u < DQ / 32; ++u)
+              dk[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trn_frag(qr[u]), df, dk[u], 0, 0, 0);
+          }
+        }
       }
     }
   }
