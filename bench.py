@@ -95,7 +95,7 @@ class Layer:
         self.k_ff = dff * keep_num // keep_den
         pairs = self.attn.pairs() + [self.ffn.pair()]
         self.pairs = (B.Pair * len(pairs))(*pairs)
-        self.scores = self._sel = self._map = self._tr = self._k = None     # descriptor arrays are built once: every buffer they name persists
+        self.scores = self._sel = self._map = self._tr = self._k = self._rope = None     # descriptor arrays are built once: every buffer they name persists
         self.idx = [torch.empty((hkv, self.k_qk_units), dtype=torch.int32, device="cuda"),
                     torch.empty((hkv, self.k_vo), dtype=torch.int32, device="cuda"),
                     torch.empty((1, self.k_ff), dtype=torch.int32, device="cuda")]
@@ -120,9 +120,11 @@ class Layer:
             self._map = (self.B_.MapItem * len(items))(*items)
             tr = self.attn.post_gather_items() + self.ffn.post_gather_items()
             self._tr = (self.B_.TransposeItem * len(tr))(*tr) if tr else None
-        elif self.attn.rope:    # the kept rotary blocks may have changed: their cos/sin tables again
-            self.attn._rope_table(self.attn._L, out=(self.attn.cos, self.attn.sin))
-        self.ctx.ecospa_compact_batch(self._map)
+        # the kept rotary blocks may have changed: their cos/sin tables are filled again by the same launch (the very
+        # first compaction precedes alloc(), which makes the first tables)
+        if self._rope is None and self.attn.rope and getattr(self.attn, "cos", None) is not None:
+            self._rope = self.attn.rope_item()
+        self.ctx.ecospa_compact_batch(self._map, self._rope)
         # transposed copies (one launch): of the gathered rows of W_o / W_out for the forward pass, of the other
         # compact matrices for the input-gradient contractions
         if self._tr is not None:

@@ -326,6 +326,20 @@ int ecospa_rope_table(ecospa_ctx* ctx, const int* idx, int h, int L, int k, int 
  * (idx: device int32[h * ld_idx], k_group: device int32[h]), the slots behind them get cos = 1, sin = 0. */
 int ecospa_rope_table_ragged(ecospa_ctx* ctx, const int* idx, int ld_idx, const int* k_group, int h, int L, int kp,
                              int d_h, double base, float* cos_out, float* sin_out);
+/* The gathers of ecospa_compact_batch and the tables of the kept rotary blocks in ONE launch (the tables follow from
+ * the same index lists as the gathers, so a layer's compaction needs no launch of their own for them): `rope` (host,
+ * NULL: plain ecospa_compact_batch) describes the tables as the arguments of ecospa_rope_table do (k_group == NULL;
+ * ld_idx = 0 means k) or as those of ecospa_rope_table_ragged do (k_group != NULL, k unused).  Everything is validated
+ * before anything is launched; errors as the separate calls. */
+typedef struct {
+  const int* idx;      /* device int32[h * ld_idx] kept blocks per head, or NULL (block i at slot i) */
+  const int* k_group;  /* device int32[h] ragged kept counts, or NULL */
+  int h, L, k, kp, d_h, ld_idx;
+  double base;
+  float *cos_out, *sin_out;   /* float[h, L, kp] */
+} ecospa_rope_item;
+int ecospa_compact_batch_rope(ecospa_ctx* ctx, const ecospa_map_item* items /*host*/, int n_items,
+                              const ecospa_rope_item* rope /*host*/);
 
 /* ------------------------------------------------------------------------------------------
  * Steps 4-5 - reduced forward and backward contractions on the compacted matrices (Eq. 1-3,

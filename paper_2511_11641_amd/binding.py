@@ -30,7 +30,7 @@ EXPORTS = (
     "ecospa_select_pairs", "ecospa_rope_table_ragged", "ecospa_adamw", "ecospa_transpose_batch",
     "ecospa_check_indices", "ecospa_contract_workspace_bytes", "ecospa_hbm_probe", "ecospa_contract_colsum", "ecospa_mfma_probe",
     "ecospa_coupled_score_static", "ecospa_coupled_score_static_max_bytes",
-    "ecospa_score_select",
+    "ecospa_score_select", "ecospa_compact_batch_rope",
     "ecospa_norm_fwd", "ecospa_norm_bwd", "ecospa_norm_bwd_workspace_bytes", "ecospa_embed_fwd", "ecospa_embed_bwd", "ecospa_xent",
 )
 NORM_RMS, NORM_LAYER = 0, 1
@@ -73,6 +73,11 @@ class MapItem(C.Structure):
                 ("other_extent", C.c_longlong), ("ld_src", C.c_longlong), ("ld_dst", C.c_longlong),
                 ("idx", C.c_void_p), ("k_group", C.c_void_p), ("ld_idx", C.c_int), ("idx_div", C.c_int),
                 ("dst_t", C.c_void_p), ("ld_dst_t", C.c_longlong), ("src_b", C.c_void_p)]
+
+
+class RopeItem(C.Structure):
+    _fields_ = [("idx", C.c_void_p), ("k_group", C.c_void_p), ("h", C.c_int), ("L", C.c_int), ("k", C.c_int), ("kp", C.c_int),
+                ("d_h", C.c_int), ("ld_idx", C.c_int), ("base", C.c_double), ("cos_out", C.c_void_p), ("sin_out", C.c_void_p)]
 
 
 class TransposeItem(C.Structure):
@@ -143,6 +148,8 @@ def load() -> C.CDLL:
     lib.ecospa_select_topk_batch.restype = ci
     lib.ecospa_compact_batch.argtypes = [vp, C.POINTER(MapItem), ci]
     lib.ecospa_compact_batch.restype = ci
+    lib.ecospa_compact_batch_rope.argtypes = [vp, C.POINTER(MapItem), ci, C.POINTER(RopeItem)]
+    lib.ecospa_compact_batch_rope.restype = ci
     lib.ecospa_rope_table.argtypes = [vp, vp, ci, ci, ci, ci, ci, C.c_double, vp, vp]
     lib.ecospa_rope_table.restype = ci
     lib.ecospa_rope_table_ragged.argtypes = [vp, vp, ci, vp, ci, ci, ci, ci, C.c_double, vp, vp]
@@ -448,9 +455,24 @@ class Context:
         self.ecospa_compact_batch([self.map_item(src, out, idx, axis, groups, n, unit, kp, scatter, k_group)])
         return out
 
-    def ecospa_compact_batch(self, items: Sequence[MapItem]):
+    def ecospa_compact_batch(self, items: Sequence[MapItem], rope: Optional[RopeItem] = None):
+        """All gathers / scatters of `items` in one launch; with `rope` (see :meth:`rope_item`) the same launch also
+        fills the cos/sin tables of the kept rotary blocks."""
         arr = items if isinstance(items, C.Array) else (MapItem * len(items))(*items)
-        self._check(self.lib.ecospa_compact_batch(self.h, arr, len(items)), "ecospa_compact_batch")
+        if rope is None:
+            self._check(self.lib.ecospa_compact_batch(self.h, arr, len(items)), "ecospa_compact_batch")
+        else:
+            self._check(self.lib.ecospa_compact_batch_rope(self.h, arr, len(items), C.byref(rope)), "ecospa_compact_batch_rope")
+
+    @staticmethod
+    def rope_item(idx: Optional[torch.Tensor], h: int, L: int, k: int, kp: int, d_h: int, base: float, cos: torch.Tensor,
+                  sin: torch.Tensor, k_group: Optional[torch.Tensor] = None) -> RopeItem:
+        """Descriptor of the cos/sin tables [h, L, kp] of the kept rotary blocks for :meth:`ecospa_compact_batch`: as
+        :meth:`ecospa_rope_table` (k blocks per head) or, with k_group, as :meth:`ecospa_rope_table_ragged`."""
+        assert cos.shape == (h, L, kp) and sin.shape == (h, L, kp) and cos.dtype == torch.float32 and sin.dtype == torch.float32
+        ld_idx = 0 if idx is None else idx.shape[1]
+        return RopeItem(_ptr(idx), _ptr(k_group), h, L, 0 if k_group is not None else k, kp, d_h, ld_idx, float(base),
+                        cos.data_ptr(), sin.data_ptr())
 
     def _mapped(self, fn, name, src, dst, axis, groups, n, unit, k, kp, idx):
         if src.dim() == 1:

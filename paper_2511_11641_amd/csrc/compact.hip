@@ -76,10 +76,46 @@ struct MapItemDev {
   unsigned char lds_path;   // axis 1 gather with aligned rows: source window staged through LDS
 };
 static_assert(sizeof(MapItemDev) == 128, "descriptor size");
+// cos/sin tables of the kept rotary blocks (Eq. 6): one element per thread.  The same code serves the launch of its
+// own and the workgroups that a gather launch carries along (the tables follow from the same index lists as the
+// gathers, so a layer's compaction needs no second launch for them).
+struct RopeArgs {
+  const int* idx;        // kept blocks per head, or null (block i at slot i)
+  const int* k_group;    // ragged kept counts per head, or null
+  float* cos_out;
+  float* sin_out;
+  double base;
+  int h, L, k, kp, d_h, ld_idx;
+};
+__device__ __forceinline__ void rope_table_element(const RopeArgs& r, long long e) {
+  const long long tot = static_cast<long long>(r.h) * r.L * r.kp;
+  if (e >= tot) return;
+  const int i = static_cast<int>(e % r.kp);
+  const int t = static_cast<int>((e / r.kp) % r.L);
+  const int g = static_cast<int>(e / (static_cast<long long>(r.kp) * r.L));
+  float c = 1.f, s = 0.f;
+  int kg = r.k;
+  if (r.k_group) {
+    const int cap = r.kp < r.ld_idx ? r.kp : r.ld_idx;
+    kg = r.k_group[g] < 0 ? 0 : (r.k_group[g] < cap ? r.k_group[g] : cap);
+  }
+  if (i < kg) {
+    const int p = r.idx ? r.idx[static_cast<long long>(g) * r.ld_idx + i] : i;
+    const double theta = exp(-2.0 * static_cast<double>(p) / static_cast<double>(r.d_h) * log(r.base));
+    const double ang = static_cast<double>(t) * theta;
+    c = static_cast<float>(cos(ang));
+    s = static_cast<float>(sin(ang));
+  }
+  r.cos_out[e] = c;
+  r.sin_out[e] = s;
+}
+
 struct MapBatch {
   int n_items;
+  int rope_blk0;                  // first of the workgroups that fill the rotary tables (behind the copies), -1: none
   int first_blk[MAP_MAX_ITEMS];   // blk_begin of every item, side by side: the search for a block's item stays in a few cache lines
   MapItemDev it[MAP_MAX_ITEMS];
+  RopeArgs rope;
 };
 static_assert(sizeof(MapBatch) <= 16384, "kernel arguments of one launch");
 
@@ -357,6 +393,10 @@ __global__ __launch_bounds__(256) void map_batch_kernel(const MapBatch b) {
   constexpr int LDS_COLS = MAP_LDS_ROWS * MAP_LDS_CHUNKS * 16 + (MAP_LDS_GROUPS * 8 + 2) * 4, LDS_TR = 64 * 65 * 4 + 64 * 8;
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[LDS_COLS > LDS_TR ? LDS_COLS : LDS_TR];
   const int blk = blockIdx.x;
+  if (b.rope_blk0 >= 0 && blk >= b.rope_blk0) {
+    rope_table_element(b.rope, static_cast<long long>(blk - b.rope_blk0) * 256 + threadIdx.x);
+    return;
+  }
   int i = 0, hi = b.n_items - 1;          // last item whose first block is <= blk
   while (i < hi) {
     const int mid = (i + hi + 1) >> 1;
@@ -414,16 +454,40 @@ static int validate_map(const ecospa_map_item& q) {
   return ECOSPA_OK;
 }
 
-extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* items, int n_items) {
+static int validate_rope(const ecospa_rope_item& r) {
+  if (!r.cos_out || !r.sin_out) return ECOSPA_ERR_NULL;
+  if (r.h < 1 || r.L < 1 || r.d_h < 2 || !(r.base > 1.0)) return ECOSPA_ERR_SHAPE;
+  if (r.k_group) {
+    if (!r.idx) return ECOSPA_ERR_NULL;
+    if (r.kp < 1 || r.ld_idx < 1) return ECOSPA_ERR_K;
+  } else if (r.k < 1 || r.kp < r.k || r.k > r.d_h / 2 || (r.ld_idx != 0 && r.ld_idx < r.k)) {
+    return ECOSPA_ERR_K;
+  }
+  if (static_cast<long long>(r.h) * r.L * r.kp > (1ll << 31) - 1) return ECOSPA_ERR_SHAPE;
+  return ECOSPA_OK;
+}
+static RopeArgs rope_args(const ecospa_rope_item& r) {
+  RopeArgs a;
+  a.idx = r.idx; a.k_group = r.k_group; a.cos_out = r.cos_out; a.sin_out = r.sin_out; a.base = r.base;
+  a.h = r.h; a.L = r.L; a.k = r.k; a.kp = r.kp; a.d_h = r.d_h; a.ld_idx = r.ld_idx ? r.ld_idx : r.k;
+  return a;
+}
+
+extern "C" int ecospa_compact_batch_rope(ecospa_ctx* ctx, const ecospa_map_item* items, int n_items, const ecospa_rope_item* rope) {
   if (!ctx || !items) return ECOSPA_ERR_NULL;
   if (n_items < 1) return ECOSPA_ERR_SHAPE;
   for (int i = 0; i < n_items; ++i) {
     const int rc = validate_map(items[i]);
     if (rc) return rc;
   }
+  if (rope) {
+    const int rc = validate_rope(*rope);
+    if (rc) return rc;
+  }
   for (int first = 0; first < n_items; first += MAP_MAX_ITEMS) {
     MapBatch b;
     memset(&b, 0, sizeof(b));
+    b.rope_blk0 = -1;
     b.n_items = n_items - first < MAP_MAX_ITEMS ? n_items - first : MAP_MAX_ITEMS;
     // workgroups the launch has with the most rows per workgroup: only a launch that would leave the
     // chip short of work at that size (a single layer's matrices) takes fewer rows per workgroup
@@ -485,10 +549,20 @@ extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* item
       }
       if (blk > (1ll << 30)) return ECOSPA_ERR_SHAPE;
     }
+    if (rope && first + MAP_MAX_ITEMS >= n_items) {      // the tables ride on the last launch of the batch
+      b.rope = rope_args(*rope);
+      b.rope_blk0 = static_cast<int>(blk);
+      blk += (static_cast<long long>(rope->h) * rope->L * rope->kp + 255) / 256;
+      if (blk > (1ll << 30)) return ECOSPA_ERR_SHAPE;
+    }
     hipLaunchKernelGGL(map_batch_kernel, dim3(static_cast<unsigned>(blk)), dim3(256), 0, ctx->stream, b);
     ECOSPA_CHECK_LAUNCH(ctx, "map_batch_kernel");
   }
   return ECOSPA_OK;
+}
+
+extern "C" int ecospa_compact_batch(ecospa_ctx* ctx, const ecospa_map_item* items, int n_items) {
+  return ecospa_compact_batch_rope(ctx, items, n_items, nullptr);
 }
 
 static int mapped_copy(ecospa_ctx* ctx, const void* src, void* dst, int dtype, int axis, int groups, int n, int unit,
@@ -660,52 +734,29 @@ extern "C" int ecospa_transpose_batch(ecospa_ctx* ctx, const ecospa_transpose_it
 }
 
 // ---- cos/sin tables of the kept rotary blocks (Eq. 6) -------------------------------------------
-__global__ void rope_table_kernel(const int* __restrict__ idx, int h, int L, int k, int kp, int d_h, double base,
-                                  float* __restrict__ cos_out, float* __restrict__ sin_out,
-                                  const int* __restrict__ k_group, int ld_idx) {
-  const long long tot = static_cast<long long>(h) * L * kp;
-  const long long e = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (e >= tot) return;
-  const int i = static_cast<int>(e % kp);
-  const int t = static_cast<int>((e / kp) % L);
-  const int g = static_cast<int>(e / (static_cast<long long>(kp) * L));
-  float c = 1.f, s = 0.f;
-  int kg = k;
-  if (k_group) {
-    const int cap = kp < ld_idx ? kp : ld_idx;
-    kg = k_group[g] < 0 ? 0 : (k_group[g] < cap ? k_group[g] : cap);
-  }
-  if (i < kg) {
-    const int p = idx ? idx[static_cast<long long>(g) * ld_idx + i] : i;
-    const double theta = exp(-2.0 * static_cast<double>(p) / static_cast<double>(d_h) * log(base));
-    const double ang = static_cast<double>(t) * theta;
-    c = static_cast<float>(cos(ang));
-    s = static_cast<float>(sin(ang));
-  }
-  cos_out[e] = c;
-  sin_out[e] = s;
+__global__ void rope_table_kernel(const RopeArgs r) {
+  rope_table_element(r, static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x);
+}
+
+static int rope_launch(ecospa_ctx* ctx, const ecospa_rope_item& r) {
+  const int rc = validate_rope(r);
+  if (rc) return rc;
+  const long long tot = static_cast<long long>(r.h) * r.L * r.kp;
+  hipLaunchKernelGGL(rope_table_kernel, dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream, rope_args(r));
+  ECOSPA_CHECK_LAUNCH(ctx, "rope_table_kernel");
+  return ECOSPA_OK;
 }
 
 extern "C" int ecospa_rope_table(ecospa_ctx* ctx, const int* idx, int h, int L, int k, int kp, int d_h, double base,
                                  float* cos_out, float* sin_out) {
-  if (!ctx || !cos_out || !sin_out) return ECOSPA_ERR_NULL;
-  if (h < 1 || L < 1 || d_h < 2 || !(base > 1.0)) return ECOSPA_ERR_SHAPE;
-  if (k < 1 || kp < k || k > d_h / 2) return ECOSPA_ERR_K;
-  const long long tot = static_cast<long long>(h) * L * kp;
-  hipLaunchKernelGGL(rope_table_kernel, dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream, idx,
-                     h, L, k, kp, d_h, base, cos_out, sin_out, nullptr, k);
-  ECOSPA_CHECK_LAUNCH(ctx, "rope_table_kernel");
-  return ECOSPA_OK;
+  if (!ctx) return ECOSPA_ERR_NULL;
+  const ecospa_rope_item r{idx, nullptr, h, L, k, kp, d_h, 0, base, cos_out, sin_out};
+  return rope_launch(ctx, r);
 }
 
 extern "C" int ecospa_rope_table_ragged(ecospa_ctx* ctx, const int* idx, int ld_idx, const int* k_group, int h, int L,
                                         int kp, int d_h, double base, float* cos_out, float* sin_out) {
-  if (!ctx || !idx || !k_group || !cos_out || !sin_out) return ECOSPA_ERR_NULL;
-  if (h < 1 || L < 1 || d_h < 2 || !(base > 1.0)) return ECOSPA_ERR_SHAPE;
-  if (kp < 1 || ld_idx < 1) return ECOSPA_ERR_K;
-  const long long tot = static_cast<long long>(h) * L * kp;
-  hipLaunchKernelGGL(rope_table_kernel, dim3(static_cast<unsigned>((tot + 255) / 256)), dim3(256), 0, ctx->stream, idx,
-                     h, L, 0, kp, d_h, base, cos_out, sin_out, k_group, ld_idx);
-  ECOSPA_CHECK_LAUNCH(ctx, "rope_table_kernel");
-  return ECOSPA_OK;
+  if (!ctx || !idx || !k_group) return ECOSPA_ERR_NULL;
+  const ecospa_rope_item r{idx, k_group, h, L, 0, kp, d_h, ld_idx, base, cos_out, sin_out};
+  return rope_launch(ctx, r);
 }

@@ -386,6 +386,18 @@ class AttnBlock:
         return self.ctx.ecospa_rope_table(blocks, self.h_kv, L, self.k_qk_units, self.kp_qk // 2, self.d_h,
                                           self.rope_base, out=out)
 
+    def rope_item(self):
+        """The block's rotary tables as a descriptor for :meth:`Context.ecospa_compact_batch` (after :meth:`alloc`): the
+        gather launch of a re-compaction then refreshes them itself.  None for a block without rotary embedding."""
+        if not self.rope:
+            return None
+        h, kp = self.cos.shape[0], self.cos.shape[2]
+        if self.k_qk_group is not None:
+            return B.Context.rope_item(self.idx_qk, h, self._L, 0, kp, self.d_h, self.rope_base, self.cos, self.sin,
+                                       k_group=self.k_qk_group)
+        blocks = self.idx_qk if self.orig_qk is None else self.rope_idx
+        return B.Context.rope_item(blocks, h, self._L, self.k_qk_units, kp, self.d_h, self.rope_base, self.cos, self.sin)
+
     def alloc(self, Bsz: int, L: int):
         c, h = self.ctx, self.h
         T, dt, dev = Bsz * L, self.wq.dtype, self.wq.device

@@ -345,3 +345,40 @@ def test_transposed_copy_only_with_row_gathers(ctx):
         with pytest.raises(B.EcospaError) as e:
             ctx.ecospa_compact_batch([item])
         assert e.value.code == B.ERR_SHAPE
+
+
+# ---- the rotary tables of the kept blocks from the gather launch itself ----------------------------------------------
+@pytest.mark.parametrize("ragged", [False, True])
+def test_gather_launch_fills_the_rotary_tables(ctx, ragged):
+    """ecospa_compact_batch with a table descriptor: the same gathers, and tables bit-identical to those of the launch
+    of their own (whose values are checked against the oracle's angles in the attention tests)."""
+    h, dh, L, d, k, kp = 6, 64, 77, 40, 11, 16
+    rng = np.random.default_rng(17)
+    idx_np = np.stack([np.sort(rng.choice(dh // 2, size=k, replace=False)) for _ in range(h)]).astype(np.int32)
+    idx = torch.from_numpy(idx_np).cuda()
+    src_np = synth.round_to(synth.normal(23, 1, (h * dh, d)), "bf16")
+    src = dev(src_np, "bf16")
+    dst = torch.empty((h * 2 * kp, d), dtype=torch.bfloat16, device="cuda")
+    kg = None
+    if ragged:
+        kg = torch.from_numpy(rng.integers(0, k + 1, size=h).astype(np.int32)).cuda()
+        want_cos, want_sin = ctx.ecospa_rope_table_ragged(idx, kg, L, kp, dh)
+    else:
+        want_cos, want_sin = ctx.ecospa_rope_table(idx, h, L, k, kp, dh)
+    cos = torch.full((h, L, kp), 7.0, device="cuda")
+    sin = torch.full((h, L, kp), 7.0, device="cuda")
+    item = ctx.map_item(src, dst, idx, 0, h, dh, 2, kp, k_group=kg)
+    ctx.ecospa_compact_batch([item], ctx.rope_item(idx, h, L, k, kp, dh, 10000.0, cos, sin, k_group=kg))
+    assert torch.equal(cos, want_cos) and torch.equal(sin, want_sin)
+    ref = torch.empty_like(dst)
+    ctx.ecospa_compact_batch([ctx.map_item(src, ref, idx, 0, h, dh, 2, kp, k_group=kg)])
+    assert torch.equal(dst, ref)
+    if not ragged:
+        want = pad_rows(O.compact(src_np, idx_np, 0, dh, 2), h, 2 * k, 2 * kp)
+        np.testing.assert_array_equal(host(dst), want)
+    # a bad table descriptor is refused before anything is launched
+    dst.fill_(3.0)
+    with pytest.raises(B.EcospaError) as e:
+        ctx.ecospa_compact_batch([item], ctx.rope_item(idx, h, L, k, kp, 1, 10000.0, cos, sin, k_group=kg))
+    assert e.value.code == B.ERR_SHAPE
+    assert bool((dst == 3.0).all())
